@@ -1,0 +1,321 @@
+"""Pins for the CPU oracle: each test checks it against something other than
+itself -- values the paper prints, textbook facts, closed forms, brute force."""
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import aquakv_oracle as O
+from paper_2501_19392_amd import synth
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+PAPER = json.load(open(os.path.join(GOLD, "paper_constants.json")))
+
+
+def rng(seed):
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+# ------------------------------------------------------------------ Hadamard / RHT
+def test_hadamard8_matches_textbook_matrix():
+    want = np.loadtxt(os.path.join(GOLD, "hadamard8.txt"), dtype=np.int64)
+    assert np.array_equal(O.hadamard(8), want)
+
+
+@pytest.mark.parametrize("g", [1, 2, 4, 16, 128, 1024])
+def test_hadamard_orthogonal_symmetric_integer_exact(g):
+    H = O.hadamard(g)
+    assert H.dtype.kind == "i" and set(np.unique(H)) <= {-1, 1}
+    assert np.array_equal(H @ H.T, g * np.eye(g, dtype=np.int64))
+    assert np.array_equal(H, H.T)
+
+
+def test_hadamard_kronecker_recursion():
+    for g in (2, 8, 64):
+        H = O.hadamard(g)
+        H2 = O.hadamard(2 * g)
+        assert np.array_equal(H2, np.block([[H, H], [H, -H]]))
+
+
+def fwht_butterfly(x):
+    """Independent fast transform (in-place butterflies, stride doubling)."""
+    x = np.array(x, dtype=np.float64)
+    g = x.shape[-1]
+    h = 1
+    while h < g:
+        y = x.reshape(x.shape[:-1] + (g // (2 * h), 2, h))
+        a, b = y[..., 0, :].copy(), y[..., 1, :].copy()
+        y[..., 0, :], y[..., 1, :] = a + b, a - b
+        h *= 2
+    return x
+
+
+def test_rht_equals_fast_butterfly_and_parseval_and_inverse():
+    r = rng(1).standard_normal((5, 3, 128)) * 7.0
+    s = synth.rht_signs(3, 128, 0, "k")
+    z = O.rht(r, s)
+    assert np.allclose(z, fwht_butterfly(r * s) / math.sqrt(128), rtol=0, atol=1e-12)
+    assert np.allclose(np.linalg.norm(z, axis=-1), np.linalg.norm(r, axis=-1), rtol=1e-12)
+    assert np.allclose(O.irht(z, s), r, rtol=0, atol=1e-12)
+
+
+def test_rht_sign_is_applied_before_the_rotation():
+    g = 8
+    s = np.array([1, -1, 1, 1, -1, 1, -1, -1])
+    H = np.loadtxt(os.path.join(GOLD, "hadamard8.txt"))
+    for j in range(g):
+        e = np.zeros(g)
+        e[j] = 1.0
+        # sign-before: a scalar s_j times column j; sign-after would flip rows instead
+        assert np.allclose(O.rht(e, s), s[j] * H[:, j] / math.sqrt(g))
+    # the inverse applies the sign last
+    z = rng(2).standard_normal(g)
+    assert np.allclose(O.irht(z, s), s * (H @ z) / math.sqrt(g))
+    # all-ones with all-plus signs concentrates on coordinate 0
+    assert np.allclose(O.rht(np.ones(g), np.ones(g)), [math.sqrt(g)] + [0] * (g - 1))
+
+
+# ------------------------------------------------------------------ roundings
+def test_round_bf16_matches_torch_on_fp32_inputs_and_single_rounding():
+    x = rng(3).standard_normal(200000).astype(np.float32) * np.float32(37.0)
+    x = np.concatenate([x, np.float32([0.0, -0.0, 1.0, 1.00390625, 1.01171875, 3e-39, -2e-40, 1e30])])
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(O.round_bf16(x.astype(np.float64)), want)
+    # exact ties go to even: 1 + 2^-8 is halfway between 1 and 1 + 2^-7
+    assert O.round_bf16(np.array([1.0 + 2.0 ** -8]))[0] == 1.0
+    assert O.round_bf16(np.array([1.0 + 3 * 2.0 ** -8]))[0] == 1.0 + 2 * 2.0 ** -7
+    # just above a tie in fp64 only (fp32 would see an exact tie and go down to even)
+    assert O.round_bf16(np.array([1.0 + 2.0 ** -8 + 2.0 ** -40]))[0] == 1.0 + 2.0 ** -7
+
+
+def test_fp16_scale_matches_torch_and_clamps():
+    x = np.abs(rng(4).standard_normal(100000)) * 10 ** rng(5).uniform(-6, 4, 100000)
+    x32 = x.astype(np.float32)
+    want = torch.from_numpy(x32).to(torch.float16).numpy()
+    got = O.to_fp16_scale(x32.astype(np.float64))
+    assert np.array_equal(got.view(np.uint16), want.view(np.uint16))
+    assert float(O.to_fp16_scale(1e9)) == 65504.0 and float(O.to_fp16_scale(65519.99)) == 65504.0
+    assert float(O.to_fp16_scale(1e-12)) == 0.0
+
+
+# ------------------------------------------------------------------ grid search / packing
+def test_nearest_codeword_vs_python_brute_force_and_inner_product_form(grid16, grid64):
+    for C in (grid16, grid64):
+        C = C.astype(np.float64)
+        y = rng(6).standard_normal((300, 2)) * 1.3
+        idx, gap = O.nearest_codeword(y, C)
+        for i in range(y.shape[0]):                       # plain double loop
+            best, bj = None, -1
+            for j in range(C.shape[0]):
+                d = (y[i, 0] - C[j, 0]) ** 2 + (y[i, 1] - C[j, 1]) ** 2
+                if best is None or d < best:
+                    best, bj = d, j
+            assert idx[i] == bj
+        alt = np.argmax(y @ C.T - 0.5 * (C * C).sum(1), axis=1)   # expanded form
+        assert np.array_equal(idx[gap > 1e-9], alt[gap > 1e-9])
+        assert np.all(gap >= 0)
+        # every codeword is its own nearest point
+        self_idx, _ = O.nearest_codeword(C, C)
+        assert np.array_equal(self_idx, np.arange(C.shape[0]))
+
+
+def test_nearest_codeword_tie_goes_to_lowest_index():
+    C = np.array([[1.0, 0.0], [-1.0, 0.0], [0.0, 1.0], [0.0, -1.0]])
+    idx, gap = O.nearest_codeword(np.array([[0.0, 0.0], [0.5, 0.5]]), C)
+    assert idx.tolist() == [0, 0] and np.allclose(gap, 0.0)
+
+
+def test_pack_known_bytes_and_round_trip():
+    assert O.pack_codes(np.array([1, 2, 3, 4]), 16).tolist() == [0x21, 0x43]
+    assert O.pack_codes(np.array([1, 2, 3, 4]), 64).tolist() == [0x81, 0x30, 0x10]
+    assert O.pack_codes(np.array([0xAB, 0x01]), 256).tolist() == [0xAB, 0x01]
+    for n in (16, 64, 256):
+        idx = rng(7).integers(0, n, size=(9, 2, 64))
+        packed = O.pack_codes(idx, n)
+        assert packed.dtype == np.uint8 and packed.shape == (9, 2, 64 * O.code_bits(n) // 8)
+        assert np.array_equal(O.unpack_codes(packed, n), idx)
+
+
+def test_bit_accounting_matches_table_1():
+    # 2 code bits per value plus one 16-bit scale per group of 1024 values
+    stored = O.code_bits(16) / 2 + 16 / 1024
+    assert round(stored, 2) == PAPER["higgs_2bit_gs1024_stored_bits"]
+    # this build's group of 128: 32 B of codes + 2 B scale per group at 2 bits, 48 + 2 at 3 bits
+    for n, nbytes in ((16, 34), (64, 50)):
+        idx = np.zeros((1, 1, 64), dtype=np.int64)
+        assert O.pack_codes(idx, n).size + 2 == nbytes
+
+
+def test_predictor_shapes_reproduce_the_paper_storage_figures():
+    D = 8 * 128
+    per_layer = (D * D + D * 2 * D) * 2                   # key [D, D] + value [D, 2D], 16-bit
+    assert round(PAPER["predicted_layers_3b"] * per_layer / 2 ** 20) == PAPER["predictor_mib_llama32_3b"]
+    assert round(PAPER["predicted_layers_70b"] * per_layer / 2 ** 20) == PAPER["predictor_mib_llama31_70b"]
+
+
+# ------------------------------------------------------------------ grid quality, Q as a whole
+def test_grid_mse_on_gaussian_matches_paper_and_bounds(grid16, grid64):
+    y = rng(8).standard_normal((400000, 2))
+    for C, levels, rate in ((grid16, "4", 2), (grid64, "8", 3)):
+        idx, _ = O.nearest_codeword(y, C)
+        mse = np.mean((y - C.astype(np.float64)[idx]) ** 2)
+        assert 4.0 ** -rate < mse < PAPER["lloyd_max_mse"][levels]     # R-D bound < mse < scalar product grid
+        if rate == 2:
+            assert abs((1 - mse) - PAPER["explained_variance_2bit"]) < 0.01
+
+
+def _layer(H=2, g=128, n=16, dtype="fp32", **kw):
+    C = synth.lloyd_codebook(n)
+    return O.Layer(kv_heads=H, head_dim=g, codebook=C, signs_k=synth.rht_signs(H, g, 1, "k"),
+                   signs_v=synth.rht_signs(H, g, 1, "v"), dtype=dtype, **kw)
+
+
+def test_quantizer_relative_error_is_data_free(grid16):
+    # Gaussian residuals and residuals with log-normal channel scales + x10 outliers
+    s = synth.rht_signs(2, 128, 0, "k")
+    x = rng(9).standard_normal((512, 2, 128))
+    scales = synth.channel_scales(256, 0, 0).numpy().reshape(2, 128)
+    for data, tol in ((x, 0.006), (x * scales, 0.03)):
+        idx, s16, _ = O.quantize(data, s, grid16)
+        rec = O.dequantize(idx, s16, s, grid16)
+        rel = np.sum((rec - data) ** 2) / np.sum(data ** 2)
+        assert abs(rel - 0.109) < tol, rel
+
+
+def test_scale_covariance_power_of_two_is_exact(grid16):
+    s = synth.rht_signs(2, 128, 0, "k")
+    x = rng(10).standard_normal((64, 2, 128))
+    idx0, s0, _ = O.quantize(x, s, grid16)
+    for k in (-3, 5):
+        idx, sk, _ = O.quantize(x * 2.0 ** k, s, grid16)
+        assert np.array_equal(idx, idx0)
+        assert np.array_equal(sk.astype(np.float64), s0.astype(np.float64) * 2.0 ** k)
+        assert np.array_equal(O.dequantize(idx, sk, s, grid16), O.dequantize(idx0, s0, s, grid16) * 2.0 ** k)
+    # footnote of Sect. 3.1 for a general alpha (approximately, the fp16 scale rounds differently)
+    a = 3.7
+    idx, sa, _ = O.quantize(x * a, s, grid16)
+    e0 = np.linalg.norm(O.dequantize(idx0, s0, s, grid16) - x)
+    ea = np.linalg.norm(O.dequantize(idx, sa, s, grid16) - a * x)
+    assert abs(ea / (a * e0) - 1) < 2e-3
+
+
+def test_scale_of_constant_magnitude_group_is_that_magnitude(grid16):
+    s = synth.rht_signs(1, 128, 0, "k")
+    z = 0.375 * (rng(11).integers(0, 2, size=(1, 1, 128)) * 2 - 1)
+    r = O.irht(z, s)
+    _, s16, diag = O.quantize(r, s, grid16)
+    assert float(s16[0, 0]) == 0.375 and abs(diag.sigma[0, 0] - 0.375) < 1e-14
+
+
+def test_zero_residual_round_trip_is_exact():
+    for dtype in ("fp32", "bf16"):
+        D = 256
+        eye = np.eye(D)
+        wv = np.concatenate([eye, np.zeros((D, D))], axis=1)
+        lay = _layer(dtype=dtype, w_k=eye, w_v=wv)
+        K = O.round_storage(rng(12).standard_normal((16, 2, 128)) * 3, dtype)
+        V = O.round_storage(rng(13).standard_normal((16, 2, 128)) * 3, dtype)
+        out = O.encode_layer(lay, K, V, Khat_prev=K, Vhat_prev=V)
+        assert np.all(out["k_scales"].view(np.uint16) == 0) and np.all(out["v_scales"].view(np.uint16) == 0)
+        assert np.array_equal(out["Khat"], K) and np.array_equal(out["Vhat"], V)
+
+
+# ------------------------------------------------------------------ predictor, algorithms
+def test_predict_special_cases_and_brute_force():
+    x = rng(14).standard_normal((4, 6))
+    W = rng(15).standard_normal((5, 6))
+    b = rng(16).standard_normal(5)
+    want = np.zeros((4, 5))
+    for t in range(4):
+        for o in range(5):
+            acc = b[o]
+            for i in range(6):
+                acc += x[t, i] * W[o, i]
+            want[t, o] = acc
+    assert np.allclose(O.predict(x, W, b), want, rtol=1e-6)
+    assert np.array_equal(O.predict(x, np.eye(6)), O.round_fp32(x))
+    assert np.array_equal(O.predict(x, np.zeros((5, 6))), np.zeros((4, 5)))
+
+
+def test_value_predictor_input_order_is_prev_values_then_current_keys():
+    D = 256
+    lay_v = _layer(w_k=None, w_v=np.concatenate([np.eye(D), np.zeros((D, D))], axis=1))
+    lay_k = _layer(w_k=None, w_v=np.concatenate([np.zeros((D, D)), np.eye(D)], axis=1))
+    K = O.round_fp32(rng(17).standard_normal((8, 2, 128)))
+    V = O.round_fp32(rng(18).standard_normal((8, 2, 128)))
+    Vp = O.round_fp32(rng(19).standard_normal((8, 2, 128)))
+    out_v = O.encode_layer(lay_v, K, V, Khat_prev=None, Vhat_prev=Vp)
+    out_k = O.encode_layer(lay_k, K, V, Khat_prev=None, Vhat_prev=Vp)
+    assert np.array_equal(out_v["P_v"], Vp)
+    assert np.array_equal(out_k["P_v"], out_k["Khat"])       # the *reconstructed* keys, not K
+    assert not np.array_equal(out_k["Khat"], K)
+
+
+def _small_problem(dtype, n=16, T=96, seed=20):
+    cfg = synth.Config("t", layers=2, kv_heads=2, head_dim=128, tokens=T, dtype=dtype, n_codewords=n)
+    st = synth.KVStream(cfg)
+    K0, V0 = st.next()
+    K1, V1 = st.next()
+    wk, wv = synth.analytic_predictors(st, 1)
+    sd = synth.torch_dtype(dtype)
+    wk, wv = wk.to(sd).double().numpy(), wv.to(sd).double().numpy()
+    f = lambda t: t.double().numpy()
+    return cfg, f(K0), f(V0), f(K1), f(V1), wk, wv
+
+
+@pytest.mark.parametrize("dtype,n", [("fp32", 16), ("bf16", 16), ("bf16", 64)])
+def test_closed_loop_decode_reproduces_encoder_reconstruction(dtype, n):
+    cfg, K0, V0, K1, V1, wk, wv = _small_problem(dtype, n)
+    lay0 = _layer(n=n, dtype=dtype)
+    lay1 = _layer(n=n, dtype=dtype, w_k=wk, w_v=wv)
+    e0 = O.encode_layer(lay0, K0, V0)
+    e1 = O.encode_layer(lay1, K1, V1, e0["Khat"], e0["Vhat"])
+    for lay, e, prev in ((lay0, e0, (None, None)), (lay1, e1, (e0["Khat"], e0["Vhat"]))):
+        Kh, Vh = O.decode_layer(lay, e["k_codes"], e["k_scales"], e["v_codes"], e["v_scales"], *prev)
+        assert np.array_equal(Kh, e["Khat"]) and np.array_equal(Vh, e["Vhat"])
+        assert np.array_equal(O.round_storage(Kh, dtype), Kh)
+        assert e["k_codes"].shape == (cfg.tokens, 2, 64 * O.code_bits(n) // 8)
+
+
+def test_predictors_cut_the_error_by_the_unexplained_fraction():
+    """Sect. 3.1: a predictor explaining a fraction rho of the variance leaves the
+    quantizer (1 - rho) of it, so the final relative error is about (1 - rho) * grid mse."""
+    cfg, K0, V0, K1, V1, wk, wv = _small_problem("fp32", T=256)
+    lay1 = _layer(w_k=wk, w_v=wv)
+    plain = _layer()
+    e0 = O.encode_layer(plain, K0, V0)
+    with_pred = O.encode_layer(lay1, K1, V1, e0["Khat"], e0["Vhat"])
+    without = O.encode_layer(plain, K1, V1)
+    for name, X in (("Khat", K1), ("Vhat", V1)):
+        err_p = np.sum((with_pred[name] - X) ** 2) / np.sum(X ** 2)
+        err_0 = np.sum((without[name] - X) ** 2) / np.sum(X ** 2)
+        assert abs(err_0 - 0.109) < 0.03
+        res = X - with_pred["P_k" if name == "Khat" else "P_v"]
+        unexplained = np.sum(res ** 2) / np.sum(X ** 2)
+        assert unexplained < 0.5
+        assert abs(err_p / (unexplained * err_0) - 1) < 0.25, (err_p, unexplained, err_0)
+
+
+def test_scores_second_route_and_gqa_mapping(grid16):
+    H, g, B, S, QH = 2, 128, 2, 5, 8
+    lay = _layer(H=H, g=g, dtype="fp32")
+    K = O.round_fp32(rng(21).standard_normal((B * S, H, g)))
+    V = K.copy()
+    e = O.encode_layer(lay, K, V)
+    q = O.round_fp32(rng(22).standard_normal((B, QH, g)))
+    sc = O.attn_scores(lay, B, S, q, e["k_codes"], e["k_scales"], score_scale=0.25)
+    assert sc.shape == (B, QH, S)
+    # route 2: rotate the query instead of the keys:  q . (s * H zhat / sqrt g) = (H (s*q) / sqrt g) . zhat
+    C = lay.codebook.astype(np.float64)
+    zhat = C[e["k_idx"]].reshape(B, S, H, g) * e["k_scales"].astype(np.float64).reshape(B, S, H, 1)
+    for qh in range(QH):
+        h = qh // (QH // H)
+        qrot = O.rht(q[:, qh, :], lay.signs_k[h])
+        want = 0.25 * np.einsum("bd,btd->bt", qrot, zhat[:, :, h, :])
+        assert np.allclose(sc[:, qh, :], want, rtol=0, atol=2e-6)
+    # a query that lives in one head only sees that head's keys
+    Khat = e["Khat"].reshape(B, S, H, g)
+    assert np.allclose(sc[0, 5, 3], 0.25 * q[0, 5] @ Khat[0, 3, 1], atol=1e-12)
