@@ -1,0 +1,167 @@
+/*
+ * aquakv.h -- C ABI of the MI355X (gfx950) AQUA-KV per-layer KV-cache codec.
+ *
+ * The library implements the per-layer `encode` and `decode` procedures of the
+ * AQUA-KV paper (arxiv 2501.19392; Appendix, Alg. "encode" and Alg. "decode")
+ * on top of the HIGGS-style backbone quantizer of Sect. 2 "Vector Quantization"
+ * (randomized Hadamard transform, group scale, nearest point of an n-point grid
+ * in R^2; Sect. 4.1: n = 16 / 64 / 256 for 2 / 3 / 4 bits per value) and the
+ * linear predictors of Sect. 3.2.
+ *
+ * General conventions
+ *   - Every pointer below is a DEVICE pointer owned by the caller unless the
+ *     comment says "host".  The library allocates nothing, keeps no state
+ *     between calls and never synchronises the device: all work is enqueued on
+ *     `stream` (a hipStream_t passed as void*; NULL = the default stream) and the
+ *     outputs are valid once the stream reaches that point.
+ *   - Every device pointer must be 16-byte aligned (AQUAKV_EALIGN otherwise).
+ *   - Return value: AQUAKV_OK (0) or a negative aquakv_status.  On a validation
+ *     error nothing is launched.  aquakv_last_error() returns a thread-local
+ *     text for the most recent failure on the calling thread.
+ *   - Results for a token row never depend on how many other rows are in the
+ *     call (the predictor's summation order is fixed), so `decode` reproduces
+ *     bit-for-bit the reconstructions `encode` returned.
+ *
+ * Shapes and layouts (T = tokens, H = kv_heads, g = head_dim = 128 = one
+ * rotation/scale group, D = H*g, n = n_codewords, c = log2(n) code bits):
+ *   K, V, Khat, Vhat, *_prev : [T, H, g] row-major, element type = layer.dtype
+ *   codes                    : uint8 [T, H, g*c/16]; per group a little-endian
+ *                              bit string, code i (sub-vector of rotated
+ *                              coordinates 2i, 2i+1) at bits [i*c, (i+1)*c)
+ *   scales                   : IEEE fp16 bit patterns, uint16 [T, H]
+ *   predictions P            : fp32 [T, D]
+ */
+#ifndef AQUAKV_H
+#define AQUAKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AQUAKV_VERSION 100 /* major*10000 + minor*100 + patch */
+
+typedef enum {
+  AQUAKV_OK = 0,
+  AQUAKV_EINVAL = -1,       /* a size or enum is out of range / inconsistent    */
+  AQUAKV_ENULL = -2,        /* a required pointer is NULL                       */
+  AQUAKV_EALIGN = -3,       /* a pointer is not 16-byte aligned                 */
+  AQUAKV_EUNSUPPORTED = -4, /* valid in principle, not built (e.g. head_dim 64) */
+  AQUAKV_EWORKSPACE = -5,   /* workspace smaller than aquakv_workspace_bytes()  */
+  AQUAKV_EHIP = -6          /* a HIP launch failed; see aquakv_last_error()     */
+} aquakv_status;
+
+typedef enum { AQUAKV_BF16 = 0, AQUAKV_FP32 = 1 } aquakv_dtype;
+typedef enum { AQUAKV_KEY = 0, AQUAKV_VALUE = 1 } aquakv_which;
+
+/*
+ * One layer's fixed parameters: the REQUIRE lines of Alg. "encode"/"decode"
+ * (predictors) plus what the quantizer of Sect. 2 needs (grid, sign vectors).
+ * The struct itself lives in HOST memory; the pointers in it are device pointers.
+ */
+typedef struct aquakv_layer {
+  int32_t kv_heads;     /* H >= 1                                                */
+  int32_t head_dim;     /* g; only 128 is built                                   */
+  int32_t vq_dim;       /* p; only 2 is built (Sect. 4.1: d = 2)                  */
+  int32_t n_codewords;  /* n in {16, 64, 256}: 2, 3, 4 code bits per value        */
+  int32_t dtype;        /* aquakv_dtype of K, V, reconstructions and weights      */
+  int32_t d_in_k;       /* inputs of f_key (= width of Khat_prev); 0 = no key
+                           predictor (layer 0: prediction is zero)                */
+  int32_t d_in_v;       /* inputs of f_value = width of Vhat_prev + D; 0 = none   */
+  int32_t reserved;     /* must be 0                                              */
+  const float* codebook;   /* [n, 2] fp32 grid points                             */
+  const int8_t* signs_k;   /* [H*g] entries +1 / -1: RHT signs for keys           */
+  const int8_t* signs_v;   /* [H*g] same for values                               */
+  const void* w_k;      /* [D, d_in_k] row-major, dtype: K_pred = Khat_prev w_k^T */
+  const float* b_k;     /* [D] fp32 bias or NULL                                  */
+  const void* w_v;      /* [D, d_in_v] row-major; input columns: Vhat_prev first,
+                           then this layer's Khat (Alg. "encode": [Vhat_prev; Khat]) */
+  const float* b_v;     /* [D] fp32 bias or NULL                                  */
+} aquakv_layer;
+
+int aquakv_version(void);
+const char* aquakv_status_string(int status);
+const char* aquakv_last_error(void);
+
+/* Bytes of device workspace the three layer-level calls below need for `tokens`
+ * rows (0 on invalid arguments).  It holds fp32 predictions (and a temporary
+ * Khat when the caller does not ask for one) for one chunk of rows. */
+size_t aquakv_workspace_bytes(const aquakv_layer* layer, int64_t tokens);
+
+/*
+ * Stage entry points (also what the layer-level calls are made of).
+ *
+ * aquakv_predict -- Sect. 3.2: P = [x0 | x1] W^T + b in fp32 (bf16 inputs:
+ *   bf16 MFMA with fp32 accumulation; fp32 inputs: fp32 FMA).
+ *   which = AQUAKV_KEY  : x0 = Khat_prev [T, d_in_k], x1 ignored (may be NULL)
+ *   which = AQUAKV_VALUE: x0 = Vhat_prev [T, d_in_v - D], x1 = Khat [T, D]
+ *   P: fp32 [T, D] out.  AQUAKV_EINVAL if the layer has no such predictor.
+ *
+ * aquakv_quantize -- Sect. 2: Q(X - P).  z = H_g(s*(x-p))/sqrt(g) per group,
+ *   sigma = rms(z) stored as fp16, nearest grid point of z/sigma16 per pair,
+ *   lowest index on ties.  P (fp32 [T, D]) may be NULL = zero prediction.
+ *   Xhat (nullable, dtype) receives round(P + Q^-1(codes)) exactly as
+ *   aquakv_dequantize would produce it.  Xhat may alias X; nothing else may alias.
+ *
+ * aquakv_dequantize -- Sect. 2 / Alg. "decode": Xhat = round(P + s*H_g(C[code]*sigma16)/sqrt(g)).
+ */
+int aquakv_predict(const aquakv_layer* layer, int which, int64_t tokens,
+                   const void* x0, const void* x1, float* P, void* stream);
+int aquakv_quantize(const aquakv_layer* layer, int which, int64_t tokens,
+                    const void* X, const float* P,
+                    uint8_t* codes, uint16_t* scales, void* Xhat, void* stream);
+int aquakv_dequantize(const aquakv_layer* layer, int which, int64_t tokens,
+                      const uint8_t* codes, const uint16_t* scales, const float* P,
+                      void* Xhat, void* stream);
+
+/*
+ * aquakv_encode_layer -- Alg. "encode" for one layer and `tokens` rows:
+ *   K_pred = f_key(Khat_prev); K_q = Q(K - K_pred); Khat = Q^-1(K_q) + K_pred;
+ *   V_pred = f_value([Vhat_prev; Khat]); V_q = Q(V - V_pred); Vhat likewise.
+ * Khat_prev / Vhat_prev: required iff the layer has the respective predictor.
+ * Khat, Vhat: outputs (nullable).  They are what Alg. "Inference" feeds to the
+ * next layer; the stored (rounded) Khat is also what f_value reads.
+ * tokens == 0 is a no-op.
+ */
+int aquakv_encode_layer(const aquakv_layer* layer, int64_t tokens,
+                        const void* K, const void* V,
+                        const void* Khat_prev, const void* Vhat_prev,
+                        uint8_t* k_codes, uint16_t* k_scales,
+                        uint8_t* v_codes, uint16_t* v_scales,
+                        void* Khat, void* Vhat,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * aquakv_decode_layer -- Alg. "decode":
+ *   Khat = Q^-1(K_q) + f_key(Khat_prev); Vhat = Q^-1(V_q) + f_value([Vhat_prev; Khat]).
+ * Khat is required when the layer has a value predictor and Vhat is requested;
+ * Vhat may be NULL (keys only; v_codes / v_scales are then ignored).
+ */
+int aquakv_decode_layer(const aquakv_layer* layer, int64_t tokens,
+                        const uint8_t* k_codes, const uint16_t* k_scales,
+                        const uint8_t* v_codes, const uint16_t* v_scales,
+                        const void* Khat_prev, const void* Vhat_prev,
+                        void* Khat, void* Vhat,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * aquakv_decode_attn_scores -- decode of the keys (Alg. "decode", first line)
+ * fused with grouped-query q.k scoring, so the keys need not be written:
+ *   scores[b, qh, t] = score_scale * sum_d q[b, qh, d] * Khat[b*seq_len + t, qh / (q_heads/H), d]
+ * q: [batch, q_heads, g] (dtype); scores: fp32 [batch, q_heads, seq_len];
+ * codes / scales / Khat_prev cover batch*seq_len rows; no rotary embedding.
+ * Khat_out (nullable, dtype, [batch*seq_len, H, g]) also receives the keys.
+ * q_heads must be a multiple of H with q_heads / H <= 8.
+ */
+int aquakv_decode_attn_scores(const aquakv_layer* layer, int32_t batch, int32_t seq_len, int32_t q_heads,
+                              const uint8_t* k_codes, const uint16_t* k_scales,
+                              const void* Khat_prev, const void* q, float score_scale,
+                              float* scores, void* Khat_out,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AQUAKV_H */

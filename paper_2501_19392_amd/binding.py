@@ -1,0 +1,220 @@
+"""ctypes binding of libaquakv.so: same names as the C ABI (include/aquakv.h),
+argument marshalling only.  Tensors are torch tensors on the GPU (torch is used
+for device memory and streams); every step of the path runs in the HIP kernels.
+
+Importing this module without the built library raises: there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libaquakv.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python -m paper_2501_19392_amd.build` "
+        "(or __graft_entry__.build()); there is no CPU fallback")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+AQUAKV_OK, AQUAKV_EINVAL, AQUAKV_ENULL, AQUAKV_EALIGN, AQUAKV_EUNSUPPORTED, AQUAKV_EWORKSPACE, AQUAKV_EHIP = (
+    0, -1, -2, -3, -4, -5, -6)
+AQUAKV_BF16, AQUAKV_FP32 = 0, 1
+AQUAKV_KEY, AQUAKV_VALUE = 0, 1
+
+EXPORTS = [
+    "aquakv_version", "aquakv_status_string", "aquakv_last_error", "aquakv_workspace_bytes",
+    "aquakv_predict", "aquakv_quantize", "aquakv_dequantize",
+    "aquakv_encode_layer", "aquakv_decode_layer", "aquakv_decode_attn_scores",
+]
+
+
+class aquakv_layer(ctypes.Structure):
+    _fields_ = [
+        ("kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("vq_dim", ctypes.c_int32),
+        ("n_codewords", ctypes.c_int32), ("dtype", ctypes.c_int32), ("d_in_k", ctypes.c_int32),
+        ("d_in_v", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("codebook", ctypes.c_void_p), ("signs_k", ctypes.c_void_p), ("signs_v", ctypes.c_void_p),
+        ("w_k", ctypes.c_void_p), ("b_k", ctypes.c_void_p), ("w_v", ctypes.c_void_p), ("b_v", ctypes.c_void_p),
+    ]
+
+
+_P = ctypes.c_void_p
+_LP = ctypes.POINTER(aquakv_layer)
+_lib.aquakv_version.restype = ctypes.c_int
+_lib.aquakv_status_string.restype = ctypes.c_char_p
+_lib.aquakv_status_string.argtypes = [ctypes.c_int]
+_lib.aquakv_last_error.restype = ctypes.c_char_p
+_lib.aquakv_workspace_bytes.restype = ctypes.c_size_t
+_lib.aquakv_workspace_bytes.argtypes = [_LP, ctypes.c_int64]
+_lib.aquakv_predict.argtypes = [_LP, ctypes.c_int, ctypes.c_int64, _P, _P, _P, _P]
+_lib.aquakv_quantize.argtypes = [_LP, ctypes.c_int, ctypes.c_int64, _P, _P, _P, _P, _P, _P]
+_lib.aquakv_dequantize.argtypes = [_LP, ctypes.c_int, ctypes.c_int64, _P, _P, _P, _P, _P]
+_lib.aquakv_encode_layer.argtypes = [_LP, ctypes.c_int64] + [_P] * 11 + [ctypes.c_size_t, _P]
+_lib.aquakv_decode_layer.argtypes = [_LP, ctypes.c_int64] + [_P] * 9 + [ctypes.c_size_t, _P]
+_lib.aquakv_decode_attn_scores.argtypes = ([_LP, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _P, _P, _P, _P,
+                                            ctypes.c_float, _P, _P, _P, ctypes.c_size_t, _P])
+for _n in ("aquakv_predict", "aquakv_quantize", "aquakv_dequantize", "aquakv_encode_layer", "aquakv_decode_layer",
+           "aquakv_decode_attn_scores"):
+    getattr(_lib, _n).restype = ctypes.c_int
+
+
+class AquaKVError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"{aquakv_status_string(status)} ({status}): {aquakv_last_error()}")
+
+
+def _check(status: int) -> None:
+    if status != AQUAKV_OK:
+        raise AquaKVError(status)
+
+
+def _ptr(x):
+    """None -> NULL, int -> that address, tensor -> its data pointer (must be contiguous)."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return ctypes.c_void_p(x)
+    if not x.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return ctypes.c_void_p(x.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream) if torch.cuda.is_available() else None
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dtype_code(t: torch.dtype) -> int:
+    if t == torch.bfloat16:
+        return AQUAKV_BF16
+    if t == torch.float32:
+        return AQUAKV_FP32
+    raise ValueError(f"unsupported storage dtype {t}")
+
+
+class Layer:
+    """Owns the device tensors of one layer's parameters and the C struct that points at them."""
+
+    def __init__(self, kv_heads: int, head_dim: int, codebook: torch.Tensor, signs_k: torch.Tensor,
+                 signs_v: torch.Tensor, dtype: torch.dtype, w_k: Optional[torch.Tensor] = None,
+                 w_v: Optional[torch.Tensor] = None, b_k: Optional[torch.Tensor] = None,
+                 b_v: Optional[torch.Tensor] = None):
+        self.kv_heads, self.head_dim, self.dtype = kv_heads, head_dim, dtype
+        self.d = kv_heads * head_dim
+        self.codebook = codebook.to(torch.float32).contiguous()
+        self.signs_k = signs_k.to(torch.int8).contiguous().reshape(-1)
+        self.signs_v = signs_v.to(torch.int8).contiguous().reshape(-1)
+        self.w_k = None if w_k is None else w_k.to(dtype).contiguous()
+        self.w_v = None if w_v is None else w_v.to(dtype).contiguous()
+        self.b_k = None if b_k is None else b_k.to(torch.float32).contiguous()
+        self.b_v = None if b_v is None else b_v.to(torch.float32).contiguous()
+        self.n_codewords, self.vq_dim = self.codebook.shape
+        if self.w_k is not None and self.w_k.shape[0] != self.d:
+            raise ValueError("w_k must be [D, d_in_k]")
+        if self.w_v is not None and self.w_v.shape[0] != self.d:
+            raise ValueError("w_v must be [D, d_in_v]")
+        self.c = aquakv_layer(
+            kv_heads=kv_heads, head_dim=head_dim, vq_dim=self.vq_dim, n_codewords=self.n_codewords,
+            dtype=_dtype_code(dtype), d_in_k=0 if self.w_k is None else self.w_k.shape[1],
+            d_in_v=0 if self.w_v is None else self.w_v.shape[1], reserved=0,
+            codebook=self.codebook.data_ptr(), signs_k=self.signs_k.data_ptr(), signs_v=self.signs_v.data_ptr(),
+            w_k=None if self.w_k is None else self.w_k.data_ptr(),
+            b_k=None if self.b_k is None else self.b_k.data_ptr(),
+            w_v=None if self.w_v is None else self.w_v.data_ptr(),
+            b_v=None if self.b_v is None else self.b_v.data_ptr())
+
+    @property
+    def code_bits(self) -> int:
+        return int(self.n_codewords).bit_length() - 1
+
+    @property
+    def code_bytes_per_group(self) -> int:
+        return self.head_dim // self.vq_dim * self.code_bits // 8
+
+    def alloc_codes(self, tokens: int, device="cuda"):
+        codes = torch.empty(tokens, self.kv_heads, self.code_bytes_per_group, dtype=torch.uint8, device=device)
+        scales = torch.empty(tokens, self.kv_heads, dtype=torch.int16, device=device)   # fp16 bit patterns
+        return codes, scales
+
+    def alloc_kv(self, tokens: int, device="cuda"):
+        return torch.empty(tokens, self.kv_heads, self.head_dim, dtype=self.dtype, device=device)
+
+    def alloc_workspace(self, tokens: int, device="cuda"):
+        return torch.empty(max(aquakv_workspace_bytes(self, tokens), 16), dtype=torch.uint8, device=device)
+
+
+def _layer_ref(layer):
+    return ctypes.byref(layer.c if isinstance(layer, Layer) else layer)
+
+
+# ---------------------------------------------------------------- the C ABI, same names
+def aquakv_version() -> int:
+    return _lib.aquakv_version()
+
+
+def aquakv_status_string(status: int) -> str:
+    return _lib.aquakv_status_string(status).decode()
+
+
+def aquakv_last_error() -> str:
+    return _lib.aquakv_last_error().decode()
+
+
+def aquakv_workspace_bytes(layer, tokens: int) -> int:
+    return int(_lib.aquakv_workspace_bytes(_layer_ref(layer), tokens))
+
+
+def aquakv_predict(layer, which: int, tokens: int, x0, x1, P, stream=None) -> None:
+    _check(_lib.aquakv_predict(_layer_ref(layer), which, tokens, _ptr(x0), _ptr(x1), _ptr(P), _stream(stream)))
+
+
+def aquakv_quantize(layer, which: int, tokens: int, X, P, codes, scales, Xhat, stream=None) -> None:
+    _check(_lib.aquakv_quantize(_layer_ref(layer), which, tokens, _ptr(X), _ptr(P), _ptr(codes), _ptr(scales),
+                                _ptr(Xhat), _stream(stream)))
+
+
+def aquakv_dequantize(layer, which: int, tokens: int, codes, scales, P, Xhat, stream=None) -> None:
+    _check(_lib.aquakv_dequantize(_layer_ref(layer), which, tokens, _ptr(codes), _ptr(scales), _ptr(P), _ptr(Xhat),
+                                  _stream(stream)))
+
+
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    if isinstance(workspace, tuple):
+        return ctypes.c_void_p(workspace[0]), workspace[1]
+    return _ptr(workspace), workspace.numel() * workspace.element_size()
+
+
+def aquakv_encode_layer(layer, tokens: int, K, V, Khat_prev, Vhat_prev, k_codes, k_scales, v_codes, v_scales,
+                        Khat, Vhat, workspace, stream=None) -> None:
+    ws, nbytes = _ws(workspace)
+    _check(_lib.aquakv_encode_layer(_layer_ref(layer), tokens, _ptr(K), _ptr(V), _ptr(Khat_prev), _ptr(Vhat_prev),
+                                    _ptr(k_codes), _ptr(k_scales), _ptr(v_codes), _ptr(v_scales), _ptr(Khat),
+                                    _ptr(Vhat), ws, nbytes, _stream(stream)))
+
+
+def aquakv_decode_layer(layer, tokens: int, k_codes, k_scales, v_codes, v_scales, Khat_prev, Vhat_prev, Khat, Vhat,
+                        workspace, stream=None) -> None:
+    ws, nbytes = _ws(workspace)
+    _check(_lib.aquakv_decode_layer(_layer_ref(layer), tokens, _ptr(k_codes), _ptr(k_scales), _ptr(v_codes),
+                                    _ptr(v_scales), _ptr(Khat_prev), _ptr(Vhat_prev), _ptr(Khat), _ptr(Vhat),
+                                    ws, nbytes, _stream(stream)))
+
+
+def aquakv_decode_attn_scores(layer, batch: int, seq_len: int, q_heads: int, k_codes, k_scales, Khat_prev, q,
+                              score_scale: float, scores, Khat_out, workspace, stream=None) -> None:
+    ws, nbytes = _ws(workspace)
+    _check(_lib.aquakv_decode_attn_scores(_layer_ref(layer), batch, seq_len, q_heads, _ptr(k_codes), _ptr(k_scales),
+                                          _ptr(Khat_prev), _ptr(q), ctypes.c_float(score_scale), _ptr(scores),
+                                          _ptr(Khat_out), ws, nbytes, _stream(stream)))

@@ -1,0 +1,322 @@
+// C-ABI layer: argument validation, workspace layout, chunking and dispatch.
+// No HIP call is made before validation has passed.
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "../../include/aquakv.h"
+#include "kernels.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int status, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return status;
+}
+
+// Rows handled per pass of the layer-level calls: the fp32 predictions of one
+// chunk (chunk * D * 4 bytes) stay close to the caches between the GEMM that
+// writes them and the streaming kernel that consumes them.
+constexpr int64_t kChunkRows = 16384;
+
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+inline size_t elem_bytes(int dtype) { return dtype == AQUAKV_BF16 ? 2 : 4; }
+inline int code_bits(int n) { return n == 16 ? 4 : n == 64 ? 6 : 8; }
+
+int check_layer(const aquakv_layer* L) {
+  if (L == nullptr) return fail(AQUAKV_ENULL, "layer is NULL");
+  if (L->kv_heads < 1 || L->kv_heads > 4096) return fail(AQUAKV_EINVAL, "kv_heads=%d out of range", L->kv_heads);
+  if (L->head_dim < 1 || (L->head_dim & (L->head_dim - 1)))
+    return fail(AQUAKV_EINVAL, "head_dim=%d is not a power of two", L->head_dim);
+  if (L->head_dim != 128) return fail(AQUAKV_EUNSUPPORTED, "head_dim=%d: only 128 is built", L->head_dim);
+  if (L->vq_dim < 1) return fail(AQUAKV_EINVAL, "vq_dim=%d", L->vq_dim);
+  if (L->vq_dim != 2) return fail(AQUAKV_EUNSUPPORTED, "vq_dim=%d: only 2 is built", L->vq_dim);
+  if (L->n_codewords != 16 && L->n_codewords != 64 && L->n_codewords != 256)
+    return fail(L->n_codewords >= 2 && !(L->n_codewords & (L->n_codewords - 1)) ? AQUAKV_EUNSUPPORTED : AQUAKV_EINVAL,
+                "n_codewords=%d: must be 16, 64 or 256", L->n_codewords);
+  if (L->dtype != AQUAKV_BF16 && L->dtype != AQUAKV_FP32) return fail(AQUAKV_EINVAL, "dtype=%d", L->dtype);
+  if (L->reserved != 0) return fail(AQUAKV_EINVAL, "reserved field must be 0");
+  const int D = L->kv_heads * L->head_dim;
+  if (L->d_in_k < 0 || L->d_in_k % 64) return fail(AQUAKV_EINVAL, "d_in_k=%d must be a non-negative multiple of 64", L->d_in_k);
+  if (L->d_in_v < 0 || L->d_in_v % 64) return fail(AQUAKV_EINVAL, "d_in_v=%d must be a non-negative multiple of 64", L->d_in_v);
+  if (L->d_in_v != 0 && L->d_in_v <= D)
+    return fail(AQUAKV_EINVAL, "d_in_v=%d must exceed D=%d (inputs are [Vhat_prev | Khat])", L->d_in_v, D);
+  if (L->codebook == nullptr) return fail(AQUAKV_ENULL, "codebook is NULL");
+  if (L->signs_k == nullptr || L->signs_v == nullptr) return fail(AQUAKV_ENULL, "signs_k / signs_v is NULL");
+  if (L->d_in_k && L->w_k == nullptr) return fail(AQUAKV_ENULL, "w_k is NULL but d_in_k=%d", L->d_in_k);
+  if (L->d_in_v && L->w_v == nullptr) return fail(AQUAKV_ENULL, "w_v is NULL but d_in_v=%d", L->d_in_v);
+  const void* ptrs[] = {L->codebook, L->signs_k, L->signs_v, L->w_k, L->b_k, L->w_v, L->b_v};
+  for (const void* p : ptrs)
+    if (p != nullptr && misaligned(p)) return fail(AQUAKV_EALIGN, "a pointer in aquakv_layer is not 16-byte aligned");
+  return AQUAKV_OK;
+}
+
+int check_ptr(const void* p, const char* name, bool required) {
+  if (p == nullptr) return required ? fail(AQUAKV_ENULL, "%s is NULL", name) : AQUAKV_OK;
+  if (misaligned(p)) return fail(AQUAKV_EALIGN, "%s is not 16-byte aligned", name);
+  return AQUAKV_OK;
+}
+
+#define CHECK(expr)                      \
+  do {                                   \
+    const int s_ = (expr);               \
+    if (s_ != AQUAKV_OK) return s_;      \
+  } while (0)
+
+#define HIP_TRY(expr)                                                                     \
+  do {                                                                                    \
+    const hipError_t e_ = (expr);                                                         \
+    if (e_ != hipSuccess) return fail(AQUAKV_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+struct Plan {
+  int D;
+  size_t eb;          // bytes per element of the storage dtype
+  size_t code_row;    // bytes of codes per token row
+  int64_t chunk;      // rows per pass
+  size_t p_bytes;     // fp32 predictions of one chunk
+  size_t khat_bytes;  // temporary Khat of one chunk
+};
+
+Plan make_plan(const aquakv_layer* L, int64_t tokens) {
+  Plan pl;
+  pl.D = L->kv_heads * L->head_dim;
+  pl.eb = elem_bytes(L->dtype);
+  pl.code_row = (size_t)L->kv_heads * (L->head_dim / 2) * code_bits(L->n_codewords) / 8;
+  pl.chunk = tokens < kChunkRows ? tokens : kChunkRows;
+  pl.p_bytes = (size_t)pl.chunk * pl.D * sizeof(float);
+  pl.khat_bytes = (size_t)pl.chunk * pl.D * pl.eb;
+  return pl;
+}
+
+inline const void* at(const void* base, int64_t row, size_t row_bytes) {
+  return base == nullptr ? nullptr : static_cast<const unsigned char*>(base) + row * row_bytes;
+}
+inline void* at(void* base, int64_t row, size_t row_bytes) {
+  return base == nullptr ? nullptr : static_cast<unsigned char*>(base) + row * row_bytes;
+}
+
+}  // namespace
+
+extern "C" {
+
+int aquakv_version(void) { return AQUAKV_VERSION; }
+
+const char* aquakv_status_string(int status) {
+  switch (status) {
+    case AQUAKV_OK: return "ok";
+    case AQUAKV_EINVAL: return "invalid argument";
+    case AQUAKV_ENULL: return "required pointer is NULL";
+    case AQUAKV_EALIGN: return "pointer is not 16-byte aligned";
+    case AQUAKV_EUNSUPPORTED: return "configuration not built";
+    case AQUAKV_EWORKSPACE: return "workspace too small";
+    case AQUAKV_EHIP: return "HIP error";
+    default: return "unknown status";
+  }
+}
+
+const char* aquakv_last_error(void) { return g_err; }
+
+size_t aquakv_workspace_bytes(const aquakv_layer* layer, int64_t tokens) {
+  if (check_layer(layer) != AQUAKV_OK || tokens <= 0) return 0;
+  const Plan pl = make_plan(layer, tokens);
+  return pl.p_bytes + pl.khat_bytes;
+}
+
+int aquakv_predict(const aquakv_layer* L, int which, int64_t tokens, const void* x0, const void* x1, float* P,
+                   void* stream) {
+  CHECK(check_layer(L));
+  if (which != AQUAKV_KEY && which != AQUAKV_VALUE) return fail(AQUAKV_EINVAL, "which=%d", which);
+  if (tokens < 0) return fail(AQUAKV_EINVAL, "tokens=%lld", (long long)tokens);
+  const int D = L->kv_heads * L->head_dim;
+  const int d_in = which == AQUAKV_KEY ? L->d_in_k : L->d_in_v;
+  if (d_in == 0) return fail(AQUAKV_EINVAL, "the layer has no %s predictor", which == AQUAKV_KEY ? "key" : "value");
+  CHECK(check_ptr(x0, "x0", true));
+  CHECK(check_ptr(x1, "x1", which == AQUAKV_VALUE));
+  CHECK(check_ptr(P, "P", true));
+  if (tokens == 0) return AQUAKV_OK;
+  const int d0 = which == AQUAKV_KEY ? d_in : d_in - D;
+  const int d1 = which == AQUAKV_KEY ? 0 : D;
+  HIP_TRY(aquakv::launch_predict(L->dtype, x0, d0, which == AQUAKV_KEY ? nullptr : x1, d1,
+                                 which == AQUAKV_KEY ? L->w_k : L->w_v, which == AQUAKV_KEY ? L->b_k : L->b_v, P,
+                                 tokens, D, static_cast<hipStream_t>(stream)));
+  return AQUAKV_OK;
+}
+
+int aquakv_quantize(const aquakv_layer* L, int which, int64_t tokens, const void* X, const float* P, uint8_t* codes,
+                    uint16_t* scales, void* Xhat, void* stream) {
+  CHECK(check_layer(L));
+  if (which != AQUAKV_KEY && which != AQUAKV_VALUE) return fail(AQUAKV_EINVAL, "which=%d", which);
+  if (tokens < 0) return fail(AQUAKV_EINVAL, "tokens=%lld", (long long)tokens);
+  CHECK(check_ptr(X, "X", true));
+  CHECK(check_ptr(P, "P", false));
+  CHECK(check_ptr(codes, "codes", true));
+  CHECK(check_ptr(scales, "scales", true));
+  CHECK(check_ptr(Xhat, "Xhat", false));
+  HIP_TRY(aquakv::launch_quantize(L->dtype, L->n_codewords, X, P, which == AQUAKV_KEY ? L->signs_k : L->signs_v,
+                                  L->codebook, codes, scales, Xhat, tokens, L->kv_heads,
+                                  static_cast<hipStream_t>(stream)));
+  return AQUAKV_OK;
+}
+
+int aquakv_dequantize(const aquakv_layer* L, int which, int64_t tokens, const uint8_t* codes, const uint16_t* scales,
+                      const float* P, void* Xhat, void* stream) {
+  CHECK(check_layer(L));
+  if (which != AQUAKV_KEY && which != AQUAKV_VALUE) return fail(AQUAKV_EINVAL, "which=%d", which);
+  if (tokens < 0) return fail(AQUAKV_EINVAL, "tokens=%lld", (long long)tokens);
+  CHECK(check_ptr(codes, "codes", true));
+  CHECK(check_ptr(scales, "scales", true));
+  CHECK(check_ptr(P, "P", false));
+  CHECK(check_ptr(Xhat, "Xhat", true));
+  HIP_TRY(aquakv::launch_dequantize(L->dtype, L->n_codewords, codes, scales, P,
+                                    which == AQUAKV_KEY ? L->signs_k : L->signs_v, L->codebook, Xhat, tokens,
+                                    L->kv_heads, static_cast<hipStream_t>(stream)));
+  return AQUAKV_OK;
+}
+
+int aquakv_encode_layer(const aquakv_layer* L, int64_t tokens, const void* K, const void* V, const void* Khat_prev,
+                        const void* Vhat_prev, uint8_t* k_codes, uint16_t* k_scales, uint8_t* v_codes,
+                        uint16_t* v_scales, void* Khat, void* Vhat, void* workspace, size_t workspace_bytes,
+                        void* stream_) {
+  CHECK(check_layer(L));
+  if (tokens < 0) return fail(AQUAKV_EINVAL, "tokens=%lld", (long long)tokens);
+  const bool has_k = L->d_in_k != 0, has_v = L->d_in_v != 0;
+  CHECK(check_ptr(K, "K", true));
+  CHECK(check_ptr(V, "V", true));
+  CHECK(check_ptr(Khat_prev, "Khat_prev", has_k));
+  CHECK(check_ptr(Vhat_prev, "Vhat_prev", has_v));
+  CHECK(check_ptr(k_codes, "k_codes", true));
+  CHECK(check_ptr(k_scales, "k_scales", true));
+  CHECK(check_ptr(v_codes, "v_codes", true));
+  CHECK(check_ptr(v_scales, "v_scales", true));
+  CHECK(check_ptr(Khat, "Khat", false));
+  CHECK(check_ptr(Vhat, "Vhat", false));
+  if (tokens == 0) return AQUAKV_OK;
+  const Plan pl = make_plan(L, tokens);
+  CHECK(check_ptr(workspace, "workspace", true));
+  if (workspace_bytes < pl.p_bytes + pl.khat_bytes)
+    return fail(AQUAKV_EWORKSPACE, "workspace %zu B < required %zu B", workspace_bytes, pl.p_bytes + pl.khat_bytes);
+
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  float* Pbuf = static_cast<float*>(workspace);
+  void* khat_tmp = static_cast<unsigned char*>(workspace) + pl.p_bytes;
+  const size_t row = (size_t)pl.D * pl.eb;
+  const size_t srow = (size_t)L->kv_heads * sizeof(uint16_t);
+  const int D = pl.D, H = L->kv_heads;
+
+  for (int64_t r0 = 0; r0 < tokens; r0 += pl.chunk) {
+    const int64_t n = tokens - r0 < pl.chunk ? tokens - r0 : pl.chunk;
+    // keys:  K_pred = f_key(Khat_prev);  K_q = Q(K - K_pred);  Khat = Q^-1(K_q) + K_pred
+    if (has_k)
+      HIP_TRY(aquakv::launch_predict(L->dtype, at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k, nullptr, 0,
+                                     L->w_k, L->b_k, Pbuf, n, D, stream));
+    void* khat_dst = Khat != nullptr ? at(Khat, r0, row) : (has_v ? khat_tmp : nullptr);
+    HIP_TRY(aquakv::launch_quantize(L->dtype, L->n_codewords, at(K, r0, row), has_k ? Pbuf : nullptr, L->signs_k,
+                                    L->codebook, static_cast<uint8_t*>(at(k_codes, r0, pl.code_row)),
+                                    static_cast<uint16_t*>(at(k_scales, r0, srow)), khat_dst, n, H, stream));
+    // values: V_pred = f_value([Vhat_prev; Khat]);  V_q = Q(V - V_pred)
+    if (has_v)
+      HIP_TRY(aquakv::launch_predict(L->dtype, at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb), L->d_in_v - D,
+                                     khat_dst, D, L->w_v, L->b_v, Pbuf, n, D, stream));
+    HIP_TRY(aquakv::launch_quantize(L->dtype, L->n_codewords, at(V, r0, row), has_v ? Pbuf : nullptr, L->signs_v,
+                                    L->codebook, static_cast<uint8_t*>(at(v_codes, r0, pl.code_row)),
+                                    static_cast<uint16_t*>(at(v_scales, r0, srow)), at(Vhat, r0, row), n, H, stream));
+  }
+  return AQUAKV_OK;
+}
+
+int aquakv_decode_layer(const aquakv_layer* L, int64_t tokens, const uint8_t* k_codes, const uint16_t* k_scales,
+                        const uint8_t* v_codes, const uint16_t* v_scales, const void* Khat_prev, const void* Vhat_prev,
+                        void* Khat, void* Vhat, void* workspace, size_t workspace_bytes, void* stream_) {
+  CHECK(check_layer(L));
+  if (tokens < 0) return fail(AQUAKV_EINVAL, "tokens=%lld", (long long)tokens);
+  const bool want_v = Vhat != nullptr;
+  const bool has_k = L->d_in_k != 0, has_v = L->d_in_v != 0 && want_v;
+  CHECK(check_ptr(k_codes, "k_codes", true));
+  CHECK(check_ptr(k_scales, "k_scales", true));
+  CHECK(check_ptr(v_codes, "v_codes", want_v));
+  CHECK(check_ptr(v_scales, "v_scales", want_v));
+  CHECK(check_ptr(Khat_prev, "Khat_prev", has_k));
+  CHECK(check_ptr(Vhat_prev, "Vhat_prev", has_v));
+  CHECK(check_ptr(Khat, "Khat", true));
+  CHECK(check_ptr(Vhat, "Vhat", false));
+  if (tokens == 0) return AQUAKV_OK;
+  const Plan pl = make_plan(L, tokens);
+  CHECK(check_ptr(workspace, "workspace", true));
+  if (workspace_bytes < pl.p_bytes + pl.khat_bytes)
+    return fail(AQUAKV_EWORKSPACE, "workspace %zu B < required %zu B", workspace_bytes, pl.p_bytes + pl.khat_bytes);
+
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  float* Pbuf = static_cast<float*>(workspace);
+  const size_t row = (size_t)pl.D * pl.eb;
+  const size_t srow = (size_t)L->kv_heads * sizeof(uint16_t);
+  const int D = pl.D, H = L->kv_heads;
+
+  for (int64_t r0 = 0; r0 < tokens; r0 += pl.chunk) {
+    const int64_t n = tokens - r0 < pl.chunk ? tokens - r0 : pl.chunk;
+    // Khat = Q^-1(K_q) + f_key(Khat_prev)
+    if (has_k)
+      HIP_TRY(aquakv::launch_predict(L->dtype, at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k, nullptr, 0,
+                                     L->w_k, L->b_k, Pbuf, n, D, stream));
+    HIP_TRY(aquakv::launch_dequantize(L->dtype, L->n_codewords, static_cast<const uint8_t*>(at(k_codes, r0, pl.code_row)),
+                                      static_cast<const uint16_t*>(at(k_scales, r0, srow)), has_k ? Pbuf : nullptr,
+                                      L->signs_k, L->codebook, at(Khat, r0, row), n, H, stream));
+    if (!want_v) continue;
+    // Vhat = Q^-1(V_q) + f_value([Vhat_prev; Khat])
+    if (has_v)
+      HIP_TRY(aquakv::launch_predict(L->dtype, at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb), L->d_in_v - D,
+                                     at(Khat, r0, row), D, L->w_v, L->b_v, Pbuf, n, D, stream));
+    HIP_TRY(aquakv::launch_dequantize(L->dtype, L->n_codewords, static_cast<const uint8_t*>(at(v_codes, r0, pl.code_row)),
+                                      static_cast<const uint16_t*>(at(v_scales, r0, srow)), has_v ? Pbuf : nullptr,
+                                      L->signs_v, L->codebook, at(Vhat, r0, row), n, H, stream));
+  }
+  return AQUAKV_OK;
+}
+
+int aquakv_decode_attn_scores(const aquakv_layer* L, int32_t batch, int32_t seq_len, int32_t q_heads,
+                              const uint8_t* k_codes, const uint16_t* k_scales, const void* Khat_prev, const void* q,
+                              float score_scale, float* scores, void* Khat_out, void* workspace,
+                              size_t workspace_bytes, void* stream_) {
+  CHECK(check_layer(L));
+  if (batch < 0 || seq_len < 0) return fail(AQUAKV_EINVAL, "batch=%d seq_len=%d", batch, seq_len);
+  if (q_heads < 1 || q_heads % L->kv_heads || q_heads / L->kv_heads > 8)
+    return fail(AQUAKV_EINVAL, "q_heads=%d must be a multiple of kv_heads=%d, at most 8x", q_heads, L->kv_heads);
+  const bool has_k = L->d_in_k != 0;
+  CHECK(check_ptr(k_codes, "k_codes", true));
+  CHECK(check_ptr(k_scales, "k_scales", true));
+  CHECK(check_ptr(Khat_prev, "Khat_prev", has_k));
+  CHECK(check_ptr(q, "q", true));
+  CHECK(check_ptr(scores, "scores", true));
+  CHECK(check_ptr(Khat_out, "Khat_out", false));
+  const int64_t tokens = (int64_t)batch * seq_len;
+  if (tokens == 0) return AQUAKV_OK;
+  const Plan pl = make_plan(L, tokens);
+  if (has_k) {
+    CHECK(check_ptr(workspace, "workspace", true));
+    if (workspace_bytes < pl.p_bytes)
+      return fail(AQUAKV_EWORKSPACE, "workspace %zu B < required %zu B", workspace_bytes, pl.p_bytes);
+  }
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  float* Pbuf = static_cast<float*>(workspace);
+  const size_t row = (size_t)pl.D * pl.eb;
+  const size_t srow = (size_t)L->kv_heads * sizeof(uint16_t);
+  for (int64_t r0 = 0; r0 < tokens; r0 += pl.chunk) {
+    const int64_t n = tokens - r0 < pl.chunk ? tokens - r0 : pl.chunk;
+    if (has_k)
+      HIP_TRY(aquakv::launch_predict(L->dtype, at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k, nullptr, 0,
+                                     L->w_k, L->b_k, Pbuf, n, pl.D, stream));
+    HIP_TRY(aquakv::launch_attn_scores(L->dtype, L->n_codewords, static_cast<const uint8_t*>(at(k_codes, r0, pl.code_row)),
+                                       static_cast<const uint16_t*>(at(k_scales, r0, srow)), has_k ? Pbuf : nullptr,
+                                       L->signs_k, L->codebook, q, score_scale, scores, at(Khat_out, r0, row), r0, n,
+                                       seq_len, L->kv_heads, q_heads, stream));
+  }
+  return AQUAKV_OK;
+}
+
+}  // extern "C"

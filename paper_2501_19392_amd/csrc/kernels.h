@@ -1,0 +1,31 @@
+// Host-side launchers of the gfx950 kernels (one per stage).  Arguments are
+// validated by the C-ABI layer before these are called.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace aquakv {
+
+enum Dtype : int { kBF16 = 0, kFP32 = 1 };
+
+// P[T, D] = [x0 (T x d0) | x1 (T x d1)] W^T + bias, W is [D, d0 + d1] row-major.
+hipError_t launch_predict(int dtype, const void* x0, int d0, const void* x1, int d1, const void* W,
+                          const float* bias, float* P, int64_t T, int D, hipStream_t stream);
+
+// Q(X - P): codes, scales and (optionally) the reconstruction.  rows = T, H heads of 128.
+hipError_t launch_quantize(int dtype, int n_codewords, const void* X, const float* P, const int8_t* signs,
+                           const float* codebook, uint8_t* codes, uint16_t* scales, void* Xhat, int64_t T, int H,
+                           hipStream_t stream);
+
+hipError_t launch_dequantize(int dtype, int n_codewords, const uint8_t* codes, const uint16_t* scales, const float* P,
+                             const int8_t* signs, const float* codebook, void* Xhat, int64_t T, int H,
+                             hipStream_t stream);
+
+// scores[b, qh, t] for rows [row0, row0 + rows) of the flattened [batch*seq_len] axis.
+// codes/scales/P/Khat_out point at row `row0`; q and scores at their tensor bases.
+hipError_t launch_attn_scores(int dtype, int n_codewords, const uint8_t* codes, const uint16_t* scales, const float* P,
+                              const int8_t* signs, const float* codebook, const void* q, float score_scale,
+                              float* scores, void* Khat_out, int64_t row0, int64_t rows, int seq_len, int H,
+                              int q_heads, hipStream_t stream);
+
+}  // namespace aquakv

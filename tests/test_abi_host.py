@@ -1,0 +1,104 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every
+symbol the header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2501_19392_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000  # a 16-byte aligned non-NULL address; never dereferenced on a validation error
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "aquakv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(aquakv_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    syms = header_symbols()
+    assert set(syms) == set(B.EXPORTS)
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for s in syms:
+        assert hasattr(lib, s), s
+    assert B.aquakv_version() == 100
+    assert B.aquakv_status_string(0) == "ok" and "workspace" in B.aquakv_status_string(B.AQUAKV_EWORKSPACE)
+
+
+def layer(**kw):
+    d = dict(kv_heads=8, head_dim=128, vq_dim=2, n_codewords=16, dtype=B.AQUAKV_BF16, d_in_k=1024, d_in_v=2048,
+             reserved=0, codebook=FAKE, signs_k=FAKE, signs_v=FAKE, w_k=FAKE, b_k=None, w_v=FAKE, b_v=None)
+    d.update(kw)
+    return B.aquakv_layer(**d)
+
+
+def status_of(fn, *a):
+    with pytest.raises(B.AquaKVError) as e:
+        fn(*a)
+    return e.value.status
+
+
+ENC_OK = [FAKE] * 10  # K V Khat_prev Vhat_prev k_codes k_scales v_codes v_scales Khat Vhat
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(head_dim=100), B.AQUAKV_EINVAL),
+    (dict(head_dim=64), B.AQUAKV_EUNSUPPORTED),
+    (dict(vq_dim=4), B.AQUAKV_EUNSUPPORTED),
+    (dict(n_codewords=17), B.AQUAKV_EINVAL),
+    (dict(n_codewords=32), B.AQUAKV_EUNSUPPORTED),
+    (dict(dtype=7), B.AQUAKV_EINVAL),
+    (dict(kv_heads=0), B.AQUAKV_EINVAL),
+    (dict(d_in_k=100), B.AQUAKV_EINVAL),
+    (dict(d_in_v=1024), B.AQUAKV_EINVAL),
+    (dict(codebook=None), B.AQUAKV_ENULL),
+    (dict(w_k=None), B.AQUAKV_ENULL),
+    (dict(signs_v=FAKE + 4), B.AQUAKV_EALIGN),
+    (dict(reserved=1), B.AQUAKV_EINVAL),
+])
+def test_bad_layer_is_rejected(kw, want):
+    L = layer(**kw)
+    assert status_of(B.aquakv_encode_layer, L, 128, *ENC_OK, (FAKE, 1 << 40)) == want
+    assert B.aquakv_workspace_bytes(L, 128) == 0
+    assert B.aquakv_last_error() != ""
+
+
+def test_bad_call_arguments_are_rejected_without_launching():
+    L = layer()
+    need = B.aquakv_workspace_bytes(L, 300)
+    assert need == 300 * 1024 * (4 + 2)
+    assert B.aquakv_workspace_bytes(L, 1 << 20) == 16384 * 1024 * 6          # chunked: bounded
+    args = list(ENC_OK)
+    assert status_of(B.aquakv_encode_layer, L, -1, *args, (FAKE, need)) == B.AQUAKV_EINVAL
+    assert status_of(B.aquakv_encode_layer, L, 300, *args, (FAKE, need - 1)) == B.AQUAKV_EWORKSPACE
+    assert "workspace" in B.aquakv_last_error()
+    assert status_of(B.aquakv_encode_layer, L, 300, *args, None) == B.AQUAKV_ENULL
+    for i in (0, 1, 2, 3, 4, 5, 6, 7):                                          # required pointers
+        bad = list(args)
+        bad[i] = None
+        assert status_of(B.aquakv_encode_layer, L, 300, *bad, (FAKE, need)) == B.AQUAKV_ENULL
+        bad[i] = FAKE + 8
+        assert status_of(B.aquakv_encode_layer, L, 300, *bad, (FAKE, need)) == B.AQUAKV_EALIGN
+    # tokens == 0 is a no-op even without a workspace
+    B.aquakv_encode_layer(L, 0, *args, None)
+    B.aquakv_decode_layer(L, 0, *([FAKE] * 8), None)
+    # layer 0 (no predictors) needs no *_prev
+    L0 = layer(d_in_k=0, d_in_v=0, w_k=None, w_v=None)
+    a0 = list(args)
+    a0[2] = a0[3] = None
+    assert status_of(B.aquakv_encode_layer, L0, 300, *a0, (FAKE, 10)) == B.AQUAKV_EWORKSPACE
+    # stage calls
+    assert status_of(B.aquakv_predict, L0, B.AQUAKV_KEY, 8, FAKE, None, FAKE) == B.AQUAKV_EINVAL
+    assert status_of(B.aquakv_predict, L, B.AQUAKV_VALUE, 8, FAKE, None, FAKE) == B.AQUAKV_ENULL
+    assert status_of(B.aquakv_predict, L, 5, 8, FAKE, FAKE, FAKE) == B.AQUAKV_EINVAL
+    assert status_of(B.aquakv_quantize, L, B.AQUAKV_KEY, 8, FAKE, None, None, FAKE, None) == B.AQUAKV_ENULL
+    assert status_of(B.aquakv_dequantize, L, B.AQUAKV_KEY, 8, FAKE, FAKE, None, None) == B.AQUAKV_ENULL
+    # scores
+    sc = [FAKE, FAKE, FAKE, FAKE, 1.0, FAKE, None]
+    assert status_of(B.aquakv_decode_attn_scores, L, 2, 16, 12, *sc, (FAKE, 1 << 30)) == B.AQUAKV_EINVAL   # 12 % 8
+    assert status_of(B.aquakv_decode_attn_scores, L, 2, 16, 128, *sc, (FAKE, 1 << 30)) == B.AQUAKV_EINVAL  # > 8x
+    assert status_of(B.aquakv_decode_attn_scores, L, 2, 16, 32, *sc, (FAKE, 16)) == B.AQUAKV_EWORKSPACE
+    B.aquakv_decode_attn_scores(L, 0, 16, 32, *sc, None)

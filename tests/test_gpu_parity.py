@@ -1,0 +1,349 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element
+by element on the same seeded inputs.  Codes and scales must be bit-exact except
+for counted ties; reconstructions within 1e-5 (fp32) / 2e-2 (bf16) relative."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import aquakv_oracle as O
+from paper_2501_19392_amd import synth
+from tests import parity_utils as U
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: the gpu-marked tests must run on an MI355X")
+    from paper_2501_19392_amd import binding
+    return binding
+
+
+def storage_randn(shape, dtype, seed, scale=1.0, device="cuda"):
+    g = torch.Generator().manual_seed(seed)
+    return (torch.randn(*shape, generator=g) * scale).to(synth.torch_dtype(dtype)).to(device)
+
+
+def sync():
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ predictor
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("T,H", [(1, 2), (300, 2), (515, 8)])
+def test_predict_matches_oracle_and_is_row_count_invariant(B, dtype, T, H):
+    print(f"case predict dtype={dtype} T={T} H={H}", flush=True)
+    D = H * 128
+    wk = U.random_weights(D, D, 1)
+    wv = U.random_weights(D, 2 * D, 2)
+    bk = torch.randn(D, generator=torch.Generator().manual_seed(3))
+    lo, lg = U.make_layers(H, dtype, 16, w_k=wk, w_v=wv, b_k=bk)
+    x0 = storage_randn((T, D), dtype, 4)
+    x1 = storage_randn((T, D), dtype, 5)
+    P = torch.empty(T, D, dtype=torch.float32, device="cuda")
+    for which, a0, a1, W, b in ((B.AQUAKV_KEY, x0, None, lo.w_k, lo.b_k), (B.AQUAKV_VALUE, x0, x1, lo.w_v, lo.b_v)):
+        B.aquakv_predict(lg, which, T, a0, a1, P)
+        sync()
+        xin = U.np64(a0) if a1 is None else np.concatenate([U.np64(a0), U.np64(a1)], axis=1)
+        want = O.predict(xin, W, b)
+        mag = np.abs(xin) @ np.abs(W).T + (0 if b is None else np.abs(b))
+        err = np.abs(U.np64(P) - want)
+        assert np.all(err <= 4e-6 * mag + 1e-30), float(np.max(err / (mag + 1e-30)))
+        # the same rows alone (a different launch shape) give the same bits
+        rows = [0, T // 2, T - 1]
+        for r in rows:
+            P1 = torch.empty(1, D, dtype=torch.float32, device="cuda")
+            B.aquakv_predict(lg, which, 1, a0[r:r + 1].contiguous(), None if a1 is None else a1[r:r + 1].contiguous(), P1)
+            sync()
+            assert torch.equal(P1[0], P[r])
+
+
+# ------------------------------------------------------------------ quantizer stages
+@pytest.mark.parametrize("dtype,n,T,H", [("fp32", 16, 256, 2), ("bf16", 16, 300, 8), ("bf16", 64, 257, 8),
+                                        ("fp32", 64, 33, 2), ("bf16", 256, 65, 4), ("fp32", 16, 1, 1)])
+@pytest.mark.parametrize("with_p", [False, True])
+def test_quantize_codes_scales_and_reconstruction(B, dtype, n, T, H, with_p):
+    print(f"case quantize dtype={dtype} n={n} T={T} H={H} with_p={with_p}", flush=True)
+    lo, lg = U.make_layers(H, dtype, n)
+    D = H * 128
+    ch = synth.channel_scales(D, 0, 0).float()
+    X = (storage_randn((T, D), "fp32", 10, device="cpu") * ch).to(synth.torch_dtype(dtype)).cuda().reshape(T, H, 128)
+    P = (storage_randn((T, D), "fp32", 11) * 0.8).reshape(T, H, 128).contiguous() if with_p else None
+    for which, signs in ((B.AQUAKV_KEY, lo.signs_k), (B.AQUAKV_VALUE, lo.signs_v)):
+        codes, scales = lg.alloc_codes(T)
+        Xhat = lg.alloc_kv(T)
+        B.aquakv_quantize(lg, which, T, X, P, codes, scales, Xhat)
+        sync()
+        p64 = np.zeros((T, H, 128)) if P is None else U.np64(P)
+        rep = U.compare_quantizer_outputs(U.np64(X) - p64, signs, lo.codebook, codes.cpu().numpy(),
+                                          scales.cpu().numpy(), n)
+        print("  ", rep, flush=True)
+        assert rep.other == 0, str(rep)
+        assert rep.code_mismatch <= max(2, rep.subvectors // 20000) and rep.scale_mismatch <= max(1, rep.groups // 500)
+        # the reconstruction is the oracle's decode of the GPU's own codes
+        g_idx = O.unpack_codes(codes.cpu().numpy(), n)
+        g_s16 = scales.cpu().numpy().view(np.float16)
+        want = O.round_storage(O.dequantize(g_idx, g_s16, signs, lo.codebook) + p64, dtype)
+        U.assert_close_storage(Xhat, want, dtype, "Xhat")
+        # and bit-identical to what the dequantize entry point gives
+        X2 = lg.alloc_kv(T)
+        B.aquakv_dequantize(lg, which, T, codes, scales, P, X2)
+        sync()
+        assert torch.equal(X2.view(torch.int16 if dtype == "bf16" else torch.int32),
+                           Xhat.view(torch.int16 if dtype == "bf16" else torch.int32))
+
+
+@pytest.mark.parametrize("dtype,n", [("fp32", 16), ("bf16", 64), ("bf16", 256)])
+def test_dequantize_random_codes(B, dtype, n):
+    print(f"case dequantize dtype={dtype} n={n}", flush=True)
+    T, H = 131, 8
+    lo, lg = U.make_layers(H, dtype, n)
+    rng = np.random.Generator(np.random.PCG64(12))
+    idx = rng.integers(0, n, size=(T, H, 64))
+    s16 = (np.abs(rng.standard_normal((T, H))) * 10 ** rng.uniform(-3, 2, (T, H))).astype(np.float16)
+    s16[0, 0] = 0
+    codes = torch.from_numpy(O.pack_codes(idx, n)).cuda()
+    scales = torch.from_numpy(s16.view(np.int16)).cuda()
+    P = (storage_randn((T, H * 128), "fp32", 13) * 3).reshape(T, H, 128).contiguous()
+    Xhat = lg.alloc_kv(T)
+    B.aquakv_dequantize(lg, B.AQUAKV_VALUE, T, codes, scales, P, Xhat)
+    sync()
+    want = O.round_storage(O.dequantize(idx, s16, lo.signs_v, lo.codebook) + U.np64(P), dtype)
+    U.assert_close_storage(Xhat, want, dtype, "dequantize")
+
+
+def test_quantize_edge_cases(B):
+    """Zero residual, huge values (scale clamps at the fp16 maximum), tiny values (subnormal
+    fp16 scales), in-place reconstruction, and a row count that leaves most of a block idle."""
+    print("case quantize edge cases", flush=True)
+    H, n, T = 2, 16, 5
+    lo, lg = U.make_layers(H, "fp32", n)
+    X = storage_randn((T, H, 128), "fp32", 20)
+    X[1] *= 3e6          # sigma above 65504 -> clamped
+    X[2] *= 1e-6         # sigma in the fp16 subnormal range
+    X[3] = 0             # zero residual
+    P = torch.zeros_like(X)
+    P[4] = X[4]          # residual exactly zero with a non-zero prediction
+    codes, scales = lg.alloc_codes(T)
+    Xhat = X.clone()
+    B.aquakv_quantize(lg, B.AQUAKV_KEY, T, Xhat, P, codes, scales, Xhat)      # in place
+    sync()
+    s16 = scales.cpu().numpy().view(np.float16)
+    assert np.all(s16[1] == np.float16(65504)) and np.all(s16[3] == 0) and np.all(s16[4] == 0)
+    assert np.all(s16[2] > 0) and np.all(s16[2] < 6.2e-5)
+    rep = U.compare_quantizer_outputs(U.np64(X) - U.np64(P), lo.signs_k, lo.codebook, codes.cpu().numpy(),
+                                      scales.cpu().numpy(), n)
+    print("  ", rep, flush=True)
+    assert rep.other == 0 and rep.code_mismatch == 0 and rep.scale_mismatch == 0, str(rep)
+    assert torch.equal(Xhat[3], torch.zeros_like(Xhat[3])) and torch.equal(Xhat[4], X[4])
+    g_idx = O.unpack_codes(codes.cpu().numpy(), n)
+    want = O.round_storage(O.dequantize(g_idx, s16, lo.signs_k, lo.codebook) + U.np64(P), "fp32")
+    U.assert_close_storage(Xhat, want, "fp32", "edge Xhat")
+    # tokens = 0: nothing is touched
+    B.aquakv_quantize(lg, B.AQUAKV_KEY, 0, X, None, codes, scales, None)
+    sync()
+
+
+# ------------------------------------------------------------------ whole layers
+def run_gpu_layers(B, cfg, layers_g, Ks, Vs, want_hat=True):
+    """encode every layer in order on the GPU, feeding reconstructions forward."""
+    T = Ks[0].shape[0]
+    out = []
+    Kp = Vp = None
+    for l, lg in enumerate(layers_g):
+        kc, ks = lg.alloc_codes(T)
+        vc, vs = lg.alloc_codes(T)
+        Kh, Vh = lg.alloc_kv(T), lg.alloc_kv(T)
+        ws = lg.alloc_workspace(T)
+        B.aquakv_encode_layer(lg, T, Ks[l], Vs[l], Kp, Vp, kc, ks, vc, vs, Kh, Vh, ws)
+        sync()
+        out.append(dict(k_codes=kc, k_scales=ks, v_codes=vc, v_scales=vs, Khat=Kh, Vhat=Vh, Kp=Kp, Vp=Vp))
+        Kp, Vp = Kh, Vh
+    return out
+
+
+def build_stack(cfg, device="cuda", predictors="analytic"):
+    st = synth.KVStream(cfg, device="cpu", work=torch.float64)
+    Ks, Vs, lo_l, lg_l = [], [], [], []
+    for l in range(cfg.layers):
+        K, V = st.next()
+        Ks.append(K.to(device))
+        Vs.append(V.to(device))
+        if l == 0:
+            lo, lg = U.make_layers(cfg.kv_heads, cfg.dtype, cfg.n_codewords, layer_idx=l)
+        else:
+            if predictors == "analytic":
+                wk, wv = synth.analytic_predictors(st, l)
+            else:
+                wk, wv = U.random_weights(cfg.d, cfg.d, 100 + l, 0.7), U.random_weights(cfg.d, 2 * cfg.d, 200 + l, 0.7)
+            lo, lg = U.make_layers(cfg.kv_heads, cfg.dtype, cfg.n_codewords, layer_idx=l, w_k=wk, w_v=wv)
+        lo_l.append(lo)
+        lg_l.append(lg)
+    return Ks, Vs, lo_l, lg_l
+
+
+def bits(t):
+    return t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32)
+
+
+def check_layer_against_oracle(B, lo, lg, K, V, g, rows=None):
+    """One layer, teacher-forced at every stage boundary with the GPU's own tensors:
+    each stage of the GPU result must match the oracle given the same inputs."""
+    n = lo.n_codewords
+    sel = slice(None) if rows is None else rows
+    T = K.shape[0]
+    D = lo.kv_heads * lo.head_dim
+    shape = (-1, lo.kv_heads, lo.head_dim)
+    reports = []
+    for which, X, codes, scales, hat, signs in (
+            ("k", K, g["k_codes"], g["k_scales"], g["Khat"], lo.signs_k),
+            ("v", V, g["v_codes"], g["v_scales"], g["Vhat"], lo.signs_v)):
+        has = (lo.w_k if which == "k" else lo.w_v) is not None
+        if has:
+            P = torch.empty(T, D, dtype=torch.float32, device="cuda")
+            if which == "k":
+                B.aquakv_predict(lg, B.AQUAKV_KEY, T, g["Kp"], None, P)
+                xin = U.np64(g["Kp"][sel]).reshape(-1, D)
+                want_p = O.predict(xin, lo.w_k, lo.b_k)
+                W = lo.w_k
+            else:
+                B.aquakv_predict(lg, B.AQUAKV_VALUE, T, g["Vp"], g["Khat"], P)
+                xin = np.concatenate([U.np64(g["Vp"][sel]).reshape(-1, D), U.np64(g["Khat"][sel]).reshape(-1, D)], 1)
+                want_p = O.predict(xin, lo.w_v, lo.b_v)
+                W = lo.w_v
+            sync()
+            p64 = U.np64(P[sel])
+            mag = np.abs(xin) @ np.abs(W).T
+            assert np.all(np.abs(p64 - want_p) <= 4e-6 * mag + 1e-30)
+            p64 = p64.reshape(shape)
+        else:
+            p64 = np.zeros((U.np64(X[sel]).reshape(shape)).shape)
+        x64 = U.np64(X[sel]).reshape(shape)
+        c = codes[sel].cpu().numpy()
+        s = scales[sel].cpu().numpy()
+        rep = U.compare_quantizer_outputs(x64 - p64, signs, lo.codebook, c, s, n)
+        reports.append(rep)
+        assert rep.other == 0, f"{which}: {rep}"
+        want = O.round_storage(O.dequantize(O.unpack_codes(c, n), s.view(np.float16), signs, lo.codebook) + p64, lo.dtype)
+        U.assert_close_storage(hat[sel], want, lo.dtype, which + "hat")
+    return reports
+
+
+@pytest.mark.parametrize("predictors", ["analytic", "random"])
+def test_tiny_config_fp32_end_to_end(B, predictors):
+    """Config 'Tiny' in full: every stage of every layer against the oracle, then the free-running
+    oracle (no teacher forcing), then decode reproduces encode bit for bit."""
+    print(f"case tiny e2e predictors={predictors}", flush=True)
+    cfg = synth.TINY
+    Ks, Vs, lo_l, lg_l = build_stack(cfg, predictors=predictors)
+    out = run_gpu_layers(B, cfg, lg_l, Ks, Vs)
+    for l in range(cfg.layers):
+        for rep in check_layer_against_oracle(B, lo_l[l], lg_l[l], Ks[l], Vs[l], out[l]):
+            print(f"   layer {l}: {rep}", flush=True)
+    # free-running oracle over both layers
+    Kp = Vp = None
+    for l in range(cfg.layers):
+        e = O.encode_layer(lo_l[l], U.np64(Ks[l]), U.np64(Vs[l]), Kp, Vp)
+        for name, codes_name, scales_name in (("Khat", "k_codes", "k_scales"), ("Vhat", "v_codes", "v_scales")):
+            same_codes = np.array_equal(e[codes_name], out[l][codes_name].cpu().numpy())
+            same_scales = np.array_equal(e[scales_name].view(np.int16), out[l][scales_name].cpu().numpy())
+            print(f"   free-run layer {l} {name}: codes identical={same_codes} scales identical={same_scales}", flush=True)
+            if same_codes and same_scales:
+                U.assert_close_storage(out[l][name], e[name], cfg.dtype, f"free-run {name}")
+            rel = np.linalg.norm(U.np64(out[l][name]) - e[name]) / np.linalg.norm(e[name])
+            assert rel < 2e-3, rel
+        Kp, Vp = e["Khat"], e["Vhat"]
+    # closed loop
+    for l in range(cfg.layers):
+        g, lg = out[l], lg_l[l]
+        Kh, Vh = lg.alloc_kv(cfg.tokens), lg.alloc_kv(cfg.tokens)
+        B.aquakv_decode_layer(lg, cfg.tokens, g["k_codes"], g["k_scales"], g["v_codes"], g["v_scales"], g["Kp"], g["Vp"],
+                              Kh, Vh, lg.alloc_workspace(cfg.tokens))
+        sync()
+        assert torch.equal(bits(Kh), bits(g["Khat"])) and torch.equal(bits(Vh), bits(g["Vhat"]))
+
+
+@pytest.mark.parametrize("n", [16, 64])
+def test_bf16_three_layers_ragged(B, n):
+    print(f"case bf16 3 layers n={n}", flush=True)
+    cfg = synth.Config("mid", layers=3, kv_heads=8, head_dim=128, tokens=389, dtype="bf16", n_codewords=n)
+    Ks, Vs, lo_l, lg_l = build_stack(cfg)
+    out = run_gpu_layers(B, cfg, lg_l, Ks, Vs)
+    for l in range(cfg.layers):
+        for rep in check_layer_against_oracle(B, lo_l[l], lg_l[l], Ks[l], Vs[l], out[l]):
+            print(f"   layer {l}: {rep}", flush=True)
+        g, lg = out[l], lg_l[l]
+        Kh, Vh = lg.alloc_kv(cfg.tokens), lg.alloc_kv(cfg.tokens)
+        B.aquakv_decode_layer(lg, cfg.tokens, g["k_codes"], g["k_scales"], g["v_codes"], g["v_scales"], g["Kp"], g["Vp"],
+                              Kh, Vh, lg.alloc_workspace(cfg.tokens))
+        sync()
+        assert torch.equal(bits(Kh), bits(g["Khat"])) and torch.equal(bits(Vh), bits(g["Vhat"]))
+        # decoding a sub-range of rows on its own gives the same bits (append path, M-independence)
+        r0, r1 = 100, 164
+        Kh2, Vh2 = lg.alloc_kv(r1 - r0), lg.alloc_kv(r1 - r0)
+        cut = lambda t: None if t is None else t[r0:r1].contiguous()
+        B.aquakv_decode_layer(lg, r1 - r0, cut(g["k_codes"]), cut(g["k_scales"]), cut(g["v_codes"]), cut(g["v_scales"]),
+                              cut(g["Kp"]), cut(g["Vp"]), Kh2, Vh2, lg.alloc_workspace(r1 - r0))
+        sync()
+        assert torch.equal(bits(Kh2), bits(g["Khat"][r0:r1])) and torch.equal(bits(Vh2), bits(g["Vhat"][r0:r1]))
+    # the quality claim of Sect. 3.1 on the GPU's own output: predictors cut the error several-fold
+    K2 = U.np64(Ks[2])
+    err_pred = np.sum((U.np64(out[2]["Khat"]) - K2) ** 2) / np.sum(K2 ** 2)
+    assert err_pred < (0.06 if n == 16 else 0.02), err_pred
+
+
+def test_encode_without_optional_outputs_matches(B):
+    """Khat / Vhat may be NULL: codes and scales must not change."""
+    print("case optional outputs", flush=True)
+    cfg = synth.Config("opt", layers=2, kv_heads=2, head_dim=128, tokens=77, dtype="bf16")
+    Ks, Vs, lo_l, lg_l = build_stack(cfg)
+    out = run_gpu_layers(B, cfg, lg_l, Ks, Vs)
+    g, lg, T = out[1], lg_l[1], cfg.tokens
+    kc, ks = lg.alloc_codes(T)
+    vc, vs = lg.alloc_codes(T)
+    B.aquakv_encode_layer(lg, T, Ks[1], Vs[1], g["Kp"], g["Vp"], kc, ks, vc, vs, None, None, lg.alloc_workspace(T))
+    sync()
+    for a, b in ((kc, g["k_codes"]), (ks, g["k_scales"]), (vc, g["v_codes"]), (vs, g["v_scales"])):
+        assert torch.equal(a, b)
+    # keys only decode
+    Kh = lg.alloc_kv(T)
+    B.aquakv_decode_layer(lg, T, kc, ks, None, None, g["Kp"], None, Kh, None, lg.alloc_workspace(T))
+    sync()
+    assert torch.equal(bits(Kh), bits(g["Khat"]))
+
+
+# ------------------------------------------------------------------ fused dequant + q.k
+@pytest.mark.parametrize("dtype,n,with_pred", [("fp32", 16, True), ("bf16", 16, True), ("bf16", 64, False),
+                                               ("bf16", 16, False)])
+def test_attn_scores(B, dtype, n, with_pred):
+    print(f"case scores dtype={dtype} n={n} pred={with_pred}", flush=True)
+    H, QH, batch, S = 8, 32, 3, 150
+    cfg = synth.Config("sc", layers=2, kv_heads=H, head_dim=128, tokens=batch * S, dtype=dtype, n_codewords=n)
+    Ks, Vs, lo_l, lg_l = build_stack(cfg)
+    out = run_gpu_layers(B, cfg, lg_l, Ks, Vs)
+    l = 1 if with_pred else 0
+    g, lg, lo = out[l], lg_l[l], lo_l[l]
+    q = synth.random_queries(batch, QH, 128, seed=77, dtype=dtype, device="cuda")
+    scores = torch.empty(batch, QH, S, dtype=torch.float32, device="cuda")
+    Kout = lg.alloc_kv(cfg.tokens)
+    B.aquakv_decode_attn_scores(lg, batch, S, QH, g["k_codes"], g["k_scales"], g["Kp"], q, 0.125, scores, Kout,
+                                lg.alloc_workspace(cfg.tokens))
+    sync()
+    assert torch.equal(bits(Kout), bits(g["Khat"]))
+    kp = None if g["Kp"] is None else U.np64(g["Kp"])
+    want = O.attn_scores(lo, batch, S, U.np64(q), g["k_codes"].cpu().numpy(), g["k_scales"].cpu().numpy().view(np.float16),
+                         kp, 0.125)
+    # tolerance relative to sum_d |q_d| |k_d| of the GPU's own keys
+    Kh = np.abs(U.np64(g["Khat"])).reshape(batch, S, H, 128)
+    mag = np.stack([np.einsum("bd,btd->bt", np.abs(U.np64(q))[:, qh], Kh[:, :, qh // (QH // H)]) for qh in range(QH)], 1)
+    err = np.abs(U.np64(scores) - want)
+    rtol = U.RTOL[dtype]
+    assert np.all(err <= rtol * 0.125 * mag + 1e-30), float(np.max(err / (0.125 * mag + 1e-30)))
+    print(f"   worst score error / (sum|q||k|) = {float(np.max(err / (0.125 * mag + 1e-30))):.3g}", flush=True)
+    # without Khat_out the scores are the same bits
+    s2 = torch.empty_like(scores)
+    B.aquakv_decode_attn_scores(lg, batch, S, QH, g["k_codes"], g["k_scales"], g["Kp"], q, 0.125, s2, None,
+                                lg.alloc_workspace(cfg.tokens))
+    sync()
+    assert torch.equal(s2, scores)
