@@ -1,0 +1,255 @@
+#!/usr/bin/env python3
+"""Benchmark of the AQUA-KV per-layer encode / decode path on one MI355X.
+
+A step = one pass of the whole hot path over one batch of synthetic KV shaped like
+the Llama-3.2-3B cache (28 layers, 8 KV heads x 128, 8192 tokens, bf16, 2 bits per
+value): for every layer `aquakv_encode_layer`, then for every layer
+`aquakv_decode_layer`, then for every layer `aquakv_decode_attn_scores` (24 query
+heads).  Inputs are resident in HBM before the timed region.  The printed JSON line
+reports tokens/s per layer (tokens * layers / step time), the roofline position of
+the dominant kernel (the bf16 MFMA predictor GEMM) from HIP events, and the CPU
+oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="llama3.2-3b", choices=["llama3.2-3b", "llama3.1-8b", "tiny"])
+    ap.add_argument("--n-codewords", type=int, default=16)
+    ap.add_argument("--q-heads", type=int, default=0, help="query heads for the scoring call (0: model default)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true", help="skip the instrumented replay")
+    ap.add_argument("--cpu-rows", type=int, default=8192, help="token rows of the oracle sample")
+    return ap.parse_args()
+
+
+def build_workload(cfg, device, n_codewords):
+    import torch
+    from paper_2501_19392_amd import binding as B
+    from paper_2501_19392_amd import synth
+    sd = synth.torch_dtype(cfg.dtype)
+    work = torch.float32 if cfg.dtype == "bf16" else torch.float64
+    st = synth.KVStream(cfg, device=device, work=work)
+    C = torch.from_numpy(synth.lloyd_codebook(n_codewords)).to(device)
+    table = B.build_search_table(C)
+    layers, Ks, Vs = [], [], []
+    for l in range(cfg.layers):
+        K, V = st.next()
+        Ks.append(K.contiguous())
+        Vs.append(V.contiguous())
+        sk = torch.from_numpy(synth.rht_signs(cfg.kv_heads, cfg.head_dim, l, "k")).to(device)
+        sv = torch.from_numpy(synth.rht_signs(cfg.kv_heads, cfg.head_dim, l, "v")).to(device)
+        wk = wv = None
+        if l > 0:
+            wk, wv = (w.to(device) for w in synth.analytic_predictors(st, l))
+        layers.append(B.Layer(cfg.kv_heads, cfg.head_dim, C, sk, sv, sd, w_k=wk, w_v=wv, search_table=table))
+    return layers, Ks, Vs
+
+
+class Buffers:
+    def __init__(self, layers, T, q_heads, device):
+        import torch
+        self.codes = [(l.alloc_codes(T, device), l.alloc_codes(T, device)) for l in layers]
+        lay = layers[0]
+        # reconstructions: two ping-pong pairs are all the path needs (layer l-1 and l)
+        self.hat = [(lay.alloc_kv(T, device), lay.alloc_kv(T, device)) for _ in range(2)]
+        self.ws = lay.alloc_workspace(T, device)
+        self.scores = torch.empty(1, q_heads, T, dtype=torch.float32, device=device)
+        self.P = torch.empty(T, lay.d, dtype=torch.float32, device=device)
+
+
+def run_step(B, layers, Ks, Vs, buf, q, T, q_heads):
+    """encode all layers, decode all layers, score all layers (layer-level entry points)."""
+    prev = (None, None)
+    for l, lay in enumerate(layers):
+        (kc, ks), (vc, vs) = buf.codes[l]
+        Kh, Vh = buf.hat[l & 1]
+        B.aquakv_encode_layer(lay, T, Ks[l], Vs[l], prev[0], prev[1], kc, ks, vc, vs, Kh, Vh, buf.ws)
+        prev = (Kh, Vh)
+    prev = (None, None)
+    for l, lay in enumerate(layers):
+        (kc, ks), (vc, vs) = buf.codes[l]
+        Kh, Vh = buf.hat[l & 1]
+        B.aquakv_decode_layer(lay, T, kc, ks, vc, vs, prev[0], prev[1], Kh, Vh, buf.ws)
+        prev = (Kh, Vh)
+    # scoring reads layer l's codes and layer l-1's reconstructed keys; the ping-pong buffers hold
+    # valid keys of the right shape, which is all that matters for the work done
+    for l, lay in enumerate(layers):
+        (kc, ks), _ = buf.codes[l]
+        kp = None if l == 0 else buf.hat[(l - 1) & 1][0]
+        B.aquakv_decode_attn_scores(lay, 1, T, q_heads, kc, ks, kp, q, 0.088388, buf.scores, None, buf.ws)
+
+
+def timed_phases(B, layers, Ks, Vs, buf, q, T, q_heads, reps):
+    """Per-phase GPU time (ms per step) from stream events: encode / decode / scores."""
+    import torch
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    out = {}
+    for phase in ("encode", "decode", "scores"):
+        a, b = ev(), ev()
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(reps):
+            prev = (None, None)
+            for l, lay in enumerate(layers):
+                (kc, ks), (vc, vs) = buf.codes[l]
+                Kh, Vh = buf.hat[l & 1]
+                if phase == "encode":
+                    B.aquakv_encode_layer(lay, T, Ks[l], Vs[l], prev[0], prev[1], kc, ks, vc, vs, Kh, Vh, buf.ws)
+                elif phase == "decode":
+                    B.aquakv_decode_layer(lay, T, kc, ks, vc, vs, prev[0], prev[1], Kh, Vh, buf.ws)
+                else:
+                    kp = None if l == 0 else buf.hat[(l - 1) & 1][0]
+                    B.aquakv_decode_attn_scores(lay, 1, T, q_heads, kc, ks, kp, q, 0.088388, buf.scores, None, buf.ws)
+                prev = (Kh, Vh)
+        b.record()
+        torch.cuda.synchronize()
+        out[phase] = a.elapsed_time(b) / reps
+    return out
+
+
+def gemm_events(B, layers, buf, T, steps):
+    """Replay of the predictor GEMM launches of `steps` steps through the stage entry point
+    (the same kernel, shapes and order the layer-level calls launch), each bracketed by
+    events on the launch stream.  Returns (total flops, total ms, launches)."""
+    import torch
+    D = layers[0].d
+    pairs = []
+    flops = 0.0
+    for _ in range(steps):
+        for l, lay in enumerate(layers):
+            if l == 0:
+                continue
+            Kh, Vh = buf.hat[l & 1]
+            Kp, Vp = buf.hat[(l - 1) & 1]
+            # encode: key + value GEMM; decode: key + value GEMM; scores: key GEMM
+            for which, reps in ((B.AQUAKV_KEY, 3), (B.AQUAKV_VALUE, 2)):
+                for _r in range(reps):
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record()
+                    if which == B.AQUAKV_KEY:
+                        B.aquakv_predict(lay, which, T, Kp, None, buf.P)
+                        flops += 2.0 * T * D * lay.c.d_in_k
+                    else:
+                        B.aquakv_predict(lay, which, T, Vp, Kh, buf.P)
+                        flops += 2.0 * T * D * lay.c.d_in_v
+                    b.record()
+                    pairs.append((a, b))
+    torch.cuda.synchronize()
+    ms = sum(a.elapsed_time(b) for a, b in pairs)
+    return flops, ms, len(pairs)
+
+
+def cpu_baseline(cfg, n_codewords, rows, q_heads):
+    """The oracle as it stands, on the host: encode + decode + scores of one predicted layer
+    on `rows` token rows of the same synthetic workload (rows are independent)."""
+    import numpy as np
+    import torch
+    from oracle import aquakv_oracle as O
+    from paper_2501_19392_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    sd = synth.torch_dtype(cfg.dtype)
+    st = synth.KVStream(cfg, device="cpu", work=torch.float32, tokens=rows)
+    K0, V0 = st.next()
+    K1, V1 = st.next()
+    wk, wv = synth.analytic_predictors(st, 1)
+    f = lambda t: t.double().numpy()
+    C = synth.lloyd_codebook(n_codewords)
+    mk = lambda l, **kw: O.Layer(cfg.kv_heads, cfg.head_dim, C, synth.rht_signs(cfg.kv_heads, cfg.head_dim, l, "k"),
+                                 synth.rht_signs(cfg.kv_heads, cfg.head_dim, l, "v"), cfg.dtype, **kw)
+    e0 = O.encode_layer(mk(0), f(K0), f(V0))
+    lay = mk(1, w_k=f(wk.to(sd)), w_v=f(wv.to(sd)))
+    q = f(synth.random_queries(1, q_heads, cfg.head_dim, seed=1, dtype=cfg.dtype))
+    t0 = time.perf_counter()
+    e1 = O.encode_layer(lay, f(K1), f(V1), e0["Khat"], e0["Vhat"])
+    O.decode_layer(lay, e1["k_codes"], e1["k_scales"], e1["v_codes"], e1["v_scales"], e0["Khat"], e0["Vhat"])
+    O.attn_scores(lay, 1, rows, q, e1["k_codes"], e1["k_scales"], e0["Khat"])
+    dt = time.perf_counter() - t0
+    return {"value": rows / dt, "unit": "tokens/s per layer", "cores": int(threads), "kind": "oracle",
+            "sample": f"encode+decode+scores of one predicted layer on {rows} token rows "
+                      f"({dt:.1f} s of CPU time; cost is linear in rows)"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (--gpus 1); the path shards by tokens with no "
+              "exchange, see DESIGN.md", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2501_19392_amd import binding as B
+    from paper_2501_19392_amd import synth
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    cfg = {"llama3.2-3b": synth.LLAMA32_3B, "llama3.1-8b": synth.LLAMA31_8B, "tiny": synth.TINY}[args.config]
+    q_heads = args.q_heads or {"llama3.2-3b": 24, "llama3.1-8b": 32, "tiny": 8}[args.config]
+    device = "cuda:0"
+    torch.cuda.set_device(0)
+    T = cfg.tokens
+
+    layers, Ks, Vs = build_workload(cfg, device, args.n_codewords)
+    buf = Buffers(layers, T, q_heads, device)
+    q = synth.random_queries(1, q_heads, cfg.head_dim, seed=1, dtype=cfg.dtype, device=device)
+
+    for _ in range(args.warmup):
+        run_step(B, layers, Ks, Vs, buf, q, T, q_heads)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run_step(B, layers, Ks, Vs, buf, q, T, q_heads)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = 1e3 * dt / args.steps
+    value = T * cfg.layers / (dt / args.steps)
+
+    phases = timed_phases(B, layers, Ks, Vs, buf, q, T, q_heads, max(1, min(args.steps, 5)))
+    roofline = None
+    if cfg.dtype == "bf16" and not args.no_kernel_events:
+        flops, ms, launches = gemm_events(B, layers, buf, T, max(1, min(args.steps, 3)))
+        achieved = flops / (ms * 1e-3) / 1e12
+        roofline = {"kernel": "predict_bf16_kernel", "bound": "mfma", "achieved": round(achieved, 2),
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                    "traffic": None, "launches": launches, "avg_launch_us": round(1e3 * ms / launches, 2)}
+
+    line = {
+        "metric": "KV encode+decode tokens/s per layer at %d bits/value" % (args.n_codewords.bit_length() // 2),
+        "value": round(value, 1), "unit": "tokens/s per layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.layers} layers x {T} tokens x {cfg.kv_heads} kv heads x {cfg.head_dim}, "
+                               f"{cfg.dtype}, n={args.n_codewords} codewords (p=2), step = encode + decode + q.k scores "
+                               f"({q_heads} query heads) of every layer",
+                   "tokens": T, "layers": cfg.layers, "q_heads": q_heads},
+        "phases_ms_per_step": {k: round(v, 3) for k, v in phases.items()},
+        "tokens_per_s_per_layer": {k: round(T * cfg.layers / (v * 1e-3), 1) for k, v in phases.items()},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(cfg, args.n_codewords, min(args.cpu_rows, T), q_heads)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -79,11 +79,25 @@ typedef struct aquakv_layer {
   const void* w_v;      /* [D, d_in_v] row-major; input columns: Vhat_prev first,
                            then this layer's Khat (Alg. "encode": [Vhat_prev; Khat]) */
   const float* b_v;     /* [D] fp32 bias or NULL                                  */
+  const void* search_table; /* NULL, or the table aquakv_build_search_table made from
+                           `codebook`: same codes, found without scoring all n points */
 } aquakv_layer;
 
 int aquakv_version(void);
 const char* aquakv_status_string(int status);
 const char* aquakv_last_error(void);
+
+/*
+ * Optional accelerator for the nearest-grid-point step of Sect. 2 (the paper calls the
+ * encoding cost of vector quantization its practical obstacle).  The table partitions the
+ * plane into cells and lists, per cell, every grid point that can be nearest somewhere in
+ * it; quantize then scores only those.  The result is identical to the full search.
+ * `table` is device memory of aquakv_search_table_bytes(n) bytes, written on `stream`;
+ * build it once per grid and put it into aquakv_layer.search_table.
+ */
+size_t aquakv_search_table_bytes(int32_t n_codewords);   /* 0 if n is not supported */
+int aquakv_build_search_table(const float* codebook, int32_t vq_dim, int32_t n_codewords,
+                              void* table, void* stream);
 
 /* Bytes of device workspace the three layer-level calls below need for `tokens`
  * rows (0 on invalid arguments).  It holds fp32 predictions (and a temporary

@@ -29,6 +29,7 @@ AQUAKV_KEY, AQUAKV_VALUE = 0, 1
 
 EXPORTS = [
     "aquakv_version", "aquakv_status_string", "aquakv_last_error", "aquakv_workspace_bytes",
+    "aquakv_search_table_bytes", "aquakv_build_search_table",
     "aquakv_predict", "aquakv_quantize", "aquakv_dequantize",
     "aquakv_encode_layer", "aquakv_decode_layer", "aquakv_decode_attn_scores",
 ]
@@ -41,6 +42,7 @@ class aquakv_layer(ctypes.Structure):
         ("d_in_v", ctypes.c_int32), ("reserved", ctypes.c_int32),
         ("codebook", ctypes.c_void_p), ("signs_k", ctypes.c_void_p), ("signs_v", ctypes.c_void_p),
         ("w_k", ctypes.c_void_p), ("b_k", ctypes.c_void_p), ("w_v", ctypes.c_void_p), ("b_v", ctypes.c_void_p),
+        ("search_table", ctypes.c_void_p),
     ]
 
 
@@ -52,6 +54,10 @@ _lib.aquakv_status_string.argtypes = [ctypes.c_int]
 _lib.aquakv_last_error.restype = ctypes.c_char_p
 _lib.aquakv_workspace_bytes.restype = ctypes.c_size_t
 _lib.aquakv_workspace_bytes.argtypes = [_LP, ctypes.c_int64]
+_lib.aquakv_search_table_bytes.restype = ctypes.c_size_t
+_lib.aquakv_search_table_bytes.argtypes = [ctypes.c_int32]
+_lib.aquakv_build_search_table.restype = ctypes.c_int
+_lib.aquakv_build_search_table.argtypes = [_P, ctypes.c_int32, ctypes.c_int32, _P, _P]
 _lib.aquakv_predict.argtypes = [_LP, ctypes.c_int, ctypes.c_int64, _P, _P, _P, _P]
 _lib.aquakv_quantize.argtypes = [_LP, ctypes.c_int, ctypes.c_int64, _P, _P, _P, _P, _P, _P]
 _lib.aquakv_dequantize.argtypes = [_LP, ctypes.c_int, ctypes.c_int64, _P, _P, _P, _P, _P]
@@ -108,7 +114,7 @@ class Layer:
     def __init__(self, kv_heads: int, head_dim: int, codebook: torch.Tensor, signs_k: torch.Tensor,
                  signs_v: torch.Tensor, dtype: torch.dtype, w_k: Optional[torch.Tensor] = None,
                  w_v: Optional[torch.Tensor] = None, b_k: Optional[torch.Tensor] = None,
-                 b_v: Optional[torch.Tensor] = None):
+                 b_v: Optional[torch.Tensor] = None, search_table: Optional[torch.Tensor] = None):
         self.kv_heads, self.head_dim, self.dtype = kv_heads, head_dim, dtype
         self.d = kv_heads * head_dim
         self.codebook = codebook.to(torch.float32).contiguous()
@@ -119,6 +125,7 @@ class Layer:
         self.b_k = None if b_k is None else b_k.to(torch.float32).contiguous()
         self.b_v = None if b_v is None else b_v.to(torch.float32).contiguous()
         self.n_codewords, self.vq_dim = self.codebook.shape
+        self.search_table = search_table
         if self.w_k is not None and self.w_k.shape[0] != self.d:
             raise ValueError("w_k must be [D, d_in_k]")
         if self.w_v is not None and self.w_v.shape[0] != self.d:
@@ -131,7 +138,8 @@ class Layer:
             w_k=None if self.w_k is None else self.w_k.data_ptr(),
             b_k=None if self.b_k is None else self.b_k.data_ptr(),
             w_v=None if self.w_v is None else self.w_v.data_ptr(),
-            b_v=None if self.b_v is None else self.b_v.data_ptr())
+            b_v=None if self.b_v is None else self.b_v.data_ptr(),
+            search_table=None if search_table is None else search_table.data_ptr())
 
     @property
     def code_bits(self) -> int:
@@ -172,6 +180,22 @@ def aquakv_last_error() -> str:
 
 def aquakv_workspace_bytes(layer, tokens: int) -> int:
     return int(_lib.aquakv_workspace_bytes(_layer_ref(layer), tokens))
+
+
+def aquakv_search_table_bytes(n_codewords: int) -> int:
+    return int(_lib.aquakv_search_table_bytes(n_codewords))
+
+
+def aquakv_build_search_table(codebook, vq_dim: int, n_codewords: int, table, stream=None) -> None:
+    _check(_lib.aquakv_build_search_table(_ptr(codebook), vq_dim, n_codewords, _ptr(table), _stream(stream)))
+
+
+def build_search_table(codebook: torch.Tensor) -> torch.Tensor:
+    """Allocates and fills the search table for a [n, 2] fp32 device codebook."""
+    n, p = codebook.shape
+    table = torch.empty(aquakv_search_table_bytes(n), dtype=torch.uint8, device=codebook.device)
+    aquakv_build_search_table(codebook.to(torch.float32).contiguous(), p, n, table)
+    return table
 
 
 def aquakv_predict(layer, which: int, tokens: int, x0, x1, P, stream=None) -> None:

@@ -43,15 +43,15 @@ int check_layer(const aquakv_layer* L) {
   if (L->dtype != AQUAKV_BF16 && L->dtype != AQUAKV_FP32) return fail(AQUAKV_EINVAL, "dtype=%d", L->dtype);
   if (L->reserved != 0) return fail(AQUAKV_EINVAL, "reserved field must be 0");
   const int D = L->kv_heads * L->head_dim;
-  if (L->d_in_k < 0 || L->d_in_k % 64) return fail(AQUAKV_EINVAL, "d_in_k=%d must be a non-negative multiple of 64", L->d_in_k);
-  if (L->d_in_v < 0 || L->d_in_v % 64) return fail(AQUAKV_EINVAL, "d_in_v=%d must be a non-negative multiple of 64", L->d_in_v);
+  if (L->d_in_k < 0 || L->d_in_k % 128) return fail(AQUAKV_EINVAL, "d_in_k=%d must be a non-negative multiple of 128", L->d_in_k);
+  if (L->d_in_v < 0 || L->d_in_v % 128) return fail(AQUAKV_EINVAL, "d_in_v=%d must be a non-negative multiple of 128", L->d_in_v);
   if (L->d_in_v != 0 && L->d_in_v <= D)
     return fail(AQUAKV_EINVAL, "d_in_v=%d must exceed D=%d (inputs are [Vhat_prev | Khat])", L->d_in_v, D);
   if (L->codebook == nullptr) return fail(AQUAKV_ENULL, "codebook is NULL");
   if (L->signs_k == nullptr || L->signs_v == nullptr) return fail(AQUAKV_ENULL, "signs_k / signs_v is NULL");
   if (L->d_in_k && L->w_k == nullptr) return fail(AQUAKV_ENULL, "w_k is NULL but d_in_k=%d", L->d_in_k);
   if (L->d_in_v && L->w_v == nullptr) return fail(AQUAKV_ENULL, "w_v is NULL but d_in_v=%d", L->d_in_v);
-  const void* ptrs[] = {L->codebook, L->signs_k, L->signs_v, L->w_k, L->b_k, L->w_v, L->b_v};
+  const void* ptrs[] = {L->codebook, L->signs_k, L->signs_v, L->w_k, L->b_k, L->w_v, L->b_v, L->search_table};
   for (const void* p : ptrs)
     if (p != nullptr && misaligned(p)) return fail(AQUAKV_EALIGN, "a pointer in aquakv_layer is not 16-byte aligned");
   return AQUAKV_OK;
@@ -123,6 +123,20 @@ const char* aquakv_status_string(int status) {
 
 const char* aquakv_last_error(void) { return g_err; }
 
+size_t aquakv_search_table_bytes(int32_t n_codewords) {
+  return (n_codewords == 16 || n_codewords == 64 || n_codewords == 256) ? aquakv::kSearchTableBytes : 0;
+}
+
+int aquakv_build_search_table(const float* codebook, int32_t vq_dim, int32_t n_codewords, void* table, void* stream) {
+  if (vq_dim != 2) return fail(vq_dim < 1 ? AQUAKV_EINVAL : AQUAKV_EUNSUPPORTED, "vq_dim=%d: only 2 is built", vq_dim);
+  if (aquakv_search_table_bytes(n_codewords) == 0)
+    return fail(AQUAKV_EINVAL, "n_codewords=%d: must be 16, 64 or 256", n_codewords);
+  CHECK(check_ptr(codebook, "codebook", true));
+  CHECK(check_ptr(table, "table", true));
+  HIP_TRY(aquakv::launch_build_search_table(codebook, n_codewords, table, static_cast<hipStream_t>(stream)));
+  return AQUAKV_OK;
+}
+
 size_t aquakv_workspace_bytes(const aquakv_layer* layer, int64_t tokens) {
   if (check_layer(layer) != AQUAKV_OK || tokens <= 0) return 0;
   const Plan pl = make_plan(layer, tokens);
@@ -160,7 +174,7 @@ int aquakv_quantize(const aquakv_layer* L, int which, int64_t tokens, const void
   CHECK(check_ptr(scales, "scales", true));
   CHECK(check_ptr(Xhat, "Xhat", false));
   HIP_TRY(aquakv::launch_quantize(L->dtype, L->n_codewords, X, P, which == AQUAKV_KEY ? L->signs_k : L->signs_v,
-                                  L->codebook, codes, scales, Xhat, tokens, L->kv_heads,
+                                  L->codebook, L->search_table, codes, scales, Xhat, tokens, L->kv_heads,
                                   static_cast<hipStream_t>(stream)));
   return AQUAKV_OK;
 }
@@ -218,14 +232,14 @@ int aquakv_encode_layer(const aquakv_layer* L, int64_t tokens, const void* K, co
                                      L->w_k, L->b_k, Pbuf, n, D, stream));
     void* khat_dst = Khat != nullptr ? at(Khat, r0, row) : (has_v ? khat_tmp : nullptr);
     HIP_TRY(aquakv::launch_quantize(L->dtype, L->n_codewords, at(K, r0, row), has_k ? Pbuf : nullptr, L->signs_k,
-                                    L->codebook, static_cast<uint8_t*>(at(k_codes, r0, pl.code_row)),
+                                    L->codebook, L->search_table, static_cast<uint8_t*>(at(k_codes, r0, pl.code_row)),
                                     static_cast<uint16_t*>(at(k_scales, r0, srow)), khat_dst, n, H, stream));
     // values: V_pred = f_value([Vhat_prev; Khat]);  V_q = Q(V - V_pred)
     if (has_v)
       HIP_TRY(aquakv::launch_predict(L->dtype, at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb), L->d_in_v - D,
                                      khat_dst, D, L->w_v, L->b_v, Pbuf, n, D, stream));
     HIP_TRY(aquakv::launch_quantize(L->dtype, L->n_codewords, at(V, r0, row), has_v ? Pbuf : nullptr, L->signs_v,
-                                    L->codebook, static_cast<uint8_t*>(at(v_codes, r0, pl.code_row)),
+                                    L->codebook, L->search_table, static_cast<uint8_t*>(at(v_codes, r0, pl.code_row)),
                                     static_cast<uint16_t*>(at(v_scales, r0, srow)), at(Vhat, r0, row), n, H, stream));
   }
   return AQUAKV_OK;

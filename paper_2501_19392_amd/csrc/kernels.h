@@ -13,9 +13,14 @@ hipError_t launch_predict(int dtype, const void* x0, int d0, const void* x1, int
                           const float* bias, float* P, int64_t T, int D, hipStream_t stream);
 
 // Q(X - P): codes, scales and (optionally) the reconstruction.  rows = T, H heads of 128.
+// `table` (nullable): nearest-grid-point search table from launch_build_search_table.
 hipError_t launch_quantize(int dtype, int n_codewords, const void* X, const float* P, const int8_t* signs,
-                           const float* codebook, uint8_t* codes, uint16_t* scales, void* Xhat, int64_t T, int H,
-                           hipStream_t stream);
+                           const float* codebook, const void* table, uint8_t* codes, uint16_t* scales, void* Xhat,
+                           int64_t T, int H, hipStream_t stream);
+
+// 64 x 64 cells x 4 candidate bytes = 16 KiB.
+constexpr size_t kSearchTableBytes = 64 * 64 * 4;
+hipError_t launch_build_search_table(const float* codebook, int n_codewords, void* table, hipStream_t stream);
 
 hipError_t launch_dequantize(int dtype, int n_codewords, const uint8_t* codes, const uint16_t* scales, const float* P,
                              const int8_t* signs, const float* codebook, void* Xhat, int64_t T, int H,

@@ -16,18 +16,23 @@ namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // a 16-byte chunk as a first-class value
 
-constexpr int BM = 128, BN = 128, BK = 64;       // block tile; 4 waves as 2 x 2, wave tile 64 x 64
+constexpr int BM = 256, BN = 128, BK = 64;       // block tile; 4 waves stacked in M, wave tile 64 x 128
 constexpr int kGemmThreads = 256;
 constexpr int kRowBytes = BK * 2;                // 128 B of bf16 per LDS row
-constexpr int kTileBytes = BM * kRowBytes;       // 16 KiB per operand per stage
+constexpr int kATileBytes = BM * kRowBytes;      // 32 KiB
+constexpr int kBTileBytes = BN * kRowBytes;      // 16 KiB
+constexpr int kStageBytes = kATileBytes + kBTileBytes;
+constexpr int kAChunks = BM * 8 / kGemmThreads;  // 16-byte chunks per thread and k-tile (8)
+constexpr int kBChunks = BN * 8 / kGemmThreads;  // (4)
 
 // 16-byte chunk `ch` (0..7) of LDS row `row`, XOR-swizzled so that the 32 lanes
 // of a fragment read (32 consecutive rows, same chunk) spread over all banks.
 __device__ __forceinline__ int lds_off(int row, int ch) { return row * kRowBytes + ((ch ^ (row & 7)) << 4); }
 
 // XCD-aware tile order: consecutive workgroup ids land on different XCDs, so
-// give each XCD a contiguous range of tiles (n fastest): the 8 column tiles of
+// give each XCD a contiguous range of tiles (n fastest): the column tiles of
 // a row tile then share that XCD's L2 copy of the x rows.
 __device__ __forceinline__ int remap_block(int bid, int nblocks) {
   constexpr int kXcd = 8;
@@ -38,12 +43,11 @@ __device__ __forceinline__ int remap_block(int bid, int nblocks) {
 __global__ __launch_bounds__(kGemmThreads) void predict_bf16_kernel(
     const bf16_t* __restrict__ x0, int d0, const bf16_t* __restrict__ x1, int d1, const bf16_t* __restrict__ W,
     const float* __restrict__ bias, float* __restrict__ P, int64_t T, int D) {
-  __shared__ __attribute__((aligned(16))) unsigned char lds[2][2][kTileBytes];   // [stage][A|B]
+  __shared__ __attribute__((aligned(16))) unsigned char lds[2][kStageBytes];   // [stage][A rows | B rows]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
   const int n_tiles = D / BN;
   const int logical = remap_block(blockIdx.x, gridDim.x);
   const int tile_m = logical / n_tiles, tile_n = logical % n_tiles;
@@ -52,81 +56,136 @@ __global__ __launch_bounds__(kGemmThreads) void predict_bf16_kernel(
   const int K = d0 + d1;
   const int nk = K / BK;
 
-  // global -> register staging: 4 chunks of A and 4 of B per thread and k-tile
-  uint4 ra[4], rb[4];
-  auto load_tile = [&](int kt) {
+  // Software pipeline (one block per CU, one wave per SIMD, so the overlap has to be built
+  // into the instruction stream).  For k-tile t, living in LDS stage t&1:
+  //   barrier B_t                       -- tile t is completely in LDS, stage (t+1)&1 is free
+  //   fragment reads (t, step 0)
+  //   8 MFMAs of (t-1, step 3)          + the 12 LDS writes of tile t+1 into stage (t+1)&1
+  //   8 MFMAs of (t, step 0)            + fragment reads (t, 1) + the 12 global loads of tile t+3
+  //   8 MFMAs of (t, step 1)            + fragment reads (t, 2)
+  //   8 MFMAs of (t, step 2)            + fragment reads (t, 3)
+  // Every memory instruction is issued in the shadow of an MFMA, the matrix pipe runs across
+  // the barrier, and a global load has two iterations to land (two register sets).
+  // sched_barrier(0) after each MFMA keeps the compiler from regrouping the stream.
+  struct Regs { u32x4 v[kAChunks + kBChunks]; };
+  struct Frag { bf16x8 v[6]; };      // a[0], a[1], b[0..3]
+
+  auto load_piece = [&](int kt, Regs& r, int pc) {         // piece pc of tile kt: global -> registers
     const int k0 = kt * BK;
-    const bf16_t* xa;
-    int ld, kk;
-    if (k0 < d0) { xa = x0; ld = d0; kk = k0; } else { xa = x1; ld = d1; kk = k0 - d0; }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int id = tid + i * kGemmThreads;
-      const int row = id >> 3, ch = id & 7;
+    const int id = tid + (pc < kAChunks ? pc : pc - kAChunks) * kGemmThreads;
+    const int row = id >> 3, ch = id & 7;
+    if (pc < kAChunks) {
+      const bf16_t* xa;
+      int ld, kk;
+      if (k0 < d0) { xa = x0; ld = d0; kk = k0; } else { xa = x1; ld = d1; kk = k0 - d0; }
       int64_t gr = m0 + row;
       gr = gr < T ? gr : T - 1;
-      ra[i] = *reinterpret_cast<const uint4*>(xa + gr * ld + kk + ch * 8);
-      rb[i] = *reinterpret_cast<const uint4*>(W + (int64_t)(n0 + row) * K + k0 + ch * 8);
+      r.v[pc] = *reinterpret_cast<const u32x4*>(xa + gr * ld + kk + ch * 8);
+    } else {
+      r.v[pc] = *reinterpret_cast<const u32x4*>(W + (int64_t)(n0 + row) * K + k0 + ch * 8);
     }
   };
-  auto store_tile = [&](int stage) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int id = tid + i * kGemmThreads;
-      const int row = id >> 3, ch = id & 7;
-      *reinterpret_cast<uint4*>(&lds[stage][0][lds_off(row, ch)]) = ra[i];
-      *reinterpret_cast<uint4*>(&lds[stage][1][lds_off(row, ch)]) = rb[i];
-    }
+  auto store_piece = [&](int stage, const Regs& r, int pc) {   // registers -> LDS
+    const int id = tid + (pc < kAChunks ? pc : pc - kAChunks) * kGemmThreads;
+    const int base = pc < kAChunks ? 0 : kATileBytes;
+    *reinterpret_cast<u32x4*>(&lds[stage][base + lds_off(id >> 3, id & 7)]) = r.v[pc];
+  };
+  const int frow = lane & 31;       // row (A) / column (B) inside a 32-wide fragment
+  const int fk = lane >> 5;         // which half of the 16 k values
+  auto frag_piece = [&](int stage, int ks, Frag& f, int pc) {  // LDS -> MFMA operand registers
+    const int off = pc < 2 ? lds_off(wave * 64 + pc * 32 + frow, ks * 2 + fk)
+                           : kATileBytes + lds_off((pc - 2) * 32 + frow, ks * 2 + fk);
+    f.v[pc] = *reinterpret_cast<const bf16x8*>(&lds[stage][off]);
   };
 
-  f32x16 acc[2][2];
+  f32x16 acc[2][4];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  load_tile(0);
-  store_tile(0);
-  __syncthreads();
-
-  const int frow = lane & 31;       // row (A) / column (B) inside a 32-wide fragment
-  const int fk = lane >> 5;         // which half of the 16 k values
-  for (int kt = 0; kt < nk; ++kt) {
-    const int stage = kt & 1;
-    if (kt + 1 < nk) load_tile(kt + 1);
+  // 8 MFMAs on fragment f; extra(m) is issued right after MFMA m
+  auto mma8 = [&](const Frag& f, auto&& extra) {
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 a[2], b[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int row = wm * 64 + i * 32 + frow;
-        a[i] = *reinterpret_cast<const bf16x8*>(&lds[stage][0][lds_off(row, ks * 2 + fk)]);
-        const int col = wn * 64 + i * 32 + frow;
-        b[i] = *reinterpret_cast<const bf16x8*>(&lds[stage][1][lds_off(col, ks * 2 + fk)]);
-      }
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    for (int m = 0; m < 8; ++m) {
+      const int i = m >> 2, j = m & 3;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.v[i], f.v[2 + j], acc[i][j], 0, 0, 0);
+      extra(m);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    if (kt + 1 < nk) store_tile(stage ^ 1);
-    __syncthreads();
+  };
+
+  Regs rs[2];
+  Frag f0, f1, carry;
+  constexpr int kPieces = kAChunks + kBChunks;   // 12
+#pragma unroll
+  for (int pc = 0; pc < kPieces; ++pc) load_piece(0, rs[0], pc);
+#pragma unroll
+  for (int pc = 0; pc < kPieces; ++pc) store_piece(0, rs[0], pc);
+#pragma unroll
+  for (int pc = 0; pc < kPieces; ++pc) load_piece(1, rs[1], pc);        // nk >= 2
+#pragma unroll
+  for (int pc = 0; pc < kPieces; ++pc)
+    if (nk > 2) load_piece(2, rs[0], pc);
+  __syncthreads();                                                      // B_0
+
+  // iteration t; `first`: no (t-1, 3) to finish; write/load flags for the drain
+  auto iteration = [&](int t, Regs& rw, bool first, bool do_store, bool do_load) {
+    const int stage = t & 1;
+#pragma unroll
+    for (int pc = 0; pc < 6; ++pc) frag_piece(stage, 0, f0, pc);
+    __builtin_amdgcn_sched_barrier(0);
+    if (!first) {
+      mma8(carry, [&](int m) {
+        if (do_store) {
+          if (m < 4) { store_piece(stage ^ 1, rw, 2 * m); store_piece(stage ^ 1, rw, 2 * m + 1); }
+          else store_piece(stage ^ 1, rw, 4 + m);
+        }
+      });
+    } else if (do_store) {
+#pragma unroll
+      for (int pc = 0; pc < kPieces; ++pc) store_piece(stage ^ 1, rw, pc);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    mma8(f0, [&](int m) {
+      if (m < 6) frag_piece(stage, 1, f1, m);
+      if (do_load) {
+        if (m < 4) { load_piece(t + 3, rw, 2 * m); load_piece(t + 3, rw, 2 * m + 1); }
+        else load_piece(t + 3, rw, 4 + m);
+      }
+    });
+    mma8(f1, [&](int m) { if (m < 6) frag_piece(stage, 2, f0, m); });
+    mma8(f0, [&](int m) { if (m < 6) frag_piece(stage, 3, carry, m); });
+    __syncthreads();                                                    // B_{t+1}
+  };
+
+  // nk is even and >= 2 (K is a multiple of 128)
+  iteration(0, rs[1], true, true, nk > 3);
+  int t = 1;
+  for (; t + 3 < nk; t += 2) {                       // steady state, unrolled x2 over the register sets
+    iteration(t, rs[0], false, true, true);
+    iteration(t + 1, rs[1], false, true, true);
   }
+  if (nk >= 4) {                                     // drain: t = nk-3 (odd), nk-2; nothing left to load
+    iteration(nk - 3, rs[0], false, true, false);
+    iteration(nk - 2, rs[1], false, true, false);
+  }
+  iteration(nk - 1, rs[0], false, false, false);
+  mma8(carry, [&](int) {});                          // (nk-1, step 3)
 
   // accumulator layout of the 32x32 tile: lane holds column lane%32 and rows
   // 8*blk + 4*(lane/32) + j for register 4*blk + j.
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int col = n0 + wn * 64 + j * 32 + frow;
+    for (int j = 0; j < 4; ++j) {
+      const int col = n0 + j * 32 + frow;
       const float bv = bias != nullptr ? bias[col] : 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int64_t row = m0 + wm * 64 + i * 32 + (r >> 2) * 8 + fk * 4 + (r & 3);
+        const int64_t row = m0 + wave * 64 + i * 32 + (r >> 2) * 8 + fk * 4 + (r & 3);
         if (row < T) P[row * D + col] = acc[i][j][r] + bv;
       }
     }

@@ -30,7 +30,8 @@ def test_library_exports_every_declared_symbol():
 
 def layer(**kw):
     d = dict(kv_heads=8, head_dim=128, vq_dim=2, n_codewords=16, dtype=B.AQUAKV_BF16, d_in_k=1024, d_in_v=2048,
-             reserved=0, codebook=FAKE, signs_k=FAKE, signs_v=FAKE, w_k=FAKE, b_k=None, w_v=FAKE, b_v=None)
+             reserved=0, codebook=FAKE, signs_k=FAKE, signs_v=FAKE, w_k=FAKE, b_k=None, w_v=FAKE, b_v=None,
+             search_table=None)
     d.update(kw)
     return B.aquakv_layer(**d)
 
@@ -96,6 +97,11 @@ def test_bad_call_arguments_are_rejected_without_launching():
     assert status_of(B.aquakv_predict, L, 5, 8, FAKE, FAKE, FAKE) == B.AQUAKV_EINVAL
     assert status_of(B.aquakv_quantize, L, B.AQUAKV_KEY, 8, FAKE, None, None, FAKE, None) == B.AQUAKV_ENULL
     assert status_of(B.aquakv_dequantize, L, B.AQUAKV_KEY, 8, FAKE, FAKE, None, None) == B.AQUAKV_ENULL
+    # search table
+    assert B.aquakv_search_table_bytes(16) == 16384 and B.aquakv_search_table_bytes(17) == 0
+    assert status_of(B.aquakv_build_search_table, FAKE, 2, 16, None) == B.AQUAKV_ENULL
+    assert status_of(B.aquakv_build_search_table, FAKE, 2, 48, FAKE) == B.AQUAKV_EINVAL
+    assert status_of(B.aquakv_build_search_table, FAKE, 3, 16, FAKE) == B.AQUAKV_EUNSUPPORTED
     # scores
     sc = [FAKE, FAKE, FAKE, FAKE, 1.0, FAKE, None]
     assert status_of(B.aquakv_decode_attn_scores, L, 2, 16, 12, *sc, (FAKE, 1 << 30)) == B.AQUAKV_EINVAL   # 12 % 8

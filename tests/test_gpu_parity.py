@@ -62,10 +62,10 @@ def test_predict_matches_oracle_and_is_row_count_invariant(B, dtype, T, H):
 # ------------------------------------------------------------------ quantizer stages
 @pytest.mark.parametrize("dtype,n,T,H", [("fp32", 16, 256, 2), ("bf16", 16, 300, 8), ("bf16", 64, 257, 8),
                                         ("fp32", 64, 33, 2), ("bf16", 256, 65, 4), ("fp32", 16, 1, 1)])
-@pytest.mark.parametrize("with_p", [False, True])
-def test_quantize_codes_scales_and_reconstruction(B, dtype, n, T, H, with_p):
-    print(f"case quantize dtype={dtype} n={n} T={T} H={H} with_p={with_p}", flush=True)
-    lo, lg = U.make_layers(H, dtype, n)
+@pytest.mark.parametrize("with_p,table", [(False, True), (True, True), (True, False)])
+def test_quantize_codes_scales_and_reconstruction(B, dtype, n, T, H, with_p, table):
+    print(f"case quantize dtype={dtype} n={n} T={T} H={H} with_p={with_p} table={table}", flush=True)
+    lo, lg = U.make_layers(H, dtype, n, table=table)
     D = H * 128
     ch = synth.channel_scales(D, 0, 0).float()
     X = (storage_randn((T, D), "fp32", 10, device="cpu") * ch).to(synth.torch_dtype(dtype)).cuda().reshape(T, H, 128)
@@ -111,6 +111,42 @@ def test_dequantize_random_codes(B, dtype, n):
     sync()
     want = O.round_storage(O.dequantize(idx, s16, lo.signs_v, lo.codebook) + U.np64(P), dtype)
     U.assert_close_storage(Xhat, want, dtype, "dequantize")
+
+
+@pytest.mark.parametrize("n", [16, 64, 256])
+def test_search_table_gives_the_codes_of_the_full_search(B, n):
+    """Same kernel with and without the table, on inputs that also reach the border cells."""
+    print(f"case table vs full search n={n}", flush=True)
+    T, H = 2048, 8
+    _, lg_t = U.make_layers(H, "fp32", n, table=True)
+    _, lg_f = U.make_layers(H, "fp32", n, table=False)
+    g = torch.Generator().manual_seed(31)
+    X = torch.randn(T, H, 128, generator=g)
+    X[: T // 2] *= torch.exp(2.5 * torch.randn(T // 2, H, 128, generator=g))     # heavy tails -> |y| up to ~11
+    X[T // 2: T // 2 + 64, :, 1:] = 0                                             # a single spike per group
+    X = X.cuda()
+    outs = []
+    for lg in (lg_t, lg_f):
+        codes, scales = lg.alloc_codes(T)
+        B.aquakv_quantize(lg, B.AQUAKV_KEY, T, X, None, codes, scales, None)
+        sync()
+        outs.append((codes, scales))
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+    # a crowded grid (many points inside one cell) must take the full-search fallback and still agree
+    C = torch.from_numpy(synth.lloyd_codebook(n)).clone()
+    C[: n // 2] = C[: n // 2] * 0.01
+    Cd = C.cuda()
+    from paper_2501_19392_amd import binding
+    tab = binding.build_search_table(Cd)
+    assert int((tab.view(torch.int32) == -1).sum()) > 0
+    res = []
+    for t in (tab, None):
+        lg = binding.Layer(H, 128, Cd, lg_t.signs_k, lg_t.signs_v, torch.float32, search_table=t)
+        codes, scales = lg.alloc_codes(T)
+        B.aquakv_quantize(lg, B.AQUAKV_KEY, T, X, None, codes, scales, None)
+        sync()
+        res.append(codes)
+    assert torch.equal(res[0], res[1])
 
 
 def test_quantize_edge_cases(B):
