@@ -7,7 +7,7 @@ value): for every layer `aquakv_encode_layer`, then for every layer
 `aquakv_decode_layer`, then for every layer `aquakv_decode_attn_scores` (24 query
 heads).  Inputs are resident in HBM before the timed region.  The printed JSON line
 reports tokens/s per layer (tokens * layers / step time), the roofline position of
-the dominant kernel (the bf16 MFMA predictor GEMM) from HIP events, and the CPU
+the dominant kernel (the fused bf16 MFMA predictor + quantizer kernel) from HIP events, and the CPU
 oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="skip the instrumented replay")
     ap.add_argument("--cpu-rows", type=int, default=8192, help="token rows of the oracle sample")
+    ap.add_argument("--cpu-layers", type=int, default=4, help="predicted layers of the oracle sample")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 256 MiB device copy (a known-size dispatch to scale rocprofv3 --pmc byte counters)")
     return ap.parse_args()
 
 
@@ -125,42 +128,42 @@ def timed_phases(B, layers, Ks, Vs, buf, q, T, q_heads, reps):
     return out
 
 
-def gemm_events(B, layers, buf, T, steps):
-    """Replay of the predictor GEMM launches of `steps` steps through the stage entry point
-    (the same kernel, shapes and order the layer-level calls launch), each bracketed by
-    events on the launch stream.  Returns (total flops, total ms, launches)."""
+def encode_kernel_events(B, layers, Ks, Vs, buf, T, steps):
+    """HIP events (on the launch stream) around every `aquakv_encode_layer` call of `steps` passes over
+    the predicted layers.  For a bf16 layer with predictors one call is exactly two launches of the
+    dominant kernel, fused_kernel<encode> (keys: K = d_in_k, then values: K = d_in_v).
+    Returns (predictor flops, algorithmic HBM bytes, total ms, launches)."""
     import torch
     D = layers[0].d
     pairs = []
     flops = 0.0
+    nbytes = 0.0
+    eb = 2
     for _ in range(steps):
+        prev = (None, None)
         for l, lay in enumerate(layers):
-            if l == 0:
-                continue
+            (kc, ks), (vc, vs) = buf.codes[l]
             Kh, Vh = buf.hat[l & 1]
-            Kp, Vp = buf.hat[(l - 1) & 1]
-            # encode: key + value GEMM; decode: key + value GEMM; scores: key GEMM
-            for which, reps in ((B.AQUAKV_KEY, 3), (B.AQUAKV_VALUE, 2)):
-                for _r in range(reps):
-                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    a.record()
-                    if which == B.AQUAKV_KEY:
-                        B.aquakv_predict(lay, which, T, Kp, None, buf.P)
-                        flops += 2.0 * T * D * lay.c.d_in_k
-                    else:
-                        B.aquakv_predict(lay, which, T, Vp, Kh, buf.P)
-                        flops += 2.0 * T * D * lay.c.d_in_v
-                    b.record()
-                    pairs.append((a, b))
+            if l > 0:
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+            B.aquakv_encode_layer(lay, T, Ks[l], Vs[l], prev[0], prev[1], kc, ks, vc, vs, Kh, Vh, buf.ws)
+            if l > 0:
+                b.record()
+                pairs.append((a, b))
+                flops += 2.0 * T * D * (lay.c.d_in_k + lay.c.d_in_v)
+                code_bytes = lay.kv_heads * (lay.code_bytes_per_group + 2)
+                # per token: read K, V, Khat_prev, Vhat_prev and (value predictor) Khat; write Khat, Vhat, codes+scales
+                nbytes += T * (5 * D * eb + 2 * D * eb + 2 * code_bytes) + (lay.c.d_in_k + lay.c.d_in_v) * D * eb
+            prev = (Kh, Vh)
     torch.cuda.synchronize()
     ms = sum(a.elapsed_time(b) for a, b in pairs)
-    return flops, ms, len(pairs)
+    return flops, nbytes, ms, 2 * len(pairs)
 
 
-def cpu_baseline(cfg, n_codewords, rows, q_heads):
-    """The oracle as it stands, on the host: encode + decode + scores of one predicted layer
+def cpu_baseline(cfg, n_codewords, rows, q_heads, n_layers):
+    """The oracle as it stands, on the host: encode + decode + scores of `n_layers` predicted layers
     on `rows` token rows of the same synthetic workload (rows are independent)."""
-    import numpy as np
     import torch
     from oracle import aquakv_oracle as O
     from paper_2501_19392_amd import synth
@@ -171,24 +174,28 @@ def cpu_baseline(cfg, n_codewords, rows, q_heads):
         threads = os.cpu_count() or 1
     sd = synth.torch_dtype(cfg.dtype)
     st = synth.KVStream(cfg, device="cpu", work=torch.float32, tokens=rows)
-    K0, V0 = st.next()
-    K1, V1 = st.next()
-    wk, wv = synth.analytic_predictors(st, 1)
     f = lambda t: t.double().numpy()
     C = synth.lloyd_codebook(n_codewords)
     mk = lambda l, **kw: O.Layer(cfg.kv_heads, cfg.head_dim, C, synth.rht_signs(cfg.kv_heads, cfg.head_dim, l, "k"),
                                  synth.rht_signs(cfg.kv_heads, cfg.head_dim, l, "v"), cfg.dtype, **kw)
-    e0 = O.encode_layer(mk(0), f(K0), f(V0))
-    lay = mk(1, w_k=f(wk.to(sd)), w_v=f(wv.to(sd)))
+    K0, V0 = st.next()
+    prev = O.encode_layer(mk(0), f(K0), f(V0))
     q = f(synth.random_queries(1, q_heads, cfg.head_dim, seed=1, dtype=cfg.dtype))
-    t0 = time.perf_counter()
-    e1 = O.encode_layer(lay, f(K1), f(V1), e0["Khat"], e0["Vhat"])
-    O.decode_layer(lay, e1["k_codes"], e1["k_scales"], e1["v_codes"], e1["v_scales"], e0["Khat"], e0["Vhat"])
-    O.attn_scores(lay, 1, rows, q, e1["k_codes"], e1["k_scales"], e0["Khat"])
-    dt = time.perf_counter() - t0
-    return {"value": rows / dt, "unit": "tokens/s per layer", "cores": int(threads), "kind": "oracle",
-            "sample": f"encode+decode+scores of one predicted layer on {rows} token rows "
-                      f"({dt:.1f} s of CPU time; cost is linear in rows)"}
+    dt = 0.0
+    for l in range(1, n_layers + 1):
+        K1, V1 = st.next()
+        wk, wv = synth.analytic_predictors(st, l)
+        lay = mk(l, w_k=f(wk.to(sd)), w_v=f(wv.to(sd)))
+        K1, V1 = f(K1), f(V1)
+        t0 = time.perf_counter()
+        e1 = O.encode_layer(lay, K1, V1, prev["Khat"], prev["Vhat"])
+        O.decode_layer(lay, e1["k_codes"], e1["k_scales"], e1["v_codes"], e1["v_scales"], prev["Khat"], prev["Vhat"])
+        O.attn_scores(lay, 1, rows, q, e1["k_codes"], e1["k_scales"], prev["Khat"])
+        dt += time.perf_counter() - t0
+        prev = e1
+    return {"value": rows * n_layers / dt, "unit": "tokens/s per layer", "cores": int(threads), "kind": "oracle",
+            "sample": f"encode+decode+scores of {n_layers} predicted layers on {rows} token rows "
+                      f"({dt:.1f} s of CPU time; cost is linear in rows and layers)"}
 
 
 def main():
@@ -213,6 +220,13 @@ def main():
     buf = Buffers(layers, T, q_heads, device)
     q = synth.random_queries(1, q_heads, cfg.head_dim, seed=1, dtype=cfg.dtype, device=device)
 
+    if args.calibrate_copy:
+        src = torch.zeros(64 << 20, dtype=torch.float32, device=device)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         run_step(B, layers, Ks, Vs, buf, q, T, q_heads)
     torch.cuda.synchronize()
@@ -227,11 +241,14 @@ def main():
     phases = timed_phases(B, layers, Ks, Vs, buf, q, T, q_heads, max(1, min(args.steps, 5)))
     roofline = None
     if cfg.dtype == "bf16" and not args.no_kernel_events:
-        flops, ms, launches = gemm_events(B, layers, buf, T, max(1, min(args.steps, 3)))
+        flops, nbytes, ms, launches = encode_kernel_events(B, layers, Ks, Vs, buf, T, max(1, min(args.steps, 3)))
         achieved = flops / (ms * 1e-3) / 1e12
-        roofline = {"kernel": "predict_bf16_kernel", "bound": "mfma", "achieved": round(achieved, 2),
-                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                    "traffic": None, "launches": launches, "avg_launch_us": round(1e3 * ms / launches, 2)}
+        roofline = {"kernel": "fused_kernel<encode> (bf16 MFMA predictor + quantizer epilogue)", "bound": "mfma",
+                    "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None, "launches": launches,
+                    "avg_launch_us": round(1e3 * ms / launches, 2),
+                    "algorithmic_hbm_GBs": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                    "algorithmic_hbm_frac": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
 
     line = {
         "metric": "KV encode+decode tokens/s per layer at %d bits/value" % (args.n_codewords.bit_length() // 2),
@@ -247,7 +264,7 @@ def main():
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(cfg, args.n_codewords, min(args.cpu_rows, T), q_heads)
+        line["cpu_baseline"] = cpu_baseline(cfg, args.n_codewords, min(args.cpu_rows, T), q_heads, min(args.cpu_layers, cfg.layers - 1))
     print(json.dumps(line))
 
 

@@ -20,10 +20,12 @@ int fail(int status, const char* fmt, ...) {
   return status;
 }
 
-// Rows handled per pass of the layer-level calls: the fp32 predictions of one
-// chunk (chunk * D * 4 bytes) stay close to the caches between the GEMM that
-// writes them and the streaming kernel that consumes them.
-constexpr int64_t kChunkRows = 16384;
+// Rows handled per pass of the layer-level calls.  bf16 layers run the fused kernels, which
+// need no prediction buffer (the chunk only bounds the temporary Khat).  fp32 layers run
+// predictor and quantizer as separate kernels: the fp32 predictions of one chunk
+// (chunk * D * 4 bytes) then stay close to the caches between the two.
+constexpr int64_t kChunkRowsFused = 65536;
+constexpr int64_t kChunkRowsSplit = 16384;
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 inline size_t elem_bytes(int dtype) { return dtype == AQUAKV_BF16 ? 2 : 4; }
@@ -80,6 +82,7 @@ struct Plan {
   size_t eb;          // bytes per element of the storage dtype
   size_t code_row;    // bytes of codes per token row
   int64_t chunk;      // rows per pass
+  bool fused;         // bf16: predictor fused with the quantizer kernels
   size_t p_bytes;     // fp32 predictions of one chunk
   size_t khat_bytes;  // temporary Khat of one chunk
 };
@@ -89,8 +92,10 @@ Plan make_plan(const aquakv_layer* L, int64_t tokens) {
   pl.D = L->kv_heads * L->head_dim;
   pl.eb = elem_bytes(L->dtype);
   pl.code_row = (size_t)L->kv_heads * (L->head_dim / 2) * code_bits(L->n_codewords) / 8;
-  pl.chunk = tokens < kChunkRows ? tokens : kChunkRows;
-  pl.p_bytes = (size_t)pl.chunk * pl.D * sizeof(float);
+  pl.fused = L->dtype == AQUAKV_BF16;
+  const int64_t cap = pl.fused ? kChunkRowsFused : kChunkRowsSplit;
+  pl.chunk = tokens < cap ? tokens : cap;
+  pl.p_bytes = pl.fused ? 0 : (size_t)pl.chunk * pl.D * sizeof(float);
   pl.khat_bytes = (size_t)pl.chunk * pl.D * pl.eb;
   return pl;
 }
@@ -227,20 +232,36 @@ int aquakv_encode_layer(const aquakv_layer* L, int64_t tokens, const void* K, co
   for (int64_t r0 = 0; r0 < tokens; r0 += pl.chunk) {
     const int64_t n = tokens - r0 < pl.chunk ? tokens - r0 : pl.chunk;
     // keys:  K_pred = f_key(Khat_prev);  K_q = Q(K - K_pred);  Khat = Q^-1(K_q) + K_pred
-    if (has_k)
-      HIP_TRY(aquakv::launch_predict(L->dtype, at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k, nullptr, 0,
-                                     L->w_k, L->b_k, Pbuf, n, D, stream));
     void* khat_dst = Khat != nullptr ? at(Khat, r0, row) : (has_v ? khat_tmp : nullptr);
-    HIP_TRY(aquakv::launch_quantize(L->dtype, L->n_codewords, at(K, r0, row), has_k ? Pbuf : nullptr, L->signs_k,
-                                    L->codebook, L->search_table, static_cast<uint8_t*>(at(k_codes, r0, pl.code_row)),
-                                    static_cast<uint16_t*>(at(k_scales, r0, srow)), khat_dst, n, H, stream));
+    if (has_k && pl.fused) {
+      HIP_TRY(aquakv::launch_fused_encode(L->n_codewords, at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k,
+                                          nullptr, 0, L->w_k, L->b_k, L->signs_k, L->codebook, L->search_table,
+                                          at(K, r0, row), static_cast<uint8_t*>(at(k_codes, r0, pl.code_row)),
+                                          static_cast<uint16_t*>(at(k_scales, r0, srow)), khat_dst, n, D, stream));
+    } else {
+      if (has_k)
+        HIP_TRY(aquakv::launch_predict(L->dtype, at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k, nullptr, 0,
+                                       L->w_k, L->b_k, Pbuf, n, D, stream));
+      HIP_TRY(aquakv::launch_quantize(L->dtype, L->n_codewords, at(K, r0, row), has_k ? Pbuf : nullptr, L->signs_k,
+                                      L->codebook, L->search_table, static_cast<uint8_t*>(at(k_codes, r0, pl.code_row)),
+                                      static_cast<uint16_t*>(at(k_scales, r0, srow)), khat_dst, n, H, stream));
+    }
     // values: V_pred = f_value([Vhat_prev; Khat]);  V_q = Q(V - V_pred)
-    if (has_v)
-      HIP_TRY(aquakv::launch_predict(L->dtype, at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb), L->d_in_v - D,
-                                     khat_dst, D, L->w_v, L->b_v, Pbuf, n, D, stream));
-    HIP_TRY(aquakv::launch_quantize(L->dtype, L->n_codewords, at(V, r0, row), has_v ? Pbuf : nullptr, L->signs_v,
-                                    L->codebook, L->search_table, static_cast<uint8_t*>(at(v_codes, r0, pl.code_row)),
-                                    static_cast<uint16_t*>(at(v_scales, r0, srow)), at(Vhat, r0, row), n, H, stream));
+    if (has_v && pl.fused) {
+      HIP_TRY(aquakv::launch_fused_encode(L->n_codewords, at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb),
+                                          L->d_in_v - D, khat_dst, D, L->w_v, L->b_v, L->signs_v, L->codebook,
+                                          L->search_table, at(V, r0, row),
+                                          static_cast<uint8_t*>(at(v_codes, r0, pl.code_row)),
+                                          static_cast<uint16_t*>(at(v_scales, r0, srow)), at(Vhat, r0, row), n, D,
+                                          stream));
+    } else {
+      if (has_v)
+        HIP_TRY(aquakv::launch_predict(L->dtype, at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb), L->d_in_v - D,
+                                       khat_dst, D, L->w_v, L->b_v, Pbuf, n, D, stream));
+      HIP_TRY(aquakv::launch_quantize(L->dtype, L->n_codewords, at(V, r0, row), has_v ? Pbuf : nullptr, L->signs_v,
+                                      L->codebook, L->search_table, static_cast<uint8_t*>(at(v_codes, r0, pl.code_row)),
+                                      static_cast<uint16_t*>(at(v_scales, r0, srow)), at(Vhat, r0, row), n, H, stream));
+    }
   }
   return AQUAKV_OK;
 }
@@ -275,20 +296,38 @@ int aquakv_decode_layer(const aquakv_layer* L, int64_t tokens, const uint8_t* k_
   for (int64_t r0 = 0; r0 < tokens; r0 += pl.chunk) {
     const int64_t n = tokens - r0 < pl.chunk ? tokens - r0 : pl.chunk;
     // Khat = Q^-1(K_q) + f_key(Khat_prev)
-    if (has_k)
-      HIP_TRY(aquakv::launch_predict(L->dtype, at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k, nullptr, 0,
-                                     L->w_k, L->b_k, Pbuf, n, D, stream));
-    HIP_TRY(aquakv::launch_dequantize(L->dtype, L->n_codewords, static_cast<const uint8_t*>(at(k_codes, r0, pl.code_row)),
-                                      static_cast<const uint16_t*>(at(k_scales, r0, srow)), has_k ? Pbuf : nullptr,
-                                      L->signs_k, L->codebook, at(Khat, r0, row), n, H, stream));
+    if (has_k && pl.fused) {
+      HIP_TRY(aquakv::launch_fused_decode(L->n_codewords, at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k,
+                                          nullptr, 0, L->w_k, L->b_k, L->signs_k, L->codebook,
+                                          static_cast<const uint8_t*>(at(k_codes, r0, pl.code_row)),
+                                          static_cast<const uint16_t*>(at(k_scales, r0, srow)), at(Khat, r0, row), n, D,
+                                          stream));
+    } else {
+      if (has_k)
+        HIP_TRY(aquakv::launch_predict(L->dtype, at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k, nullptr, 0,
+                                       L->w_k, L->b_k, Pbuf, n, D, stream));
+      HIP_TRY(aquakv::launch_dequantize(L->dtype, L->n_codewords,
+                                        static_cast<const uint8_t*>(at(k_codes, r0, pl.code_row)),
+                                        static_cast<const uint16_t*>(at(k_scales, r0, srow)), has_k ? Pbuf : nullptr,
+                                        L->signs_k, L->codebook, at(Khat, r0, row), n, H, stream));
+    }
     if (!want_v) continue;
     // Vhat = Q^-1(V_q) + f_value([Vhat_prev; Khat])
-    if (has_v)
-      HIP_TRY(aquakv::launch_predict(L->dtype, at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb), L->d_in_v - D,
-                                     at(Khat, r0, row), D, L->w_v, L->b_v, Pbuf, n, D, stream));
-    HIP_TRY(aquakv::launch_dequantize(L->dtype, L->n_codewords, static_cast<const uint8_t*>(at(v_codes, r0, pl.code_row)),
-                                      static_cast<const uint16_t*>(at(v_scales, r0, srow)), has_v ? Pbuf : nullptr,
-                                      L->signs_v, L->codebook, at(Vhat, r0, row), n, H, stream));
+    if (has_v && pl.fused) {
+      HIP_TRY(aquakv::launch_fused_decode(L->n_codewords, at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb),
+                                          L->d_in_v - D, at(Khat, r0, row), D, L->w_v, L->b_v, L->signs_v, L->codebook,
+                                          static_cast<const uint8_t*>(at(v_codes, r0, pl.code_row)),
+                                          static_cast<const uint16_t*>(at(v_scales, r0, srow)), at(Vhat, r0, row), n, D,
+                                          stream));
+    } else {
+      if (has_v)
+        HIP_TRY(aquakv::launch_predict(L->dtype, at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb), L->d_in_v - D,
+                                       at(Khat, r0, row), D, L->w_v, L->b_v, Pbuf, n, D, stream));
+      HIP_TRY(aquakv::launch_dequantize(L->dtype, L->n_codewords,
+                                        static_cast<const uint8_t*>(at(v_codes, r0, pl.code_row)),
+                                        static_cast<const uint16_t*>(at(v_scales, r0, srow)), has_v ? Pbuf : nullptr,
+                                        L->signs_v, L->codebook, at(Vhat, r0, row), n, H, stream));
+    }
   }
   return AQUAKV_OK;
 }
@@ -311,6 +350,13 @@ int aquakv_decode_attn_scores(const aquakv_layer* L, int32_t batch, int32_t seq_
   const int64_t tokens = (int64_t)batch * seq_len;
   if (tokens == 0) return AQUAKV_OK;
   const Plan pl = make_plan(L, tokens);
+  if (has_k && pl.fused) {
+    // one fused launch over all rows: prediction, inverse quantizer and dot products
+    HIP_TRY(aquakv::launch_fused_scores(L->n_codewords, Khat_prev, L->d_in_k, L->w_k, L->b_k, L->signs_k, L->codebook,
+                                        k_codes, k_scales, q, score_scale, scores, Khat_out, seq_len, q_heads, tokens,
+                                        pl.D, static_cast<hipStream_t>(stream_)));
+    return AQUAKV_OK;
+  }
   if (has_k) {
     CHECK(check_ptr(workspace, "workspace", true));
     if (workspace_bytes < pl.p_bytes)

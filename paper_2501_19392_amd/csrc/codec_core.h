@@ -1,0 +1,274 @@
+// Building blocks of the backbone quantizer (Sect. 2 "Vector Quantization" of the AQUA-KV
+// paper) for one rotation group held by a quad of lanes x 32 values: nearest-grid-point
+// search (full, or through the cell table), code packing, and the quantize / dequantize
+// bodies shared by the streaming kernels and by the epilogues of the fused predictor kernels.
+//
+// Nearest grid point.  The definition is a search over all n grid points.  The kernels reach
+// the same answer with a 64 x 64 table of square cells over [-4, 4]^2 (border cells are
+// unbounded outwards): each cell lists, in ascending order, every grid point that can be
+// nearest to some point of the (slightly enlarged) cell -- at most 4 (3 for n = 16), else the
+// cell is marked and the lane falls back to the full search.  Only the listed points are
+// scored, with the same fp32 expression and the same lowest-index tie rule as the full
+// search, so both give identical codes.
+#pragma once
+#include "device_utils.h"
+
+namespace aquakv {
+
+constexpr int kCells = 64;                   // table is kCells x kCells
+constexpr float kCellHalfRange = 4.0f;       // cells tile [-4, 4]^2
+constexpr float kCellScale = kCells / (2.0f * kCellHalfRange);   // 8 cells per unit
+constexpr uint32_t kCellFull = 0xffffffffu;  // too many candidates for the list: full search
+
+template <int NCW> struct CodeBits;
+template <> struct CodeBits<16> { static constexpr int c = 4; };
+template <> struct CodeBits<64> { static constexpr int c = 6; };
+template <> struct CodeBits<256> { static constexpr int c = 8; };
+
+// Grid in LDS as (a, b, -(a^2+b^2)/2, unused): argmin ||y - C||^2 = argmax y.C - |C|^2/2.
+template <int NCW>
+__device__ __forceinline__ void load_codebook(const float* __restrict__ codebook, float4* cb) {
+  for (int j = threadIdx.x; j < NCW; j += blockDim.x) {
+    const float a = codebook[2 * j], b = codebook[2 * j + 1];
+    cb[j] = make_float4(a, b, -0.5f * (a * a + b * b), 0.f);
+  }
+}
+
+__device__ __forceinline__ float score(float y0, float y1, const float4 c) {
+  return __fmaf_rn(y0, c.x, __fmaf_rn(y1, c.y, c.z));
+}
+
+// Full search over all grid points; lowest index wins ties.
+template <int NCW>
+__device__ __forceinline__ int search_full(float y0, float y1, const float4* cb) {
+  float best = score(y0, y1, cb[0]);
+  int idx = 0;
+#pragma unroll 8
+  for (int j = 1; j < NCW; ++j) {
+    const float s = score(y0, y1, cb[j]);
+    const bool better = s > best;
+    best = better ? s : best;
+    idx = better ? j : idx;
+  }
+  return idx;
+}
+
+// Table search: score the (up to 4, ascending, last one repeated) candidates of the cell.
+// Sets `crowded` if the cell lists too many points; the caller then redoes the lane's
+// sub-vectors with the full search in one compact rolled loop (rare; keeps the hot path small).
+template <int NCW>
+__device__ __forceinline__ int search_cell(float y0, float y1, const float4* cb, const uint32_t* table,
+                                           bool& crowded) {
+  const float fx = __builtin_amdgcn_fmed3f(__fmaf_rn(y0, kCellScale, 0.5f * kCells), 0.0f, kCells - 0.5f);
+  const float fy = __builtin_amdgcn_fmed3f(__fmaf_rn(y1, kCellScale, 0.5f * kCells), 0.0f, kCells - 0.5f);
+  const uint32_t e = table[(int)fy * kCells + (int)fx];
+  crowded = e == kCellFull;
+  int idx = e & 0xff;
+  float best = score(y0, y1, cb[idx]);
+  constexpr int kCand = NCW == 16 ? 3 : 4;       // the builder marks cells of a 16-point grid with more than 3
+#pragma unroll
+  for (int k = 1; k < kCand; ++k) {
+    const int j = (e >> (8 * k)) & 0xff;
+    const float s = score(y0, y1, cb[j]);
+    const bool better = s > best;                // duplicates of the last candidate never win
+    best = better ? s : best;
+    idx = better ? j : idx;
+  }
+  return idx;
+}
+
+// Full search for the sub-vectors of this lane whose bit is set in `mask` (grid points in the
+// outer, rolled loop so that the code stays small).
+template <int NCW>
+__device__ __forceinline__ void search_full_masked(const float (&v)[32], float inv, const float4* cb, uint32_t mask,
+                                                int (&idx)[16]) {
+  float best[16];
+  int bi[16];
+  {
+    const float4 c0 = cb[0];
+#pragma unroll
+    for (int m = 0; m < 16; ++m) {
+      best[m] = score(v[2 * m] * inv, v[2 * m + 1] * inv, c0);
+      bi[m] = 0;
+    }
+  }
+#pragma unroll 1
+  for (int j = 1; j < NCW; ++j) {
+    const float4 cj = cb[j];
+#pragma unroll
+    for (int m = 0; m < 16; ++m) {
+      const float s = score(v[2 * m] * inv, v[2 * m + 1] * inv, cj);
+      const bool better = s > best[m];
+      best[m] = better ? s : best[m];
+      bi[m] = better ? j : bi[m];
+    }
+  }
+#pragma unroll
+  for (int m = 0; m < 16; ++m)
+    if ((mask >> m) & 1) idx[m] = bi[m];
+}
+
+// 16 codes of c bits per lane = 4c contiguous bytes of the group's little-endian bit string.
+template <int NCW>
+__device__ __forceinline__ void store_codes(uint8_t* __restrict__ codes, int64_t gid, int q, const int (&idx)[16]) {
+  constexpr int c = CodeBits<NCW>::c;
+  uint32_t* dst = reinterpret_cast<uint32_t*>(codes + gid * (kGroup / 2 * c / 8) + q * (2 * c));
+  if constexpr (c == 4) {
+    uint32_t d[2] = {0, 0};
+#pragma unroll
+    for (int m = 0; m < 16; ++m) d[m >> 3] |= (uint32_t)idx[m] << (4 * (m & 7));
+    u32x2 v; v.x = d[0]; v.y = d[1];
+    *reinterpret_cast<u32x2*>(dst) = v;
+  } else if constexpr (c == 6) {
+    uint32_t d[3] = {0, 0, 0};
+#pragma unroll
+    for (int m = 0; m < 16; ++m) {
+      const int bit = 6 * m, w = bit >> 5, sh = bit & 31;
+      d[w] |= (uint32_t)idx[m] << sh;
+      if (sh > 26) d[w + 1] |= (uint32_t)idx[m] >> (32 - sh);
+    }
+    dst[0] = d[0]; dst[1] = d[1]; dst[2] = d[2];
+  } else {
+    u32x4 v;
+    uint32_t d[4];
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+      d[w] = (uint32_t)idx[4 * w] | ((uint32_t)idx[4 * w + 1] << 8) | ((uint32_t)idx[4 * w + 2] << 16) |
+             ((uint32_t)idx[4 * w + 3] << 24);
+    v.x = d[0]; v.y = d[1]; v.z = d[2]; v.w = d[3];
+    *reinterpret_cast<u32x4*>(dst) = v;
+  }
+}
+
+// the 4c code bytes of a lane, as loaded into (the first c/2 dwords of) a register quad -> 16 indices
+template <int NCW>
+__device__ __forceinline__ void unpack_codes(const u32x4 raw, int (&idx)[16]) {
+  constexpr int c = CodeBits<NCW>::c;
+  const uint32_t d[4] = {raw.x, raw.y, raw.z, raw.w};
+  if constexpr (c == 4) {
+#pragma unroll
+    for (int m = 0; m < 16; ++m) idx[m] = (d[m >> 3] >> (4 * (m & 7))) & 15;
+  } else if constexpr (c == 6) {
+#pragma unroll
+    for (int m = 0; m < 16; ++m) {
+      const int bit = 6 * m, w = bit >> 5, sh = bit & 31;
+      uint32_t x = d[w] >> sh;
+      if (sh > 26) x |= d[w + 1] << (32 - sh);
+      idx[m] = x & 63;
+    }
+  } else {
+#pragma unroll
+    for (int m = 0; m < 16; ++m) idx[m] = (d[m >> 2] >> (8 * (m & 3))) & 255;
+  }
+}
+
+template <int NCW>
+__device__ __forceinline__ void load_codes(const uint8_t* __restrict__ codes, int64_t gid, int q, int (&idx)[16]) {
+  constexpr int c = CodeBits<NCW>::c;
+  const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + gid * (kGroup / 2 * c / 8) + q * (2 * c));
+  u32x4 raw = {0, 0, 0, 0};
+  if constexpr (c == 4) {
+    const u32x2 v = *reinterpret_cast<const u32x2*>(src);
+    raw.x = v.x; raw.y = v.y;
+  } else if constexpr (c == 6) {
+    raw.x = src[0]; raw.y = src[1]; raw.z = src[2];
+  } else {
+    raw = *reinterpret_cast<const u32x4*>(src);
+  }
+  unpack_codes<NCW>(raw, idx);
+}
+
+__device__ __forceinline__ float half_bits_to_float(uint16_t h) {
+  return static_cast<float>(__builtin_bit_cast(_Float16, h));
+}
+
+// codes + scale of one lane's part of a group -> zhat (rotated, scaled by sigma16)
+__device__ __forceinline__ void gather_zhat(const int (&idx)[16], float s16, const float4* cb, float (&z)[32]) {
+#pragma unroll
+  for (int m = 0; m < 16; ++m) {
+    const float4 cw = cb[idx[m]];
+    z[2 * m] = cw.x * s16;
+    z[2 * m + 1] = cw.y * s16;
+  }
+}
+
+struct Lds {
+  float4 cb[256];
+  uint32_t table[kCells * kCells];
+};
+
+template <int NCW>
+__device__ __forceinline__ void stage_lds(Lds& lds, const float* __restrict__ codebook,
+                                          const uint32_t* __restrict__ table) {
+  load_codebook<NCW>(codebook, lds.cb);
+  if (table != nullptr) {
+    const u32x4* src = reinterpret_cast<const u32x4*>(table);
+    u32x4* dst = reinterpret_cast<u32x4*>(lds.table);
+    for (int i = threadIdx.x; i < kCells * kCells / 4; i += blockDim.x) dst[i] = src[i];
+  }
+  __syncthreads();
+}
+
+
+// ------------------------------------------------------------------ group bodies
+// Q(x - p) for the 32 coordinates this lane holds of group `gid`.  On entry v = x; on exit v
+// holds the (unrounded) reconstruction p + Q^-1(codes) if `want_hat`.  Codes and the scale are
+// stored when `active` (inactive lanes only keep the quad's DPP exchanges in step).
+template <int NCW>
+__device__ __forceinline__ void quantize_group(float (&v)[32], const float (&p)[32], const uint32_t (&sb)[32], int q,
+                                               const float4* cb, const uint32_t* table, bool active, int64_t gid,
+                                               uint8_t* __restrict__ codes, uint16_t* __restrict__ scales,
+                                               bool want_hat) {
+#pragma unroll
+  for (int r = 0; r < 32; ++r) v[r] = __uint_as_float(__float_as_uint(v[r] - p[r]) ^ sb[r]);   // s * (x - p)
+  wht128(v, q);                                           // w = H u (unnormalised)
+
+  float ss = 0.f;
+#pragma unroll
+  for (int r = 0; r < 32; ++r) ss = __fmaf_rn(v[r], v[r], ss);
+  ss = quad_sum(ss);
+  // z = w / sqrt(g)  =>  rms(z) = sqrt(sum w^2) / g
+  float sigma = __fsqrt_rn(ss) * (1.0f / kGroup);
+  sigma = fminf(sigma, 65504.0f);
+  const _Float16 s16h = static_cast<_Float16>(sigma);     // round to nearest even
+  const float s16 = static_cast<float>(s16h);
+  const float inv = s16 > 0.f ? __fdiv_rn(kRsqrtG, s16) : 0.f;
+
+  int idx[16];
+  if (table != nullptr) {
+    uint32_t crowded_mask = 0;
+#pragma unroll
+    for (int m = 0; m < 16; ++m) {
+      bool crowded;
+      idx[m] = search_cell<NCW>(v[2 * m] * inv, v[2 * m + 1] * inv, cb, table, crowded);
+      crowded_mask |= crowded ? 1u << m : 0u;
+    }
+    if (__builtin_expect(__builtin_amdgcn_ballot_w64(crowded_mask != 0) != 0, 0))
+      search_full_masked<NCW>(v, inv, cb, crowded_mask, idx);
+  } else {
+#pragma unroll
+    for (int m = 0; m < 16; ++m) idx[m] = search_full<NCW>(v[2 * m] * inv, v[2 * m + 1] * inv, cb);
+  }
+  if (active) {
+    store_codes<NCW>(codes, gid, q, idx);
+    if (q == 0) scales[gid] = __builtin_bit_cast(uint16_t, s16h);
+  }
+  if (want_hat) {
+    gather_zhat(idx, s16, cb, v);
+    reconstruct(v, q, sb, p);
+  }
+}
+
+// Q^-1(codes) + p for the 32 coordinates this lane holds of group `gid` (unrounded, in z).
+template <int NCW>
+__device__ __forceinline__ void dequantize_group(float (&z)[32], const float (&p)[32], const uint32_t (&sb)[32], int q,
+                                                 const float4* cb, int64_t gid, const uint8_t* __restrict__ codes,
+                                                 const uint16_t* __restrict__ scales) {
+  int idx[16];
+  load_codes<NCW>(codes, gid, q, idx);
+  const float s16 = half_bits_to_float(scales[gid]);
+  gather_zhat(idx, s16, cb, z);
+  reconstruct(z, q, sb, p);
+}
+
+}  // namespace aquakv

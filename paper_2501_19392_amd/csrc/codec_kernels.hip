@@ -2,20 +2,12 @@
 // the AQUA-KV paper, HIGGS-style): quantize (residual -> RHT -> group scale ->
 // nearest grid point -> packed codes, plus the reconstruction), dequantize, and
 // dequantize fused with grouped-query q.k scoring; plus the builder of the
-// nearest-grid-point search table.
+// nearest-grid-point search table.  These are the stand-alone forms (prediction
+// read from memory, or absent); the fused forms live in fused_kernels.hip.
 //
 // One rotation group is held by a quad of lanes x 32 values (see device_utils.h);
 // a 256-thread block covers 64 groups per pass.
-//
-// Nearest grid point.  The definition is a search over all n grid points.  The
-// kernels reach the same answer with a 64 x 64 table of square cells over
-// [-4, 4]^2 (border cells are unbounded outwards): each cell
-// lists, in ascending order, every grid point that can be nearest to some point
-// of the (slightly enlarged) cell -- at most 4, else the cell is marked and the
-// lane falls back to the full search.  Only the listed points are scored, with
-// the same fp32 expression and the same lowest-index tie rule as the full
-// search, so both give identical codes.
-#include "device_utils.h"
+#include "codec_core.h"
 #include "kernels.h"
 
 namespace aquakv {
@@ -23,153 +15,6 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kGroupsPerBlock = kThreads / kLanesPerGroup;   // 64
-constexpr int kCells = 64;                   // table is kCells x kCells
-constexpr float kCellHalfRange = 4.0f;       // cells tile [-4, 4]^2
-constexpr float kCellScale = kCells / (2.0f * kCellHalfRange);   // 8 cells per unit
-constexpr uint32_t kCellFull = 0xffffffffu;  // too many candidates for the list: full search
-
-template <int NCW> struct CodeBits;
-template <> struct CodeBits<16> { static constexpr int c = 4; };
-template <> struct CodeBits<64> { static constexpr int c = 6; };
-template <> struct CodeBits<256> { static constexpr int c = 8; };
-
-// Grid in LDS as (a, b, -(a^2+b^2)/2, unused): argmin ||y - C||^2 = argmax y.C - |C|^2/2.
-template <int NCW>
-__device__ __forceinline__ void load_codebook(const float* __restrict__ codebook, float4* cb) {
-  for (int j = threadIdx.x; j < NCW; j += kThreads) {
-    const float a = codebook[2 * j], b = codebook[2 * j + 1];
-    cb[j] = make_float4(a, b, -0.5f * (a * a + b * b), 0.f);
-  }
-}
-
-__device__ __forceinline__ float score(float y0, float y1, const float4 c) {
-  return __fmaf_rn(y0, c.x, __fmaf_rn(y1, c.y, c.z));
-}
-
-// Full search over all grid points; lowest index wins ties.
-template <int NCW>
-__device__ __forceinline__ int search_full(float y0, float y1, const float4* cb) {
-  float best = score(y0, y1, cb[0]);
-  int idx = 0;
-#pragma unroll 8
-  for (int j = 1; j < NCW; ++j) {
-    const float s = score(y0, y1, cb[j]);
-    const bool better = s > best;
-    best = better ? s : best;
-    idx = better ? j : idx;
-  }
-  return idx;
-}
-
-// Table search: score the (up to 4, ascending, last one repeated) candidates of the cell.
-template <int NCW>
-__device__ __forceinline__ int search_cell(float y0, float y1, const float4* cb, const uint32_t* table) {
-  const float fx = __builtin_amdgcn_fmed3f(__fmaf_rn(y0, kCellScale, 0.5f * kCells), 0.0f, kCells - 0.5f);
-  const float fy = __builtin_amdgcn_fmed3f(__fmaf_rn(y1, kCellScale, 0.5f * kCells), 0.0f, kCells - 0.5f);
-  const uint32_t e = table[(int)fy * kCells + (int)fx];
-  int idx = e & 0xff;
-  float best = score(y0, y1, cb[idx]);
-  constexpr int kCand = NCW == 16 ? 3 : 4;       // 16 grid points never need more than 3 per cell
-#pragma unroll
-  for (int k = 1; k < kCand; ++k) {
-    const int j = (e >> (8 * k)) & 0xff;
-    const float s = score(y0, y1, cb[j]);
-    const bool better = s > best;                // duplicates of the last candidate never win
-    best = better ? s : best;
-    idx = better ? j : idx;
-  }
-  if (__builtin_expect(e == kCellFull, 0)) idx = search_full<NCW>(y0, y1, cb);   // crowded cell
-  return idx;
-}
-
-// 16 codes of c bits per lane = 4c contiguous bytes of the group's little-endian bit string.
-template <int NCW>
-__device__ __forceinline__ void store_codes(uint8_t* __restrict__ codes, int64_t gid, int q, const int (&idx)[16]) {
-  constexpr int c = CodeBits<NCW>::c;
-  uint32_t* dst = reinterpret_cast<uint32_t*>(codes + gid * (kGroup / 2 * c / 8) + q * (2 * c));
-  if constexpr (c == 4) {
-    uint32_t d[2] = {0, 0};
-#pragma unroll
-    for (int m = 0; m < 16; ++m) d[m >> 3] |= (uint32_t)idx[m] << (4 * (m & 7));
-    u32x2 v; v.x = d[0]; v.y = d[1];
-    *reinterpret_cast<u32x2*>(dst) = v;
-  } else if constexpr (c == 6) {
-    uint32_t d[3] = {0, 0, 0};
-#pragma unroll
-    for (int m = 0; m < 16; ++m) {
-      const int bit = 6 * m, w = bit >> 5, sh = bit & 31;
-      d[w] |= (uint32_t)idx[m] << sh;
-      if (sh > 26) d[w + 1] |= (uint32_t)idx[m] >> (32 - sh);
-    }
-    dst[0] = d[0]; dst[1] = d[1]; dst[2] = d[2];
-  } else {
-    u32x4 v;
-    uint32_t d[4];
-#pragma unroll
-    for (int w = 0; w < 4; ++w)
-      d[w] = (uint32_t)idx[4 * w] | ((uint32_t)idx[4 * w + 1] << 8) | ((uint32_t)idx[4 * w + 2] << 16) |
-             ((uint32_t)idx[4 * w + 3] << 24);
-    v.x = d[0]; v.y = d[1]; v.z = d[2]; v.w = d[3];
-    *reinterpret_cast<u32x4*>(dst) = v;
-  }
-}
-
-template <int NCW>
-__device__ __forceinline__ void load_codes(const uint8_t* __restrict__ codes, int64_t gid, int q, int (&idx)[16]) {
-  constexpr int c = CodeBits<NCW>::c;
-  const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + gid * (kGroup / 2 * c / 8) + q * (2 * c));
-  if constexpr (c == 4) {
-    const u32x2 v = *reinterpret_cast<const u32x2*>(src);
-    const uint32_t d[2] = {v.x, v.y};
-#pragma unroll
-    for (int m = 0; m < 16; ++m) idx[m] = (d[m >> 3] >> (4 * (m & 7))) & 15;
-  } else if constexpr (c == 6) {
-    const uint32_t d[3] = {src[0], src[1], src[2]};
-#pragma unroll
-    for (int m = 0; m < 16; ++m) {
-      const int bit = 6 * m, w = bit >> 5, sh = bit & 31;
-      uint32_t x = d[w] >> sh;
-      if (sh > 26) x |= d[w + 1] << (32 - sh);
-      idx[m] = x & 63;
-    }
-  } else {
-    const u32x4 v = *reinterpret_cast<const u32x4*>(src);
-    const uint32_t d[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-    for (int m = 0; m < 16; ++m) idx[m] = (d[m >> 2] >> (8 * (m & 3))) & 255;
-  }
-}
-
-__device__ __forceinline__ float half_bits_to_float(uint16_t h) {
-  return static_cast<float>(__builtin_bit_cast(_Float16, h));
-}
-
-// codes + scale of one lane's part of a group -> zhat (rotated, scaled by sigma16)
-__device__ __forceinline__ void gather_zhat(const int (&idx)[16], float s16, const float4* cb, float (&z)[32]) {
-#pragma unroll
-  for (int m = 0; m < 16; ++m) {
-    const float4 cw = cb[idx[m]];
-    z[2 * m] = cw.x * s16;
-    z[2 * m + 1] = cw.y * s16;
-  }
-}
-
-struct Lds {
-  float4 cb[256];
-  uint32_t table[kCells * kCells];
-};
-
-template <int NCW>
-__device__ __forceinline__ void stage_lds(Lds& lds, const float* __restrict__ codebook,
-                                          const uint32_t* __restrict__ table) {
-  load_codebook<NCW>(codebook, lds.cb);
-  if (table != nullptr) {
-    const u32x4* src = reinterpret_cast<const u32x4*>(table);
-    u32x4* dst = reinterpret_cast<u32x4*>(lds.table);
-    for (int i = threadIdx.x; i < kCells * kCells / 4; i += kThreads) dst[i] = src[i];
-  }
-  __syncthreads();
-}
 
 // ------------------------------------------------------------------ quantize
 template <typename T, int NCW>
@@ -199,36 +44,9 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const T* X, const fl
       for (int r = 0; r < 32; ++r) p[r] = 0.f;
     }
     load_sign_bits(signs, head, q, sb);
-#pragma unroll
-    for (int r = 0; r < 32; ++r) v[r] = __uint_as_float(__float_as_uint(v[r] - p[r]) ^ sb[r]);   // s * (x - p)
-    wht128(v, q);                                           // w = H u (unnormalised)
-
-    float ss = 0.f;
-#pragma unroll
-    for (int r = 0; r < 32; ++r) ss = __fmaf_rn(v[r], v[r], ss);
-    ss = quad_sum(ss);
-    // z = w / sqrt(g)  =>  rms(z) = sqrt(sum w^2) / g
-    float sigma = __fsqrt_rn(ss) * (1.0f / kGroup);
-    sigma = fminf(sigma, 65504.0f);
-    const _Float16 s16h = static_cast<_Float16>(sigma);     // round to nearest even
-    const float s16 = static_cast<float>(s16h);
-    const float inv = s16 > 0.f ? __fdiv_rn(kRsqrtG, s16) : 0.f;
-
-    int idx[16];
-#pragma unroll
-    for (int m = 0; m < 16; ++m) {
-      const float y0 = v[2 * m] * inv, y1 = v[2 * m + 1] * inv;
-      idx[m] = table != nullptr ? search_cell<NCW>(y0, y1, lds.cb, lds.table) : search_full<NCW>(y0, y1, lds.cb);
-    }
-    if (active) {
-      store_codes<NCW>(codes, gid, q, idx);
-      if (q == 0) scales[gid] = __builtin_bit_cast(uint16_t, s16h);
-    }
-    if (Xhat != nullptr) {
-      gather_zhat(idx, s16, lds.cb, v);
-      reconstruct(v, q, sb, p);
-      if (active) Storage<T>::store32(Xhat + off, v);
-    }
+    quantize_group<NCW>(v, p, sb, q, lds.cb, table != nullptr ? lds.table : nullptr, active, gid, codes, scales,
+                        Xhat != nullptr);
+    if (Xhat != nullptr && active) Storage<T>::store32(Xhat + off, v);
   }
 }
 
@@ -253,9 +71,6 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint8_t* __r
 
     float p[32], z[32];
     uint32_t sb[32];
-    int idx[16];
-    load_codes<NCW>(codes, gid, q, idx);
-    const float s16 = half_bits_to_float(scales[gid]);
     if (P != nullptr) {
       load32_f32(P + off, p);
     } else {
@@ -263,8 +78,7 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint8_t* __r
       for (int r = 0; r < 32; ++r) p[r] = 0.f;
     }
     load_sign_bits(signs, head, q, sb);
-    gather_zhat(idx, s16, cb, z);
-    reconstruct(z, q, sb, p);
+    dequantize_group<NCW>(z, p, sb, q, cb, gid, codes, scales);
     if (active) Storage<T>::store32(Xhat + off, z);
   }
 }
@@ -294,9 +108,6 @@ __global__ __launch_bounds__(kThreads) void attn_scores_kernel(
 
     float p[32], z[32];
     uint32_t sb[32];
-    int idx[16];
-    load_codes<NCW>(codes, gid, q, idx);
-    const float s16 = half_bits_to_float(scales[gid]);
     if (P != nullptr) {
       load32_f32(P + off, p);
     } else {
@@ -304,8 +115,7 @@ __global__ __launch_bounds__(kThreads) void attn_scores_kernel(
       for (int r = 0; r < 32; ++r) p[r] = 0.f;
     }
     load_sign_bits(signs, head, q, sb);
-    gather_zhat(idx, s16, cb, z);
-    reconstruct(z, q, sb, p);
+    dequantize_group<NCW>(z, p, sb, q, cb, gid, codes, scales);
     if (Khat_out != nullptr && active) Storage<T>::store32(Khat_out + off, z);
 #pragma unroll
     for (int r = 0; r < 32; ++r) z[r] = Storage<T>::round(z[r]);      // score the stored keys

@@ -79,6 +79,16 @@ template <> struct Storage<bf16_t> {
   }
 };
 
+// 8 bf16 in a 16-byte register quad -> fp32
+__device__ __forceinline__ void unpack_bf16x8(const u32x4 r, float* v) {
+  const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    v[2 * i] = __uint_as_float(w[i] << 16);
+    v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+  }
+}
+
 __device__ __forceinline__ void load32_f32(const float* p, float (&v)[32]) { Storage<float>::load32(p, v); }
 
 // ---------------------------------------------------------------- cross-lane moves inside a quad
@@ -87,7 +97,7 @@ template <int MASK> __device__ __forceinline__ float quad_xor(float x) {
   static_assert(MASK == 1 || MASK == 2, "mask");
   const int xi = __float_as_int(x);
   constexpr int ctrl = MASK == 1 ? 0xB1 /* [1,0,3,2] */ : 0x4E /* [2,3,0,1] */;
-  return __int_as_float(__builtin_amdgcn_update_dpp(xi, xi, ctrl, 0xF, 0xF, false));
+  return __int_as_float(__builtin_amdgcn_mov_dpp(xi, ctrl, 0xF, 0xF, true));   // folds into the consuming add
 }
 
 // Sum over the 4 lanes of a group; every lane gets the total (fixed order).

@@ -1,0 +1,204 @@
+// Fused predictor kernels (bf16): the prediction never leaves the chip.
+//
+// Alg. "encode" / "decode" of the AQUA-KV paper apply the linear predictor of Sect. 3.2 and
+// then the backbone quantizer of Sect. 2 (or its inverse) to the same rows.  One workgroup
+// computes a 256-row x 128-column tile of the prediction on the matrix cores -- 128 columns
+// are exactly one kv head = one rotation group per row -- parks it in LDS in fp32, and runs
+// the quantizer (encode), its inverse (decode), or its inverse plus the grouped-query q.k
+// dot products (scores) on those 256 groups as the epilogue.  Against separate kernels this
+// saves writing and re-reading 4 bytes per value of fp32 predictions and a launch.
+//
+// Arithmetic is the same as in the stand-alone kernels (same main loop, same group bodies,
+// prediction carried in fp32), so fused and unfused paths give identical bits.
+#include "codec_core.h"
+#include "gemm_core.h"
+#include "kernels.h"
+
+namespace aquakv {
+namespace {
+
+constexpr int kLdP = BN + 4;                        // padded fp32 row of the parked prediction tile
+constexpr int kWaveTileBytes = 64 * kLdP * 4;       // one wave's 64 rows
+constexpr int kPredBytes = 4 * kWaveTileBytes;      // 135168: reuses (and exceeds) the main loop's 2 stages
+constexpr int kFusedLdsBytes = kPredBytes + (int)sizeof(Lds);
+static_assert(kPredBytes >= 2 * kStageBytes, "prediction tile must cover the main-loop stages");
+static_assert(kFusedLdsBytes <= 160 * 1024, "LDS of one CU");
+
+enum Mode : int { kEncode = 0, kDecode = 1, kScores = 2 };
+
+template <int NCW, int MODE>
+__global__ __launch_bounds__(kGemmThreads) void fused_kernel(
+    const bf16_t* __restrict__ x0, int d0, const bf16_t* __restrict__ x1, int d1, const bf16_t* __restrict__ W,
+    const float* __restrict__ bias, const int8_t* __restrict__ signs, const float* __restrict__ codebook,
+    const uint32_t* __restrict__ table, const bf16_t* X, uint8_t* codes, uint16_t* scales, bf16_t* Xhat,
+    const bf16_t* __restrict__ qv, float score_scale, float* __restrict__ scores, int seq_len, int q_heads, int64_t T,
+    int D) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[kFusedLdsBytes];
+  Lds& cl = *reinterpret_cast<Lds*>(smem + kPredBytes);
+  const bool use_table = MODE == kEncode && table != nullptr;
+  load_codebook<NCW>(codebook, cl.cb);               // made visible by the main loop's first barrier
+  if (use_table) {
+    const u32x4* src = reinterpret_cast<const u32x4*>(table);
+    u32x4* dst = reinterpret_cast<u32x4*>(cl.table);
+    for (int i = threadIdx.x; i < kCells * kCells / 4; i += kGemmThreads) dst[i] = src[i];
+  }
+
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int H = D / BN;
+  const int logical = remap_block(blockIdx.x, gridDim.x);
+  const int tile_m = logical / H, head = logical % H;
+  const int64_t m0 = (int64_t)tile_m * BM;
+  const int n0 = head * BN;
+
+  f32x16 acc[2][4];
+  gemm_mainloop(smem, x0, d0, x1, d1, W, T, m0, n0, acc);
+
+  // park the tile (+ bias) in LDS, row-major fp32, each wave its own 64 rows
+  float* wl = reinterpret_cast<float*>(smem) + wave * 64 * kLdP;
+  {
+    const int frow = lane & 31, fk = lane >> 5;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int col = j * 32 + frow;
+      const float bv = bias != nullptr ? bias[n0 + col] : 0.f;
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int lrow = i * 32 + (r >> 2) * 8 + fk * 4 + (r & 3);
+          wl[lrow * kLdP + col] = acc[i][j][r] + bv;
+        }
+    }
+  }
+  __syncthreads();
+
+  // Epilogue: 4 passes of 16 groups per wave, one group per quad.  The loop is kept rolled (the
+  // body is large and the instruction cache is shared); the global inputs of pass p+1 are
+  // requested before pass p is worked on, since one wave per SIMD hides no load latency.
+  const int q = lane & 3;
+  uint32_t sb[32];
+  load_sign_bits(signs, head, q, sb);
+  constexpr int c = CodeBits<NCW>::c;
+  struct In { u32x4 x[4]; u32x4 code; uint16_t scale; };
+  const auto fetch = [&](int pass, In& in) {
+    int64_t row = m0 + wave * 64 + pass * 16 + (lane >> 2);
+    row = row < T ? row : T - 1;
+    if constexpr (MODE == kEncode) {
+      const u32x4* src = reinterpret_cast<const u32x4*>(X + row * D + n0 + q * kValsPerLane);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) in.x[k] = src[k];
+    } else {
+      const int64_t gid = row * H + head;
+      const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + gid * (kGroup / 2 * c / 8) + q * (2 * c));
+      if constexpr (c == 4) {
+        const u32x2 v2 = *reinterpret_cast<const u32x2*>(src);
+        in.code.x = v2.x; in.code.y = v2.y;
+      } else if constexpr (c == 6) {
+        in.code.x = src[0]; in.code.y = src[1]; in.code.z = src[2];
+      } else {
+        in.code = *reinterpret_cast<const u32x4*>(src);
+      }
+      in.scale = scales[gid];
+    }
+  };
+  In cur, next;
+  fetch(0, next);
+#pragma unroll 1
+  for (int pass = 0; pass < 4; ++pass) {
+    cur = next;
+    if (pass < 3) fetch(pass + 1, next);
+    const int lrow = pass * 16 + (lane >> 2);
+    const int64_t row = m0 + wave * 64 + lrow;
+    const bool active = row < T;
+    const int64_t rowc = active ? row : T - 1;
+    const int64_t gid = rowc * H + head;
+    const int64_t off = rowc * D + n0 + q * kValsPerLane;
+    float p[32], v[32];
+    {
+      const f32x4* src = reinterpret_cast<const f32x4*>(wl + lrow * kLdP + q * kValsPerLane);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const f32x4 a = src[k];
+        p[4 * k] = a.x; p[4 * k + 1] = a.y; p[4 * k + 2] = a.z; p[4 * k + 3] = a.w;
+      }
+    }
+    if constexpr (MODE == kEncode) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) unpack_bf16x8(cur.x[k], &v[8 * k]);
+      quantize_group<NCW>(v, p, sb, q, cl.cb, use_table ? cl.table : nullptr, active, gid, codes, scales,
+                          Xhat != nullptr);
+      if (Xhat != nullptr && active) Storage<bf16_t>::store32(Xhat + off, v);
+    } else {
+      int idx[16];
+      unpack_codes<NCW>(cur.code, idx);
+      gather_zhat(idx, half_bits_to_float(cur.scale), cl.cb, v);
+      reconstruct(v, q, sb, p);
+      if (Xhat != nullptr && active) Storage<bf16_t>::store32(Xhat + off, v);
+      if constexpr (MODE == kScores) {
+#pragma unroll
+        for (int r = 0; r < 32; ++r) v[r] = Storage<bf16_t>::round(v[r]);      // score the stored keys
+        const int rep = q_heads / H;
+        const int64_t b = rowc / seq_len, t = rowc % seq_len;
+        for (int r = 0; r < rep; ++r) {
+          const int qh = head * rep + r;
+          float qf[32];
+          Storage<bf16_t>::load32(qv + (b * q_heads + qh) * kGroup + q * kValsPerLane, qf);
+          float s = 0.f;
+#pragma unroll
+          for (int i = 0; i < 32; ++i) s = __fmaf_rn(qf[i], v[i], s);
+          s = quad_sum(s);
+          if (active && q == 0) scores[(b * q_heads + qh) * seq_len + t] = s * score_scale;
+        }
+      }
+    }
+  }
+}
+
+template <int MODE>
+hipError_t launch(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W, const float* bias,
+                  const int8_t* signs, const float* codebook, const void* table, const void* X, uint8_t* codes,
+                  uint16_t* scales, void* Xhat, const void* q, float score_scale, float* scores, int seq_len,
+                  int q_heads, int64_t T, int D, hipStream_t stream) {
+  if (T == 0) return hipSuccess;
+  const unsigned blocks = (unsigned)(((T + BM - 1) / BM) * (D / BN));
+#define AQUAKV_FUSED(N)                                                                                          \
+  fused_kernel<N, MODE><<<blocks, kGemmThreads, 0, stream>>>(                                                    \
+      static_cast<const bf16_t*>(x0), d0, static_cast<const bf16_t*>(x1), d1, static_cast<const bf16_t*>(W), bias, \
+      signs, codebook, static_cast<const uint32_t*>(table), static_cast<const bf16_t*>(X), codes, scales,         \
+      static_cast<bf16_t*>(Xhat), static_cast<const bf16_t*>(q), score_scale, scores, seq_len, q_heads, T, D)
+  if (n_codewords == 16) AQUAKV_FUSED(16);
+  else if (n_codewords == 64) AQUAKV_FUSED(64);
+  else AQUAKV_FUSED(256);
+#undef AQUAKV_FUSED
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_fused_encode(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W,
+                               const float* bias, const int8_t* signs, const float* codebook, const void* table,
+                               const void* X, uint8_t* codes, uint16_t* scales, void* Xhat, int64_t T, int D,
+                               hipStream_t stream) {
+  return launch<kEncode>(n_codewords, x0, d0, x1, d1, W, bias, signs, codebook, table, X, codes, scales, Xhat, nullptr,
+                         0.f, nullptr, 1, 1, T, D, stream);
+}
+
+hipError_t launch_fused_decode(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W,
+                               const float* bias, const int8_t* signs, const float* codebook, const uint8_t* codes,
+                               const uint16_t* scales, void* Xhat, int64_t T, int D, hipStream_t stream) {
+  return launch<kDecode>(n_codewords, x0, d0, x1, d1, W, bias, signs, codebook, nullptr, nullptr,
+                         const_cast<uint8_t*>(codes), const_cast<uint16_t*>(scales), Xhat, nullptr, 0.f, nullptr, 1, 1,
+                         T, D, stream);
+}
+
+hipError_t launch_fused_scores(int n_codewords, const void* x0, int d0, const void* W, const float* bias,
+                               const int8_t* signs, const float* codebook, const uint8_t* codes,
+                               const uint16_t* scales, const void* q, float score_scale, float* scores, void* Khat_out,
+                               int seq_len, int q_heads, int64_t T, int D, hipStream_t stream) {
+  return launch<kScores>(n_codewords, x0, d0, nullptr, 0, W, bias, signs, codebook, nullptr, nullptr,
+                         const_cast<uint8_t*>(codes), const_cast<uint16_t*>(scales), Khat_out, q, score_scale, scores,
+                         seq_len, q_heads, T, D, stream);
+}
+
+}  // namespace aquakv

@@ -33,4 +33,18 @@ hipError_t launch_attn_scores(int dtype, int n_codewords, const uint8_t* codes, 
                               float* scores, void* Khat_out, int64_t row0, int64_t rows, int seq_len, int H,
                               int q_heads, hipStream_t stream);
 
+// Fused bf16 forms: prediction [x0 | x1] W^T + bias on the matrix cores, consumed in the same
+// kernel by the quantizer (encode), its inverse (decode) or its inverse plus q.k (scores).
+hipError_t launch_fused_encode(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W,
+                               const float* bias, const int8_t* signs, const float* codebook, const void* table,
+                               const void* X, uint8_t* codes, uint16_t* scales, void* Xhat, int64_t T, int D,
+                               hipStream_t stream);
+hipError_t launch_fused_decode(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W,
+                               const float* bias, const int8_t* signs, const float* codebook, const uint8_t* codes,
+                               const uint16_t* scales, void* Xhat, int64_t T, int D, hipStream_t stream);
+hipError_t launch_fused_scores(int n_codewords, const void* x0, int d0, const void* W, const float* bias,
+                               const int8_t* signs, const float* codebook, const uint8_t* codes,
+                               const uint16_t* scales, const void* q, float score_scale, float* scores, void* Khat_out,
+                               int seq_len, int q_heads, int64_t T, int D, hipStream_t stream);
+
 }  // namespace aquakv

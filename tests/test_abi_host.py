@@ -70,8 +70,11 @@ def test_bad_layer_is_rejected(kw, want):
 def test_bad_call_arguments_are_rejected_without_launching():
     L = layer()
     need = B.aquakv_workspace_bytes(L, 300)
-    assert need == 300 * 1024 * (4 + 2)
-    assert B.aquakv_workspace_bytes(L, 1 << 20) == 16384 * 1024 * 6          # chunked: bounded
+    assert need == 300 * 1024 * 2                                            # bf16: only a temporary Khat
+    assert B.aquakv_workspace_bytes(L, 1 << 20) == 65536 * 1024 * 2          # chunked: bounded
+    L32 = layer(dtype=B.AQUAKV_FP32)
+    assert B.aquakv_workspace_bytes(L32, 300) == 300 * 1024 * (4 + 4)        # fp32: predictions + Khat
+    assert B.aquakv_workspace_bytes(L32, 1 << 20) == 16384 * 1024 * 8
     args = list(ENC_OK)
     assert status_of(B.aquakv_encode_layer, L, -1, *args, (FAKE, need)) == B.AQUAKV_EINVAL
     assert status_of(B.aquakv_encode_layer, L, 300, *args, (FAKE, need - 1)) == B.AQUAKV_EWORKSPACE
@@ -106,5 +109,5 @@ def test_bad_call_arguments_are_rejected_without_launching():
     sc = [FAKE, FAKE, FAKE, FAKE, 1.0, FAKE, None]
     assert status_of(B.aquakv_decode_attn_scores, L, 2, 16, 12, *sc, (FAKE, 1 << 30)) == B.AQUAKV_EINVAL   # 12 % 8
     assert status_of(B.aquakv_decode_attn_scores, L, 2, 16, 128, *sc, (FAKE, 1 << 30)) == B.AQUAKV_EINVAL  # > 8x
-    assert status_of(B.aquakv_decode_attn_scores, L, 2, 16, 32, *sc, (FAKE, 16)) == B.AQUAKV_EWORKSPACE
+    assert status_of(B.aquakv_decode_attn_scores, L32, 2, 16, 32, *sc, (FAKE, 16)) == B.AQUAKV_EWORKSPACE
     B.aquakv_decode_attn_scores(L, 0, 16, 32, *sc, None)
