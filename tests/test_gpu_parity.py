@@ -383,3 +383,114 @@ def test_attn_scores(B, dtype, n, with_pred):
                                 lg.alloc_workspace(cfg.tokens))
     sync()
     assert torch.equal(s2, scores)
+
+
+# ------------------------------------------------------------------ full sizes, sampled rows
+def sampled_rows(T, n, seed):
+    """Seeded sample of token rows that always includes the first / last rows and both sides
+    of workgroup-tile boundaries (tiles are 256 rows)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    fixed = [0, 1, 255, 256, 257, T // 2, T - 257, T - 256, T - 2, T - 1]
+    extra = rng.choice(T, size=n - len(fixed), replace=False).tolist()
+    return torch.tensor(sorted(set(fixed + extra)), device="cuda")
+
+
+def stream_layers(cfg, n_layers, n_per_layer, device="cuda"):
+    """Layer-by-layer generator on the GPU (as bench.py does): yields (l, K, V, oracle layer, gpu layer)."""
+    st = synth.KVStream(cfg, device=device, work=torch.float32)
+    for l in range(n_layers):
+        K, V = st.next()
+        if l == 0:
+            lo, lg = U.make_layers(cfg.kv_heads, cfg.dtype, n_per_layer[l], layer_idx=l)
+        else:
+            wk, wv = synth.analytic_predictors(st, l)
+            lo, lg = U.make_layers(cfg.kv_heads, cfg.dtype, n_per_layer[l], layer_idx=l, w_k=wk, w_v=wv)
+        yield l, K.contiguous(), V.contiguous(), lo, lg
+
+
+@pytest.mark.parametrize("name,T,n_per_layer", [
+    ("llama3.2-3b bench shape", 8192, [16, 16, 16]),
+    ("llama3.1-8b shape, 3-bit", 32768, [64, 64]),
+    ("llama3.1-70b shape, mixed 2/3-bit", 131072, [16, 64, 16]),
+])
+def test_full_size_layers_on_sampled_rows(B, name, T, n_per_layer):
+    """The launch configuration bench.py times (all rows of a layer in one call), checked on a
+    seeded sample of rows: tokens are independent, so the oracle can follow single rows exactly."""
+    print(f"case full size: {name} T={T}", flush=True)
+    cfg = synth.Config(name, layers=len(n_per_layer), kv_heads=8, head_dim=128, tokens=T, dtype="bf16")
+    rows = sampled_rows(T, 160, 5)
+    Kp = Vp = None
+    for l, K, V, lo, lg in stream_layers(cfg, len(n_per_layer), n_per_layer):
+        kc, ks = lg.alloc_codes(T)
+        vc, vs = lg.alloc_codes(T)
+        Kh, Vh = lg.alloc_kv(T), lg.alloc_kv(T)
+        ws = lg.alloc_workspace(T)
+        B.aquakv_encode_layer(lg, T, K, V, Kp, Vp, kc, ks, vc, vs, Kh, Vh, ws)
+        sync()
+        g = dict(k_codes=kc, k_scales=ks, v_codes=vc, v_scales=vs, Khat=Kh, Vhat=Vh, Kp=Kp, Vp=Vp)
+        for rep in check_layer_against_oracle(B, lo, lg, K, V, g, rows=rows):
+            print(f"   layer {l}: {rep}", flush=True)
+        Kd, Vd = lg.alloc_kv(T), lg.alloc_kv(T)
+        B.aquakv_decode_layer(lg, T, kc, ks, vc, vs, Kp, Vp, Kd, Vd, ws)
+        sync()
+        assert torch.equal(bits(Kd), bits(Kh)) and torch.equal(bits(Vd), bits(Vh))
+        # properties that hold at any size: every scale is a finite non-negative fp16, the relative
+        # reconstruction error of the whole tensor is what the grid and the predictor allow
+        s = ks.view(torch.float16).float()
+        assert torch.isfinite(s).all() and (s >= 0).all()
+        rel = ((Kh.float() - K.float()).pow(2).sum() / K.float().pow(2).sum()).item()
+        bound = {16: 0.13, 64: 0.04}[n_per_layer[l]] if l == 0 else {16: 0.06, 64: 0.02}[n_per_layer[l]]
+        assert rel < bound, (l, rel)
+        Kp, Vp = Kh, Vh
+
+
+def test_decode_read_path_batch_of_long_sequences(B):
+    """The decode-phase read path (batched sequences of 16384 cached tokens, 32 query heads on 8 kv
+    heads): fused dequantize + q.k against the oracle on sampled (sequence, token) pairs, plus the
+    one-new-token-per-sequence append through aquakv_encode_layer."""
+    print("case decode read path", flush=True)
+    batch, S, H, QH, n = 8, 16384, 8, 32, 16
+    T = batch * S
+    cfg = synth.Config("read-path", layers=2, kv_heads=H, head_dim=128, tokens=T, dtype="bf16")
+    outs = []
+    Kp = Vp = None
+    for l, K, V, lo, lg in stream_layers(cfg, 2, [n, n]):
+        kc, ks = lg.alloc_codes(T)
+        vc, vs = lg.alloc_codes(T)
+        Kh, Vh = lg.alloc_kv(T), lg.alloc_kv(T)
+        B.aquakv_encode_layer(lg, T, K, V, Kp, Vp, kc, ks, vc, vs, Kh, Vh, lg.alloc_workspace(T))
+        sync()
+        outs.append((lo, lg, kc, ks, Kh, Kp, K, V, Vp, vc, vs, Vh))
+        Kp, Vp = Kh, Vh
+    q = synth.random_queries(batch, QH, 128, seed=9, dtype="bf16", device="cuda")
+    for l, (lo, lg, kc, ks, Kh, Kprev, K, V, Vprev, vc, vs, Vh) in enumerate(outs):
+        scores = torch.empty(batch, QH, S, dtype=torch.float32, device="cuda")
+        B.aquakv_decode_attn_scores(lg, batch, S, QH, kc, ks, Kprev, q, 0.0883883, scores, None, lg.alloc_workspace(T))
+        sync()
+        rng = np.random.Generator(np.random.PCG64(17 + l))
+        for b in (0, 3, batch - 1):
+            ts = np.unique(np.concatenate([[0, 255, 256, S - 1], rng.choice(S, 40, replace=False)]))
+            sel = torch.from_numpy(b * S + ts).cuda()
+            kp = None if Kprev is None else U.np64(Kprev[sel])
+            want = O.attn_scores(lo, 1, len(ts), U.np64(q[b:b + 1]), kc[sel].cpu().numpy(),
+                                 ks[sel].cpu().numpy().view(np.float16), kp, 0.0883883)[0]
+            got = U.np64(scores[b][:, torch.from_numpy(ts).cuda()])
+            Ka = np.abs(U.np64(Kh[sel])).reshape(len(ts), H, 128)
+            mag = np.stack([np.abs(U.np64(q[b, qh])) @ Ka[:, qh // (QH // H)].T for qh in range(QH)], 0)
+            err = np.abs(got - want)
+            assert np.all(err <= U.RTOL["bf16"] * 0.0883883 * mag + 1e-30)
+            print(f"   layer {l} seq {b}: worst score error / sum|q||k| = "
+                  f"{float(np.max(err / (0.0883883 * mag + 1e-30))):.2e}", flush=True)
+    # append: one new token per sequence = an encode call with tokens = batch; it must give the
+    # same bytes as the rows had inside the big call (row-count independence of the predictor)
+    lo, lg, kc, ks, Kh, Kprev, K, V, Vprev, vc, vs, Vh = outs[1]
+    new = torch.arange(batch, device="cuda") * S + (S - 1)
+    cut = lambda t: t[new].contiguous()
+    kc2, ks2 = lg.alloc_codes(batch)
+    vc2, vs2 = lg.alloc_codes(batch)
+    Kh2, Vh2 = lg.alloc_kv(batch), lg.alloc_kv(batch)
+    B.aquakv_encode_layer(lg, batch, cut(K), cut(V), cut(Kprev), cut(Vprev), kc2, ks2, vc2, vs2, Kh2, Vh2,
+                          lg.alloc_workspace(batch))
+    sync()
+    assert torch.equal(kc2, cut(kc)) and torch.equal(ks2, cut(ks)) and torch.equal(vc2, cut(vc))
+    assert torch.equal(bits(Kh2), bits(cut(Kh))) and torch.equal(bits(Vh2), bits(cut(Vh)))
