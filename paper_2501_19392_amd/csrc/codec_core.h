@@ -78,34 +78,41 @@ __device__ __forceinline__ int search_cell(float y0, float y1, const float4* cb,
 }
 
 // Full search for the sub-vectors of this lane whose bit is set in `mask` (grid points in the
-// outer, rolled loop so that the code stays small).
+// outer, rolled loop and 8 sub-vectors at a time, so that code and live registers stay small).
 template <int NCW>
 __device__ __forceinline__ void search_full_masked(const float (&v)[32], float inv, const float4* cb, uint32_t mask,
-                                                int (&idx)[16]) {
-  float best[16];
-  int bi[16];
-  {
+                                                   int (&idx)[16]) {
+#pragma unroll 1
+  for (int half = 0; half < 2; ++half) {
+    float y[16], best[8];
+    int bi[8];
     const float4 c0 = cb[0];
 #pragma unroll
-    for (int m = 0; m < 16; ++m) {
-      best[m] = score(v[2 * m] * inv, v[2 * m + 1] * inv, c0);
+    for (int m = 0; m < 8; ++m) {
+      // select this half's values without dynamic register indexing
+      y[2 * m] = (half ? v[16 + 2 * m] : v[2 * m]) * inv;
+      y[2 * m + 1] = (half ? v[16 + 2 * m + 1] : v[2 * m + 1]) * inv;
+      best[m] = score(y[2 * m], y[2 * m + 1], c0);
       bi[m] = 0;
     }
-  }
 #pragma unroll 1
-  for (int j = 1; j < NCW; ++j) {
-    const float4 cj = cb[j];
+    for (int j = 1; j < NCW; ++j) {
+      const float4 cj = cb[j];
 #pragma unroll
-    for (int m = 0; m < 16; ++m) {
-      const float s = score(v[2 * m] * inv, v[2 * m + 1] * inv, cj);
-      const bool better = s > best[m];
-      best[m] = better ? s : best[m];
-      bi[m] = better ? j : bi[m];
+      for (int m = 0; m < 8; ++m) {
+        const float s = score(y[2 * m], y[2 * m + 1], cj);
+        const bool better = s > best[m];
+        best[m] = better ? s : best[m];
+        bi[m] = better ? j : bi[m];
+      }
+    }
+#pragma unroll
+    for (int m = 0; m < 8; ++m) {
+      const bool take = (mask >> (8 * half + m)) & 1;
+      if (half) idx[8 + m] = take ? bi[m] : idx[8 + m];
+      else idx[m] = take ? bi[m] : idx[m];
     }
   }
-#pragma unroll
-  for (int m = 0; m < 16; ++m)
-    if ((mask >> m) & 1) idx[m] = bi[m];
 }
 
 // 16 codes of c bits per lane = 4c contiguous bytes of the group's little-endian bit string.
@@ -247,7 +254,8 @@ __device__ __forceinline__ void quantize_group(float (&v)[32], const float (&p)[
       search_full_masked<NCW>(v, inv, cb, crowded_mask, idx);
   } else {
 #pragma unroll
-    for (int m = 0; m < 16; ++m) idx[m] = search_full<NCW>(v[2 * m] * inv, v[2 * m + 1] * inv, cb);
+    for (int m = 0; m < 16; ++m) idx[m] = 0;
+    search_full_masked<NCW>(v, inv, cb, 0xffffu, idx);      // the definition: scan all n points
   }
   if (active) {
     store_codes<NCW>(codes, gid, q, idx);

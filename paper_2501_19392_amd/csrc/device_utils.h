@@ -60,10 +60,11 @@ template <> struct Storage<bf16_t> {
     }
   }
   static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
-    const bf16_t a = static_cast<bf16_t>(lo);   // round to nearest even
-    const bf16_t b = static_cast<bf16_t>(hi);
-    return static_cast<uint32_t>(__builtin_bit_cast(uint16_t, a)) |
-           (static_cast<uint32_t>(__builtin_bit_cast(uint16_t, b)) << 16);
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    f32x2_t f;
+    f.x = lo; f.y = hi;
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));   // one packed RNE convert
   }
   static __device__ __forceinline__ void store32(bf16_t* p, const float (&v)[32]) {
 #pragma unroll

@@ -73,9 +73,8 @@ __global__ __launch_bounds__(kGemmThreads) void fused_kernel(
   }
   __syncthreads();
 
-  // Epilogue: 4 passes of 16 groups per wave, one group per quad.  The loop is kept rolled (the
-  // body is large and the instruction cache is shared); the global inputs of pass p+1 are
-  // requested before pass p is worked on, since one wave per SIMD hides no load latency.
+  // Epilogue: 4 passes of 16 groups per wave, one group per quad; all global inputs are
+  // requested up front, since one wave per SIMD hides no load latency.
   const int q = lane & 3;
   uint32_t sb[32];
   load_sign_bits(signs, head, q, sb);
@@ -102,12 +101,8 @@ __global__ __launch_bounds__(kGemmThreads) void fused_kernel(
       in.scale = scales[gid];
     }
   };
-  In cur, next;
-  fetch(0, next);
-#pragma unroll 1
-  for (int pass = 0; pass < 4; ++pass) {
-    cur = next;
-    if (pass < 3) fetch(pass + 1, next);
+  // one pass: 16 groups of this wave (rows pass*16 .. +15), inputs already in `in`
+  const auto do_pass = [&](int pass, const In& in) {
     const int lrow = pass * 16 + (lane >> 2);
     const int64_t row = m0 + wave * 64 + lrow;
     const bool active = row < T;
@@ -125,14 +120,14 @@ __global__ __launch_bounds__(kGemmThreads) void fused_kernel(
     }
     if constexpr (MODE == kEncode) {
 #pragma unroll
-      for (int k = 0; k < 4; ++k) unpack_bf16x8(cur.x[k], &v[8 * k]);
+      for (int k = 0; k < 4; ++k) unpack_bf16x8(in.x[k], &v[8 * k]);
       quantize_group<NCW>(v, p, sb, q, cl.cb, use_table ? cl.table : nullptr, active, gid, codes, scales,
                           Xhat != nullptr);
       if (Xhat != nullptr && active) Storage<bf16_t>::store32(Xhat + off, v);
     } else {
       int idx[16];
-      unpack_codes<NCW>(cur.code, idx);
-      gather_zhat(idx, half_bits_to_float(cur.scale), cl.cb, v);
+      unpack_codes<NCW>(in.code, idx);
+      gather_zhat(idx, half_bits_to_float(in.scale), cl.cb, v);
       reconstruct(v, q, sb, p);
       if (Xhat != nullptr && active) Storage<bf16_t>::store32(Xhat + off, v);
       if constexpr (MODE == kScores) {
@@ -152,7 +147,19 @@ __global__ __launch_bounds__(kGemmThreads) void fused_kernel(
         }
       }
     }
-  }
+  };
+  // two passes per iteration: their instruction streams are independent, which gives the
+  // scheduler something to fill LDS / DPP latencies with (there is no second wave to do it)
+  In a0, a1, b0, b1;
+  fetch(0, a0);
+  fetch(1, a1);
+  fetch(2, b0);
+  fetch(3, b1);
+  do_pass(0, a0);
+  do_pass(1, a1);
+  __builtin_amdgcn_sched_barrier(0);
+  do_pass(2, b0);
+  do_pass(3, b1);
 }
 
 template <int MODE>
