@@ -52,32 +52,60 @@ __device__ __forceinline__ void gemm_mainloop(unsigned char* lds_base, const bf1
   const int nk = K / BK;
 
   // Software pipeline (one block per CU, one wave per SIMD, so the overlap has to be built
-  // into the instruction stream).  For k-tile t, living in LDS stage t&1:
-  //   barrier B_t                       -- tile t is completely in LDS, stage (t+1)&1 is free
-  //   fragment reads (t, step 0)
-  //   8 MFMAs of (t-1, step 3)          + the 12 LDS writes of tile t+1 into stage (t+1)&1
-  //   8 MFMAs of (t, step 0)            + fragment reads (t, 1) + the 12 global loads of tile t+3
-  //   8 MFMAs of (t, step 1)            + fragment reads (t, 2)
-  //   8 MFMAs of (t, step 2)            + fragment reads (t, 3)
-  // Every memory instruction is issued in the shadow of an MFMA, the matrix pipe runs across
-  // the barrier, and a global load has two iterations to land (two register sets).
+  // into the instruction stream).  k-tile t lives in LDS stage t&1 and is multiplied in four
+  // steps of 16 k (8 MFMAs each).  Between barrier B_t (tile t complete in LDS) and B_{t+1}:
+  //   8 MFMAs (t-1, step 2)   + fragment reads (t, 0)   + 6 LDS writes of tile t+1
+  //   8 MFMAs (t-1, step 3)   + fragment reads (t, 1)   + 6 LDS writes of tile t+1
+  //   8 MFMAs (t,   step 0)   + fragment reads (t, 2)   + 6 global loads of tile t+3
+  //   8 MFMAs (t,   step 1)   + fragment reads (t, 3)   + 6 global loads of tile t+3
+  // At most two memory instructions sit in the shadow of one MFMA, every fragment is requested
+  // at least 8 MFMAs before its use, the matrix pipe keeps running across the barrier, and a
+  // global load has two iterations to land (two register sets, one fragment buffer per step).
+  // Loads use a scalar base (advanced per k-tile) plus a per-thread byte offset, so that no
+  // 64-bit vector address arithmetic is left in the loop.
   // sched_barrier(0) after each MFMA keeps the compiler from regrouping the stream.
   struct Regs { u32x4 v[kAChunks + kBChunks]; };
   struct Frag { bf16x8 v[6]; };      // a[0], a[1], b[0..3]
+  constexpr int kPieces = kAChunks + kBChunks;   // 12
 
+  const int ch16 = (tid & 7) * 16;                         // byte offset of this thread's chunk in a tile row
+  int rowc[kAChunks];                                      // tile-local x row of piece pc, clamped to the last valid row
+  uint32_t offB[kBChunks];                                 // byte offset of piece pc in W relative to (n0, k0)
+  {
+    const int last = (int)((T - 1 - m0) < (BM - 1) ? (T - 1 - m0) : (BM - 1));
+#pragma unroll
+    for (int pc = 0; pc < kAChunks; ++pc) {
+      const int row = (tid >> 3) + pc * (kGemmThreads / 8);
+      rowc[pc] = row < last ? row : last;
+    }
+#pragma unroll
+    for (int pc = 0; pc < kBChunks; ++pc)
+      offB[pc] = (uint32_t)((tid >> 3) + pc * (kGemmThreads / 8)) * (uint32_t)(K * 2) + ch16;
+  }
+  const char* const wbase = reinterpret_cast<const char*>(W) + (int64_t)n0 * K * 2;
+
+  // wave-uniform values are pinned to scalar registers so that the loads take the
+  // "scalar base + 32-bit vector offset" form
+  typedef const __attribute__((address_space(1))) char* gptr_t;          // global address space
+  typedef const __attribute__((address_space(1))) u32x4* gvec_t;
+  const auto uniform_ptr = [](const char* p) {
+    const uint64_t u = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
+    return (gptr_t)(((uint64_t)hi << 32) | lo);
+  };
   auto load_piece = [&](int kt, Regs& r, int pc) {         // piece pc of tile kt: global -> registers
     const int k0 = kt * BK;
-    const int id = tid + (pc < kAChunks ? pc : pc - kAChunks) * kGemmThreads;
-    const int row = id >> 3, ch = id & 7;
     if (pc < kAChunks) {
-      const bf16_t* xa;
-      int ld, kk;
-      if (k0 < d0) { xa = x0; ld = d0; kk = k0; } else { xa = x1; ld = d1; kk = k0 - d0; }
-      int64_t gr = m0 + row;
-      gr = gr < T ? gr : T - 1;
-      r.v[pc] = *reinterpret_cast<const u32x4*>(xa + gr * ld + kk + ch * 8);
+      const bool second = k0 >= d0;                        // which K-panel of the concatenated input
+      const int ld2 = __builtin_amdgcn_readfirstlane((second ? d1 : d0) * 2);
+      const gptr_t base = uniform_ptr(reinterpret_cast<const char*>(second ? x1 : x0) +
+                                      (m0 * ld2 + (int64_t)(second ? k0 - d0 : k0) * 2));
+      const uint32_t off = (uint32_t)__umul24(rowc[pc], ld2) + ch16;
+      r.v[pc] = *(gvec_t)(base + off);
     } else {
-      r.v[pc] = *reinterpret_cast<const u32x4*>(W + (int64_t)(n0 + row) * K + k0 + ch * 8);
+      const gptr_t base = uniform_ptr(wbase + (int64_t)k0 * 2);
+      r.v[pc] = *(gvec_t)(base + offB[pc - kAChunks]);
     }
   };
   auto store_piece = [&](int stage, const Regs& r, int pc) {   // registers -> LDS
@@ -112,8 +140,7 @@ __device__ __forceinline__ void gemm_mainloop(unsigned char* lds_base, const bf1
   };
 
   Regs rs[2];
-  Frag f0, f1, carry;
-  constexpr int kPieces = kAChunks + kBChunks;   // 12
+  Frag f[4];                                               // one buffer per step of a tile
 #pragma unroll
   for (int pc = 0; pc < kPieces; ++pc) load_piece(0, rs[0], pc);
 #pragma unroll
@@ -125,33 +152,43 @@ __device__ __forceinline__ void gemm_mainloop(unsigned char* lds_base, const bf1
     if (nk > 2) load_piece(2, rs[0], pc);
   __syncthreads();                                                      // B_0
 
-  // iteration t; `first`: no (t-1, 3) to finish; write/load flags for the drain
+  // iteration t (see the table above); rw holds tile t+1 and then receives tile t+3
   auto iteration = [&](int t, Regs& rw, bool first, bool do_store, bool do_load) {
     const int stage = t & 1;
-#pragma unroll
-    for (int pc = 0; pc < 6; ++pc) frag_piece(stage, 0, f0, pc);
-    __builtin_amdgcn_sched_barrier(0);
     if (!first) {
-      mma8(carry, [&](int m) {
-        if (do_store) {
-          if (m < 4) { store_piece(stage ^ 1, rw, 2 * m); store_piece(stage ^ 1, rw, 2 * m + 1); }
-          else store_piece(stage ^ 1, rw, 4 + m);
+      mma8(f[2], [&](int m) {
+        if (m < 6) {
+          frag_piece(stage, 0, f[0], m);
+          if (do_store) store_piece(stage ^ 1, rw, m);
         }
       });
-    } else if (do_store) {
+      mma8(f[3], [&](int m) {
+        if (m < 6) {
+          frag_piece(stage, 1, f[1], m);
+          if (do_store) store_piece(stage ^ 1, rw, 6 + m);
+        }
+      });
+    } else {
 #pragma unroll
-      for (int pc = 0; pc < kPieces; ++pc) store_piece(stage ^ 1, rw, pc);
+      for (int pc = 0; pc < 6; ++pc) { frag_piece(stage, 0, f[0], pc); frag_piece(stage, 1, f[1], pc); }
+      if (do_store) {
+#pragma unroll
+        for (int pc = 0; pc < kPieces; ++pc) store_piece(stage ^ 1, rw, pc);
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
-    mma8(f0, [&](int m) {
-      if (m < 6) frag_piece(stage, 1, f1, m);
-      if (do_load) {
-        if (m < 4) { load_piece(t + 3, rw, 2 * m); load_piece(t + 3, rw, 2 * m + 1); }
-        else load_piece(t + 3, rw, 4 + m);
+    mma8(f[0], [&](int m) {
+      if (m < 6) {
+        frag_piece(stage, 2, f[2], m);
+        if (do_load) load_piece(t + 3, rw, m);
       }
     });
-    mma8(f1, [&](int m) { if (m < 6) frag_piece(stage, 2, f0, m); });
-    mma8(f0, [&](int m) { if (m < 6) frag_piece(stage, 3, carry, m); });
+    mma8(f[1], [&](int m) {
+      if (m < 6) {
+        frag_piece(stage, 3, f[3], m);
+        if (do_load) load_piece(t + 3, rw, 6 + m);
+      }
+    });
     __syncthreads();                                                    // B_{t+1}
   };
 
@@ -167,8 +204,8 @@ __device__ __forceinline__ void gemm_mainloop(unsigned char* lds_base, const bf1
     iteration(nk - 2, rs[1], false, true, false);
   }
   iteration(nk - 1, rs[0], false, false, false);
-  mma8(carry, [&](int) {});                          // (nk-1, step 3)
-
+  mma8(f[2], [&](int) {});                           // (nk-1, steps 2 and 3)
+  mma8(f[3], [&](int) {});
 }
 
 }  // namespace aquakv
