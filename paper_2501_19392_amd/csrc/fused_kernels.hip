@@ -2,7 +2,7 @@
 //
 // Alg. "encode" / "decode" of the AQUA-KV paper apply the linear predictor of Sect. 3.2 and
 // then the backbone quantizer of Sect. 2 (or its inverse) to the same rows.  One workgroup
-// computes a 256-row x 128-column tile of the prediction on the matrix cores -- 128 columns
+// (8 wavefronts) computes a 256-row x 128-column tile of the prediction on the matrix cores -- 128 columns
 // are exactly one kv head = one rotation group per row -- parks it in LDS in fp32, and runs
 // the quantizer (encode), its inverse (decode), or its inverse plus the grouped-query q.k
 // dot products (scores) on those 256 groups as the epilogue.  Against separate kernels this
@@ -18,16 +18,15 @@ namespace aquakv {
 namespace {
 
 constexpr int kLdP = BN + 4;                        // padded fp32 row of the parked prediction tile
-constexpr int kWaveTileBytes = 64 * kLdP * 4;       // one wave's 64 rows
-constexpr int kPredBytes = 4 * kWaveTileBytes;      // 135168: reuses (and exceeds) the main loop's 2 stages
+constexpr int kPredBytes = BM * kLdP * 4;           // 135168: reuses (and exceeds) the main loop's 2 stages
 constexpr int kFusedLdsBytes = kPredBytes + (int)sizeof(Lds);
 static_assert(kPredBytes >= 2 * kStageBytes, "prediction tile must cover the main-loop stages");
 static_assert(kFusedLdsBytes <= 160 * 1024, "LDS of one CU");
 
 enum Mode : int { kEncode = 0, kDecode = 1, kScores = 2 };
 
-template <int NCW, int MODE>
-__global__ __launch_bounds__(kGemmThreads) void fused_kernel(
+template <int NCW, int MODE, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void fused_kernel(
     const bf16_t* __restrict__ x0, int d0, const bf16_t* __restrict__ x1, int d1, const bf16_t* __restrict__ W,
     const float* __restrict__ bias, const int8_t* __restrict__ signs, const float* __restrict__ codebook,
     const uint32_t* __restrict__ table, const bf16_t* X, uint8_t* codes, uint16_t* scales, bf16_t* Xhat,
@@ -40,7 +39,7 @@ __global__ __launch_bounds__(kGemmThreads) void fused_kernel(
   if (use_table) {
     const u32x4* src = reinterpret_cast<const u32x4*>(table);
     u32x4* dst = reinterpret_cast<u32x4*>(cl.table);
-    for (int i = threadIdx.x; i < kCells * kCells / 4; i += kGemmThreads) dst[i] = src[i];
+    for (int i = threadIdx.x; i < kCells * kCells / 4; i += WAVES * 64) dst[i] = src[i];
   }
 
   const int lane = threadIdx.x & 63;
@@ -51,11 +50,13 @@ __global__ __launch_bounds__(kGemmThreads) void fused_kernel(
   const int64_t m0 = (int64_t)tile_m * BM;
   const int n0 = head * BN;
 
-  f32x16 acc[2][4];
-  gemm_mainloop(smem, x0, d0, x1, d1, W, T, m0, n0, acc);
+  constexpr int MI = BM / WAVES / 32;              // 32-row blocks per wave
+  constexpr int kRowsPerWave = MI * 32;
+  f32x16 acc[MI][4];
+  gemm_mainloop<WAVES>(smem, x0, d0, x1, d1, W, T, m0, n0, acc);
 
   // park the tile (+ bias) in LDS, row-major fp32, each wave its own 64 rows
-  float* wl = reinterpret_cast<float*>(smem) + wave * 64 * kLdP;
+  float* wl = reinterpret_cast<float*>(smem) + wave * kRowsPerWave * kLdP;
   {
     const int frow = lane & 31, fk = lane >> 5;
 #pragma unroll
@@ -63,7 +64,7 @@ __global__ __launch_bounds__(kGemmThreads) void fused_kernel(
       const int col = j * 32 + frow;
       const float bv = bias != nullptr ? bias[n0 + col] : 0.f;
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int lrow = i * 32 + (r >> 2) * 8 + fk * 4 + (r & 3);
@@ -73,15 +74,15 @@ __global__ __launch_bounds__(kGemmThreads) void fused_kernel(
   }
   __syncthreads();
 
-  // Epilogue: 4 passes of 16 groups per wave, one group per quad; all global inputs are
-  // requested up front, since one wave per SIMD hides no load latency.
+  // Epilogue: passes of 16 groups per wave, one group per quad; all global inputs are
+  // requested up front.
   const int q = lane & 3;
   uint32_t sb[32];
   load_sign_bits(signs, head, q, sb);
   constexpr int c = CodeBits<NCW>::c;
   struct In { u32x4 x[4]; u32x4 code; uint16_t scale; };
   const auto fetch = [&](int pass, In& in) {
-    int64_t row = m0 + wave * 64 + pass * 16 + (lane >> 2);
+    int64_t row = m0 + wave * kRowsPerWave + pass * 16 + (lane >> 2);
     row = row < T ? row : T - 1;
     if constexpr (MODE == kEncode) {
       const u32x4* src = reinterpret_cast<const u32x4*>(X + row * D + n0 + q * kValsPerLane);
@@ -104,7 +105,7 @@ __global__ __launch_bounds__(kGemmThreads) void fused_kernel(
   // one pass: 16 groups of this wave (rows pass*16 .. +15), inputs already in `in`
   const auto do_pass = [&](int pass, const In& in) {
     const int lrow = pass * 16 + (lane >> 2);
-    const int64_t row = m0 + wave * 64 + lrow;
+    const int64_t row = m0 + wave * kRowsPerWave + lrow;
     const bool active = row < T;
     const int64_t rowc = active ? row : T - 1;
     const int64_t gid = rowc * H + head;
@@ -148,18 +149,16 @@ __global__ __launch_bounds__(kGemmThreads) void fused_kernel(
       }
     }
   };
-  // two passes per iteration: their instruction streams are independent, which gives the
-  // scheduler something to fill LDS / DPP latencies with (there is no second wave to do it)
-  In a0, a1, b0, b1;
-  fetch(0, a0);
-  fetch(1, a1);
-  fetch(2, b0);
-  fetch(3, b1);
-  do_pass(0, a0);
-  do_pass(1, a1);
-  __builtin_amdgcn_sched_barrier(0);
-  do_pass(2, b0);
-  do_pass(3, b1);
+  // kRowsPerWave / 16 passes; all inputs are requested first
+  constexpr int kPasses = kRowsPerWave / 16;
+  In in[kPasses];
+#pragma unroll
+  for (int pass = 0; pass < kPasses; ++pass) fetch(pass, in[pass]);
+#pragma unroll
+  for (int pass = 0; pass < kPasses; ++pass) {
+    do_pass(pass, in[pass]);
+    __builtin_amdgcn_sched_barrier(0);
+  }
 }
 
 template <int MODE>
@@ -169,8 +168,12 @@ hipError_t launch(int n_codewords, const void* x0, int d0, const void* x1, int d
                   int q_heads, int64_t T, int D, hipStream_t stream) {
   if (T == 0) return hipSuccess;
   const unsigned blocks = (unsigned)(((T + BM - 1) / BM) * (D / BN));
+  // 8 wavefronts per tile (two per SIMD): the main loop is bound by L2 -> LDS traffic either
+  // way, and the second wave fills the issue slots the first leaves in the VALU-heavy epilogue
+  // (measured: encode 10 % faster than with 4 wavefronts, decode unchanged).
+  constexpr int kWaves = 8;
 #define AQUAKV_FUSED(N)                                                                                          \
-  fused_kernel<N, MODE><<<blocks, kGemmThreads, 0, stream>>>(                                                    \
+  fused_kernel<N, MODE, kWaves><<<blocks, kWaves * 64, 0, stream>>>(                                             \
       static_cast<const bf16_t*>(x0), d0, static_cast<const bf16_t*>(x1), d1, static_cast<const bf16_t*>(W), bias, \
       signs, codebook, static_cast<const uint32_t*>(table), static_cast<const bf16_t*>(X), codes, scales,         \
       static_cast<bf16_t*>(Xhat), static_cast<const bf16_t*>(q), score_scale, scores, seq_len, q_heads, T, D)

@@ -14,14 +14,15 @@ namespace aquakv {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
-constexpr int BM = 256, BN = 128, BK = 64;       // block tile; 4 waves stacked in M, wave tile 64 x 128
-constexpr int kGemmThreads = 256;
+constexpr int BM = 256, BN = 128, BK = 64;       // block tile; the waves are stacked in M
 constexpr int kRowBytes = BK * 2;                // 128 B of bf16 per LDS row
 constexpr int kATileBytes = BM * kRowBytes;      // 32 KiB
 constexpr int kBTileBytes = BN * kRowBytes;      // 16 KiB
 constexpr int kStageBytes = kATileBytes + kBTileBytes;
-constexpr int kAChunks = BM * 8 / kGemmThreads;  // 16-byte chunks per thread and k-tile (8)
-constexpr int kBChunks = BN * 8 / kGemmThreads;  // (4)
+// The tile is worked on by WAVES = 4 or 8 wavefronts (one or two per SIMD); wave w owns rows
+// (256 / WAVES) * w ... of the tile and all 128 columns.  Both shapes run the same MFMAs in the
+// same K order per output element, so they give identical bits.
+constexpr int kGemmThreads = 256;                // the 4-wave shape (stand-alone predictor kernel)
 
 // 16-byte chunk `ch` (0..7) of LDS row `row`, XOR-swizzled so that the 32 lanes
 // of a fragment read (32 consecutive rows, same chunk) spread over all banks.
@@ -36,14 +37,22 @@ __device__ __forceinline__ int remap_block(int bid, int nblocks) {
   return (bid % kXcd) * (nblocks / kXcd) + bid / kXcd;
 }
 
-// The workgroup's accumulator tile: wave w owns rows 64w .. 64w+63 of the 256, all 128 columns;
-// acc[i][j] is the 32 x 32 block at rows 32i, columns 32j; inside it the lane holds column
-// lane%32 and rows 8*blk + 4*(lane/32) + r4 in register 4*blk + r4.
+// The workgroup's accumulator tile: wave w owns rows (256/WAVES)*w ... of the 256, all 128 columns;
+// acc[i][j] is the 32 x 32 block at rows 32i, columns 32j of the wave's rows; inside it the lane
+// holds column lane%32 and rows 8*blk + 4*(lane/32) + r4 in register 4*blk + r4.
 // `lds_base` points at 2 * kStageBytes bytes of LDS.  Ends with a barrier after the last LDS read,
 // so the caller may reuse the LDS at once.  Requires K = d0 + d1 a multiple of 128, d0 of 64.
+template <int WAVES>
 __device__ __forceinline__ void gemm_mainloop(unsigned char* lds_base, const bf16_t* __restrict__ x0, int d0,
                                               const bf16_t* __restrict__ x1, int d1, const bf16_t* __restrict__ W,
-                                              int64_t T, int64_t m0, int n0, f32x16 (&acc)[2][4]) {
+                                              int64_t T, int64_t m0, int n0, f32x16 (&acc)[BM / WAVES / 32][4]) {
+  static_assert(WAVES == 4 || WAVES == 8, "one or two waves per SIMD");
+  constexpr int kThreadsW = WAVES * 64;
+  constexpr int MI = BM / WAVES / 32;              // 32-row blocks per wave (2 or 1)
+  constexpr int kAChunks = BM * 8 / kThreadsW;     // 16-byte chunks per thread and k-tile (8 or 4)
+  constexpr int kBChunks = BN * 8 / kThreadsW;     // (4 or 2)
+  constexpr int kFragPieces = MI + 4;              // a[0..MI), b[0..4)
+  constexpr int kMma = MI * 4;                     // MFMAs per step of 16 k
   unsigned char (*lds)[kStageBytes] = reinterpret_cast<unsigned char (*)[kStageBytes]>(lds_base);
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -51,13 +60,14 @@ __device__ __forceinline__ void gemm_mainloop(unsigned char* lds_base, const bf1
   const int K = d0 + d1;
   const int nk = K / BK;
 
-  // Software pipeline (one block per CU, one wave per SIMD, so the overlap has to be built
-  // into the instruction stream).  k-tile t lives in LDS stage t&1 and is multiplied in four
+  // Software pipeline (one block per CU and at most two waves per SIMD, so the overlap has to
+  // be built into the instruction stream).  k-tile t lives in LDS stage t&1 and is multiplied in four
   // steps of 16 k (8 MFMAs each).  Between barrier B_t (tile t complete in LDS) and B_{t+1}:
-  //   8 MFMAs (t-1, step 2)   + fragment reads (t, 0)   + 6 LDS writes of tile t+1
-  //   8 MFMAs (t-1, step 3)   + fragment reads (t, 1)   + 6 LDS writes of tile t+1
-  //   8 MFMAs (t,   step 0)   + fragment reads (t, 2)   + 6 global loads of tile t+3
-  //   8 MFMAs (t,   step 1)   + fragment reads (t, 3)   + 6 global loads of tile t+3
+  //   MFMAs (t-1, step 2)   + fragment reads (t, 0)   + half of the LDS writes of tile t+1
+  //   MFMAs (t-1, step 3)   + fragment reads (t, 1)   + the other half
+  //   MFMAs (t,   step 0)   + fragment reads (t, 2)   + half of the global loads of tile t+3
+  //   MFMAs (t,   step 1)   + fragment reads (t, 3)   + the other half
+  // (8 MFMAs per step and wave with 4 waves, 4 with 8 waves.)
   // At most two memory instructions sit in the shadow of one MFMA, every fragment is requested
   // at least 8 MFMAs before its use, the matrix pipe keeps running across the barrier, and a
   // global load has two iterations to land (two register sets, one fragment buffer per step).
@@ -65,8 +75,8 @@ __device__ __forceinline__ void gemm_mainloop(unsigned char* lds_base, const bf1
   // 64-bit vector address arithmetic is left in the loop.
   // sched_barrier(0) after each MFMA keeps the compiler from regrouping the stream.
   struct Regs { u32x4 v[kAChunks + kBChunks]; };
-  struct Frag { bf16x8 v[6]; };      // a[0], a[1], b[0..3]
-  constexpr int kPieces = kAChunks + kBChunks;   // 12
+  struct Frag { bf16x8 v[kFragPieces]; };
+  constexpr int kPieces = kAChunks + kBChunks;   // 12 or 6
 
   const int ch16 = (tid & 7) * 16;                         // byte offset of this thread's chunk in a tile row
   int rowc[kAChunks];                                      // tile-local x row of piece pc, clamped to the last valid row
@@ -75,12 +85,12 @@ __device__ __forceinline__ void gemm_mainloop(unsigned char* lds_base, const bf1
     const int last = (int)((T - 1 - m0) < (BM - 1) ? (T - 1 - m0) : (BM - 1));
 #pragma unroll
     for (int pc = 0; pc < kAChunks; ++pc) {
-      const int row = (tid >> 3) + pc * (kGemmThreads / 8);
+      const int row = (tid >> 3) + pc * (kThreadsW / 8);
       rowc[pc] = row < last ? row : last;
     }
 #pragma unroll
     for (int pc = 0; pc < kBChunks; ++pc)
-      offB[pc] = (uint32_t)((tid >> 3) + pc * (kGemmThreads / 8)) * (uint32_t)(K * 2) + ch16;
+      offB[pc] = (uint32_t)((tid >> 3) + pc * (kThreadsW / 8)) * (uint32_t)(K * 2) + ch16;
   }
   const char* const wbase = reinterpret_cast<const char*>(W) + (int64_t)n0 * K * 2;
 
@@ -109,34 +119,40 @@ __device__ __forceinline__ void gemm_mainloop(unsigned char* lds_base, const bf1
     }
   };
   auto store_piece = [&](int stage, const Regs& r, int pc) {   // registers -> LDS
-    const int id = tid + (pc < kAChunks ? pc : pc - kAChunks) * kGemmThreads;
+    const int id = tid + (pc < kAChunks ? pc : pc - kAChunks) * kThreadsW;
     const int base = pc < kAChunks ? 0 : kATileBytes;
     *reinterpret_cast<u32x4*>(&lds[stage][base + lds_off(id >> 3, id & 7)]) = r.v[pc];
   };
   const int frow = lane & 31;       // row (A) / column (B) inside a 32-wide fragment
   const int fk = lane >> 5;         // which half of the 16 k values
   auto frag_piece = [&](int stage, int ks, Frag& f, int pc) {  // LDS -> MFMA operand registers
-    const int off = pc < 2 ? lds_off(wave * 64 + pc * 32 + frow, ks * 2 + fk)
-                           : kATileBytes + lds_off((pc - 2) * 32 + frow, ks * 2 + fk);
+    const int off = pc < MI ? lds_off(wave * (MI * 32) + pc * 32 + frow, ks * 2 + fk)
+                            : kATileBytes + lds_off((pc - MI) * 32 + frow, ks * 2 + fk);
     f.v[pc] = *reinterpret_cast<const bf16x8*>(&lds[stage][off]);
   };
 
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // 8 MFMAs on fragment f; extra(m) is issued right after MFMA m
+  // the MFMAs of one step on fragment f; extra(m) is issued right after MFMA m
   auto mma8 = [&](const Frag& f, auto&& extra) {
 #pragma unroll
-    for (int m = 0; m < 8; ++m) {
+    for (int m = 0; m < kMma; ++m) {
       const int i = m >> 2, j = m & 3;
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.v[i], f.v[2 + j], acc[i][j], 0, 0, 0);
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.v[i], f.v[MI + j], acc[i][j], 0, 0, 0);
       extra(m);
       __builtin_amdgcn_sched_barrier(0);
     }
+  };
+  // memory work attached to MFMA slot m of a step: the step's share of a list of n items is
+  // spread two per slot from slot 0 on (n <= 2 * kMma)
+  auto spread = [&](int m, int n, auto&& item) {
+    if (2 * m < n) item(2 * m);
+    if (2 * m + 1 < n) item(2 * m + 1);
   };
 
   Regs rs[2];
@@ -152,25 +168,27 @@ __device__ __forceinline__ void gemm_mainloop(unsigned char* lds_base, const bf1
     if (nk > 2) load_piece(2, rs[0], pc);
   __syncthreads();                                                      // B_0
 
-  // iteration t (see the table above); rw holds tile t+1 and then receives tile t+3
+  // iteration t (see the table above); rw holds tile t+1 and then receives tile t+3.
+  // Per step: the fragment pieces of a later step, plus half of the tile's LDS writes or loads.
+  constexpr int kHalf = kPieces / 2;
   auto iteration = [&](int t, Regs& rw, bool first, bool do_store, bool do_load) {
     const int stage = t & 1;
     if (!first) {
       mma8(f[2], [&](int m) {
-        if (m < 6) {
-          frag_piece(stage, 0, f[0], m);
-          if (do_store) store_piece(stage ^ 1, rw, m);
-        }
+        spread(m, kFragPieces + kHalf, [&](int e) {
+          if (e < kFragPieces) frag_piece(stage, 0, f[0], e);
+          else if (do_store) store_piece(stage ^ 1, rw, e - kFragPieces);
+        });
       });
       mma8(f[3], [&](int m) {
-        if (m < 6) {
-          frag_piece(stage, 1, f[1], m);
-          if (do_store) store_piece(stage ^ 1, rw, 6 + m);
-        }
+        spread(m, kFragPieces + kHalf, [&](int e) {
+          if (e < kFragPieces) frag_piece(stage, 1, f[1], e);
+          else if (do_store) store_piece(stage ^ 1, rw, kHalf + e - kFragPieces);
+        });
       });
     } else {
 #pragma unroll
-      for (int pc = 0; pc < 6; ++pc) { frag_piece(stage, 0, f[0], pc); frag_piece(stage, 1, f[1], pc); }
+      for (int pc = 0; pc < kFragPieces; ++pc) { frag_piece(stage, 0, f[0], pc); frag_piece(stage, 1, f[1], pc); }
       if (do_store) {
 #pragma unroll
         for (int pc = 0; pc < kPieces; ++pc) store_piece(stage ^ 1, rw, pc);
@@ -178,16 +196,16 @@ __device__ __forceinline__ void gemm_mainloop(unsigned char* lds_base, const bf1
       __builtin_amdgcn_sched_barrier(0);
     }
     mma8(f[0], [&](int m) {
-      if (m < 6) {
-        frag_piece(stage, 2, f[2], m);
-        if (do_load) load_piece(t + 3, rw, m);
-      }
+      spread(m, kFragPieces + kHalf, [&](int e) {
+        if (e < kFragPieces) frag_piece(stage, 2, f[2], e);
+        else if (do_load) load_piece(t + 3, rw, e - kFragPieces);
+      });
     });
     mma8(f[1], [&](int m) {
-      if (m < 6) {
-        frag_piece(stage, 3, f[3], m);
-        if (do_load) load_piece(t + 3, rw, 6 + m);
-      }
+      spread(m, kFragPieces + kHalf, [&](int e) {
+        if (e < kFragPieces) frag_piece(stage, 3, f[3], e);
+        else if (do_load) load_piece(t + 3, rw, kHalf + e - kFragPieces);
+      });
     });
     __syncthreads();                                                    // B_{t+1}
   };
