@@ -18,6 +18,14 @@ namespace aquakv {
 namespace {
 
 constexpr int kLdP = BN + 4;                        // padded fp32 row of the parked prediction tile
+// Position of column `col` inside a parked row.  A quad reads 16-byte slot 8q + k of a row in
+// its k-th load; q and q+2 would be 128 B = half the banks apart and collide with the next
+// rows, so the upper half of the row has its slots XOR-ed by 4: the 16 lanes served together
+// (4 rows x 4 lanes) then touch all 64 banks once.
+__device__ __forceinline__ constexpr int park_col(int col) {
+  const int slot = col >> 2;
+  return (((slot & 16) ? (slot ^ 4) : slot) << 2) | (col & 3);
+}
 constexpr int kPredBytes = BM * kLdP * 4;           // 135168: reuses (and exceeds) the main loop's 2 stages
 constexpr int kFusedLdsBytes = kPredBytes + (int)sizeof(Lds);
 static_assert(kPredBytes >= 2 * kStageBytes, "prediction tile must cover the main-loop stages");
@@ -68,7 +76,7 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int lrow = i * 32 + (r >> 2) * 8 + fk * 4 + (r & 3);
-          wl[lrow * kLdP + col] = acc[i][j][r] + bv;
+          wl[lrow * kLdP + park_col(col)] = acc[i][j][r] + bv;
         }
     }
   }
@@ -112,10 +120,10 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
     const int64_t off = rowc * D + n0 + q * kValsPerLane;
     float p[32], v[32];
     {
-      const f32x4* src = reinterpret_cast<const f32x4*>(wl + lrow * kLdP + q * kValsPerLane);
+      const float* rowp = wl + lrow * kLdP;
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
-        const f32x4 a = src[k];
+        const f32x4 a = *reinterpret_cast<const f32x4*>(rowp + park_col(q * kValsPerLane + 4 * k));
         p[4 * k] = a.x; p[4 * k + 1] = a.y; p[4 * k + 2] = a.z; p[4 * k + 3] = a.w;
       }
     }
@@ -171,7 +179,10 @@ hipError_t launch(int n_codewords, const void* x0, int d0, const void* x1, int d
   // 8 wavefronts per tile (two per SIMD): the main loop is bound by L2 -> LDS traffic either
   // way, and the second wave fills the issue slots the first leaves in the VALU-heavy epilogue
   // (measured: encode 10 % faster than with 4 wavefronts, decode unchanged).
-  constexpr int kWaves = 8;
+#ifndef AQUAKV_FUSED_WAVES
+#define AQUAKV_FUSED_WAVES 8
+#endif
+  constexpr int kWaves = AQUAKV_FUSED_WAVES;
 #define AQUAKV_FUSED(N)                                                                                          \
   fused_kernel<N, MODE, kWaves><<<blocks, kWaves * 64, 0, stream>>>(                                             \
       static_cast<const bf16_t*>(x0), d0, static_cast<const bf16_t*>(x1), d1, static_cast<const bf16_t*>(W), bias, \

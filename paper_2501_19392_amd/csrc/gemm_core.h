@@ -24,9 +24,11 @@ constexpr int kStageBytes = kATileBytes + kBTileBytes;
 // same K order per output element, so they give identical bits.
 constexpr int kGemmThreads = 256;                // the 4-wave shape (stand-alone predictor kernel)
 
-// 16-byte chunk `ch` (0..7) of LDS row `row`, XOR-swizzled so that the 32 lanes
-// of a fragment read (32 consecutive rows, same chunk) spread over all banks.
-__device__ __forceinline__ int lds_off(int row, int ch) { return row * kRowBytes + ((ch ^ (row & 7)) << 4); }
+// 16-byte chunk `ch` (0..7) of LDS row `row`.  A row is 128 B = half of the 64 banks, so even
+// and odd rows already sit in different bank halves; the chunk is XOR-swizzled with row/2 so
+// that the 16 lanes served together by a 128-bit fragment read (16 consecutive rows, same
+// chunk) touch all 64 banks exactly once.
+__device__ __forceinline__ int lds_off(int row, int ch) { return row * kRowBytes + ((ch ^ ((row >> 1) & 7)) << 4); }
 
 // XCD-aware tile order: consecutive workgroup ids land on different XCDs, so
 // give each XCD a contiguous range of tiles (n fastest): the column tiles of
