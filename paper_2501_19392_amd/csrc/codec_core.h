@@ -228,7 +228,7 @@ __device__ __forceinline__ void quantize_group(float (&v)[32], const float (&p)[
                                                bool want_hat) {
 #pragma unroll
   for (int r = 0; r < 32; ++r) v[r] = __uint_as_float(__float_as_uint(v[r] - p[r]) ^ sb[r]);   // s * (x - p)
-  wht128(v, q);                                           // w = H u (unnormalised)
+  wht128(v, q);                                           // w = +-H u (unnormalised, lane sign pending)
 
   float ss = 0.f;
 #pragma unroll
@@ -239,7 +239,7 @@ __device__ __forceinline__ void quantize_group(float (&v)[32], const float (&p)[
   sigma = fminf(sigma, 65504.0f);
   const _Float16 s16h = static_cast<_Float16>(sigma);     // round to nearest even
   const float s16 = static_cast<float>(s16h);
-  const float inv = s16 > 0.f ? __fdiv_rn(kRsqrtG, s16) : 0.f;
+  const float inv = s16 > 0.f ? quad_sign(q) * __fdiv_rn(kRsqrtG, s16) : 0.f;   // also undoes wht128's lane sign
 
   int idx[16];
   if (table != nullptr) {

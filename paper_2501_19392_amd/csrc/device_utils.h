@@ -109,17 +109,46 @@ __device__ __forceinline__ float quad_sum(float x) {
 }
 
 // ---------------------------------------------------------------- 128-point WHT
-// v[r] is coordinate 32*q + r of the group (q = lane % 4).  Unnormalised
-// Sylvester-order transform: coordinate bits 0..4 are butterflied in registers,
-// bits 5..6 across the quad.  The holder of the 0-bit keeps a+b, the other a-b.
-template <int MASK> __device__ __forceinline__ void wht_quad_stage(float (&v)[32], uint32_t upper_signbit) {
+// v[r] is coordinate 32*q + r of the group (q = lane % 4).  Unnormalised Sylvester-order
+// transform: coordinate bits 0..4 are butterflied in registers, bits 5..6 across the quad.
+//
+// A cross-lane butterfly wants partner + v on the lane holding the 0-bit and partner - v on
+// the other.  Both lanes instead run the same multiply-add v + s * partner with a per-lane
+// s = +1 / -1 (one DPP instruction per value, exact), which leaves the upper lane with the
+// NEGATED result.  The sign is the same for all 32 values of a lane, passes through the
+// following (linear) stage unchanged, and is handed back to the caller, who folds it into a
+// multiplication it performs anyway:  true transform = quad_sign(q) * (what wht128 leaves in v).
+//
+// The compiler does not fold the lane permute into a multiply-add, so the stage is written as
+// v_fmac_f32 with a DPP quad permute on its first source (dst += permuted(dst) * s).  A DPP
+// read of a register written by the VALU instruction just before it needs two idle issue
+// slots; the compiler cannot see into the block, so each block of 16 starts with them.
+#define AQUAKV_FMAC_DPP(i, perm) "v_fmac_f32_dpp %" #i ", %" #i ", %16 quad_perm:" perm " row_mask:0xf bank_mask:0xf\n\t"
+#define AQUAKV_FMAC_DPP16(perm)                                                                               \
+  "s_nop 1\n\t" AQUAKV_FMAC_DPP(0, perm) AQUAKV_FMAC_DPP(1, perm) AQUAKV_FMAC_DPP(2, perm) AQUAKV_FMAC_DPP(3, perm)  \
+  AQUAKV_FMAC_DPP(4, perm) AQUAKV_FMAC_DPP(5, perm) AQUAKV_FMAC_DPP(6, perm) AQUAKV_FMAC_DPP(7, perm)               \
+  AQUAKV_FMAC_DPP(8, perm) AQUAKV_FMAC_DPP(9, perm) AQUAKV_FMAC_DPP(10, perm) AQUAKV_FMAC_DPP(11, perm)             \
+  AQUAKV_FMAC_DPP(12, perm) AQUAKV_FMAC_DPP(13, perm) AQUAKV_FMAC_DPP(14, perm) AQUAKV_FMAC_DPP(15, perm)
+template <int MASK> __device__ __forceinline__ void wht_quad_stage(float (&v)[32], float s) {
+  static_assert(MASK == 1 || MASK == 2, "mask");
 #pragma unroll
-  for (int r = 0; r < 32; ++r) {
-    const float partner = quad_xor<MASK>(v[r]);
-    const float self = __uint_as_float(__float_as_uint(v[r]) ^ upper_signbit);   // -v on the upper lane
-    v[r] = partner + self;
+  for (int b = 0; b < 32; b += 16) {
+    if constexpr (MASK == 1)
+      asm(AQUAKV_FMAC_DPP16("[1,0,3,2]")
+          : "+v"(v[b]), "+v"(v[b + 1]), "+v"(v[b + 2]), "+v"(v[b + 3]), "+v"(v[b + 4]), "+v"(v[b + 5]), "+v"(v[b + 6]),
+            "+v"(v[b + 7]), "+v"(v[b + 8]), "+v"(v[b + 9]), "+v"(v[b + 10]), "+v"(v[b + 11]), "+v"(v[b + 12]),
+            "+v"(v[b + 13]), "+v"(v[b + 14]), "+v"(v[b + 15])
+          : "v"(s));
+    else
+      asm(AQUAKV_FMAC_DPP16("[2,3,0,1]")
+          : "+v"(v[b]), "+v"(v[b + 1]), "+v"(v[b + 2]), "+v"(v[b + 3]), "+v"(v[b + 4]), "+v"(v[b + 5]), "+v"(v[b + 6]),
+            "+v"(v[b + 7]), "+v"(v[b + 8]), "+v"(v[b + 9]), "+v"(v[b + 10]), "+v"(v[b + 11]), "+v"(v[b + 12]),
+            "+v"(v[b + 13]), "+v"(v[b + 14]), "+v"(v[b + 15])
+          : "v"(s));
   }
 }
+
+__device__ __forceinline__ float quad_sign(int q) { return (q == 1 || q == 2) ? -1.0f : 1.0f; }
 
 __device__ __forceinline__ void wht128(float (&v)[32], int q) {
 #pragma unroll
@@ -133,8 +162,8 @@ __device__ __forceinline__ void wht128(float (&v)[32], int q) {
       }
     }
   }
-  wht_quad_stage<1>(v, (uint32_t)(q & 1) << 31);
-  wht_quad_stage<2>(v, (uint32_t)(q & 2) << 30);
+  wht_quad_stage<1>(v, (q & 1) ? -1.0f : 1.0f);
+  wht_quad_stage<2>(v, (q & 2) ? -1.0f : 1.0f);
 }
 
 // sign bits of the 32 RHT signs this lane needs (+1 -> 0, -1 -> 0x80000000)
@@ -156,9 +185,10 @@ __device__ __forceinline__ void load_sign_bits(const int8_t* signs, int head, in
 // three produce bit-identical keys/values.
 __device__ __forceinline__ void reconstruct(float (&z)[32], int q, const uint32_t (&sb)[32], const float (&p)[32]) {
   wht128(z, q);
+  const float norm = quad_sign(q) * kRsqrtG;
 #pragma unroll
   for (int r = 0; r < 32; ++r) {
-    const float x = __uint_as_float(__float_as_uint(z[r] * kRsqrtG) ^ sb[r]);
+    const float x = __uint_as_float(__float_as_uint(z[r] * norm) ^ sb[r]);
     z[r] = x + p[r];
   }
 }

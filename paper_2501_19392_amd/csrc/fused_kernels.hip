@@ -43,12 +43,25 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
   __shared__ __attribute__((aligned(16))) unsigned char smem[kFusedLdsBytes];
   Lds& cl = *reinterpret_cast<Lds*>(smem + kPredBytes);
   const bool use_table = MODE == kEncode && table != nullptr;
-  load_codebook<NCW>(codebook, cl.cb);               // made visible by the main loop's first barrier
+  // grid and cell table: requested now, written to LDS from inside the main loop's prologue
+  constexpr int kTableChunks = kCells * kCells / 4 / (WAVES * 64);
+  static_assert(NCW <= WAVES * 64, "one grid point per thread");
+  float cb_a = 0.f, cb_b = 0.f;
+  u32x4 table_regs[kTableChunks];
+  if (threadIdx.x < NCW) { cb_a = codebook[2 * threadIdx.x]; cb_b = codebook[2 * threadIdx.x + 1]; }
   if (use_table) {
-    const u32x4* src = reinterpret_cast<const u32x4*>(table);
-    u32x4* dst = reinterpret_cast<u32x4*>(cl.table);
-    for (int i = threadIdx.x; i < kCells * kCells / 4; i += WAVES * 64) dst[i] = src[i];
+#pragma unroll
+    for (int i = 0; i < kTableChunks; ++i)
+      table_regs[i] = reinterpret_cast<const u32x4*>(table)[threadIdx.x + i * WAVES * 64];
   }
+  const auto stage_tables = [&] {
+    if (threadIdx.x < NCW) cl.cb[threadIdx.x] = make_float4(cb_a, cb_b, -0.5f * (cb_a * cb_a + cb_b * cb_b), 0.f);
+    if (use_table) {
+#pragma unroll
+      for (int i = 0; i < kTableChunks; ++i)
+        reinterpret_cast<u32x4*>(cl.table)[threadIdx.x + i * WAVES * 64] = table_regs[i];
+    }
+  };
 
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
@@ -60,35 +73,15 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
 
   constexpr int MI = BM / WAVES / 32;              // 32-row blocks per wave
   constexpr int kRowsPerWave = MI * 32;
-  f32x16 acc[MI][4];
-  gemm_mainloop<WAVES>(smem, x0, d0, x1, d1, W, T, m0, n0, acc);
+  const int q = lane & 3;                          // position in the quad that owns a group
 
-  // park the tile (+ bias) in LDS, row-major fp32, each wave its own 64 rows
-  float* wl = reinterpret_cast<float*>(smem) + wave * kRowsPerWave * kLdP;
-  {
-    const int frow = lane & 31, fk = lane >> 5;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int col = j * 32 + frow;
-      const float bv = bias != nullptr ? bias[n0 + col] : 0.f;
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int lrow = i * 32 + (r >> 2) * 8 + fk * 4 + (r & 3);
-          wl[lrow * kLdP + park_col(col)] = acc[i][j][r] + bv;
-        }
-    }
-  }
-  __syncthreads();
-
-  // Epilogue: passes of 16 groups per wave, one group per quad; all global inputs are
-  // requested up front.
-  const int q = lane & 3;
-  uint32_t sb[32];
-  load_sign_bits(signs, head, q, sb);
+  // What the epilogue reads from global memory (rows to quantize, or codes and scales) is
+  // requested from inside the main loop, when its own last operand loads are out, so the
+  // latency is covered by the remaining MFMA work.
   constexpr int c = CodeBits<NCW>::c;
   struct In { u32x4 x[4]; u32x4 code; uint16_t scale; };
+  constexpr int kPasses = kRowsPerWave / 16;          // passes of 16 groups per wave, one group per quad
+  In in[kPasses];
   const auto fetch = [&](int pass, In& in) {
     int64_t row = m0 + wave * kRowsPerWave + pass * 16 + (lane >> 2);
     row = row < T ? row : T - 1;
@@ -110,6 +103,35 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
       in.scale = scales[gid];
     }
   };
+
+  f32x16 acc[MI][4];
+  gemm_mainloop<WAVES>(smem, x0, d0, x1, d1, W, T, m0, n0, acc, stage_tables, [&] {
+#pragma unroll
+    for (int pass = 0; pass < kPasses; ++pass) fetch(pass, in[pass]);
+  });
+
+  // park the tile (+ bias) in LDS, row-major fp32, each wave its own 64 rows
+  float* wl = reinterpret_cast<float*>(smem) + wave * kRowsPerWave * kLdP;
+  {
+    const int frow = lane & 31, fk = lane >> 5;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int col = j * 32 + frow;
+      const float bv = bias != nullptr ? bias[n0 + col] : 0.f;
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int lrow = i * 32 + (r >> 2) * 8 + fk * 4 + (r & 3);
+          wl[lrow * kLdP + park_col(col)] = acc[i][j][r] + bv;
+        }
+    }
+  }
+  __syncthreads();
+
+  // Epilogue: passes of 16 groups per wave, one group per quad.
+  uint32_t sb[32];
+  load_sign_bits(signs, head, q, sb);
   // one pass: 16 groups of this wave (rows pass*16 .. +15), inputs already in `in`
   const auto do_pass = [&](int pass, const In& in) {
     const int lrow = pass * 16 + (lane >> 2);
@@ -157,11 +179,6 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
       }
     }
   };
-  // kRowsPerWave / 16 passes; all inputs are requested first
-  constexpr int kPasses = kRowsPerWave / 16;
-  In in[kPasses];
-#pragma unroll
-  for (int pass = 0; pass < kPasses; ++pass) fetch(pass, in[pass]);
 #pragma unroll
   for (int pass = 0; pass < kPasses; ++pass) {
     do_pass(pass, in[pass]);

@@ -44,10 +44,16 @@ __device__ __forceinline__ int remap_block(int bid, int nblocks) {
 // holds column lane%32 and rows 8*blk + 4*(lane/32) + r4 in register 4*blk + r4.
 // `lds_base` points at 2 * kStageBytes bytes of LDS.  Ends with a barrier after the last LDS read,
 // so the caller may reuse the LDS at once.  Requires K = d0 + d1 a multiple of 128, d0 of 64.
-template <int WAVES>
+// `after_first_stage()` is called once the first k-tile has arrived and the next loads are in flight:
+// global loads the caller issued before the call have landed by then (loads return in order), so it
+// can move them to LDS (outside the two stages) without exposing their latency.
+// `before_drain()` is called once, when the last global loads of the operands have been issued and
+// about three k-tiles of MFMA work remain: the place to request what the caller's epilogue reads.
+template <int WAVES, typename AfterFirstStage, typename BeforeDrain>
 __device__ __forceinline__ void gemm_mainloop(unsigned char* lds_base, const bf16_t* __restrict__ x0, int d0,
                                               const bf16_t* __restrict__ x1, int d1, const bf16_t* __restrict__ W,
-                                              int64_t T, int64_t m0, int n0, f32x16 (&acc)[BM / WAVES / 32][4]) {
+                                              int64_t T, int64_t m0, int n0, f32x16 (&acc)[BM / WAVES / 32][4],
+                                              AfterFirstStage&& after_first_stage, BeforeDrain&& before_drain) {
   static_assert(WAVES == 4 || WAVES == 8, "one or two waves per SIMD");
   constexpr int kThreadsW = WAVES * 64;
   constexpr int MI = BM / WAVES / 32;              // 32-row blocks per wave (2 or 1)
@@ -168,6 +174,7 @@ __device__ __forceinline__ void gemm_mainloop(unsigned char* lds_base, const bf1
 #pragma unroll
   for (int pc = 0; pc < kPieces; ++pc)
     if (nk > 2) load_piece(2, rs[0], pc);
+  after_first_stage();
   __syncthreads();                                                      // B_0
 
   // iteration t (see the table above); rw holds tile t+1 and then receives tile t+3.
@@ -219,6 +226,8 @@ __device__ __forceinline__ void gemm_mainloop(unsigned char* lds_base, const bf1
     iteration(t, rs[0], false, true, true);
     iteration(t + 1, rs[1], false, true, true);
   }
+  before_drain();
+  __builtin_amdgcn_sched_barrier(0);
   if (nk >= 4) {                                     // drain: t = nk-3 (odd), nk-2; nothing left to load
     iteration(nk - 3, rs[0], false, true, false);
     iteration(nk - 2, rs[1], false, true, false);

@@ -24,7 +24,7 @@ __global__ __launch_bounds__(kGemmThreads) void predict_bf16_kernel(
   const int frow = lane & 31, fk = lane >> 5;
 
   f32x16 acc[2][4];
-  gemm_mainloop<4>(lds, x0, d0, x1, d1, W, T, m0, n0, acc);
+  gemm_mainloop<4>(lds, x0, d0, x1, d1, W, T, m0, n0, acc, [] {}, [] {});
 
   // accumulator layout of the 32x32 tile: lane holds column lane%32 and rows
   // 8*blk + 4*(lane/32) + j for register 4*blk + j.
