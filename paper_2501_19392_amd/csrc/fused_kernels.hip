@@ -26,9 +26,11 @@ __device__ __forceinline__ constexpr int park_col(int col) {
   const int slot = col >> 2;
   return (((slot & 16) ? (slot ^ 4) : slot) << 2) | (col & 3);
 }
-constexpr int kPredBytes = BM * kLdP * 4;           // 135168: reuses (and exceeds) the main loop's 2 stages
-constexpr int kFusedLdsBytes = kPredBytes + (int)sizeof(Lds);
-static_assert(kPredBytes >= 2 * kStageBytes, "prediction tile must cover the main-loop stages");
+constexpr int kPredBytes = BM * kLdP * 4;           // 135168
+// LDS use over time: the main loop's ring of k-tiles (3 x 48 KiB), then the parked prediction
+// tile followed by the grid and the cell table, which are written once the main loop is done.
+constexpr int kEpilogueLdsBytes = kPredBytes + (int)sizeof(Lds);
+constexpr int kFusedLdsBytes = kEpilogueLdsBytes > kMainLoopLdsBytes ? kEpilogueLdsBytes : kMainLoopLdsBytes;
 static_assert(kFusedLdsBytes <= 160 * 1024, "LDS of one CU");
 
 enum Mode : int { kEncode = 0, kDecode = 1, kScores = 2 };
@@ -43,7 +45,7 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
   __shared__ __attribute__((aligned(16))) unsigned char smem[kFusedLdsBytes];
   Lds& cl = *reinterpret_cast<Lds*>(smem + kPredBytes);
   const bool use_table = MODE == kEncode && table != nullptr;
-  // grid and cell table: requested now, written to LDS from inside the main loop's prologue
+  // grid and cell table: requested now, kept in registers while the main loop owns the LDS
   constexpr int kTableChunks = kCells * kCells / 4 / (WAVES * 64);
   static_assert(NCW <= WAVES * 64, "one grid point per thread");
   float cb_a = 0.f, cb_b = 0.f;
@@ -105,12 +107,13 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
   };
 
   f32x16 acc[MI][4];
-  gemm_mainloop<WAVES>(smem, x0, d0, x1, d1, W, T, m0, n0, acc, stage_tables, [&] {
+  gemm_mainloop<WAVES>(smem, x0, d0, x1, d1, W, T, m0, n0, acc, [&] {
 #pragma unroll
     for (int pass = 0; pass < kPasses; ++pass) fetch(pass, in[pass]);
   });
 
-  // park the tile (+ bias) in LDS, row-major fp32, each wave its own 64 rows
+  // the LDS is free again: grid and table, then the tile (+ bias) parked row-major in fp32, each wave its own rows
+  stage_tables();
   float* wl = reinterpret_cast<float*>(smem) + wave * kRowsPerWave * kLdP;
   {
     const int frow = lane & 31, fk = lane >> 5;

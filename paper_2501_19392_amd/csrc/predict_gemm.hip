@@ -12,7 +12,7 @@ namespace {
 __global__ __launch_bounds__(kGemmThreads) void predict_bf16_kernel(
     const bf16_t* __restrict__ x0, int d0, const bf16_t* __restrict__ x1, int d1, const bf16_t* __restrict__ W,
     const float* __restrict__ bias, float* __restrict__ P, int64_t T, int D) {
-  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * kStageBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char lds[kMainLoopLdsBytes];
 
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
@@ -24,7 +24,7 @@ __global__ __launch_bounds__(kGemmThreads) void predict_bf16_kernel(
   const int frow = lane & 31, fk = lane >> 5;
 
   f32x16 acc[2][4];
-  gemm_mainloop<4>(lds, x0, d0, x1, d1, W, T, m0, n0, acc, [] {}, [] {});
+  gemm_mainloop<4>(lds, x0, d0, x1, d1, W, T, m0, n0, acc, [] {});
 
   // accumulator layout of the 32x32 tile: lane holds column lane%32 and rows
   // 8*blk + 4*(lane/32) + j for register 4*blk + j.
