@@ -24,6 +24,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+# HBM-side bytes per fused encode launch measured with rocprofv3 --pmc (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the
+# factors being what the same counters read for a 256 MiB device copy): profiles/bench_llama32_3b_pmc_counters.md.
+# Keyed by (config, n_codewords); other workloads report null.
+MEASURED_TRAFFIC_BYTES = {("llama3.2-3b", 16): (2.0 * 33035.0 + 1.0 * 18560.0) * 1024.0}
 
 
 def parse():
@@ -245,7 +249,9 @@ def main():
         achieved = flops / (ms * 1e-3) / 1e12
         roofline = {"kernel": "fused_kernel<encode> (bf16 MFMA predictor + quantizer epilogue)", "bound": "mfma",
                     "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None, "launches": launches,
+                    "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                    "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, args.n_codewords)), "launches": launches,
+                    "algorithmic_bytes_per_launch": round(nbytes / launches, 1),
                     "avg_launch_us": round(1e3 * ms / launches, 2),
                     "algorithmic_hbm_GBs": round(nbytes / (ms * 1e-3) / 1e9, 1),
                     "algorithmic_hbm_frac": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
