@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--no-kernel-events", action="store_true", help="skip the instrumented replay")
     ap.add_argument("--cpu-rows", type=int, default=8192, help="token rows of the oracle sample")
     ap.add_argument("--cpu-layers", type=int, default=4, help="predicted layers of the oracle sample")
+    ap.add_argument("--scores-form", default="folded", choices=["folded", "recompute"],
+                    help="folded: key predictor folded into the query (needs the scores workspace); recompute: "
+                         "prediction recomputed in the scoring kernel")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device copy (a known-size dispatch to scale rocprofv3 --pmc byte counters)")
     return ap.parse_args()
@@ -71,7 +74,7 @@ def build_workload(cfg, device, n_codewords):
 
 
 class Buffers:
-    def __init__(self, layers, T, q_heads, device):
+    def __init__(self, layers, T, q_heads, device, scores_form="folded"):
         import torch
         self.codes = [(l.alloc_codes(T, device), l.alloc_codes(T, device)) for l in layers]
         lay = layers[0]
@@ -80,6 +83,14 @@ class Buffers:
         self.ws = lay.alloc_workspace(T, device)
         self.scores = torch.empty(1, q_heads, T, dtype=torch.float32, device=device)
         self.P = torch.empty(T, lay.d, dtype=torch.float32, device=device)
+        # the scoring call folds the predictor into the query iff it is handed this workspace
+        from paper_2501_19392_amd import binding as B
+        if B.aquakv_scores_workspace_bytes(layers[-1], 1, q_heads) == 0:
+            self.ws_scores = self.ws                      # no folded form for this layer type (fp32): prediction workspace
+        elif scores_form == "folded":
+            self.ws_scores = layers[-1].alloc_scores_workspace(1, q_heads, device)
+        else:
+            self.ws_scores = torch.empty(16, dtype=torch.uint8, device=device)
 
 
 def run_step(B, layers, Ks, Vs, buf, q, T, q_heads):
@@ -101,7 +112,7 @@ def run_step(B, layers, Ks, Vs, buf, q, T, q_heads):
     for l, lay in enumerate(layers):
         (kc, ks), _ = buf.codes[l]
         kp = None if l == 0 else buf.hat[(l - 1) & 1][0]
-        B.aquakv_decode_attn_scores(lay, 1, T, q_heads, kc, ks, kp, q, 0.088388, buf.scores, None, buf.ws)
+        B.aquakv_decode_attn_scores(lay, 1, T, q_heads, kc, ks, kp, q, 0.088388, buf.scores, None, buf.ws_scores)
 
 
 def timed_phases(B, layers, Ks, Vs, buf, q, T, q_heads, reps):
@@ -124,7 +135,7 @@ def timed_phases(B, layers, Ks, Vs, buf, q, T, q_heads, reps):
                     B.aquakv_decode_layer(lay, T, kc, ks, vc, vs, prev[0], prev[1], Kh, Vh, buf.ws)
                 else:
                     kp = None if l == 0 else buf.hat[(l - 1) & 1][0]
-                    B.aquakv_decode_attn_scores(lay, 1, T, q_heads, kc, ks, kp, q, 0.088388, buf.scores, None, buf.ws)
+                    B.aquakv_decode_attn_scores(lay, 1, T, q_heads, kc, ks, kp, q, 0.088388, buf.scores, None, buf.ws_scores)
                 prev = (Kh, Vh)
         b.record()
         torch.cuda.synchronize()
@@ -221,7 +232,7 @@ def main():
     T = cfg.tokens
 
     layers, Ks, Vs = build_workload(cfg, device, args.n_codewords)
-    buf = Buffers(layers, T, q_heads, device)
+    buf = Buffers(layers, T, q_heads, device, args.scores_form)
     q = synth.random_queries(1, q_heads, cfg.head_dim, seed=1, dtype=cfg.dtype, device=device)
 
     if args.calibrate_copy:

@@ -168,7 +168,18 @@ int aquakv_decode_layer(const aquakv_layer* layer, int64_t tokens,
  * codes / scales / Khat_prev cover batch*seq_len rows; no rotary embedding.
  * Khat_out (nullable, dtype, [batch*seq_len, H, g]) also receives the keys.
  * q_heads must be a multiple of H with q_heads / H <= 8.
+ *
+ * Folded form.  A score is linear in the key, so with a key predictor (Sect. 3.2)
+ *   q . Khat[t] = Khat_prev[t] . (W_h^T q) + q . b_h + sigma[t] * (R q) . C[codes[t]],
+ * R q the rotated query: one 1024-long dot product per token and query head instead of the
+ * predictor product, bound by reading Khat_prev and the codes once.  The call takes this form
+ * when Khat_out is NULL and `workspace` holds at least aquakv_scores_workspace_bytes() bytes
+ * (a nonzero value says the form exists for this layer and shape: bf16, 8 kv heads, key
+ * predictor with 1024 inputs, q_heads <= 32); otherwise it recomputes the prediction.  The
+ * folded scores use the unrounded keys and agree with the definition above to the storage
+ * precision of Khat (2^-9 relative per term in bf16).
  */
+size_t aquakv_scores_workspace_bytes(const aquakv_layer* layer, int32_t batch, int32_t q_heads);
 int aquakv_decode_attn_scores(const aquakv_layer* layer, int32_t batch, int32_t seq_len, int32_t q_heads,
                               const uint8_t* k_codes, const uint16_t* k_scales,
                               const void* Khat_prev, const void* q, float score_scale,

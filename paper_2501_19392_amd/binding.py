@@ -32,6 +32,7 @@ EXPORTS = [
     "aquakv_search_table_bytes", "aquakv_build_search_table",
     "aquakv_predict", "aquakv_quantize", "aquakv_dequantize",
     "aquakv_encode_layer", "aquakv_decode_layer", "aquakv_decode_attn_scores",
+    "aquakv_scores_workspace_bytes",
 ]
 
 
@@ -54,6 +55,8 @@ _lib.aquakv_status_string.argtypes = [ctypes.c_int]
 _lib.aquakv_last_error.restype = ctypes.c_char_p
 _lib.aquakv_workspace_bytes.restype = ctypes.c_size_t
 _lib.aquakv_workspace_bytes.argtypes = [_LP, ctypes.c_int64]
+_lib.aquakv_scores_workspace_bytes.restype = ctypes.c_size_t
+_lib.aquakv_scores_workspace_bytes.argtypes = [_LP, ctypes.c_int32, ctypes.c_int32]
 _lib.aquakv_search_table_bytes.restype = ctypes.c_size_t
 _lib.aquakv_search_table_bytes.argtypes = [ctypes.c_int32]
 _lib.aquakv_build_search_table.restype = ctypes.c_int
@@ -160,6 +163,10 @@ class Layer:
     def alloc_workspace(self, tokens: int, device="cuda"):
         return torch.empty(max(aquakv_workspace_bytes(self, tokens), 16), dtype=torch.uint8, device=device)
 
+    def alloc_scores_workspace(self, batch: int, q_heads: int, device="cuda"):
+        """Workspace that lets aquakv_decode_attn_scores take its folded form (16 bytes if there is none)."""
+        return torch.empty(max(aquakv_scores_workspace_bytes(self, batch, q_heads), 16), dtype=torch.uint8, device=device)
+
 
 def _layer_ref(layer):
     return ctypes.byref(layer.c if isinstance(layer, Layer) else layer)
@@ -180,6 +187,10 @@ def aquakv_last_error() -> str:
 
 def aquakv_workspace_bytes(layer, tokens: int) -> int:
     return int(_lib.aquakv_workspace_bytes(_layer_ref(layer), tokens))
+
+
+def aquakv_scores_workspace_bytes(layer, batch: int, q_heads: int) -> int:
+    return int(_lib.aquakv_scores_workspace_bytes(_layer_ref(layer), batch, q_heads))
 
 
 def aquakv_search_table_bytes(n_codewords: int) -> int:

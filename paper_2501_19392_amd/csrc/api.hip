@@ -332,6 +332,12 @@ int aquakv_decode_layer(const aquakv_layer* L, int64_t tokens, const uint8_t* k_
   return AQUAKV_OK;
 }
 
+size_t aquakv_scores_workspace_bytes(const aquakv_layer* L, int32_t batch, int32_t q_heads) {
+  if (check_layer(L) != AQUAKV_OK || batch < 1 || q_heads < 1) return 0;
+  if (L->dtype != AQUAKV_BF16 || !aquakv::folded_scores_supported(L->kv_heads, L->d_in_k, q_heads)) return 0;
+  return aquakv::folded_scores_workspace_bytes(batch);
+}
+
 int aquakv_decode_attn_scores(const aquakv_layer* L, int32_t batch, int32_t seq_len, int32_t q_heads,
                               const uint8_t* k_codes, const uint16_t* k_scales, const void* Khat_prev, const void* q,
                               float score_scale, float* scores, void* Khat_out, void* workspace,
@@ -350,6 +356,16 @@ int aquakv_decode_attn_scores(const aquakv_layer* L, int32_t batch, int32_t seq_
   const int64_t tokens = (int64_t)batch * seq_len;
   if (tokens == 0) return AQUAKV_OK;
   const Plan pl = make_plan(L, tokens);
+  if (has_k && pl.fused && Khat_out == nullptr && workspace != nullptr &&
+      aquakv::folded_scores_supported(L->kv_heads, L->d_in_k, q_heads) &&
+      workspace_bytes >= aquakv::folded_scores_workspace_bytes(batch)) {
+    // predictor folded into the query: Khat_prev and the codes are read once, nothing is recomputed
+    CHECK(check_ptr(workspace, "workspace", true));
+    HIP_TRY(aquakv::launch_folded_scores(L->n_codewords, Khat_prev, L->w_k, L->b_k, L->signs_k, L->codebook, k_codes,
+                                         k_scales, q, score_scale, scores, workspace, batch, seq_len, q_heads,
+                                         static_cast<hipStream_t>(stream_)));
+    return AQUAKV_OK;
+  }
   if (has_k && pl.fused) {
     // one fused launch over all rows: prediction, inverse quantizer and dot products
     HIP_TRY(aquakv::launch_fused_scores(L->n_codewords, Khat_prev, L->d_in_k, L->w_k, L->b_k, L->signs_k, L->codebook,

@@ -13,6 +13,7 @@ namespace aquakv {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
 
 constexpr int BM = 256, BN = 128, BK = 64;       // block tile; the waves are stacked in M
 constexpr int kRowBytes = BK * 2;                // 128 B of bf16 per LDS row

@@ -47,4 +47,13 @@ hipError_t launch_fused_scores(int n_codewords, const void* x0, int d0, const vo
                                const uint16_t* scales, const void* q, float score_scale, float* scores, void* Khat_out,
                                int seq_len, int q_heads, int64_t T, int D, hipStream_t stream);
 
+// Scores with the key predictor folded into the query (bf16, 8 kv heads, 1024 predictor inputs,
+// q_heads <= 32): reads Khat_prev and the codes once.  `workspace`: folded_scores_workspace_bytes(batch).
+bool folded_scores_supported(int kv_heads, int d_in_k, int q_heads);
+size_t folded_scores_workspace_bytes(int batch);
+hipError_t launch_folded_scores(int n_codewords, const void* Khat_prev, const void* W, const float* bias,
+                                const int8_t* signs, const float* codebook, const uint8_t* codes,
+                                const uint16_t* scales, const void* q, float score_scale, float* scores, void* workspace,
+                                int batch, int seq_len, int q_heads, hipStream_t stream);
+
 }  // namespace aquakv

@@ -199,7 +199,7 @@ def run_gpu_layers(B, cfg, layers_g, Ks, Vs, want_hat=True):
     return out
 
 
-def build_stack(cfg, device="cuda", predictors="analytic"):
+def build_stack(cfg, device="cuda", predictors="analytic", bias=False):
     st = synth.KVStream(cfg, device="cpu", work=torch.float64)
     Ks, Vs, lo_l, lg_l = [], [], [], []
     for l in range(cfg.layers):
@@ -213,7 +213,10 @@ def build_stack(cfg, device="cuda", predictors="analytic"):
                 wk, wv = synth.analytic_predictors(st, l)
             else:
                 wk, wv = U.random_weights(cfg.d, cfg.d, 100 + l, 0.7), U.random_weights(cfg.d, 2 * cfg.d, 200 + l, 0.7)
-            lo, lg = U.make_layers(cfg.kv_heads, cfg.dtype, cfg.n_codewords, layer_idx=l, w_k=wk, w_v=wv)
+            gb = torch.Generator().manual_seed(300 + l)
+            bk = torch.randn(cfg.d, generator=gb) * 0.3 if bias else None
+            bv = torch.randn(cfg.d, generator=gb) * 0.3 if bias else None
+            lo, lg = U.make_layers(cfg.kv_heads, cfg.dtype, cfg.n_codewords, layer_idx=l, w_k=wk, w_v=wv, b_k=bk, b_v=bv)
         lo_l.append(lo)
         lg_l.append(lg)
     return Ks, Vs, lo_l, lg_l
@@ -377,12 +380,63 @@ def test_attn_scores(B, dtype, n, with_pred):
     rtol = U.RTOL[dtype]
     assert np.all(err <= rtol * 0.125 * mag + 1e-30), float(np.max(err / (0.125 * mag + 1e-30)))
     print(f"   worst score error / (sum|q||k|) = {float(np.max(err / (0.125 * mag + 1e-30))):.3g}", flush=True)
-    # without Khat_out the scores are the same bits
+    # without Khat_out (and without the workspace of the folded form) the scores are the same bits
     s2 = torch.empty_like(scores)
-    B.aquakv_decode_attn_scores(lg, batch, S, QH, g["k_codes"], g["k_scales"], g["Kp"], q, 0.125, s2, None,
-                                lg.alloc_workspace(cfg.tokens))
+    small_ws = torch.empty(16, dtype=torch.uint8, device="cuda") if dtype == "bf16" else lg.alloc_workspace(cfg.tokens)
+    B.aquakv_decode_attn_scores(lg, batch, S, QH, g["k_codes"], g["k_scales"], g["Kp"], q, 0.125, s2, None, small_ws)
     sync()
     assert torch.equal(s2, scores)
+    # folded form (predictor folded into the query): same definition, unrounded keys
+    need = B.aquakv_scores_workspace_bytes(lg, batch, QH)
+    assert (need > 0) == (dtype == "bf16" and with_pred)
+    if need:
+        s3 = torch.full_like(scores, float("nan"))
+        B.aquakv_decode_attn_scores(lg, batch, S, QH, g["k_codes"], g["k_scales"], g["Kp"], q, 0.125, s3, None,
+                                    lg.alloc_scores_workspace(batch, QH))
+        sync()
+        err3 = np.abs(U.np64(s3) - want)
+        assert np.all(err3 <= rtol * 0.125 * mag + 1e-30), float(np.max(err3 / (0.125 * mag + 1e-30)))
+        assert not torch.equal(s3, scores)          # it really was the other kernel
+        print(f"   folded: worst score error / (sum|q||k|) = {float(np.max(err3 / (0.125 * mag + 1e-30))):.3g}", flush=True)
+
+
+@pytest.mark.parametrize("n,QH,batch,S,bias", [(16, 24, 2, 100, True), (64, 32, 1, 1000, False), (256, 8, 3, 33, True),
+                                              (16, 16, 5, 31, False)])
+def test_folded_scores_against_definition(B, n, QH, batch, S, bias):
+    """aquakv_decode_attn_scores in its folded form against the oracle's plain definition
+    (decode the keys, round them to storage, dot with q): query heads per kv head 1..4, all
+    three grids, predictor bias, ragged last tile, sequences shorter than one tile."""
+    print(f"case folded scores n={n} QH={QH} batch={batch} S={S} bias={bias}", flush=True)
+    H = 8
+    cfg = synth.Config("fold", layers=2, kv_heads=H, head_dim=128, tokens=batch * S, dtype="bf16", n_codewords=n)
+    Ks, Vs, lo_l, lg_l = build_stack(cfg, bias=bias)
+    out = run_gpu_layers(B, cfg, lg_l, Ks, Vs)
+    g, lg, lo = out[1], lg_l[1], lo_l[1]
+    q = synth.random_queries(batch, QH, 128, seed=5, dtype="bf16", device="cuda")
+    need = B.aquakv_scores_workspace_bytes(lg, batch, QH)
+    assert need > 0
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    scores = torch.full((batch, QH, S), float("nan"), dtype=torch.float32, device="cuda")
+    B.aquakv_decode_attn_scores(lg, batch, S, QH, g["k_codes"], g["k_scales"], g["Kp"], q, 0.25, scores, None, ws)
+    sync()
+    want = O.attn_scores(lo, batch, S, U.np64(q), g["k_codes"].cpu().numpy(), g["k_scales"].cpu().numpy().view(np.float16),
+                         U.np64(g["Kp"]), 0.25)
+    Kh = np.abs(U.np64(g["Khat"])).reshape(batch, S, H, 128)
+    mag = np.stack([np.einsum("bd,btd->bt", np.abs(U.np64(q))[:, qh], Kh[:, :, qh // (QH // H)]) for qh in range(QH)], 1)
+    err = np.abs(U.np64(scores) - want)
+    worst = float(np.max(err / (0.25 * mag + 1e-30)))
+    assert np.all(err <= U.RTOL["bf16"] * 0.25 * mag + 1e-30), worst
+    print(f"   worst score error / (sum|q||k|) = {worst:.3g}", flush=True)
+    # a second call into the same workspace with other queries (fewer heads) leaves no residue
+    QH2 = 8
+    q2 = synth.random_queries(batch, QH2, 128, seed=6, dtype="bf16", device="cuda")
+    sc2 = torch.empty(batch, QH2, S, dtype=torch.float32, device="cuda")
+    B.aquakv_decode_attn_scores(lg, batch, S, QH2, g["k_codes"], g["k_scales"], g["Kp"], q2, 0.25, sc2, None, ws)
+    sync()
+    want2 = O.attn_scores(lo, batch, S, U.np64(q2), g["k_codes"].cpu().numpy(),
+                          g["k_scales"].cpu().numpy().view(np.float16), U.np64(g["Kp"]), 0.25)
+    mag2 = np.stack([np.einsum("bd,btd->bt", np.abs(U.np64(q2))[:, qh], Kh[:, :, qh]) for qh in range(QH2)], 1)
+    assert np.all(np.abs(U.np64(sc2) - want2) <= U.RTOL["bf16"] * 0.25 * mag2 + 1e-30)
 
 
 # ------------------------------------------------------------------ full sizes, sampled rows
