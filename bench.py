@@ -13,6 +13,9 @@ oracle timed on a bounded sample of the same workload.
 from __future__ import annotations
 
 import argparse
+import dataclasses
+
+import numpy as np
 import json
 import os
 import sys
@@ -35,7 +38,11 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", default="llama3.2-3b", choices=["llama3.2-3b", "llama3.1-8b", "tiny"])
+    ap.add_argument("--config", default="llama3.2-3b",
+                    choices=["llama3.2-3b", "llama3.1-8b", "llama3.1-70b", "decode-read", "tiny"],
+                    help="llama3.1-70b: 80 layers x 131072 tokens, grid of 16 or 64 points per layer (seeded coin); "
+                         "decode-read: 64 sequences x 16384 cached tokens, scoring call + one-token append per layer")
+    ap.add_argument("--layers", type=int, default=0, help="use only the first N layers of the configuration (0: all)")
     ap.add_argument("--n-codewords", type=int, default=16)
     ap.add_argument("--q-heads", type=int, default=0, help="query heads for the scoring call (0: model default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -50,17 +57,29 @@ def parse():
     return ap.parse_args()
 
 
-def build_workload(cfg, device, n_codewords):
+def grids_on_device(ns, device):
+    """{n: (grid tensor, search table)} for the grid sizes in `ns`."""
+    import torch
+    from paper_2501_19392_amd import binding as B
+    from paper_2501_19392_amd import synth
+    out = {}
+    for n in sorted(set(ns)):
+        C = torch.from_numpy(synth.lloyd_codebook(n)).to(device)
+        out[n] = (C, B.build_search_table(C))
+    return out
+
+
+def build_workload(cfg, device, n_per_layer):
     import torch
     from paper_2501_19392_amd import binding as B
     from paper_2501_19392_amd import synth
     sd = synth.torch_dtype(cfg.dtype)
     work = torch.float32 if cfg.dtype == "bf16" else torch.float64
     st = synth.KVStream(cfg, device=device, work=work)
-    C = torch.from_numpy(synth.lloyd_codebook(n_codewords)).to(device)
-    table = B.build_search_table(C)
+    grids = grids_on_device(n_per_layer, device)
     layers, Ks, Vs = [], [], []
     for l in range(cfg.layers):
+        C, table = grids[n_per_layer[l]]
         K, V = st.next()
         Ks.append(K.contiguous())
         Vs.append(V.contiguous())
@@ -213,6 +232,116 @@ def cpu_baseline(cfg, n_codewords, rows, q_heads, n_layers):
                       f"({dt:.1f} s of CPU time; cost is linear in rows and layers)"}
 
 
+def decode_read_path(args, device):
+    """The decode-phase read path: 64 sequences x 16384 cached tokens per layer, 32 query heads on 8 kv heads.
+    A step = for every layer the scoring call over the whole compressed cache (aquakv_decode_attn_scores, one new
+    query per sequence) and the append of one new token per sequence (aquakv_encode_layer with tokens = 64)."""
+    import torch
+    from paper_2501_19392_amd import binding as B
+    from paper_2501_19392_amd import synth
+    batch, S, q_heads, n = 64, 16384, args.q_heads or 32, args.n_codewords
+    L = args.layers or 8
+    T = batch * S
+    cfg = synth.Config("decode-read", layers=L, kv_heads=8, head_dim=128, tokens=T, dtype="bf16")
+    sd = torch.bfloat16
+    st = synth.KVStream(cfg, device=device, work=torch.float32)
+    C, table = grids_on_device([n], device)[n]
+    layers, codes, khat, new_rows = [], [], [], []
+    vh = [None, None]
+    ws = None
+    prev = (None, None)
+    # set-up (untimed): encode the cache layer by layer; only the compressed keys and the reconstructed keys
+    # (the predictor input of the next layer's scoring call) are kept
+    for l in range(L):
+        K, V = st.next()
+        sk = torch.from_numpy(synth.rht_signs(8, 128, l, "k")).to(device)
+        sv = torch.from_numpy(synth.rht_signs(8, 128, l, "v")).to(device)
+        wk = wv = None
+        if l > 0:
+            wk, wv = (w.to(device) for w in synth.analytic_predictors(st, l))
+        lay = B.Layer(8, 128, C, sk, sv, sd, w_k=wk, w_v=wv, search_table=table)
+        ws = ws if ws is not None else lay.alloc_workspace(T, device)
+        kc, ks = lay.alloc_codes(T, device)
+        vc, vs = lay.alloc_codes(T, device)
+        Kh = lay.alloc_kv(T, device)
+        vh[l & 1] = vh[l & 1] if vh[l & 1] is not None else lay.alloc_kv(T, device)
+        B.aquakv_encode_layer(lay, T, K, V, prev[0], prev[1], kc, ks, vc, vs, Kh, vh[l & 1], ws)
+        torch.cuda.synchronize()
+        # the new token of every sequence: reuse the last cached row of each sequence as its content
+        last = torch.arange(batch, device=device) * S + (S - 1)
+        new_rows.append(tuple(t[last].contiguous() for t in (K, V)) +
+                        tuple(None if t is None else t[last].contiguous() for t in prev))
+        layers.append(lay); codes.append((kc, ks)); khat.append(Kh)
+        prev = (Kh, vh[l & 1])
+        del K, V, vc, vs
+    q = synth.random_queries(batch, q_heads, 128, seed=1, dtype="bf16", device=device)
+    scores = torch.empty(batch, q_heads, S, dtype=torch.float32, device=device)
+    folded = args.scores_form == "folded" and B.aquakv_scores_workspace_bytes(layers[-1], batch, q_heads) > 0
+    ws_scores = layers[-1].alloc_scores_workspace(batch, q_heads, device) if folded else torch.empty(16, dtype=torch.uint8, device=device)
+    app = [(layers[0].alloc_codes(batch, device), layers[0].alloc_codes(batch, device), layers[0].alloc_kv(batch, device),
+            layers[0].alloc_kv(batch, device))]
+    ws_app = layers[-1].alloc_workspace(batch, device)
+
+    def score_all():
+        for l, lay in enumerate(layers):
+            B.aquakv_decode_attn_scores(lay, batch, S, q_heads, codes[l][0], codes[l][1], None if l == 0 else khat[l - 1], q,
+                                        0.088388, scores, None, ws_scores)
+
+    def append_all():
+        (kc, ks), (vc, vs), Kh, Vh = app[0]
+        for l, lay in enumerate(layers):
+            Kn, Vn, Kp, Vp = new_rows[l]
+            B.aquakv_encode_layer(lay, batch, Kn, Vn, Kp, Vp, kc, ks, vc, vs, Kh, Vh, ws_app)
+
+    for _ in range(args.warmup):
+        score_all(); append_all()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        score_all(); append_all()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    phases = {}
+    for name, fn in (("scores", score_all), ("append", append_all)):
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(max(1, min(args.steps, 5))):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        phases[name] = a.elapsed_time(b) / max(1, min(args.steps, 5))
+    # scoring call of one predicted layer: read Khat_prev, codes, scales; write the scores
+    pred_layers = L - 1
+    call_bytes = T * (1024 * 2 + 8 * (layers[-1].code_bytes_per_group + 2)) + batch * q_heads * S * 4
+    a, b = ev(), ev()
+    reps = max(1, min(args.steps, 5))
+    a.record()
+    for _ in range(reps):
+        for l in range(1, L):
+            B.aquakv_decode_attn_scores(layers[l], batch, S, q_heads, codes[l][0], codes[l][1], khat[l - 1], q, 0.088388,
+                                        scores, None, ws_scores)
+    b.record()
+    torch.cuda.synchronize()
+    call_ms = a.elapsed_time(b) / (reps * pred_layers)
+    gbs = call_bytes / (call_ms * 1e-3) / 1e9
+    return {
+        "metric": "decode read path: cached tokens scored per second per layer at %d bits/value" % (n.bit_length() // 2),
+        "value": round(T * L / dt, 1), "unit": "tokens/s per layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(1e3 * dt, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"decode-read: {L} layers x {batch} sequences x {S} cached tokens x 8 kv heads x 128, bf16, "
+                               f"n={n}, step = q.k scores ({q_heads} query heads, {args.scores_form} form) over the whole "
+                               f"cache + append of one token per sequence, for every layer",
+                   "tokens": T, "layers": L, "q_heads": q_heads, "batch": batch, "seq_len": S},
+        "phases_ms_per_step": {k: round(v, 3) for k, v in phases.items()},
+        "roofline": {"kernel": "aquakv_decode_attn_scores of a predicted layer (query folding + streaming kernel)"
+                     if folded else "fused_kernel<scores>", "bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None, "launches": reps * pred_layers,
+                     "avg_launch_us": round(1e3 * call_ms, 1), "algorithmic_bytes_per_launch": call_bytes},
+    }
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -225,13 +354,29 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
-    cfg = {"llama3.2-3b": synth.LLAMA32_3B, "llama3.1-8b": synth.LLAMA31_8B, "tiny": synth.TINY}[args.config]
-    q_heads = args.q_heads or {"llama3.2-3b": 24, "llama3.1-8b": 32, "tiny": 8}[args.config]
     device = "cuda:0"
     torch.cuda.set_device(0)
+    if args.config == "decode-read":
+        print(json.dumps(decode_read_path(args, device)))
+        return
+    cfg = {"llama3.2-3b": synth.LLAMA32_3B, "llama3.1-8b": synth.LLAMA31_8B, "llama3.1-70b": synth.LLAMA31_70B,
+           "tiny": synth.TINY}[args.config]
+    if args.layers:
+        cfg = dataclasses.replace(cfg, layers=min(args.layers, cfg.layers))
+    q_heads = args.q_heads or {"llama3.2-3b": 24, "llama3.1-8b": 32, "llama3.1-70b": 64, "tiny": 8}[args.config]
     T = cfg.tokens
+    if args.config == "llama3.1-70b":
+        # grid of 16 or 64 points per layer by a seeded fair coin (2 or 3 code bits per value, 2.5 on average)
+        coin = np.random.Generator(np.random.PCG64(synth.BASE_SEED + 99)).integers(0, 2, size=cfg.layers)
+        n_per_layer = [16 if c == 0 else 64 for c in coin]
+        bits_label = "%.2f (grid of 16 or 64 points per layer)" % (sum(n.bit_length() // 2 for n in n_per_layer) / cfg.layers)
+        grid_label = "n=16|64 per layer"
+    else:
+        n_per_layer = [args.n_codewords] * cfg.layers
+        bits_label = "%d" % (args.n_codewords.bit_length() // 2)
+        grid_label = f"n={args.n_codewords}"
 
-    layers, Ks, Vs = build_workload(cfg, device, args.n_codewords)
+    layers, Ks, Vs = build_workload(cfg, device, n_per_layer)
     buf = Buffers(layers, T, q_heads, device, args.scores_form)
     q = synth.random_queries(1, q_heads, cfg.head_dim, seed=1, dtype=cfg.dtype, device=device)
 
@@ -268,12 +413,12 @@ def main():
                     "algorithmic_hbm_frac": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
 
     line = {
-        "metric": "KV encode+decode tokens/s per layer at %d bits/value" % (args.n_codewords.bit_length() // 2),
+        "metric": "KV encode+decode tokens/s per layer at %s bits/value" % bits_label,
         "value": round(value, 1), "unit": "tokens/s per layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.layers} layers x {T} tokens x {cfg.kv_heads} kv heads x {cfg.head_dim}, "
-                               f"{cfg.dtype}, n={args.n_codewords} codewords (p=2), step = encode + decode + q.k scores "
+                               f"{cfg.dtype}, {grid_label} codewords (p=2), step = encode + decode + q.k scores "
                                f"({q_heads} query heads) of every layer",
                    "tokens": T, "layers": cfg.layers, "q_heads": q_heads},
         "phases_ms_per_step": {k: round(v, 3) for k, v in phases.items()},

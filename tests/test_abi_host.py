@@ -111,3 +111,19 @@ def test_bad_call_arguments_are_rejected_without_launching():
     assert status_of(B.aquakv_decode_attn_scores, L, 2, 16, 128, *sc, (FAKE, 1 << 30)) == B.AQUAKV_EINVAL  # > 8x
     assert status_of(B.aquakv_decode_attn_scores, L32, 2, 16, 32, *sc, (FAKE, 16)) == B.AQUAKV_EWORKSPACE
     B.aquakv_decode_attn_scores(L, 0, 16, 32, *sc, None)
+
+
+def test_scores_workspace_query():
+    """aquakv_scores_workspace_bytes: nonzero exactly where the folded scoring form exists (bf16, 8 kv heads,
+    key predictor with 1024 inputs, at most 32 query heads), linear in the batch."""
+    L = layer()
+    per_batch = 8 * 2 * 8 * 1024 + 32 * 128 * 4 + 32 * 4      # operands of W^T q, rotated queries, q . b
+    assert B.aquakv_scores_workspace_bytes(L, 1, 32) == per_batch
+    assert B.aquakv_scores_workspace_bytes(L, 64, 24) == 64 * per_batch
+    assert per_batch % 16 == 0
+    assert B.aquakv_scores_workspace_bytes(L, 1, 64) == 0                                   # more than 32 query heads
+    assert B.aquakv_scores_workspace_bytes(L, 0, 32) == 0
+    assert B.aquakv_scores_workspace_bytes(layer(dtype=B.AQUAKV_FP32), 1, 32) == 0
+    assert B.aquakv_scores_workspace_bytes(layer(kv_heads=4), 1, 32) == 0
+    assert B.aquakv_scores_workspace_bytes(layer(d_in_k=0, d_in_v=0, w_k=None, w_v=None), 1, 32) == 0   # layer 0
+    assert B.aquakv_scores_workspace_bytes(layer(head_dim=64), 1, 32) == 0                  # invalid layer
