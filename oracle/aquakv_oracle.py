@@ -36,6 +36,10 @@ notes of the repository):
     the rounded tensor that feeds the value predictor and the next layer.
   * layer 0 has no predictor: the prediction is zero and the tensors are
     quantized like any other residual.
+  * rotary embedding (Sect. 3.3 "Positional embeddings": keys are compressed
+    before it): when scoring, the decoded key of token t is rotated by position
+    t, coordinate d paired with d + g/2, angles from caller-supplied cos / sin
+    tables; the query is taken as already rotated.
 
 Pins (tests/test_oracle_pins.py): Hadamard orthogonality and Parseval, the
 Kronecker recursion, fast-butterfly agreement, inverse round trip, exact
@@ -46,7 +50,9 @@ the paper's "2-bit explains about 0.89 of the variance" and the textbook
 Lloyd-Max / rate-distortion bounds, bit accounting 2 + 16/1024 = 2.02 and the
 predictor storage sizes of Table 1, bf16 / fp16 rounding against torch's
 conversions, the predictor against identity / zero weights, closed loop
-decode(encode(x)), and the score identity q . iRHT(z) = RHT'(q) . z.
+decode(encode(x)), the score identity q . iRHT(z) = RHT'(q) . z, and for the
+rotary embedding: identity at position 0, norm preservation, the complex
+multiplication form, and scores that depend only on the position difference.
 No function here is "parity unpinned".
 """
 from __future__ import annotations
@@ -337,12 +343,36 @@ def decode_layer(layer: Layer, k_codes, k_scales, v_codes, v_scales, Khat_prev=N
     return Khat, Vhat
 
 
-def attn_scores(layer: Layer, batch: int, seq_len: int, q, k_codes, k_scales, Khat_prev=None, score_scale=1.0):
+def rope_tables(seq_len: int, head_dim: int, base: float = 10000.0):
+    """cos / sin of the rotary angles, [seq_len, head_dim/2]: angle(t, i) = t * base^(-2i/head_dim)
+    (RoFormer; what the models of Sect. 4 of the paper use), rounded to fp32 like the tables a caller passes."""
+    half = head_dim // 2
+    inv_freq = base ** (-np.arange(half, dtype=np.float64) * 2.0 / head_dim)
+    ang = np.arange(seq_len, dtype=np.float64)[:, None] * inv_freq[None, :]
+    return round_fp32(np.cos(ang)), round_fp32(np.sin(ang))
+
+
+def apply_rope(x, cos, sin):
+    """Rotary embedding of x[..., t, :, g] by per-token tables cos, sin [t, g/2]: coordinate pairs (d, d + g/2)
+    are rotated by the token's angle (the "rotate half" pairing of the model implementation the paper runs on,
+    Sect. 4.3): x'_d = x_d cos - x_{d+g/2} sin, x'_{d+g/2} = x_{d+g/2} cos + x_d sin."""
+    x = np.asarray(x, dtype=np.float64)
+    half = x.shape[-1] // 2
+    c = np.asarray(cos, dtype=np.float64)[:, None, :]
+    s_ = np.asarray(sin, dtype=np.float64)[:, None, :]
+    lo, hi = x[..., :half], x[..., half:]
+    return np.concatenate([lo * c - hi * s_, hi * c + lo * s_], axis=-1)
+
+
+def attn_scores(layer: Layer, batch: int, seq_len: int, q, k_codes, k_scales, Khat_prev=None, score_scale=1.0, rope=None):
     """scores[b, qh, t] = score_scale * q[b, qh, :] . Khat[b, t, kvh(qh), :].
 
     Khat is the storage-rounded reconstruction of Alg. "decode" for the keys;
-    query head qh reads kv head qh // (q_heads // kv_heads); no rotary embedding.
+    query head qh reads kv head qh // (q_heads // kv_heads).
     q: [batch, q_heads, g]; codes/scales/Khat_prev are [batch*seq_len, H, ...].
+    rope = (cos, sin), each [seq_len, g/2]: the cache holds keys from before the rotary embedding
+    (Sect. 3.3 "Positional embeddings"), so the key of token t is rotated by position t after decoding
+    and before the dot product; q is taken as already rotated.  None: no rotary embedding.
     """
     q = np.asarray(q, dtype=np.float64)
     T = batch * seq_len
@@ -353,6 +383,8 @@ def attn_scores(layer: Layer, batch: int, seq_len: int, q, k_codes, k_scales, Kh
     Khat = round_storage(dequantize(k_idx, np.asarray(k_scales).reshape(T, -1), layer.signs_k, layer.codebook) + P_k,
                          layer.dtype)
     Khat = Khat.reshape(batch, seq_len, layer.kv_heads, layer.head_dim)
+    if rope is not None:
+        Khat = apply_rope(Khat, rope[0], rope[1])
     q_heads = q.shape[1]
     rep = q_heads // layer.kv_heads
     out = np.empty((batch, q_heads, seq_len))

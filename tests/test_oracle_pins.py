@@ -319,3 +319,57 @@ def test_scores_second_route_and_gqa_mapping(grid16):
     # a query that lives in one head only sees that head's keys
     Khat = e["Khat"].reshape(B, S, H, g)
     assert np.allclose(sc[0, 5, 3], 0.25 * q[0, 5] @ Khat[0, 3, 1], atol=1e-12)
+
+
+# ------------------------------------------------------------------ rotary embedding of the decoded keys
+def test_rope_is_a_rotation_by_the_token_angle():
+    g, S = 128, 37
+    cos, sin = O.rope_tables(S, g)
+    assert cos.shape == (S, g // 2) and np.all(cos[0] == 1.0) and np.all(sin[0] == 0.0)
+    # the first frequency is 1 radian per position, the last one base^(-(g-2)/g)
+    assert abs(cos[5, 0] - math.cos(5.0)) < 1e-7 and abs(sin[5, 0] - math.sin(5.0)) < 1e-7
+    assert abs(sin[9, g // 2 - 1] - math.sin(9.0 * 10000.0 ** (-(g - 2) / g))) < 1e-7
+    x = rng(31).standard_normal((S, 3, g))
+    y = O.apply_rope(x, cos, sin)
+    assert np.array_equal(y[0], x[0])                                         # position 0: identity
+    # a rotation: norms are kept (up to the fp32 rounding of the tables)
+    assert np.allclose(np.linalg.norm(y, axis=-1), np.linalg.norm(x, axis=-1), rtol=1e-6)
+    # complex form: (x_d + i x_{d+g/2}) * exp(i angle)
+    z = (x[..., : g // 2] + 1j * x[..., g // 2:]) * (cos + 1j * sin)[:, None, :]
+    assert np.allclose(y[..., : g // 2], z.real, atol=1e-12) and np.allclose(y[..., g // 2:], z.imag, atol=1e-12)
+    # transposed operand check: rotating by the negative angle undoes it
+    back = O.apply_rope(y, cos, -sin)
+    assert np.allclose(back, x, atol=1e-6)
+
+
+def test_rope_scores_depend_on_the_position_difference_only(grid16):
+    """(R_s q) . (R_t k) = (R_{s+d} q) . (R_{t+d} k): scoring keys that were cached before the rotary
+    embedding at positions t and t + d with a query rotated for s and s + d gives the same number."""
+    H, g, S, QH, d = 2, 128, 12, 4, 7
+    lay = _layer(H=H, g=g, dtype="fp32")
+    K = O.round_fp32(rng(41).standard_normal((S, H, g)))
+    e = O.encode_layer(lay, K, K.copy())
+    cos, sin = O.rope_tables(S + d + 1, g)
+    # exact angle tables for the algebra (the fp32-rounded ones would add 1e-7 noise)
+    ang = np.arange(S + d + 1)[:, None] * (10000.0 ** (-np.arange(g // 2) * 2.0 / g))[None, :]
+    cos, sin = np.cos(ang), np.sin(ang)
+    q = rng(42).standard_normal((1, QH, g))
+    s = 5
+
+    def rotated_query(pos):
+        return O.apply_rope(np.repeat(q, 1, axis=0).transpose(1, 0, 2), cos[pos:pos + 1].repeat(QH, 0), sin[pos:pos + 1].repeat(QH, 0)
+                            ).transpose(1, 0, 2)
+
+    a = O.attn_scores(lay, 1, S, rotated_query(s), e["k_codes"], e["k_scales"], rope=(cos[:S], sin[:S]))
+    b = O.attn_scores(lay, 1, S, rotated_query(s + d), e["k_codes"], e["k_scales"], rope=(cos[d:d + S], sin[d:d + S]))
+    assert np.allclose(a, b, rtol=0, atol=1e-10)
+    # and with all angles zero it is the plain score
+    plain = O.attn_scores(lay, 1, S, q, e["k_codes"], e["k_scales"])
+    same = O.attn_scores(lay, 1, S, q, e["k_codes"], e["k_scales"], rope=(np.ones((S, g // 2)), np.zeros((S, g // 2))))
+    assert np.array_equal(plain, same)
+    # relative-position form, one entry by hand: q . R_{t-s} k
+    t, qh = 9, 3
+    Khat = e["Khat"].reshape(S, H, g)
+    k = Khat[t, qh // (QH // H)]
+    kr = O.apply_rope(k[None, None, :], cos[t - s:t - s + 1], sin[t - s:t - s + 1])[0, 0]
+    assert abs(a[0, qh, t] - q[0, qh] @ kr) < 1e-10
