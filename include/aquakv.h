@@ -186,6 +186,24 @@ int aquakv_decode_attn_scores(const aquakv_layer* layer, int32_t batch, int32_t 
                               float* scores, void* Khat_out,
                               void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * aquakv_decode_attn_scores_rope -- the same call for caches that hold the keys from BEFORE the
+ * rotary positional embedding (Sect. 3.3 "Positional embeddings": predictors and quantizer work
+ * best there).  The decoded (storage-rounded) key of token t of every sequence is rotated by
+ * position t before the dot product: coordinate d is paired with d + g/2,
+ *   k'_d = k_d cos[t, d] - k_{d+g/2} sin[t, d],   k'_{d+g/2} = k_{d+g/2} cos[t, d] + k_d sin[t, d],
+ * rope_cos / rope_sin: device, fp32 [seq_len, g/2], 16-byte aligned, owned by the caller (any
+ * frequency base or scaling).  q must already be rotated for its own position.  Khat_out
+ * (nullable) receives the UNROTATED keys, which is what the next layer's predictor reads.
+ * Always recomputes the prediction (the folded form does not commute with a per-token rotation).
+ */
+int aquakv_decode_attn_scores_rope(const aquakv_layer* layer, int32_t batch, int32_t seq_len, int32_t q_heads,
+                                   const uint8_t* k_codes, const uint16_t* k_scales,
+                                   const void* Khat_prev, const void* q,
+                                   const float* rope_cos, const float* rope_sin, float score_scale,
+                                   float* scores, void* Khat_out,
+                                   void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

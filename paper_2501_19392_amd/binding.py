@@ -32,7 +32,7 @@ EXPORTS = [
     "aquakv_search_table_bytes", "aquakv_build_search_table",
     "aquakv_predict", "aquakv_quantize", "aquakv_dequantize",
     "aquakv_encode_layer", "aquakv_decode_layer", "aquakv_decode_attn_scores",
-    "aquakv_scores_workspace_bytes",
+    "aquakv_scores_workspace_bytes", "aquakv_decode_attn_scores_rope",
 ]
 
 
@@ -68,8 +68,10 @@ _lib.aquakv_encode_layer.argtypes = [_LP, ctypes.c_int64] + [_P] * 11 + [ctypes.
 _lib.aquakv_decode_layer.argtypes = [_LP, ctypes.c_int64] + [_P] * 9 + [ctypes.c_size_t, _P]
 _lib.aquakv_decode_attn_scores.argtypes = ([_LP, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _P, _P, _P, _P,
                                             ctypes.c_float, _P, _P, _P, ctypes.c_size_t, _P])
+_lib.aquakv_decode_attn_scores_rope.argtypes = ([_LP, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _P, _P, _P, _P, _P, _P,
+                                                 ctypes.c_float, _P, _P, _P, ctypes.c_size_t, _P])
 for _n in ("aquakv_predict", "aquakv_quantize", "aquakv_dequantize", "aquakv_encode_layer", "aquakv_decode_layer",
-           "aquakv_decode_attn_scores"):
+           "aquakv_decode_attn_scores", "aquakv_decode_attn_scores_rope"):
     getattr(_lib, _n).restype = ctypes.c_int
 
 
@@ -245,6 +247,15 @@ def aquakv_decode_layer(layer, tokens: int, k_codes, k_scales, v_codes, v_scales
     _check(_lib.aquakv_decode_layer(_layer_ref(layer), tokens, _ptr(k_codes), _ptr(k_scales), _ptr(v_codes),
                                     _ptr(v_scales), _ptr(Khat_prev), _ptr(Vhat_prev), _ptr(Khat), _ptr(Vhat),
                                     ws, nbytes, _stream(stream)))
+
+
+def aquakv_decode_attn_scores_rope(layer, batch: int, seq_len: int, q_heads: int, k_codes, k_scales, Khat_prev, q,
+                                   rope_cos, rope_sin, score_scale: float, scores, Khat_out, workspace, stream=None) -> None:
+    ws, nbytes = _ws(workspace)
+    _check(_lib.aquakv_decode_attn_scores_rope(_layer_ref(layer), batch, seq_len, q_heads, _ptr(k_codes), _ptr(k_scales),
+                                               _ptr(Khat_prev), _ptr(q), _ptr(rope_cos), _ptr(rope_sin),
+                                               ctypes.c_float(score_scale), _ptr(scores), _ptr(Khat_out), ws, nbytes,
+                                               _stream(stream)))
 
 
 def aquakv_decode_attn_scores(layer, batch: int, seq_len: int, q_heads: int, k_codes, k_scales, Khat_prev, q,

@@ -338,10 +338,14 @@ size_t aquakv_scores_workspace_bytes(const aquakv_layer* L, int32_t batch, int32
   return aquakv::folded_scores_workspace_bytes(batch);
 }
 
-int aquakv_decode_attn_scores(const aquakv_layer* L, int32_t batch, int32_t seq_len, int32_t q_heads,
-                              const uint8_t* k_codes, const uint16_t* k_scales, const void* Khat_prev, const void* q,
-                              float score_scale, float* scores, void* Khat_out, void* workspace,
-                              size_t workspace_bytes, void* stream_) {
+}  // extern "C"
+
+namespace {
+// shared body of the two scoring entry points; rope_cos / rope_sin both NULL: no rotary embedding
+int decode_attn_scores(const aquakv_layer* L, int32_t batch, int32_t seq_len, int32_t q_heads, const uint8_t* k_codes,
+                       const uint16_t* k_scales, const void* Khat_prev, const void* q, const float* rope_cos,
+                       const float* rope_sin, float score_scale, float* scores, void* Khat_out, void* workspace,
+                       size_t workspace_bytes, void* stream_) {
   CHECK(check_layer(L));
   if (batch < 0 || seq_len < 0) return fail(AQUAKV_EINVAL, "batch=%d seq_len=%d", batch, seq_len);
   if (q_heads < 1 || q_heads % L->kv_heads || q_heads / L->kv_heads > 8)
@@ -356,7 +360,7 @@ int aquakv_decode_attn_scores(const aquakv_layer* L, int32_t batch, int32_t seq_
   const int64_t tokens = (int64_t)batch * seq_len;
   if (tokens == 0) return AQUAKV_OK;
   const Plan pl = make_plan(L, tokens);
-  if (has_k && pl.fused && Khat_out == nullptr && workspace != nullptr &&
+  if (has_k && pl.fused && Khat_out == nullptr && rope_cos == nullptr && workspace != nullptr &&
       aquakv::folded_scores_supported(L->kv_heads, L->d_in_k, q_heads) &&
       workspace_bytes >= aquakv::folded_scores_workspace_bytes(batch)) {
     // predictor folded into the query: Khat_prev and the codes are read once, nothing is recomputed
@@ -370,7 +374,7 @@ int aquakv_decode_attn_scores(const aquakv_layer* L, int32_t batch, int32_t seq_
     // one fused launch over all rows: prediction, inverse quantizer and dot products
     HIP_TRY(aquakv::launch_fused_scores(L->n_codewords, Khat_prev, L->d_in_k, L->w_k, L->b_k, L->signs_k, L->codebook,
                                         k_codes, k_scales, q, score_scale, scores, Khat_out, seq_len, q_heads, tokens,
-                                        pl.D, static_cast<hipStream_t>(stream_)));
+                                        pl.D, rope_cos, rope_sin, static_cast<hipStream_t>(stream_)));
     return AQUAKV_OK;
   }
   if (has_k) {
@@ -390,9 +394,31 @@ int aquakv_decode_attn_scores(const aquakv_layer* L, int32_t batch, int32_t seq_
     HIP_TRY(aquakv::launch_attn_scores(L->dtype, L->n_codewords, static_cast<const uint8_t*>(at(k_codes, r0, pl.code_row)),
                                        static_cast<const uint16_t*>(at(k_scales, r0, srow)), has_k ? Pbuf : nullptr,
                                        L->signs_k, L->codebook, q, score_scale, scores, at(Khat_out, r0, row), r0, n,
-                                       seq_len, L->kv_heads, q_heads, stream));
+                                       seq_len, L->kv_heads, q_heads, rope_cos, rope_sin, stream));
   }
   return AQUAKV_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int aquakv_decode_attn_scores(const aquakv_layer* L, int32_t batch, int32_t seq_len, int32_t q_heads,
+                              const uint8_t* k_codes, const uint16_t* k_scales, const void* Khat_prev, const void* q,
+                              float score_scale, float* scores, void* Khat_out, void* workspace,
+                              size_t workspace_bytes, void* stream_) {
+  return decode_attn_scores(L, batch, seq_len, q_heads, k_codes, k_scales, Khat_prev, q, nullptr, nullptr, score_scale,
+                            scores, Khat_out, workspace, workspace_bytes, stream_);
+}
+
+int aquakv_decode_attn_scores_rope(const aquakv_layer* L, int32_t batch, int32_t seq_len, int32_t q_heads,
+                                   const uint8_t* k_codes, const uint16_t* k_scales, const void* Khat_prev,
+                                   const void* q, const float* rope_cos, const float* rope_sin, float score_scale,
+                                   float* scores, void* Khat_out, void* workspace, size_t workspace_bytes,
+                                   void* stream_) {
+  CHECK(check_ptr(rope_cos, "rope_cos", true));
+  CHECK(check_ptr(rope_sin, "rope_sin", true));
+  return decode_attn_scores(L, batch, seq_len, q_heads, k_codes, k_scales, Khat_prev, q, rope_cos, rope_sin, score_scale,
+                            scores, Khat_out, workspace, workspace_bytes, stream_);
 }
 
 }  // extern "C"

@@ -90,7 +90,7 @@ __global__ __launch_bounds__(kThreads) void attn_scores_kernel(
     const uint8_t* __restrict__ codes, const uint16_t* __restrict__ scales, const float* __restrict__ P,
     const int8_t* __restrict__ signs, const float* __restrict__ codebook, const T* __restrict__ qv_,
     float score_scale, float* __restrict__ scores, T* __restrict__ Khat_out, int64_t row0, int64_t n_groups,
-    int seq_len, int H, int q_heads) {
+    int seq_len, int H, int q_heads, const float* __restrict__ rope_cos, const float* __restrict__ rope_sin) {
   __shared__ float4 cb[NCW];
   load_codebook<NCW>(codebook, cb);
   __syncthreads();
@@ -119,6 +119,7 @@ __global__ __launch_bounds__(kThreads) void attn_scores_kernel(
     if (Khat_out != nullptr && active) Storage<T>::store32(Khat_out + off, z);
 #pragma unroll
     for (int r = 0; r < 32; ++r) z[r] = Storage<T>::round(z[r]);      // score the stored keys
+    if (rope_cos != nullptr) rope128(z, q, rope_cos + t * (kGroup / 2), rope_sin + t * (kGroup / 2));   // cached before RoPE
 
     for (int r = 0; r < rep; ++r) {
       const int qh = head * rep + r;
@@ -233,13 +234,13 @@ hipError_t launch_dequantize(int dtype, int n_codewords, const uint8_t* codes, c
 hipError_t launch_attn_scores(int dtype, int n_codewords, const uint8_t* codes, const uint16_t* scales, const float* P,
                               const int8_t* signs, const float* codebook, const void* q, float score_scale,
                               float* scores, void* Khat_out, int64_t row0, int64_t rows, int seq_len, int H,
-                              int q_heads, hipStream_t stream) {
+                              int q_heads, const float* rope_cos, const float* rope_sin, hipStream_t stream) {
   const int64_t n_groups = rows * H;
   if (n_groups == 0) return hipSuccess;
   AQUAKV_DISPATCH(dtype, n_codewords,
                   (attn_scores_kernel<T, N><<<blocks_for(n_groups), kThreads, 0, stream>>>(
                       codes, scales, P, signs, codebook, static_cast<const T*>(q), score_scale, scores,
-                      static_cast<T*>(Khat_out), row0, n_groups, seq_len, H, q_heads)));
+                      static_cast<T*>(Khat_out), row0, n_groups, seq_len, H, q_heads, rope_cos, rope_sin)));
   return hipGetLastError();
 }
 

@@ -194,4 +194,20 @@ __device__ __forceinline__ void reconstruct(float (&z)[32], int q, const uint32_
   }
 }
 
+// Rotary embedding (RoFormer) of the 32 coordinates this lane holds of a 128-long head vector.  Coordinate d is
+// paired with d + 64, which is the same register of lane q ^ 2; `cos_t` / `sin_t` point at the 64 angles of the
+// token's position.  x'_d = x_d cos - x_{d+64} sin,  x'_{d+64} = x_{d+64} cos + x_d sin.
+__device__ __forceinline__ void rope128(float (&v)[32], int q, const float* __restrict__ cos_t,
+                                        const float* __restrict__ sin_t) {
+  float c[32], s[32];
+  load32_f32(cos_t + 32 * (q & 1), c);
+  load32_f32(sin_t + 32 * (q & 1), s);
+  const float sgn = (q & 2) ? 1.0f : -1.0f;
+#pragma unroll
+  for (int r = 0; r < 32; ++r) {
+    const float partner = quad_xor<2>(v[r]);
+    v[r] = __fmaf_rn(v[r], c[r], sgn * (partner * s[r]));
+  }
+}
+
 }  // namespace aquakv

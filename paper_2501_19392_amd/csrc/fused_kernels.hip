@@ -41,7 +41,7 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
     const float* __restrict__ bias, const int8_t* __restrict__ signs, const float* __restrict__ codebook,
     const uint32_t* __restrict__ table, const bf16_t* X, uint8_t* codes, uint16_t* scales, bf16_t* Xhat,
     const bf16_t* __restrict__ qv, float score_scale, float* __restrict__ scores, int seq_len, int q_heads, int64_t T,
-    int D) {
+    int D, const float* __restrict__ rope_cos, const float* __restrict__ rope_sin) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[kFusedLdsBytes];
   Lds& cl = *reinterpret_cast<Lds*>(smem + kPredBytes);
   const bool use_table = MODE == kEncode && table != nullptr;
@@ -169,6 +169,7 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
         for (int r = 0; r < 32; ++r) v[r] = Storage<bf16_t>::round(v[r]);      // score the stored keys
         const int rep = q_heads / H;
         const int64_t b = rowc / seq_len, t = rowc % seq_len;
+        if (rope_cos != nullptr) rope128(v, q, rope_cos + t * (kGroup / 2), rope_sin + t * (kGroup / 2));   // cached before RoPE
         for (int r = 0; r < rep; ++r) {
           const int qh = head * rep + r;
           float qf[32];
@@ -193,7 +194,7 @@ template <int MODE>
 hipError_t launch(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W, const float* bias,
                   const int8_t* signs, const float* codebook, const void* table, const void* X, uint8_t* codes,
                   uint16_t* scales, void* Xhat, const void* q, float score_scale, float* scores, int seq_len,
-                  int q_heads, int64_t T, int D, hipStream_t stream) {
+                  int q_heads, int64_t T, int D, const float* rope_cos, const float* rope_sin, hipStream_t stream) {
   if (T == 0) return hipSuccess;
   const unsigned blocks = (unsigned)(((T + BM - 1) / BM) * (D / BN));
   // 8 wavefronts per tile (two per SIMD): the main loop is bound by L2 -> LDS traffic either
@@ -207,7 +208,8 @@ hipError_t launch(int n_codewords, const void* x0, int d0, const void* x1, int d
   fused_kernel<N, MODE, kWaves><<<blocks, kWaves * 64, 0, stream>>>(                                             \
       static_cast<const bf16_t*>(x0), d0, static_cast<const bf16_t*>(x1), d1, static_cast<const bf16_t*>(W), bias, \
       signs, codebook, static_cast<const uint32_t*>(table), static_cast<const bf16_t*>(X), codes, scales,         \
-      static_cast<bf16_t*>(Xhat), static_cast<const bf16_t*>(q), score_scale, scores, seq_len, q_heads, T, D)
+      static_cast<bf16_t*>(Xhat), static_cast<const bf16_t*>(q), score_scale, scores, seq_len, q_heads, T, D, rope_cos,  \
+      rope_sin)
   if (n_codewords == 16) AQUAKV_FUSED(16);
   else if (n_codewords == 64) AQUAKV_FUSED(64);
   else AQUAKV_FUSED(256);
@@ -222,7 +224,7 @@ hipError_t launch_fused_encode(int n_codewords, const void* x0, int d0, const vo
                                const void* X, uint8_t* codes, uint16_t* scales, void* Xhat, int64_t T, int D,
                                hipStream_t stream) {
   return launch<kEncode>(n_codewords, x0, d0, x1, d1, W, bias, signs, codebook, table, X, codes, scales, Xhat, nullptr,
-                         0.f, nullptr, 1, 1, T, D, stream);
+                         0.f, nullptr, 1, 1, T, D, nullptr, nullptr, stream);
 }
 
 hipError_t launch_fused_decode(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W,
@@ -230,16 +232,17 @@ hipError_t launch_fused_decode(int n_codewords, const void* x0, int d0, const vo
                                const uint16_t* scales, void* Xhat, int64_t T, int D, hipStream_t stream) {
   return launch<kDecode>(n_codewords, x0, d0, x1, d1, W, bias, signs, codebook, nullptr, nullptr,
                          const_cast<uint8_t*>(codes), const_cast<uint16_t*>(scales), Xhat, nullptr, 0.f, nullptr, 1, 1,
-                         T, D, stream);
+                         T, D, nullptr, nullptr, stream);
 }
 
 hipError_t launch_fused_scores(int n_codewords, const void* x0, int d0, const void* W, const float* bias,
                                const int8_t* signs, const float* codebook, const uint8_t* codes,
                                const uint16_t* scales, const void* q, float score_scale, float* scores, void* Khat_out,
-                               int seq_len, int q_heads, int64_t T, int D, hipStream_t stream) {
+                               int seq_len, int q_heads, int64_t T, int D, const float* rope_cos, const float* rope_sin,
+                               hipStream_t stream) {
   return launch<kScores>(n_codewords, x0, d0, nullptr, 0, W, bias, signs, codebook, nullptr, nullptr,
                          const_cast<uint8_t*>(codes), const_cast<uint16_t*>(scales), Khat_out, q, score_scale, scores,
-                         seq_len, q_heads, T, D, stream);
+                         seq_len, q_heads, T, D, rope_cos, rope_sin, stream);
 }
 
 }  // namespace aquakv

@@ -28,10 +28,11 @@ hipError_t launch_dequantize(int dtype, int n_codewords, const uint8_t* codes, c
 
 // scores[b, qh, t] for rows [row0, row0 + rows) of the flattened [batch*seq_len] axis.
 // codes/scales/P/Khat_out point at row `row0`; q and scores at their tensor bases.
+// rope_cos / rope_sin (nullable, fp32 [seq_len, 64]): rotate the decoded key of token t by position t first.
 hipError_t launch_attn_scores(int dtype, int n_codewords, const uint8_t* codes, const uint16_t* scales, const float* P,
                               const int8_t* signs, const float* codebook, const void* q, float score_scale,
                               float* scores, void* Khat_out, int64_t row0, int64_t rows, int seq_len, int H,
-                              int q_heads, hipStream_t stream);
+                              int q_heads, const float* rope_cos, const float* rope_sin, hipStream_t stream);
 
 // Fused bf16 forms: prediction [x0 | x1] W^T + bias on the matrix cores, consumed in the same
 // kernel by the quantizer (encode), its inverse (decode) or its inverse plus q.k (scores).
@@ -45,7 +46,8 @@ hipError_t launch_fused_decode(int n_codewords, const void* x0, int d0, const vo
 hipError_t launch_fused_scores(int n_codewords, const void* x0, int d0, const void* W, const float* bias,
                                const int8_t* signs, const float* codebook, const uint8_t* codes,
                                const uint16_t* scales, const void* q, float score_scale, float* scores, void* Khat_out,
-                               int seq_len, int q_heads, int64_t T, int D, hipStream_t stream);
+                               int seq_len, int q_heads, int64_t T, int D, const float* rope_cos, const float* rope_sin,
+                               hipStream_t stream);
 
 // Scores with the key predictor folded into the query (bf16, 8 kv heads, 1024 predictor inputs,
 // q_heads <= 32): reads Khat_prev and the codes once.  `workspace`: folded_scores_workspace_bytes(batch).

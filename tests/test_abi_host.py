@@ -111,6 +111,12 @@ def test_bad_call_arguments_are_rejected_without_launching():
     assert status_of(B.aquakv_decode_attn_scores, L, 2, 16, 128, *sc, (FAKE, 1 << 30)) == B.AQUAKV_EINVAL  # > 8x
     assert status_of(B.aquakv_decode_attn_scores, L32, 2, 16, 32, *sc, (FAKE, 16)) == B.AQUAKV_EWORKSPACE
     B.aquakv_decode_attn_scores(L, 0, 16, 32, *sc, None)
+    # rotary form: both tables are required and must be aligned
+    rp = [FAKE, FAKE, FAKE, FAKE]   # k_codes k_scales Khat_prev q
+    assert status_of(B.aquakv_decode_attn_scores_rope, L, 2, 16, 32, *rp, None, FAKE, 1.0, FAKE, None, (FAKE, 1 << 30)) == B.AQUAKV_ENULL
+    assert status_of(B.aquakv_decode_attn_scores_rope, L, 2, 16, 32, *rp, FAKE, FAKE + 4, 1.0, FAKE, None, (FAKE, 1 << 30)) == B.AQUAKV_EALIGN
+    assert status_of(B.aquakv_decode_attn_scores_rope, L, 2, 16, 12, *rp, FAKE, FAKE, 1.0, FAKE, None, (FAKE, 1 << 30)) == B.AQUAKV_EINVAL
+    B.aquakv_decode_attn_scores_rope(L, 0, 16, 32, *rp, FAKE, FAKE, 1.0, FAKE, None, None)
 
 
 def test_scores_workspace_query():

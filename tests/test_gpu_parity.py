@@ -439,6 +439,50 @@ def test_folded_scores_against_definition(B, n, QH, batch, S, bias):
     assert np.all(np.abs(U.np64(sc2) - want2) <= U.RTOL["bf16"] * 0.25 * mag2 + 1e-30)
 
 
+@pytest.mark.parametrize("dtype,n,with_pred", [("bf16", 16, True), ("bf16", 64, False), ("fp32", 16, True)])
+def test_attn_scores_with_rotary_embedding(B, dtype, n, with_pred):
+    """aquakv_decode_attn_scores_rope: keys cached before the rotary embedding are rotated by their position
+    after decoding (fused kernel with predictor, stand-alone kernel for layer 0 and fp32); Khat_out stays unrotated."""
+    print(f"case rope scores dtype={dtype} n={n} pred={with_pred}", flush=True)
+    H, QH, batch, S = (8, 32, 2, 300) if dtype == "bf16" else (2, 8, 2, 70)
+    cfg = synth.Config("rope", layers=2, kv_heads=H, head_dim=128, tokens=batch * S, dtype=dtype, n_codewords=n)
+    Ks, Vs, lo_l, lg_l = build_stack(cfg)
+    out = run_gpu_layers(B, cfg, lg_l, Ks, Vs)
+    l = 1 if with_pred else 0
+    g, lg, lo = out[l], lg_l[l], lo_l[l]
+    q = synth.random_queries(batch, QH, 128, seed=78, dtype=dtype, device="cuda")
+    cos, sin = O.rope_tables(S, 128, base=500000.0)
+    cos_d = torch.from_numpy(cos.astype(np.float32)).cuda()
+    sin_d = torch.from_numpy(sin.astype(np.float32)).cuda()
+    scores = torch.full((batch, QH, S), float("nan"), dtype=torch.float32, device="cuda")
+    Kout = lg.alloc_kv(cfg.tokens)
+    B.aquakv_decode_attn_scores_rope(lg, batch, S, QH, g["k_codes"], g["k_scales"], g["Kp"], q, cos_d, sin_d, 0.125, scores,
+                                     Kout, lg.alloc_workspace(cfg.tokens))
+    sync()
+    assert torch.equal(bits(Kout), bits(g["Khat"]))                      # unrotated keys out
+    kp = None if g["Kp"] is None else U.np64(g["Kp"])
+    want = O.attn_scores(lo, batch, S, U.np64(q), g["k_codes"].cpu().numpy(), g["k_scales"].cpu().numpy().view(np.float16),
+                         kp, 0.125, rope=(cos, sin))
+    plain = O.attn_scores(lo, batch, S, U.np64(q), g["k_codes"].cpu().numpy(), g["k_scales"].cpu().numpy().view(np.float16),
+                          kp, 0.125)
+    assert np.max(np.abs(want - plain)[:, :, 1:]) > 0.1                   # the rotation matters in this test
+    Kh = np.abs(U.np64(g["Khat"])).reshape(batch, S, H, 128)
+    # a rotation mixes |k_d| and |k_{d+64}|: bound each rotated magnitude by their sum
+    Kh = Kh + np.concatenate([Kh[..., 64:], Kh[..., :64]], axis=-1)
+    mag = np.stack([np.einsum("bd,btd->bt", np.abs(U.np64(q))[:, qh], Kh[:, :, qh // (QH // H)]) for qh in range(QH)], 1)
+    err = np.abs(U.np64(scores) - want)
+    rtol = U.RTOL[dtype]
+    worst = float(np.max(err / (0.125 * mag + 1e-30)))
+    assert np.all(err <= rtol * 0.125 * mag + 1e-30), worst
+    print(f"   worst score error / (sum|q||k|) = {worst:.3g}", flush=True)
+    # position 0 is the identity: the first token of every sequence scores as without rotation
+    s0 = torch.empty_like(scores)
+    small = torch.empty(16, dtype=torch.uint8, device="cuda") if dtype == "bf16" and with_pred else lg.alloc_workspace(cfg.tokens)
+    B.aquakv_decode_attn_scores(lg, batch, S, QH, g["k_codes"], g["k_scales"], g["Kp"], q, 0.125, s0, None, small)
+    sync()
+    assert torch.equal(s0[:, :, 0], scores[:, :, 0])
+
+
 # ------------------------------------------------------------------ full sizes, sampled rows
 def sampled_rows(T, n, seed):
     """Seeded sample of token rows that always includes the first / last rows and both sides
