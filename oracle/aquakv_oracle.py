@@ -22,7 +22,10 @@ notes of the repository):
 
   * RHT: z = H_g (s * r) / sqrt(g), H_g the Sylvester Hadamard matrix in natural
     order, s a fixed +-1 vector per channel; inverse x = s * (H_g z) / sqrt(g).
-    One group = one (token, kv head) vector of g = head_dim values.
+    One group = one (token, kv head) vector of g = head_dim values by default;
+    Layer.rht_group = kv_heads * head_dim gives the grouping of the paper's
+    experiments (Sect. 4.1: groups of 1024, one 16-bit scale per group, hence
+    the 2.02 bits of Table 1): the whole token vector is one group.
   * scale: sigma = sqrt(mean(z^2)) of the rotated group, stored as IEEE fp16
     (round to nearest even, clamped to the largest finite fp16); the group is
     normalised by the *stored* value; a stored zero means the group decodes to 0.
@@ -270,16 +273,35 @@ class Layer:
     b_k: Optional[np.ndarray] = None
     w_v: Optional[np.ndarray] = None     # [D, 2D]     inputs: [Vhat_prev, Khat]
     b_v: Optional[np.ndarray] = None
+    rht_group: Optional[int] = None      # values per rotation group and scale; None => head_dim.
+    #                                      The experiments of Sect. 4.1 run the backbone quantizer with
+    #                                      groups of 1024 = the whole token vector across the kv heads.
 
     @property
     def n_codewords(self):
         return int(np.asarray(self.codebook).shape[0])
 
+    @property
+    def group(self):
+        g = self.head_dim if self.rht_group is None else int(self.rht_group)
+        if (self.kv_heads * self.head_dim) % g:
+            raise ValueError("rht_group must divide kv_heads * head_dim")
+        return g
+
+    @property
+    def groups_per_token(self):
+        return self.kv_heads * self.head_dim // self.group
+
 
 def _as_groups(x, layer: Layer):
+    """[T, ...] -> [T, groups per token, group]: the token vector (kv heads side by side) cut into rotation groups."""
     x = np.asarray(x, dtype=np.float64)
     T = x.shape[0]
-    return x.reshape(T, layer.kv_heads, layer.head_dim)
+    return x.reshape(T, layer.groups_per_token, layer.group)
+
+
+def _group_signs(signs, layer: Layer):
+    return np.asarray(signs, dtype=np.float64).reshape(layer.groups_per_token, layer.group)
 
 
 def _key_prediction(layer: Layer, Khat_prev, T):
@@ -303,7 +325,8 @@ def encode_layer(layer: Layer, K, V, Khat_prev=None, Vhat_prev=None):
     """Alg. "encode", with the reconstructions the inference loop needs next.
 
     K, V: [T, H, g] holding storage-dtype values.  Returns a dict with
-    k_codes/v_codes (uint8 [T, H, g*c/(8p)]), k_scales/v_scales (float16 [T, H]),
+    k_codes/v_codes (uint8 [T, groups per token, group*c/(8p)]), k_scales/v_scales (float16
+    [T, groups per token]; groups per token = H unless the layer sets rht_group),
     Khat/Vhat (fp64 arrays holding storage-dtype values), P_k/P_v, and the
     QuantDiag of both tensors.
     """
@@ -311,18 +334,21 @@ def encode_layer(layer: Layer, K, V, Khat_prev=None, Vhat_prev=None):
     V = _as_groups(V, layer)
     T = K.shape[0]
     n = layer.n_codewords
+    gshape = K.shape                                                      # [T, groups per token, group]
     shape = (T, layer.kv_heads, layer.head_dim)
+    sk, sv = _group_signs(layer.signs_k, layer), _group_signs(layer.signs_v, layer)
 
-    P_k = _key_prediction(layer, Khat_prev, T).reshape(shape)             # K_pred
-    k_idx, k_s16, k_diag = quantize(K - P_k, layer.signs_k, layer.codebook)  # K_q
-    Khat = round_storage(dequantize(k_idx, k_s16, layer.signs_k, layer.codebook) + P_k, layer.dtype)
+    P_k = _key_prediction(layer, Khat_prev, T).reshape(gshape)            # K_pred
+    k_idx, k_s16, k_diag = quantize(K - P_k, sk, layer.codebook)          # K_q
+    Khat = round_storage(dequantize(k_idx, k_s16, sk, layer.codebook) + P_k, layer.dtype)
 
-    P_v = _value_prediction(layer, Vhat_prev, Khat, T).reshape(shape)     # V_pred uses Khat
-    v_idx, v_s16, v_diag = quantize(V - P_v, layer.signs_v, layer.codebook)  # V_q
-    Vhat = round_storage(dequantize(v_idx, v_s16, layer.signs_v, layer.codebook) + P_v, layer.dtype)
+    P_v = _value_prediction(layer, Vhat_prev, Khat, T).reshape(gshape)    # V_pred uses Khat
+    v_idx, v_s16, v_diag = quantize(V - P_v, sv, layer.codebook)          # V_q
+    Vhat = round_storage(dequantize(v_idx, v_s16, sv, layer.codebook) + P_v, layer.dtype)
 
     return dict(k_codes=pack_codes(k_idx, n), k_scales=k_s16, v_codes=pack_codes(v_idx, n), v_scales=v_s16,
-                Khat=Khat, Vhat=Vhat, P_k=P_k, P_v=P_v, k_idx=k_idx, v_idx=v_idx, k_diag=k_diag, v_diag=v_diag)
+                Khat=Khat.reshape(shape), Vhat=Vhat.reshape(shape), P_k=P_k.reshape(shape), P_v=P_v.reshape(shape),
+                k_idx=k_idx, v_idx=v_idx, k_diag=k_diag, v_diag=v_diag)
 
 
 def decode_layer(layer: Layer, k_codes, k_scales, v_codes, v_scales, Khat_prev=None, Vhat_prev=None):
@@ -331,16 +357,16 @@ def decode_layer(layer: Layer, k_codes, k_scales, v_codes, v_scales, Khat_prev=N
     T = k_codes.shape[0]
     n = layer.n_codewords
     shape = (T, layer.kv_heads, layer.head_dim)
-    k_idx = unpack_codes(k_codes.reshape(T, layer.kv_heads, -1), n)
-    v_idx = unpack_codes(np.asarray(v_codes).reshape(T, layer.kv_heads, -1), n)
+    gshape = (T, layer.groups_per_token, layer.group)
+    sk, sv = _group_signs(layer.signs_k, layer), _group_signs(layer.signs_v, layer)
+    k_idx = unpack_codes(k_codes.reshape(T, layer.groups_per_token, -1), n)
+    v_idx = unpack_codes(np.asarray(v_codes).reshape(T, layer.groups_per_token, -1), n)
 
-    P_k = _key_prediction(layer, Khat_prev, T).reshape(shape)
-    Khat = round_storage(dequantize(k_idx, np.asarray(k_scales).reshape(T, -1), layer.signs_k, layer.codebook) + P_k,
-                         layer.dtype)
-    P_v = _value_prediction(layer, Vhat_prev, Khat, T).reshape(shape)
-    Vhat = round_storage(dequantize(v_idx, np.asarray(v_scales).reshape(T, -1), layer.signs_v, layer.codebook) + P_v,
-                         layer.dtype)
-    return Khat, Vhat
+    P_k = _key_prediction(layer, Khat_prev, T).reshape(gshape)
+    Khat = round_storage(dequantize(k_idx, np.asarray(k_scales).reshape(T, -1), sk, layer.codebook) + P_k, layer.dtype)
+    P_v = _value_prediction(layer, Vhat_prev, Khat, T).reshape(gshape)
+    Vhat = round_storage(dequantize(v_idx, np.asarray(v_scales).reshape(T, -1), sv, layer.codebook) + P_v, layer.dtype)
+    return Khat.reshape(shape), Vhat.reshape(shape)
 
 
 def rope_tables(seq_len: int, head_dim: int, base: float = 10000.0):
@@ -377,11 +403,11 @@ def attn_scores(layer: Layer, batch: int, seq_len: int, q, k_codes, k_scales, Kh
     q = np.asarray(q, dtype=np.float64)
     T = batch * seq_len
     n = layer.n_codewords
-    shape = (T, layer.kv_heads, layer.head_dim)
-    k_idx = unpack_codes(np.asarray(k_codes).reshape(T, layer.kv_heads, -1), n)
-    P_k = _key_prediction(layer, Khat_prev, T).reshape(shape)
-    Khat = round_storage(dequantize(k_idx, np.asarray(k_scales).reshape(T, -1), layer.signs_k, layer.codebook) + P_k,
-                         layer.dtype)
+    gshape = (T, layer.groups_per_token, layer.group)
+    k_idx = unpack_codes(np.asarray(k_codes).reshape(T, layer.groups_per_token, -1), n)
+    P_k = _key_prediction(layer, Khat_prev, T).reshape(gshape)
+    Khat = round_storage(dequantize(k_idx, np.asarray(k_scales).reshape(T, -1), _group_signs(layer.signs_k, layer),
+                                    layer.codebook) + P_k, layer.dtype)
     Khat = Khat.reshape(batch, seq_len, layer.kv_heads, layer.head_dim)
     if rope is not None:
         Khat = apply_rope(Khat, rope[0], rope[1])

@@ -373,3 +373,41 @@ def test_rope_scores_depend_on_the_position_difference_only(grid16):
     k = Khat[t, qh // (QH // H)]
     kr = O.apply_rope(k[None, None, :], cos[t - s:t - s + 1], sin[t - s:t - s + 1])[0, 0]
     assert abs(a[0, qh, t] - q[0, qh] @ kr) < 1e-10
+
+
+# ------------------------------------------------------------------ rotation group of 1024 across the kv heads
+def test_group_1024_is_the_papers_accounting_and_a_kronecker_rotation(grid16):
+    """Layer.rht_group = kv_heads * head_dim: the grouping of the paper's experiments (Sect. 4.1)."""
+    H, g, T = 8, 128, 24
+    lay = _layer(H=H, g=g, dtype="fp32", rht_group=H * g)
+    lay128 = _layer(H=H, g=g, dtype="fp32")
+    K = O.round_fp32(rng(51).standard_normal((T, H, g)) * synth.channel_scales(H * g, 0, 0).numpy().reshape(H, g))
+    V = O.round_fp32(rng(52).standard_normal((T, H, g)))
+    e = O.encode_layer(lay, K, V)
+    # one 16-bit scale per 1024 values: 2 + 16/1024 = 2.02 stored bits per value (Table 1)
+    stored_bits = 8.0 * (e["k_codes"][0].size + e["k_scales"][0].size * 2) / (H * g)
+    assert e["k_scales"].shape == (T, 1) and e["k_codes"].shape == (T, 1, 256)
+    assert abs(stored_bits - (2 + 16 / 1024)) < 1e-12 and round(stored_bits, 2) == PAPER["higgs_2bit_gs1024_stored_bits"]
+    # the code bytes are laid out like those of 8 groups of 128 (64 codes = 32 bytes per head)
+    assert O.encode_layer(lay128, K, V)["k_codes"].reshape(T, -1).shape == e["k_codes"].reshape(T, -1).shape
+    # second route to the rotation: H_1024 = H_8 (x) H_128, i.e. rotate inside every head, then across the heads
+    s = lay.signs_k.reshape(H, g).astype(np.float64)
+    inner = np.stack([O.rht(K[:, h, :], s[h]) for h in range(H)], axis=1)              # [T, H, g], each / sqrt(128)
+    across = np.einsum("ab,tbg->tag", O.hadamard(H).astype(np.float64), inner) / math.sqrt(H)
+    assert np.allclose(across.reshape(T, H * g), O.rht(K.reshape(T, H * g), s.reshape(-1)), atol=1e-12)
+    # Parseval and the scale: sigma is the rms of the whole token vector
+    sig = e["k_diag"].sigma.reshape(T)
+    assert np.allclose(sig, np.sqrt(np.mean(K.reshape(T, -1) ** 2, axis=1)), rtol=1e-12)
+    # closed loop and the quantizer's data-free error (a 1024-point rotation gaussianises better than 128)
+    Kd, Vd = O.decode_layer(lay, e["k_codes"], e["k_scales"], e["v_codes"], e["v_scales"])
+    assert np.array_equal(Kd, e["Khat"]) and np.array_equal(Vd, e["Vhat"])
+    rel = np.sum((e["Khat"] - K) ** 2) / np.sum(K ** 2)
+    assert abs(rel - 0.109) < 0.012, rel
+    # scale covariance by a power of two stays exact
+    e2 = O.encode_layer(lay, 4.0 * K, 4.0 * V)
+    assert np.array_equal(e2["k_codes"], e["k_codes"]) and np.array_equal(e2["k_scales"], 4.0 * e["k_scales"].astype(np.float64))
+    # a single-head layer with rht_group = head_dim is the default grouping
+    one = _layer(H=1, g=128, dtype="fp32", rht_group=128)
+    ref = _layer(H=1, g=128, dtype="fp32")
+    a, b = O.encode_layer(one, K[:, :1], V[:, :1]), O.encode_layer(ref, K[:, :1], V[:, :1])
+    assert np.array_equal(a["k_codes"], b["k_codes"]) and np.array_equal(a["Khat"], b["Khat"])
