@@ -42,6 +42,9 @@ def parse():
                     choices=["llama3.2-3b", "llama3.1-8b", "llama3.1-70b", "decode-read", "tiny"],
                     help="llama3.1-70b: 80 layers x 131072 tokens, grid of 16 or 64 points per layer (seeded coin); "
                          "decode-read: 64 sequences x 16384 cached tokens, scoring call + one-token append per layer")
+    ap.add_argument("--rht-group", type=int, default=0, choices=[0, 128, 1024],
+                    help="values per rotation group and scale: 128 (one head, default) or 1024 (the whole token, the "
+                         "grouping of the paper's experiments; predictor and quantizer then run as separate kernels)")
     ap.add_argument("--layers", type=int, default=0, help="use only the first N layers of the configuration (0: all)")
     ap.add_argument("--n-codewords", type=int, default=16)
     ap.add_argument("--q-heads", type=int, default=0, help="query heads for the scoring call (0: model default)")
@@ -69,7 +72,7 @@ def grids_on_device(ns, device):
     return out
 
 
-def build_workload(cfg, device, n_per_layer):
+def build_workload(cfg, device, n_per_layer, rht_group=0):
     import torch
     from paper_2501_19392_amd import binding as B
     from paper_2501_19392_amd import synth
@@ -88,7 +91,8 @@ def build_workload(cfg, device, n_per_layer):
         wk = wv = None
         if l > 0:
             wk, wv = (w.to(device) for w in synth.analytic_predictors(st, l))
-        layers.append(B.Layer(cfg.kv_heads, cfg.head_dim, C, sk, sv, sd, w_k=wk, w_v=wv, search_table=table))
+        layers.append(B.Layer(cfg.kv_heads, cfg.head_dim, C, sk, sv, sd, w_k=wk, w_v=wv, search_table=table,
+                              rht_group=rht_group))
     return layers, Ks, Vs
 
 
@@ -376,7 +380,10 @@ def main():
         bits_label = "%d" % (args.n_codewords.bit_length() // 2)
         grid_label = f"n={args.n_codewords}"
 
-    layers, Ks, Vs = build_workload(cfg, device, n_per_layer)
+    layers, Ks, Vs = build_workload(cfg, device, n_per_layer, args.rht_group)
+    wide = args.rht_group not in (0, cfg.head_dim)
+    if wide:
+        grid_label += f", rotation groups of {args.rht_group} (one scale per token)"
     buf = Buffers(layers, T, q_heads, device, args.scores_form)
     q = synth.random_queries(1, q_heads, cfg.head_dim, seed=1, dtype=cfg.dtype, device=device)
 
@@ -403,10 +410,13 @@ def main():
     if cfg.dtype == "bf16" and not args.no_kernel_events:
         flops, nbytes, ms, launches = encode_kernel_events(B, layers, Ks, Vs, buf, T, max(1, min(args.steps, 3)))
         achieved = flops / (ms * 1e-3) / 1e12
-        roofline = {"kernel": "fused_kernel<encode> (bf16 MFMA predictor + quantizer epilogue)", "bound": "mfma",
+        if wide:
+            launches *= 2
+        roofline = {"kernel": "predict_bf16_kernel + quantize_kernel per tensor (groups across heads are not fused)" if wide
+                    else "fused_kernel<encode> (bf16 MFMA predictor + quantizer epilogue)", "bound": "mfma",
                     "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                    "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, args.n_codewords)), "launches": launches,
+                    "traffic": None if wide else MEASURED_TRAFFIC_BYTES.get((args.config, args.n_codewords)), "launches": launches,
                     "algorithmic_bytes_per_launch": round(nbytes / launches, 1),
                     "avg_launch_us": round(1e3 * ms / launches, 2),
                     "algorithmic_hbm_GBs": round(nbytes / (ms * 1e-3) / 1e9, 1),

@@ -14,7 +14,8 @@
  *     between calls and never synchronises the device: all work is enqueued on
  *     `stream` (a hipStream_t passed as void*; NULL = the default stream) and the
  *     outputs are valid once the stream reaches that point.
- *   - Every device pointer must be 16-byte aligned (AQUAKV_EALIGN otherwise).
+ *   - Every device pointer must be 16-byte aligned (AQUAKV_EALIGN otherwise), except the scale
+ *     arrays, which need 2 bytes (with one scale per token a row range starts at any even address).
  *   - Return value: AQUAKV_OK (0) or a negative aquakv_status.  On a validation
  *     error nothing is launched.  aquakv_last_error() returns a thread-local
  *     text for the most recent failure on the calling thread.
@@ -70,7 +71,15 @@ typedef struct aquakv_layer {
   int32_t d_in_k;       /* inputs of f_key (= width of Khat_prev); 0 = no key
                            predictor (layer 0: prediction is zero)                */
   int32_t d_in_v;       /* inputs of f_value = width of Vhat_prev + D; 0 = none   */
-  int32_t reserved;     /* must be 0                                              */
+  int32_t rht_group;    /* values per rotation group and scale: 0 or head_dim = one
+                           group per (token, kv head), scales [tokens, kv_heads];
+                           kv_heads * head_dim = the whole token vector is one group
+                           with one scale, scales [tokens] (the grouping of the paper's
+                           experiments, Sect. 4.1: 1024 values, 2.02 stored bits per
+                           value; built for 8 heads of 128).  The code bytes have the
+                           same layout either way.  Groups across heads are not
+                           fused with the predictor: the calls then need the fp32
+                           prediction workspace also in bf16.                      */
   const float* codebook;   /* [n, 2] fp32 grid points                             */
   const int8_t* signs_k;   /* [H*g] entries +1 / -1: RHT signs for keys           */
   const int8_t* signs_v;   /* [H*g] same for values                               */

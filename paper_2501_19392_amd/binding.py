@@ -40,7 +40,7 @@ class aquakv_layer(ctypes.Structure):
     _fields_ = [
         ("kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("vq_dim", ctypes.c_int32),
         ("n_codewords", ctypes.c_int32), ("dtype", ctypes.c_int32), ("d_in_k", ctypes.c_int32),
-        ("d_in_v", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("d_in_v", ctypes.c_int32), ("rht_group", ctypes.c_int32),
         ("codebook", ctypes.c_void_p), ("signs_k", ctypes.c_void_p), ("signs_v", ctypes.c_void_p),
         ("w_k", ctypes.c_void_p), ("b_k", ctypes.c_void_p), ("w_v", ctypes.c_void_p), ("b_v", ctypes.c_void_p),
         ("search_table", ctypes.c_void_p),
@@ -119,8 +119,9 @@ class Layer:
     def __init__(self, kv_heads: int, head_dim: int, codebook: torch.Tensor, signs_k: torch.Tensor,
                  signs_v: torch.Tensor, dtype: torch.dtype, w_k: Optional[torch.Tensor] = None,
                  w_v: Optional[torch.Tensor] = None, b_k: Optional[torch.Tensor] = None,
-                 b_v: Optional[torch.Tensor] = None, search_table: Optional[torch.Tensor] = None):
+                 b_v: Optional[torch.Tensor] = None, search_table: Optional[torch.Tensor] = None, rht_group: int = 0):
         self.kv_heads, self.head_dim, self.dtype = kv_heads, head_dim, dtype
+        self.rht_group = rht_group or head_dim          # values per rotation group and scale
         self.d = kv_heads * head_dim
         self.codebook = codebook.to(torch.float32).contiguous()
         self.signs_k = signs_k.to(torch.int8).contiguous().reshape(-1)
@@ -138,7 +139,7 @@ class Layer:
         self.c = aquakv_layer(
             kv_heads=kv_heads, head_dim=head_dim, vq_dim=self.vq_dim, n_codewords=self.n_codewords,
             dtype=_dtype_code(dtype), d_in_k=0 if self.w_k is None else self.w_k.shape[1],
-            d_in_v=0 if self.w_v is None else self.w_v.shape[1], reserved=0,
+            d_in_v=0 if self.w_v is None else self.w_v.shape[1], rht_group=rht_group,
             codebook=self.codebook.data_ptr(), signs_k=self.signs_k.data_ptr(), signs_v=self.signs_v.data_ptr(),
             w_k=None if self.w_k is None else self.w_k.data_ptr(),
             b_k=None if self.b_k is None else self.b_k.data_ptr(),
@@ -156,7 +157,7 @@ class Layer:
 
     def alloc_codes(self, tokens: int, device="cuda"):
         codes = torch.empty(tokens, self.kv_heads, self.code_bytes_per_group, dtype=torch.uint8, device=device)
-        scales = torch.empty(tokens, self.kv_heads, dtype=torch.int16, device=device)   # fp16 bit patterns
+        scales = torch.empty(tokens, self.d // self.rht_group, dtype=torch.int16, device=device)   # fp16 bit patterns
         return codes, scales
 
     def alloc_kv(self, tokens: int, device="cuda"):

@@ -43,8 +43,11 @@ int check_layer(const aquakv_layer* L) {
     return fail(L->n_codewords >= 2 && !(L->n_codewords & (L->n_codewords - 1)) ? AQUAKV_EUNSUPPORTED : AQUAKV_EINVAL,
                 "n_codewords=%d: must be 16, 64 or 256", L->n_codewords);
   if (L->dtype != AQUAKV_BF16 && L->dtype != AQUAKV_FP32) return fail(AQUAKV_EINVAL, "dtype=%d", L->dtype);
-  if (L->reserved != 0) return fail(AQUAKV_EINVAL, "reserved field must be 0");
   const int D = L->kv_heads * L->head_dim;
+  if (L->rht_group != 0 && L->rht_group != L->head_dim) {
+    if (L->rht_group != D) return fail(AQUAKV_EINVAL, "rht_group=%d must be 0, head_dim or kv_heads * head_dim", L->rht_group);
+    if (D != 1024) return fail(AQUAKV_EUNSUPPORTED, "rht_group=%d: groups across heads are built for 8 heads of 128", L->rht_group);
+  }
   if (L->d_in_k < 0 || L->d_in_k % 128) return fail(AQUAKV_EINVAL, "d_in_k=%d must be a non-negative multiple of 128", L->d_in_k);
   if (L->d_in_v < 0 || L->d_in_v % 128) return fail(AQUAKV_EINVAL, "d_in_v=%d must be a non-negative multiple of 128", L->d_in_v);
   if (L->d_in_v != 0 && L->d_in_v <= D)
@@ -59,9 +62,21 @@ int check_layer(const aquakv_layer* L) {
   return AQUAKV_OK;
 }
 
+// rotation group = the whole token vector (Sect. 4.1 of the paper) instead of one head
+inline bool is_wide(const aquakv_layer* L) { return L->rht_group != 0 && L->rht_group != L->head_dim; }
+inline size_t scale_row_bytes(const aquakv_layer* L) { return (is_wide(L) ? 1 : (size_t)L->kv_heads) * sizeof(uint16_t); }
+
 int check_ptr(const void* p, const char* name, bool required) {
   if (p == nullptr) return required ? fail(AQUAKV_ENULL, "%s is NULL", name) : AQUAKV_OK;
   if (misaligned(p)) return fail(AQUAKV_EALIGN, "%s is not 16-byte aligned", name);
+  return AQUAKV_OK;
+}
+
+// scales are read and written one fp16 at a time: with one scale per token a row range of the cache starts at
+// any even address
+int check_scales(const void* p, const char* name, bool required) {
+  if (p == nullptr) return required ? fail(AQUAKV_ENULL, "%s is NULL", name) : AQUAKV_OK;
+  if (reinterpret_cast<uintptr_t>(p) & 1u) return fail(AQUAKV_EALIGN, "%s is not 2-byte aligned", name);
   return AQUAKV_OK;
 }
 
@@ -92,7 +107,7 @@ Plan make_plan(const aquakv_layer* L, int64_t tokens) {
   pl.D = L->kv_heads * L->head_dim;
   pl.eb = elem_bytes(L->dtype);
   pl.code_row = (size_t)L->kv_heads * (L->head_dim / 2) * code_bits(L->n_codewords) / 8;
-  pl.fused = L->dtype == AQUAKV_BF16;
+  pl.fused = L->dtype == AQUAKV_BF16 && !is_wide(L);   // a fused tile is one head wide
   const int64_t cap = pl.fused ? kChunkRowsFused : kChunkRowsSplit;
   pl.chunk = tokens < cap ? tokens : cap;
   pl.p_bytes = pl.fused ? 0 : (size_t)pl.chunk * pl.D * sizeof(float);
@@ -176,10 +191,10 @@ int aquakv_quantize(const aquakv_layer* L, int which, int64_t tokens, const void
   CHECK(check_ptr(X, "X", true));
   CHECK(check_ptr(P, "P", false));
   CHECK(check_ptr(codes, "codes", true));
-  CHECK(check_ptr(scales, "scales", true));
+  CHECK(check_scales(scales, "scales", true));
   CHECK(check_ptr(Xhat, "Xhat", false));
   HIP_TRY(aquakv::launch_quantize(L->dtype, L->n_codewords, X, P, which == AQUAKV_KEY ? L->signs_k : L->signs_v,
-                                  L->codebook, L->search_table, codes, scales, Xhat, tokens, L->kv_heads,
+                                  L->codebook, L->search_table, codes, scales, Xhat, tokens, L->kv_heads, is_wide(L),
                                   static_cast<hipStream_t>(stream)));
   return AQUAKV_OK;
 }
@@ -190,12 +205,12 @@ int aquakv_dequantize(const aquakv_layer* L, int which, int64_t tokens, const ui
   if (which != AQUAKV_KEY && which != AQUAKV_VALUE) return fail(AQUAKV_EINVAL, "which=%d", which);
   if (tokens < 0) return fail(AQUAKV_EINVAL, "tokens=%lld", (long long)tokens);
   CHECK(check_ptr(codes, "codes", true));
-  CHECK(check_ptr(scales, "scales", true));
+  CHECK(check_scales(scales, "scales", true));
   CHECK(check_ptr(P, "P", false));
   CHECK(check_ptr(Xhat, "Xhat", true));
   HIP_TRY(aquakv::launch_dequantize(L->dtype, L->n_codewords, codes, scales, P,
                                     which == AQUAKV_KEY ? L->signs_k : L->signs_v, L->codebook, Xhat, tokens,
-                                    L->kv_heads, static_cast<hipStream_t>(stream)));
+                                    L->kv_heads, is_wide(L), static_cast<hipStream_t>(stream)));
   return AQUAKV_OK;
 }
 
@@ -211,9 +226,9 @@ int aquakv_encode_layer(const aquakv_layer* L, int64_t tokens, const void* K, co
   CHECK(check_ptr(Khat_prev, "Khat_prev", has_k));
   CHECK(check_ptr(Vhat_prev, "Vhat_prev", has_v));
   CHECK(check_ptr(k_codes, "k_codes", true));
-  CHECK(check_ptr(k_scales, "k_scales", true));
+  CHECK(check_scales(k_scales, "k_scales", true));
   CHECK(check_ptr(v_codes, "v_codes", true));
-  CHECK(check_ptr(v_scales, "v_scales", true));
+  CHECK(check_scales(v_scales, "v_scales", true));
   CHECK(check_ptr(Khat, "Khat", false));
   CHECK(check_ptr(Vhat, "Vhat", false));
   if (tokens == 0) return AQUAKV_OK;
@@ -226,7 +241,7 @@ int aquakv_encode_layer(const aquakv_layer* L, int64_t tokens, const void* K, co
   float* Pbuf = static_cast<float*>(workspace);
   void* khat_tmp = static_cast<unsigned char*>(workspace) + pl.p_bytes;
   const size_t row = (size_t)pl.D * pl.eb;
-  const size_t srow = (size_t)L->kv_heads * sizeof(uint16_t);
+  const size_t srow = scale_row_bytes(L);
   const int D = pl.D, H = L->kv_heads;
 
   for (int64_t r0 = 0; r0 < tokens; r0 += pl.chunk) {
@@ -244,7 +259,7 @@ int aquakv_encode_layer(const aquakv_layer* L, int64_t tokens, const void* K, co
                                        L->w_k, L->b_k, Pbuf, n, D, stream));
       HIP_TRY(aquakv::launch_quantize(L->dtype, L->n_codewords, at(K, r0, row), has_k ? Pbuf : nullptr, L->signs_k,
                                       L->codebook, L->search_table, static_cast<uint8_t*>(at(k_codes, r0, pl.code_row)),
-                                      static_cast<uint16_t*>(at(k_scales, r0, srow)), khat_dst, n, H, stream));
+                                      static_cast<uint16_t*>(at(k_scales, r0, srow)), khat_dst, n, H, is_wide(L), stream));
     }
     // values: V_pred = f_value([Vhat_prev; Khat]);  V_q = Q(V - V_pred)
     if (has_v && pl.fused) {
@@ -260,7 +275,7 @@ int aquakv_encode_layer(const aquakv_layer* L, int64_t tokens, const void* K, co
                                        khat_dst, D, L->w_v, L->b_v, Pbuf, n, D, stream));
       HIP_TRY(aquakv::launch_quantize(L->dtype, L->n_codewords, at(V, r0, row), has_v ? Pbuf : nullptr, L->signs_v,
                                       L->codebook, L->search_table, static_cast<uint8_t*>(at(v_codes, r0, pl.code_row)),
-                                      static_cast<uint16_t*>(at(v_scales, r0, srow)), at(Vhat, r0, row), n, H, stream));
+                                      static_cast<uint16_t*>(at(v_scales, r0, srow)), at(Vhat, r0, row), n, H, is_wide(L), stream));
     }
   }
   return AQUAKV_OK;
@@ -274,9 +289,9 @@ int aquakv_decode_layer(const aquakv_layer* L, int64_t tokens, const uint8_t* k_
   const bool want_v = Vhat != nullptr;
   const bool has_k = L->d_in_k != 0, has_v = L->d_in_v != 0 && want_v;
   CHECK(check_ptr(k_codes, "k_codes", true));
-  CHECK(check_ptr(k_scales, "k_scales", true));
+  CHECK(check_scales(k_scales, "k_scales", true));
   CHECK(check_ptr(v_codes, "v_codes", want_v));
-  CHECK(check_ptr(v_scales, "v_scales", want_v));
+  CHECK(check_scales(v_scales, "v_scales", want_v));
   CHECK(check_ptr(Khat_prev, "Khat_prev", has_k));
   CHECK(check_ptr(Vhat_prev, "Vhat_prev", has_v));
   CHECK(check_ptr(Khat, "Khat", true));
@@ -290,7 +305,7 @@ int aquakv_decode_layer(const aquakv_layer* L, int64_t tokens, const uint8_t* k_
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   float* Pbuf = static_cast<float*>(workspace);
   const size_t row = (size_t)pl.D * pl.eb;
-  const size_t srow = (size_t)L->kv_heads * sizeof(uint16_t);
+  const size_t srow = scale_row_bytes(L);
   const int D = pl.D, H = L->kv_heads;
 
   for (int64_t r0 = 0; r0 < tokens; r0 += pl.chunk) {
@@ -309,7 +324,7 @@ int aquakv_decode_layer(const aquakv_layer* L, int64_t tokens, const uint8_t* k_
       HIP_TRY(aquakv::launch_dequantize(L->dtype, L->n_codewords,
                                         static_cast<const uint8_t*>(at(k_codes, r0, pl.code_row)),
                                         static_cast<const uint16_t*>(at(k_scales, r0, srow)), has_k ? Pbuf : nullptr,
-                                        L->signs_k, L->codebook, at(Khat, r0, row), n, H, stream));
+                                        L->signs_k, L->codebook, at(Khat, r0, row), n, H, is_wide(L), stream));
     }
     if (!want_v) continue;
     // Vhat = Q^-1(V_q) + f_value([Vhat_prev; Khat])
@@ -326,7 +341,7 @@ int aquakv_decode_layer(const aquakv_layer* L, int64_t tokens, const uint8_t* k_
       HIP_TRY(aquakv::launch_dequantize(L->dtype, L->n_codewords,
                                         static_cast<const uint8_t*>(at(v_codes, r0, pl.code_row)),
                                         static_cast<const uint16_t*>(at(v_scales, r0, srow)), has_v ? Pbuf : nullptr,
-                                        L->signs_v, L->codebook, at(Vhat, r0, row), n, H, stream));
+                                        L->signs_v, L->codebook, at(Vhat, r0, row), n, H, is_wide(L), stream));
     }
   }
   return AQUAKV_OK;
@@ -334,7 +349,7 @@ int aquakv_decode_layer(const aquakv_layer* L, int64_t tokens, const uint8_t* k_
 
 size_t aquakv_scores_workspace_bytes(const aquakv_layer* L, int32_t batch, int32_t q_heads) {
   if (check_layer(L) != AQUAKV_OK || batch < 1 || q_heads < 1) return 0;
-  if (L->dtype != AQUAKV_BF16 || !aquakv::folded_scores_supported(L->kv_heads, L->d_in_k, q_heads)) return 0;
+  if (L->dtype != AQUAKV_BF16 || is_wide(L) || !aquakv::folded_scores_supported(L->kv_heads, L->d_in_k, q_heads)) return 0;
   return aquakv::folded_scores_workspace_bytes(batch);
 }
 
@@ -352,7 +367,7 @@ int decode_attn_scores(const aquakv_layer* L, int32_t batch, int32_t seq_len, in
     return fail(AQUAKV_EINVAL, "q_heads=%d must be a multiple of kv_heads=%d, at most 8x", q_heads, L->kv_heads);
   const bool has_k = L->d_in_k != 0;
   CHECK(check_ptr(k_codes, "k_codes", true));
-  CHECK(check_ptr(k_scales, "k_scales", true));
+  CHECK(check_scales(k_scales, "k_scales", true));
   CHECK(check_ptr(Khat_prev, "Khat_prev", has_k));
   CHECK(check_ptr(q, "q", true));
   CHECK(check_ptr(scores, "scores", true));
@@ -385,7 +400,7 @@ int decode_attn_scores(const aquakv_layer* L, int32_t batch, int32_t seq_len, in
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   float* Pbuf = static_cast<float*>(workspace);
   const size_t row = (size_t)pl.D * pl.eb;
-  const size_t srow = (size_t)L->kv_heads * sizeof(uint16_t);
+  const size_t srow = scale_row_bytes(L);
   for (int64_t r0 = 0; r0 < tokens; r0 += pl.chunk) {
     const int64_t n = tokens - r0 < pl.chunk ? tokens - r0 : pl.chunk;
     if (has_k)
@@ -394,7 +409,7 @@ int decode_attn_scores(const aquakv_layer* L, int32_t batch, int32_t seq_len, in
     HIP_TRY(aquakv::launch_attn_scores(L->dtype, L->n_codewords, static_cast<const uint8_t*>(at(k_codes, r0, pl.code_row)),
                                        static_cast<const uint16_t*>(at(k_scales, r0, srow)), has_k ? Pbuf : nullptr,
                                        L->signs_k, L->codebook, q, score_scale, scores, at(Khat_out, r0, row), r0, n,
-                                       seq_len, L->kv_heads, q_heads, rope_cos, rope_sin, stream));
+                                       seq_len, L->kv_heads, q_heads, rope_cos, rope_sin, is_wide(L), stream));
   }
   return AQUAKV_OK;
 }

@@ -218,28 +218,32 @@ __device__ __forceinline__ void stage_lds(Lds& lds, const float* __restrict__ co
 
 
 // ------------------------------------------------------------------ group bodies
-// Q(x - p) for the 32 coordinates this lane holds of group `gid`.  On entry v = x; on exit v
-// holds the (unrounded) reconstruction p + Q^-1(codes) if `want_hat`.  Codes and the scale are
-// stored when `active` (inactive lanes only keep the quad's DPP exchanges in step).
-template <int NCW>
-__device__ __forceinline__ void quantize_group(float (&v)[32], const float (&p)[32], const uint32_t (&sb)[32], int q,
+// Q(x - p) for the 32 coordinates this lane holds of head group `gid` (= token * H + head).  On entry
+// v = x; on exit v holds the (unrounded) reconstruction p + Q^-1(codes) if `want_hat`.  Codes and the
+// scale are stored when `active` (inactive lanes only keep the cross-lane exchanges in step).
+// `l` is the lane's index inside its rotation group: lane % 4 for groups of 128 (WIDE = false, one
+// scale per head group), lane % 32 for groups of 1024 = the whole token (WIDE = true, kv_heads = 8, one
+// scale per token at scales[gid / 8]).  The code bytes have the same layout in both cases.
+template <int NCW, bool WIDE = false>
+__device__ __forceinline__ void quantize_group(float (&v)[32], const float (&p)[32], const uint32_t (&sb)[32], int l,
                                                const float4* cb, const uint32_t* table, bool active, int64_t gid,
                                                uint8_t* __restrict__ codes, uint16_t* __restrict__ scales,
                                                bool want_hat) {
 #pragma unroll
   for (int r = 0; r < 32; ++r) v[r] = __uint_as_float(__float_as_uint(v[r] - p[r]) ^ sb[r]);   // s * (x - p)
-  wht128(v, q);                                           // w = +-H u (unnormalised, lane sign pending)
+  const int q = l & 3;
+  Rot<WIDE>::wht(v, l);                                   // w = +-H u (unnormalised, lane sign pending)
 
   float ss = 0.f;
 #pragma unroll
   for (int r = 0; r < 32; ++r) ss = __fmaf_rn(v[r], v[r], ss);
-  ss = quad_sum(ss);
+  ss = Rot<WIDE>::sum(ss);
   // z = w / sqrt(g)  =>  rms(z) = sqrt(sum w^2) / g
-  float sigma = __fsqrt_rn(ss) * (1.0f / kGroup);
+  float sigma = __fsqrt_rn(ss) * Rot<WIDE>::kInvG;
   sigma = fminf(sigma, 65504.0f);
   const _Float16 s16h = static_cast<_Float16>(sigma);     // round to nearest even
   const float s16 = static_cast<float>(s16h);
-  const float inv = s16 > 0.f ? quad_sign(q) * __fdiv_rn(kRsqrtG, s16) : 0.f;   // also undoes wht128's lane sign
+  const float inv = s16 > 0.f ? Rot<WIDE>::sign(l) * __fdiv_rn(Rot<WIDE>::kNorm, s16) : 0.f;   // also undoes the lane sign
 
   int idx[16];
   if (table != nullptr) {
@@ -259,24 +263,24 @@ __device__ __forceinline__ void quantize_group(float (&v)[32], const float (&p)[
   }
   if (active) {
     store_codes<NCW>(codes, gid, q, idx);
-    if (q == 0) scales[gid] = __builtin_bit_cast(uint16_t, s16h);
+    if (l == 0) scales[WIDE ? gid >> 3 : gid] = __builtin_bit_cast(uint16_t, s16h);
   }
   if (want_hat) {
     gather_zhat(idx, s16, cb, v);
-    reconstruct(v, q, sb, p);
+    reconstruct<WIDE>(v, l, sb, p);
   }
 }
 
 // Q^-1(codes) + p for the 32 coordinates this lane holds of group `gid` (unrounded, in z).
-template <int NCW>
-__device__ __forceinline__ void dequantize_group(float (&z)[32], const float (&p)[32], const uint32_t (&sb)[32], int q,
+template <int NCW, bool WIDE = false>
+__device__ __forceinline__ void dequantize_group(float (&z)[32], const float (&p)[32], const uint32_t (&sb)[32], int l,
                                                  const float4* cb, int64_t gid, const uint8_t* __restrict__ codes,
                                                  const uint16_t* __restrict__ scales) {
   int idx[16];
-  load_codes<NCW>(codes, gid, q, idx);
-  const float s16 = half_bits_to_float(scales[gid]);
+  load_codes<NCW>(codes, gid, l & 3, idx);
+  const float s16 = half_bits_to_float(scales[WIDE ? gid >> 3 : gid]);
   gather_zhat(idx, s16, cb, z);
-  reconstruct(z, q, sb, p);
+  reconstruct<WIDE>(z, l, sb, p);
 }
 
 }  // namespace aquakv

@@ -5,8 +5,10 @@
 // nearest-grid-point search table.  These are the stand-alone forms (prediction
 // read from memory, or absent); the fused forms live in fused_kernels.hip.
 //
-// One rotation group is held by a quad of lanes x 32 values (see device_utils.h);
-// a 256-thread block covers 64 groups per pass.
+// One head group (128 values) is held by a quad of lanes x 32 values (see device_utils.h);
+// a 256-thread block covers 64 head groups = 8 tokens of 8 heads per pass.  WIDE = true selects
+// rotation groups of 1024 = the whole token (the grouping of the paper's experiments, Sect. 4.1):
+// the 8 quads of a token (32 consecutive lanes) then share three more butterfly stages and one scale.
 #include "codec_core.h"
 #include "kernels.h"
 
@@ -17,7 +19,7 @@ constexpr int kThreads = 256;
 constexpr int kGroupsPerBlock = kThreads / kLanesPerGroup;   // 64
 
 // ------------------------------------------------------------------ quantize
-template <typename T, int NCW>
+template <typename T, int NCW, bool WIDE>
 __global__ __launch_bounds__(kThreads) void quantize_kernel(const T* X, const float* __restrict__ P,
                                                             const int8_t* __restrict__ signs,
                                                             const float* __restrict__ codebook,
@@ -44,14 +46,14 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const T* X, const fl
       for (int r = 0; r < 32; ++r) p[r] = 0.f;
     }
     load_sign_bits(signs, head, q, sb);
-    quantize_group<NCW>(v, p, sb, q, lds.cb, table != nullptr ? lds.table : nullptr, active, gid, codes, scales,
-                        Xhat != nullptr);
+    quantize_group<NCW, WIDE>(v, p, sb, WIDE ? (int)(threadIdx.x & 31) : q, lds.cb, table != nullptr ? lds.table : nullptr,
+                              active, gid, codes, scales, Xhat != nullptr);
     if (Xhat != nullptr && active) Storage<T>::store32(Xhat + off, v);
   }
 }
 
 // ------------------------------------------------------------------ dequantize
-template <typename T, int NCW>
+template <typename T, int NCW, bool WIDE>
 __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint8_t* __restrict__ codes,
                                                               const uint16_t* __restrict__ scales,
                                                               const float* __restrict__ P,
@@ -78,14 +80,14 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint8_t* __r
       for (int r = 0; r < 32; ++r) p[r] = 0.f;
     }
     load_sign_bits(signs, head, q, sb);
-    dequantize_group<NCW>(z, p, sb, q, cb, gid, codes, scales);
+    dequantize_group<NCW, WIDE>(z, p, sb, WIDE ? (int)(threadIdx.x & 31) : q, cb, gid, codes, scales);
     if (active) Storage<T>::store32(Xhat + off, z);
   }
 }
 
 // ------------------------------------------------------------------ dequantize + q.k
 // Group gid = row * H + head of the chunk; row = b * seq_len + t (global row = row0 + row).
-template <typename T, int NCW>
+template <typename T, int NCW, bool WIDE>
 __global__ __launch_bounds__(kThreads) void attn_scores_kernel(
     const uint8_t* __restrict__ codes, const uint16_t* __restrict__ scales, const float* __restrict__ P,
     const int8_t* __restrict__ signs, const float* __restrict__ codebook, const T* __restrict__ qv_,
@@ -115,7 +117,7 @@ __global__ __launch_bounds__(kThreads) void attn_scores_kernel(
       for (int r = 0; r < 32; ++r) p[r] = 0.f;
     }
     load_sign_bits(signs, head, q, sb);
-    dequantize_group<NCW>(z, p, sb, q, cb, gid, codes, scales);
+    dequantize_group<NCW, WIDE>(z, p, sb, WIDE ? (int)(threadIdx.x & 31) : q, cb, gid, codes, scales);
     if (Khat_out != nullptr && active) Storage<T>::store32(Khat_out + off, z);
 #pragma unroll
     for (int r = 0; r < 32; ++r) z[r] = Storage<T>::round(z[r]);      // score the stored keys
@@ -188,18 +190,23 @@ inline unsigned blocks_for(int64_t n_groups) {
 
 }  // namespace
 
-#define AQUAKV_DISPATCH(DT, NCW, CALL)                                                  \
+#define AQUAKV_DISPATCH_N(NCW, CALL)                                                    \
+  do {                                                                                  \
+    if ((NCW) == 16) { constexpr int N = 16; CALL; }                                    \
+    else if ((NCW) == 64) { constexpr int N = 64; CALL; }                               \
+    else { constexpr int N = 256; CALL; }                                               \
+  } while (0)
+// binds T (storage type), N (grid size) and W (rotation group of 1024) as compile-time names for CALL
+#define AQUAKV_DISPATCH(DT, NCW, WIDE_, CALL)                                           \
   do {                                                                                  \
     if ((DT) == kBF16) {                                                                \
       typedef bf16_t T;                                                                 \
-      if ((NCW) == 16) { constexpr int N = 16; CALL; }                                  \
-      else if ((NCW) == 64) { constexpr int N = 64; CALL; }                             \
-      else { constexpr int N = 256; CALL; }                                             \
+      if (WIDE_) { constexpr bool W = true; AQUAKV_DISPATCH_N(NCW, CALL); }             \
+      else { constexpr bool W = false; AQUAKV_DISPATCH_N(NCW, CALL); }                  \
     } else {                                                                            \
       typedef float T;                                                                  \
-      if ((NCW) == 16) { constexpr int N = 16; CALL; }                                  \
-      else if ((NCW) == 64) { constexpr int N = 64; CALL; }                             \
-      else { constexpr int N = 256; CALL; }                                             \
+      if (WIDE_) { constexpr bool W = true; AQUAKV_DISPATCH_N(NCW, CALL); }             \
+      else { constexpr bool W = false; AQUAKV_DISPATCH_N(NCW, CALL); }                  \
     }                                                                                   \
   } while (0)
 
@@ -210,23 +217,23 @@ hipError_t launch_build_search_table(const float* codebook, int n_codewords, voi
 
 hipError_t launch_quantize(int dtype, int n_codewords, const void* X, const float* P, const int8_t* signs,
                            const float* codebook, const void* table, uint8_t* codes, uint16_t* scales, void* Xhat,
-                           int64_t T_, int H, hipStream_t stream) {
+                           int64_t T_, int H, bool wide, hipStream_t stream) {
   const int64_t n_groups = T_ * H;
   if (n_groups == 0) return hipSuccess;
-  AQUAKV_DISPATCH(dtype, n_codewords,
-                  (quantize_kernel<T, N><<<blocks_for(n_groups), kThreads, 0, stream>>>(
+  AQUAKV_DISPATCH(dtype, n_codewords, wide,
+                  (quantize_kernel<T, N, W><<<blocks_for(n_groups), kThreads, 0, stream>>>(
                       static_cast<const T*>(X), P, signs, codebook, static_cast<const uint32_t*>(table), codes, scales,
                       static_cast<T*>(Xhat), n_groups, H)));
   return hipGetLastError();
 }
 
 hipError_t launch_dequantize(int dtype, int n_codewords, const uint8_t* codes, const uint16_t* scales, const float* P,
-                             const int8_t* signs, const float* codebook, void* Xhat, int64_t T_, int H,
+                             const int8_t* signs, const float* codebook, void* Xhat, int64_t T_, int H, bool wide,
                              hipStream_t stream) {
   const int64_t n_groups = T_ * H;
   if (n_groups == 0) return hipSuccess;
-  AQUAKV_DISPATCH(dtype, n_codewords,
-                  (dequantize_kernel<T, N><<<blocks_for(n_groups), kThreads, 0, stream>>>(
+  AQUAKV_DISPATCH(dtype, n_codewords, wide,
+                  (dequantize_kernel<T, N, W><<<blocks_for(n_groups), kThreads, 0, stream>>>(
                       codes, scales, P, signs, codebook, static_cast<T*>(Xhat), n_groups, H)));
   return hipGetLastError();
 }
@@ -234,11 +241,11 @@ hipError_t launch_dequantize(int dtype, int n_codewords, const uint8_t* codes, c
 hipError_t launch_attn_scores(int dtype, int n_codewords, const uint8_t* codes, const uint16_t* scales, const float* P,
                               const int8_t* signs, const float* codebook, const void* q, float score_scale,
                               float* scores, void* Khat_out, int64_t row0, int64_t rows, int seq_len, int H,
-                              int q_heads, const float* rope_cos, const float* rope_sin, hipStream_t stream) {
+                              int q_heads, const float* rope_cos, const float* rope_sin, bool wide, hipStream_t stream) {
   const int64_t n_groups = rows * H;
   if (n_groups == 0) return hipSuccess;
-  AQUAKV_DISPATCH(dtype, n_codewords,
-                  (attn_scores_kernel<T, N><<<blocks_for(n_groups), kThreads, 0, stream>>>(
+  AQUAKV_DISPATCH(dtype, n_codewords, wide,
+                  (attn_scores_kernel<T, N, W><<<blocks_for(n_groups), kThreads, 0, stream>>>(
                       codes, scales, P, signs, codebook, static_cast<const T*>(q), score_scale, scores,
                       static_cast<T*>(Khat_out), row0, n_groups, seq_len, H, q_heads, rope_cos, rope_sin)));
   return hipGetLastError();

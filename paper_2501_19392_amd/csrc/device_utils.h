@@ -167,6 +167,54 @@ __device__ __forceinline__ void wht128(float (&v)[32], int q) {
   wht_quad_stage<2>(v, (q & 2) ? -1.0f : 1.0f);
 }
 
+// ---------------------------------------------------------------- 1024-point WHT (rotation group = whole token)
+// A token's 1024 values (8 heads x 128) sit in 32 consecutive lanes, lane j holding coordinates 32 j ... 32 j + 31,
+// i.e. 8 quads that each hold one head.  H_1024 = H_8 (x) H_128: after wht128 inside every quad, three more
+// butterfly stages pair lanes j and j ^ 4, j ^ 8, j ^ 16.  Same multiply-add form and pending lane sign as the
+// quad stages; lane ^ 8 is a DPP row rotation by 8, lane ^ 4 and lane ^ 16 go through ds_swizzle.
+template <int XOR_MASK> __device__ __forceinline__ float swizzle_xor(float x) {
+  static_assert(XOR_MASK == 4 || XOR_MASK == 16, "mask");
+  // bit-mask mode: lane' = ((lane & 0x1f) | 0) ^ XOR_MASK within each group of 32 lanes
+  return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(x), (XOR_MASK << 10) | 0x1f));
+}
+__device__ __forceinline__ float row_xor8(float x) {     // value of lane ^ 8 (rotation by 8 within a row of 16)
+  return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(x), 0x128 /* row_ror:8 */, 0xF, 0xF, true));
+}
+__device__ __forceinline__ void wht1024_tail(float (&v)[32], int lane32) {
+  const float s4 = (lane32 & 4) ? -1.0f : 1.0f, s8 = (lane32 & 8) ? -1.0f : 1.0f, s16 = (lane32 & 16) ? -1.0f : 1.0f;
+#pragma unroll
+  for (int r = 0; r < 32; ++r) v[r] = __fmaf_rn(swizzle_xor<4>(v[r]), s4, v[r]);
+#pragma unroll
+  for (int r = 0; r < 32; ++r) v[r] = __fmaf_rn(row_xor8(v[r]), s8, v[r]);
+#pragma unroll
+  for (int r = 0; r < 32; ++r) v[r] = __fmaf_rn(swizzle_xor<16>(v[r]), s16, v[r]);
+}
+// sum over the 32 lanes of a token; every lane gets the total (fixed order)
+__device__ __forceinline__ float token_sum(float x) {
+  x = quad_sum(x);
+  x = x + swizzle_xor<4>(x);
+  x = x + row_xor8(x);
+  x = x + swizzle_xor<16>(x);
+  return x;
+}
+
+// Rotation group layouts.  WIDE = false: one group = one head = a quad of lanes (g = 128).  WIDE = true: one group =
+// the whole token vector of 8 heads = 32 lanes (g = 1024).  `l` is the lane's index inside its token (0..31).
+template <bool WIDE> struct Rot {
+  static constexpr float kNorm = WIDE ? 0.03125f : kRsqrtG;            // 1 / sqrt(g)
+  static constexpr float kInvG = WIDE ? 1.0f / 1024 : 1.0f / kGroup;
+  static __device__ __forceinline__ void wht(float (&v)[32], int l) {
+    wht128(v, l & 3);
+    if constexpr (WIDE) wht1024_tail(v, l);
+  }
+  // sign pending on the lane's values after wht(): -1 for every cross-lane stage in which the lane was the upper one
+  static __device__ __forceinline__ float sign(int l) {
+    const int bits = WIDE ? (l & 31) : (l & 3);
+    return (__builtin_popcount(bits) & 1) ? -1.0f : 1.0f;
+  }
+  static __device__ __forceinline__ float sum(float x) { return WIDE ? token_sum(x) : quad_sum(x); }
+};
+
 // sign bits of the 32 RHT signs this lane needs (+1 -> 0, -1 -> 0x80000000)
 __device__ __forceinline__ void load_sign_bits(const int8_t* signs, int head, int q, uint32_t (&sb)[32]) {
   const u32x4* src = reinterpret_cast<const u32x4*>(signs + head * kGroup + q * kValsPerLane);
@@ -184,9 +232,10 @@ __device__ __forceinline__ void load_sign_bits(const int8_t* signs, int head, in
 // Reconstruction tail: zhat (rotated, already scaled by sigma16) -> s*H(zhat)/sqrt(g) + p.
 // Used unchanged by the quantize, dequantize and scoring kernels so that all
 // three produce bit-identical keys/values.
-__device__ __forceinline__ void reconstruct(float (&z)[32], int q, const uint32_t (&sb)[32], const float (&p)[32]) {
-  wht128(z, q);
-  const float norm = quad_sign(q) * kRsqrtG;
+template <bool WIDE = false>
+__device__ __forceinline__ void reconstruct(float (&z)[32], int l, const uint32_t (&sb)[32], const float (&p)[32]) {
+  Rot<WIDE>::wht(z, l);
+  const float norm = Rot<WIDE>::sign(l) * Rot<WIDE>::kNorm;
 #pragma unroll
   for (int r = 0; r < 32; ++r) {
     const float x = __uint_as_float(__float_as_uint(z[r] * norm) ^ sb[r]);

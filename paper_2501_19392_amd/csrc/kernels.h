@@ -13,17 +13,18 @@ hipError_t launch_predict(int dtype, const void* x0, int d0, const void* x1, int
                           const float* bias, float* P, int64_t T, int D, hipStream_t stream);
 
 // Q(X - P): codes, scales and (optionally) the reconstruction.  rows = T, H heads of 128.
+// wide: rotation groups of 1024 = the whole token (H must be 8), scales [T] instead of [T, H].
 // `table` (nullable): nearest-grid-point search table from launch_build_search_table.
 hipError_t launch_quantize(int dtype, int n_codewords, const void* X, const float* P, const int8_t* signs,
                            const float* codebook, const void* table, uint8_t* codes, uint16_t* scales, void* Xhat,
-                           int64_t T, int H, hipStream_t stream);
+                           int64_t T, int H, bool wide, hipStream_t stream);
 
 // 64 x 64 cells x 4 candidate bytes = 16 KiB.
 constexpr size_t kSearchTableBytes = 64 * 64 * 4;
 hipError_t launch_build_search_table(const float* codebook, int n_codewords, void* table, hipStream_t stream);
 
 hipError_t launch_dequantize(int dtype, int n_codewords, const uint8_t* codes, const uint16_t* scales, const float* P,
-                             const int8_t* signs, const float* codebook, void* Xhat, int64_t T, int H,
+                             const int8_t* signs, const float* codebook, void* Xhat, int64_t T, int H, bool wide,
                              hipStream_t stream);
 
 // scores[b, qh, t] for rows [row0, row0 + rows) of the flattened [batch*seq_len] axis.
@@ -32,7 +33,7 @@ hipError_t launch_dequantize(int dtype, int n_codewords, const uint8_t* codes, c
 hipError_t launch_attn_scores(int dtype, int n_codewords, const uint8_t* codes, const uint16_t* scales, const float* P,
                               const int8_t* signs, const float* codebook, const void* q, float score_scale,
                               float* scores, void* Khat_out, int64_t row0, int64_t rows, int seq_len, int H,
-                              int q_heads, const float* rope_cos, const float* rope_sin, hipStream_t stream);
+                              int q_heads, const float* rope_cos, const float* rope_sin, bool wide, hipStream_t stream);
 
 // Fused bf16 forms: prediction [x0 | x1] W^T + bias on the matrix cores, consumed in the same
 // kernel by the quantizer (encode), its inverse (decode) or its inverse plus q.k (scores).

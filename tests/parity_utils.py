@@ -20,7 +20,8 @@ def np64(t: torch.Tensor) -> np.ndarray:
     return t.detach().double().cpu().numpy()
 
 
-def make_layers(kv_heads, dtype, n, layer_idx=1, w_k=None, w_v=None, b_k=None, b_v=None, device="cuda", table=True):
+def make_layers(kv_heads, dtype, n, layer_idx=1, w_k=None, w_v=None, b_k=None, b_v=None, device="cuda", table=True,
+                rht_group=None):
     """(oracle layer, binding layer) from the same arrays.  w_* are torch fp32 [D, d_in]
     and are rounded to the storage dtype first so that both sides see identical weights."""
     from paper_2501_19392_amd import binding as B
@@ -33,13 +34,14 @@ def make_layers(kv_heads, dtype, n, layer_idx=1, w_k=None, w_v=None, b_k=None, b
     wv = None if w_v is None else w_v.to(sd)
     lo = O.Layer(kv_heads=kv_heads, head_dim=g, codebook=C, signs_k=sk, signs_v=sv, dtype=dtype,
                  w_k=None if wk is None else np64(wk), w_v=None if wv is None else np64(wv),
-                 b_k=None if b_k is None else np64(b_k.float()), b_v=None if b_v is None else np64(b_v.float()))
+                 b_k=None if b_k is None else np64(b_k.float()), b_v=None if b_v is None else np64(b_v.float()),
+                 rht_group=rht_group)
     dev = lambda t: None if t is None else t.to(device)
     Cd = torch.from_numpy(C).to(device)
     lg = B.Layer(kv_heads, g, Cd, torch.from_numpy(sk).to(device),
                  torch.from_numpy(sv).to(device), sd, w_k=dev(wk), w_v=dev(wv),
                  b_k=dev(None if b_k is None else b_k.float()), b_v=dev(None if b_v is None else b_v.float()),
-                 search_table=B.build_search_table(Cd) if table else None)
+                 search_table=B.build_search_table(Cd) if table else None, rht_group=rht_group or 0)
     return lo, lg
 
 

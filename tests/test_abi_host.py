@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
 
 def layer(**kw):
     d = dict(kv_heads=8, head_dim=128, vq_dim=2, n_codewords=16, dtype=B.AQUAKV_BF16, d_in_k=1024, d_in_v=2048,
-             reserved=0, codebook=FAKE, signs_k=FAKE, signs_v=FAKE, w_k=FAKE, b_k=None, w_v=FAKE, b_v=None,
+             rht_group=0, codebook=FAKE, signs_k=FAKE, signs_v=FAKE, w_k=FAKE, b_k=None, w_v=FAKE, b_v=None,
              search_table=None)
     d.update(kw)
     return B.aquakv_layer(**d)
@@ -58,7 +58,8 @@ ENC_OK = [FAKE] * 10  # K V Khat_prev Vhat_prev k_codes k_scales v_codes v_scale
     (dict(codebook=None), B.AQUAKV_ENULL),
     (dict(w_k=None), B.AQUAKV_ENULL),
     (dict(signs_v=FAKE + 4), B.AQUAKV_EALIGN),
-    (dict(reserved=1), B.AQUAKV_EINVAL),
+    (dict(rht_group=64), B.AQUAKV_EINVAL),
+    (dict(rht_group=512, kv_heads=4, d_in_v=1024), B.AQUAKV_EUNSUPPORTED),
 ])
 def test_bad_layer_is_rejected(kw, want):
     L = layer(**kw)
@@ -75,6 +76,8 @@ def test_bad_call_arguments_are_rejected_without_launching():
     L32 = layer(dtype=B.AQUAKV_FP32)
     assert B.aquakv_workspace_bytes(L32, 300) == 300 * 1024 * (4 + 4)        # fp32: predictions + Khat
     assert B.aquakv_workspace_bytes(L32, 1 << 20) == 16384 * 1024 * 8
+    Lw = layer(rht_group=1024)                                               # groups across heads: predictor not fused
+    assert B.aquakv_workspace_bytes(Lw, 300) == 300 * 1024 * (4 + 2)
     args = list(ENC_OK)
     assert status_of(B.aquakv_encode_layer, L, -1, *args, (FAKE, need)) == B.AQUAKV_EINVAL
     assert status_of(B.aquakv_encode_layer, L, 300, *args, (FAKE, need - 1)) == B.AQUAKV_EWORKSPACE
@@ -84,7 +87,7 @@ def test_bad_call_arguments_are_rejected_without_launching():
         bad = list(args)
         bad[i] = None
         assert status_of(B.aquakv_encode_layer, L, 300, *bad, (FAKE, need)) == B.AQUAKV_ENULL
-        bad[i] = FAKE + 8
+        bad[i] = FAKE + (1 if i in (5, 7) else 8)        # scale arrays need 2-byte alignment, the rest 16
         assert status_of(B.aquakv_encode_layer, L, 300, *bad, (FAKE, need)) == B.AQUAKV_EALIGN
     # tokens == 0 is a no-op even without a workspace
     B.aquakv_encode_layer(L, 0, *args, None)

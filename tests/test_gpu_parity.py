@@ -199,7 +199,7 @@ def run_gpu_layers(B, cfg, layers_g, Ks, Vs, want_hat=True):
     return out
 
 
-def build_stack(cfg, device="cuda", predictors="analytic", bias=False):
+def build_stack(cfg, device="cuda", predictors="analytic", bias=False, rht_group=None):
     st = synth.KVStream(cfg, device="cpu", work=torch.float64)
     Ks, Vs, lo_l, lg_l = [], [], [], []
     for l in range(cfg.layers):
@@ -207,7 +207,7 @@ def build_stack(cfg, device="cuda", predictors="analytic", bias=False):
         Ks.append(K.to(device))
         Vs.append(V.to(device))
         if l == 0:
-            lo, lg = U.make_layers(cfg.kv_heads, cfg.dtype, cfg.n_codewords, layer_idx=l)
+            lo, lg = U.make_layers(cfg.kv_heads, cfg.dtype, cfg.n_codewords, layer_idx=l, rht_group=rht_group)
         else:
             if predictors == "analytic":
                 wk, wv = synth.analytic_predictors(st, l)
@@ -216,7 +216,8 @@ def build_stack(cfg, device="cuda", predictors="analytic", bias=False):
             gb = torch.Generator().manual_seed(300 + l)
             bk = torch.randn(cfg.d, generator=gb) * 0.3 if bias else None
             bv = torch.randn(cfg.d, generator=gb) * 0.3 if bias else None
-            lo, lg = U.make_layers(cfg.kv_heads, cfg.dtype, cfg.n_codewords, layer_idx=l, w_k=wk, w_v=wv, b_k=bk, b_v=bv)
+            lo, lg = U.make_layers(cfg.kv_heads, cfg.dtype, cfg.n_codewords, layer_idx=l, w_k=wk, w_v=wv, b_k=bk, b_v=bv,
+                                   rht_group=rht_group)
         lo_l.append(lo)
         lg_l.append(lg)
     return Ks, Vs, lo_l, lg_l
@@ -233,7 +234,7 @@ def check_layer_against_oracle(B, lo, lg, K, V, g, rows=None):
     sel = slice(None) if rows is None else rows
     T = K.shape[0]
     D = lo.kv_heads * lo.head_dim
-    shape = (-1, lo.kv_heads, lo.head_dim)
+    shape = (-1, lo.groups_per_token, lo.group)           # rotation groups: one per head, or the whole token
     reports = []
     for which, X, codes, scales, hat, signs in (
             ("k", K, g["k_codes"], g["k_scales"], g["Khat"], lo.signs_k),
@@ -259,8 +260,9 @@ def check_layer_against_oracle(B, lo, lg, K, V, g, rows=None):
         else:
             p64 = np.zeros((U.np64(X[sel]).reshape(shape)).shape)
         x64 = U.np64(X[sel]).reshape(shape)
-        c = codes[sel].cpu().numpy()
+        c = codes[sel].cpu().numpy().reshape(x64.shape[0], lo.groups_per_token, -1)
         s = scales[sel].cpu().numpy()
+        signs = np.asarray(signs).reshape(lo.groups_per_token, lo.group)
         rep = U.compare_quantizer_outputs(x64 - p64, signs, lo.codebook, c, s, n)
         reports.append(rep)
         assert rep.other == 0, f"{which}: {rep}"
@@ -350,6 +352,54 @@ def test_encode_without_optional_outputs_matches(B):
     B.aquakv_decode_layer(lg, T, kc, ks, None, None, g["Kp"], None, Kh, None, lg.alloc_workspace(T))
     sync()
     assert torch.equal(bits(Kh), bits(g["Khat"]))
+
+
+# ------------------------------------------------------------------ rotation groups of 1024 across the heads
+@pytest.mark.parametrize("dtype,n", [("bf16", 16), ("bf16", 64), ("fp32", 16), ("bf16", 256)])
+def test_rotation_group_1024_across_heads(B, dtype, n):
+    """rht_group = kv_heads * head_dim (the grouping of the paper's experiments): one rotation and one scale per
+    token.  Every stage teacher-forced against the oracle, closed loop, row-count independence, scores."""
+    print(f"case group 1024 dtype={dtype} n={n}", flush=True)
+    H, T = 8, 333
+    cfg = synth.Config("wide", layers=3, kv_heads=H, head_dim=128, tokens=T, dtype=dtype, n_codewords=n)
+    Ks, Vs, lo_l, lg_l = build_stack(cfg, rht_group=H * 128)
+    out = run_gpu_layers(B, cfg, lg_l, Ks, Vs)
+    for l in range(cfg.layers):
+        g, lg = out[l], lg_l[l]
+        assert g["k_scales"].shape == (T, 1) and g["k_codes"].shape == (T, H, 16 * (n.bit_length() - 1) // 2)
+        for rep in check_layer_against_oracle(B, lo_l[l], lg, Ks[l], Vs[l], g):
+            print(f"   layer {l}: {rep}", flush=True)
+        Kh, Vh = lg.alloc_kv(T), lg.alloc_kv(T)
+        B.aquakv_decode_layer(lg, T, g["k_codes"], g["k_scales"], g["v_codes"], g["v_scales"], g["Kp"], g["Vp"], Kh, Vh,
+                              lg.alloc_workspace(T))
+        sync()
+        assert torch.equal(bits(Kh), bits(g["Khat"])) and torch.equal(bits(Vh), bits(g["Vhat"]))
+        r0, r1 = 57, 121
+        cut = lambda t: None if t is None else t[r0:r1].contiguous()
+        Kh2, Vh2 = lg.alloc_kv(r1 - r0), lg.alloc_kv(r1 - r0)
+        B.aquakv_decode_layer(lg, r1 - r0, cut(g["k_codes"]), cut(g["k_scales"]), cut(g["v_codes"]), cut(g["v_scales"]),
+                              cut(g["Kp"]), cut(g["Vp"]), Kh2, Vh2, lg.alloc_workspace(r1 - r0))
+        sync()
+        assert torch.equal(bits(Kh2), bits(g["Khat"][r0:r1])) and torch.equal(bits(Vh2), bits(g["Vhat"][r0:r1]))
+    # the 1024-point rotation gaussianises the synthetic outlier channels better than 128 points:
+    # layer-0 relative error close to the grid's own (0.109 / 0.030 / 0.0084)
+    K0 = U.np64(Ks[0])
+    rel = float(np.sum((U.np64(out[0]["Khat"]) - K0) ** 2) / np.sum(K0 ** 2))
+    assert abs(rel / {16: 0.109, 64: 0.030, 256: 0.0084}[n] - 1) < 0.12, rel
+    # scores of a predicted layer (the folded form does not exist for this grouping)
+    g, lg, lo = out[2], lg_l[2], lo_l[2]
+    QH, batch, S = 16, 3, 111
+    assert B.aquakv_scores_workspace_bytes(lg, batch, QH) == 0
+    q = synth.random_queries(batch, QH, 128, seed=3, dtype=dtype, device="cuda")
+    scores = torch.empty(batch, QH, S, dtype=torch.float32, device="cuda")
+    B.aquakv_decode_attn_scores(lg, batch, S, QH, g["k_codes"], g["k_scales"], g["Kp"], q, 0.5, scores, None,
+                                lg.alloc_workspace(T))
+    sync()
+    want = O.attn_scores(lo, batch, S, U.np64(q), g["k_codes"].cpu().numpy(), g["k_scales"].cpu().numpy().view(np.float16),
+                         U.np64(g["Kp"]), 0.5)
+    Kh = np.abs(U.np64(g["Khat"])).reshape(batch, S, H, 128)
+    mag = np.stack([np.einsum("bd,btd->bt", np.abs(U.np64(q))[:, qh], Kh[:, :, qh // (QH // H)]) for qh in range(QH)], 1)
+    assert np.all(np.abs(U.np64(scores) - want) <= U.RTOL[dtype] * 0.5 * mag + 1e-30)
 
 
 # ------------------------------------------------------------------ fused dequant + q.k
