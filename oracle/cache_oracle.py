@@ -1,0 +1,101 @@
+"""CPU oracle of the cache policy around the per-layer encode / decode calls.
+
+TEST INFRASTRUCTURE ONLY (same rules as aquakv_oracle.py: imported by tests only, shares no
+code with the product package).
+
+What it follows (AQUA-KV paper, arxiv 2501.19392):
+  * Sect. 3.3 "Relation between AQUA-KV and Attention Sinks": the first few tokens (4 in the
+    experiments) stay uncompressed.
+  * Sect. 3.3 "Inference Algorithm" and Alg. "Inference": a buffer of up to r = 128 recent tokens
+    is kept uncompressed; when it is full its contents are quantized layer by layer from the first
+    layer to the last (each layer's predictors read the previous layer's reconstruction of the same
+    tokens); to attend, the past is recovered one layer at a time with Alg. "decode", every layer
+    from the previous layer's recovered past.
+
+Quantization is per token, so flushing the buffer in pieces gives the same codes as encoding the
+same token range in one call; the pin in tests/test_cache_policy.py checks exactly that, and that
+sinks and buffered tokens come back untouched.
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+from . import aquakv_oracle as O
+
+
+class CacheOracle:
+    def __init__(self, layers: Sequence[O.Layer], sink_tokens: int = 4, buffer_tokens: int = 128):
+        self.layers = list(layers)
+        self.sink_tokens, self.buffer_tokens = sink_tokens, buffer_tokens
+        L = len(self.layers)
+        empty = lambda: [None] * L
+        self.sink_k, self.sink_v = empty(), empty()          # [<= sink_tokens, H, g] as given
+        self.buf_k, self.buf_v = empty(), empty()            # [<  buffer_tokens, H, g] as given
+        self.codes = [dict(k_codes=[], k_scales=[], v_codes=[], v_scales=[]) for _ in range(L)]
+        self.n_sink = self.n_compressed = self.n_buffered = 0
+
+    @property
+    def n_tokens(self):
+        return self.n_sink + self.n_compressed + self.n_buffered
+
+    @staticmethod
+    def _cat(a, b):
+        return b if a is None else np.concatenate([a, b], axis=0)
+
+    def append(self, kv: Sequence[Tuple[np.ndarray, np.ndarray]]):
+        """kv[l] = (K, V) of the new tokens at layer l, [t, H, g] holding storage-dtype values."""
+        t = kv[0][0].shape[0]
+        pos = 0
+        while pos < t:
+            if self.n_sink < self.sink_tokens:
+                take = min(self.sink_tokens - self.n_sink, t - pos)
+                for l, (K, V) in enumerate(kv):
+                    self.sink_k[l] = self._cat(self.sink_k[l], np.asarray(K[pos:pos + take], dtype=np.float64))
+                    self.sink_v[l] = self._cat(self.sink_v[l], np.asarray(V[pos:pos + take], dtype=np.float64))
+                self.n_sink += take
+            else:
+                take = min(self.buffer_tokens - self.n_buffered, t - pos)
+                for l, (K, V) in enumerate(kv):
+                    self.buf_k[l] = self._cat(self.buf_k[l], np.asarray(K[pos:pos + take], dtype=np.float64))
+                    self.buf_v[l] = self._cat(self.buf_v[l], np.asarray(V[pos:pos + take], dtype=np.float64))
+                self.n_buffered += take
+                if self.n_buffered == self.buffer_tokens:
+                    self._flush()
+            pos += take
+
+    def _flush(self):
+        """The full buffer is quantized from the first layer to the last (Alg. "encode" per layer)."""
+        Kp = Vp = None
+        for l, lay in enumerate(self.layers):
+            e = O.encode_layer(lay, self.buf_k[l], self.buf_v[l], Kp, Vp)
+            for name in ("k_codes", "k_scales", "v_codes", "v_scales"):
+                self.codes[l][name].append(e[name])
+            Kp, Vp = e["Khat"], e["Vhat"]
+            self.buf_k[l] = self.buf_v[l] = None
+        self.n_compressed += self.n_buffered
+        self.n_buffered = 0
+
+    def sweep(self):
+        """Yield (layer, K, V) for every layer in order: sinks, recovered compressed past, buffered tokens.
+        Only one layer's past is alive at a time (Alg. "Inference", first line of the loop)."""
+        Kp = Vp = None
+        for l, lay in enumerate(self.layers):
+            parts_k, parts_v = [], []
+            if self.n_sink:
+                parts_k.append(self.sink_k[l]); parts_v.append(self.sink_v[l])
+            if self.n_compressed:
+                c = {k: np.concatenate(v, axis=0) for k, v in self.codes[l].items()}
+                Kp, Vp = O.decode_layer(lay, c["k_codes"], c["k_scales"], c["v_codes"], c["v_scales"], Kp, Vp)
+                parts_k.append(Kp); parts_v.append(Vp)
+            if self.n_buffered:
+                parts_k.append(self.buf_k[l]); parts_v.append(self.buf_v[l])
+            yield l, np.concatenate(parts_k, axis=0), np.concatenate(parts_v, axis=0)
+
+    def stored_bytes(self, elem_bytes: int = 2) -> int:
+        """Bytes held for all layers: uncompressed sinks and buffer, packed codes and fp16 scales."""
+        per_tok = self.layers[0].kv_heads * self.layers[0].head_dim * elem_bytes * 2
+        raw = (self.n_sink + self.n_buffered) * per_tok * len(self.layers)
+        comp = sum(int(a.size) * a.itemsize for c in self.codes for v in c.values() for a in v)
+        return raw + comp

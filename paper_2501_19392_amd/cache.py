@@ -1,0 +1,111 @@
+"""Cache policy around the per-layer calls: attention sinks, recent-token buffer, flush and recovery.
+
+AQUA-KV paper (arxiv 2501.19392), Sect. 3.3: the first few tokens ("attention sinks", 4 in the
+experiments) stay in 16 bits; up to r = 128 recent tokens are kept uncompressed and, when that buffer
+is full, quantized layer by layer from the first layer to the last; Alg. "Inference": to attend, the
+compressed past is recovered one layer at a time, each layer from the previous layer's recovered past.
+
+This class is bookkeeping only: every number is produced by the C-ABI calls (`aquakv_encode_layer`,
+`aquakv_decode_layer`); torch tensors are the device memory they work on.  One sequence per cache.
+"""
+from __future__ import annotations
+
+from typing import Iterator, List, Sequence, Tuple
+
+import torch
+
+from . import binding as B
+
+
+class AquaKVCache:
+    def __init__(self, layers: Sequence[B.Layer], max_tokens: int, sink_tokens: int = 4, buffer_tokens: int = 128,
+                 device="cuda"):
+        if buffer_tokens < 1 or sink_tokens < 0:
+            raise ValueError("buffer_tokens >= 1 and sink_tokens >= 0")
+        self.layers = list(layers)
+        self.sink_tokens, self.buffer_tokens, self.max_tokens = sink_tokens, buffer_tokens, max_tokens
+        lay0 = self.layers[0]
+        H, g, dt = lay0.kv_heads, lay0.head_dim, lay0.dtype
+        raw = lambda t: torch.empty(t, H, g, dtype=dt, device=device)
+        self.sink = [(raw(max(sink_tokens, 1)), raw(max(sink_tokens, 1))) for _ in self.layers]
+        self.buf = [(raw(buffer_tokens), raw(buffer_tokens)) for _ in self.layers]
+        cap = max(max_tokens - sink_tokens, 0) // buffer_tokens * buffer_tokens      # the compressed range grows by whole buffers
+        self.codes = [(l.alloc_codes(max(cap, 1), device), l.alloc_codes(max(cap, 1), device)) for l in self.layers]
+        self.capacity = cap
+        # flush: reconstructions of the flushed tokens, two ping-pong pairs (layer l - 1 feeds layer l)
+        self._flush_hat = [(raw(buffer_tokens), raw(buffer_tokens)) for _ in range(2)]
+        self._flush_ws = max((l.alloc_workspace(buffer_tokens, device) for l in self.layers), key=lambda t: t.numel())
+        # recovery: [sinks | compressed | buffer] of one layer, two ping-pong pairs
+        self._view = [(raw(max_tokens), raw(max_tokens)) for _ in range(2)]
+        self._view_ws = max((l.alloc_workspace(max(cap, 1), device) for l in self.layers), key=lambda t: t.numel())
+        self.n_sink = self.n_compressed = self.n_buffered = 0
+
+    @property
+    def n_tokens(self) -> int:
+        return self.n_sink + self.n_compressed + self.n_buffered
+
+    def append(self, kv: Sequence[Tuple[torch.Tensor, torch.Tensor]]) -> None:
+        """kv[l] = (K, V) of the new tokens at layer l, [t, kv_heads, head_dim] in the storage dtype."""
+        if len(kv) != len(self.layers):
+            raise ValueError("one (K, V) pair per layer")
+        t = kv[0][0].shape[0]
+        if self.n_tokens + t > self.max_tokens:
+            raise ValueError("cache is full")
+        pos = 0
+        while pos < t:
+            if self.n_sink < self.sink_tokens:
+                take = min(self.sink_tokens - self.n_sink, t - pos)
+                for l, (K, V) in enumerate(kv):
+                    self.sink[l][0][self.n_sink:self.n_sink + take].copy_(K[pos:pos + take])
+                    self.sink[l][1][self.n_sink:self.n_sink + take].copy_(V[pos:pos + take])
+                self.n_sink += take
+            else:
+                take = min(self.buffer_tokens - self.n_buffered, t - pos)
+                for l, (K, V) in enumerate(kv):
+                    self.buf[l][0][self.n_buffered:self.n_buffered + take].copy_(K[pos:pos + take])
+                    self.buf[l][1][self.n_buffered:self.n_buffered + take].copy_(V[pos:pos + take])
+                self.n_buffered += take
+                if self.n_buffered == self.buffer_tokens:
+                    self._flush()
+            pos += take
+
+    def _flush(self) -> None:
+        """The full buffer is quantized from the first layer to the last; codes land behind the compressed range."""
+        r, at = self.buffer_tokens, self.n_compressed
+        Kp = Vp = None
+        for l, lay in enumerate(self.layers):
+            (kc, ks), (vc, vs) = self.codes[l]
+            Kh, Vh = self._flush_hat[l & 1]
+            B.aquakv_encode_layer(lay, r, self.buf[l][0], self.buf[l][1], Kp, Vp, kc[at:at + r], ks[at:at + r],
+                                  vc[at:at + r], vs[at:at + r], Kh, Vh, self._flush_ws)
+            Kp, Vp = Kh, Vh
+        self.n_compressed += r
+        self.n_buffered = 0
+
+    def sweep(self) -> Iterator[Tuple[int, torch.Tensor, torch.Tensor]]:
+        """Yield (layer, K, V) for every layer in order, K and V being [n_tokens, kv_heads, head_dim]: sinks, the
+        recovered compressed past, the buffered tokens.  The tensors are views of two ping-pong buffers: layer l's
+        are valid until layer l + 2 is produced."""
+        s, c, b = self.n_sink, self.n_compressed, self.n_buffered
+        Kp = Vp = None
+        for l, lay in enumerate(self.layers):
+            K, V = self._view[l & 1]
+            if s:
+                K[:s].copy_(self.sink[l][0][:s]); V[:s].copy_(self.sink[l][1][:s])
+            if c:
+                (kc, ks), (vc, vs) = self.codes[l]
+                B.aquakv_decode_layer(lay, c, kc[:c], ks[:c], vc[:c], vs[:c], Kp, Vp, K[s:s + c], V[s:s + c], self._view_ws)
+                Kp, Vp = K[s:s + c], V[s:s + c]
+            if b:
+                K[s + c:s + c + b].copy_(self.buf[l][0][:b]); V[s + c:s + c + b].copy_(self.buf[l][1][:b])
+            yield l, K[:s + c + b], V[:s + c + b]
+
+    def stored_bytes(self) -> int:
+        """Bytes the cache content occupies (all layers): 16-bit sinks and buffer, packed codes and fp16 scales."""
+        lay0 = self.layers[0]
+        per_tok = lay0.d * self.sink[0][0].element_size() * 2
+        total = (self.n_sink + self.n_buffered) * per_tok * len(self.layers)
+        for lay in self.layers:
+            groups = lay.d // lay.rht_group
+            total += 2 * self.n_compressed * (lay.kv_heads * lay.code_bytes_per_group + 2 * groups)
+        return total
