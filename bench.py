@@ -166,6 +166,29 @@ def timed_phases(B, layers, Ks, Vs, buf, q, T, q_heads, reps):
     return out
 
 
+def layer0_times(B, layers, Ks, Vs, buf, T, reps):
+    """Layer 0 (no predictor: the stand-alone quantize / dequantize kernels) on its own, ms per call pair."""
+    import torch
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    lay = layers[0]
+    (kc, ks), (vc, vs) = buf.codes[0]
+    Kh, Vh = buf.hat[0]
+    out = {}
+    for phase in ("encode", "decode"):
+        a, b = ev(), ev()
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(reps):
+            if phase == "encode":
+                B.aquakv_encode_layer(lay, T, Ks[0], Vs[0], None, None, kc, ks, vc, vs, Kh, Vh, buf.ws)
+            else:
+                B.aquakv_decode_layer(lay, T, kc, ks, vc, vs, None, None, Kh, Vh, buf.ws)
+        b.record()
+        torch.cuda.synchronize()
+        out[phase] = a.elapsed_time(b) / reps
+    return out
+
+
 def encode_kernel_events(B, layers, Ks, Vs, buf, T, steps):
     """HIP events (on the launch stream) around every `aquakv_encode_layer` call of `steps` passes over
     the predicted layers.  For a bf16 layer with predictors one call is exactly two launches of the
@@ -406,6 +429,14 @@ def main():
     value = T * cfg.layers / (dt / args.steps)
 
     phases = timed_phases(B, layers, Ks, Vs, buf, q, T, q_heads, max(1, min(args.steps, 5)))
+    l0 = layer0_times(B, layers, Ks, Vs, buf, T, 5)
+    eb = 2 if cfg.dtype == "bf16" else 4
+    D = cfg.kv_heads * cfg.head_dim
+    code_b = 2 * T * (cfg.kv_heads * layers[0].code_bytes_per_group + 2 * (D // layers[0].rht_group))
+    # layer 0 moves, per call: encode reads K, V and writes Khat, Vhat + codes; decode reads codes and writes Khat, Vhat
+    l0_bytes = {"encode": 4 * T * D * eb + code_b, "decode": 2 * T * D * eb + code_b}
+    n_pred = max(cfg.layers - 1, 1)
+    pred_ms = {k: (phases[k] - l0[k]) / n_pred for k in ("encode", "decode")}
     roofline = None
     if cfg.dtype == "bf16" and not args.no_kernel_events:
         flops, nbytes, ms, launches = encode_kernel_events(B, layers, Ks, Vs, buf, T, max(1, min(args.steps, 3)))
@@ -433,6 +464,14 @@ def main():
                    "tokens": T, "layers": cfg.layers, "q_heads": q_heads},
         "phases_ms_per_step": {k: round(v, 3) for k, v in phases.items()},
         "tokens_per_s_per_layer": {k: round(T * cfg.layers / (v * 1e-3), 1) for k, v in phases.items()},
+        # encode + decode combined, T / (t_enc + t_dec) per layer: predicted layers (average) and layer 0 apart
+        "encode_plus_decode_tokens_per_s": {
+            "predicted_layers": round(T / ((pred_ms["encode"] + pred_ms["decode"]) * 1e-3), 1),
+            "layer0": round(T / ((l0["encode"] + l0["decode"]) * 1e-3), 1)},
+        "layer0": {"encode_ms": round(l0["encode"], 4), "decode_ms": round(l0["decode"], 4),
+                   "encode_GBs": round(l0_bytes["encode"] / (l0["encode"] * 1e-3) / 1e9, 1),
+                   "decode_GBs": round(l0_bytes["decode"] / (l0["decode"] * 1e-3) / 1e9, 1),
+                   "bound": "alu (VALU issue; HBM peak %.0f GB/s)" % PEAK_HBM_GBS},
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:
