@@ -372,8 +372,8 @@ def decode_read_path(args, device):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (--gpus 1); the path shards by tokens with no "
-              "exchange, see DESIGN.md", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (--gpus 1); the path shards along tokens with no "
+              "exchange between GPUs, so N GPUs are N independent copies of this run", file=sys.stderr)
         sys.exit(2)
     import torch
     from paper_2501_19392_amd import binding as B

@@ -592,6 +592,46 @@ def test_full_size_layers_on_sampled_rows(B, name, T, n_per_layer):
         Kp, Vp = Kh, Vh
 
 
+def test_folded_scores_at_the_full_decode_read_shape(B):
+    """64 sequences x 16384 cached tokens, 32 query heads (the launch configuration of `bench.py --config
+    decode-read`: 32 tiles per workgroup): the folded scoring call against the oracle on sampled (sequence, token)
+    pairs.  The oracle scores any codes, so the cache content is drawn directly (random codes, scales, Khat_prev)."""
+    print("case folded scores, full decode-read shape", flush=True)
+    batch, S, H, QH, n = 64, 16384, 8, 32, 16
+    T = batch * S
+    gen = torch.Generator(device="cuda").manual_seed(synth.BASE_SEED + 404)
+    wk = U.random_weights(1024, 1024, 7, 0.7)
+    lo, lg = U.make_layers(H, "bf16", n, layer_idx=3, w_k=wk, w_v=U.random_weights(1024, 2048, 8, 0.7))
+    Kprev = torch.randn(T, H, 128, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    kc, ks = lg.alloc_codes(T)
+    kc.copy_(torch.randint(0, 256, kc.shape, generator=gen, device="cuda", dtype=torch.int32).to(torch.uint8))
+    ks.copy_((torch.rand(T, H, generator=gen, device="cuda") * 2 + 0.05).half().view(torch.int16))
+    q = synth.random_queries(batch, QH, 128, seed=12, dtype="bf16", device="cuda")
+    need = B.aquakv_scores_workspace_bytes(lg, batch, QH)
+    assert need > 0
+    scores = torch.full((batch, QH, S), float("nan"), dtype=torch.float32, device="cuda")
+    B.aquakv_decode_attn_scores(lg, batch, S, QH, kc, ks, Kprev, q, 0.0883883, scores, None,
+                                torch.empty(need, dtype=torch.uint8, device="cuda"))
+    sync()
+    assert torch.isfinite(scores).all()
+    rng = np.random.Generator(np.random.PCG64(91))
+    worst = 0.0
+    for b in (0, 17, batch - 1):
+        ts = np.unique(np.concatenate([[0, 31, 32, 1023, 1024, S - 33, S - 1], rng.choice(S, 48, replace=False)]))
+        sel = torch.from_numpy(b * S + ts).cuda()
+        want = O.attn_scores(lo, 1, len(ts), U.np64(q[b:b + 1]), kc[sel].cpu().numpy(), ks[sel].cpu().numpy().view(np.float16),
+                             U.np64(Kprev[sel]), 0.0883883)[0]
+        got = U.np64(scores[b][:, torch.from_numpy(ts).cuda()])
+        Khat, _ = O.decode_layer(lo, kc[sel].cpu().numpy(), ks[sel].cpu().numpy().view(np.float16), kc[sel].cpu().numpy(),
+                                 ks[sel].cpu().numpy().view(np.float16), U.np64(Kprev[sel]), U.np64(Kprev[sel]))
+        Ka = np.abs(Khat)
+        mag = np.stack([np.abs(U.np64(q[b, qh])) @ Ka[:, qh // (QH // H)].T for qh in range(QH)], 0)
+        err = np.abs(got - want)
+        assert np.all(err <= U.RTOL["bf16"] * 0.0883883 * mag + 1e-30)
+        worst = max(worst, float(np.max(err / (0.0883883 * mag + 1e-30))))
+    print(f"   worst score error / sum|q||k| = {worst:.2e}", flush=True)
+
+
 def test_decode_read_path_batch_of_long_sequences(B):
     """The decode-phase read path (batched sequences of 16384 cached tokens, 32 query heads on 8 kv
     heads): fused dequantize + q.k against the oracle on sampled (sequence, token) pairs, plus the
