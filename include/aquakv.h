@@ -146,6 +146,7 @@ int aquakv_dequantize(const aquakv_layer* layer, int which, int64_t tokens,
  * Khat_prev / Vhat_prev: required iff the layer has the respective predictor.
  * Khat, Vhat: outputs (nullable).  They are what Alg. "Inference" feeds to the
  * next layer; the stored (rounded) Khat is also what f_value reads.
+ * Khat may alias K and Vhat may alias V (reconstruction in place); nothing else may alias.
  * tokens == 0 is a no-op.
  */
 int aquakv_encode_layer(const aquakv_layer* layer, int64_t tokens,

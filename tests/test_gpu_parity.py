@@ -354,6 +354,26 @@ def test_encode_without_optional_outputs_matches(B):
     assert torch.equal(bits(Kh), bits(g["Khat"]))
 
 
+def test_encode_layer_in_place(B):
+    """Khat may alias K and Vhat may alias V (the reconstruction overwrites the raw tensor): same codes, same
+    reconstructions as out of place, in the fused bf16 path (predicted layer) and the stand-alone path (layer 0)."""
+    print("case encode in place", flush=True)
+    cfg = synth.Config("inplace", layers=2, kv_heads=8, head_dim=128, tokens=517, dtype="bf16", n_codewords=16)
+    Ks, Vs, lo_l, lg_l = build_stack(cfg)
+    out = run_gpu_layers(B, cfg, lg_l, Ks, Vs)
+    T = cfg.tokens
+    for l, lg in enumerate(lg_l):
+        g = out[l]
+        K2, V2 = Ks[l].clone(), Vs[l].clone()
+        kc, ks = lg.alloc_codes(T)
+        vc, vs = lg.alloc_codes(T)
+        B.aquakv_encode_layer(lg, T, K2, V2, g["Kp"], g["Vp"], kc, ks, vc, vs, K2, V2, lg.alloc_workspace(T))
+        sync()
+        assert torch.equal(kc, g["k_codes"]) and torch.equal(ks, g["k_scales"])
+        assert torch.equal(vc, g["v_codes"]) and torch.equal(vs, g["v_scales"])
+        assert torch.equal(bits(K2), bits(g["Khat"])) and torch.equal(bits(V2), bits(g["Vhat"]))
+
+
 # ------------------------------------------------------------------ rotation groups of 1024 across the heads
 @pytest.mark.parametrize("dtype,n", [("bf16", 16), ("bf16", 64), ("fp32", 16), ("bf16", 256)])
 def test_rotation_group_1024_across_heads(B, dtype, n):
