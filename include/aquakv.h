@@ -171,6 +171,29 @@ int aquakv_decode_layer(const aquakv_layer* layer, int64_t tokens,
                         void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The two halves of Alg. "encode" / "decode" as calls of their own (same kernels, same bits as the
+ * layer-level calls).  Over a stack of layers the key chain depends on keys only
+ * (Khat of layer l from Khat of layer l-1), the value chain on the previous layer's values and this
+ * layer's keys, so a caller may put the two chains on two streams, with an event from each key call
+ * to the value call of the same layer, and let the kernels of neighbouring layers overlap.
+ *   aquakv_encode_keys   : K_q = Q(K - f_key(Khat_prev)); Khat (nullable) = reconstruction.
+ *   aquakv_encode_values : V_q = Q(V - f_value([Vhat_prev; Khat])); Khat is an INPUT here (required iff
+ *                          the layer has a value predictor); Vhat (nullable) = reconstruction.
+ *   aquakv_decode_values : Vhat = Q^-1(V_q) + f_value([Vhat_prev; Khat]); Khat is an INPUT.
+ *   (keys only of Alg. "decode": aquakv_decode_layer with Vhat = NULL.)
+ * Workspace: the fp32 prediction part of aquakv_workspace_bytes() suffices (none for fused bf16 layers).
+ */
+int aquakv_encode_keys(const aquakv_layer* layer, int64_t tokens, const void* K, const void* Khat_prev,
+                       uint8_t* k_codes, uint16_t* k_scales, void* Khat,
+                       void* workspace, size_t workspace_bytes, void* stream);
+int aquakv_encode_values(const aquakv_layer* layer, int64_t tokens, const void* V, const void* Vhat_prev,
+                         const void* Khat, uint8_t* v_codes, uint16_t* v_scales, void* Vhat,
+                         void* workspace, size_t workspace_bytes, void* stream);
+int aquakv_decode_values(const aquakv_layer* layer, int64_t tokens, const uint8_t* v_codes, const uint16_t* v_scales,
+                         const void* Vhat_prev, const void* Khat, void* Vhat,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * aquakv_decode_attn_scores -- decode of the keys (Alg. "decode", first line)
  * fused with grouped-query q.k scoring, so the keys need not be written:
  *   scores[b, qh, t] = score_scale * sum_d q[b, qh, d] * Khat[b*seq_len + t, qh / (q_heads/H), d]

@@ -33,6 +33,7 @@ EXPORTS = [
     "aquakv_predict", "aquakv_quantize", "aquakv_dequantize",
     "aquakv_encode_layer", "aquakv_decode_layer", "aquakv_decode_attn_scores",
     "aquakv_scores_workspace_bytes", "aquakv_decode_attn_scores_rope",
+    "aquakv_encode_keys", "aquakv_encode_values", "aquakv_decode_values",
 ]
 
 
@@ -70,8 +71,12 @@ _lib.aquakv_decode_attn_scores.argtypes = ([_LP, ctypes.c_int32, ctypes.c_int32,
                                             ctypes.c_float, _P, _P, _P, ctypes.c_size_t, _P])
 _lib.aquakv_decode_attn_scores_rope.argtypes = ([_LP, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _P, _P, _P, _P, _P, _P,
                                                  ctypes.c_float, _P, _P, _P, ctypes.c_size_t, _P])
+_lib.aquakv_encode_keys.argtypes = [_LP, ctypes.c_int64] + [_P] * 6 + [ctypes.c_size_t, _P]
+_lib.aquakv_encode_values.argtypes = [_LP, ctypes.c_int64] + [_P] * 7 + [ctypes.c_size_t, _P]
+_lib.aquakv_decode_values.argtypes = [_LP, ctypes.c_int64] + [_P] * 6 + [ctypes.c_size_t, _P]
 for _n in ("aquakv_predict", "aquakv_quantize", "aquakv_dequantize", "aquakv_encode_layer", "aquakv_decode_layer",
-           "aquakv_decode_attn_scores", "aquakv_decode_attn_scores_rope"):
+           "aquakv_decode_attn_scores", "aquakv_decode_attn_scores_rope", "aquakv_encode_keys", "aquakv_encode_values",
+           "aquakv_decode_values"):
     getattr(_lib, _n).restype = ctypes.c_int
 
 
@@ -248,6 +253,24 @@ def aquakv_decode_layer(layer, tokens: int, k_codes, k_scales, v_codes, v_scales
     _check(_lib.aquakv_decode_layer(_layer_ref(layer), tokens, _ptr(k_codes), _ptr(k_scales), _ptr(v_codes),
                                     _ptr(v_scales), _ptr(Khat_prev), _ptr(Vhat_prev), _ptr(Khat), _ptr(Vhat),
                                     ws, nbytes, _stream(stream)))
+
+
+def aquakv_encode_keys(layer, tokens: int, K, Khat_prev, k_codes, k_scales, Khat, workspace, stream=None) -> None:
+    ws, nbytes = _ws(workspace)
+    _check(_lib.aquakv_encode_keys(_layer_ref(layer), tokens, _ptr(K), _ptr(Khat_prev), _ptr(k_codes), _ptr(k_scales),
+                                   _ptr(Khat), ws, nbytes, _stream(stream)))
+
+
+def aquakv_encode_values(layer, tokens: int, V, Vhat_prev, Khat, v_codes, v_scales, Vhat, workspace, stream=None) -> None:
+    ws, nbytes = _ws(workspace)
+    _check(_lib.aquakv_encode_values(_layer_ref(layer), tokens, _ptr(V), _ptr(Vhat_prev), _ptr(Khat), _ptr(v_codes),
+                                     _ptr(v_scales), _ptr(Vhat), ws, nbytes, _stream(stream)))
+
+
+def aquakv_decode_values(layer, tokens: int, v_codes, v_scales, Vhat_prev, Khat, Vhat, workspace, stream=None) -> None:
+    ws, nbytes = _ws(workspace)
+    _check(_lib.aquakv_decode_values(_layer_ref(layer), tokens, _ptr(v_codes), _ptr(v_scales), _ptr(Vhat_prev), _ptr(Khat),
+                                     _ptr(Vhat), ws, nbytes, _stream(stream)))
 
 
 def aquakv_decode_attn_scores_rope(layer, batch: int, seq_len: int, q_heads: int, k_codes, k_scales, Khat_prev, q,

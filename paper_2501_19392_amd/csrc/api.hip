@@ -122,6 +122,99 @@ inline void* at(void* base, int64_t row, size_t row_bytes) {
   return base == nullptr ? nullptr : static_cast<unsigned char*>(base) + row * row_bytes;
 }
 
+// ---- one chunk of rows [r0, r0 + n) of one tensor; pointers are the tensors' bases -------------------------------
+// keys of Alg. "encode":  K_pred = f_key(Khat_prev);  K_q = Q(K - K_pred);  khat_dst (chunk-local, nullable) = Q^-1(K_q) + K_pred
+int encode_keys_chunk(const aquakv_layer* L, const Plan& pl, int64_t r0, int64_t n, const void* K, const void* Khat_prev,
+                      uint8_t* k_codes, uint16_t* k_scales, void* khat_dst, float* Pbuf, hipStream_t stream) {
+  const bool has_k = L->d_in_k != 0;
+  const size_t row = (size_t)pl.D * pl.eb, srow = scale_row_bytes(L);
+  if (has_k && pl.fused) {
+    HIP_TRY(aquakv::launch_fused_encode(L->n_codewords, at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k, nullptr, 0,
+                                        L->w_k, L->b_k, L->signs_k, L->codebook, L->search_table, at(K, r0, row),
+                                        static_cast<uint8_t*>(at(k_codes, r0, pl.code_row)),
+                                        static_cast<uint16_t*>(at(k_scales, r0, srow)), khat_dst, n, pl.D, stream));
+    return AQUAKV_OK;
+  }
+  if (has_k)
+    HIP_TRY(aquakv::launch_predict(L->dtype, at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k, nullptr, 0, L->w_k,
+                                   L->b_k, Pbuf, n, pl.D, stream));
+  HIP_TRY(aquakv::launch_quantize(L->dtype, L->n_codewords, at(K, r0, row), has_k ? Pbuf : nullptr, L->signs_k, L->codebook,
+                                  L->search_table, static_cast<uint8_t*>(at(k_codes, r0, pl.code_row)),
+                                  static_cast<uint16_t*>(at(k_scales, r0, srow)), khat_dst, n, L->kv_heads, is_wide(L),
+                                  stream));
+  return AQUAKV_OK;
+}
+
+// values of Alg. "encode":  V_pred = f_value([Vhat_prev; Khat]);  V_q = Q(V - V_pred);  khat_src is chunk-local
+int encode_values_chunk(const aquakv_layer* L, const Plan& pl, int64_t r0, int64_t n, const void* V, const void* Vhat_prev,
+                        const void* khat_src, uint8_t* v_codes, uint16_t* v_scales, void* Vhat, float* Pbuf,
+                        hipStream_t stream) {
+  const bool has_v = L->d_in_v != 0;
+  const int D = pl.D;
+  const size_t row = (size_t)D * pl.eb, srow = scale_row_bytes(L);
+  if (has_v && pl.fused) {
+    HIP_TRY(aquakv::launch_fused_encode(L->n_codewords, at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb), L->d_in_v - D,
+                                        khat_src, D, L->w_v, L->b_v, L->signs_v, L->codebook, L->search_table, at(V, r0, row),
+                                        static_cast<uint8_t*>(at(v_codes, r0, pl.code_row)),
+                                        static_cast<uint16_t*>(at(v_scales, r0, srow)), at(Vhat, r0, row), n, D, stream));
+    return AQUAKV_OK;
+  }
+  if (has_v)
+    HIP_TRY(aquakv::launch_predict(L->dtype, at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb), L->d_in_v - D, khat_src, D,
+                                   L->w_v, L->b_v, Pbuf, n, D, stream));
+  HIP_TRY(aquakv::launch_quantize(L->dtype, L->n_codewords, at(V, r0, row), has_v ? Pbuf : nullptr, L->signs_v, L->codebook,
+                                  L->search_table, static_cast<uint8_t*>(at(v_codes, r0, pl.code_row)),
+                                  static_cast<uint16_t*>(at(v_scales, r0, srow)), at(Vhat, r0, row), n, L->kv_heads,
+                                  is_wide(L), stream));
+  return AQUAKV_OK;
+}
+
+// keys of Alg. "decode":  Khat = Q^-1(K_q) + f_key(Khat_prev)
+int decode_keys_chunk(const aquakv_layer* L, const Plan& pl, int64_t r0, int64_t n, const uint8_t* k_codes,
+                      const uint16_t* k_scales, const void* Khat_prev, void* Khat, float* Pbuf, hipStream_t stream) {
+  const bool has_k = L->d_in_k != 0;
+  const size_t row = (size_t)pl.D * pl.eb, srow = scale_row_bytes(L);
+  if (has_k && pl.fused) {
+    HIP_TRY(aquakv::launch_fused_decode(L->n_codewords, at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k, nullptr, 0,
+                                        L->w_k, L->b_k, L->signs_k, L->codebook,
+                                        static_cast<const uint8_t*>(at(k_codes, r0, pl.code_row)),
+                                        static_cast<const uint16_t*>(at(k_scales, r0, srow)), at(Khat, r0, row), n, pl.D,
+                                        stream));
+    return AQUAKV_OK;
+  }
+  if (has_k)
+    HIP_TRY(aquakv::launch_predict(L->dtype, at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k, nullptr, 0, L->w_k,
+                                   L->b_k, Pbuf, n, pl.D, stream));
+  HIP_TRY(aquakv::launch_dequantize(L->dtype, L->n_codewords, static_cast<const uint8_t*>(at(k_codes, r0, pl.code_row)),
+                                    static_cast<const uint16_t*>(at(k_scales, r0, srow)), has_k ? Pbuf : nullptr, L->signs_k,
+                                    L->codebook, at(Khat, r0, row), n, L->kv_heads, is_wide(L), stream));
+  return AQUAKV_OK;
+}
+
+// values of Alg. "decode":  Vhat = Q^-1(V_q) + f_value([Vhat_prev; Khat])
+int decode_values_chunk(const aquakv_layer* L, const Plan& pl, int64_t r0, int64_t n, const uint8_t* v_codes,
+                        const uint16_t* v_scales, const void* Vhat_prev, const void* Khat, void* Vhat, float* Pbuf,
+                        hipStream_t stream) {
+  const bool has_v = L->d_in_v != 0;
+  const int D = pl.D;
+  const size_t row = (size_t)D * pl.eb, srow = scale_row_bytes(L);
+  if (has_v && pl.fused) {
+    HIP_TRY(aquakv::launch_fused_decode(L->n_codewords, at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb), L->d_in_v - D,
+                                        at(Khat, r0, row), D, L->w_v, L->b_v, L->signs_v, L->codebook,
+                                        static_cast<const uint8_t*>(at(v_codes, r0, pl.code_row)),
+                                        static_cast<const uint16_t*>(at(v_scales, r0, srow)), at(Vhat, r0, row), n, D,
+                                        stream));
+    return AQUAKV_OK;
+  }
+  if (has_v)
+    HIP_TRY(aquakv::launch_predict(L->dtype, at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb), L->d_in_v - D,
+                                   at(Khat, r0, row), D, L->w_v, L->b_v, Pbuf, n, D, stream));
+  HIP_TRY(aquakv::launch_dequantize(L->dtype, L->n_codewords, static_cast<const uint8_t*>(at(v_codes, r0, pl.code_row)),
+                                    static_cast<const uint16_t*>(at(v_scales, r0, srow)), has_v ? Pbuf : nullptr, L->signs_v,
+                                    L->codebook, at(Vhat, r0, row), n, L->kv_heads, is_wide(L), stream));
+  return AQUAKV_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -241,42 +334,12 @@ int aquakv_encode_layer(const aquakv_layer* L, int64_t tokens, const void* K, co
   float* Pbuf = static_cast<float*>(workspace);
   void* khat_tmp = static_cast<unsigned char*>(workspace) + pl.p_bytes;
   const size_t row = (size_t)pl.D * pl.eb;
-  const size_t srow = scale_row_bytes(L);
-  const int D = pl.D, H = L->kv_heads;
 
   for (int64_t r0 = 0; r0 < tokens; r0 += pl.chunk) {
     const int64_t n = tokens - r0 < pl.chunk ? tokens - r0 : pl.chunk;
-    // keys:  K_pred = f_key(Khat_prev);  K_q = Q(K - K_pred);  Khat = Q^-1(K_q) + K_pred
     void* khat_dst = Khat != nullptr ? at(Khat, r0, row) : (has_v ? khat_tmp : nullptr);
-    if (has_k && pl.fused) {
-      HIP_TRY(aquakv::launch_fused_encode(L->n_codewords, at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k,
-                                          nullptr, 0, L->w_k, L->b_k, L->signs_k, L->codebook, L->search_table,
-                                          at(K, r0, row), static_cast<uint8_t*>(at(k_codes, r0, pl.code_row)),
-                                          static_cast<uint16_t*>(at(k_scales, r0, srow)), khat_dst, n, D, stream));
-    } else {
-      if (has_k)
-        HIP_TRY(aquakv::launch_predict(L->dtype, at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k, nullptr, 0,
-                                       L->w_k, L->b_k, Pbuf, n, D, stream));
-      HIP_TRY(aquakv::launch_quantize(L->dtype, L->n_codewords, at(K, r0, row), has_k ? Pbuf : nullptr, L->signs_k,
-                                      L->codebook, L->search_table, static_cast<uint8_t*>(at(k_codes, r0, pl.code_row)),
-                                      static_cast<uint16_t*>(at(k_scales, r0, srow)), khat_dst, n, H, is_wide(L), stream));
-    }
-    // values: V_pred = f_value([Vhat_prev; Khat]);  V_q = Q(V - V_pred)
-    if (has_v && pl.fused) {
-      HIP_TRY(aquakv::launch_fused_encode(L->n_codewords, at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb),
-                                          L->d_in_v - D, khat_dst, D, L->w_v, L->b_v, L->signs_v, L->codebook,
-                                          L->search_table, at(V, r0, row),
-                                          static_cast<uint8_t*>(at(v_codes, r0, pl.code_row)),
-                                          static_cast<uint16_t*>(at(v_scales, r0, srow)), at(Vhat, r0, row), n, D,
-                                          stream));
-    } else {
-      if (has_v)
-        HIP_TRY(aquakv::launch_predict(L->dtype, at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb), L->d_in_v - D,
-                                       khat_dst, D, L->w_v, L->b_v, Pbuf, n, D, stream));
-      HIP_TRY(aquakv::launch_quantize(L->dtype, L->n_codewords, at(V, r0, row), has_v ? Pbuf : nullptr, L->signs_v,
-                                      L->codebook, L->search_table, static_cast<uint8_t*>(at(v_codes, r0, pl.code_row)),
-                                      static_cast<uint16_t*>(at(v_scales, r0, srow)), at(Vhat, r0, row), n, H, is_wide(L), stream));
-    }
+    CHECK(encode_keys_chunk(L, pl, r0, n, K, Khat_prev, k_codes, k_scales, khat_dst, Pbuf, stream));
+    CHECK(encode_values_chunk(L, pl, r0, n, V, Vhat_prev, khat_dst, v_codes, v_scales, Vhat, Pbuf, stream));
   }
   return AQUAKV_OK;
 }
@@ -304,45 +367,90 @@ int aquakv_decode_layer(const aquakv_layer* L, int64_t tokens, const uint8_t* k_
 
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   float* Pbuf = static_cast<float*>(workspace);
-  const size_t row = (size_t)pl.D * pl.eb;
-  const size_t srow = scale_row_bytes(L);
-  const int D = pl.D, H = L->kv_heads;
 
   for (int64_t r0 = 0; r0 < tokens; r0 += pl.chunk) {
     const int64_t n = tokens - r0 < pl.chunk ? tokens - r0 : pl.chunk;
-    // Khat = Q^-1(K_q) + f_key(Khat_prev)
-    if (has_k && pl.fused) {
-      HIP_TRY(aquakv::launch_fused_decode(L->n_codewords, at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k,
-                                          nullptr, 0, L->w_k, L->b_k, L->signs_k, L->codebook,
-                                          static_cast<const uint8_t*>(at(k_codes, r0, pl.code_row)),
-                                          static_cast<const uint16_t*>(at(k_scales, r0, srow)), at(Khat, r0, row), n, D,
-                                          stream));
-    } else {
-      if (has_k)
-        HIP_TRY(aquakv::launch_predict(L->dtype, at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k, nullptr, 0,
-                                       L->w_k, L->b_k, Pbuf, n, D, stream));
-      HIP_TRY(aquakv::launch_dequantize(L->dtype, L->n_codewords,
-                                        static_cast<const uint8_t*>(at(k_codes, r0, pl.code_row)),
-                                        static_cast<const uint16_t*>(at(k_scales, r0, srow)), has_k ? Pbuf : nullptr,
-                                        L->signs_k, L->codebook, at(Khat, r0, row), n, H, is_wide(L), stream));
-    }
-    if (!want_v) continue;
-    // Vhat = Q^-1(V_q) + f_value([Vhat_prev; Khat])
-    if (has_v && pl.fused) {
-      HIP_TRY(aquakv::launch_fused_decode(L->n_codewords, at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb),
-                                          L->d_in_v - D, at(Khat, r0, row), D, L->w_v, L->b_v, L->signs_v, L->codebook,
-                                          static_cast<const uint8_t*>(at(v_codes, r0, pl.code_row)),
-                                          static_cast<const uint16_t*>(at(v_scales, r0, srow)), at(Vhat, r0, row), n, D,
-                                          stream));
-    } else {
-      if (has_v)
-        HIP_TRY(aquakv::launch_predict(L->dtype, at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb), L->d_in_v - D,
-                                       at(Khat, r0, row), D, L->w_v, L->b_v, Pbuf, n, D, stream));
-      HIP_TRY(aquakv::launch_dequantize(L->dtype, L->n_codewords,
-                                        static_cast<const uint8_t*>(at(v_codes, r0, pl.code_row)),
-                                        static_cast<const uint16_t*>(at(v_scales, r0, srow)), has_v ? Pbuf : nullptr,
-                                        L->signs_v, L->codebook, at(Vhat, r0, row), n, H, is_wide(L), stream));
-    }
+    CHECK(decode_keys_chunk(L, pl, r0, n, k_codes, k_scales, Khat_prev, Khat, Pbuf, stream));
+    if (want_v) CHECK(decode_values_chunk(L, pl, r0, n, v_codes, v_scales, Vhat_prev, Khat, Vhat, Pbuf, stream));
+  }
+  return AQUAKV_OK;
+}
+
+// ---- the two halves of Alg. "encode" / "decode" as calls of their own -------------------------------------------
+// The key chain of a layer stack depends on keys only, the value chain on the previous values and this layer's keys,
+// so a caller can run them on two streams (events between them) and overlap the kernels of neighbouring layers.
+int aquakv_encode_keys(const aquakv_layer* L, int64_t tokens, const void* K, const void* Khat_prev, uint8_t* k_codes,
+                       uint16_t* k_scales, void* Khat, void* workspace, size_t workspace_bytes, void* stream_) {
+  CHECK(check_layer(L));
+  if (tokens < 0) return fail(AQUAKV_EINVAL, "tokens=%lld", (long long)tokens);
+  CHECK(check_ptr(K, "K", true));
+  CHECK(check_ptr(Khat_prev, "Khat_prev", L->d_in_k != 0));
+  CHECK(check_ptr(k_codes, "k_codes", true));
+  CHECK(check_scales(k_scales, "k_scales", true));
+  CHECK(check_ptr(Khat, "Khat", false));
+  if (tokens == 0) return AQUAKV_OK;
+  const Plan pl = make_plan(L, tokens);
+  if (pl.p_bytes != 0) {
+    CHECK(check_ptr(workspace, "workspace", true));
+    if (workspace_bytes < pl.p_bytes) return fail(AQUAKV_EWORKSPACE, "workspace %zu B < required %zu B", workspace_bytes, pl.p_bytes);
+  }
+  const size_t row = (size_t)pl.D * pl.eb;
+  for (int64_t r0 = 0; r0 < tokens; r0 += pl.chunk) {
+    const int64_t n = tokens - r0 < pl.chunk ? tokens - r0 : pl.chunk;
+    CHECK(encode_keys_chunk(L, pl, r0, n, K, Khat_prev, k_codes, k_scales, at(Khat, r0, row), static_cast<float*>(workspace),
+                            static_cast<hipStream_t>(stream_)));
+  }
+  return AQUAKV_OK;
+}
+
+int aquakv_encode_values(const aquakv_layer* L, int64_t tokens, const void* V, const void* Vhat_prev, const void* Khat,
+                         uint8_t* v_codes, uint16_t* v_scales, void* Vhat, void* workspace, size_t workspace_bytes,
+                         void* stream_) {
+  CHECK(check_layer(L));
+  if (tokens < 0) return fail(AQUAKV_EINVAL, "tokens=%lld", (long long)tokens);
+  const bool has_v = L->d_in_v != 0;
+  CHECK(check_ptr(V, "V", true));
+  CHECK(check_ptr(Vhat_prev, "Vhat_prev", has_v));
+  CHECK(check_ptr(Khat, "Khat", has_v));
+  CHECK(check_ptr(v_codes, "v_codes", true));
+  CHECK(check_scales(v_scales, "v_scales", true));
+  CHECK(check_ptr(Vhat, "Vhat", false));
+  if (tokens == 0) return AQUAKV_OK;
+  const Plan pl = make_plan(L, tokens);
+  if (pl.p_bytes != 0) {
+    CHECK(check_ptr(workspace, "workspace", true));
+    if (workspace_bytes < pl.p_bytes) return fail(AQUAKV_EWORKSPACE, "workspace %zu B < required %zu B", workspace_bytes, pl.p_bytes);
+  }
+  const size_t row = (size_t)pl.D * pl.eb;
+  for (int64_t r0 = 0; r0 < tokens; r0 += pl.chunk) {
+    const int64_t n = tokens - r0 < pl.chunk ? tokens - r0 : pl.chunk;
+    CHECK(encode_values_chunk(L, pl, r0, n, V, Vhat_prev, at(Khat, r0, row), v_codes, v_scales, Vhat,
+                              static_cast<float*>(workspace), static_cast<hipStream_t>(stream_)));
+  }
+  return AQUAKV_OK;
+}
+
+int aquakv_decode_values(const aquakv_layer* L, int64_t tokens, const uint8_t* v_codes, const uint16_t* v_scales,
+                         const void* Vhat_prev, const void* Khat, void* Vhat, void* workspace, size_t workspace_bytes,
+                         void* stream_) {
+  CHECK(check_layer(L));
+  if (tokens < 0) return fail(AQUAKV_EINVAL, "tokens=%lld", (long long)tokens);
+  const bool has_v = L->d_in_v != 0;
+  CHECK(check_ptr(v_codes, "v_codes", true));
+  CHECK(check_scales(v_scales, "v_scales", true));
+  CHECK(check_ptr(Vhat_prev, "Vhat_prev", has_v));
+  CHECK(check_ptr(Khat, "Khat", has_v));
+  CHECK(check_ptr(Vhat, "Vhat", true));
+  if (tokens == 0) return AQUAKV_OK;
+  const Plan pl = make_plan(L, tokens);
+  if (pl.p_bytes != 0) {
+    CHECK(check_ptr(workspace, "workspace", true));
+    if (workspace_bytes < pl.p_bytes) return fail(AQUAKV_EWORKSPACE, "workspace %zu B < required %zu B", workspace_bytes, pl.p_bytes);
+  }
+  for (int64_t r0 = 0; r0 < tokens; r0 += pl.chunk) {
+    const int64_t n = tokens - r0 < pl.chunk ? tokens - r0 : pl.chunk;
+    CHECK(decode_values_chunk(L, pl, r0, n, v_codes, v_scales, Vhat_prev, Khat, Vhat, static_cast<float*>(workspace),
+                              static_cast<hipStream_t>(stream_)));
   }
   return AQUAKV_OK;
 }

@@ -136,3 +136,21 @@ def test_scores_workspace_query():
     assert B.aquakv_scores_workspace_bytes(layer(kv_heads=4), 1, 32) == 0
     assert B.aquakv_scores_workspace_bytes(layer(d_in_k=0, d_in_v=0, w_k=None, w_v=None), 1, 32) == 0   # layer 0
     assert B.aquakv_scores_workspace_bytes(layer(head_dim=64), 1, 32) == 0                  # invalid layer
+
+
+def test_half_calls_validate_their_arguments():
+    L = layer()
+    ws = (FAKE, 1 << 30)
+    assert status_of(B.aquakv_encode_keys, L, 8, None, FAKE, FAKE, FAKE, FAKE, ws) == B.AQUAKV_ENULL          # K
+    assert status_of(B.aquakv_encode_keys, L, 8, FAKE, None, FAKE, FAKE, FAKE, ws) == B.AQUAKV_ENULL          # Khat_prev
+    assert status_of(B.aquakv_encode_keys, L, -1, FAKE, FAKE, FAKE, FAKE, FAKE, ws) == B.AQUAKV_EINVAL
+    assert status_of(B.aquakv_encode_values, L, 8, FAKE, FAKE, None, FAKE, FAKE, FAKE, ws) == B.AQUAKV_ENULL  # Khat is an input
+    assert status_of(B.aquakv_encode_values, L, 8, FAKE, FAKE, FAKE + 8, FAKE, FAKE, FAKE, ws) == B.AQUAKV_EALIGN
+    assert status_of(B.aquakv_decode_values, L, 8, FAKE, FAKE, FAKE, FAKE, None, ws) == B.AQUAKV_ENULL        # Vhat out
+    L32 = layer(dtype=B.AQUAKV_FP32)
+    assert status_of(B.aquakv_decode_values, L32, 8, FAKE, FAKE, FAKE, FAKE, FAKE, (FAKE, 16)) == B.AQUAKV_EWORKSPACE
+    B.aquakv_encode_keys(L, 0, FAKE, FAKE, FAKE, FAKE, None, None)               # tokens == 0: no-op
+    B.aquakv_encode_values(L, 0, FAKE, FAKE, FAKE, FAKE, FAKE, None, None)
+    B.aquakv_decode_values(L, 0, FAKE, FAKE, FAKE, FAKE, FAKE, None)
+    L0 = layer(d_in_k=0, d_in_v=0, w_k=None, w_v=None)                          # no predictors: no *_prev, no Khat input
+    assert status_of(B.aquakv_encode_values, L0, 8, FAKE, None, None, None, FAKE, FAKE, ws) == B.AQUAKV_ENULL  # v_codes

@@ -374,6 +374,53 @@ def test_encode_layer_in_place(B):
         assert torch.equal(bits(K2), bits(g["Khat"])) and torch.equal(bits(V2), bits(g["Vhat"]))
 
 
+@pytest.mark.parametrize("dtype,rht_group", [("bf16", None), ("fp32", None), ("bf16", 1024)])
+def test_key_and_value_halves_on_two_streams(B, dtype, rht_group):
+    """aquakv_encode_keys / aquakv_encode_values / aquakv_decode_values (+ keys-only aquakv_decode_layer): the key
+    chain on one stream, the value chain on another with an event per layer, give the same bytes as the layer calls."""
+    print(f"case halves dtype={dtype} rht_group={rht_group}", flush=True)
+    H = 8 if dtype == "bf16" else 2
+    cfg = synth.Config("halves", layers=4, kv_heads=H, head_dim=128, tokens=700, dtype=dtype, n_codewords=16)
+    Ks, Vs, lo_l, lg_l = build_stack(cfg, rht_group=rht_group)
+    out = run_gpu_layers(B, cfg, lg_l, Ks, Vs)
+    T = cfg.tokens
+    sk, sv = torch.cuda.Stream(), torch.cuda.Stream()
+    sk.wait_stream(torch.cuda.current_stream()); sv.wait_stream(torch.cuda.current_stream())
+    enc, dec = [], []
+    Kp = Vp = None
+    for l, lg in enumerate(lg_l):                        # encode: K chain on sk, V chain on sv
+        kc, ks = lg.alloc_codes(T)
+        vc, vs = lg.alloc_codes(T)
+        Kh, Vh = lg.alloc_kv(T), lg.alloc_kv(T)
+        wk, wv = lg.alloc_workspace(T), lg.alloc_workspace(T)
+        B.aquakv_encode_keys(lg, T, Ks[l], Kp, kc, ks, Kh, wk, stream=sk)
+        ev = torch.cuda.Event(); ev.record(sk)
+        sv.wait_event(ev)
+        B.aquakv_encode_values(lg, T, Vs[l], Vp, Kh, vc, vs, Vh, wv, stream=sv)
+        enc.append((kc, ks, vc, vs, Kh, Vh, wk, wv))
+        Kp, Vp = Kh, Vh
+    sk.synchronize(); sv.synchronize()
+    for l, (kc, ks, vc, vs, Kh, Vh, _, _) in enumerate(enc):
+        g = out[l]
+        assert torch.equal(kc, g["k_codes"]) and torch.equal(ks, g["k_scales"]) and torch.equal(bits(Kh), bits(g["Khat"])), l
+        assert torch.equal(vc, g["v_codes"]) and torch.equal(vs, g["v_scales"]) and torch.equal(bits(Vh), bits(g["Vhat"])), l
+    Kp = Vp = None
+    for l, lg in enumerate(lg_l):                        # decode likewise
+        g = out[l]
+        Kh, Vh = lg.alloc_kv(T), lg.alloc_kv(T)
+        wk, wv = lg.alloc_workspace(T), lg.alloc_workspace(T)
+        with torch.cuda.stream(sk):
+            B.aquakv_decode_layer(lg, T, g["k_codes"], g["k_scales"], None, None, Kp, None, Kh, None, wk, stream=sk)
+        ev = torch.cuda.Event(); ev.record(sk)
+        sv.wait_event(ev)
+        B.aquakv_decode_values(lg, T, g["v_codes"], g["v_scales"], Vp, Kh, Vh, wv, stream=sv)
+        dec.append((Kh, Vh, wk, wv))
+        Kp, Vp = Kh, Vh
+    sk.synchronize(); sv.synchronize()
+    for l, (Kh, Vh, _, _) in enumerate(dec):
+        assert torch.equal(bits(Kh), bits(out[l]["Khat"])) and torch.equal(bits(Vh), bits(out[l]["Vhat"])), l
+
+
 # ------------------------------------------------------------------ rotation groups of 1024 across the heads
 @pytest.mark.parametrize("dtype,n", [("bf16", 16), ("bf16", 64), ("fp32", 16), ("bf16", 256)])
 def test_rotation_group_1024_across_heads(B, dtype, n):
