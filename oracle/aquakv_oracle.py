@@ -16,6 +16,8 @@ function cites the passage of the AQUA-KV paper (arxiv 2501.19392) it follows:
     reconstructed keys).
   * Appendix, Alg. "encode" and Alg. "decode": order of the steps per layer.
   * Sect. 3.1 footnote: Q is scale independent "due to the use of scales".
+  * Sect. 4.1 "Backbone quantization": the second backbone, uniform round-to-nearest
+    with per-group normalisation (groups of 64 channels of a token), rtn_quantize.
 
 Readings taken where the paper is silent (all are also listed in the design
 notes of the repository):
@@ -39,6 +41,10 @@ notes of the repository):
     the rounded tensor that feeds the value predictor and the next layer.
   * layer 0 has no predictor: the prediction is zero and the tensors are
     quantized like any other residual.
+  * round-to-nearest backbone: the paper names the scheme and Table 1 its size
+    (2.50 bits at 2 bits and groups of 64 = 32 bits of metadata per group); taken as
+    min/max over a range that always holds 0, an fp16 step and an integer zero point
+    (details in rtn_quantize).
   * rotary embedding (Sect. 3.3 "Positional embeddings": keys are compressed
     before it): when scoring, the decoded key of token t is rotated by position
     t, coordinate d paired with d + g/2, angles from caller-supplied cos / sin
@@ -55,7 +61,10 @@ predictor storage sizes of Table 1, bf16 / fp16 rounding against torch's
 conversions, the predictor against identity / zero weights, closed loop
 decode(encode(x)), the score identity q . iRHT(z) = RHT'(q) . z, and for the
 rotary embedding: identity at position 0, norm preservation, the complex
-multiplication form, and scores that depend only on the position difference.
+multiplication form, and scores that depend only on the position difference;
+for the round-to-nearest backbone: a group worked by hand, brute force over all
+levels, the half-step error bound, 0 decoding to 0, group independence, the
+2.50 / 2.03 bits of the paper's tables, closed loop through predictors.
 No function here is "parity unpinned".
 """
 from __future__ import annotations
@@ -250,6 +259,65 @@ def dequantize(idx, sigma16, signs, codebook):
 
 
 # --------------------------------------------------------------------------
+# second backbone: uniform round-to-nearest with a zero point (Sect. 4.1, "Backbone quantization")
+# --------------------------------------------------------------------------
+@dataclass
+class RtnDiag:
+    """Side information for reporting ties; not part of the method."""
+    scale: np.ndarray      # fp64 step before rounding to fp16          [..., groups]
+    zero_frac: np.ndarray  # distance of -lo/step to the nearest rounding boundary (x.5) [..., groups]
+    frac: np.ndarray       # the same for every value / step                [..., groups, group]
+
+
+def rtn_quantize(r, bits: int, group: int = 64, scale16_override=None):
+    """Uniform b-bit round-to-nearest with per-group min/max normalisation and an integer zero point.
+
+    Sect. 4.1 names the scheme (simple round-to-nearest with absmax normalisation, group size 64, per-token
+    compression) and Table 1 fixes its size: 2.50 bits per value at 2 bits, i.e. 32 bits of metadata per 64
+    values -- a 16-bit step and a 16-bit zero point.  Reading taken: groups are `group` consecutive channels of a
+    token; lo = min(0, min r), hi = max(0, max r) (the range always holds 0, which then decodes to itself);
+    step = (hi - lo) / (2^b - 1) stored as fp16 (nearest even, clamped to the largest finite value); zero =
+    round(-lo / step) clipped to [0, 2^b - 1]; code = clip(round(r / step) + zero, 0, 2^b - 1), rounding half to
+    even, with the *stored* step.  A stored step of 0 gives codes = zero = 0.
+
+    r: [..., d].  Returns (codes [..., d/group, group] int64, step16 [..., d/group] float16,
+    zero [..., d/group] int64, RtnDiag).
+    """
+    r = np.asarray(r, dtype=np.float64)
+    L = (1 << bits) - 1
+    x = r.reshape(r.shape[:-1] + (r.shape[-1] // group, group))
+    lo = np.minimum(x.min(axis=-1), 0.0)
+    hi = np.maximum(x.max(axis=-1), 0.0)
+    step = (hi - lo) / L
+    step16 = to_fp16_scale(step) if scale16_override is None else np.asarray(scale16_override, dtype=np.float16)
+    s = step16.astype(np.float64)
+    ok = s > 0
+    zf = np.divide(-lo, s, out=np.zeros_like(s), where=ok)
+    zero = np.clip(np.rint(zf), 0, L).astype(np.int64)
+    y = np.divide(x, s[..., None], out=np.zeros_like(x), where=ok[..., None])
+    codes = np.clip(np.rint(y).astype(np.int64) + zero[..., None], 0, L)
+    half = lambda a: np.abs(np.abs(a - np.floor(a)) - 0.5)
+    return codes, step16, zero, RtnDiag(scale=step, zero_frac=half(zf), frac=half(y))
+
+
+def rtn_dequantize(codes, step16, zero):
+    """(code - zero) * step, [..., groups, group] -> [..., groups * group]."""
+    codes = np.asarray(codes, dtype=np.float64)
+    out = (codes - np.asarray(zero, dtype=np.float64)[..., None]) * np.asarray(step16).astype(np.float64)[..., None]
+    return out.reshape(out.shape[:-2] + (-1,))
+
+
+def rtn_pack_meta(step16, zero) -> np.ndarray:
+    """Per group (fp16 bits of the step, zero point) as uint16 [..., groups, 2]."""
+    return np.stack([np.asarray(step16, dtype=np.float16).view(np.uint16), np.asarray(zero).astype(np.uint16)], axis=-1)
+
+
+def rtn_unpack_meta(meta):
+    meta = np.ascontiguousarray(meta).view(np.uint16)
+    return np.ascontiguousarray(meta[..., 0]).view(np.float16), meta[..., 1].astype(np.int64)
+
+
+# --------------------------------------------------------------------------
 # predictors (Sect. 3.2) and the per-layer procedures (Alg. "encode"/"decode")
 # --------------------------------------------------------------------------
 def predict(x, W, b=None):
@@ -265,9 +333,9 @@ class Layer:
     """One layer's fixed parameters (the REQUIRE lines of Alg. encode/decode)."""
     kv_heads: int
     head_dim: int
-    codebook: np.ndarray                 # [n, p]
-    signs_k: np.ndarray                  # [kv_heads, head_dim] +-1
-    signs_v: np.ndarray
+    codebook: Optional[np.ndarray] = None    # [n, p]                        (grid backbone)
+    signs_k: Optional[np.ndarray] = None     # [kv_heads, head_dim] +-1      (grid backbone)
+    signs_v: Optional[np.ndarray] = None
     dtype: str = "bf16"                  # storage dtype of K, V, reconstructions, weights
     w_k: Optional[np.ndarray] = None     # [D, D]      None => no predictor (layer 0)
     b_k: Optional[np.ndarray] = None
@@ -276,16 +344,23 @@ class Layer:
     rht_group: Optional[int] = None      # values per rotation group and scale; None => head_dim.
     #                                      The experiments of Sect. 4.1 run the backbone quantizer with
     #                                      groups of 1024 = the whole token vector across the kv heads.
+    rtn_bits: Optional[int] = None       # set => the uniform round-to-nearest backbone (rtn_quantize) with this many
+    rtn_group: int = 64                  #        bits and groups of rtn_group consecutive channels; no grid, no signs
 
     @property
     def n_codewords(self):
+        if self.rtn_bits is not None:
+            return 1 << self.rtn_bits
         return int(np.asarray(self.codebook).shape[0])
 
     @property
     def group(self):
-        g = self.head_dim if self.rht_group is None else int(self.rht_group)
+        if self.rtn_bits is not None:
+            g = int(self.rtn_group)
+        else:
+            g = self.head_dim if self.rht_group is None else int(self.rht_group)
         if (self.kv_heads * self.head_dim) % g:
-            raise ValueError("rht_group must divide kv_heads * head_dim")
+            raise ValueError("the group size must divide kv_heads * head_dim")
         return g
 
     @property
@@ -301,7 +376,30 @@ def _as_groups(x, layer: Layer):
 
 
 def _group_signs(signs, layer: Layer):
+    if layer.rtn_bits is not None:
+        return None
     return np.asarray(signs, dtype=np.float64).reshape(layer.groups_per_token, layer.group)
+
+
+def _quantize_residual(layer: Layer, r, signs):
+    """The layer's backbone Q and its inverse on residual groups r [T, groups per token, group].
+    Returns (packed codes, stored scales, code indices, diag, Q^-1(Q(r)) shaped like r)."""
+    n = layer.n_codewords
+    if layer.rtn_bits is not None:
+        T = r.shape[0]
+        idx, step16, zero, diag = rtn_quantize(r.reshape(T, -1), layer.rtn_bits, layer.group)
+        return pack_codes(idx, n), rtn_pack_meta(step16, zero), idx, diag, rtn_dequantize(idx, step16, zero).reshape(r.shape)
+    idx, s16, diag = quantize(r, signs, layer.codebook)
+    return pack_codes(idx, n), s16, idx, diag, dequantize(idx, s16, signs, layer.codebook)
+
+
+def _dequantize_stored(layer: Layer, codes, scales, signs, T):
+    """Q^-1 of stored codes and scales -> residual groups [T, groups per token, group]."""
+    idx = unpack_codes(np.asarray(codes).reshape(T, layer.groups_per_token, -1), layer.n_codewords)
+    if layer.rtn_bits is not None:
+        step16, zero = rtn_unpack_meta(np.asarray(scales).reshape(T, layer.groups_per_token, 2))
+        return rtn_dequantize(idx, step16, zero).reshape(T, layer.groups_per_token, layer.group)
+    return dequantize(idx, np.asarray(scales).reshape(T, -1), signs, layer.codebook)
 
 
 def _key_prediction(layer: Layer, Khat_prev, T):
@@ -333,20 +431,19 @@ def encode_layer(layer: Layer, K, V, Khat_prev=None, Vhat_prev=None):
     K = _as_groups(K, layer)
     V = _as_groups(V, layer)
     T = K.shape[0]
-    n = layer.n_codewords
     gshape = K.shape                                                      # [T, groups per token, group]
     shape = (T, layer.kv_heads, layer.head_dim)
     sk, sv = _group_signs(layer.signs_k, layer), _group_signs(layer.signs_v, layer)
 
     P_k = _key_prediction(layer, Khat_prev, T).reshape(gshape)            # K_pred
-    k_idx, k_s16, k_diag = quantize(K - P_k, sk, layer.codebook)          # K_q
-    Khat = round_storage(dequantize(k_idx, k_s16, sk, layer.codebook) + P_k, layer.dtype)
+    k_codes, k_scales, k_idx, k_diag, k_rhat = _quantize_residual(layer, K - P_k, sk)     # K_q
+    Khat = round_storage(k_rhat + P_k, layer.dtype)
 
     P_v = _value_prediction(layer, Vhat_prev, Khat, T).reshape(gshape)    # V_pred uses Khat
-    v_idx, v_s16, v_diag = quantize(V - P_v, sv, layer.codebook)          # V_q
-    Vhat = round_storage(dequantize(v_idx, v_s16, sv, layer.codebook) + P_v, layer.dtype)
+    v_codes, v_scales, v_idx, v_diag, v_rhat = _quantize_residual(layer, V - P_v, sv)     # V_q
+    Vhat = round_storage(v_rhat + P_v, layer.dtype)
 
-    return dict(k_codes=pack_codes(k_idx, n), k_scales=k_s16, v_codes=pack_codes(v_idx, n), v_scales=v_s16,
+    return dict(k_codes=k_codes, k_scales=k_scales, v_codes=v_codes, v_scales=v_scales,
                 Khat=Khat.reshape(shape), Vhat=Vhat.reshape(shape), P_k=P_k.reshape(shape), P_v=P_v.reshape(shape),
                 k_idx=k_idx, v_idx=v_idx, k_diag=k_diag, v_diag=v_diag)
 
@@ -355,17 +452,14 @@ def decode_layer(layer: Layer, k_codes, k_scales, v_codes, v_scales, Khat_prev=N
     """Alg. "decode": Khat = Q^{-1}(K_q) + f_key(Khat_prev); Vhat likewise from [Vhat_prev, Khat]."""
     k_codes = np.asarray(k_codes)
     T = k_codes.shape[0]
-    n = layer.n_codewords
     shape = (T, layer.kv_heads, layer.head_dim)
     gshape = (T, layer.groups_per_token, layer.group)
     sk, sv = _group_signs(layer.signs_k, layer), _group_signs(layer.signs_v, layer)
-    k_idx = unpack_codes(k_codes.reshape(T, layer.groups_per_token, -1), n)
-    v_idx = unpack_codes(np.asarray(v_codes).reshape(T, layer.groups_per_token, -1), n)
 
     P_k = _key_prediction(layer, Khat_prev, T).reshape(gshape)
-    Khat = round_storage(dequantize(k_idx, np.asarray(k_scales).reshape(T, -1), sk, layer.codebook) + P_k, layer.dtype)
+    Khat = round_storage(_dequantize_stored(layer, k_codes, k_scales, sk, T) + P_k, layer.dtype)
     P_v = _value_prediction(layer, Vhat_prev, Khat, T).reshape(gshape)
-    Vhat = round_storage(dequantize(v_idx, np.asarray(v_scales).reshape(T, -1), sv, layer.codebook) + P_v, layer.dtype)
+    Vhat = round_storage(_dequantize_stored(layer, v_codes, v_scales, sv, T) + P_v, layer.dtype)
     return Khat.reshape(shape), Vhat.reshape(shape)
 
 
@@ -402,12 +496,10 @@ def attn_scores(layer: Layer, batch: int, seq_len: int, q, k_codes, k_scales, Kh
     """
     q = np.asarray(q, dtype=np.float64)
     T = batch * seq_len
-    n = layer.n_codewords
     gshape = (T, layer.groups_per_token, layer.group)
-    k_idx = unpack_codes(np.asarray(k_codes).reshape(T, layer.groups_per_token, -1), n)
     P_k = _key_prediction(layer, Khat_prev, T).reshape(gshape)
-    Khat = round_storage(dequantize(k_idx, np.asarray(k_scales).reshape(T, -1), _group_signs(layer.signs_k, layer),
-                                    layer.codebook) + P_k, layer.dtype)
+    Khat = round_storage(_dequantize_stored(layer, k_codes, k_scales, _group_signs(layer.signs_k, layer), T) + P_k,
+                         layer.dtype)
     Khat = Khat.reshape(batch, seq_len, layer.kv_heads, layer.head_dim)
     if rope is not None:
         Khat = apply_rope(Khat, rope[0], rope[1])

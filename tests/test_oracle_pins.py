@@ -411,3 +411,77 @@ def test_group_1024_is_the_papers_accounting_and_a_kronecker_rotation(grid16):
     ref = _layer(H=1, g=128, dtype="fp32")
     a, b = O.encode_layer(one, K[:, :1], V[:, :1]), O.encode_layer(ref, K[:, :1], V[:, :1])
     assert np.array_equal(a["k_codes"], b["k_codes"]) and np.array_equal(a["Khat"], b["Khat"])
+
+
+# ------------------------------------------------------------------ second backbone: uniform round-to-nearest
+def test_rtn_worked_example_by_hand():
+    """2 bits, one group: lo = -1, hi = 2 => step 1, zero point 1; 0.5 rounds to the even neighbour 0."""
+    r = np.zeros(64)
+    r[:4] = [-1.0, 0.5, 2.0, 1.5]
+    codes, step16, zero, _ = O.rtn_quantize(r, bits=2, group=64)
+    assert float(step16[0]) == 1.0 and int(zero[0]) == 1
+    assert codes[0, :5].tolist() == [0, 1, 3, 3, 1]          # -1 -> 0, 0.5 -> 0 + 1, 2 -> 3, 1.5 -> 2 + 1, 0 -> zero
+    assert O.rtn_dequantize(codes, step16, zero)[:5].tolist() == [-1.0, 0.0, 2.0, 2.0, 0.0]
+    # the range always holds 0: an all-positive group still starts at 0
+    codes, step16, zero, _ = O.rtn_quantize(np.full(64, 3.0), bits=2, group=64)
+    assert float(step16[0]) == 1.0 and int(zero[0]) == 0 and set(codes.ravel()) == {3}
+    # an all-zero group: step 0, codes 0, decodes to 0
+    codes, step16, zero, _ = O.rtn_quantize(np.zeros(64), bits=2, group=64)
+    assert float(step16[0]) == 0.0 and not codes.any() and not O.rtn_dequantize(codes, step16, zero).any()
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+def test_rtn_is_nearest_level_by_brute_force(bits):
+    """Independent route: among the 2^b levels (k - zero) * step the chosen one is nearest to r (values on a rounding
+    boundary aside); unclipped values are within step / 2; 0 decodes to exactly 0."""
+    g = rng(61)
+    r = g.standard_normal((50, 256)) * np.exp(g.standard_normal((50, 4))).repeat(64, axis=1)
+    r[:, ::17] = 0.0
+    codes, step16, zero, diag = O.rtn_quantize(r, bits=bits, group=64)
+    s = step16.astype(np.float64)
+    levels = (np.arange(1 << bits)[None, None, :] - zero[..., None]) * s[..., None]            # [50, 4, 2^b]
+    x = r.reshape(50, 4, 64)
+    brute = np.argmin(np.abs(x[..., None] - levels[:, :, None, :]), axis=-1)
+    clear = diag.frac > 1e-9
+    assert np.array_equal(brute[clear], codes[clear])
+    rhat = O.rtn_dequantize(codes, step16, zero).reshape(x.shape)
+    inside = (codes > 0) & (codes < (1 << bits) - 1)
+    assert np.all(np.abs(rhat - x)[inside] <= 0.5 * s[..., None].repeat(64, axis=-1)[inside] * (1 + 1e-12))
+    assert np.all(np.abs(rhat - x) <= s[..., None] * (1 + 1e-3))       # clipped ends: at most one step (fp16 step, rounded zero)
+    assert not rhat[x == 0.0].any()
+    # the step is the group's own range / (2^b - 1): scaling one group leaves the others alone
+    r2 = r.copy(); r2[:, 64:128] *= 8.0
+    c2, s2, z2, _ = O.rtn_quantize(r2, bits=bits, group=64)
+    assert np.array_equal(c2, codes) and np.array_equal(s2[:, [0, 2, 3]], step16[:, [0, 2, 3]])
+    assert np.array_equal(s2[:, 1].astype(np.float64), 8.0 * s[:, 1])
+
+
+def test_rtn_bit_accounting_and_layer_round_trip():
+    """Table 1: 2-bit round-to-nearest with groups of 64 stores 2.50 bits per value (16-bit step + 16-bit zero point per
+    group); with groups of 1024, 2.03.  Closed loop through the layer procedures with predictors."""
+    H, gdim, T = 8, 128, 40
+    D = H * gdim
+    g = rng(62)
+    wk = O.round_bf16(g.standard_normal((D, D)) / math.sqrt(D) * 0.7)
+    wv = O.round_bf16(g.standard_normal((D, 2 * D)) / math.sqrt(2 * D) * 0.7)
+    lay0 = O.Layer(kv_heads=H, head_dim=gdim, dtype="bf16", rtn_bits=2)
+    lay1 = O.Layer(kv_heads=H, head_dim=gdim, dtype="bf16", rtn_bits=2, w_k=wk, w_v=wv, b_k=g.standard_normal(D) * 0.1)
+    K0, V0, K1, V1 = (O.round_bf16(g.standard_normal((T, H, gdim))) for _ in range(4))
+    e0 = O.encode_layer(lay0, K0, V0)
+    stored = 8.0 * (e0["k_codes"][0].size + e0["k_scales"][0].size * 2) / D
+    assert stored == 2.5 == PAPER["rtn_2bit_gs64_stored_bits"]
+    assert round(2 + 32 / 1024, 2) == PAPER["rtn_2bit_gs1024_stored_bits"]
+    assert e0["k_codes"].reshape(T, -1).shape == (T, D // 4) and e0["k_scales"].shape == (T, D // 64, 2)
+    e1 = O.encode_layer(lay1, K1, V1, e0["Khat"], e0["Vhat"])
+    Kd0, Vd0 = O.decode_layer(lay0, e0["k_codes"], e0["k_scales"], e0["v_codes"], e0["v_scales"])
+    Kd1, Vd1 = O.decode_layer(lay1, e1["k_codes"], e1["k_scales"], e1["v_codes"], e1["v_scales"], Kd0, Vd0)
+    assert np.array_equal(Kd0, e0["Khat"]) and np.array_equal(Kd1, e1["Khat"]) and np.array_equal(Vd1, e1["Vhat"])
+    # the residual, not the tensor, is what gets quantized: the reconstruction error is bounded by the residual's step
+    step = e1["k_scales"][..., 0].copy().view(np.float16).astype(np.float64)            # [T, D/64]
+    err = np.abs(e1["Khat"] - K1).reshape(T, D // 64, 64)
+    assert np.all(err <= step[..., None] * 1.001 + 2.0 ** -8 * np.abs(K1).reshape(err.shape) + 1e-6)
+    # scores through the same procedure
+    q = g.standard_normal((1, 2 * H, gdim))
+    sc = O.attn_scores(lay1, 1, T, q, e1["k_codes"], e1["k_scales"], Kd0, score_scale=0.5)
+    want = 0.5 * np.einsum("qd,tqd->qt", q[0], np.repeat(e1["Khat"], 2, axis=1))
+    assert np.allclose(sc[0], want, rtol=1e-12, atol=1e-12)
