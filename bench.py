@@ -47,6 +47,8 @@ def parse():
                          "grouping of the paper's experiments; predictor and quantizer then run as separate kernels)")
     ap.add_argument("--layers", type=int, default=0, help="use only the first N layers of the configuration (0: all)")
     ap.add_argument("--n-codewords", type=int, default=16)
+    ap.add_argument("--rtn-bits", type=int, default=0, choices=[0, 2, 4],
+                    help="2 or 4: the uniform round-to-nearest backbone (groups of 64) instead of the grid (0)")
     ap.add_argument("--q-heads", type=int, default=0, help="query heads for the scoring call (0: model default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="skip the instrumented replay")
@@ -76,25 +78,28 @@ def grids_on_device(ns, device):
     return out
 
 
-def build_workload(cfg, device, n_per_layer, rht_group=0):
+def build_workload(cfg, device, n_per_layer, rht_group=0, rtn_bits=0):
     import torch
     from paper_2501_19392_amd import binding as B
     from paper_2501_19392_amd import synth
     sd = synth.torch_dtype(cfg.dtype)
     work = torch.float32 if cfg.dtype == "bf16" else torch.float64
     st = synth.KVStream(cfg, device=device, work=work)
-    grids = grids_on_device(n_per_layer, device)
+    grids = {} if rtn_bits else grids_on_device(n_per_layer, device)
     layers, Ks, Vs = [], [], []
     for l in range(cfg.layers):
-        C, table = grids[n_per_layer[l]]
         K, V = st.next()
         Ks.append(K.contiguous())
         Vs.append(V.contiguous())
-        sk = torch.from_numpy(synth.rht_signs(cfg.kv_heads, cfg.head_dim, l, "k")).to(device)
-        sv = torch.from_numpy(synth.rht_signs(cfg.kv_heads, cfg.head_dim, l, "v")).to(device)
         wk = wv = None
         if l > 0:
             wk, wv = (w.to(device) for w in synth.analytic_predictors(st, l))
+        if rtn_bits:
+            layers.append(B.Layer(cfg.kv_heads, cfg.head_dim, None, None, None, sd, w_k=wk, w_v=wv, rtn_bits=rtn_bits))
+            continue
+        C, table = grids[n_per_layer[l]]
+        sk = torch.from_numpy(synth.rht_signs(cfg.kv_heads, cfg.head_dim, l, "k")).to(device)
+        sv = torch.from_numpy(synth.rht_signs(cfg.kv_heads, cfg.head_dim, l, "v")).to(device)
         layers.append(B.Layer(cfg.kv_heads, cfg.head_dim, C, sk, sv, sd, w_k=wk, w_v=wv, search_table=table,
                               rht_group=rht_group))
     return layers, Ks, Vs
@@ -268,7 +273,7 @@ def encode_kernel_events(B, layers, Ks, Vs, buf, T, steps):
                 b.record()
                 pairs.append((a, b))
                 flops += 2.0 * T * D * (lay.c.d_in_k + lay.c.d_in_v)
-                code_bytes = lay.kv_heads * (lay.code_bytes_per_group + 2)
+                code_bytes = lay.kv_heads * lay.code_bytes_per_group + 2 * (D // lay.rht_group) * lay.scale_words_per_group
                 # per token: read K, V, Khat_prev, Vhat_prev and (value predictor) Khat; write Khat, Vhat, codes+scales
                 nbytes += T * (5 * D * eb + 2 * D * eb + 2 * code_bytes) + (lay.c.d_in_k + lay.c.d_in_v) * D * eb
             prev = (Kh, Vh)
@@ -277,7 +282,7 @@ def encode_kernel_events(B, layers, Ks, Vs, buf, T, steps):
     return flops, nbytes, ms, 2 * len(pairs)
 
 
-def cpu_baseline(cfg, n_codewords, rows, q_heads, n_layers):
+def cpu_baseline(cfg, n_codewords, rows, q_heads, n_layers, rtn_bits=0):
     """The oracle as it stands, on the host: encode + decode + scores of `n_layers` predicted layers
     on `rows` token rows of the same synthetic workload (rows are independent)."""
     import torch
@@ -291,9 +296,12 @@ def cpu_baseline(cfg, n_codewords, rows, q_heads, n_layers):
     sd = synth.torch_dtype(cfg.dtype)
     st = synth.KVStream(cfg, device="cpu", work=torch.float32, tokens=rows)
     f = lambda t: t.double().numpy()
-    C = synth.lloyd_codebook(n_codewords)
-    mk = lambda l, **kw: O.Layer(cfg.kv_heads, cfg.head_dim, C, synth.rht_signs(cfg.kv_heads, cfg.head_dim, l, "k"),
-                                 synth.rht_signs(cfg.kv_heads, cfg.head_dim, l, "v"), cfg.dtype, **kw)
+    if rtn_bits:
+        mk = lambda l, **kw: O.Layer(cfg.kv_heads, cfg.head_dim, dtype=cfg.dtype, rtn_bits=rtn_bits, **kw)
+    else:
+        C = synth.lloyd_codebook(n_codewords)
+        mk = lambda l, **kw: O.Layer(cfg.kv_heads, cfg.head_dim, C, synth.rht_signs(cfg.kv_heads, cfg.head_dim, l, "k"),
+                                     synth.rht_signs(cfg.kv_heads, cfg.head_dim, l, "v"), cfg.dtype, **kw)
     K0, V0 = st.next()
     prev = O.encode_layer(mk(0), f(K0), f(V0))
     q = f(synth.random_queries(1, q_heads, cfg.head_dim, seed=1, dtype=cfg.dtype))
@@ -457,11 +465,18 @@ def main():
         n_per_layer = [args.n_codewords] * cfg.layers
         bits_label = "%d" % (args.n_codewords.bit_length() // 2)
         grid_label = f"n={args.n_codewords}"
+    if args.rtn_bits:
+        if args.config == "llama3.1-70b" or args.rht_group:
+            sys.exit("bench.py: --rtn-bits goes with one backbone for all layers and its own groups of 64")
+        bits_label = "%d (uniform round-to-nearest backbone, groups of 64: %.2f stored)" % (args.rtn_bits, args.rtn_bits + 0.5)
+        grid_label = ""
 
-    layers, Ks, Vs = build_workload(cfg, device, n_per_layer, args.rht_group)
+    layers, Ks, Vs = build_workload(cfg, device, n_per_layer, args.rht_group, args.rtn_bits)
     wide = args.rht_group not in (0, cfg.head_dim)
     if wide:
         grid_label += f", rotation groups of {args.rht_group} (one scale per token)"
+    quantizer_label = (f"uniform round-to-nearest with {1 << args.rtn_bits} levels, groups of 64" if args.rtn_bits
+                       else f"{grid_label} codewords (p=2)")
     buf = Buffers(layers, T, q_heads, device, args.scores_form)
     q = synth.random_queries(1, q_heads, cfg.head_dim, seed=1, dtype=cfg.dtype, device=device)
 
@@ -488,7 +503,8 @@ def main():
     l0 = layer0_times(B, layers, Ks, Vs, buf, T, 5)
     eb = 2 if cfg.dtype == "bf16" else 4
     D = cfg.kv_heads * cfg.head_dim
-    code_b = 2 * T * (cfg.kv_heads * layers[0].code_bytes_per_group + 2 * (D // layers[0].rht_group))
+    code_b = 2 * T * (cfg.kv_heads * layers[0].code_bytes_per_group
+                      + 2 * (D // layers[0].rht_group) * layers[0].scale_words_per_group)
     # layer 0 moves, per call: encode reads K, V and writes Khat, Vhat + codes; decode reads codes and writes Khat, Vhat
     l0_bytes = {"encode": 4 * T * D * eb + code_b, "decode": 2 * T * D * eb + code_b}
     n_pred = max(cfg.layers - 1, 1)
@@ -503,7 +519,7 @@ def main():
                     else "fused_kernel<encode> (bf16 MFMA predictor + quantizer epilogue)", "bound": "mfma",
                     "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                    "traffic": None if wide else MEASURED_TRAFFIC_BYTES.get((args.config, args.n_codewords)), "launches": launches,
+                    "traffic": None if wide or args.rtn_bits else MEASURED_TRAFFIC_BYTES.get((args.config, args.n_codewords)), "launches": launches,
                     "algorithmic_bytes_per_launch": round(nbytes / launches, 1),
                     "avg_launch_us": round(1e3 * ms / launches, 2),
                     "algorithmic_hbm_GBs": round(nbytes / (ms * 1e-3) / 1e9, 1),
@@ -515,7 +531,7 @@ def main():
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.layers} layers x {T} tokens x {cfg.kv_heads} kv heads x {cfg.head_dim}, "
-                               f"{cfg.dtype}, {grid_label} codewords (p=2), step = encode + decode + q.k scores "
+                               f"{cfg.dtype}, {quantizer_label}, step = encode + decode + q.k scores "
                                f"({q_heads} query heads) of every layer"
                                + (", key and value chains of the sweeps on two streams" if args.streams == 2 else ""),
                    "tokens": T, "layers": cfg.layers, "q_heads": q_heads, "streams": args.streams},
@@ -532,7 +548,8 @@ def main():
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(cfg, args.n_codewords, min(args.cpu_rows, T), q_heads, min(args.cpu_layers, cfg.layers - 1))
+        line["cpu_baseline"] = cpu_baseline(cfg, args.n_codewords, min(args.cpu_rows, T), q_heads, min(args.cpu_layers, cfg.layers - 1),
+                                            args.rtn_bits)
     print(json.dumps(line))
 
 

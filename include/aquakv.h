@@ -31,6 +31,18 @@
  *                              coordinates 2i, 2i+1) at bits [i*c, (i+1)*c)
  *   scales                   : IEEE fp16 bit patterns, uint16 [T, H]
  *   predictions P            : fp32 [T, D]
+ *
+ * Second backbone (Sect. 4.1 "Backbone quantization": uniform round-to-nearest, groups of 64
+ * channels of a token, 2.50 stored bits per value at 2 bits in Table 1), selected by vq_dim = 1
+ * with n_codewords = 4 or 16 levels (b = 2 or 4 bits per value); no grid, no rotation:
+ *   per group of 64 consecutive channels of x - p: lo = min(0, min), hi = max(0, max),
+ *   step = (hi - lo) / (n - 1) stored as fp16, zero = round(-lo / step),
+ *   code = clamp(round((x - p) / step) + zero, 0, n - 1), rounding half to even;
+ *   reconstruction p + (code - zero) * step.
+ *   codes  : uint8 [T, D*b/8], b bits per value in channel order, little-endian
+ *   scales : uint16 [T, D/64, 2] = (fp16 bits of the step, zero point) per group; 4-byte aligned
+ * Every entry point below takes such a layer; where a comment says "scales [T, H]" read the
+ * layout above instead.  The folded form of the scoring call is built for the grids only.
  */
 #ifndef AQUAKV_H
 #define AQUAKV_H
@@ -65,8 +77,10 @@ typedef enum { AQUAKV_KEY = 0, AQUAKV_VALUE = 1 } aquakv_which;
 typedef struct aquakv_layer {
   int32_t kv_heads;     /* H >= 1                                                */
   int32_t head_dim;     /* g; only 128 is built                                   */
-  int32_t vq_dim;       /* p; only 2 is built (Sect. 4.1: d = 2)                  */
-  int32_t n_codewords;  /* n in {16, 64, 256}: 2, 3, 4 code bits per value        */
+  int32_t vq_dim;       /* p = 2: grid in R^2 behind the rotation (Sect. 4.1: d = 2);
+                           1: uniform round-to-nearest backbone (see above)       */
+  int32_t n_codewords;  /* p = 2: n in {16, 64, 256} = 2, 3, 4 code bits per value;
+                           p = 1: 4 or 16 levels                                  */
   int32_t dtype;        /* aquakv_dtype of K, V, reconstructions and weights      */
   int32_t d_in_k;       /* inputs of f_key (= width of Khat_prev); 0 = no key
                            predictor (layer 0: prediction is zero)                */
@@ -79,8 +93,10 @@ typedef struct aquakv_layer {
                            value; built for 8 heads of 128).  The code bytes have the
                            same layout either way.  Groups across heads are not
                            fused with the predictor: the calls then need the fp32
-                           prediction workspace also in bf16.                      */
-  const float* codebook;   /* [n, 2] fp32 grid points                             */
+                           prediction workspace also in bf16.  With vq_dim = 1: 0 or
+                           64, the group of the round-to-nearest backbone.         */
+  const float* codebook;   /* [n, 2] fp32 grid points (ignored when vq_dim = 1, like
+                              signs_k, signs_v and search_table)                  */
   const int8_t* signs_k;   /* [H*g] entries +1 / -1: RHT signs for keys           */
   const int8_t* signs_v;   /* [H*g] same for values                               */
   const void* w_k;      /* [D, d_in_k] row-major, dtype: K_pred = Khat_prev w_k^T */

@@ -269,7 +269,7 @@ class RtnDiag:
     frac: np.ndarray       # the same for every value / step                [..., groups, group]
 
 
-def rtn_quantize(r, bits: int, group: int = 64, scale16_override=None):
+def rtn_quantize(r, bits: int, group: int = 64, scale16_override=None, zero_override=None):
     """Uniform b-bit round-to-nearest with per-group min/max normalisation and an integer zero point.
 
     Sect. 4.1 names the scheme (simple round-to-nearest with absmax normalisation, group size 64, per-token
@@ -281,7 +281,9 @@ def rtn_quantize(r, bits: int, group: int = 64, scale16_override=None):
     even, with the *stored* step.  A stored step of 0 gives codes = zero = 0.
 
     r: [..., d].  Returns (codes [..., d/group, group] int64, step16 [..., d/group] float16,
-    zero [..., d/group] int64, RtnDiag).
+    zero [..., d/group] int64, RtnDiag).  scale16_override / zero_override replace the stored step / zero point;
+    they exist so that a test can tell a step that sat on an fp16 rounding boundary, or a zero point that sat on
+    x.5, from any other disagreement.
     """
     r = np.asarray(r, dtype=np.float64)
     L = (1 << bits) - 1
@@ -293,7 +295,7 @@ def rtn_quantize(r, bits: int, group: int = 64, scale16_override=None):
     s = step16.astype(np.float64)
     ok = s > 0
     zf = np.divide(-lo, s, out=np.zeros_like(s), where=ok)
-    zero = np.clip(np.rint(zf), 0, L).astype(np.int64)
+    zero = np.clip(np.rint(zf), 0, L).astype(np.int64) if zero_override is None else np.asarray(zero_override, dtype=np.int64)
     y = np.divide(x, s[..., None], out=np.zeros_like(x), where=ok[..., None])
     codes = np.clip(np.rint(y).astype(np.int64) + zero[..., None], 0, L)
     half = lambda a: np.abs(np.abs(a - np.floor(a)) - 0.5)

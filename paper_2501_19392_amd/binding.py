@@ -121,21 +121,30 @@ def _dtype_code(t: torch.dtype) -> int:
 class Layer:
     """Owns the device tensors of one layer's parameters and the C struct that points at them."""
 
-    def __init__(self, kv_heads: int, head_dim: int, codebook: torch.Tensor, signs_k: torch.Tensor,
-                 signs_v: torch.Tensor, dtype: torch.dtype, w_k: Optional[torch.Tensor] = None,
+    def __init__(self, kv_heads: int, head_dim: int, codebook: Optional[torch.Tensor], signs_k: Optional[torch.Tensor],
+                 signs_v: Optional[torch.Tensor], dtype: torch.dtype, w_k: Optional[torch.Tensor] = None,
                  w_v: Optional[torch.Tensor] = None, b_k: Optional[torch.Tensor] = None,
-                 b_v: Optional[torch.Tensor] = None, search_table: Optional[torch.Tensor] = None, rht_group: int = 0):
+                 b_v: Optional[torch.Tensor] = None, search_table: Optional[torch.Tensor] = None, rht_group: int = 0,
+                 rtn_bits: Optional[int] = None):
+        """rtn_bits = 2 or 4 selects the uniform round-to-nearest backbone (vq_dim = 1, groups of 64): codebook,
+        signs and search_table are then None."""
         self.kv_heads, self.head_dim, self.dtype = kv_heads, head_dim, dtype
-        self.rht_group = rht_group or head_dim          # values per rotation group and scale
+        self.rtn_bits = rtn_bits
         self.d = kv_heads * head_dim
-        self.codebook = codebook.to(torch.float32).contiguous()
-        self.signs_k = signs_k.to(torch.int8).contiguous().reshape(-1)
-        self.signs_v = signs_v.to(torch.int8).contiguous().reshape(-1)
+        if rtn_bits is not None:
+            self.rht_group = rht_group or 64            # values per group of the round-to-nearest backbone
+            self.codebook = self.signs_k = self.signs_v = None
+            self.n_codewords, self.vq_dim = 1 << rtn_bits, 1
+        else:
+            self.rht_group = rht_group or head_dim      # values per rotation group and scale
+            self.codebook = codebook.to(torch.float32).contiguous()
+            self.signs_k = signs_k.to(torch.int8).contiguous().reshape(-1)
+            self.signs_v = signs_v.to(torch.int8).contiguous().reshape(-1)
+            self.n_codewords, self.vq_dim = self.codebook.shape
         self.w_k = None if w_k is None else w_k.to(dtype).contiguous()
         self.w_v = None if w_v is None else w_v.to(dtype).contiguous()
         self.b_k = None if b_k is None else b_k.to(torch.float32).contiguous()
         self.b_v = None if b_v is None else b_v.to(torch.float32).contiguous()
-        self.n_codewords, self.vq_dim = self.codebook.shape
         self.search_table = search_table
         if self.w_k is not None and self.w_k.shape[0] != self.d:
             raise ValueError("w_k must be [D, d_in_k]")
@@ -145,7 +154,9 @@ class Layer:
             kv_heads=kv_heads, head_dim=head_dim, vq_dim=self.vq_dim, n_codewords=self.n_codewords,
             dtype=_dtype_code(dtype), d_in_k=0 if self.w_k is None else self.w_k.shape[1],
             d_in_v=0 if self.w_v is None else self.w_v.shape[1], rht_group=rht_group,
-            codebook=self.codebook.data_ptr(), signs_k=self.signs_k.data_ptr(), signs_v=self.signs_v.data_ptr(),
+            codebook=None if self.codebook is None else self.codebook.data_ptr(),
+            signs_k=None if self.signs_k is None else self.signs_k.data_ptr(),
+            signs_v=None if self.signs_v is None else self.signs_v.data_ptr(),
             w_k=None if self.w_k is None else self.w_k.data_ptr(),
             b_k=None if self.b_k is None else self.b_k.data_ptr(),
             w_v=None if self.w_v is None else self.w_v.data_ptr(),
@@ -160,9 +171,16 @@ class Layer:
     def code_bytes_per_group(self) -> int:
         return self.head_dim // self.vq_dim * self.code_bits // 8
 
+    @property
+    def scale_words_per_group(self) -> int:
+        """uint16 words stored per group: the fp16 scale; for the round-to-nearest backbone (fp16 step, zero point)."""
+        return 1 if self.rtn_bits is None else 2
+
     def alloc_codes(self, tokens: int, device="cuda"):
         codes = torch.empty(tokens, self.kv_heads, self.code_bytes_per_group, dtype=torch.uint8, device=device)
-        scales = torch.empty(tokens, self.d // self.rht_group, dtype=torch.int16, device=device)   # fp16 bit patterns
+        groups = self.d // self.rht_group
+        shape = (tokens, groups) if self.rtn_bits is None else (tokens, groups, 2)
+        scales = torch.empty(*shape, dtype=torch.int16, device=device)   # fp16 bit patterns (and zero points)
         return codes, scales
 
     def alloc_kv(self, tokens: int, device="cuda"):

@@ -107,5 +107,5 @@ class AquaKVCache:
         total = (self.n_sink + self.n_buffered) * per_tok * len(self.layers)
         for lay in self.layers:
             groups = lay.d // lay.rht_group
-            total += 2 * self.n_compressed * (lay.kv_heads * lay.code_bytes_per_group + 2 * groups)
+            total += 2 * self.n_compressed * (lay.kv_heads * lay.code_bytes_per_group + 2 * groups * lay.scale_words_per_group)
         return total

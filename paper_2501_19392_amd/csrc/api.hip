@@ -29,7 +29,17 @@ constexpr int64_t kChunkRowsSplit = 16384;
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 inline size_t elem_bytes(int dtype) { return dtype == AQUAKV_BF16 ? 2 : 4; }
-inline int code_bits(int n) { return n == 16 ? 4 : n == 64 ? 6 : 8; }
+// Sect. 4.1 "Backbone quantization": vq_dim 2 = grid in R^2 behind a Hadamard rotation, vq_dim 1 = uniform
+// round-to-nearest on groups of 64 channels
+inline bool is_rtn(const aquakv_layer* L) { return L->vq_dim == 1; }
+constexpr int kRtnGroup = 64;
+// what the kernels are instantiated on: the grid size, or the bits per value of the round-to-nearest backbone
+inline int quantizer_id(const aquakv_layer* L) { return is_rtn(L) ? (L->n_codewords == 4 ? 2 : 4) : L->n_codewords; }
+// code bits per pair of values
+inline int code_bits(const aquakv_layer* L) {
+  if (is_rtn(L)) return L->n_codewords == 4 ? 4 : 8;
+  return L->n_codewords == 16 ? 4 : L->n_codewords == 64 ? 6 : 8;
+}
 
 int check_layer(const aquakv_layer* L) {
   if (L == nullptr) return fail(AQUAKV_ENULL, "layer is NULL");
@@ -38,13 +48,19 @@ int check_layer(const aquakv_layer* L) {
     return fail(AQUAKV_EINVAL, "head_dim=%d is not a power of two", L->head_dim);
   if (L->head_dim != 128) return fail(AQUAKV_EUNSUPPORTED, "head_dim=%d: only 128 is built", L->head_dim);
   if (L->vq_dim < 1) return fail(AQUAKV_EINVAL, "vq_dim=%d", L->vq_dim);
-  if (L->vq_dim != 2) return fail(AQUAKV_EUNSUPPORTED, "vq_dim=%d: only 2 is built", L->vq_dim);
-  if (L->n_codewords != 16 && L->n_codewords != 64 && L->n_codewords != 256)
-    return fail(L->n_codewords >= 2 && !(L->n_codewords & (L->n_codewords - 1)) ? AQUAKV_EUNSUPPORTED : AQUAKV_EINVAL,
-                "n_codewords=%d: must be 16, 64 or 256", L->n_codewords);
+  if (L->vq_dim > 2) return fail(AQUAKV_EUNSUPPORTED, "vq_dim=%d: only 1 and 2 are built", L->vq_dim);
+  const bool pow2 = L->n_codewords >= 2 && !(L->n_codewords & (L->n_codewords - 1));
+  if (is_rtn(L)) {
+    if (L->n_codewords != 4 && L->n_codewords != 16)
+      return fail(pow2 ? AQUAKV_EUNSUPPORTED : AQUAKV_EINVAL, "n_codewords=%d: vq_dim 1 is built for 4 or 16 levels", L->n_codewords);
+    if (L->rht_group != 0 && L->rht_group != kRtnGroup)
+      return fail(AQUAKV_EUNSUPPORTED, "rht_group=%d: vq_dim 1 is built for groups of %d", L->rht_group, kRtnGroup);
+  } else if (L->n_codewords != 16 && L->n_codewords != 64 && L->n_codewords != 256) {
+    return fail(pow2 ? AQUAKV_EUNSUPPORTED : AQUAKV_EINVAL, "n_codewords=%d: must be 16, 64 or 256", L->n_codewords);
+  }
   if (L->dtype != AQUAKV_BF16 && L->dtype != AQUAKV_FP32) return fail(AQUAKV_EINVAL, "dtype=%d", L->dtype);
   const int D = L->kv_heads * L->head_dim;
-  if (L->rht_group != 0 && L->rht_group != L->head_dim) {
+  if (!is_rtn(L) && L->rht_group != 0 && L->rht_group != L->head_dim) {
     if (L->rht_group != D) return fail(AQUAKV_EINVAL, "rht_group=%d must be 0, head_dim or kv_heads * head_dim", L->rht_group);
     if (D != 1024) return fail(AQUAKV_EUNSUPPORTED, "rht_group=%d: groups across heads are built for 8 heads of 128", L->rht_group);
   }
@@ -52,8 +68,10 @@ int check_layer(const aquakv_layer* L) {
   if (L->d_in_v < 0 || L->d_in_v % 128) return fail(AQUAKV_EINVAL, "d_in_v=%d must be a non-negative multiple of 128", L->d_in_v);
   if (L->d_in_v != 0 && L->d_in_v <= D)
     return fail(AQUAKV_EINVAL, "d_in_v=%d must exceed D=%d (inputs are [Vhat_prev | Khat])", L->d_in_v, D);
-  if (L->codebook == nullptr) return fail(AQUAKV_ENULL, "codebook is NULL");
-  if (L->signs_k == nullptr || L->signs_v == nullptr) return fail(AQUAKV_ENULL, "signs_k / signs_v is NULL");
+  if (!is_rtn(L)) {      // the round-to-nearest backbone has neither grid nor rotation; the three pointers are ignored
+    if (L->codebook == nullptr) return fail(AQUAKV_ENULL, "codebook is NULL");
+    if (L->signs_k == nullptr || L->signs_v == nullptr) return fail(AQUAKV_ENULL, "signs_k / signs_v is NULL");
+  }
   if (L->d_in_k && L->w_k == nullptr) return fail(AQUAKV_ENULL, "w_k is NULL but d_in_k=%d", L->d_in_k);
   if (L->d_in_v && L->w_v == nullptr) return fail(AQUAKV_ENULL, "w_v is NULL but d_in_v=%d", L->d_in_v);
   const void* ptrs[] = {L->codebook, L->signs_k, L->signs_v, L->w_k, L->b_k, L->w_v, L->b_v, L->search_table};
@@ -63,8 +81,12 @@ int check_layer(const aquakv_layer* L) {
 }
 
 // rotation group = the whole token vector (Sect. 4.1 of the paper) instead of one head
-inline bool is_wide(const aquakv_layer* L) { return L->rht_group != 0 && L->rht_group != L->head_dim; }
-inline size_t scale_row_bytes(const aquakv_layer* L) { return (is_wide(L) ? 1 : (size_t)L->kv_heads) * sizeof(uint16_t); }
+inline bool is_wide(const aquakv_layer* L) { return !is_rtn(L) && L->rht_group != 0 && L->rht_group != L->head_dim; }
+// bytes of scales per token row: one fp16 per rotation group, or (fp16 step, 16-bit zero point) per group of 64
+inline size_t scale_row_bytes(const aquakv_layer* L) {
+  if (is_rtn(L)) return (size_t)L->kv_heads * (L->head_dim / kRtnGroup) * 2 * sizeof(uint16_t);
+  return (is_wide(L) ? 1 : (size_t)L->kv_heads) * sizeof(uint16_t);
+}
 
 int check_ptr(const void* p, const char* name, bool required) {
   if (p == nullptr) return required ? fail(AQUAKV_ENULL, "%s is NULL", name) : AQUAKV_OK;
@@ -74,9 +96,11 @@ int check_ptr(const void* p, const char* name, bool required) {
 
 // scales are read and written one fp16 at a time: with one scale per token a row range of the cache starts at
 // any even address
-int check_scales(const void* p, const char* name, bool required) {
+// (the round-to-nearest backbone stores a step and a zero point together as one 4-byte word)
+int check_scales(const aquakv_layer* L, const void* p, const char* name, bool required) {
   if (p == nullptr) return required ? fail(AQUAKV_ENULL, "%s is NULL", name) : AQUAKV_OK;
-  if (reinterpret_cast<uintptr_t>(p) & 1u) return fail(AQUAKV_EALIGN, "%s is not 2-byte aligned", name);
+  const unsigned need = is_rtn(L) ? 4u : 2u;
+  if (reinterpret_cast<uintptr_t>(p) & (need - 1u)) return fail(AQUAKV_EALIGN, "%s is not %u-byte aligned", name, need);
   return AQUAKV_OK;
 }
 
@@ -106,7 +130,7 @@ Plan make_plan(const aquakv_layer* L, int64_t tokens) {
   Plan pl;
   pl.D = L->kv_heads * L->head_dim;
   pl.eb = elem_bytes(L->dtype);
-  pl.code_row = (size_t)L->kv_heads * (L->head_dim / 2) * code_bits(L->n_codewords) / 8;
+  pl.code_row = (size_t)L->kv_heads * (L->head_dim / 2) * code_bits(L) / 8;
   pl.fused = L->dtype == AQUAKV_BF16 && !is_wide(L);   // a fused tile is one head wide
   const int64_t cap = pl.fused ? kChunkRowsFused : kChunkRowsSplit;
   pl.chunk = tokens < cap ? tokens : cap;
@@ -129,7 +153,7 @@ int encode_keys_chunk(const aquakv_layer* L, const Plan& pl, int64_t r0, int64_t
   const bool has_k = L->d_in_k != 0;
   const size_t row = (size_t)pl.D * pl.eb, srow = scale_row_bytes(L);
   if (has_k && pl.fused) {
-    HIP_TRY(aquakv::launch_fused_encode(L->n_codewords, at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k, nullptr, 0,
+    HIP_TRY(aquakv::launch_fused_encode(quantizer_id(L), at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k, nullptr, 0,
                                         L->w_k, L->b_k, L->signs_k, L->codebook, L->search_table, at(K, r0, row),
                                         static_cast<uint8_t*>(at(k_codes, r0, pl.code_row)),
                                         static_cast<uint16_t*>(at(k_scales, r0, srow)), khat_dst, n, pl.D, stream));
@@ -138,7 +162,7 @@ int encode_keys_chunk(const aquakv_layer* L, const Plan& pl, int64_t r0, int64_t
   if (has_k)
     HIP_TRY(aquakv::launch_predict(L->dtype, at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k, nullptr, 0, L->w_k,
                                    L->b_k, Pbuf, n, pl.D, stream));
-  HIP_TRY(aquakv::launch_quantize(L->dtype, L->n_codewords, at(K, r0, row), has_k ? Pbuf : nullptr, L->signs_k, L->codebook,
+  HIP_TRY(aquakv::launch_quantize(L->dtype, quantizer_id(L), at(K, r0, row), has_k ? Pbuf : nullptr, L->signs_k, L->codebook,
                                   L->search_table, static_cast<uint8_t*>(at(k_codes, r0, pl.code_row)),
                                   static_cast<uint16_t*>(at(k_scales, r0, srow)), khat_dst, n, L->kv_heads, is_wide(L),
                                   stream));
@@ -153,7 +177,7 @@ int encode_values_chunk(const aquakv_layer* L, const Plan& pl, int64_t r0, int64
   const int D = pl.D;
   const size_t row = (size_t)D * pl.eb, srow = scale_row_bytes(L);
   if (has_v && pl.fused) {
-    HIP_TRY(aquakv::launch_fused_encode(L->n_codewords, at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb), L->d_in_v - D,
+    HIP_TRY(aquakv::launch_fused_encode(quantizer_id(L), at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb), L->d_in_v - D,
                                         khat_src, D, L->w_v, L->b_v, L->signs_v, L->codebook, L->search_table, at(V, r0, row),
                                         static_cast<uint8_t*>(at(v_codes, r0, pl.code_row)),
                                         static_cast<uint16_t*>(at(v_scales, r0, srow)), at(Vhat, r0, row), n, D, stream));
@@ -162,7 +186,7 @@ int encode_values_chunk(const aquakv_layer* L, const Plan& pl, int64_t r0, int64
   if (has_v)
     HIP_TRY(aquakv::launch_predict(L->dtype, at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb), L->d_in_v - D, khat_src, D,
                                    L->w_v, L->b_v, Pbuf, n, D, stream));
-  HIP_TRY(aquakv::launch_quantize(L->dtype, L->n_codewords, at(V, r0, row), has_v ? Pbuf : nullptr, L->signs_v, L->codebook,
+  HIP_TRY(aquakv::launch_quantize(L->dtype, quantizer_id(L), at(V, r0, row), has_v ? Pbuf : nullptr, L->signs_v, L->codebook,
                                   L->search_table, static_cast<uint8_t*>(at(v_codes, r0, pl.code_row)),
                                   static_cast<uint16_t*>(at(v_scales, r0, srow)), at(Vhat, r0, row), n, L->kv_heads,
                                   is_wide(L), stream));
@@ -175,7 +199,7 @@ int decode_keys_chunk(const aquakv_layer* L, const Plan& pl, int64_t r0, int64_t
   const bool has_k = L->d_in_k != 0;
   const size_t row = (size_t)pl.D * pl.eb, srow = scale_row_bytes(L);
   if (has_k && pl.fused) {
-    HIP_TRY(aquakv::launch_fused_decode(L->n_codewords, at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k, nullptr, 0,
+    HIP_TRY(aquakv::launch_fused_decode(quantizer_id(L), at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k, nullptr, 0,
                                         L->w_k, L->b_k, L->signs_k, L->codebook,
                                         static_cast<const uint8_t*>(at(k_codes, r0, pl.code_row)),
                                         static_cast<const uint16_t*>(at(k_scales, r0, srow)), at(Khat, r0, row), n, pl.D,
@@ -185,7 +209,7 @@ int decode_keys_chunk(const aquakv_layer* L, const Plan& pl, int64_t r0, int64_t
   if (has_k)
     HIP_TRY(aquakv::launch_predict(L->dtype, at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k, nullptr, 0, L->w_k,
                                    L->b_k, Pbuf, n, pl.D, stream));
-  HIP_TRY(aquakv::launch_dequantize(L->dtype, L->n_codewords, static_cast<const uint8_t*>(at(k_codes, r0, pl.code_row)),
+  HIP_TRY(aquakv::launch_dequantize(L->dtype, quantizer_id(L), static_cast<const uint8_t*>(at(k_codes, r0, pl.code_row)),
                                     static_cast<const uint16_t*>(at(k_scales, r0, srow)), has_k ? Pbuf : nullptr, L->signs_k,
                                     L->codebook, at(Khat, r0, row), n, L->kv_heads, is_wide(L), stream));
   return AQUAKV_OK;
@@ -199,7 +223,7 @@ int decode_values_chunk(const aquakv_layer* L, const Plan& pl, int64_t r0, int64
   const int D = pl.D;
   const size_t row = (size_t)D * pl.eb, srow = scale_row_bytes(L);
   if (has_v && pl.fused) {
-    HIP_TRY(aquakv::launch_fused_decode(L->n_codewords, at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb), L->d_in_v - D,
+    HIP_TRY(aquakv::launch_fused_decode(quantizer_id(L), at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb), L->d_in_v - D,
                                         at(Khat, r0, row), D, L->w_v, L->b_v, L->signs_v, L->codebook,
                                         static_cast<const uint8_t*>(at(v_codes, r0, pl.code_row)),
                                         static_cast<const uint16_t*>(at(v_scales, r0, srow)), at(Vhat, r0, row), n, D,
@@ -209,7 +233,7 @@ int decode_values_chunk(const aquakv_layer* L, const Plan& pl, int64_t r0, int64
   if (has_v)
     HIP_TRY(aquakv::launch_predict(L->dtype, at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb), L->d_in_v - D,
                                    at(Khat, r0, row), D, L->w_v, L->b_v, Pbuf, n, D, stream));
-  HIP_TRY(aquakv::launch_dequantize(L->dtype, L->n_codewords, static_cast<const uint8_t*>(at(v_codes, r0, pl.code_row)),
+  HIP_TRY(aquakv::launch_dequantize(L->dtype, quantizer_id(L), static_cast<const uint8_t*>(at(v_codes, r0, pl.code_row)),
                                     static_cast<const uint16_t*>(at(v_scales, r0, srow)), has_v ? Pbuf : nullptr, L->signs_v,
                                     L->codebook, at(Vhat, r0, row), n, L->kv_heads, is_wide(L), stream));
   return AQUAKV_OK;
@@ -284,9 +308,9 @@ int aquakv_quantize(const aquakv_layer* L, int which, int64_t tokens, const void
   CHECK(check_ptr(X, "X", true));
   CHECK(check_ptr(P, "P", false));
   CHECK(check_ptr(codes, "codes", true));
-  CHECK(check_scales(scales, "scales", true));
+  CHECK(check_scales(L, scales, "scales", true));
   CHECK(check_ptr(Xhat, "Xhat", false));
-  HIP_TRY(aquakv::launch_quantize(L->dtype, L->n_codewords, X, P, which == AQUAKV_KEY ? L->signs_k : L->signs_v,
+  HIP_TRY(aquakv::launch_quantize(L->dtype, quantizer_id(L), X, P, which == AQUAKV_KEY ? L->signs_k : L->signs_v,
                                   L->codebook, L->search_table, codes, scales, Xhat, tokens, L->kv_heads, is_wide(L),
                                   static_cast<hipStream_t>(stream)));
   return AQUAKV_OK;
@@ -298,10 +322,10 @@ int aquakv_dequantize(const aquakv_layer* L, int which, int64_t tokens, const ui
   if (which != AQUAKV_KEY && which != AQUAKV_VALUE) return fail(AQUAKV_EINVAL, "which=%d", which);
   if (tokens < 0) return fail(AQUAKV_EINVAL, "tokens=%lld", (long long)tokens);
   CHECK(check_ptr(codes, "codes", true));
-  CHECK(check_scales(scales, "scales", true));
+  CHECK(check_scales(L, scales, "scales", true));
   CHECK(check_ptr(P, "P", false));
   CHECK(check_ptr(Xhat, "Xhat", true));
-  HIP_TRY(aquakv::launch_dequantize(L->dtype, L->n_codewords, codes, scales, P,
+  HIP_TRY(aquakv::launch_dequantize(L->dtype, quantizer_id(L), codes, scales, P,
                                     which == AQUAKV_KEY ? L->signs_k : L->signs_v, L->codebook, Xhat, tokens,
                                     L->kv_heads, is_wide(L), static_cast<hipStream_t>(stream)));
   return AQUAKV_OK;
@@ -319,9 +343,9 @@ int aquakv_encode_layer(const aquakv_layer* L, int64_t tokens, const void* K, co
   CHECK(check_ptr(Khat_prev, "Khat_prev", has_k));
   CHECK(check_ptr(Vhat_prev, "Vhat_prev", has_v));
   CHECK(check_ptr(k_codes, "k_codes", true));
-  CHECK(check_scales(k_scales, "k_scales", true));
+  CHECK(check_scales(L, k_scales, "k_scales", true));
   CHECK(check_ptr(v_codes, "v_codes", true));
-  CHECK(check_scales(v_scales, "v_scales", true));
+  CHECK(check_scales(L, v_scales, "v_scales", true));
   CHECK(check_ptr(Khat, "Khat", false));
   CHECK(check_ptr(Vhat, "Vhat", false));
   if (tokens == 0) return AQUAKV_OK;
@@ -352,9 +376,9 @@ int aquakv_decode_layer(const aquakv_layer* L, int64_t tokens, const uint8_t* k_
   const bool want_v = Vhat != nullptr;
   const bool has_k = L->d_in_k != 0, has_v = L->d_in_v != 0 && want_v;
   CHECK(check_ptr(k_codes, "k_codes", true));
-  CHECK(check_scales(k_scales, "k_scales", true));
+  CHECK(check_scales(L, k_scales, "k_scales", true));
   CHECK(check_ptr(v_codes, "v_codes", want_v));
-  CHECK(check_scales(v_scales, "v_scales", want_v));
+  CHECK(check_scales(L, v_scales, "v_scales", want_v));
   CHECK(check_ptr(Khat_prev, "Khat_prev", has_k));
   CHECK(check_ptr(Vhat_prev, "Vhat_prev", has_v));
   CHECK(check_ptr(Khat, "Khat", true));
@@ -386,7 +410,7 @@ int aquakv_encode_keys(const aquakv_layer* L, int64_t tokens, const void* K, con
   CHECK(check_ptr(K, "K", true));
   CHECK(check_ptr(Khat_prev, "Khat_prev", L->d_in_k != 0));
   CHECK(check_ptr(k_codes, "k_codes", true));
-  CHECK(check_scales(k_scales, "k_scales", true));
+  CHECK(check_scales(L, k_scales, "k_scales", true));
   CHECK(check_ptr(Khat, "Khat", false));
   if (tokens == 0) return AQUAKV_OK;
   const Plan pl = make_plan(L, tokens);
@@ -413,7 +437,7 @@ int aquakv_encode_values(const aquakv_layer* L, int64_t tokens, const void* V, c
   CHECK(check_ptr(Vhat_prev, "Vhat_prev", has_v));
   CHECK(check_ptr(Khat, "Khat", has_v));
   CHECK(check_ptr(v_codes, "v_codes", true));
-  CHECK(check_scales(v_scales, "v_scales", true));
+  CHECK(check_scales(L, v_scales, "v_scales", true));
   CHECK(check_ptr(Vhat, "Vhat", false));
   if (tokens == 0) return AQUAKV_OK;
   const Plan pl = make_plan(L, tokens);
@@ -437,7 +461,7 @@ int aquakv_decode_values(const aquakv_layer* L, int64_t tokens, const uint8_t* v
   if (tokens < 0) return fail(AQUAKV_EINVAL, "tokens=%lld", (long long)tokens);
   const bool has_v = L->d_in_v != 0;
   CHECK(check_ptr(v_codes, "v_codes", true));
-  CHECK(check_scales(v_scales, "v_scales", true));
+  CHECK(check_scales(L, v_scales, "v_scales", true));
   CHECK(check_ptr(Vhat_prev, "Vhat_prev", has_v));
   CHECK(check_ptr(Khat, "Khat", has_v));
   CHECK(check_ptr(Vhat, "Vhat", true));
@@ -457,7 +481,7 @@ int aquakv_decode_values(const aquakv_layer* L, int64_t tokens, const uint8_t* v
 
 size_t aquakv_scores_workspace_bytes(const aquakv_layer* L, int32_t batch, int32_t q_heads) {
   if (check_layer(L) != AQUAKV_OK || batch < 1 || q_heads < 1) return 0;
-  if (L->dtype != AQUAKV_BF16 || is_wide(L) || !aquakv::folded_scores_supported(L->kv_heads, L->d_in_k, q_heads)) return 0;
+  if (L->dtype != AQUAKV_BF16 || is_wide(L) || is_rtn(L) || !aquakv::folded_scores_supported(L->kv_heads, L->d_in_k, q_heads)) return 0;
   return aquakv::folded_scores_workspace_bytes(batch);
 }
 
@@ -475,7 +499,7 @@ int decode_attn_scores(const aquakv_layer* L, int32_t batch, int32_t seq_len, in
     return fail(AQUAKV_EINVAL, "q_heads=%d must be a multiple of kv_heads=%d, at most 8x", q_heads, L->kv_heads);
   const bool has_k = L->d_in_k != 0;
   CHECK(check_ptr(k_codes, "k_codes", true));
-  CHECK(check_scales(k_scales, "k_scales", true));
+  CHECK(check_scales(L, k_scales, "k_scales", true));
   CHECK(check_ptr(Khat_prev, "Khat_prev", has_k));
   CHECK(check_ptr(q, "q", true));
   CHECK(check_ptr(scores, "scores", true));
@@ -483,7 +507,7 @@ int decode_attn_scores(const aquakv_layer* L, int32_t batch, int32_t seq_len, in
   const int64_t tokens = (int64_t)batch * seq_len;
   if (tokens == 0) return AQUAKV_OK;
   const Plan pl = make_plan(L, tokens);
-  if (has_k && pl.fused && Khat_out == nullptr && rope_cos == nullptr && workspace != nullptr &&
+  if (has_k && pl.fused && !is_rtn(L) && Khat_out == nullptr && rope_cos == nullptr && workspace != nullptr &&
       aquakv::folded_scores_supported(L->kv_heads, L->d_in_k, q_heads) &&
       workspace_bytes >= aquakv::folded_scores_workspace_bytes(batch)) {
     // predictor folded into the query: Khat_prev and the codes are read once, nothing is recomputed
@@ -495,7 +519,7 @@ int decode_attn_scores(const aquakv_layer* L, int32_t batch, int32_t seq_len, in
   }
   if (has_k && pl.fused) {
     // one fused launch over all rows: prediction, inverse quantizer and dot products
-    HIP_TRY(aquakv::launch_fused_scores(L->n_codewords, Khat_prev, L->d_in_k, L->w_k, L->b_k, L->signs_k, L->codebook,
+    HIP_TRY(aquakv::launch_fused_scores(quantizer_id(L), Khat_prev, L->d_in_k, L->w_k, L->b_k, L->signs_k, L->codebook,
                                         k_codes, k_scales, q, score_scale, scores, Khat_out, seq_len, q_heads, tokens,
                                         pl.D, rope_cos, rope_sin, static_cast<hipStream_t>(stream_)));
     return AQUAKV_OK;
@@ -514,7 +538,7 @@ int decode_attn_scores(const aquakv_layer* L, int32_t batch, int32_t seq_len, in
     if (has_k)
       HIP_TRY(aquakv::launch_predict(L->dtype, at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k, nullptr, 0,
                                      L->w_k, L->b_k, Pbuf, n, pl.D, stream));
-    HIP_TRY(aquakv::launch_attn_scores(L->dtype, L->n_codewords, static_cast<const uint8_t*>(at(k_codes, r0, pl.code_row)),
+    HIP_TRY(aquakv::launch_attn_scores(L->dtype, quantizer_id(L), static_cast<const uint8_t*>(at(k_codes, r0, pl.code_row)),
                                        static_cast<const uint16_t*>(at(k_scales, r0, srow)), has_k ? Pbuf : nullptr,
                                        L->signs_k, L->codebook, q, score_scale, scores, at(Khat_out, r0, row), r0, n,
                                        seq_len, L->kv_heads, q_heads, rope_cos, rope_sin, is_wide(L), stream));

@@ -20,7 +20,15 @@ constexpr float kCellHalfRange = 4.0f;       // cells tile [-4, 4]^2
 constexpr float kCellScale = kCells / (2.0f * kCellHalfRange);   // 8 cells per unit
 constexpr uint32_t kCellFull = 0xffffffffu;  // too many candidates for the list: full search
 
+// Quantizer ids, the NCW template argument everywhere: 16 / 64 / 256 = a grid of that many points in R^2;
+// kRtn2 / kRtn4 = the uniform round-to-nearest backbone with 2 / 4 bits per value (see rtn_quantize_group).
+constexpr int kRtn2 = 2, kRtn4 = 4;
+__host__ __device__ constexpr bool is_rtn(int id) { return id < 16; }
+
+// c = code bits per pair of values (a lane holds 16 pairs = 4c code bytes, whatever the quantizer)
 template <int NCW> struct CodeBits;
+template <> struct CodeBits<kRtn2> { static constexpr int c = 4; };
+template <> struct CodeBits<kRtn4> { static constexpr int c = 8; };
 template <> struct CodeBits<16> { static constexpr int c = 4; };
 template <> struct CodeBits<64> { static constexpr int c = 6; };
 template <> struct CodeBits<256> { static constexpr int c = 8; };
@@ -28,6 +36,7 @@ template <> struct CodeBits<256> { static constexpr int c = 8; };
 // Grid in LDS as (a, b, -(a^2+b^2)/2, unused): argmin ||y - C||^2 = argmax y.C - |C|^2/2.
 template <int NCW>
 __device__ __forceinline__ void load_codebook(const float* __restrict__ codebook, float4* cb) {
+  if constexpr (is_rtn(NCW)) return;          // no grid
   for (int j = threadIdx.x; j < NCW; j += blockDim.x) {
     const float a = codebook[2 * j], b = codebook[2 * j + 1];
     cb[j] = make_float4(a, b, -0.5f * (a * a + b * b), 0.f);
@@ -217,6 +226,97 @@ __device__ __forceinline__ void stage_lds(Lds& lds, const float* __restrict__ co
 }
 
 
+// ------------------------------------------------------------------ uniform round-to-nearest backbone
+// Sect. 4.1 "Backbone quantization" of the paper: b-bit round-to-nearest with per-group normalisation, groups of
+// 64 consecutive channels of a token = the 2 x 32 values of a lane pair (quad lanes 0,1 and 2,3).  Per group:
+// lo = min(0, min r), hi = max(0, max r), step = (hi - lo) / (2^b - 1) stored as fp16, zero = round(-lo / step),
+// code = clamp(round(r / step) + zero, 0, 2^b - 1) with the stored step, rounding half to even.  Stored per
+// group: (fp16 step, 16-bit zero point), i.e. `scales` holds two uint16 per group, [T, H, 2 groups, 2].
+// Codes: b bits per value in channel order, little-endian: the lane's 32 values are 4b contiguous bytes.
+template <int BITS>
+__device__ __forceinline__ void rtn_store_codes(uint8_t* __restrict__ codes, int64_t gid, int q, const uint32_t (&code)[32]) {
+  uint32_t* dst = reinterpret_cast<uint32_t*>(codes + gid * (kGroup * BITS / 8) + q * (4 * BITS));
+  constexpr int kPerWord = 32 / BITS;
+  uint32_t d[BITS] = {};
+#pragma unroll
+  for (int r = 0; r < 32; ++r) d[r / kPerWord] |= code[r] << (BITS * (r % kPerWord));
+  if constexpr (BITS == 2) {
+    u32x2 v; v.x = d[0]; v.y = d[1];
+    *reinterpret_cast<u32x2*>(dst) = v;
+  } else {
+    u32x4 v; v.x = d[0]; v.y = d[1]; v.z = d[2]; v.w = d[3];
+    *reinterpret_cast<u32x4*>(dst) = v;
+  }
+}
+
+// the lane's code bytes (first BITS dwords of `raw`) and its group's (step, zero) word -> p + (code - zero) * step
+template <int BITS>
+__device__ __forceinline__ void rtn_reconstruct(const u32x4 raw, uint32_t meta, const float (&p)[32], float (&v)[32]) {
+  const uint32_t d[4] = {raw.x, raw.y, raw.z, raw.w};
+  constexpr int kPerWord = 32 / BITS;
+  const float s16 = half_bits_to_float((uint16_t)(meta & 0xffffu));
+  const int zero = (int)(meta >> 16);
+#pragma unroll
+  for (int r = 0; r < 32; ++r) {
+    const int code = (int)((d[r / kPerWord] >> (BITS * (r % kPerWord))) & ((1u << BITS) - 1u));
+    v[r] = __fmaf_rn((float)(code - zero), s16, p[r]);     // the product is exact: small integer x fp16
+  }
+}
+
+template <int BITS>
+__device__ __forceinline__ u32x4 rtn_load_codes(const uint8_t* __restrict__ codes, int64_t gid, int q) {
+  const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + gid * (kGroup * BITS / 8) + q * (4 * BITS));
+  u32x4 raw = {0, 0, 0, 0};
+  if constexpr (BITS == 2) {
+    const u32x2 v = *reinterpret_cast<const u32x2*>(src);
+    raw.x = v.x; raw.y = v.y;
+  } else {
+    raw = *reinterpret_cast<const u32x4*>(src);
+  }
+  return raw;
+}
+
+__device__ __forceinline__ uint32_t rtn_load_meta(const uint16_t* __restrict__ scales, int64_t gid, int q) {
+  return reinterpret_cast<const uint32_t*>(scales)[gid * 2 + (q >> 1)];
+}
+
+// Q(x - p) for the 32 values this lane holds of head group gid; same contract as quantize_group below.
+template <int BITS>
+__device__ __forceinline__ void rtn_quantize_group(float (&v)[32], const float (&p)[32], int q, bool active, int64_t gid,
+                                                   uint8_t* __restrict__ codes, uint16_t* __restrict__ scales,
+                                                   bool want_hat) {
+  constexpr float kTop = (float)((1 << BITS) - 1);
+  float lo = 0.f, hi = 0.f;
+#pragma unroll
+  for (int r = 0; r < 32; ++r) {
+    v[r] -= p[r];
+    lo = fminf(lo, v[r]);
+    hi = fmaxf(hi, v[r]);
+  }
+  lo = fminf(lo, quad_xor<1>(lo));
+  hi = fmaxf(hi, quad_xor<1>(hi));
+  const float step = fminf(__fdiv_rn(hi - lo, kTop), 65504.0f);
+  const _Float16 s16h = static_cast<_Float16>(step);      // round to nearest even
+  const float s16 = static_cast<float>(s16h);
+  const bool ok = s16 > 0.f;
+  const float inv = ok ? __fdiv_rn(1.0f, s16) : 0.f;
+  const float zf = ok ? __builtin_amdgcn_fmed3f(__builtin_rintf(__fdiv_rn(-lo, s16)), 0.f, kTop) : 0.f;
+  uint32_t code[32];
+#pragma unroll
+  for (int r = 0; r < 32; ++r)
+    code[r] = (uint32_t)__builtin_amdgcn_fmed3f(__builtin_rintf(v[r] * inv) + zf, 0.f, kTop);
+  if (active) {
+    rtn_store_codes<BITS>(codes, gid, q, code);
+    if ((q & 1) == 0)
+      reinterpret_cast<uint32_t*>(scales)[gid * 2 + (q >> 1)] =
+          (uint32_t)__builtin_bit_cast(uint16_t, s16h) | ((uint32_t)zf << 16);
+  }
+  if (want_hat) {
+#pragma unroll
+    for (int r = 0; r < 32; ++r) v[r] = __fmaf_rn((float)code[r] - zf, s16, p[r]);
+  }
+}
+
 // ------------------------------------------------------------------ group bodies
 // Q(x - p) for the 32 coordinates this lane holds of head group `gid` (= token * H + head).  On entry
 // v = x; on exit v holds the (unrounded) reconstruction p + Q^-1(codes) if `want_hat`.  Codes and the
@@ -229,6 +329,10 @@ __device__ __forceinline__ void quantize_group(float (&v)[32], const float (&p)[
                                                const float4* cb, const uint32_t* table, bool active, int64_t gid,
                                                uint8_t* __restrict__ codes, uint16_t* __restrict__ scales,
                                                bool want_hat) {
+  if constexpr (is_rtn(NCW)) {
+    rtn_quantize_group<NCW>(v, p, l & 3, active, gid, codes, scales, want_hat);
+    return;
+  }
 #pragma unroll
   for (int r = 0; r < 32; ++r) v[r] = __uint_as_float(__float_as_uint(v[r] - p[r]) ^ sb[r]);   // s * (x - p)
   const int q = l & 3;
@@ -276,6 +380,10 @@ template <int NCW, bool WIDE = false>
 __device__ __forceinline__ void dequantize_group(float (&z)[32], const float (&p)[32], const uint32_t (&sb)[32], int l,
                                                  const float4* cb, int64_t gid, const uint8_t* __restrict__ codes,
                                                  const uint16_t* __restrict__ scales) {
+  if constexpr (is_rtn(NCW)) {
+    rtn_reconstruct<NCW>(rtn_load_codes<NCW>(codes, gid, l & 3), rtn_load_meta(scales, gid, l & 3), p, z);
+    return;
+  }
   int idx[16];
   load_codes<NCW>(codes, gid, l & 3, idx);
   const float s16 = half_bits_to_float(scales[WIDE ? gid >> 3 : gid]);

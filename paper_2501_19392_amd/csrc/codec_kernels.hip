@@ -37,7 +37,7 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const T* X, const fl
     const int64_t off = gid * kGroup + q * kValsPerLane;
 
     float v[32], p[32];
-    uint32_t sb[32];
+    uint32_t sb[32] = {};
     Storage<T>::load32(X + off, v);
     if (P != nullptr) {
       load32_f32(P + off, p);
@@ -45,7 +45,7 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const T* X, const fl
 #pragma unroll
       for (int r = 0; r < 32; ++r) p[r] = 0.f;
     }
-    load_sign_bits(signs, head, q, sb);
+    if constexpr (!is_rtn(NCW)) load_sign_bits(signs, head, q, sb);
     quantize_group<NCW, WIDE>(v, p, sb, WIDE ? (int)(threadIdx.x & 31) : q, lds.cb, table != nullptr ? lds.table : nullptr,
                               active, gid, codes, scales, Xhat != nullptr);
     if (Xhat != nullptr && active) Storage<T>::store32(Xhat + off, v);
@@ -60,7 +60,7 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint8_t* __r
                                                               const int8_t* __restrict__ signs,
                                                               const float* __restrict__ codebook, T* __restrict__ Xhat,
                                                               int64_t n_groups, int H) {
-  __shared__ float4 cb[NCW];
+  __shared__ float4 cb[is_rtn(NCW) ? 1 : NCW];
   load_codebook<NCW>(codebook, cb);
   __syncthreads();
   const int q = threadIdx.x & 3;
@@ -72,14 +72,14 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint8_t* __r
     const int64_t off = gid * kGroup + q * kValsPerLane;
 
     float p[32], z[32];
-    uint32_t sb[32];
+    uint32_t sb[32] = {};
     if (P != nullptr) {
       load32_f32(P + off, p);
     } else {
 #pragma unroll
       for (int r = 0; r < 32; ++r) p[r] = 0.f;
     }
-    load_sign_bits(signs, head, q, sb);
+    if constexpr (!is_rtn(NCW)) load_sign_bits(signs, head, q, sb);
     dequantize_group<NCW, WIDE>(z, p, sb, WIDE ? (int)(threadIdx.x & 31) : q, cb, gid, codes, scales);
     if (active) Storage<T>::store32(Xhat + off, z);
   }
@@ -93,7 +93,7 @@ __global__ __launch_bounds__(kThreads) void attn_scores_kernel(
     const int8_t* __restrict__ signs, const float* __restrict__ codebook, const T* __restrict__ qv_,
     float score_scale, float* __restrict__ scores, T* __restrict__ Khat_out, int64_t row0, int64_t n_groups,
     int seq_len, int H, int q_heads, const float* __restrict__ rope_cos, const float* __restrict__ rope_sin) {
-  __shared__ float4 cb[NCW];
+  __shared__ float4 cb[is_rtn(NCW) ? 1 : NCW];
   load_codebook<NCW>(codebook, cb);
   __syncthreads();
   const int q = threadIdx.x & 3;
@@ -109,14 +109,14 @@ __global__ __launch_bounds__(kThreads) void attn_scores_kernel(
     const int64_t off = gid * kGroup + q * kValsPerLane;
 
     float p[32], z[32];
-    uint32_t sb[32];
+    uint32_t sb[32] = {};
     if (P != nullptr) {
       load32_f32(P + off, p);
     } else {
 #pragma unroll
       for (int r = 0; r < 32; ++r) p[r] = 0.f;
     }
-    load_sign_bits(signs, head, q, sb);
+    if constexpr (!is_rtn(NCW)) load_sign_bits(signs, head, q, sb);
     dequantize_group<NCW, WIDE>(z, p, sb, WIDE ? (int)(threadIdx.x & 31) : q, cb, gid, codes, scales);
     if (Khat_out != nullptr && active) Storage<T>::store32(Khat_out + off, z);
 #pragma unroll
@@ -190,22 +190,29 @@ inline unsigned blocks_for(int64_t n_groups) {
 
 }  // namespace
 
-#define AQUAKV_DISPATCH_N(NCW, CALL)                                                    \
+#define AQUAKV_DISPATCH_GRID(NCW, CALL)                                                 \
   do {                                                                                  \
     if ((NCW) == 16) { constexpr int N = 16; CALL; }                                    \
     else if ((NCW) == 64) { constexpr int N = 64; CALL; }                               \
     else { constexpr int N = 256; CALL; }                                               \
   } while (0)
-// binds T (storage type), N (grid size) and W (rotation group of 1024) as compile-time names for CALL
+#define AQUAKV_DISPATCH_N(NCW, CALL)                                                    \
+  do {                                                                                  \
+    if ((NCW) == kRtn2) { constexpr int N = kRtn2; CALL; }                              \
+    else if ((NCW) == kRtn4) { constexpr int N = kRtn4; CALL; }                         \
+    else AQUAKV_DISPATCH_GRID(NCW, CALL);                                               \
+  } while (0)
+// binds T (storage type), N (quantizer id: grid size, or kRtn2 / kRtn4) and W (rotation group of 1024, grids only)
+// as compile-time names for CALL
 #define AQUAKV_DISPATCH(DT, NCW, WIDE_, CALL)                                           \
   do {                                                                                  \
     if ((DT) == kBF16) {                                                                \
       typedef bf16_t T;                                                                 \
-      if (WIDE_) { constexpr bool W = true; AQUAKV_DISPATCH_N(NCW, CALL); }             \
+      if (WIDE_) { constexpr bool W = true; AQUAKV_DISPATCH_GRID(NCW, CALL); }          \
       else { constexpr bool W = false; AQUAKV_DISPATCH_N(NCW, CALL); }                  \
     } else {                                                                            \
       typedef float T;                                                                  \
-      if (WIDE_) { constexpr bool W = true; AQUAKV_DISPATCH_N(NCW, CALL); }             \
+      if (WIDE_) { constexpr bool W = true; AQUAKV_DISPATCH_GRID(NCW, CALL); }          \
       else { constexpr bool W = false; AQUAKV_DISPATCH_N(NCW, CALL); }                  \
     }                                                                                   \
   } while (0)

@@ -48,16 +48,17 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
   // grid and cell table: requested now, kept in registers while the main loop owns the LDS
   constexpr int kTableChunks = kCells * kCells / 4 / (WAVES * 64);
   static_assert(NCW <= WAVES * 64, "one grid point per thread");
+  constexpr int kGridPoints = is_rtn(NCW) ? 0 : NCW;
   float cb_a = 0.f, cb_b = 0.f;
   u32x4 table_regs[kTableChunks];
-  if (threadIdx.x < NCW) { cb_a = codebook[2 * threadIdx.x]; cb_b = codebook[2 * threadIdx.x + 1]; }
+  if (threadIdx.x < kGridPoints) { cb_a = codebook[2 * threadIdx.x]; cb_b = codebook[2 * threadIdx.x + 1]; }
   if (use_table) {
 #pragma unroll
     for (int i = 0; i < kTableChunks; ++i)
       table_regs[i] = reinterpret_cast<const u32x4*>(table)[threadIdx.x + i * WAVES * 64];
   }
   const auto stage_tables = [&] {
-    if (threadIdx.x < NCW) cl.cb[threadIdx.x] = make_float4(cb_a, cb_b, -0.5f * (cb_a * cb_a + cb_b * cb_b), 0.f);
+    if (threadIdx.x < kGridPoints) cl.cb[threadIdx.x] = make_float4(cb_a, cb_b, -0.5f * (cb_a * cb_a + cb_b * cb_b), 0.f);
     if (use_table) {
 #pragma unroll
       for (int i = 0; i < kTableChunks; ++i)
@@ -81,7 +82,7 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
   // requested from inside the main loop, when its own last operand loads are out, so the
   // latency is covered by the remaining MFMA work.
   constexpr int c = CodeBits<NCW>::c;
-  struct In { u32x4 x[4]; u32x4 code; uint16_t scale; };
+  struct In { u32x4 x[4]; u32x4 code; uint32_t scale; };     // scale: fp16 bits (grids) or (step, zero point) (round-to-nearest)
   constexpr int kPasses = kRowsPerWave / 16;          // passes of 16 groups per wave, one group per quad
   In in[kPasses];
   const auto fetch = [&](int pass, In& in) {
@@ -102,7 +103,8 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
       } else {
         in.code = *reinterpret_cast<const u32x4*>(src);
       }
-      in.scale = scales[gid];
+      if constexpr (is_rtn(NCW)) in.scale = rtn_load_meta(scales, gid, q);
+      else in.scale = scales[gid];
     }
   };
 
@@ -133,8 +135,8 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
   __syncthreads();
 
   // Epilogue: passes of 16 groups per wave, one group per quad.
-  uint32_t sb[32];
-  load_sign_bits(signs, head, q, sb);
+  uint32_t sb[32] = {};
+  if constexpr (!is_rtn(NCW)) load_sign_bits(signs, head, q, sb);
   // one pass: 16 groups of this wave (rows pass*16 .. +15), inputs already in `in`
   const auto do_pass = [&](int pass, const In& in) {
     const int lrow = pass * 16 + (lane >> 2);
@@ -159,10 +161,14 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
                           Xhat != nullptr);
       if (Xhat != nullptr && active) Storage<bf16_t>::store32(Xhat + off, v);
     } else {
-      int idx[16];
-      unpack_codes<NCW>(in.code, idx);
-      gather_zhat(idx, half_bits_to_float(in.scale), cl.cb, v);
-      reconstruct(v, q, sb, p);
+      if constexpr (is_rtn(NCW)) {
+        rtn_reconstruct<NCW>(in.code, in.scale, p, v);
+      } else {
+        int idx[16];
+        unpack_codes<NCW>(in.code, idx);
+        gather_zhat(idx, half_bits_to_float((uint16_t)in.scale), cl.cb, v);
+        reconstruct(v, q, sb, p);
+      }
       if (Xhat != nullptr && active) Storage<bf16_t>::store32(Xhat + off, v);
       if constexpr (MODE == kScores) {
 #pragma unroll
@@ -190,6 +196,7 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
   }
 }
 
+// n_codewords: the quantizer id (grid size, or kRtn2 / kRtn4)
 template <int MODE>
 hipError_t launch(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W, const float* bias,
                   const int8_t* signs, const float* codebook, const void* table, const void* X, uint8_t* codes,
@@ -210,7 +217,9 @@ hipError_t launch(int n_codewords, const void* x0, int d0, const void* x1, int d
       signs, codebook, static_cast<const uint32_t*>(table), static_cast<const bf16_t*>(X), codes, scales,         \
       static_cast<bf16_t*>(Xhat), static_cast<const bf16_t*>(q), score_scale, scores, seq_len, q_heads, T, D, rope_cos,  \
       rope_sin)
-  if (n_codewords == 16) AQUAKV_FUSED(16);
+  if (n_codewords == kRtn2) AQUAKV_FUSED(kRtn2);
+  else if (n_codewords == kRtn4) AQUAKV_FUSED(kRtn4);
+  else if (n_codewords == 16) AQUAKV_FUSED(16);
   else if (n_codewords == 64) AQUAKV_FUSED(64);
   else AQUAKV_FUSED(256);
 #undef AQUAKV_FUSED

@@ -21,12 +21,24 @@ def np64(t: torch.Tensor) -> np.ndarray:
 
 
 def make_layers(kv_heads, dtype, n, layer_idx=1, w_k=None, w_v=None, b_k=None, b_v=None, device="cuda", table=True,
-                rht_group=None):
+                rht_group=None, rtn_bits=None):
     """(oracle layer, binding layer) from the same arrays.  w_* are torch fp32 [D, d_in]
-    and are rounded to the storage dtype first so that both sides see identical weights."""
+    and are rounded to the storage dtype first so that both sides see identical weights.
+    rtn_bits: the uniform round-to-nearest backbone instead of the grid of n points."""
     from paper_2501_19392_amd import binding as B
     g = 128
     sd = synth.torch_dtype(dtype)
+    if rtn_bits is not None:
+        wk = None if w_k is None else w_k.to(sd)
+        wv = None if w_v is None else w_v.to(sd)
+        f32 = lambda t: None if t is None else t.float()
+        lo = O.Layer(kv_heads=kv_heads, head_dim=g, dtype=dtype, rtn_bits=rtn_bits,
+                     w_k=None if wk is None else np64(wk), w_v=None if wv is None else np64(wv),
+                     b_k=None if b_k is None else np64(f32(b_k)), b_v=None if b_v is None else np64(f32(b_v)))
+        dev = lambda t: None if t is None else t.to(device)
+        lg = B.Layer(kv_heads, g, None, None, None, sd, w_k=dev(wk), w_v=dev(wv), b_k=dev(f32(b_k)), b_v=dev(f32(b_v)),
+                     rtn_bits=rtn_bits)
+        return lo, lg
     C = synth.lloyd_codebook(n)
     sk = synth.rht_signs(kv_heads, g, layer_idx, "k")
     sv = synth.rht_signs(kv_heads, g, layer_idx, "v")
@@ -106,6 +118,55 @@ def compare_quantizer_outputs(residual, signs, codebook, gpu_codes, gpu_scales, 
     rep.distance_ties = int(ties.sum())
     rep.other += int((cm & ~ties).sum())
     return rep
+
+
+RTN_TIE = 1e-5         # distance of value / step (or -lo / step) to x.5 below which a rounding counts as tied
+
+
+def compare_rtn_outputs(residual, gpu_codes, gpu_meta, bits) -> CodeReport:
+    """Round-to-nearest backbone: codes, steps and zero points of the HIP path against the oracle, same residual.
+
+    residual [T, D]; gpu_codes uint8 [T, ...]; gpu_meta (u)int16 [T, D/64, 2].  A step that differs must sit on an
+    fp16 rounding boundary of the oracle's fp64 step, a zero point that differs on x.5; such groups are re-assigned
+    by the oracle under the GPU's step / zero point.  A code that differs must be a value within RTN_TIE of a
+    rounding boundary.  Anything else is `other`."""
+    T = residual.shape[0]
+    idx_o, s16_o, zero_o, diag = O.rtn_quantize(residual, bits)
+    groups = s16_o.shape[-1]
+    g_s16, g_zero = O.rtn_unpack_meta(np.ascontiguousarray(gpu_meta).reshape(T, groups, 2))
+    g_idx = O.unpack_codes(np.ascontiguousarray(gpu_codes).reshape(T, groups, -1), 1 << bits)
+    rep = CodeReport(groups=s16_o.size, subvectors=idx_o.size)
+    sm = g_s16.view(np.uint16) != s16_o.view(np.uint16)
+    zm = g_zero != zero_o
+    rep.scale_mismatch = int((sm | zm).sum())
+    bad = np.zeros_like(sm)
+    if rep.scale_mismatch:
+        near = fp16_boundary_distance(diag.scale) <= SCALE_TIE_REL
+        adjacent = np.abs(g_s16.view(np.uint16).astype(np.int64) - s16_o.view(np.uint16).astype(np.int64)) == 1
+        s_ok = sm & near & adjacent
+        # the zero point is judged under the step that is finally used
+        idx_o, _, zero_o, diag = O.rtn_quantize(residual, bits, scale16_override=np.where(s_ok, g_s16, s16_o))
+        zm = g_zero != zero_o
+        z_ok = zm & (diag.zero_frac <= RTN_TIE) & (np.abs(g_zero - zero_o) == 1)
+        bad = (sm & ~s_ok) | (zm & ~z_ok)
+        rep.scale_ties = int((s_ok | z_ok).sum())
+        rep.other += int(bad.sum())
+        idx_o, _, _, diag = O.rtn_quantize(residual, bits, scale16_override=np.where(s_ok, g_s16, s16_o),
+                                           zero_override=np.where(z_ok, g_zero, zero_o))
+    cm = (g_idx != idx_o) & ~bad[..., None]
+    rep.code_mismatch = int(cm.sum())
+    ties = cm & (diag.frac <= RTN_TIE) & (np.abs(g_idx - idx_o) == 1)
+    rep.distance_ties = int(ties.sum())
+    rep.other += int((cm & ~ties).sum())
+    return rep
+
+
+def rtn_decode(gpu_codes, gpu_meta, bits, T):
+    """The oracle's inverse of stored round-to-nearest codes -> residual [T, D]."""
+    meta = np.ascontiguousarray(gpu_meta).reshape(T, -1, 2)
+    s16, zero = O.rtn_unpack_meta(meta)
+    idx = O.unpack_codes(np.ascontiguousarray(gpu_codes).reshape(T, meta.shape[1], -1), 1 << bits)
+    return O.rtn_dequantize(idx, s16, zero)
 
 
 def assert_close_storage(got: torch.Tensor, want: np.ndarray, dtype: str, what: str):

@@ -154,3 +154,26 @@ def test_half_calls_validate_their_arguments():
     B.aquakv_decode_values(L, 0, FAKE, FAKE, FAKE, FAKE, FAKE, None)
     L0 = layer(d_in_k=0, d_in_v=0, w_k=None, w_v=None)                          # no predictors: no *_prev, no Khat input
     assert status_of(B.aquakv_encode_values, L0, 8, FAKE, None, None, None, FAKE, FAKE, ws) == B.AQUAKV_ENULL  # v_codes
+
+
+def test_round_to_nearest_backbone_layer_validation():
+    """vq_dim = 1: the uniform round-to-nearest backbone (Sect. 4.1): 4 or 16 levels, groups of 64, no grid / signs,
+    (step, zero point) words need 4-byte alignment, no folded scoring form."""
+    rtn = dict(vq_dim=1, n_codewords=4, codebook=None, signs_k=None, signs_v=None)
+    L = layer(**rtn)
+    assert B.aquakv_workspace_bytes(L, 300) == 300 * 1024 * 2                # bf16: fused like the grids
+    assert B.aquakv_workspace_bytes(layer(**dict(rtn, n_codewords=16, rht_group=64)), 300) == 300 * 1024 * 2
+    assert B.aquakv_workspace_bytes(layer(**dict(rtn, dtype=B.AQUAKV_FP32)), 300) == 300 * 1024 * 8
+    assert B.aquakv_scores_workspace_bytes(L, 1, 32) == 0
+    ws = (FAKE, 1 << 30)
+    for kw, want in ((dict(n_codewords=8), B.AQUAKV_EUNSUPPORTED), (dict(n_codewords=5), B.AQUAKV_EINVAL),
+                     (dict(n_codewords=64), B.AQUAKV_EUNSUPPORTED), (dict(rht_group=128), B.AQUAKV_EUNSUPPORTED),
+                     (dict(rht_group=1024), B.AQUAKV_EUNSUPPORTED)):
+        assert status_of(B.aquakv_encode_layer, layer(**dict(rtn, **kw)), 8, *ENC_OK, ws) == want, kw
+    bad = list(ENC_OK)
+    bad[5] = FAKE + 2                                                          # k_scales: 2-byte aligned is not enough
+    assert status_of(B.aquakv_encode_layer, L, 8, *bad, ws) == B.AQUAKV_EALIGN
+    bad[5] = FAKE + 4
+    bad[0] = None
+    assert status_of(B.aquakv_encode_layer, L, 8, *bad, ws) == B.AQUAKV_ENULL   # alignment passed, K is missing
+    B.aquakv_encode_layer(L, 0, *ENC_OK, None)
