@@ -1,0 +1,103 @@
+"""The layer calls under HIP graph capture: the library allocates nothing, keeps no state and never synchronises, so a
+whole encode / decode / scoring sweep can be captured once and replayed.  Every replay is checked bit for bit
+against the eager calls on the same inputs, with eager work and synchronisations between the replays."""
+import pytest
+import torch
+
+from paper_2501_19392_amd import synth
+from tests import parity_utils as U
+
+pytestmark = pytest.mark.gpu
+
+
+def bits_of(t):
+    return t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32)
+
+
+@pytest.mark.parametrize("dtype,rtn_bits", [("bf16", None), ("fp32", None), ("bf16", 2)])
+def test_layer_sweeps_replay_from_a_graph(dtype, rtn_bits):
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: the gpu-marked tests must run on an MI355X")
+    from paper_2501_19392_amd import binding as B
+    print(f"case graph capture dtype={dtype} rtn_bits={rtn_bits}", flush=True)
+    H, QH, T, L = 8, 24, 515, 3
+    D = H * 128
+    sd = synth.torch_dtype(dtype)
+    layers = []
+    for l in range(L):
+        kw = {} if l == 0 else dict(w_k=U.random_weights(D, D, 400 + l, 0.7), w_v=U.random_weights(D, 2 * D, 500 + l, 0.7),
+                                    b_k=torch.randn(D, generator=torch.Generator().manual_seed(600 + l)) * 0.1)
+        layers.append(U.make_layers(H, dtype, 16, layer_idx=l, rtn_bits=rtn_bits, **kw)[1])
+
+    def inputs(seed):
+        g = torch.Generator().manual_seed(seed)
+        return [((torch.randn(T, H, 128, generator=g)).to(sd).cuda(), (torch.randn(T, H, 128, generator=g)).to(sd).cuda())
+                for _ in range(L)], torch.randn(1, QH, 128, generator=g).to(sd).cuda()
+
+    class Bufs:
+        def __init__(self):
+            self.kv = [(layers[0].alloc_kv(T), layers[0].alloc_kv(T)) for _ in range(L)]
+            self.q = torch.empty(1, QH, 128, dtype=sd, device="cuda")
+            self.codes = [(lay.alloc_codes(T), lay.alloc_codes(T)) for lay in layers]
+            self.hat = [(lay.alloc_kv(T), lay.alloc_kv(T)) for lay in layers]
+            self.dec = [(lay.alloc_kv(T), lay.alloc_kv(T)) for lay in layers]
+            self.scores = [torch.empty(1, QH, T, dtype=torch.float32, device="cuda") for _ in layers]
+            self.ws = max((lay.alloc_workspace(T) for lay in layers), key=lambda t: t.numel())
+            self.ws_scores = [lay.alloc_scores_workspace(1, QH) for lay in layers]
+
+        def load(self, kv, q):
+            for (K, V), (k, v) in zip(self.kv, kv):
+                K.copy_(k); V.copy_(v)
+            self.q.copy_(q)
+
+        def outputs(self):
+            out = []
+            for l in range(L):
+                (kc, ks), (vc, vs) = self.codes[l]
+                out += [kc, ks, vc, vs, bits_of(self.hat[l][0]), bits_of(self.hat[l][1]), bits_of(self.dec[l][0]),
+                        bits_of(self.dec[l][1]), self.scores[l]]
+            return [t.clone() for t in out]
+
+    def sweep(b):
+        Kp = Vp = None
+        for l, lay in enumerate(layers):
+            (kc, ks), (vc, vs) = b.codes[l]
+            B.aquakv_encode_layer(lay, T, b.kv[l][0], b.kv[l][1], Kp, Vp, kc, ks, vc, vs, b.hat[l][0], b.hat[l][1], b.ws)
+            Kp, Vp = b.hat[l]
+        Kp = Vp = None
+        for l, lay in enumerate(layers):
+            (kc, ks), (vc, vs) = b.codes[l]
+            B.aquakv_decode_layer(lay, T, kc, ks, vc, vs, Kp, Vp, b.dec[l][0], b.dec[l][1], b.ws)
+            # layers with a folded form take it (their own workspace); the others recompute the prediction
+            folded = B.aquakv_scores_workspace_bytes(lay, 1, QH) > 0
+            B.aquakv_decode_attn_scores(lay, 1, T, QH, kc, ks, Kp, b.q, 0.125, b.scores[l], None,
+                                        b.ws_scores[l] if folded else b.ws)
+            Kp, Vp = b.dec[l]
+
+    eager, graphed = Bufs(), Bufs()
+    kv0, q0 = inputs(1)
+    graphed.load(kv0, q0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        sweep(graphed)                                       # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        sweep(graphed)
+    torch.cuda.synchronize()
+    for rep, seed in enumerate((2, 3, 1, 4)):
+        kv, q = inputs(seed)
+        eager.load(kv, q)
+        sweep(eager)                                         # the program's own eager work between replays
+        torch.cuda.synchronize()
+        want = eager.outputs()
+        graphed.load(kv, q)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = graphed.outputs()
+        same = [torch.equal(a, b) for a, b in zip(got, want)]
+        print(f"   replay {rep} (inputs {seed}): {sum(same)} of {len(same)} outputs identical", flush=True)
+        assert all(same)
