@@ -12,6 +12,11 @@ What it follows (AQUA-KV paper, arxiv 2501.19392):
     tokens); to attend, the past is recovered one layer at a time with Alg. "decode", every layer
     from the previous layer's recovered past.
 
+  * Sect. 4.1 (first-layer strategies, Table 1 "1st Layer Keys & Values"): the first layer has no predictor and
+    is either quantized by the backbone alone (the default for the Llama models: a 4-bit grid) or kept in 16
+    bits (the Qwen setting).  Here every layer brings its own grid, and a layer given as None is kept in 16 bits:
+    its flushed tokens are stored as they are and feed the next layer's predictors exactly.
+
 Quantization is per token, so flushing the buffer in pieces gives the same codes as encoding the
 same token range in one call; the pin in tests/test_cache_policy.py checks exactly that, and that
 sinks and buffered tokens come back untouched.
@@ -34,6 +39,7 @@ class CacheOracle:
         self.sink_k, self.sink_v = empty(), empty()          # [<= sink_tokens, H, g] as given
         self.buf_k, self.buf_v = empty(), empty()            # [<  buffer_tokens, H, g] as given
         self.codes = [dict(k_codes=[], k_scales=[], v_codes=[], v_scales=[]) for _ in range(L)]
+        self.raw = [dict(k=[], v=[]) for _ in range(L)]      # flushed tokens of the layers kept in 16 bits
         self.n_sink = self.n_compressed = self.n_buffered = 0
 
     @property
@@ -69,10 +75,14 @@ class CacheOracle:
         """The full buffer is quantized from the first layer to the last (Alg. "encode" per layer)."""
         Kp = Vp = None
         for l, lay in enumerate(self.layers):
-            e = O.encode_layer(lay, self.buf_k[l], self.buf_v[l], Kp, Vp)
-            for name in ("k_codes", "k_scales", "v_codes", "v_scales"):
-                self.codes[l][name].append(e[name])
-            Kp, Vp = e["Khat"], e["Vhat"]
+            if lay is None:                                   # kept in 16 bits: stored as is
+                self.raw[l]["k"].append(self.buf_k[l]); self.raw[l]["v"].append(self.buf_v[l])
+                Kp, Vp = self.buf_k[l], self.buf_v[l]
+            else:
+                e = O.encode_layer(lay, self.buf_k[l], self.buf_v[l], Kp, Vp)
+                for name in ("k_codes", "k_scales", "v_codes", "v_scales"):
+                    self.codes[l][name].append(e[name])
+                Kp, Vp = e["Khat"], e["Vhat"]
             self.buf_k[l] = self.buf_v[l] = None
         self.n_compressed += self.n_buffered
         self.n_buffered = 0
@@ -86,8 +96,11 @@ class CacheOracle:
             if self.n_sink:
                 parts_k.append(self.sink_k[l]); parts_v.append(self.sink_v[l])
             if self.n_compressed:
-                c = {k: np.concatenate(v, axis=0) for k, v in self.codes[l].items()}
-                Kp, Vp = O.decode_layer(lay, c["k_codes"], c["k_scales"], c["v_codes"], c["v_scales"], Kp, Vp)
+                if lay is None:
+                    Kp, Vp = np.concatenate(self.raw[l]["k"], axis=0), np.concatenate(self.raw[l]["v"], axis=0)
+                else:
+                    c = {k: np.concatenate(v, axis=0) for k, v in self.codes[l].items()}
+                    Kp, Vp = O.decode_layer(lay, c["k_codes"], c["k_scales"], c["v_codes"], c["v_scales"], Kp, Vp)
                 parts_k.append(Kp); parts_v.append(Vp)
             if self.n_buffered:
                 parts_k.append(self.buf_k[l]); parts_v.append(self.buf_v[l])
@@ -95,7 +108,9 @@ class CacheOracle:
 
     def stored_bytes(self, elem_bytes: int = 2) -> int:
         """Bytes held for all layers: uncompressed sinks and buffer, packed codes and fp16 scales."""
-        per_tok = self.layers[0].kv_heads * self.layers[0].head_dim * elem_bytes * 2
+        some = next(l for l in self.layers if l is not None)
+        per_tok = some.kv_heads * some.head_dim * elem_bytes * 2
         raw = (self.n_sink + self.n_buffered) * per_tok * len(self.layers)
+        raw += sum(int(a.size) * elem_bytes for r in self.raw for v in r.values() for a in v)
         comp = sum(int(a.size) * a.itemsize for c in self.codes for v in c.values() for a in v)
         return raw + comp

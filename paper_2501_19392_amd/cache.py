@@ -5,6 +5,10 @@ experiments) stay in 16 bits; up to r = 128 recent tokens are kept uncompressed 
 is full, quantized layer by layer from the first layer to the last; Alg. "Inference": to attend, the
 compressed past is recovered one layer at a time, each layer from the previous layer's recovered past.
 
+Sect. 4.1 (first-layer strategies): every layer brings its own grid (the paper's default quantizes the first layer,
+which has no predictor, with the 4-bit grid), and a layer given as None is kept in 16 bits (its flushed tokens are
+stored as they are and feed the next layer's predictors).
+
 This class is bookkeeping only: every number is produced by the C-ABI calls (`aquakv_encode_layer`,
 `aquakv_decode_layer`); torch tensors are the device memory they work on.  One sequence per cache.
 """
@@ -24,20 +28,23 @@ class AquaKVCache:
             raise ValueError("buffer_tokens >= 1 and sink_tokens >= 0")
         self.layers = list(layers)
         self.sink_tokens, self.buffer_tokens, self.max_tokens = sink_tokens, buffer_tokens, max_tokens
-        lay0 = self.layers[0]
+        lay0 = next(l for l in self.layers if l is not None)
         H, g, dt = lay0.kv_heads, lay0.head_dim, lay0.dtype
         raw = lambda t: torch.empty(t, H, g, dtype=dt, device=device)
         self.sink = [(raw(max(sink_tokens, 1)), raw(max(sink_tokens, 1))) for _ in self.layers]
         self.buf = [(raw(buffer_tokens), raw(buffer_tokens)) for _ in self.layers]
         cap = max(max_tokens - sink_tokens, 0) // buffer_tokens * buffer_tokens      # the compressed range grows by whole buffers
-        self.codes = [(l.alloc_codes(max(cap, 1), device), l.alloc_codes(max(cap, 1), device)) for l in self.layers]
+        self.codes = [None if l is None else (l.alloc_codes(max(cap, 1), device), l.alloc_codes(max(cap, 1), device))
+                      for l in self.layers]
+        self.raw = [(raw(max(cap, 1)), raw(max(cap, 1))) if l is None else None for l in self.layers]   # layers kept in 16 bits
         self.capacity = cap
         # flush: reconstructions of the flushed tokens, two ping-pong pairs (layer l - 1 feeds layer l)
         self._flush_hat = [(raw(buffer_tokens), raw(buffer_tokens)) for _ in range(2)]
-        self._flush_ws = max((l.alloc_workspace(buffer_tokens, device) for l in self.layers), key=lambda t: t.numel())
+        coded = [l for l in self.layers if l is not None]
+        self._flush_ws = max((l.alloc_workspace(buffer_tokens, device) for l in coded), key=lambda t: t.numel())
         # recovery: [sinks | compressed | buffer] of one layer, two ping-pong pairs
         self._view = [(raw(max_tokens), raw(max_tokens)) for _ in range(2)]
-        self._view_ws = max((l.alloc_workspace(max(cap, 1), device) for l in self.layers), key=lambda t: t.numel())
+        self._view_ws = max((l.alloc_workspace(max(cap, 1), device) for l in coded), key=lambda t: t.numel())
         self.n_sink = self.n_compressed = self.n_buffered = 0
 
     @property
@@ -74,6 +81,10 @@ class AquaKVCache:
         r, at = self.buffer_tokens, self.n_compressed
         Kp = Vp = None
         for l, lay in enumerate(self.layers):
+            if lay is None:                                  # kept in 16 bits: stored as is, feeds the next layer exactly
+                Kp, Vp = self.raw[l][0][at:at + r], self.raw[l][1][at:at + r]
+                Kp.copy_(self.buf[l][0]); Vp.copy_(self.buf[l][1])
+                continue
             (kc, ks), (vc, vs) = self.codes[l]
             Kh, Vh = self._flush_hat[l & 1]
             B.aquakv_encode_layer(lay, r, self.buf[l][0], self.buf[l][1], Kp, Vp, kc[at:at + r], ks[at:at + r],
@@ -92,7 +103,10 @@ class AquaKVCache:
             K, V = self._view[l & 1]
             if s:
                 K[:s].copy_(self.sink[l][0][:s]); V[:s].copy_(self.sink[l][1][:s])
-            if c:
+            if c and lay is None:
+                K[s:s + c].copy_(self.raw[l][0][:c]); V[s:s + c].copy_(self.raw[l][1][:c])
+                Kp, Vp = K[s:s + c], V[s:s + c]
+            elif c:
                 (kc, ks), (vc, vs) = self.codes[l]
                 B.aquakv_decode_layer(lay, c, kc[:c], ks[:c], vc[:c], vs[:c], Kp, Vp, K[s:s + c], V[s:s + c], self._view_ws)
                 Kp, Vp = K[s:s + c], V[s:s + c]
@@ -102,10 +116,13 @@ class AquaKVCache:
 
     def stored_bytes(self) -> int:
         """Bytes the cache content occupies (all layers): 16-bit sinks and buffer, packed codes and fp16 scales."""
-        lay0 = self.layers[0]
+        lay0 = next(l for l in self.layers if l is not None)
         per_tok = lay0.d * self.sink[0][0].element_size() * 2
         total = (self.n_sink + self.n_buffered) * per_tok * len(self.layers)
         for lay in self.layers:
+            if lay is None:
+                total += self.n_compressed * per_tok
+                continue
             groups = lay.d // lay.rht_group
             total += 2 * self.n_compressed * (lay.kv_heads * lay.code_bytes_per_group + 2 * groups * lay.scale_words_per_group)
         return total
