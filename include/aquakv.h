@@ -224,7 +224,8 @@ int aquakv_decode_values(const aquakv_layer* layer, int64_t tokens, const uint8_
  * predictor product, bound by reading Khat_prev and the codes once.  The call takes this form
  * when Khat_out is NULL and `workspace` holds at least aquakv_scores_workspace_bytes() bytes
  * (a nonzero value says the form exists for this layer and shape: bf16, 8 kv heads, key
- * predictor with 1024 inputs, q_heads <= 32); otherwise it recomputes the prediction.  The
+ * predictor with 1024 inputs, q_heads <= 64: one pass over the cache per 4 query heads of a kv
+ * head, so two passes above 32 query heads); otherwise it recomputes the prediction.  The
  * folded scores use the unrounded keys and agree with the definition above to the storage
  * precision of Khat (2^-9 relative per term in bf16).
  */

@@ -22,6 +22,9 @@
 // head h by the group's 64 grid points (looked up in LDS, fp16 operands: a correction term) and scales
 // the result by the group's sigma.  The 8 partial tiles are added in a fixed order through LDS.
 // Nothing but the scores is written.
+//
+// A pass handles up to 4 query heads per kv head (32 rows = one MFMA block).  Models with more (8 query heads
+// per kv head) take two passes over the cache, pass p scoring query heads 4 p ... 4 p + 3 of every kv head.
 #include "codec_core.h"
 #include "gemm_core.h"
 #include "kernels.h"
@@ -47,13 +50,16 @@ constexpr int kFoldChunks = 8;
 __global__ __launch_bounds__(256) void fold_query_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ W,
                                                          const float* __restrict__ bias,
                                                          const int8_t* __restrict__ signs, unsigned char* ws,
-                                                         int q_heads, int kv_heads) {
+                                                         int q_heads, int kv_heads, int r0, int rep) {
+  // q_heads: query heads of the model; this pass takes query heads r0 ... r0 + rep - 1 (rep <= 4) of every kv head
+  // and numbers them h * rep + r ("row" below)
   __shared__ float qs[4][128];
   __shared__ float part[16][4][128 + 4];
   const int cc = blockIdx.x % kFoldChunks;
   const int bh = blockIdx.x / kFoldChunks;
   const int b = bh / kv_heads, h = bh % kv_heads;
-  const int rep = q_heads / kv_heads;            // <= 4
+  const int rep_model = q_heads / kv_heads;
+  const int rows = kv_heads * rep;               // rows of this pass that exist
   const int tid = threadIdx.x;
   const int cg = tid & 15, dp = tid >> 4;
   // predictor rows 8 dp ... + 7 of this head, channels 128 cc + 8 cg ... + 7
@@ -62,7 +68,7 @@ __global__ __launch_bounds__(256) void fold_query_kernel(const bf16_t* __restric
 #pragma unroll
   for (int d = 0; d < 8; ++d) wraw[d] = *reinterpret_cast<const u32x4*>(Wc + (size_t)d * kFoldK);
   for (int e = tid; e < rep * 128; e += 256)
-    qs[e >> 7][e & 127] = static_cast<float>(q[((size_t)b * q_heads + h * rep + (e >> 7)) * 128 + (e & 127)]);
+    qs[e >> 7][e & 127] = static_cast<float>(q[((size_t)b * q_heads + h * rep_model + r0 + (e >> 7)) * 128 + (e & 127)]);
   __syncthreads();
 
   unsigned char* wsb = ws + (size_t)b * kFoldBytesPerBatch;
@@ -116,7 +122,7 @@ __global__ __launch_bounds__(256) void fold_query_kernel(const bf16_t* __restric
     }
     // rows of query heads that do not exist multiply as zero: kv head h clears rows q_heads + h, + 8, ...
     if (half == 0) {
-      for (int qh = q_heads + h; qh < kFoldQ; qh += kv_heads) {
+      for (int qh = rows + h; qh < kFoldQ; qh += kv_heads) {
         const size_t pos = (size_t)(qh + 32 * khalf) * 8 + e;
         U[frag + pos] = static_cast<bf16_t>(0.f);
         U[frag + lo_off + pos] = static_cast<bf16_t>(0.f);
@@ -177,7 +183,9 @@ __global__ __launch_bounds__(512) void folded_scores_kernel(const bf16_t* __rest
                                                             const unsigned char* __restrict__ ws, float score_scale,
                                                             float* __restrict__ scores, int seq_len, int q_heads,
                                                             int tiles_per_seq, int tiles_per_block,
-                                                            int blocks_per_seq) {
+                                                            int blocks_per_seq, int r0, int rep) {
+  // q_heads: query heads of the model (row stride of `scores`); this pass scores query heads r0 ... r0 + rep - 1
+  // (rep <= 4) of every kv head, numbered h * rep + r as in fold_query_kernel
   constexpr int c = CodeBits<NCW>::c;
   constexpr int H = 8;
   __shared__ __attribute__((aligned(16))) unsigned char smem[kFoldLdsBytes];
@@ -192,7 +200,8 @@ __global__ __launch_bounds__(512) void folded_scores_kernel(const bf16_t* __rest
   const int b = blockIdx.x / blocks_per_seq;
   const int tile0 = (blockIdx.x % blocks_per_seq) * tiles_per_block;
   const int ntiles = tiles_per_seq - tile0 < tiles_per_block ? tiles_per_seq - tile0 : tiles_per_block;
-  const int rep = q_heads / H;
+  const int rows = H * rep;
+  const int rep_model = q_heads / H;
   const unsigned char* wsb = ws + (size_t)b * kFoldBytesPerBatch;
   const float* qrot = reinterpret_cast<const float*>(wsb + kUBytesPerBatch);
   const float* cdot = qrot + kFoldQ * 128;
@@ -212,7 +221,7 @@ __global__ __launch_bounds__(512) void folded_scores_kernel(const bf16_t* __rest
     for (int ks = 0; ks < 8; ++ks)
       u[hl][ks] = *reinterpret_cast<const bf16x8*>(wsb + ((size_t)(wave * 2 + hl) * 8 + ks) * kUFragBytes + lane * 16);
   {
-    const bool mine = ftok < q_heads && ftok / rep == wave;
+    const bool mine = ftok < rows && ftok / rep == wave;
     const float* src = qrot + (mine ? ftok : 0) * 128 + 64 * fk;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
@@ -295,8 +304,12 @@ __global__ __launch_bounds__(512) void folded_scores_kernel(const bf16_t* __rest
   // flight while tile it is multiplied; codes are fetched two tiles ahead
   // the two query heads this lane finishes per tile (see the end of the loop) and their q . b
   const int qh0 = 8 * (wave >> 1) + 4 * fk + 2 * (wave & 1);
-  const float cd0 = qh0 < q_heads ? cdot[qh0] : 0.f;
-  const float cd1 = qh0 + 1 < q_heads ? cdot[qh0 + 1] : 0.f;
+  const float cd0 = qh0 < rows ? cdot[qh0] : 0.f;
+  const float cd1 = qh0 + 1 < rows ? cdot[qh0 + 1] : 0.f;
+  // the model's query head behind a row of this pass
+  const auto model_head = [&](int row) { return (row / rep) * rep_model + r0 + row % rep; };
+  float* const out0 = scores + ((size_t)b * q_heads + model_head(qh0)) * seq_len;
+  float* const out1 = scores + ((size_t)b * q_heads + model_head(qh0 + 1)) * seq_len;
   Packed c0, c1;
   fetch_codes(tile0, c0);
   c1 = c0;
@@ -390,9 +403,8 @@ __global__ __launch_bounds__(512) void folded_scores_kernel(const bf16_t* __rest
       dot1 += pr.y;
     }
     if (t0 + ftok < seq_len) {
-      float* dst = scores + ((size_t)b * q_heads + qh0) * seq_len + t0 + ftok;
-      if (qh0 < q_heads) dst[0] = (dot0 + cd0) * score_scale;
-      if (qh0 + 1 < q_heads) dst[seq_len] = (dot1 + cd1) * score_scale;
+      if (qh0 < rows) out0[t0 + ftok] = (dot0 + cd0) * score_scale;
+      if (qh0 + 1 < rows) out1[t0 + ftok] = (dot1 + cd1) * score_scale;
     }
     barrier();                                              // partials consumed: the exchange area may be rewritten
   }
@@ -400,10 +412,17 @@ __global__ __launch_bounds__(512) void folded_scores_kernel(const bf16_t* __rest
 
 }  // namespace
 
-size_t folded_scores_workspace_bytes(int batch) { return (size_t)batch * kFoldBytesPerBatch; }
+namespace {
+constexpr int kRepPerPass = kFoldQ / 8;          // query heads per kv head in one pass
+inline int passes_for(int q_heads) { return (q_heads / 8 + kRepPerPass - 1) / kRepPerPass; }
+}  // namespace
+
+size_t folded_scores_workspace_bytes(int batch, int q_heads) {
+  return (size_t)passes_for(q_heads) * batch * kFoldBytesPerBatch;
+}
 
 bool folded_scores_supported(int kv_heads, int d_in_k, int q_heads) {
-  return kv_heads == 8 && d_in_k == kFoldK && q_heads <= kFoldQ && q_heads % kv_heads == 0;
+  return kv_heads == 8 && d_in_k == kFoldK && q_heads <= 2 * kFoldQ && q_heads % kv_heads == 0;
 }
 
 hipError_t launch_folded_scores(int n_codewords, const void* Khat_prev, const void* W, const float* bias,
@@ -411,9 +430,6 @@ hipError_t launch_folded_scores(int n_codewords, const void* Khat_prev, const vo
                                 const uint16_t* scales, const void* q, float score_scale, float* scores, void* workspace,
                                 int batch, int seq_len, int q_heads, hipStream_t stream) {
   if (batch == 0 || seq_len == 0) return hipSuccess;
-  unsigned char* ws = static_cast<unsigned char*>(workspace);
-  fold_query_kernel<<<batch * 8 * kFoldChunks, 256, 0, stream>>>(static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(W), bias,
-                                                  signs, ws, q_heads, 8);
   const int tiles_per_seq = (seq_len + kTokTile - 1) / kTokTile;
   // enough workgroups to fill the 256 CUs several times over; up to 32 consecutive tiles each, over which the
   // query operands loaded at kernel start are reused
@@ -421,13 +437,22 @@ hipError_t launch_folded_scores(int n_codewords, const void* Khat_prev, const vo
   tiles_per_block = tiles_per_block < 1 ? 1 : tiles_per_block > 32 ? 32 : tiles_per_block;
   const int blocks_per_seq = (tiles_per_seq + tiles_per_block - 1) / tiles_per_block;
   const unsigned blocks = (unsigned)(blocks_per_seq * batch);
+  const int rep_model = q_heads / 8;
 #define AQUAKV_FOLDED(N)                                                                                       \
   folded_scores_kernel<N><<<blocks, 512, 0, stream>>>(static_cast<const bf16_t*>(Khat_prev), codes, scales,      \
                                                       codebook, ws, score_scale, scores, seq_len, q_heads,      \
-                                                      tiles_per_seq, tiles_per_block, blocks_per_seq)
-  if (n_codewords == 16) AQUAKV_FOLDED(16);
-  else if (n_codewords == 64) AQUAKV_FOLDED(64);
-  else AQUAKV_FOLDED(256);
+                                                      tiles_per_seq, tiles_per_block, blocks_per_seq, r0, rep)
+  for (int pass = 0; pass < passes_for(q_heads); ++pass) {
+    unsigned char* ws = static_cast<unsigned char*>(workspace) + (size_t)pass * batch * kFoldBytesPerBatch;
+    const int r0 = pass * kRepPerPass;
+    const int rep = rep_model - r0 < kRepPerPass ? rep_model - r0 : kRepPerPass;
+    fold_query_kernel<<<batch * 8 * kFoldChunks, 256, 0, stream>>>(static_cast<const bf16_t*>(q),
+                                                                    static_cast<const bf16_t*>(W), bias, signs, ws,
+                                                                    q_heads, 8, r0, rep);
+    if (n_codewords == 16) AQUAKV_FOLDED(16);
+    else if (n_codewords == 64) AQUAKV_FOLDED(64);
+    else AQUAKV_FOLDED(256);
+  }
 #undef AQUAKV_FOLDED
   return hipGetLastError();
 }

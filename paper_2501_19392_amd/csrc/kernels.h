@@ -51,9 +51,10 @@ hipError_t launch_fused_scores(int n_codewords, const void* x0, int d0, const vo
                                hipStream_t stream);
 
 // Scores with the key predictor folded into the query (bf16, 8 kv heads, 1024 predictor inputs,
-// q_heads <= 32): reads Khat_prev and the codes once.  `workspace`: folded_scores_workspace_bytes(batch).
+// q_heads <= 64): reads Khat_prev and the codes once per 4 query heads of a kv head (one pass up to 32 query
+// heads, two up to 64).  `workspace`: folded_scores_workspace_bytes(batch, q_heads).
 bool folded_scores_supported(int kv_heads, int d_in_k, int q_heads);
-size_t folded_scores_workspace_bytes(int batch);
+size_t folded_scores_workspace_bytes(int batch, int q_heads);
 hipError_t launch_folded_scores(int n_codewords, const void* Khat_prev, const void* W, const float* bias,
                                 const int8_t* signs, const float* codebook, const uint8_t* codes,
                                 const uint16_t* scales, const void* q, float score_scale, float* scores, void* workspace,

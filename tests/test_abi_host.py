@@ -124,13 +124,16 @@ def test_bad_call_arguments_are_rejected_without_launching():
 
 def test_scores_workspace_query():
     """aquakv_scores_workspace_bytes: nonzero exactly where the folded scoring form exists (bf16, 8 kv heads,
-    key predictor with 1024 inputs, at most 32 query heads), linear in the batch."""
+    key predictor with 1024 inputs, at most 64 query heads), linear in the batch and in the passes of 4 query
+    heads per kv head."""
     L = layer()
     per_batch = 8 * 2 * 8 * 1024 + 32 * 128 * 4 + 32 * 4      # operands of W^T q, rotated queries, q . b
     assert B.aquakv_scores_workspace_bytes(L, 1, 32) == per_batch
     assert B.aquakv_scores_workspace_bytes(L, 64, 24) == 64 * per_batch
     assert per_batch % 16 == 0
-    assert B.aquakv_scores_workspace_bytes(L, 1, 64) == 0                                   # more than 32 query heads
+    assert B.aquakv_scores_workspace_bytes(L, 1, 64) == 2 * per_batch                       # two passes
+    assert B.aquakv_scores_workspace_bytes(L, 3, 40) == 6 * per_batch
+    assert B.aquakv_scores_workspace_bytes(L, 1, 72) == 0                                   # more than 64 query heads
     assert B.aquakv_scores_workspace_bytes(L, 0, 32) == 0
     assert B.aquakv_scores_workspace_bytes(layer(dtype=B.AQUAKV_FP32), 1, 32) == 0
     assert B.aquakv_scores_workspace_bytes(layer(kv_heads=4), 1, 32) == 0

@@ -518,11 +518,11 @@ def test_attn_scores(B, dtype, n, with_pred):
 
 
 @pytest.mark.parametrize("n,QH,batch,S,bias", [(16, 24, 2, 100, True), (64, 32, 1, 1000, False), (256, 8, 3, 33, True),
-                                              (16, 16, 5, 31, False)])
+                                              (16, 16, 5, 31, False), (16, 64, 2, 70, True), (64, 40, 1, 130, False)])
 def test_folded_scores_against_definition(B, n, QH, batch, S, bias):
     """aquakv_decode_attn_scores in its folded form against the oracle's plain definition
-    (decode the keys, round them to storage, dot with q): query heads per kv head 1..4, all
-    three grids, predictor bias, ragged last tile, sequences shorter than one tile."""
+    (decode the keys, round them to storage, dot with q): query heads per kv head 1..4 (one pass), 5 and 8
+    (two passes), all three grids, predictor bias, ragged last tile, sequences shorter than one tile."""
     print(f"case folded scores n={n} QH={QH} batch={batch} S={S} bias={bias}", flush=True)
     H = 8
     cfg = synth.Config("fold", layers=2, kv_heads=H, head_dim=128, tokens=batch * S, dtype="bf16", n_codewords=n)
