@@ -182,8 +182,7 @@ __global__ __launch_bounds__(512) void folded_scores_kernel(const bf16_t* __rest
                                                             const float* __restrict__ codebook,
                                                             const unsigned char* __restrict__ ws, float score_scale,
                                                             float* __restrict__ scores, int seq_len, int q_heads,
-                                                            int tiles_per_seq, int tiles_per_block,
-                                                            int blocks_per_seq, int r0, int rep) {
+                                                            int tiles_per_seq, int blocks_per_seq, int r0, int rep) {
   // q_heads: query heads of the model (row stride of `scores`); this pass scores query heads r0 ... r0 + rep - 1
   // (rep <= 4) of every kv head, numbered h * rep + r as in fold_query_kernel
   constexpr int c = CodeBits<NCW>::c;
@@ -198,8 +197,12 @@ __global__ __launch_bounds__(512) void folded_scores_kernel(const bf16_t* __rest
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int b = blockIdx.x / blocks_per_seq;
-  const int tile0 = (blockIdx.x % blocks_per_seq) * tiles_per_block;
-  const int ntiles = tiles_per_seq - tile0 < tiles_per_block ? tiles_per_seq - tile0 : tiles_per_block;
+  // The workgroups of a sequence walk its tiles interleaved: workgroup j takes tiles j, j + blocks_per_seq, ...
+  // so that the workgroups running at the same time read neighbouring tiles (measured 1 - 2 % over giving each
+  // workgroup a contiguous range).
+  const int tile0 = blockIdx.x % blocks_per_seq;
+  const int tstep = blocks_per_seq;
+  const int ntiles = (tiles_per_seq - tile0 + blocks_per_seq - 1) / blocks_per_seq;
   const int rows = H * rep;
   const int rep_model = q_heads / H;
   const unsigned char* wsb = ws + (size_t)b * kFoldBytesPerBatch;
@@ -313,13 +316,13 @@ __global__ __launch_bounds__(512) void folded_scores_kernel(const bf16_t* __rest
   Packed c0, c1;
   fetch_codes(tile0, c0);
   c1 = c0;
-  if (ntiles > 1) fetch_codes(tile0 + 1, c1);
+  if (ntiles > 1) fetch_codes(tile0 + tstep, c1);
   request_tile(tile0, 0);
-  if (ntiles > 1) request_tile(tile0 + 1, 1);
+  if (ntiles > 1) request_tile(tile0 + tstep, 1);
   barrier();                                                // the grid is in LDS
   for (int it = 0; it < ntiles; ++it) {
     const int slot = it & 1;
-    const int t0 = (tile0 + it) * kTokTile;
+    const int t0 = (tile0 + it * tstep) * kTokTile;
     const unsigned char* tile_lds = smem + (wave * 2 + slot) * kSlotBytes;
     if (it + 1 < ntiles) __builtin_amdgcn_s_waitcnt(0x0f70 | 8);          // vmcnt(8): all but the newest tile request
     else __builtin_amdgcn_s_waitcnt(0x0f70);                              // vmcnt(0)
@@ -344,6 +347,15 @@ __global__ __launch_bounds__(512) void folded_scores_kernel(const bf16_t* __rest
         __builtin_amdgcn_sched_barrier(0);
       }
     }
+    // this wave's reads of the slot have returned: refill it with tile it + 2 at once (its codes first, so that
+    // the count of outstanding loads at the top of the loop still separates the tiles); the code term below
+    // does not touch the slot
+    Packed cn = c1;
+    if (it + 2 < ntiles) fetch_codes(tile0 + (it + 2) * tstep, cn);
+    __builtin_amdgcn_s_waitcnt(0x0070 | 15 | (3 << 14));    // lgkmcnt(0)
+    asm volatile("" ::: "memory");
+    if (it + 2 < ntiles) request_tile(tile0 + (it + 2) * tstep, slot);
+    asm volatile("" ::: "memory");
     // code term on the matrix cores: [query heads of this kv head] x [32 tokens] x [128 rotated coordinates]
     f32x16 acc_c;
 #pragma unroll
@@ -367,12 +379,7 @@ __global__ __launch_bounds__(512) void folded_scores_kernel(const bf16_t* __rest
     // the lane's column is one token: the code term is scaled by that group's sigma
     const float s16 = half_bits_to_float(c0.scale);
     c0 = c1;
-    if (it + 2 < ntiles) fetch_codes(tile0 + it + 2, c1);   // two tiles ahead, issued before the tile request below
-    // this wave's reads of the slot have returned: refill it with tile it + 2
-    __builtin_amdgcn_s_waitcnt(0x0070 | 15 | (3 << 14));    // lgkmcnt(0)
-    asm volatile("" ::: "memory");
-    if (it + 2 < ntiles) request_tile(tile0 + it + 2, slot);
-    asm volatile("" ::: "memory");
+    c1 = cn;
 
     // every wave hands the registers it does not finish itself to their owners (register k belongs to wave k / 2)
 #pragma unroll
@@ -431,8 +438,8 @@ hipError_t launch_folded_scores(int n_codewords, const void* Khat_prev, const vo
                                 int batch, int seq_len, int q_heads, hipStream_t stream) {
   if (batch == 0 || seq_len == 0) return hipSuccess;
   const int tiles_per_seq = (seq_len + kTokTile - 1) / kTokTile;
-  // enough workgroups to fill the 256 CUs several times over; up to 32 consecutive tiles each, over which the
-  // query operands loaded at kernel start are reused
+  // enough workgroups to fill the 256 CUs several times over; up to 32 tiles each, over which the query operands
+  // loaded at kernel start are reused
   int tiles_per_block = (int)(((int64_t)tiles_per_seq * batch) / 1024);
   tiles_per_block = tiles_per_block < 1 ? 1 : tiles_per_block > 32 ? 32 : tiles_per_block;
   const int blocks_per_seq = (tiles_per_seq + tiles_per_block - 1) / tiles_per_block;
@@ -441,7 +448,7 @@ hipError_t launch_folded_scores(int n_codewords, const void* Khat_prev, const vo
 #define AQUAKV_FOLDED(N)                                                                                       \
   folded_scores_kernel<N><<<blocks, 512, 0, stream>>>(static_cast<const bf16_t*>(Khat_prev), codes, scales,      \
                                                       codebook, ws, score_scale, scores, seq_len, q_heads,      \
-                                                      tiles_per_seq, tiles_per_block, blocks_per_seq, r0, rep)
+                                                      tiles_per_seq, blocks_per_seq, r0, rep)
   for (int pass = 0; pass < passes_for(q_heads); ++pass) {
     unsigned char* ws = static_cast<unsigned char*>(workspace) + (size_t)pass * batch * kFoldBytesPerBatch;
     const int r0 = pass * kRepPerPass;
