@@ -334,6 +334,36 @@ def test_bf16_three_layers_ragged(B, n):
     assert err_pred < (0.06 if n == 16 else 0.02), err_pred
 
 
+@pytest.mark.parametrize("dtype,H,T", [("bf16", 1, 1), ("bf16", 1, 255), ("bf16", 3, 256), ("bf16", 5, 257), ("bf16", 16, 300),
+                                       ("bf16", 6, 513), ("fp32", 3, 130), ("fp32", 16, 65)])
+def test_head_counts_and_tile_edges(B, dtype, H, T):
+    """Head counts other than 8 (odd ones: the workgroup count is then not a multiple of the 8 XCDs; 16: predictor
+    inputs of 2048 / 4096) at token counts around the edges of the 256-row tile: every stage against the oracle,
+    decode reproduces encode bit for bit, scores against the decoded keys."""
+    print(f"case head counts dtype={dtype} H={H} T={T}", flush=True)
+    cfg = synth.Config("shapes", layers=2, kv_heads=H, head_dim=128, tokens=T, dtype=dtype)
+    Ks, Vs, lo_l, lg_l = build_stack(cfg, predictors="random", bias=True)
+    out = run_gpu_layers(B, cfg, lg_l, Ks, Vs)
+    for l in range(cfg.layers):
+        for rep in check_layer_against_oracle(B, lo_l[l], lg_l[l], Ks[l], Vs[l], out[l]):
+            print(f"   layer {l}: {rep}", flush=True)
+        g, lg = out[l], lg_l[l]
+        Kh, Vh = lg.alloc_kv(T), lg.alloc_kv(T)
+        ws = lg.alloc_workspace(T)
+        B.aquakv_decode_layer(lg, T, g["k_codes"], g["k_scales"], g["v_codes"], g["v_scales"], g["Kp"], g["Vp"], Kh, Vh, ws)
+        sync()
+        assert torch.equal(bits(Kh), bits(g["Khat"])) and torch.equal(bits(Vh), bits(g["Vhat"]))
+        QH = 2 * H
+        q = synth.random_queries(1, QH, 128, seed=7, dtype=dtype, device="cuda")
+        scores = torch.empty(1, QH, T, dtype=torch.float32, device="cuda")
+        B.aquakv_decode_attn_scores(lg, 1, T, QH, g["k_codes"], g["k_scales"], g["Kp"], q, 1.0, scores, None, ws)
+        sync()
+        k64 = np.repeat(U.np64(g["Khat"]), 2, axis=1)
+        want = np.einsum("qd,tqd->qt", U.np64(q)[0], k64)
+        mag = np.einsum("qd,tqd->qt", np.abs(U.np64(q)[0]), np.abs(k64))
+        assert np.all(np.abs(U.np64(scores)[0] - want) <= U.RTOL[dtype] * mag + 1e-30)
+
+
 def test_encode_without_optional_outputs_matches(B):
     """Khat / Vhat may be NULL: codes and scales must not change."""
     print("case optional outputs", flush=True)
