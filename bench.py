@@ -54,13 +54,15 @@ def parse():
     ap.add_argument("--no-kernel-events", action="store_true", help="skip the instrumented replay")
     ap.add_argument("--cpu-rows", type=int, default=8192, help="token rows of the oracle sample")
     ap.add_argument("--cpu-layers", type=int, default=4, help="predicted layers of the oracle sample")
-    ap.add_argument("--scores-form", default="folded", choices=["folded", "recompute"],
-                    help="folded: key predictor folded into the query (needs the scores workspace); recompute: "
-                         "prediction recomputed in the scoring kernel")
+    ap.add_argument("--scores-form", default="sweep", choices=["sweep", "folded", "recompute"],
+                    help="sweep: the scores come out of the decode sweep (aquakv_decode_attn_scores with Khat_out is the "
+                         "key half of decode, aquakv_decode_values the value half); folded / recompute: a scoring "
+                         "call of its own per layer after the decode sweep, with the key predictor folded into the "
+                         "query or recomputed in the scoring kernel (the decode-read configuration has no sweep form)")
     ap.add_argument("--streams", type=int, default=1, choices=[1, 2],
                     help="2: the key chain and the value chain of the layer stack on two streams (aquakv_encode_keys / "
                          "_values, aquakv_decode_layer keys-only / aquakv_decode_values, an event per layer), so that the "
-                         "kernels of neighbouring layers overlap (measured: about 1 % faster); 1: the layer-level calls on one stream")
+                         "kernels of neighbouring layers overlap (measured: about 1 %% faster); 1: the layer-level calls on one stream")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device copy (a known-size dispatch to scale rocprofv3 --pmc byte counters)")
     return ap.parse_args()
@@ -132,7 +134,23 @@ class Buffers:
             self.ws_scores = torch.empty(16, dtype=torch.uint8, device=device)
 
 
-def run_step(B, layers, Ks, Vs, buf, q, T, q_heads):
+SCORE_SCALE = 0.088388          # 1 / sqrt(128)
+
+
+def decode_sweep_with_scores(B, layers, buf, q, T, q_heads):
+    """Decode of every layer with the scores as a by-product: the scoring call with Khat_out is the key half of
+    Alg. "decode" (same kernel as decode, the q . k dot products added to its epilogue), aquakv_decode_values the
+    value half.  Outputs: Khat, Vhat and scores of every layer, as from decode_layer + a scoring call."""
+    prev = (None, None)
+    for l, lay in enumerate(layers):
+        (kc, ks), (vc, vs) = buf.codes[l]
+        Kh, Vh = buf.hat[l & 1]
+        B.aquakv_decode_attn_scores(lay, 1, T, q_heads, kc, ks, prev[0], q, SCORE_SCALE, buf.scores, Kh, buf.ws)
+        B.aquakv_decode_values(lay, T, vc, vs, prev[1], Kh, Vh, buf.ws)
+        prev = (Kh, Vh)
+
+
+def run_step(B, layers, Ks, Vs, buf, q, T, q_heads, scores_in_sweep=True):
     """encode all layers, decode all layers, score all layers (layer-level entry points)."""
     prev = (None, None)
     for l, lay in enumerate(layers):
@@ -140,6 +158,9 @@ def run_step(B, layers, Ks, Vs, buf, q, T, q_heads):
         Kh, Vh = buf.hat[l & 1]
         B.aquakv_encode_layer(lay, T, Ks[l], Vs[l], prev[0], prev[1], kc, ks, vc, vs, Kh, Vh, buf.ws)
         prev = (Kh, Vh)
+    if scores_in_sweep:
+        decode_sweep_with_scores(B, layers, buf, q, T, q_heads)
+        return
     prev = (None, None)
     for l, lay in enumerate(layers):
         (kc, ks), (vc, vs) = buf.codes[l]
@@ -151,7 +172,7 @@ def run_step(B, layers, Ks, Vs, buf, q, T, q_heads):
     for l, lay in enumerate(layers):
         (kc, ks), _ = buf.codes[l]
         kp = None if l == 0 else buf.hat[(l - 1) & 1][0]
-        B.aquakv_decode_attn_scores(lay, 1, T, q_heads, kc, ks, kp, q, 0.088388, buf.scores, None, buf.ws_scores)
+        B.aquakv_decode_attn_scores(lay, 1, T, q_heads, kc, ks, kp, q, SCORE_SCALE, buf.scores, None, buf.ws_scores)
 
 
 def chains_on_two_streams(B, layers, Ks, Vs, buf, T, phase):
@@ -185,26 +206,31 @@ def chains_on_two_streams(B, layers, Ks, Vs, buf, T, phase):
     cur.wait_stream(sv)
 
 
-def run_step_two_streams(B, layers, Ks, Vs, buf, q, T, q_heads):
-    """The same work as run_step, key and value chains of the encode and decode sweeps on two streams."""
+def run_step_two_streams(B, layers, Ks, Vs, buf, q, T, q_heads, scores_in_sweep=False):
+    """The same work as run_step (scores by calls of their own), key and value chains of the encode and decode
+    sweeps on two streams."""
     chains_on_two_streams(B, layers, Ks, Vs, buf, T, "encode")
     chains_on_two_streams(B, layers, Ks, Vs, buf, T, "decode")
     for l, lay in enumerate(layers):
         (kc, ks), _ = buf.codes[l]
         kp = None if l == 0 else buf.hat4[(l - 1) & 3][0]
-        B.aquakv_decode_attn_scores(lay, 1, T, q_heads, kc, ks, kp, q, 0.088388, buf.scores, None, buf.ws_scores)
+        B.aquakv_decode_attn_scores(lay, 1, T, q_heads, kc, ks, kp, q, SCORE_SCALE, buf.scores, None, buf.ws_scores)
 
 
-def timed_phases(B, layers, Ks, Vs, buf, q, T, q_heads, reps, streams=1):
-    """Per-phase GPU time (ms per step) from stream events: encode / decode / scores."""
+def timed_phases(B, layers, Ks, Vs, buf, q, T, q_heads, reps, streams=1, scores_in_sweep=False):
+    """Per-phase GPU time (ms per step) from stream events: encode / decode / scores (scoring calls of their own),
+    and decode+scores (the decode sweep that also yields the scores) when that is the step's form."""
     import torch
     ev = lambda: torch.cuda.Event(enable_timing=True)
     out = {}
-    for phase in ("encode", "decode", "scores"):
+    for phase in ("encode", "decode", "scores") + (("decode+scores",) if scores_in_sweep else ()):
         a, b = ev(), ev()
         torch.cuda.synchronize()
         a.record()
         for _ in range(reps):
+            if phase == "decode+scores":
+                decode_sweep_with_scores(B, layers, buf, q, T, q_heads)
+                continue
             if streams == 2 and phase != "scores":
                 chains_on_two_streams(B, layers, Ks, Vs, buf, T, phase)      # joined into the current stream
                 continue
@@ -218,7 +244,7 @@ def timed_phases(B, layers, Ks, Vs, buf, q, T, q_heads, reps, streams=1):
                     B.aquakv_decode_layer(lay, T, kc, ks, vc, vs, prev[0], prev[1], Kh, Vh, buf.ws)
                 else:
                     kp = None if l == 0 else buf.hat[(l - 1) & 1][0]
-                    B.aquakv_decode_attn_scores(lay, 1, T, q_heads, kc, ks, kp, q, 0.088388, buf.scores, None, buf.ws_scores)
+                    B.aquakv_decode_attn_scores(lay, 1, T, q_heads, kc, ks, kp, q, SCORE_SCALE, buf.scores, None, buf.ws_scores)
                 prev = (Kh, Vh)
         b.record()
         torch.cuda.synchronize()
@@ -366,7 +392,7 @@ def decode_read_path(args, device):
         del K, V, vc, vs
     q = synth.random_queries(batch, q_heads, 128, seed=1, dtype="bf16", device=device)
     scores = torch.empty(batch, q_heads, S, dtype=torch.float32, device=device)
-    folded = args.scores_form == "folded" and B.aquakv_scores_workspace_bytes(layers[-1], batch, q_heads) > 0
+    folded = args.scores_form != "recompute" and B.aquakv_scores_workspace_bytes(layers[-1], batch, q_heads) > 0
     ws_scores = layers[-1].alloc_scores_workspace(batch, q_heads, device) if folded else torch.empty(16, dtype=torch.uint8, device=device)
     app = [(layers[0].alloc_codes(batch, device), layers[0].alloc_codes(batch, device), layers[0].alloc_kv(batch, device),
             layers[0].alloc_kv(batch, device))]
@@ -421,7 +447,7 @@ def decode_read_path(args, device):
         "ms_per_step": round(1e3 * dt, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"decode-read: {L} layers x {batch} sequences x {S} cached tokens x 8 kv heads x 128, bf16, "
-                               f"n={n}, step = q.k scores ({q_heads} query heads, {args.scores_form} form) over the whole "
+                               f"n={n}, step = q.k scores ({q_heads} query heads, {'folded' if folded else 'recompute'} form) over the whole "
                                f"cache + append of one token per sequence, for every layer",
                    "tokens": T, "layers": L, "q_heads": q_heads, "batch": batch, "seq_len": S},
         "phases_ms_per_step": {k: round(v, 3) for k, v in phases.items()},
@@ -477,7 +503,9 @@ def main():
         grid_label += f", rotation groups of {args.rht_group} (one scale per token)"
     quantizer_label = (f"uniform round-to-nearest with {1 << args.rtn_bits} levels, groups of 64" if args.rtn_bits
                        else f"{grid_label} codewords (p=2)")
-    buf = Buffers(layers, T, q_heads, device, args.scores_form)
+    # the two-stream schedule keeps scoring calls of their own (folded where the form exists)
+    sweep = args.scores_form == "sweep" and args.streams == 1
+    buf = Buffers(layers, T, q_heads, device, "folded" if args.scores_form == "sweep" else args.scores_form)
     q = synth.random_queries(1, q_heads, cfg.head_dim, seed=1, dtype=cfg.dtype, device=device)
 
     if args.calibrate_copy:
@@ -489,17 +517,17 @@ def main():
         del src, dst
     step = run_step_two_streams if args.streams == 2 else run_step
     for _ in range(args.warmup):
-        step(B, layers, Ks, Vs, buf, q, T, q_heads)
+        step(B, layers, Ks, Vs, buf, q, T, q_heads, sweep)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step(B, layers, Ks, Vs, buf, q, T, q_heads)
+        step(B, layers, Ks, Vs, buf, q, T, q_heads, sweep)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = 1e3 * dt / args.steps
     value = T * cfg.layers / (dt / args.steps)
 
-    phases = timed_phases(B, layers, Ks, Vs, buf, q, T, q_heads, max(1, min(args.steps, 5)), args.streams)
+    phases = timed_phases(B, layers, Ks, Vs, buf, q, T, q_heads, max(1, min(args.steps, 5)), args.streams, sweep)
     l0 = layer0_times(B, layers, Ks, Vs, buf, T, 5)
     eb = 2 if cfg.dtype == "bf16" else 4
     D = cfg.kv_heads * cfg.head_dim
@@ -533,8 +561,13 @@ def main():
         "config": {"workload": f"{cfg.name}: {cfg.layers} layers x {T} tokens x {cfg.kv_heads} kv heads x {cfg.head_dim}, "
                                f"{cfg.dtype}, {quantizer_label}, step = encode + decode + q.k scores "
                                f"({q_heads} query heads) of every layer"
+                               + (", the scores produced by the decode sweep (scoring call with Khat_out = key half of "
+                                  "decode, then the value half)" if sweep else ", scoring calls of their own after the decode sweep")
                                + (", key and value chains of the sweeps on two streams" if args.streams == 2 else ""),
-                   "tokens": T, "layers": cfg.layers, "q_heads": q_heads, "streams": args.streams},
+                   "tokens": T, "layers": cfg.layers, "q_heads": q_heads, "streams": args.streams,
+                   "scores": "decode sweep" if sweep else "own calls"},
+        # a step is encode + decode+scores when the scores come out of the decode sweep, else encode + decode + scores;
+        # the other entries are the same phases measured apart, for reference
         "phases_ms_per_step": {k: round(v, 3) for k, v in phases.items()},
         "tokens_per_s_per_layer": {k: round(T * cfg.layers / (v * 1e-3), 1) for k, v in phases.items()},
         # encode + decode combined, T / (t_enc + t_dec) per layer: predicted layers (average) and layer 0 apart
