@@ -679,6 +679,21 @@ def test_full_size_layers_on_sampled_rows(B, name, T, n_per_layer):
         B.aquakv_decode_layer(lg, T, kc, ks, vc, vs, Kp, Vp, Kd, Vd, ws)
         sync()
         assert torch.equal(bits(Kd), bits(Kh)) and torch.equal(bits(Vd), bits(Vh))
+        # the decode sweep in the form bench.py times: the scoring call with Khat_out is the key half of decode,
+        # aquakv_decode_values the value half; same bits, and the scores are q . Khat on the sampled rows
+        QH = 64 if T == 131072 else 24
+        q = synth.random_queries(1, QH, 128, seed=9 + l, dtype="bf16", device="cuda")
+        scores = torch.empty(1, QH, T, dtype=torch.float32, device="cuda")
+        Kd2, Vd2 = lg.alloc_kv(T), lg.alloc_kv(T)
+        B.aquakv_decode_attn_scores(lg, 1, T, QH, kc, ks, Kp, q, 0.088388, scores, Kd2, ws)
+        B.aquakv_decode_values(lg, T, vc, vs, Vp, Kd2, Vd2, ws)
+        sync()
+        assert torch.equal(bits(Kd2), bits(Kh)) and torch.equal(bits(Vd2), bits(Vh))
+        k64 = np.repeat(U.np64(Kh[rows]), QH // 8, axis=1)                       # [rows, QH, 128]
+        want = 0.088388 * np.einsum("qd,tqd->qt", U.np64(q)[0], k64)
+        mag = 0.088388 * np.einsum("qd,tqd->qt", np.abs(U.np64(q)[0]), np.abs(k64))
+        got = U.np64(scores[0][:, rows])
+        assert np.all(np.abs(got - want) <= U.RTOL["bf16"] * mag + 1e-30), float(np.max(np.abs(got - want) / (mag + 1e-30)))
         # properties that hold at any size: every scale is a finite non-negative fp16, the relative
         # reconstruction error of the whole tensor is what the grid and the predictor allow
         s = ks.view(torch.float16).float()
