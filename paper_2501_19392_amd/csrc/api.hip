@@ -479,6 +479,34 @@ int aquakv_decode_values(const aquakv_layer* L, int64_t tokens, const uint8_t* v
   return AQUAKV_OK;
 }
 
+// ---- calibration: ridge least-squares fit of one predictor (Alg. "Calibration") --------------------------------
+size_t aquakv_fit_workspace_bytes(int32_t d_in, int32_t d_out) {
+  if (d_in < 64 || d_in > 8192 || d_in % 64 || d_out < 64 || d_out > 8192 || d_out % 64) return 0;
+  return aquakv::fit_workspace_bytes(d_in, d_out);
+}
+
+int aquakv_fit_predictor(int32_t dtype, int64_t tokens, const void* x0, int32_t d0, const void* x1, int32_t d1,
+                         const void* Y, int32_t d_out, double rate, void* W, double* W64, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+  if (dtype != AQUAKV_BF16 && dtype != AQUAKV_FP32) return fail(AQUAKV_EINVAL, "dtype=%d", dtype);
+  if (tokens < 1) return fail(AQUAKV_EINVAL, "tokens=%lld: at least one row is needed", (long long)tokens);
+  if (d0 < 64 || d0 % 64 || d1 < 0 || d1 % 64) return fail(AQUAKV_EINVAL, "d0=%d d1=%d must be multiples of 64, d0 >= 64", d0, d1);
+  if (d_out < 64 || d_out % 64) return fail(AQUAKV_EINVAL, "d_out=%d must be a positive multiple of 64", d_out);
+  if ((int64_t)d0 + d1 > 8192 || d_out > 8192) return fail(AQUAKV_EUNSUPPORTED, "at most 8192 inputs and outputs");
+  if (!(rate >= 0.0) || rate > 1e6) return fail(AQUAKV_EINVAL, "rate=%g", rate);
+  CHECK(check_ptr(x0, "x0", true));
+  CHECK(check_ptr(x1, "x1", d1 != 0));
+  CHECK(check_ptr(Y, "Y", true));
+  CHECK(check_ptr(W, "W", true));
+  CHECK(check_ptr(W64, "W64", false));
+  CHECK(check_ptr(workspace, "workspace", true));
+  const size_t need = aquakv::fit_workspace_bytes(d0 + d1, d_out);
+  if (workspace_bytes < need) return fail(AQUAKV_EWORKSPACE, "workspace %zu B < required %zu B", workspace_bytes, need);
+  HIP_TRY(aquakv::launch_fit_predictor(dtype, tokens, x0, d0, d1 != 0 ? x1 : nullptr, d1, Y, d_out, rate, W, W64, workspace,
+                                       static_cast<hipStream_t>(stream)));
+  return AQUAKV_OK;
+}
+
 size_t aquakv_scores_workspace_bytes(const aquakv_layer* L, int32_t batch, int32_t q_heads) {
   if (check_layer(L) != AQUAKV_OK || batch < 1 || q_heads < 1) return 0;
   if (L->dtype != AQUAKV_BF16 || is_wide(L) || is_rtn(L) || !aquakv::folded_scores_supported(L->kv_heads, L->d_in_k, q_heads)) return 0;

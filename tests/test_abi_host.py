@@ -180,3 +180,21 @@ def test_round_to_nearest_backbone_layer_validation():
     bad[0] = None
     assert status_of(B.aquakv_encode_layer, L, 8, *bad, ws) == B.AQUAKV_ENULL   # alignment passed, K is missing
     B.aquakv_encode_layer(L, 0, *ENC_OK, None)
+
+
+def test_fit_predictor_validates_its_arguments():
+    assert B.aquakv_fit_workspace_bytes(1024, 1024) == (1024 * 1024 * 2) * 8 + 16
+    assert B.aquakv_fit_workspace_bytes(2048, 1024) == (2048 * 2048 + 2048 * 1024) * 8 + 16
+    assert B.aquakv_fit_workspace_bytes(100, 1024) == 0 and B.aquakv_fit_workspace_bytes(1024, 16384) == 0
+    ws = (FAKE, 1 << 40)
+    ok = dict(dtype=B.AQUAKV_BF16, tokens=100, x0=FAKE, d0=1024, x1=FAKE, d1=1024, Y=FAKE, d_out=1024, rate=1e-3, W=FAKE, W64=None)
+    call = lambda **kw: status_of(lambda: B.aquakv_fit_predictor(*{**ok, **kw}.values(), ws))
+    assert call(dtype=5) == B.AQUAKV_EINVAL
+    assert call(tokens=0) == B.AQUAKV_EINVAL
+    assert call(d0=1000) == B.AQUAKV_EINVAL and call(d1=32) == B.AQUAKV_EINVAL and call(d_out=0) == B.AQUAKV_EINVAL
+    assert call(d0=8192, d1=64) == B.AQUAKV_EUNSUPPORTED
+    assert call(rate=-1.0) == B.AQUAKV_EINVAL and call(rate=float("nan")) == B.AQUAKV_EINVAL
+    assert call(x0=None) == B.AQUAKV_ENULL and call(x1=None) == B.AQUAKV_ENULL and call(W=None) == B.AQUAKV_ENULL
+    assert call(Y=FAKE + 8) == B.AQUAKV_EALIGN
+    assert status_of(lambda: B.aquakv_fit_predictor(*ok.values(), (FAKE, 100))) == B.AQUAKV_EWORKSPACE
+    assert status_of(lambda: B.aquakv_fit_predictor(*{**ok, "x1": None, "d1": 0}.values(), None)) == B.AQUAKV_ENULL   # x1 optional, workspace not
