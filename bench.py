@@ -39,9 +39,11 @@ def parse():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", default="llama3.2-3b",
-                    choices=["llama3.2-3b", "llama3.1-8b", "llama3.1-70b", "decode-read", "tiny"],
+                    choices=["llama3.2-3b", "llama3.1-8b", "llama3.1-70b", "decode-read", "calibrate", "tiny"],
                     help="llama3.1-70b: 80 layers x 131072 tokens, grid of 16 or 64 points per layer (seeded coin); "
-                         "decode-read: 64 sequences x 16384 cached tokens, scoring call + one-token append per layer")
+                         "decode-read: 64 sequences x 16384 cached tokens, scoring call + one-token append per layer; "
+                         "calibrate: fitting the predictors of --layers layers (default 4) on --calib-tokens tokens")
+    ap.add_argument("--calib-tokens", type=int, default=262144, help="tokens of the calibration set (--config calibrate)")
     ap.add_argument("--rht-group", type=int, default=0, choices=[0, 128, 1024],
                     help="values per rotation group and scale: 128 (one head, default) or 1024 (the whole token, the "
                          "grouping of the paper's experiments; predictor and quantizer then run as separate kernels)")
@@ -348,6 +350,68 @@ def cpu_baseline(cfg, n_codewords, rows, q_heads, n_layers, rtn_bits=0):
                       f"({dt:.1f} s of CPU time; cost is linear in rows and layers)"}
 
 
+PEAK_FP64_TFLOPS = 78.6          # MI355X fp64 vector
+
+
+def calibration_path(args, device):
+    """Calibration of the predictors (Alg. "Calibration") on the Llama-3.2-3B KV shape: a step = for every predicted
+    layer fit f_key, encode the keys, fit f_value, encode the values (paper_2501_19392_amd.calibrate).  Reported
+    per layer; the roofline entry is the fit call (fp64 FMA arithmetic; FLOPs of the two Gram products, the
+    factorisation and the solves)."""
+    import torch
+    from paper_2501_19392_amd import binding as B
+    from paper_2501_19392_amd import synth
+    from paper_2501_19392_amd.calibrate import calibrate
+    T, L, n = args.calib_tokens, (args.layers or 4) + 1, args.n_codewords
+    cfg = synth.Config("llama3.2-3b-kv calibration", layers=L, kv_heads=8, head_dim=128, tokens=T, dtype="bf16")
+    st = synth.KVStream(cfg, device=device, work=torch.float32)
+    kv = [st.next() for _ in range(L)]
+    C, table = grids_on_device([n], device)[n]
+    signs = [(torch.from_numpy(synth.rht_signs(8, 128, l, "k")).to(device), torch.from_numpy(synth.rht_signs(8, 128, l, "v")).to(device))
+             for l in range(L)]
+    make_layer = lambda l, w_k=None, w_v=None: B.Layer(8, 128, C, signs[l][0], signs[l][1], torch.bfloat16, w_k=w_k, w_v=w_v,
+                                                       search_table=table)
+    run = lambda: calibrate(make_layer, L, lambda l: kv[l], rate=1e-3, device=device)
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        layers = run()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    # the fit call alone (value predictor: 2048 inputs), events on the launch stream
+    D = 1024
+    ws = torch.empty(B.aquakv_fit_workspace_bytes(2 * D, D), dtype=torch.uint8, device=device)
+    W = torch.empty(D, 2 * D, dtype=torch.bfloat16, device=device)
+    x0, x1, Y = kv[0][1], kv[1][0], kv[1][1]
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    B.aquakv_fit_predictor(torch.bfloat16, T, x0, D, x1, D, Y, D, 1e-3, W, None, ws)
+    torch.cuda.synchronize()
+    reps = 3
+    a.record()
+    for _ in range(reps):
+        B.aquakv_fit_predictor(torch.bfloat16, T, x0, D, x1, D, Y, D, 1e-3, W, None, ws)
+    b.record()
+    torch.cuda.synchronize()
+    fit_ms = a.elapsed_time(b) / reps
+    d = 2 * D
+    flops = 2.0 * T * (d * (d + 64) / 2 + d * D) + d ** 3 / 3.0 + 2.0 * d * d * D    # Gram products (G: lower triangle of 64-tiles), Cholesky, two solves
+    achieved = flops / (fit_ms * 1e-3) / 1e12
+    return {
+        "metric": "predictor calibration, calibration tokens/s per layer", "value": round(T / (dt / (L - 1)), 1),
+        "unit": "tokens/s per layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(1e3 * dt, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64", "data": "synthetic",
+        "config": {"workload": f"calibration of {L - 1} predicted layers of the llama3.2-3b KV shape (8 kv heads x 128, bf16, "
+                               f"n={n}) on {T} tokens: per layer key fit (1024 inputs), key encode, value fit (2048 inputs), "
+                               f"value encode", "tokens": T, "layers": L - 1},
+        "roofline": {"kernel": "aquakv_fit_predictor, value predictor (gram_kernel and the block factorisation / solve kernels)",
+                     "bound": "alu", "achieved": round(achieved, 2), "peak": PEAK_FP64_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / PEAK_FP64_TFLOPS, 4), "traffic": None, "fit_ms": round(fit_ms, 3)},
+    }
+
+
 def decode_read_path(args, device):
     """The decode-phase read path: 64 sequences x 16384 cached tokens per layer, 32 query heads on 8 kv heads.
     A step = for every layer the scoring call over the whole compressed cache (aquakv_decode_attn_scores, one new
@@ -474,6 +538,9 @@ def main():
     torch.cuda.set_device(0)
     if args.config == "decode-read":
         print(json.dumps(decode_read_path(args, device)))
+        return
+    if args.config == "calibrate":
+        print(json.dumps(calibration_path(args, device)))
         return
     cfg = {"llama3.2-3b": synth.LLAMA32_3B, "llama3.1-8b": synth.LLAMA31_8B, "llama3.1-70b": synth.LLAMA31_70B,
            "tiny": synth.TINY}[args.config]

@@ -4,11 +4,11 @@
 // L Z = C, L^T S = Z, W = S^T rounded to the storage dtype.
 //
 // Everything is tiled in 64 x 64 blocks of doubles.  The two Gram products stream the tokens once per output tile
-// (tokens in ascending order in one accumulator per output: the result does not depend on the launch shape); the
-// factorisation and the two triangular solves are right-looking block algorithms, one small launch per block
-// step and kind (diagonal block / panel / trailing update), so that the trailing updates use the whole chip.
-// Plain fp64 FMA arithmetic: calibration runs once per model, its cost is the Gram products, and fp64 keeps the
-// solution within rounding of the definition.
+// (tokens in ascending order in one accumulator per output: the result does not depend on the launch shape) on the
+// fp64 matrix cores; the factorisation and the two triangular solves are right-looking block algorithms in plain
+// fp64 FMA arithmetic, one small launch per block step and kind (diagonal block / panel / trailing update), so
+// that the trailing updates use the whole chip.  Calibration runs once per model, its cost is the Gram products,
+// and fp64 keeps the solution within rounding of the definition.
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -18,12 +18,23 @@ namespace {
 constexpr int kNb = 64;                      // block size of every tile
 constexpr int kFitThreads = 256;             // 16 x 16 threads, 4 x 4 outputs each
 
-template <typename T> __device__ __forceinline__ double to_double(T v);
-template <> __device__ __forceinline__ double to_double<float>(float v) { return (double)v; }
-template <> __device__ __forceinline__ double to_double<bf16_t>(bf16_t v) { return (double)static_cast<float>(v); }
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
+// 8 consecutive storage elements (16-byte aligned) -> doubles
+__device__ __forceinline__ void load8(const float* p, double (&v)[8]) {
+  const f32x4 a = reinterpret_cast<const f32x4*>(p)[0], b = reinterpret_cast<const f32x4*>(p)[1];
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ __forceinline__ void load8(const bf16_t* p, double (&v)[8]) {
+  float f[8];
+  unpack_bf16x8(*reinterpret_cast<const u32x4*>(p), f);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = f[e];
+}
 
 // ------------------------------------------------------------------ Gram products
-// blockIdx.x = tile index: tiles [0, nd * nd) are G(i, j) = sum_t X[t, 64 i ...] X[t, 64 j ...], the following
+// blockIdx.x = tile index: the first nd (nd + 1) / 2 tiles are the lower triangle of the symmetric
+// G(i, j) = sum_t X[t, 64 i ...] X[t, 64 j ...], j <= i (the tile is also stored mirrored at (j, i)), the following
 // nd * no tiles are C(i, j) = sum_t X[t, 64 i ...] Y[t, 64 j ...].  X is the concatenation [x0 | x1]; d0 is a
 // multiple of 64, so a tile's 64 columns come from one of the two.
 template <typename T>
@@ -31,13 +42,22 @@ __global__ __launch_bounds__(kFitThreads) void gram_kernel(const T* __restrict__
                                                            int d1, const T* __restrict__ Y, int d_out, int64_t tokens,
                                                            double* __restrict__ G, double* __restrict__ C) {
   constexpr int kChunk = 32;                 // tokens per LDS chunk
-  __shared__ double As[kChunk][kNb + 1], Bs[kChunk][kNb + 1];
+  // rows 80 doubles apart: the 4 token rows a fragment read touches start 32 banks apart
+  __shared__ double As[kChunk][kNb + 16], Bs[kChunk][kNb + 16];
   const int d_in = d0 + d1;
   const int nd = d_in / kNb, no = d_out / kNb;
   int tile = blockIdx.x;
-  const bool is_c = tile >= nd * nd;
-  if (is_c) tile -= nd * nd;
-  const int ti = is_c ? tile / no : tile / nd, tj = is_c ? tile % no : tile % nd;
+  const int n_sym = nd * (nd + 1) / 2;
+  const bool is_c = tile >= n_sym;
+  int ti, tj;
+  if (is_c) {
+    tile -= n_sym;
+    ti = tile / no; tj = tile % no;
+  } else {
+    ti = 0;
+    while (tile > ti) { tile -= ti + 1; ++ti; }          // row ti of the triangle holds ti + 1 tiles
+    tj = tile;
+  }
   // column sources of the two operands
   const int ca = ti * kNb;
   const T* pa = ca < d0 ? x0 + ca : x1 + (ca - d0);
@@ -51,38 +71,56 @@ __global__ __launch_bounds__(kFitThreads) void gram_kernel(const T* __restrict__
     pb = cb < d0 ? x0 + cb : x1 + (cb - d0);
     ldb = cb < d0 ? d0 : d1;
   }
-  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;      // outputs rows 4 ty ..., columns 4 tx ...
-  double acc[4][4] = {};
+  // fp64 matrix cores (v_mfma_f64_16x16x4_f64: D[16 x 16] += A[16 x 4] B[4 x 16], lane l holds A[l % 16][l / 16] and
+  // B[l / 16][l % 16], i.e. one double each, and D[4 v + l / 16][l % 16] in register v).  With the tokens as the
+  // contracted index both operands are read from the token-major LDS chunk as they lie.  Wave w owns the 32 x 32
+  // quarter at rows 32 (w / 2), columns 32 (w % 2) of the tile: 2 x 2 blocks.
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int fr = lane & 15, fk = lane >> 4;
+  const int ra = 32 * (wave >> 1), cbq = 32 * (wave & 1);
+  f64x4 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = f64x4{0.0, 0.0, 0.0, 0.0};
   for (int64_t t0 = 0; t0 < tokens; t0 += kChunk) {
     // 32 tokens x 64 columns per operand: 8 elements per thread, a thread reads 8 consecutive columns of one token
     {
       const int r = threadIdx.x >> 3, c8 = (threadIdx.x & 7) * 8;
       const int64_t t = t0 + r;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        As[r][c8 + e] = t < tokens ? to_double(pa[t * lda + c8 + e]) : 0.0;
-        Bs[r][c8 + e] = t < tokens ? to_double(pb[t * ldb + c8 + e]) : 0.0;
+      double va[8] = {}, vb[8] = {};
+      if (t < tokens) {
+        load8(pa + t * lda + c8, va);
+        load8(pb + t * ldb + c8, vb);
       }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { As[r][c8 + e] = va[e]; Bs[r][c8 + e] = vb[e]; }
     }
     __syncthreads();
-#pragma unroll 4
-    for (int k = 0; k < kChunk; ++k) {
-      double a[4], b[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) { a[i] = As[k][4 * ty + i]; b[i] = Bs[k][4 * tx + i]; }
+    for (int k0 = 0; k0 < kChunk; k0 += 4) {
+      double a[2], b[2];
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < 2; ++i) { a[i] = As[k0 + fk][ra + 16 * i + fr]; b[i] = Bs[k0 + fk][cbq + 16 * i + fr]; }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = __fma_rn(a[i], b[j], acc[i][j]);
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
     }
     __syncthreads();
   }
   double* out = is_c ? C : G;
   const int ldo = is_c ? d_out : d_in;
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) out[(int64_t)(ti * kNb + 4 * ty + i) * ldo + tj * kNb + 4 * tx + j] = acc[i][j];
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int row = ti * kNb + ra + 16 * i + 4 * v + fk, col = tj * kNb + cbq + 16 * j + fr;
+        out[(int64_t)row * ldo + col] = acc[i][j][v];
+        if (!is_c && ti != tj) out[(int64_t)col * ldo + row] = acc[i][j][v];
+      }
 }
 
 // G[i][i] += rate * trace(G) / d (one block; the trace is summed in a fixed order); clears the status word
@@ -274,7 +312,7 @@ hipError_t launch_fit_predictor(int dtype, int64_t tokens, const void* x0, int d
   double* G = static_cast<double*>(workspace);
   double* C = G + (size_t)d * d;
   int* status = reinterpret_cast<int*>(C + (size_t)d * d_out);
-  const unsigned tiles = (unsigned)(nb * nb + nb * nr);
+  const unsigned tiles = (unsigned)(nb * (nb + 1) / 2 + nb * nr);
   if (dtype == kBF16)
     gram_kernel<bf16_t><<<tiles, kFitThreads, 0, stream>>>(static_cast<const bf16_t*>(x0), d0, static_cast<const bf16_t*>(x1),
                                                            d1, static_cast<const bf16_t*>(Y), d_out, tokens, G, C);
