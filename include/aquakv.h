@@ -263,15 +263,17 @@ int aquakv_decode_attn_scores_rope(const aquakv_layer* layer, int32_t batch, int
  * `dtype`.  x0 [tokens, d0], x1 [tokens, d1] (NULL iff d1 = 0), Y [tokens, d_out], all `dtype`, row-major;
  * d0, d1, d_out multiples of 64, at most 8192 inputs / outputs.  W [d_out, d0 + d1] out: the layout of
  * aquakv_layer.w_k / w_v (key predictor: x0 = Khat_prev, Y = K; value predictor: x0 = Vhat_prev, x1 = Khat, Y = V).
- * W64 (nullable) receives the unrounded fp64 solution in the same layout.  If the matrix X^T X + lambda I is not
- * positive definite in fp64, W (and W64) are filled with NaN.  `workspace`: aquakv_fit_workspace_bytes(d0 + d1, d_out)
+ * W64 (nullable) receives the unrounded fp64 solution in the same layout.  bias (nullable, fp32 [d_out], the layout
+ * of aquakv_layer.b_k / b_v): if given, an intercept is fitted as well, X W^T + b: the regression of the centred Y
+ * on the centred X (lambda acts on W only, with the trace of the centred X^T X), b = mean(Y) - W mean(X).  If the
+ * matrix X^T X + lambda I is not positive definite in fp64, W (and W64, bias) are filled with NaN.  `workspace`: aquakv_fit_workspace_bytes(d0 + d1, d_out)
  * bytes (0 for unsupported sizes).  The layer-by-layer procedure of the algorithm (fit the key predictor, encode
  * the keys with it, fit the value predictor on [Vhat_prev | Khat], encode, move on) is made of this call and
  * aquakv_encode_keys / aquakv_encode_values.
  */
 size_t aquakv_fit_workspace_bytes(int32_t d_in, int32_t d_out);
 int aquakv_fit_predictor(int32_t dtype, int64_t tokens, const void* x0, int32_t d0, const void* x1, int32_t d1,
-                         const void* Y, int32_t d_out, double rate, void* W, double* W64,
+                         const void* Y, int32_t d_out, double rate, void* W, double* W64, float* bias,
                          void* workspace, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus

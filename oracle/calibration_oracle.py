@@ -14,7 +14,9 @@ Readings taken where the paper is silent or at odds with itself:
     W = (X^T X + lambda I)^-1 X^T Y, lambda = rate * trace(X^T X) / d_in; rate = 0 is the plain argmin of the
     algorithm (needs X of full column rank).  The appendix quotes a "regularizer rate" of 1e-3 for its linear
     probes without saying relative to what; relative to the mean diagonal of X^T X makes it scale free.
-  * No bias term is fitted (the synthetic workloads have zero-mean channels); layers may still carry one.
+  * The fit has an optional intercept (centred regression; Sect. 4.1 lists a bias-only predictor among its
+    ablations, so the predictors carry a bias).  The layer-by-layer procedure here fits none: the synthetic
+    workloads have zero-mean channels.
   * The weights are rounded to the storage dtype before they are used to encode the layer: it is the rounded
     predictor that inference runs, so the next layer is fitted on what that predictor reconstructs.
   * The first layer: the algorithm's listing hands its raw K, V to the second layer's fit, the text says the
@@ -38,15 +40,22 @@ import numpy as np
 from . import aquakv_oracle as O
 
 
-def fit_predictor(X, Y, rate: float = 1e-3) -> np.ndarray:
+def fit_predictor(X, Y, rate: float = 1e-3, bias: bool = False):
     """Ridge least squares through the normal equations.  X [T, d_in], Y [T, d_out] -> W [d_out, d_in] (fp64),
-    the layout of Layer.w_k / w_v: prediction = X @ W.T."""
+    the layout of Layer.w_k / w_v: prediction = X @ W.T.
+
+    bias = True fits an intercept as well, prediction = X @ W.T + b: the regression of the centred Y on the centred
+    X (the ridge term acts on W only, and on the centred Gram matrix), b = mean(Y) - W mean(X); returns (W, b)."""
     X = np.asarray(X, dtype=np.float64)
     Y = np.asarray(Y, dtype=np.float64)
     d_in = X.shape[1]
+    if bias:
+        mx, my = X.mean(axis=0), Y.mean(axis=0)
+        X, Y = X - mx, Y - my
     G = X.T @ X
     lam = rate * np.trace(G) / d_in
-    return np.linalg.solve(G + lam * np.eye(d_in), X.T @ Y).T
+    W = np.linalg.solve(G + lam * np.eye(d_in), X.T @ Y).T
+    return (W, my - W @ mx) if bias else W
 
 
 def calibrate(layers: Sequence[Optional[O.Layer]], Ks: Sequence[np.ndarray], Vs: Sequence[np.ndarray],

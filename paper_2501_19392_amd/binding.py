@@ -78,7 +78,7 @@ _lib.aquakv_decode_values.argtypes = [_LP, ctypes.c_int64] + [_P] * 6 + [ctypes.
 _lib.aquakv_fit_workspace_bytes.restype = ctypes.c_size_t
 _lib.aquakv_fit_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32]
 _lib.aquakv_fit_predictor.argtypes = [ctypes.c_int32, ctypes.c_int64, _P, ctypes.c_int32, _P, ctypes.c_int32, _P, ctypes.c_int32,
-                                      ctypes.c_double, _P, _P, _P, ctypes.c_size_t, _P]
+                                      ctypes.c_double, _P, _P, _P, _P, ctypes.c_size_t, _P]
 for _n in ("aquakv_predict", "aquakv_quantize", "aquakv_dequantize", "aquakv_encode_layer", "aquakv_decode_layer",
            "aquakv_decode_attn_scores", "aquakv_decode_attn_scores_rope", "aquakv_encode_keys", "aquakv_encode_values",
            "aquakv_decode_values", "aquakv_fit_predictor"):
@@ -301,12 +301,12 @@ def aquakv_fit_workspace_bytes(d_in: int, d_out: int) -> int:
 
 
 def aquakv_fit_predictor(dtype, tokens: int, x0, d0: int, x1, d1: int, Y, d_out: int, rate: float, W, W64, workspace,
-                         stream=None) -> None:
-    """dtype: torch.bfloat16 / torch.float32 (or the C enum value)."""
+                         stream=None, bias=None) -> None:
+    """dtype: torch.bfloat16 / torch.float32 (or the C enum value).  bias: fp32 [d_out] out, fits an intercept too."""
     ws, nbytes = _ws(workspace)
     code = dtype if isinstance(dtype, int) else _dtype_code(dtype)
     _check(_lib.aquakv_fit_predictor(code, tokens, _ptr(x0), d0, _ptr(x1), d1, _ptr(Y), d_out, ctypes.c_double(rate),
-                                     _ptr(W), _ptr(W64), ws, nbytes, _stream(stream)))
+                                     _ptr(W), _ptr(W64), _ptr(bias), ws, nbytes, _stream(stream)))
 
 
 def aquakv_decode_attn_scores_rope(layer, batch: int, seq_len: int, q_heads: int, k_codes, k_scales, Khat_prev, q,

@@ -486,7 +486,7 @@ size_t aquakv_fit_workspace_bytes(int32_t d_in, int32_t d_out) {
 }
 
 int aquakv_fit_predictor(int32_t dtype, int64_t tokens, const void* x0, int32_t d0, const void* x1, int32_t d1,
-                         const void* Y, int32_t d_out, double rate, void* W, double* W64, void* workspace,
+                         const void* Y, int32_t d_out, double rate, void* W, double* W64, float* bias, void* workspace,
                          size_t workspace_bytes, void* stream) {
   if (dtype != AQUAKV_BF16 && dtype != AQUAKV_FP32) return fail(AQUAKV_EINVAL, "dtype=%d", dtype);
   if (tokens < 1) return fail(AQUAKV_EINVAL, "tokens=%lld: at least one row is needed", (long long)tokens);
@@ -499,10 +499,11 @@ int aquakv_fit_predictor(int32_t dtype, int64_t tokens, const void* x0, int32_t 
   CHECK(check_ptr(Y, "Y", true));
   CHECK(check_ptr(W, "W", true));
   CHECK(check_ptr(W64, "W64", false));
+  CHECK(check_ptr(bias, "bias", false));
   CHECK(check_ptr(workspace, "workspace", true));
   const size_t need = aquakv::fit_workspace_bytes(d0 + d1, d_out);
   if (workspace_bytes < need) return fail(AQUAKV_EWORKSPACE, "workspace %zu B < required %zu B", workspace_bytes, need);
-  HIP_TRY(aquakv::launch_fit_predictor(dtype, tokens, x0, d0, d1 != 0 ? x1 : nullptr, d1, Y, d_out, rate, W, W64, workspace,
+  HIP_TRY(aquakv::launch_fit_predictor(dtype, tokens, x0, d0, d1 != 0 ? x1 : nullptr, d1, Y, d_out, rate, W, W64, bias, workspace,
                                        static_cast<hipStream_t>(stream)));
   return AQUAKV_OK;
 }

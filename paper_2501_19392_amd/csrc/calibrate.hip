@@ -1,7 +1,8 @@
 // Least-squares fit of a linear predictor (Alg. "Calibration" of the AQUA-KV paper, Sect. 3.2):
 //   W = argmin || [x0 | x1] W^T - Y ||^2 + lambda ||W||^2,   lambda = rate * trace(X^T X) / d_in,
 // through the normal equations in fp64:  G = X^T X + lambda I,  C = X^T Y,  G = L L^T (Cholesky),
-// L Z = C, L^T S = Z, W = S^T rounded to the storage dtype.
+// L Z = C, L^T S = Z, W = S^T rounded to the storage dtype.  With an intercept, X and Y are centred first (the Gram
+// products of the centred data are those of the raw data minus T mean mean^T) and b = mean(Y) - W mean(X).
 //
 // Everything is tiled in 64 x 64 blocks of doubles.  The two Gram products stream the tokens once per output tile
 // (tokens in ascending order in one accumulator per output: the result does not depend on the launch shape) on the
@@ -121,6 +122,54 @@ __global__ __launch_bounds__(kFitThreads) void gram_kernel(const T* __restrict__
         out[(int64_t)row * ldo + col] = acc[i][j][v];
         if (!is_c && ti != tj) out[(int64_t)col * ldo + row] = acc[i][j][v];
       }
+}
+
+// ------------------------------------------------------------------ intercept (centred regression)
+// Column means of [X | Y]: blockIdx.x = 64-column block (the first d_in / 64 blocks are X, the rest Y); 4 strands of
+// tokens per column, added in a fixed order.
+template <typename T>
+__global__ __launch_bounds__(kFitThreads) void column_mean_kernel(const T* __restrict__ x0, int d0, const T* __restrict__ x1,
+                                                                  int d1, const T* __restrict__ Y, int d_out, int64_t tokens,
+                                                                  double* __restrict__ mean) {
+  __shared__ double part[4][kNb];
+  const int d_in = d0 + d1;
+  const int c0 = blockIdx.x * kNb;
+  const T* p;
+  int ld;
+  if (c0 < d0) { p = x0 + c0; ld = d0; }
+  else if (c0 < d_in) { p = x1 + (c0 - d0); ld = d1; }
+  else { p = Y + (c0 - d_in); ld = d_out; }
+  const int c = threadIdx.x & 63, strand = threadIdx.x >> 6;
+  double s = 0.0;
+  for (int64_t t = strand; t < tokens; t += 4) s += (double)static_cast<float>(p[t * ld + c]);
+  part[strand][c] = s;
+  __syncthreads();
+  if (strand == 0) mean[c0 + c] = (((part[0][c] + part[1][c]) + part[2][c]) + part[3][c]) / (double)tokens;
+}
+
+// G -= T mx mx^T, C -= T mx my^T: the Gram products of the centred data from those of the raw data
+__global__ void centre_kernel(double* __restrict__ G, double* __restrict__ C, const double* __restrict__ mean, int d_in,
+                              int d_out, double tokens) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t ng = (int64_t)d_in * d_in;
+  if (e < ng) {
+    const int i = (int)(e / d_in), j = (int)(e % d_in);
+    G[e] -= tokens * mean[i] * mean[j];
+  } else if (e < ng + (int64_t)d_in * d_out) {
+    const int64_t f = e - ng;
+    const int i = (int)(f / d_out), o = (int)(f % d_out);
+    C[f] -= tokens * mean[i] * mean[d_in + o];
+  }
+}
+
+// b[o] = my[o] - sum_i S[i][o] mx[i] (i ascending), fp32 out; NaN after a failed factorisation
+__global__ void intercept_kernel(const double* __restrict__ S, const double* __restrict__ mean, int d_in, int d_out,
+                                 float* __restrict__ bias, const int* __restrict__ status) {
+  const int o = blockIdx.x * blockDim.x + threadIdx.x;
+  if (o >= d_out) return;
+  double b = mean[d_in + o];
+  for (int i = 0; i < d_in; ++i) b -= S[(int64_t)i * d_out + o] * mean[i];
+  bias[o] = *status != 0 ? __uint_as_float(0x7fc00000u) : (float)b;
 }
 
 // G[i][i] += rate * trace(G) / d (one block; the trace is summed in a fixed order); clears the status word
@@ -302,16 +351,19 @@ __global__ void transpose_round_kernel(const double* __restrict__ S, int d_in, i
 }  // namespace
 
 size_t fit_workspace_bytes(int d_in, int d_out) {
-  return ((size_t)d_in * d_in + (size_t)d_in * d_out) * sizeof(double) + 16;      // G, C / solution, status word
+  // G, C / solution, column means of [X | Y], status word
+  return ((size_t)d_in * d_in + (size_t)d_in * d_out + d_in + d_out) * sizeof(double) + 16;
 }
 
 hipError_t launch_fit_predictor(int dtype, int64_t tokens, const void* x0, int d0, const void* x1, int d1, const void* Y,
-                                int d_out, double rate, void* W, double* W64, void* workspace, hipStream_t stream) {
+                                int d_out, double rate, void* W, double* W64, float* bias, void* workspace,
+                                hipStream_t stream) {
   const int d = d0 + d1;
   const int nb = d / kNb, nr = d_out / kNb;
   double* G = static_cast<double*>(workspace);
   double* C = G + (size_t)d * d;
-  int* status = reinterpret_cast<int*>(C + (size_t)d * d_out);
+  double* mean = C + (size_t)d * d_out;
+  int* status = reinterpret_cast<int*>(mean + d + d_out);
   const unsigned tiles = (unsigned)(nb * (nb + 1) / 2 + nb * nr);
   if (dtype == kBF16)
     gram_kernel<bf16_t><<<tiles, kFitThreads, 0, stream>>>(static_cast<const bf16_t*>(x0), d0, static_cast<const bf16_t*>(x1),
@@ -319,6 +371,18 @@ hipError_t launch_fit_predictor(int dtype, int64_t tokens, const void* x0, int d
   else
     gram_kernel<float><<<tiles, kFitThreads, 0, stream>>>(static_cast<const float*>(x0), d0, static_cast<const float*>(x1), d1,
                                                           static_cast<const float*>(Y), d_out, tokens, G, C);
+  if (bias != nullptr) {       // intercept: regress the centred Y on the centred X
+    if (dtype == kBF16)
+      column_mean_kernel<bf16_t><<<nb + nr, kFitThreads, 0, stream>>>(static_cast<const bf16_t*>(x0), d0,
+                                                                      static_cast<const bf16_t*>(x1), d1,
+                                                                      static_cast<const bf16_t*>(Y), d_out, tokens, mean);
+    else
+      column_mean_kernel<float><<<nb + nr, kFitThreads, 0, stream>>>(static_cast<const float*>(x0), d0,
+                                                                     static_cast<const float*>(x1), d1,
+                                                                     static_cast<const float*>(Y), d_out, tokens, mean);
+    const int64_t ne = (int64_t)d * d + (int64_t)d * d_out;
+    centre_kernel<<<(unsigned)((ne + 255) / 256), 256, 0, stream>>>(G, C, mean, d, d_out, (double)tokens);
+  }
   ridge_kernel<<<1, kFitThreads, 0, stream>>>(G, d, rate, status);
   // G = L L^T, block column by block column
   for (int k = 0; k < nb; ++k) {
@@ -339,6 +403,7 @@ hipError_t launch_fit_predictor(int dtype, int64_t tokens, const void* x0, int d
     trsm_diag_kernel<true><<<nr, kNb, 0, stream>>>(G, d, C, d_out, k);
     if (k > 0) block_update_kernel<<<k * nr, kFitThreads, 0, stream>>>(G, d, C, d_out, k, 2);
   }
+  if (bias != nullptr) intercept_kernel<<<(d_out + 255) / 256, 256, 0, stream>>>(C, mean, d, d_out, bias, status);
   const int64_t n = (int64_t)d * d_out;
   const unsigned blocks = (unsigned)((n + 255) / 256);
   if (dtype == kBF16) transpose_round_kernel<bf16_t><<<blocks, 256, 0, stream>>>(C, d, d_out, static_cast<bf16_t*>(W), W64, status);

@@ -63,8 +63,10 @@ hipError_t launch_folded_scores(int n_codewords, const void* Khat_prev, const vo
 // Ridge least-squares fit of a predictor, W [d_out, d0 + d1] = argmin || [x0 | x1] W^T - Y ||^2 + lambda ||W||^2 with
 // lambda = rate * trace(X^T X) / d_in, in fp64 through the normal equations.  d0, d1, d_out multiples of 64.
 // `workspace`: fit_workspace_bytes(d0 + d1, d_out).  W64 (nullable): the unrounded solution [d_out, d_in].
+// bias (nullable, fp32 [d_out]): fit an intercept as well (centred regression).
 size_t fit_workspace_bytes(int d_in, int d_out);
 hipError_t launch_fit_predictor(int dtype, int64_t tokens, const void* x0, int d0, const void* x1, int d1, const void* Y,
-                                int d_out, double rate, void* W, double* W64, void* workspace, hipStream_t stream);
+                                int d_out, double rate, void* W, double* W64, float* bias, void* workspace,
+                                hipStream_t stream);
 
 }  // namespace aquakv

@@ -183,8 +183,8 @@ def test_round_to_nearest_backbone_layer_validation():
 
 
 def test_fit_predictor_validates_its_arguments():
-    assert B.aquakv_fit_workspace_bytes(1024, 1024) == (1024 * 1024 * 2) * 8 + 16
-    assert B.aquakv_fit_workspace_bytes(2048, 1024) == (2048 * 2048 + 2048 * 1024) * 8 + 16
+    assert B.aquakv_fit_workspace_bytes(1024, 1024) == (1024 * 1024 * 2 + 2048) * 8 + 16
+    assert B.aquakv_fit_workspace_bytes(2048, 1024) == (2048 * 2048 + 2048 * 1024 + 3072) * 8 + 16
     assert B.aquakv_fit_workspace_bytes(100, 1024) == 0 and B.aquakv_fit_workspace_bytes(1024, 16384) == 0
     ws = (FAKE, 1 << 40)
     ok = dict(dtype=B.AQUAKV_BF16, tokens=100, x0=FAKE, d0=1024, x1=FAKE, d1=1024, Y=FAKE, d_out=1024, rate=1e-3, W=FAKE, W64=None)

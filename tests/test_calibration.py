@@ -45,6 +45,25 @@ def test_fit_satisfies_the_regularised_normal_equations():
     assert np.linalg.norm(C.fit_predictor(X, Y, 1.0)) < np.linalg.norm(C.fit_predictor(X, Y, 1e-3)) < np.linalg.norm(C.fit_predictor(X, Y, 0.0)) + 1e-12
 
 
+def test_fit_with_intercept_is_least_squares_on_a_ones_column():
+    g = rng(4)
+    X = g.standard_normal((150, 12)) + 3.0 * g.standard_normal(12)          # columns with means
+    W_true, b_true = g.standard_normal((7, 12)), g.standard_normal(7)
+    Y = X @ W_true.T + b_true
+    W, b = C.fit_predictor(X, Y, rate=0.0, bias=True)
+    assert np.allclose(W, W_true, atol=1e-9) and np.allclose(b, b_true, atol=1e-9)        # an affine map is recovered
+    Yn = Y + 0.2 * g.standard_normal(Y.shape)
+    W, b = C.fit_predictor(X, Yn, rate=0.0, bias=True)
+    sol = np.linalg.lstsq(np.hstack([X, np.ones((150, 1))]), Yn, rcond=None)[0]            # numpy's routine, ones column
+    assert np.allclose(W, sol[:12].T, atol=1e-9) and np.allclose(b, sol[12], atol=1e-9)
+    # without the intercept the same data is fitted worse
+    W0 = C.fit_predictor(X, Yn, rate=0.0)
+    assert np.sum((X @ W0.T - Yn) ** 2) > np.sum((X @ W.T + b - Yn) ** 2)
+    # the residual has zero mean, with or without the ridge term
+    W, b = C.fit_predictor(X, Yn, rate=0.05, bias=True)
+    assert np.max(np.abs(np.mean(X @ W.T + b - Yn, axis=0))) < 1e-12
+
+
 def small_stream(L, T, H, corr=0.8, seed=3):
     """Layer l + 1 = corr * (layer l mixed by an orthogonal map) + noise: a stream that linear predictors explain."""
     g = rng(seed)
@@ -265,3 +284,36 @@ def test_gpu_tiny_config_calibrated_on_its_first_half():
     err_plain = np.sum((e_plain["Khat"][half:] - K1) ** 2) / np.sum(K1 ** 2)
     print(f"   held-out keys: relative error {err:.4f} with the calibrated predictor, {err_plain:.4f} without", flush=True)
     assert err < err_plain
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype,T,d0,d1,d_out", [("fp32", 700, 256, 0, 128), ("bf16", 2000, 512, 512, 256)])
+def test_gpu_fit_with_intercept_against_the_oracle(dtype, T, d0, d1, d_out):
+    from paper_2501_19392_amd import binding as B
+    from tests import parity_utils as U
+    print(f"case fit with intercept dtype={dtype} T={T} d0={d0} d1={d1} d_out={d_out}", flush=True)
+    sd = synth.torch_dtype(dtype)
+    g = torch.Generator().manual_seed(21)
+    d = d0 + d1
+    X = (torch.randn(T, d, generator=g) + 2.0 * torch.randn(d, generator=g)).to(sd)         # channels with means
+    W_true = torch.randn(d_out, d, generator=g) / d ** 0.5
+    Y = (X.float() @ W_true.T + torch.randn(d_out, generator=g) + 0.3 * torch.randn(T, d_out, generator=g)).to(sd)
+    x0 = X[:, :d0].contiguous().cuda()
+    x1 = X[:, d0:].contiguous().cuda() if d1 else None
+    W = torch.empty(d_out, d, dtype=sd, device="cuda")
+    W64 = torch.empty(d_out, d, dtype=torch.float64, device="cuda")
+    bias = torch.empty(d_out, dtype=torch.float32, device="cuda")
+    ws = torch.empty(B.aquakv_fit_workspace_bytes(d, d_out), dtype=torch.uint8, device="cuda")
+    B.aquakv_fit_predictor(sd, T, x0, d0, x1, d1, Y.cuda(), d_out, 1e-3, W, W64, ws, bias=bias)
+    torch.cuda.synchronize()
+    want_w, want_b = C.fit_predictor(U.np64(X), U.np64(Y), 1e-3, bias=True)
+    rel_w = np.linalg.norm(W64.cpu().numpy() - want_w) / np.linalg.norm(want_w)
+    rel_b = np.linalg.norm(U.np64(bias) - want_b) / np.linalg.norm(want_b)
+    print(f"   relative difference to the oracle: weights {rel_w:.2e}, intercept {rel_b:.2e}", flush=True)
+    assert rel_w < 1e-9 and rel_b < 1e-6                   # the intercept is returned in fp32
+    assert np.array_equal(U.np64(W), O.round_storage(W64.cpu().numpy(), dtype))
+    # without the bias argument the same call fits no intercept
+    B.aquakv_fit_predictor(sd, T, x0, d0, x1, d1, Y.cuda(), d_out, 1e-3, W, W64, ws)
+    torch.cuda.synchronize()
+    want0 = C.fit_predictor(U.np64(X), U.np64(Y), 1e-3)
+    assert np.linalg.norm(W64.cpu().numpy() - want0) / np.linalg.norm(want0) < 1e-9
