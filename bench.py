@@ -55,7 +55,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="skip the instrumented replay")
     ap.add_argument("--cpu-rows", type=int, default=8192, help="token rows of the oracle sample")
-    ap.add_argument("--cpu-layers", type=int, default=4, help="predicted layers of the oracle sample")
+    ap.add_argument("--cpu-layers", type=int, default=8, help="predicted layers of the oracle sample")
     ap.add_argument("--scores-form", default="sweep", choices=["sweep", "folded", "recompute"],
                     help="sweep: the scores come out of the decode sweep (aquakv_decode_attn_scores with Khat_out is the "
                          "key half of decode, aquakv_decode_values the value half); folded / recompute: a scoring "
