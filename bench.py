@@ -425,7 +425,7 @@ def decode_read_path(args, device):
     cfg = synth.Config("decode-read", layers=L, kv_heads=8, head_dim=128, tokens=T, dtype="bf16")
     sd = torch.bfloat16
     st = synth.KVStream(cfg, device=device, work=torch.float32)
-    C, table = grids_on_device([n], device)[n]
+    C, table = (None, None) if args.rtn_bits else grids_on_device([n], device)[n]
     layers, codes, khat, new_rows = [], [], [], []
     vh = [None, None]
     ws = None
@@ -439,7 +439,10 @@ def decode_read_path(args, device):
         wk = wv = None
         if l > 0:
             wk, wv = (w.to(device) for w in synth.analytic_predictors(st, l))
-        lay = B.Layer(8, 128, C, sk, sv, sd, w_k=wk, w_v=wv, search_table=table)
+        if args.rtn_bits:
+            lay = B.Layer(8, 128, None, None, None, sd, w_k=wk, w_v=wv, rtn_bits=args.rtn_bits)
+        else:
+            lay = B.Layer(8, 128, C, sk, sv, sd, w_k=wk, w_v=wv, search_table=table)
         ws = ws if ws is not None else lay.alloc_workspace(T, device)
         kc, ks = lay.alloc_codes(T, device)
         vc, vs = lay.alloc_codes(T, device)
@@ -493,7 +496,9 @@ def decode_read_path(args, device):
         phases[name] = a.elapsed_time(b) / max(1, min(args.steps, 5))
     # scoring call of one predicted layer: read Khat_prev, codes, scales; write the scores
     pred_layers = L - 1
-    call_bytes = T * (1024 * 2 + 8 * (layers[-1].code_bytes_per_group + 2)) + batch * q_heads * S * 4
+    lay_ = layers[-1]
+    call_bytes = (T * (1024 * 2 + 8 * lay_.code_bytes_per_group + 2 * (1024 // lay_.rht_group) * lay_.scale_words_per_group)
+                  + batch * q_heads * S * 4)
     a, b = ev(), ev()
     reps = max(1, min(args.steps, 5))
     a.record()
@@ -506,12 +511,12 @@ def decode_read_path(args, device):
     call_ms = a.elapsed_time(b) / (reps * pred_layers)
     gbs = call_bytes / (call_ms * 1e-3) / 1e9
     return {
-        "metric": "decode read path: cached tokens scored per second per layer at %d bits/value" % (n.bit_length() // 2),
+        "metric": "decode read path: cached tokens scored per second per layer at %d bits/value" % (args.rtn_bits or n.bit_length() // 2),
         "value": round(T * L / dt, 1), "unit": "tokens/s per layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(1e3 * dt, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"decode-read: {L} layers x {batch} sequences x {S} cached tokens x 8 kv heads x 128, bf16, "
-                               f"n={n}, step = q.k scores ({q_heads} query heads, {'folded' if folded else 'recompute'} form) over the whole "
+                               f"{'round-to-nearest backbone' if args.rtn_bits else 'n=%d' % n}, step = q.k scores ({q_heads} query heads, {'folded' if folded else 'recompute'} form) over the whole "
                                f"cache + append of one token per sequence, for every layer",
                    "tokens": T, "layers": L, "q_heads": q_heads, "batch": batch, "seq_len": S},
         "phases_ms_per_step": {k: round(v, 3) for k, v in phases.items()},

@@ -42,7 +42,8 @@
  *   codes  : uint8 [T, D*b/8], b bits per value in channel order, little-endian
  *   scales : uint16 [T, D/64, 2] = (fp16 bits of the step, zero point) per group; 4-byte aligned
  * Every entry point below takes such a layer; where a comment says "scales [T, H]" read the
- * layout above instead.  The folded form of the scoring call is built for the grids only.
+ * layout above instead.  In the folded form of the scoring call the code term is
+ * step * sum_i q_i (code_i - zero) per group (no rotation).
  */
 #ifndef AQUAKV_H
 #define AQUAKV_H

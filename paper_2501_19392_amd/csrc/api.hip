@@ -510,7 +510,7 @@ int aquakv_fit_predictor(int32_t dtype, int64_t tokens, const void* x0, int32_t 
 
 size_t aquakv_scores_workspace_bytes(const aquakv_layer* L, int32_t batch, int32_t q_heads) {
   if (check_layer(L) != AQUAKV_OK || batch < 1 || q_heads < 1) return 0;
-  if (L->dtype != AQUAKV_BF16 || is_wide(L) || is_rtn(L) || !aquakv::folded_scores_supported(L->kv_heads, L->d_in_k, q_heads)) return 0;
+  if (L->dtype != AQUAKV_BF16 || is_wide(L) || !aquakv::folded_scores_supported(L->kv_heads, L->d_in_k, q_heads)) return 0;
   return aquakv::folded_scores_workspace_bytes(batch, q_heads);
 }
 
@@ -536,12 +536,12 @@ int decode_attn_scores(const aquakv_layer* L, int32_t batch, int32_t seq_len, in
   const int64_t tokens = (int64_t)batch * seq_len;
   if (tokens == 0) return AQUAKV_OK;
   const Plan pl = make_plan(L, tokens);
-  if (has_k && pl.fused && !is_rtn(L) && Khat_out == nullptr && rope_cos == nullptr && workspace != nullptr &&
+  if (has_k && pl.fused && Khat_out == nullptr && rope_cos == nullptr && workspace != nullptr &&
       aquakv::folded_scores_supported(L->kv_heads, L->d_in_k, q_heads) &&
       workspace_bytes >= aquakv::folded_scores_workspace_bytes(batch, q_heads)) {
     // predictor folded into the query: Khat_prev and the codes are read once, nothing is recomputed
     CHECK(check_ptr(workspace, "workspace", true));
-    HIP_TRY(aquakv::launch_folded_scores(L->n_codewords, Khat_prev, L->w_k, L->b_k, L->signs_k, L->codebook, k_codes,
+    HIP_TRY(aquakv::launch_folded_scores(quantizer_id(L), Khat_prev, L->w_k, L->b_k, L->signs_k, L->codebook, k_codes,
                                          k_scales, q, score_scale, scores, workspace, batch, seq_len, q_heads,
                                          static_cast<hipStream_t>(stream_)));
     return AQUAKV_OK;

@@ -142,15 +142,22 @@ __global__ __launch_bounds__(256) void fold_query_kernel(const bf16_t* __restric
   // rotated query: one quad of lanes per query head (second wave, so that it overlaps the q . b loop)
   if (tid >= 64 && tid < 64 + 4 * rep) {
     const int r = (tid - 64) >> 2, qd = tid & 3;
-    uint32_t sb[32];
-    load_sign_bits(signs, h, qd, sb);
     float v[32];
+    if (signs != nullptr) {
+      uint32_t sb[32];
+      load_sign_bits(signs, h, qd, sb);
 #pragma unroll
-    for (int k = 0; k < 32; ++k) v[k] = __uint_as_float(__float_as_uint(qs[r][32 * qd + k]) ^ sb[k]);
-    wht128(v, qd);
-    const float norm = quad_sign(qd) * kRsqrtG;
+      for (int k = 0; k < 32; ++k) v[k] = __uint_as_float(__float_as_uint(qs[r][32 * qd + k]) ^ sb[k]);
+      wht128(v, qd);
+      const float norm = quad_sign(qd) * kRsqrtG;
 #pragma unroll
-    for (int k = 0; k < 32; ++k) qrot[(h * rep + r) * 128 + 32 * qd + k] = v[k] * norm;
+      for (int k = 0; k < 32; ++k) v[k] *= norm;
+    } else {                                   // backbone without a rotation: the code term multiplies q itself
+#pragma unroll
+      for (int k = 0; k < 32; ++k) v[k] = qs[r][32 * qd + k];
+    }
+#pragma unroll
+    for (int k = 0; k < 32; ++k) qrot[(h * rep + r) * 128 + 32 * qd + k] = v[k];
   }
 }
 
@@ -161,7 +168,7 @@ template <int NCW> __device__ __forceinline__ int code_of(const u32x4& raw, int 
   const int bit = c * m, w = bit >> 5, sh = bit & 31;
   uint32_t x = d[w] >> sh;
   if (sh + c > 32) x |= d[w + 1] << (32 - sh);
-  return (int)(x & (NCW - 1));
+  return (int)(x & ((1u << c) - 1u));
 }
 
 // ------------------------------------------------------------------ streaming kernel
@@ -235,8 +242,15 @@ __global__ __launch_bounds__(512) void folded_scores_kernel(const bf16_t* __rest
       for (int e = 0; e < 8; ++e) r[ks][e] = static_cast<_Float16>(mine ? v[e] : 0.f);
     }
   }
-  if (tid < NCW) {
-    const _Float16 a = static_cast<_Float16>(codebook[2 * tid]), bb = static_cast<_Float16>(codebook[2 * tid + 1]);
+  if (tid < (1 << c)) {
+    _Float16 a, bb;
+    if constexpr (is_rtn(NCW)) {               // c bits = the codes of two consecutive values, as numbers
+      a = static_cast<_Float16>((float)(tid & ((1 << (c / 2)) - 1)));
+      bb = static_cast<_Float16>((float)(tid >> (c / 2)));
+    } else {
+      a = static_cast<_Float16>(codebook[2 * tid]);
+      bb = static_cast<_Float16>(codebook[2 * tid + 1]);
+    }
     cb_s[tid] = (uint32_t)__builtin_bit_cast(uint16_t, a) | ((uint32_t)__builtin_bit_cast(uint16_t, bb) << 16);
   }
 
@@ -282,7 +296,7 @@ __global__ __launch_bounds__(512) void folded_scores_kernel(const bf16_t* __rest
 
   // codes and scale of the group (token lane % 32 of a tile, kv head = wave): the half of the 64 codes that
   // belongs to rotated coordinates 64 fk ... + 63
-  struct Packed { u32x4 r0, r1; uint16_t scale; };
+  struct Packed { u32x4 r0, r1; uint32_t scale, scale2; };   // scale: fp16 bits; round-to-nearest: (step, zero) of both groups
   auto fetch_codes = [&](int tile, Packed& p) {
     const int t = tile * kTokTile + ftok;
     const int64_t gid = (seq_row0 + (t < seq_len ? t : seq_len - 1)) * H + wave;
@@ -300,7 +314,12 @@ __global__ __launch_bounds__(512) void folded_scores_kernel(const bf16_t* __rest
       p.r0 = reinterpret_cast<const u32x4*>(src)[0];
       p.r1 = reinterpret_cast<const u32x4*>(src)[1];
     }
-    p.scale = scales[gid];
+    if constexpr (is_rtn(NCW)) {
+      const u32x2 m = reinterpret_cast<const u32x2*>(scales)[gid];      // (step, zero) of the head's two groups of 64
+      p.scale = m.x; p.scale2 = m.y;
+    } else {
+      p.scale = scales[gid]; p.scale2 = 0;
+    }
   };
 
   // pipeline: tiles it + 1 (requested one iteration ago) and, from the middle of iteration it on, it + 2 are in
@@ -356,6 +375,21 @@ __global__ __launch_bounds__(512) void folded_scores_kernel(const bf16_t* __rest
     asm volatile("" ::: "memory");
     if (it + 2 < ntiles) request_tile(tile0 + (it + 2) * tstep, slot);
     asm volatile("" ::: "memory");
+    // Round-to-nearest backbone: the lane's 64 values are one group with its own step and zero point, the other half
+    // of the token's head (lane ^ 32) another.  Both go into one accumulator, so the operand carries
+    // (code - zero) * step / max(step of the two groups) in fp16 and the result is scaled by that maximum.
+    f16x8 rtn_mul, rtn_add;
+    float rtn_scale = 0.f;
+    if constexpr (is_rtn(NCW)) {
+      const float s_a = half_bits_to_float((uint16_t)(c0.scale & 0xffffu)), s_b = half_bits_to_float((uint16_t)(c0.scale2 & 0xffffu));
+      rtn_scale = fmaxf(s_a, s_b);
+      const uint32_t mine = fk ? c0.scale2 : c0.scale;
+      const float ratio = rtn_scale > 0.f ? __fdiv_rn(fk ? s_b : s_a, rtn_scale) : 0.f;
+      const _Float16 rh = static_cast<_Float16>(ratio);
+      const _Float16 ah = static_cast<_Float16>(-(float)(mine >> 16) * static_cast<float>(rh));
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { rtn_mul[e] = rh; rtn_add[e] = ah; }
+    }
     // code term on the matrix cores: [query heads of this kv head] x [32 tokens] x [128 rotated coordinates]
     f32x16 acc_c;
 #pragma unroll
@@ -370,14 +404,15 @@ __global__ __launch_bounds__(512) void folded_scores_kernel(const bf16_t* __rest
       u32x4 pts = lookup(0);
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        const f16x8 cf = __builtin_bit_cast(f16x8, pts);
+        f16x8 cf = __builtin_bit_cast(f16x8, pts);
+        if constexpr (is_rtn(NCW)) cf = cf * rtn_mul + rtn_add;          // (code - zero) * step / max step
         if (ks + 1 < 8) pts = lookup(ks + 1);
         acc_c = __builtin_amdgcn_mfma_f32_32x32x16_f16(r[ks], cf, acc_c, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
     // the lane's column is one token: the code term is scaled by that group's sigma
-    const float s16 = half_bits_to_float(c0.scale);
+    const float s16 = is_rtn(NCW) ? rtn_scale : half_bits_to_float((uint16_t)c0.scale);
     c0 = c1;
     c1 = cn;
 
@@ -456,7 +491,9 @@ hipError_t launch_folded_scores(int n_codewords, const void* Khat_prev, const vo
     fold_query_kernel<<<batch * 8 * kFoldChunks, 256, 0, stream>>>(static_cast<const bf16_t*>(q),
                                                                     static_cast<const bf16_t*>(W), bias, signs, ws,
                                                                     q_heads, 8, r0, rep);
-    if (n_codewords == 16) AQUAKV_FOLDED(16);
+    if (n_codewords == kRtn2) AQUAKV_FOLDED(kRtn2);
+    else if (n_codewords == kRtn4) AQUAKV_FOLDED(kRtn4);
+    else if (n_codewords == 16) AQUAKV_FOLDED(16);
     else if (n_codewords == 64) AQUAKV_FOLDED(64);
     else AQUAKV_FOLDED(256);
   }

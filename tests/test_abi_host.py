@@ -161,13 +161,13 @@ def test_half_calls_validate_their_arguments():
 
 def test_round_to_nearest_backbone_layer_validation():
     """vq_dim = 1: the uniform round-to-nearest backbone (Sect. 4.1): 4 or 16 levels, groups of 64, no grid / signs,
-    (step, zero point) words need 4-byte alignment, no folded scoring form."""
+    (step, zero point) words need 4-byte alignment."""
     rtn = dict(vq_dim=1, n_codewords=4, codebook=None, signs_k=None, signs_v=None)
     L = layer(**rtn)
     assert B.aquakv_workspace_bytes(L, 300) == 300 * 1024 * 2                # bf16: fused like the grids
     assert B.aquakv_workspace_bytes(layer(**dict(rtn, n_codewords=16, rht_group=64)), 300) == 300 * 1024 * 2
     assert B.aquakv_workspace_bytes(layer(**dict(rtn, dtype=B.AQUAKV_FP32)), 300) == 300 * 1024 * 8
-    assert B.aquakv_scores_workspace_bytes(L, 1, 32) == 0
+    assert B.aquakv_scores_workspace_bytes(L, 1, 32) == 8 * 2 * 8 * 1024 + 32 * 128 * 4 + 32 * 4      # folded form as for the grids
     ws = (FAKE, 1 << 30)
     for kw, want in ((dict(n_codewords=8), B.AQUAKV_EUNSUPPORTED), (dict(n_codewords=5), B.AQUAKV_EINVAL),
                      (dict(n_codewords=64), B.AQUAKV_EUNSUPPORTED), (dict(rht_group=128), B.AQUAKV_EUNSUPPORTED),

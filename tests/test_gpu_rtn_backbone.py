@@ -165,10 +165,20 @@ def test_rtn_layer_stack(B, dtype, bits, T):
         want = 0.25 * np.einsum("qd,tqd->qt", U.np64(q)[0], np.repeat(U.np64(Kh), QH // H, axis=1))
         mag = 0.25 * np.einsum("qd,tqd->qt", np.abs(U.np64(q)[0]), np.repeat(np.abs(U.np64(Kh)), QH // H, axis=1))
         assert np.all(np.abs(U.np64(scores)[0] - want) <= 4e-6 * mag + 1e-30)
-        s2 = torch.empty_like(scores)
-        B.aquakv_decode_attn_scores(lg, 1, T, QH, kc, km, Kp, q, 0.25, s2, None, ws)       # without the by-product
+        # without the by-product: layers with a key predictor take the folded form in bf16 (predictor folded into the
+        # query, code term step * sum q (code - zero) per group), everything else recomputes as above
+        s2 = torch.full_like(scores, float("nan"))
+        B.aquakv_decode_attn_scores(lg, 1, T, QH, kc, km, Kp, q, 0.25, s2, None, ws)
         torch.cuda.synchronize()
-        assert torch.equal(s2, scores)
+        folded = l > 0 and dtype == "bf16"
+        assert (B.aquakv_scores_workspace_bytes(lg, 1, QH) > 0) == folded
+        if folded:
+            worst = float(np.max(np.abs(U.np64(s2)[0] - want) / (mag + 1e-30)))
+            print(f"   layer {l}: folded scores, worst error / (sum|q||k|) = {worst:.3g}", flush=True)
+            assert np.all(np.abs(U.np64(s2)[0] - want) <= U.RTOL["bf16"] * mag + 1e-30), worst
+            assert not torch.equal(s2, scores)                 # (it really is another path)
+        else:
+            assert torch.equal(s2, scores)
         outs.append((kc, km, vc, vm))
         Kp, Vp = Kh, Vh
     # the free-running oracle (no teacher forcing) stays close: same codes wherever no rounding tie moved one
