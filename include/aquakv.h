@@ -95,7 +95,8 @@ typedef struct aquakv_layer {
                            same layout either way.  Groups across heads are not
                            fused with the predictor: the calls then need the fp32
                            prediction workspace also in bf16.  With vq_dim = 1: 0 or
-                           64, the group of the round-to-nearest backbone.         */
+                           64, the group of the round-to-nearest backbone, or 1024 =
+                           the whole token of 8 heads (one (step, zero) per token).  */
   const float* codebook;   /* [n, 2] fp32 grid points (ignored when vq_dim = 1, like
                               signs_k, signs_v and search_table)                  */
   const int8_t* signs_k;   /* [H*g] entries +1 / -1: RHT signs for keys           */

@@ -53,8 +53,9 @@ int check_layer(const aquakv_layer* L) {
   if (is_rtn(L)) {
     if (L->n_codewords != 4 && L->n_codewords != 16)
       return fail(pow2 ? AQUAKV_EUNSUPPORTED : AQUAKV_EINVAL, "n_codewords=%d: vq_dim 1 is built for 4 or 16 levels", L->n_codewords);
-    if (L->rht_group != 0 && L->rht_group != kRtnGroup)
-      return fail(AQUAKV_EUNSUPPORTED, "rht_group=%d: vq_dim 1 is built for groups of %d", L->rht_group, kRtnGroup);
+    if (L->rht_group != 0 && L->rht_group != kRtnGroup && !(L->rht_group == 1024 && L->kv_heads * L->head_dim == 1024))
+      return fail(AQUAKV_EUNSUPPORTED, "rht_group=%d: vq_dim 1 is built for groups of %d, and of 1024 = the whole token of 8 heads",
+                  L->rht_group, kRtnGroup);
   } else if (L->n_codewords != 16 && L->n_codewords != 64 && L->n_codewords != 256) {
     return fail(pow2 ? AQUAKV_EUNSUPPORTED : AQUAKV_EINVAL, "n_codewords=%d: must be 16, 64 or 256", L->n_codewords);
   }
@@ -81,10 +82,13 @@ int check_layer(const aquakv_layer* L) {
 }
 
 // rotation group = the whole token vector (Sect. 4.1 of the paper) instead of one head
-inline bool is_wide(const aquakv_layer* L) { return !is_rtn(L) && L->rht_group != 0 && L->rht_group != L->head_dim; }
+inline bool is_wide(const aquakv_layer* L) {
+  if (is_rtn(L)) return L->rht_group == 1024;
+  return L->rht_group != 0 && L->rht_group != L->head_dim;
+}
 // bytes of scales per token row: one fp16 per rotation group, or (fp16 step, 16-bit zero point) per group of 64
 inline size_t scale_row_bytes(const aquakv_layer* L) {
-  if (is_rtn(L)) return (size_t)L->kv_heads * (L->head_dim / kRtnGroup) * 2 * sizeof(uint16_t);
+  if (is_rtn(L)) return (is_wide(L) ? 1 : (size_t)L->kv_heads * (L->head_dim / kRtnGroup)) * 2 * sizeof(uint16_t);
   return (is_wide(L) ? 1 : (size_t)L->kv_heads) * sizeof(uint16_t);
 }
 

@@ -276,15 +276,19 @@ __device__ __forceinline__ u32x4 rtn_load_codes(const uint8_t* __restrict__ code
   return raw;
 }
 
+// the (step, zero) word of the lane's group: two groups of 64 per head, or (WIDE, 8 heads) one group per token
+template <bool WIDE = false>
 __device__ __forceinline__ uint32_t rtn_load_meta(const uint16_t* __restrict__ scales, int64_t gid, int q) {
-  return reinterpret_cast<const uint32_t*>(scales)[gid * 2 + (q >> 1)];
+  return reinterpret_cast<const uint32_t*>(scales)[WIDE ? gid >> 3 : gid * 2 + (q >> 1)];
 }
 
-// Q(x - p) for the 32 values this lane holds of head group gid; same contract as quantize_group below.
-template <int BITS>
-__device__ __forceinline__ void rtn_quantize_group(float (&v)[32], const float (&p)[32], int q, bool active, int64_t gid,
+// Q(x - p) for the 32 values this lane holds of head group gid; same contract as quantize_group below
+// (`l`: lane % 4, or with WIDE lane % 32: the group is then the whole token of 8 heads, one (step, zero) per token).
+template <int BITS, bool WIDE = false>
+__device__ __forceinline__ void rtn_quantize_group(float (&v)[32], const float (&p)[32], int l, bool active, int64_t gid,
                                                    uint8_t* __restrict__ codes, uint16_t* __restrict__ scales,
                                                    bool want_hat) {
+  const int q = l & 3;
   constexpr float kTop = (float)((1 << BITS) - 1);
   float lo = 0.f, hi = 0.f;
 #pragma unroll
@@ -295,6 +299,12 @@ __device__ __forceinline__ void rtn_quantize_group(float (&v)[32], const float (
   }
   lo = fminf(lo, quad_xor<1>(lo));
   hi = fmaxf(hi, quad_xor<1>(hi));
+  if constexpr (WIDE) {
+    lo = fminf(lo, quad_xor<2>(lo));    hi = fmaxf(hi, quad_xor<2>(hi));
+    lo = fminf(lo, swizzle_xor<4>(lo)); hi = fmaxf(hi, swizzle_xor<4>(hi));
+    lo = fminf(lo, row_xor8(lo));       hi = fmaxf(hi, row_xor8(hi));
+    lo = fminf(lo, swizzle_xor<16>(lo)); hi = fmaxf(hi, swizzle_xor<16>(hi));
+  }
   const float step = fminf(__fdiv_rn(hi - lo, kTop), 65504.0f);
   const _Float16 s16h = static_cast<_Float16>(step);      // round to nearest even
   const float s16 = static_cast<float>(s16h);
@@ -307,9 +317,12 @@ __device__ __forceinline__ void rtn_quantize_group(float (&v)[32], const float (
     code[r] = (uint32_t)__builtin_amdgcn_fmed3f(__builtin_rintf(v[r] * inv) + zf, 0.f, kTop);
   if (active) {
     rtn_store_codes<BITS>(codes, gid, q, code);
-    if ((q & 1) == 0)
-      reinterpret_cast<uint32_t*>(scales)[gid * 2 + (q >> 1)] =
-          (uint32_t)__builtin_bit_cast(uint16_t, s16h) | ((uint32_t)zf << 16);
+    const uint32_t word = (uint32_t)__builtin_bit_cast(uint16_t, s16h) | ((uint32_t)zf << 16);
+    if constexpr (WIDE) {
+      if (l == 0) reinterpret_cast<uint32_t*>(scales)[gid >> 3] = word;
+    } else {
+      if ((q & 1) == 0) reinterpret_cast<uint32_t*>(scales)[gid * 2 + (q >> 1)] = word;
+    }
   }
   if (want_hat) {
 #pragma unroll
@@ -330,7 +343,7 @@ __device__ __forceinline__ void quantize_group(float (&v)[32], const float (&p)[
                                                uint8_t* __restrict__ codes, uint16_t* __restrict__ scales,
                                                bool want_hat) {
   if constexpr (is_rtn(NCW)) {
-    rtn_quantize_group<NCW>(v, p, l & 3, active, gid, codes, scales, want_hat);
+    rtn_quantize_group<NCW, WIDE>(v, p, l, active, gid, codes, scales, want_hat);
     return;
   }
 #pragma unroll
@@ -381,7 +394,7 @@ __device__ __forceinline__ void dequantize_group(float (&z)[32], const float (&p
                                                  const float4* cb, int64_t gid, const uint8_t* __restrict__ codes,
                                                  const uint16_t* __restrict__ scales) {
   if constexpr (is_rtn(NCW)) {
-    rtn_reconstruct<NCW>(rtn_load_codes<NCW>(codes, gid, l & 3), rtn_load_meta(scales, gid, l & 3), p, z);
+    rtn_reconstruct<NCW>(rtn_load_codes<NCW>(codes, gid, l & 3), rtn_load_meta<WIDE>(scales, gid, l & 3), p, z);
     return;
   }
   int idx[16];

@@ -202,17 +202,17 @@ inline unsigned blocks_for(int64_t n_groups) {
     else if ((NCW) == kRtn4) { constexpr int N = kRtn4; CALL; }                         \
     else AQUAKV_DISPATCH_GRID(NCW, CALL);                                               \
   } while (0)
-// binds T (storage type), N (quantizer id: grid size, or kRtn2 / kRtn4) and W (rotation group of 1024, grids only)
+// binds T (storage type), N (quantizer id: grid size, or kRtn2 / kRtn4) and W (groups of 1024 = the whole token)
 // as compile-time names for CALL
 #define AQUAKV_DISPATCH(DT, NCW, WIDE_, CALL)                                           \
   do {                                                                                  \
     if ((DT) == kBF16) {                                                                \
       typedef bf16_t T;                                                                 \
-      if (WIDE_) { constexpr bool W = true; AQUAKV_DISPATCH_GRID(NCW, CALL); }          \
+      if (WIDE_) { constexpr bool W = true; AQUAKV_DISPATCH_N(NCW, CALL); }             \
       else { constexpr bool W = false; AQUAKV_DISPATCH_N(NCW, CALL); }                  \
     } else {                                                                            \
       typedef float T;                                                                  \
-      if (WIDE_) { constexpr bool W = true; AQUAKV_DISPATCH_GRID(NCW, CALL); }          \
+      if (WIDE_) { constexpr bool W = true; AQUAKV_DISPATCH_N(NCW, CALL); }             \
       else { constexpr bool W = false; AQUAKV_DISPATCH_N(NCW, CALL); }                  \
     }                                                                                   \
   } while (0)

@@ -103,7 +103,7 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
       } else {
         in.code = *reinterpret_cast<const u32x4*>(src);
       }
-      if constexpr (is_rtn(NCW)) in.scale = rtn_load_meta(scales, gid, q);
+      if constexpr (is_rtn(NCW)) in.scale = rtn_load_meta<false>(scales, gid, q);
       else in.scale = scales[gid];
     }
   };

@@ -32,12 +32,12 @@ def make_layers(kv_heads, dtype, n, layer_idx=1, w_k=None, w_v=None, b_k=None, b
         wk = None if w_k is None else w_k.to(sd)
         wv = None if w_v is None else w_v.to(sd)
         f32 = lambda t: None if t is None else t.float()
-        lo = O.Layer(kv_heads=kv_heads, head_dim=g, dtype=dtype, rtn_bits=rtn_bits,
+        lo = O.Layer(kv_heads=kv_heads, head_dim=g, dtype=dtype, rtn_bits=rtn_bits, rtn_group=rht_group or 64,
                      w_k=None if wk is None else np64(wk), w_v=None if wv is None else np64(wv),
                      b_k=None if b_k is None else np64(f32(b_k)), b_v=None if b_v is None else np64(f32(b_v)))
         dev = lambda t: None if t is None else t.to(device)
         lg = B.Layer(kv_heads, g, None, None, None, sd, w_k=dev(wk), w_v=dev(wv), b_k=dev(f32(b_k)), b_v=dev(f32(b_v)),
-                     rtn_bits=rtn_bits)
+                     rtn_bits=rtn_bits, rht_group=rht_group or 0)
         return lo, lg
     C = synth.lloyd_codebook(n)
     sk = synth.rht_signs(kv_heads, g, layer_idx, "k")
@@ -123,7 +123,7 @@ def compare_quantizer_outputs(residual, signs, codebook, gpu_codes, gpu_scales, 
 RTN_TIE = 1e-5         # distance of value / step (or -lo / step) to x.5 below which a rounding counts as tied
 
 
-def compare_rtn_outputs(residual, gpu_codes, gpu_meta, bits) -> CodeReport:
+def compare_rtn_outputs(residual, gpu_codes, gpu_meta, bits, group=64) -> CodeReport:
     """Round-to-nearest backbone: codes, steps and zero points of the HIP path against the oracle, same residual.
 
     residual [T, D]; gpu_codes uint8 [T, ...]; gpu_meta (u)int16 [T, D/64, 2].  A step that differs must sit on an
@@ -131,7 +131,7 @@ def compare_rtn_outputs(residual, gpu_codes, gpu_meta, bits) -> CodeReport:
     by the oracle under the GPU's step / zero point.  A code that differs must be a value within RTN_TIE of a
     rounding boundary.  Anything else is `other`."""
     T = residual.shape[0]
-    idx_o, s16_o, zero_o, diag = O.rtn_quantize(residual, bits)
+    idx_o, s16_o, zero_o, diag = O.rtn_quantize(residual, bits, group)
     groups = s16_o.shape[-1]
     g_s16, g_zero = O.rtn_unpack_meta(np.ascontiguousarray(gpu_meta).reshape(T, groups, 2))
     g_idx = O.unpack_codes(np.ascontiguousarray(gpu_codes).reshape(T, groups, -1), 1 << bits)
@@ -145,13 +145,13 @@ def compare_rtn_outputs(residual, gpu_codes, gpu_meta, bits) -> CodeReport:
         adjacent = np.abs(g_s16.view(np.uint16).astype(np.int64) - s16_o.view(np.uint16).astype(np.int64)) == 1
         s_ok = sm & near & adjacent
         # the zero point is judged under the step that is finally used
-        idx_o, _, zero_o, diag = O.rtn_quantize(residual, bits, scale16_override=np.where(s_ok, g_s16, s16_o))
+        idx_o, _, zero_o, diag = O.rtn_quantize(residual, bits, group, scale16_override=np.where(s_ok, g_s16, s16_o))
         zm = g_zero != zero_o
         z_ok = zm & (diag.zero_frac <= RTN_TIE) & (np.abs(g_zero - zero_o) == 1)
         bad = (sm & ~s_ok) | (zm & ~z_ok)
         rep.scale_ties = int((s_ok | z_ok).sum())
         rep.other += int(bad.sum())
-        idx_o, _, _, diag = O.rtn_quantize(residual, bits, scale16_override=np.where(s_ok, g_s16, s16_o),
+        idx_o, _, _, diag = O.rtn_quantize(residual, bits, group, scale16_override=np.where(s_ok, g_s16, s16_o),
                                            zero_override=np.where(z_ok, g_zero, zero_o))
     cm = (g_idx != idx_o) & ~bad[..., None]
     rep.code_mismatch = int(cm.sum())

@@ -167,11 +167,13 @@ def test_round_to_nearest_backbone_layer_validation():
     assert B.aquakv_workspace_bytes(L, 300) == 300 * 1024 * 2                # bf16: fused like the grids
     assert B.aquakv_workspace_bytes(layer(**dict(rtn, n_codewords=16, rht_group=64)), 300) == 300 * 1024 * 2
     assert B.aquakv_workspace_bytes(layer(**dict(rtn, dtype=B.AQUAKV_FP32)), 300) == 300 * 1024 * 8
+    assert B.aquakv_workspace_bytes(layer(**dict(rtn, rht_group=1024)), 300) == 300 * 1024 * (4 + 2)   # whole-token groups: not fused
+    assert B.aquakv_scores_workspace_bytes(layer(**dict(rtn, rht_group=1024)), 1, 32) == 0
     assert B.aquakv_scores_workspace_bytes(L, 1, 32) == 8 * 2 * 8 * 1024 + 32 * 128 * 4 + 32 * 4      # folded form as for the grids
     ws = (FAKE, 1 << 30)
     for kw, want in ((dict(n_codewords=8), B.AQUAKV_EUNSUPPORTED), (dict(n_codewords=5), B.AQUAKV_EINVAL),
                      (dict(n_codewords=64), B.AQUAKV_EUNSUPPORTED), (dict(rht_group=128), B.AQUAKV_EUNSUPPORTED),
-                     (dict(rht_group=1024), B.AQUAKV_EUNSUPPORTED)):
+                     (dict(rht_group=512), B.AQUAKV_EUNSUPPORTED), (dict(rht_group=1024, kv_heads=4, d_in_v=1024), B.AQUAKV_EUNSUPPORTED)):
         assert status_of(B.aquakv_encode_layer, layer(**dict(rtn, **kw)), 8, *ENC_OK, ws) == want, kw
     bad = list(ENC_OK)
     bad[5] = FAKE + 2                                                          # k_scales: 2-byte aligned is not enough

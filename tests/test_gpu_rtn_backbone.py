@@ -189,3 +189,60 @@ def test_rtn_layer_stack(B, dtype, bits, T):
         print(f"   free-run layer {l}: key code bytes differing {frac:.2e}", flush=True)
         assert frac < (2e-2 if dtype == "bf16" else 1e-3)
         Kp, Vp = e["Khat"], e["Vhat"]
+
+
+@pytest.mark.parametrize("dtype,bits", [("bf16", 2), ("fp32", 4)])
+def test_rtn_groups_of_1024(B, dtype, bits):
+    """Groups of 1024 = the whole token of 8 heads, one (step, zero) per token (2 + 32 / 1024 = 2.03 stored bits at
+    2 bits, the appendix table of Sect. 4.1): every stage against the oracle, closed loop, scores."""
+    print(f"case rtn groups of 1024 dtype={dtype} bits={bits}", flush=True)
+    H, T, QH = 8, 203, 16
+    D = H * 128
+    cfg = synth.Config("rtn-1024", layers=2, kv_heads=H, head_dim=128, tokens=T, dtype=dtype)
+    st = synth.KVStream(cfg, device="cpu", work=torch.float64)
+    K0, V0 = (t.cuda() for t in st.next())
+    K1, V1 = (t.cuda() for t in st.next())
+    wk, wv = synth.analytic_predictors(st, 1)
+    lo0, lg0 = U.make_layers(H, dtype, None, rtn_bits=bits, rht_group=1024)
+    lo1, lg1 = U.make_layers(H, dtype, None, w_k=wk, w_v=wv, rtn_bits=bits, rht_group=1024)
+    Kp = Vp = None
+    for l, (lo, lg, K, V) in enumerate(((lo0, lg0, K0, V0), (lo1, lg1, K1, V1))):
+        kc, km = lg.alloc_codes(T)
+        vc, vm = lg.alloc_codes(T)
+        assert km.shape == (T, 1, 2)
+        Kh, Vh = lg.alloc_kv(T), lg.alloc_kv(T)
+        ws = lg.alloc_workspace(T)
+        B.aquakv_encode_layer(lg, T, K, V, Kp, Vp, kc, km, vc, vm, Kh, Vh, ws)
+        torch.cuda.synchronize()
+        for which, X, codes, meta, hat in (("k", K, kc, km, Kh), ("v", V, vc, vm, Vh)):
+            if l == 0:
+                p64 = np.zeros((T, D))
+            else:
+                P = torch.empty(T, D, dtype=torch.float32, device="cuda")
+                if which == "k":
+                    B.aquakv_predict(lg, B.AQUAKV_KEY, T, Kp, None, P)
+                else:
+                    B.aquakv_predict(lg, B.AQUAKV_VALUE, T, Vp, Kh, P)
+                torch.cuda.synchronize()
+                p64 = U.np64(P)
+            rep = U.compare_rtn_outputs(U.np64(X).reshape(T, D) - p64, codes.cpu().numpy(), meta.cpu().numpy(), bits, group=1024)
+            print(f"   layer {l} {which}: {rep}", flush=True)
+            assert rep.other == 0 and rep.groups == T, str(rep)
+            idx = O.unpack_codes(codes.cpu().numpy().reshape(T, 1, -1), 1 << bits)
+            s16, zero = O.rtn_unpack_meta(meta.cpu().numpy().reshape(T, 1, 2))
+            want = O.round_storage(O.rtn_dequantize(idx, s16, zero) + p64, dtype)
+            U.assert_close_storage(hat, want.reshape(T, H, 128), dtype, which + "hat")
+        stored_bits = 8.0 * (kc[0].numel() + km[0].numel() * 2) / D
+        assert abs(stored_bits - (bits + 32 / 1024)) < 1e-12
+        Kd, Vd = lg.alloc_kv(T), lg.alloc_kv(T)
+        B.aquakv_decode_layer(lg, T, kc, km, vc, vm, Kp, Vp, Kd, Vd, ws)
+        q = storage_randn((1, QH, 128), dtype, 95 + l)
+        scores = torch.empty(1, QH, T, dtype=torch.float32, device="cuda")
+        B.aquakv_decode_attn_scores(lg, 1, T, QH, kc, km, Kp, q, 0.5, scores, None, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(bits_of(Kd), bits_of(Kh)) and torch.equal(bits_of(Vd), bits_of(Vh))
+        k64 = np.repeat(U.np64(Kh), QH // H, axis=1)
+        want = 0.5 * np.einsum("qd,tqd->qt", U.np64(q)[0], k64)
+        mag = 0.5 * np.einsum("qd,tqd->qt", np.abs(U.np64(q)[0]), np.abs(k64))
+        assert np.all(np.abs(U.np64(scores)[0] - want) <= 4e-6 * mag + 1e-30)
+        Kp, Vp = Kh, Vh
