@@ -317,3 +317,43 @@ def test_gpu_fit_with_intercept_against_the_oracle(dtype, T, d0, d1, d_out):
     torch.cuda.synchronize()
     want0 = C.fit_predictor(U.np64(X), U.np64(Y), 1e-3)
     assert np.linalg.norm(W64.cpu().numpy() - want0) / np.linalg.norm(want0) < 1e-9
+
+
+@pytest.mark.gpu
+def test_gpu_calibrate_then_serve_from_the_cache():
+    """The pieces together, as a user would run them: calibrate the predictors on one stretch of a stream, then feed a
+    later stretch token by token into the cache manager (sinks, recent buffer, flushes) and recover it layer by layer.
+    The compressed range must come back several times closer to the original than with the backbone alone."""
+    from paper_2501_19392_amd import binding as B
+    from paper_2501_19392_amd.cache import AquaKVCache
+    from paper_2501_19392_amd.calibrate import calibrate
+    L, H, T_cal, T_run = 3, 8, 4096, 600
+    cfg = synth.Config("journey", layers=L, kv_heads=H, head_dim=128, tokens=T_cal + T_run, dtype="bf16")
+    st = synth.KVStream(cfg, device="cuda", work=torch.float32)
+    kv = [st.next() for _ in range(L)]
+    Cb = torch.from_numpy(synth.lloyd_codebook(16)).cuda()
+    table = B.build_search_table(Cb)
+    signs = [(torch.from_numpy(synth.rht_signs(H, 128, l, "k")).cuda(), torch.from_numpy(synth.rht_signs(H, 128, l, "v")).cuda())
+             for l in range(L)]
+    make_layer = lambda l, w_k=None, w_v=None: B.Layer(H, 128, Cb, signs[l][0], signs[l][1], torch.bfloat16, w_k=w_k, w_v=w_v,
+                                                       search_table=table)
+    fitted = calibrate(make_layer, L, lambda l: (kv[l][0][:T_cal].contiguous(), kv[l][1][:T_cal].contiguous()), rate=1e-3)
+    plain = [make_layer(l) for l in range(L)]
+    errs = {}
+    for name, layers in (("calibrated", fitted), ("backbone alone", plain)):
+        cache = AquaKVCache(layers, max_tokens=T_run, sink_tokens=4, buffer_tokens=128)
+        pos = T_cal
+        for piece in (1, 3, 200, 77, 319):                         # 600 tokens, ragged pieces
+            cache.append([(K[pos:pos + piece], V[pos:pos + piece]) for K, V in kv])
+            pos += piece
+        assert (cache.n_sink, cache.n_compressed, cache.n_buffered) == (4, 512, 84)
+        lo, hi = 4, 4 + cache.n_compressed
+        for l, K, V in cache.sweep():
+            torch.cuda.synchronize()
+            ref = kv[l][0][T_cal:T_cal + T_run]
+            assert torch.equal(K[:lo], ref[:lo]) and torch.equal(K[hi:], ref[hi:])             # sinks and buffer exact
+            if l == L - 1:
+                errs[name] = float(((K[lo:hi].float() - ref[lo:hi].float()) ** 2).sum() / (ref[lo:hi].float() ** 2).sum())
+        print(f"   {name}: relative error of the last layer's compressed keys {errs[name]:.4f}; "
+              f"cache holds {cache.stored_bytes()} bytes for {T_run} tokens x {L} layers", flush=True)
+    assert errs["calibrated"] < 0.5 * errs["backbone alone"], errs
