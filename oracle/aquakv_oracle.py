@@ -49,6 +49,12 @@ notes of the repository):
     before it): when scoring, the decoded key of token t is rotated by position
     t, coordinate d paired with d + g/2, angles from caller-supplied cos / sin
     tables; the query is taken as already rotated.
+  * value side of attention (Sect. 2 "Transformer attention": the output is the
+    weighted sum of the cached values): the paper's experiments hand the decoded
+    tensors to a stock attention; attn_values is that sum written out over the
+    storage-rounded values of Alg. "decode", for weights the caller supplies
+    (softmax_rows of the scores in the plain case), grouped-query heads mapped as
+    in attn_scores.
 
 Pins (tests/test_oracle_pins.py): Hadamard orthogonality and Parseval, the
 Kronecker recursion, fast-butterfly agreement, inverse round trip, exact
@@ -64,7 +70,11 @@ rotary embedding: identity at position 0, norm preservation, the complex
 multiplication form, and scores that depend only on the position difference;
 for the round-to-nearest backbone: a group worked by hand, brute force over all
 levels, the half-step error bound, 0 decoding to 0, group independence, the
-2.50 / 2.03 bits of the paper's tables, closed loop through predictors.
+2.50 / 2.03 bits of the paper's tables, closed loop through predictors;
+for the value side: soft-max against scipy's routine, shift invariance and rows
+summing to one, one-hot weights returning a decoded row, uniform weights the
+mean, brute-force triple loop with the grouped-query head map, linearity in the
+weights, and the full attention against torch's scaled_dot_product_attention.
 No function here is "parity unpinned".
 """
 from __future__ import annotations
@@ -511,3 +521,35 @@ def attn_scores(layer: Layer, batch: int, seq_len: int, q, k_codes, k_scales, Kh
     for qh in range(q_heads):
         out[:, qh, :] = np.einsum("bd,btd->bt", q[:, qh, :], Khat[:, :, qh // rep, :])
     return score_scale * out
+
+
+def softmax_rows(scores):
+    """Soft-max over the last axis: p = exp(s - max s) / sum exp(s - max s) (the attention weights of
+    Sect. 2 "Transformer attention"; subtracting the row maximum changes nothing mathematically)."""
+    s = np.asarray(scores, dtype=np.float64)
+    e = np.exp(s - s.max(axis=-1, keepdims=True))
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+def attn_values(layer: Layer, batch: int, seq_len: int, weights, v_codes, v_scales, Vhat_prev=None, Khat=None):
+    """out[b, qh, :] = sum_t weights[b, qh, t] * Vhat[b, t, kvh(qh), :]  and Vhat itself.
+
+    Vhat is the storage-rounded reconstruction of the values of Alg. "decode" (second line:
+    Q^{-1}(V_q) + f_value([Vhat_prev; Khat])); query head qh reads kv head qh // (q_heads // kv_heads).
+    The weighted sum is the value side of attention (Sect. 2): with weights = softmax_rows(scores) it is
+    the attention output over the cached tokens.  weights: [batch, q_heads, seq_len], any real numbers.
+    Returns (out [batch, q_heads, head_dim], Vhat [batch*seq_len, kv_heads, head_dim]).
+    """
+    w = np.asarray(weights, dtype=np.float64)
+    T = batch * seq_len
+    gshape = (T, layer.groups_per_token, layer.group)
+    P_v = _value_prediction(layer, Vhat_prev, Khat, T).reshape(gshape)
+    Vhat = round_storage(_dequantize_stored(layer, v_codes, v_scales, _group_signs(layer.signs_v, layer), T) + P_v,
+                         layer.dtype)
+    Vhat = Vhat.reshape(batch, seq_len, layer.kv_heads, layer.head_dim)
+    q_heads = w.shape[1]
+    rep = q_heads // layer.kv_heads
+    out = np.empty((batch, q_heads, layer.head_dim))
+    for qh in range(q_heads):
+        out[:, qh, :] = np.einsum("bt,btd->bd", w[:, qh, :], Vhat[:, :, qh // rep, :])
+    return out, Vhat.reshape(T, layer.kv_heads, layer.head_dim)

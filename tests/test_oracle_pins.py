@@ -321,6 +321,76 @@ def test_scores_second_route_and_gqa_mapping(grid16):
     assert np.allclose(sc[0, 5, 3], 0.25 * q[0, 5] @ Khat[0, 3, 1], atol=1e-12)
 
 
+# ------------------------------------------------------------------ value side of attention
+def test_softmax_rows_against_scipy_shift_invariance_and_unit_sum():
+    from scipy.special import softmax as sp_softmax
+    s = rng(31).standard_normal((3, 4, 17)) * 5
+    p = O.softmax_rows(s)
+    assert np.allclose(p, sp_softmax(s, axis=-1), rtol=1e-14, atol=0)
+    assert np.allclose(p.sum(-1), 1.0, atol=1e-15)
+    assert np.allclose(O.softmax_rows(s + 1000.0), p, rtol=1e-12)       # no overflow, same weights
+    assert np.allclose(O.softmax_rows(np.log(np.array([[1.0, 2.0, 5.0]]))), [[0.125, 0.25, 0.625]], rtol=1e-15)
+
+
+def test_attn_values_special_weights_brute_force_and_head_map():
+    H, g, B, S, QH = 2, 128, 2, 6, 6
+    D = H * g
+    Wk = O.round_bf16(0.8 * np.eye(D) + rng(39).standard_normal((D, D)) / (4 * math.sqrt(D)))
+    Wv = O.round_bf16(np.concatenate([0.6 * np.eye(D), 0.2 * np.eye(D)], axis=1) + rng(40).standard_normal((D, 2 * D)) / (4 * math.sqrt(D)))
+    lay0 = _layer(H=H, g=g, dtype="bf16")
+    lay = _layer(H=H, g=g, dtype="bf16", w_k=Wk, w_v=Wv)
+    K0, V0 = (O.round_bf16(rng(s).standard_normal((B * S, H, g))) for s in (41, 42))
+    e0 = O.encode_layer(lay0, K0, V0)
+    K1 = O.round_bf16(0.8 * K0 + 0.3 * rng(43).standard_normal(K0.shape))
+    V1 = O.round_bf16(0.8 * V0 + 0.3 * rng(44).standard_normal(K0.shape))
+    e1 = O.encode_layer(lay, K1, V1, e0["Khat"], e0["Vhat"])
+    args = (e1["v_codes"], e1["v_scales"], e0["Vhat"], e1["Khat"])
+    _, Vhat = O.decode_layer(lay, e1["k_codes"], e1["k_scales"], e1["v_codes"], e1["v_scales"], e0["Khat"], e0["Vhat"])
+    V4 = Vhat.reshape(B, S, H, g)
+    rep = QH // H
+    # one-hot weights return one decoded row of the kv head that serves the query head
+    w = np.zeros((B, QH, S))
+    for b in range(B):
+        for qh in range(QH):
+            w[b, qh, (3 * b + qh) % S] = 1.0
+    out, Vh2 = O.attn_values(lay, B, S, w, *args)
+    assert np.array_equal(Vh2, Vhat)
+    for b in range(B):
+        for qh in range(QH):
+            assert np.array_equal(out[b, qh], V4[b, (3 * b + qh) % S, qh // rep])
+    # uniform weights: the mean over the sequence
+    out, _ = O.attn_values(lay, B, S, np.full((B, QH, S), 1.0 / S), *args)
+    assert np.allclose(out[1, 4], V4[1, :, 4 // rep].mean(axis=0), rtol=1e-13, atol=1e-15)
+    # brute force, and linearity in the weights
+    wa, wb = rng(45).standard_normal((2, B, QH, S))
+    oa, _ = O.attn_values(lay, B, S, wa, *args)
+    ob, _ = O.attn_values(lay, B, S, wb, *args)
+    oc, _ = O.attn_values(lay, B, S, 2.0 * wa - 0.5 * wb, *args)
+    assert np.allclose(oc, 2.0 * oa - 0.5 * ob, rtol=0, atol=1e-12)
+    for b in range(B):
+        for qh in range(QH):
+            for d in (0, 77, 127):
+                acc = 0.0
+                for t in range(S):
+                    acc += wa[b, qh, t] * V4[b, t, qh // rep, d]
+                assert abs(acc - oa[b, qh, d]) < 1e-12
+
+
+def test_scores_softmax_values_are_torch_attention_over_the_decoded_cache():
+    H, g, B, S, QH = 2, 128, 2, 9, 4
+    lay = _layer(H=H, g=g, dtype="fp32")
+    K, V = (O.round_fp32(rng(s).standard_normal((B * S, H, g))) for s in (51, 52))
+    e = O.encode_layer(lay, K, V)
+    q = O.round_fp32(rng(53).standard_normal((B, QH, g)))
+    scale = 1.0 / math.sqrt(g)
+    p = O.softmax_rows(O.attn_scores(lay, B, S, q, e["k_codes"], e["k_scales"], score_scale=scale))
+    out, _ = O.attn_values(lay, B, S, p, e["v_codes"], e["v_scales"])
+    Khat, Vhat = (torch.from_numpy(e[k].reshape(B, S, H, g)).permute(0, 2, 1, 3).repeat_interleave(QH // H, dim=1)
+                  for k in ("Khat", "Vhat"))
+    want = torch.nn.functional.scaled_dot_product_attention(torch.from_numpy(q)[:, :, None, :], Khat, Vhat)
+    assert np.allclose(out, want[:, :, 0, :].numpy(), rtol=1e-12, atol=1e-13)
+
+
 # ------------------------------------------------------------------ rotary embedding of the decoded keys
 def test_rope_is_a_rotation_by_the_token_angle():
     g, S = 128, 37
