@@ -125,6 +125,8 @@ class Buffers:
         self.ev_k = [torch.cuda.Event() for _ in layers]
         self.ev_v = [torch.cuda.Event() for _ in layers]
         self.scores = torch.empty(1, q_heads, T, dtype=torch.float32, device=device)
+        self.attn_out = torch.empty(1, q_heads, lay.head_dim, dtype=torch.float32, device=device)
+        self.ws_weighted = lay.alloc_weighted_workspace(1, T, q_heads, device)
         self.P = torch.empty(T, lay.d, dtype=torch.float32, device=device)
         # the scoring call folds the predictor into the query iff it is handed this workspace
         from paper_2501_19392_amd import binding as B
@@ -149,6 +151,19 @@ def decode_sweep_with_scores(B, layers, buf, q, T, q_heads):
         Kh, Vh = buf.hat[l & 1]
         B.aquakv_decode_attn_scores(lay, 1, T, q_heads, kc, ks, prev[0], q, SCORE_SCALE, buf.scores, Kh, buf.ws)
         B.aquakv_decode_values(lay, T, vc, vs, prev[1], Kh, Vh, buf.ws)
+        prev = (Kh, Vh)
+
+
+def decode_sweep_with_attention(B, layers, buf, q, T, q_heads):
+    """The decode sweep with the whole attention of one query over the cache as a by-product: scores from the key
+    half, soft-max over the sequence, and the value half with the weighted sum over tokens taken in its epilogue."""
+    prev = (None, None)
+    for l, lay in enumerate(layers):
+        (kc, ks), (vc, vs) = buf.codes[l]
+        Kh, Vh = buf.hat[l & 1]
+        B.aquakv_decode_attn_scores(lay, 1, T, q_heads, kc, ks, prev[0], q, SCORE_SCALE, buf.scores, Kh, buf.ws)
+        B.aquakv_softmax(q_heads, T, buf.scores, buf.scores)
+        B.aquakv_decode_values_weighted(lay, 1, T, q_heads, vc, vs, prev[1], Kh, buf.scores, Vh, buf.attn_out, buf.ws_weighted)
         prev = (Kh, Vh)
 
 
@@ -221,17 +236,21 @@ def run_step_two_streams(B, layers, Ks, Vs, buf, q, T, q_heads, scores_in_sweep=
 
 def timed_phases(B, layers, Ks, Vs, buf, q, T, q_heads, reps, streams=1, scores_in_sweep=False):
     """Per-phase GPU time (ms per step) from stream events: encode / decode / scores (scoring calls of their own),
-    and decode+scores (the decode sweep that also yields the scores) when that is the step's form."""
+    and, when that is the step's form, decode+scores (the decode sweep that also yields the scores) and, for
+    reference only, decode+attention (that sweep with soft-max and the weighted sum over the values as well)."""
     import torch
     ev = lambda: torch.cuda.Event(enable_timing=True)
     out = {}
-    for phase in ("encode", "decode", "scores") + (("decode+scores",) if scores_in_sweep else ()):
+    for phase in ("encode", "decode", "scores") + (("decode+scores", "decode+attention") if scores_in_sweep else ()):
         a, b = ev(), ev()
         torch.cuda.synchronize()
         a.record()
         for _ in range(reps):
             if phase == "decode+scores":
                 decode_sweep_with_scores(B, layers, buf, q, T, q_heads)
+                continue
+            if phase == "decode+attention":       # for reference: not part of the step
+                decode_sweep_with_attention(B, layers, buf, q, T, q_heads)
                 continue
             if streams == 2 and phase != "scores":
                 chains_on_two_streams(B, layers, Ks, Vs, buf, T, phase)      # joined into the current stream

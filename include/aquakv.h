@@ -257,6 +257,40 @@ int aquakv_decode_attn_scores_rope(const aquakv_layer* layer, int32_t batch, int
                                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Value side of attention over the compressed cache (Alg. "Inference": the block call attends over the
+ * recovered keys and values, its output is the weighted sum of the values; Sect. 5 of the paper names the integration of the cache with
+ * attention as the step its own implementation leaves open).
+ *
+ * aquakv_softmax -- probs[r, :] = exp(s - max s) / sum exp(s - max s) over each of `rows` rows of
+ *   n fp32 values (device memory; probs may be scores: in place).  rows = batch * q_heads and
+ *   n = seq_len turns the scores of aquakv_decode_attn_scores into attention weights.
+ *
+ * aquakv_decode_values_weighted -- decode of the values (Alg. "decode", second line) together with
+ *   out[b, qh, :] = sum_t weights[b, qh, t] * Vhat[b*seq_len + t, qh / (q_heads/H), :],
+ *   Vhat being the storage-rounded reconstruction (what aquakv_decode_values writes).
+ *   weights: device, fp32 [batch, q_heads, seq_len], any real numbers (soft-max rows in the plain case;
+ *   a caller that also attends to tokens outside the compressed cache normalises over all of them
+ *   and adds their share itself).  out: device, fp32 [batch, q_heads, g].  Vhat (dtype,
+ *   [batch*seq_len, H, g]) receives the decoded values, which the next layer's predictor reads.
+ *   For bf16 layers with a value predictor, rotation groups of one head and seq_len a multiple of 256
+ *   the sums are taken inside the decode kernel from the values it holds
+ *   on chip (weights enter as bf16 pairs hi + lo, i.e. with 16 mantissa bits; products accumulate in
+ *   fp32), and Vhat may then be NULL: nothing but `out` is written (the last layer of a sweep).
+ *   Otherwise Vhat is required, the values are decoded to it first and summed from there in fp32.
+ *   q_heads must be a multiple of H with q_heads / H <= 8.  `workspace`: at least
+ *   aquakv_weighted_workspace_bytes() bytes, holding the per-256-token partial sums (added in token
+ *   order: the result does not depend on scheduling) and, for layers that are not fused, the fp32
+ *   prediction.  Errors as for aquakv_decode_values.
+ */
+int aquakv_softmax(int64_t rows, int64_t n, const float* scores, float* probs, void* stream);
+size_t aquakv_weighted_workspace_bytes(const aquakv_layer* layer, int32_t batch, int32_t seq_len, int32_t q_heads);
+int aquakv_decode_values_weighted(const aquakv_layer* layer, int32_t batch, int32_t seq_len, int32_t q_heads,
+                                  const uint8_t* v_codes, const uint16_t* v_scales,
+                                  const void* Vhat_prev, const void* Khat, const float* weights,
+                                  void* Vhat, float* out,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * aquakv_fit_predictor -- calibration of one predictor (Alg. "Calibration", Sect. 3.2): the linear map that best
  * predicts Y from X = [x0 | x1] in the least-squares sense,
  *     W = argmin || X W^T - Y ||^2 + lambda ||W||^2,   lambda = rate * trace(X^T X) / d_in   (rate = 0: plain

@@ -49,8 +49,8 @@ notes of the repository):
     before it): when scoring, the decoded key of token t is rotated by position
     t, coordinate d paired with d + g/2, angles from caller-supplied cos / sin
     tables; the query is taken as already rotated.
-  * value side of attention (Sect. 2 "Transformer attention": the output is the
-    weighted sum of the cached values): the paper's experiments hand the decoded
+  * value side of attention (Alg. "Inference": the block call attends over the
+    recovered keys and values; its output is the weighted sum of the values): the paper's experiments hand the decoded
     tensors to a stock attention; attn_values is that sum written out over the
     storage-rounded values of Alg. "decode", for weights the caller supplies
     (softmax_rows of the scores in the plain case), grouped-query heads mapped as
@@ -524,8 +524,8 @@ def attn_scores(layer: Layer, batch: int, seq_len: int, q, k_codes, k_scales, Kh
 
 
 def softmax_rows(scores):
-    """Soft-max over the last axis: p = exp(s - max s) / sum exp(s - max s) (the attention weights of
-    Sect. 2 "Transformer attention"; subtracting the row maximum changes nothing mathematically)."""
+    """Soft-max over the last axis: p = exp(s - max s) / sum exp(s - max s) (the attention weights of the
+    block call in Alg. "Inference"; subtracting the row maximum changes nothing mathematically)."""
     s = np.asarray(scores, dtype=np.float64)
     e = np.exp(s - s.max(axis=-1, keepdims=True))
     return e / e.sum(axis=-1, keepdims=True)
@@ -536,7 +536,7 @@ def attn_values(layer: Layer, batch: int, seq_len: int, weights, v_codes, v_scal
 
     Vhat is the storage-rounded reconstruction of the values of Alg. "decode" (second line:
     Q^{-1}(V_q) + f_value([Vhat_prev; Khat])); query head qh reads kv head qh // (q_heads // kv_heads).
-    The weighted sum is the value side of attention (Sect. 2): with weights = softmax_rows(scores) it is
+    The weighted sum is the value side of attention (block call of Alg. "Inference"): with weights = softmax_rows(scores) it is
     the attention output over the cached tokens.  weights: [batch, q_heads, seq_len], any real numbers.
     Returns (out [batch, q_heads, head_dim], Vhat [batch*seq_len, kv_heads, head_dim]).
     """

@@ -4,8 +4,9 @@
 // then the backbone quantizer of Sect. 2 (or its inverse) to the same rows.  One workgroup
 // (8 wavefronts) computes a 256-row x 128-column tile of the prediction on the matrix cores -- 128 columns
 // are exactly one kv head = one rotation group per row -- parks it in LDS in fp32, and runs
-// the quantizer (encode), its inverse (decode), or its inverse plus the grouped-query q.k
-// dot products (scores) on those 256 groups as the epilogue.  Against separate kernels this
+// the quantizer (encode), its inverse (decode), its inverse plus the grouped-query q.k
+// dot products (scores), or its inverse plus the weighted sum over the tile's tokens that the
+// value side of attention needs (weighted), on those 256 groups as the epilogue.  Against separate kernels this
 // saves writing and re-reading 4 bytes per value of fp32 predictions and a launch.
 //
 // Arithmetic is the same as in the stand-alone kernels (same main loop, same group bodies,
@@ -33,7 +34,19 @@ constexpr int kEpilogueLdsBytes = kPredBytes + (int)sizeof(Lds);
 constexpr int kFusedLdsBytes = kEpilogueLdsBytes > kMainLoopLdsBytes ? kEpilogueLdsBytes : kMainLoopLdsBytes;
 static_assert(kFusedLdsBytes <= 160 * 1024, "LDS of one CU");
 
-enum Mode : int { kEncode = 0, kDecode = 1, kScores = 2 };
+enum Mode : int { kEncode = 0, kDecode = 1, kScores = 2, kWeighted = 3 };
+
+// kWeighted: a wave keeps the bf16 values it decodes (32 token rows x 128) in the part of its parked rows it has
+// already consumed, one row every kVRowBytes (264 B: rows 8 apart then sit 16 banks apart, which makes the
+// token-strided 2-byte reads of the matrix-core operand conflict free), followed by its share of the sums
+// (16 head slots x 128 fp32).
+constexpr int kVRowBytes = kGroup * 2 + 8;
+constexpr int kVBufBytes = 32 * kVRowBytes;          // 8448 = exactly 16 parked rows
+static_assert(kVBufBytes == 16 * kLdP * 4, "the decoded rows of both passes fill the first pass's parked rows");
+static_assert(kVBufBytes + 16 * kGroup * 4 <= 32 * kLdP * 4, "sums fit behind the decoded rows");
+typedef unsigned int u32x2_alias __attribute__((ext_vector_type(2), may_alias));
+typedef unsigned short u16_alias __attribute__((may_alias));
+typedef float f32_alias __attribute__((may_alias));
 
 template <int NCW, int MODE, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
@@ -41,7 +54,8 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
     const float* __restrict__ bias, const int8_t* __restrict__ signs, const float* __restrict__ codebook,
     const uint32_t* __restrict__ table, const bf16_t* X, uint8_t* codes, uint16_t* scales, bf16_t* Xhat,
     const bf16_t* __restrict__ qv, float score_scale, float* __restrict__ scores, int seq_len, int q_heads, int64_t T,
-    int D, const float* __restrict__ rope_cos, const float* __restrict__ rope_sin) {
+    int D, const float* __restrict__ rope_cos, const float* __restrict__ rope_sin, const float* __restrict__ weights,
+    float* __restrict__ part) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[kFusedLdsBytes];
   Lds& cl = *reinterpret_cast<Lds*>(smem + kPredBytes);
   const bool use_table = MODE == kEncode && table != nullptr;
@@ -108,10 +122,24 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
     }
   };
 
+  // kWeighted: the attention weights of query head slot lane % 16 (of this kv head) for 8 of the wave's 32 token rows,
+  // in the layout of the A operand of the 16x16x32 matrix instruction; slots beyond the group's heads stay zero.
+  // The launcher guarantees seq_len % BM == 0, so a tile lies inside one sequence and has no rows beyond T.
+  u32x4 wreg[2] = {};
   f32x16 acc[MI][4];
   gemm_mainloop<WAVES>(smem, x0, d0, x1, d1, W, T, m0, n0, acc, [&] {
 #pragma unroll
     for (int pass = 0; pass < kPasses; ++pass) fetch(pass, in[pass]);
+    if constexpr (MODE == kWeighted) {
+      static_assert(MODE != kWeighted || kRowsPerWave == 32, "one 32-token contraction per wave");
+      const int rep = q_heads / H, slot = lane & 15;
+      if (slot < rep) {
+        const int64_t r0 = m0 + wave * kRowsPerWave + 8 * (lane >> 4);
+        const int64_t b = r0 / seq_len, t = r0 % seq_len;
+        const u32x4* src = reinterpret_cast<const u32x4*>(weights + (b * q_heads + head * rep + slot) * seq_len + t);
+        wreg[0] = src[0]; wreg[1] = src[1];
+      }
+    }
   });
 
   // the LDS is free again: grid and table, then the tile (+ bias) parked row-major in fp32, each wave its own rows
@@ -170,6 +198,19 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
         reconstruct(v, q, sb, p);
       }
       if (Xhat != nullptr && active) Storage<bf16_t>::store32(Xhat + off, v);
+      if constexpr (MODE == kWeighted) {
+        // every parked row of this pass has been read by now (no load may sink below this point): the decoded
+        // rows, rounded as they are stored, go where the first pass's rows were
+        asm volatile("" ::: "memory");
+        unsigned char* dst = reinterpret_cast<unsigned char*>(wl) + lrow * kVRowBytes + q * (kValsPerLane * 2);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          u32x2_alias w2;
+          w2.x = Storage<bf16_t>::pack2(v[4 * k], v[4 * k + 1]);
+          w2.y = Storage<bf16_t>::pack2(v[4 * k + 2], v[4 * k + 3]);
+          *reinterpret_cast<u32x2_alias*>(dst + 8 * k) = w2;
+        }
+      }
       if constexpr (MODE == kScores) {
 #pragma unroll
         for (int r = 0; r < 32; ++r) v[r] = Storage<bf16_t>::round(v[r]);      // score the stored keys
@@ -194,6 +235,62 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
     do_pass(pass, in[pass]);
     __builtin_amdgcn_sched_barrier(0);
   }
+
+  if constexpr (MODE == kWeighted) {
+    // sums[slot][dim] = sum over the wave's 32 tokens of weight[slot][token] * Vhat[token][dim] on the matrix cores:
+    // 16 head slots x 16 dims x 32 tokens per instruction.  The weights go in as a bf16 pair hi + lo (hi = rounded
+    // weight, lo = rounded remainder), which carries 16 of their mantissa bits; the values are bf16 as stored.
+    typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4v;
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_wave_barrier();
+    const int rep = q_heads / H;
+    u32x4 whi, wlo;
+    {
+      const uint32_t wb[8] = {wreg[0].x, wreg[0].y, wreg[0].z, wreg[0].w, wreg[1].x, wreg[1].y, wreg[1].z, wreg[1].w};
+      uint32_t hi[4], lo[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float a = __uint_as_float(wb[2 * j]), b = __uint_as_float(wb[2 * j + 1]);
+        hi[j] = Storage<bf16_t>::pack2(a, b);
+        lo[j] = Storage<bf16_t>::pack2(a - __uint_as_float(hi[j] << 16), b - __uint_as_float(hi[j] & 0xffff0000u));
+      }
+      whi.x = hi[0]; whi.y = hi[1]; whi.z = hi[2]; whi.w = hi[3];
+      wlo.x = lo[0]; wlo.y = lo[1]; wlo.z = lo[2]; wlo.w = lo[3];
+    }
+    const bf16x8 a_hi = __builtin_bit_cast(bf16x8, whi), a_lo = __builtin_bit_cast(bf16x8, wlo);
+    const int n = lane & 15, kg = lane >> 4;
+    const unsigned char* vb = reinterpret_cast<const unsigned char*>(wl) + kg * 8 * kVRowBytes + n * 2;
+    f32_alias* red = reinterpret_cast<f32_alias*>(reinterpret_cast<unsigned char*>(wl) + kVBufBytes);
+#pragma unroll
+    for (int nb = 0; nb < kGroup / 16; ++nb) {
+      u32x4 bw;
+      uint32_t bq[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t e0 = *reinterpret_cast<const u16_alias*>(vb + (2 * j) * kVRowBytes + nb * 32);
+        const uint32_t e1 = *reinterpret_cast<const u16_alias*>(vb + (2 * j + 1) * kVRowBytes + nb * 32);
+        bq[j] = e0 | (e1 << 16);
+      }
+      bw.x = bq[0]; bw.y = bq[1]; bw.z = bq[2]; bw.w = bq[3];
+      const bf16x8 bfrag = __builtin_bit_cast(bf16x8, bw);
+      f32x4v c = {0.f, 0.f, 0.f, 0.f};
+      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo, bfrag, c, 0, 0, 0);
+      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi, bfrag, c, 0, 0, 0);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        red[(4 * kg + r) * kGroup + nb * 16 + n] = c[r];     // row 4 kg + r of the product; rows beyond rep are zero
+      }
+    }
+    __syncthreads();
+    // the tile's sums: the 8 waves' shares added in wave order
+    for (int idx = threadIdx.x; idx < rep * kGroup; idx += WAVES * 64) {
+      float sum = 0.f;
+#pragma unroll
+      for (int w = 0; w < WAVES; ++w)
+        sum += *reinterpret_cast<const f32_alias*>(smem + (size_t)w * kRowsPerWave * kLdP * 4 + kVBufBytes + idx * 4);
+      part[((int64_t)tile_m * q_heads + head * rep + idx / kGroup) * kGroup + idx % kGroup] = sum;
+    }
+  }
 }
 
 // n_codewords: the quantizer id (grid size, or kRtn2 / kRtn4)
@@ -201,7 +298,8 @@ template <int MODE>
 hipError_t launch(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W, const float* bias,
                   const int8_t* signs, const float* codebook, const void* table, const void* X, uint8_t* codes,
                   uint16_t* scales, void* Xhat, const void* q, float score_scale, float* scores, int seq_len,
-                  int q_heads, int64_t T, int D, const float* rope_cos, const float* rope_sin, hipStream_t stream) {
+                  int q_heads, int64_t T, int D, const float* rope_cos, const float* rope_sin, const float* weights,
+                  float* part, hipStream_t stream) {
   if (T == 0) return hipSuccess;
   const unsigned blocks = (unsigned)(((T + BM - 1) / BM) * (D / BN));
   // 8 wavefronts per tile (two per SIMD): the main loop is bound by L2 -> LDS traffic either
@@ -216,7 +314,7 @@ hipError_t launch(int n_codewords, const void* x0, int d0, const void* x1, int d
       static_cast<const bf16_t*>(x0), d0, static_cast<const bf16_t*>(x1), d1, static_cast<const bf16_t*>(W), bias, \
       signs, codebook, static_cast<const uint32_t*>(table), static_cast<const bf16_t*>(X), codes, scales,         \
       static_cast<bf16_t*>(Xhat), static_cast<const bf16_t*>(q), score_scale, scores, seq_len, q_heads, T, D, rope_cos,  \
-      rope_sin)
+      rope_sin, weights, part)
   if (n_codewords == kRtn2) AQUAKV_FUSED(kRtn2);
   else if (n_codewords == kRtn4) AQUAKV_FUSED(kRtn4);
   else if (n_codewords == 16) AQUAKV_FUSED(16);
@@ -233,7 +331,7 @@ hipError_t launch_fused_encode(int n_codewords, const void* x0, int d0, const vo
                                const void* X, uint8_t* codes, uint16_t* scales, void* Xhat, int64_t T, int D,
                                hipStream_t stream) {
   return launch<kEncode>(n_codewords, x0, d0, x1, d1, W, bias, signs, codebook, table, X, codes, scales, Xhat, nullptr,
-                         0.f, nullptr, 1, 1, T, D, nullptr, nullptr, stream);
+                         0.f, nullptr, 1, 1, T, D, nullptr, nullptr, nullptr, nullptr, stream);
 }
 
 hipError_t launch_fused_decode(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W,
@@ -241,7 +339,7 @@ hipError_t launch_fused_decode(int n_codewords, const void* x0, int d0, const vo
                                const uint16_t* scales, void* Xhat, int64_t T, int D, hipStream_t stream) {
   return launch<kDecode>(n_codewords, x0, d0, x1, d1, W, bias, signs, codebook, nullptr, nullptr,
                          const_cast<uint8_t*>(codes), const_cast<uint16_t*>(scales), Xhat, nullptr, 0.f, nullptr, 1, 1,
-                         T, D, nullptr, nullptr, stream);
+                         T, D, nullptr, nullptr, nullptr, nullptr, stream);
 }
 
 hipError_t launch_fused_scores(int n_codewords, const void* x0, int d0, const void* W, const float* bias,
@@ -251,7 +349,16 @@ hipError_t launch_fused_scores(int n_codewords, const void* x0, int d0, const vo
                                hipStream_t stream) {
   return launch<kScores>(n_codewords, x0, d0, nullptr, 0, W, bias, signs, codebook, nullptr, nullptr,
                          const_cast<uint8_t*>(codes), const_cast<uint16_t*>(scales), Khat_out, q, score_scale, scores,
-                         seq_len, q_heads, T, D, rope_cos, rope_sin, stream);
+                         seq_len, q_heads, T, D, rope_cos, rope_sin, nullptr, nullptr, stream);
+}
+
+hipError_t launch_fused_weighted(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W,
+                                 const float* bias, const int8_t* signs, const float* codebook, const uint8_t* codes,
+                                 const uint16_t* scales, void* Xhat, const float* weights, float* part, int seq_len,
+                                 int q_heads, int64_t T, int D, hipStream_t stream) {
+  return launch<kWeighted>(n_codewords, x0, d0, x1, d1, W, bias, signs, codebook, nullptr, nullptr,
+                           const_cast<uint8_t*>(codes), const_cast<uint16_t*>(scales), Xhat, nullptr, 0.f, nullptr,
+                           seq_len, q_heads, T, D, nullptr, nullptr, weights, part, stream);
 }
 
 }  // namespace aquakv

@@ -1,0 +1,138 @@
+// Value side of attention over the decoded cache (Alg. "Inference" of the AQUA-KV paper: the block call attends over
+// the recovered keys and values; its output is the weighted sum of the values): soft-max of the score rows, the weighted sum over values
+// that already sit in memory, and the reduction of the per-chunk sums that both this kernel and the fused
+// decode kernel leave behind.  All sums run in a fixed order, so a call gives the same bits every time.
+#include "device_utils.h"
+#include "kernels.h"
+
+namespace aquakv {
+namespace {
+
+constexpr int kThreads = 256;
+
+// Block-wide reduction in a fixed tree order; every thread gets the result.
+template <bool MAX> __device__ __forceinline__ float block_reduce(float x, float* buf) {
+  buf[threadIdx.x] = x;
+  __syncthreads();
+#pragma unroll
+  for (int s = kThreads / 2; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) {
+      const float a = buf[threadIdx.x], b = buf[threadIdx.x + s];
+      buf[threadIdx.x] = MAX ? fmaxf(a, b) : a + b;
+    }
+    __syncthreads();
+  }
+  const float r = buf[0];
+  __syncthreads();
+  return r;
+}
+
+// One workgroup per row: p = exp(s - max) / sum exp(s - max).
+__global__ __launch_bounds__(kThreads) void softmax_rows_kernel(const float* scores, float* probs, int64_t n) {
+  __shared__ float buf[kThreads];
+  const float* s = scores + (int64_t)blockIdx.x * n;
+  float* p = probs + (int64_t)blockIdx.x * n;
+  float m = -INFINITY;
+  for (int64_t i = threadIdx.x; i < n; i += kThreads) m = fmaxf(m, s[i]);
+  m = block_reduce<true>(m, buf);
+  float sum = 0.f;
+  for (int64_t i = threadIdx.x; i < n; i += kThreads) sum += expf(s[i] - m);
+  sum = block_reduce<false>(sum, buf);
+  const float inv = 1.0f / sum;
+  for (int64_t i = threadIdx.x; i < n; i += kThreads) p[i] = expf(s[i] - m) * inv;
+}
+
+template <typename T> __device__ __forceinline__ void load8(const T* p, float (&v)[8]);
+template <> __device__ __forceinline__ void load8<float>(const float* p, float (&v)[8]) {
+  const f32x4 a = reinterpret_cast<const f32x4*>(p)[0], b = reinterpret_cast<const f32x4*>(p)[1];
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+template <> __device__ __forceinline__ void load8<bf16_t>(const bf16_t* p, float (&v)[8]) {
+  unpack_bf16x8(*reinterpret_cast<const u32x4*>(p), v);
+}
+
+// One workgroup per (sequence, chunk of 256 tokens, kv head).  Thread (tsub = tid / 16, l = tid % 16) walks tokens
+// tsub, tsub + 16, ... of the chunk and owns dims 8 l .. 8 l + 7; the 16 token classes are added through LDS.
+// The chunk is re-read (from cache) once per query head of the group: this is the path for what the fused
+// kernel does not cover, not the fast one.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void weighted_values_kernel(const T* __restrict__ Vhat, const float* __restrict__ weights,
+                                                                   float* __restrict__ part, int seq_len, int H, int q_heads,
+                                                                   int chunks_per_seq) {
+  __shared__ float red[16][kGroup];
+  const int b = blockIdx.x / chunks_per_seq, chunk = blockIdx.x % chunks_per_seq, head = blockIdx.y;
+  const int rep = q_heads / H;
+  const int tsub = threadIdx.x >> 4, l = threadIdx.x & 15;
+  const int t0 = chunk * kWeightedChunk;
+  const T* vbase = Vhat + ((int64_t)b * seq_len * H + head) * kGroup + l * 8;
+  for (int r = 0; r < rep; ++r) {
+    const int qh = head * rep + r;
+    const float* w = weights + ((int64_t)b * q_heads + qh) * seq_len;
+    float acc[8] = {};
+    for (int it = 0; it < kWeightedChunk / 16; ++it) {
+      const int t = t0 + it * 16 + tsub;
+      if (t < seq_len) {
+        float v[8];
+        load8<T>(vbase + (int64_t)t * H * kGroup, v);
+        const float wt = w[t];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = __fmaf_rn(wt, v[i], acc[i]);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) red[tsub][l * 8 + i] = acc[i];
+    __syncthreads();
+    if (threadIdx.x < kGroup) {
+      float sum = 0.f;
+#pragma unroll
+      for (int k = 0; k < 16; ++k) sum += red[k][threadIdx.x];
+      part[((int64_t)blockIdx.x * q_heads + qh) * kGroup + threadIdx.x] = sum;
+    }
+    __syncthreads();
+  }
+}
+
+// out[b, qh, d] = chunk sums added in chunk order
+__global__ __launch_bounds__(kThreads) void combine_weighted_kernel(const float* __restrict__ part, float* __restrict__ out,
+                                                                    int chunks_per_seq, int row, int64_t total) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;       // index into out[batch][row], row = q_heads * 128
+  if (i >= total) return;
+  const int64_t b = i / row, j = i % row;
+  const float* src = part + b * chunks_per_seq * row + j;
+  float sum = 0.f;
+  for (int c = 0; c < chunks_per_seq; ++c) sum += src[(int64_t)c * row];
+  out[i] = sum;
+}
+
+}  // namespace
+
+hipError_t launch_softmax_rows(const float* scores, float* probs, int64_t rows, int64_t n, hipStream_t stream) {
+  if (rows == 0 || n == 0) return hipSuccess;
+  softmax_rows_kernel<<<(unsigned)rows, kThreads, 0, stream>>>(scores, probs, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_weighted_values(int dtype, const void* Vhat, const float* weights, float* part, int batch, int seq_len,
+                                  int H, int q_heads, hipStream_t stream) {
+  if (batch == 0 || seq_len == 0) return hipSuccess;
+  const int chunks = (seq_len + kWeightedChunk - 1) / kWeightedChunk;
+  const dim3 grid((unsigned)batch * chunks, (unsigned)H);
+  if (dtype == kBF16)
+    weighted_values_kernel<bf16_t><<<grid, kThreads, 0, stream>>>(static_cast<const bf16_t*>(Vhat), weights, part, seq_len, H,
+                                                                  q_heads, chunks);
+  else
+    weighted_values_kernel<float><<<grid, kThreads, 0, stream>>>(static_cast<const float*>(Vhat), weights, part, seq_len, H,
+                                                                 q_heads, chunks);
+  return hipGetLastError();
+}
+
+hipError_t launch_combine_weighted(const float* part, float* out, int batch, int seq_len, int q_heads, hipStream_t stream) {
+  if (batch == 0) return hipSuccess;
+  const int chunks = (seq_len + kWeightedChunk - 1) / kWeightedChunk;
+  const int row = q_heads * kGroup;
+  const int64_t total = (int64_t)batch * row;
+  combine_weighted_kernel<<<(unsigned)((total + kThreads - 1) / kThreads), kThreads, 0, stream>>>(part, out, chunks, row, total);
+  return hipGetLastError();
+}
+
+}  // namespace aquakv

@@ -159,6 +159,50 @@ def test_half_calls_validate_their_arguments():
     assert status_of(B.aquakv_encode_values, L0, 8, FAKE, None, None, None, FAKE, FAKE, ws) == B.AQUAKV_ENULL  # v_codes
 
 
+def test_weighted_values_call_validates_its_arguments():
+    """Value side of attention: argument checks and the workspace size (partial sums per 256 tokens, plus the
+    fp32 prediction where the layer does not run fused)."""
+    L = layer()
+    ws = (FAKE, 1 << 30)
+    ok = [FAKE] * 7                       # v_codes v_scales Vhat_prev Khat weights Vhat out
+    call = B.aquakv_decode_values_weighted
+    assert B.aquakv_weighted_workspace_bytes(L, 1, 8192, 24) == 32 * 24 * 128 * 4
+    assert B.aquakv_weighted_workspace_bytes(L, 3, 257, 8) == 3 * 2 * 8 * 128 * 4
+    assert B.aquakv_weighted_workspace_bytes(L, 1, 100, 8) == 8 * 128 * 4
+    L32 = layer(dtype=B.AQUAKV_FP32)
+    assert B.aquakv_weighted_workspace_bytes(L32, 1, 100, 8) == 8 * 128 * 4 + 100 * 1024 * 4
+    assert B.aquakv_weighted_workspace_bytes(L, 0, 100, 8) == 0
+    assert B.aquakv_weighted_workspace_bytes(layer(head_dim=64), 1, 100, 8) == 0
+    assert status_of(call, L, 1, 256, 12, *ok, ws) == B.AQUAKV_EINVAL                 # not a multiple of kv heads
+    assert status_of(call, L, 1, 256, 72, *ok, ws) == B.AQUAKV_EINVAL                 # more than 8 per kv head
+    assert status_of(call, L, -1, 256, 8, *ok, ws) == B.AQUAKV_EINVAL
+    for i, name in enumerate(["v_codes", "v_scales", "Vhat_prev", "Khat", "weights", None, "out"]):
+        if name is None:
+            continue
+        a = list(ok)
+        a[i] = None
+        assert status_of(call, L, 1, 256, 8, *a, ws) == B.AQUAKV_ENULL, name
+    a = list(ok)
+    a[4] = FAKE + 2
+    assert status_of(call, L, 1, 256, 8, *a, ws) == B.AQUAKV_EALIGN
+    a = list(ok)
+    a[5] = None                                                                     # no Vhat: only where the sums are fused
+    assert status_of(call, L, 1, 255, 8, *a, ws) == B.AQUAKV_ENULL                    # ragged sequence
+    assert status_of(call, L32, 1, 256, 8, *a, ws) == B.AQUAKV_ENULL
+    assert status_of(call, layer(rht_group=1024), 1, 256, 8, *a, ws) == B.AQUAKV_ENULL
+    assert status_of(call, layer(d_in_k=0, d_in_v=0, w_k=None, w_v=None), 1, 256, 8, FAKE, FAKE, None, None, FAKE, None,
+                     FAKE, ws) == B.AQUAKV_ENULL                                    # first layer
+    assert status_of(call, L, 1, 256, 8, *ok, (FAKE, 1024)) == B.AQUAKV_EWORKSPACE
+    assert status_of(call, L, 1, 256, 8, *ok, None) == B.AQUAKV_ENULL                 # workspace
+    call(L, 0, 256, 8, *ok, None)                                                   # no tokens: no-op
+    call(L, 1, 0, 8, *ok, None)
+    assert status_of(B.aquakv_softmax, 4, 10, None, FAKE) == B.AQUAKV_ENULL
+    assert status_of(B.aquakv_softmax, 4, 10, FAKE, None) == B.AQUAKV_ENULL
+    assert status_of(B.aquakv_softmax, -1, 10, FAKE, FAKE) == B.AQUAKV_EINVAL
+    B.aquakv_softmax(0, 10, FAKE, FAKE)
+    B.aquakv_softmax(4, 0, FAKE, FAKE)
+
+
 def test_round_to_nearest_backbone_layer_validation():
     """vq_dim = 1: the uniform round-to-nearest backbone (Sect. 4.1): 4 or 16 levels, groups of 64, no grid / signs,
     (step, zero point) words need 4-byte alignment."""
