@@ -27,7 +27,7 @@ template <bool MAX> __device__ __forceinline__ float block_reduce(float x, float
   return r;
 }
 
-// One workgroup per row: p = exp(s - max) / sum exp(s - max).
+// One workgroup per row: p = exp(s - max) / sum exp(s - max).  Any row length; three passes over the row.
 __global__ __launch_bounds__(kThreads) void softmax_rows_kernel(const float* scores, float* probs, int64_t n) {
   __shared__ float buf[kThreads];
   const float* s = scores + (int64_t)blockIdx.x * n;
@@ -40,6 +40,62 @@ __global__ __launch_bounds__(kThreads) void softmax_rows_kernel(const float* sco
   sum = block_reduce<false>(sum, buf);
   const float inv = 1.0f / sum;
   for (int64_t i = threadIdx.x; i < n; i += kThreads) p[i] = expf(s[i] - m) * inv;
+}
+
+// The same for rows of up to 1024 * 4 * VEC values with n % 4 == 0: 1024 threads hold the row in registers
+// (VEC 16-byte pieces each), so it is read once, and the two reductions go through the wavefronts' lanes
+// and then 16 partial results in LDS.
+constexpr int kWideThreads = 1024;
+template <bool MAX> __device__ __forceinline__ float wide_reduce(float x, float* buf) {
+#pragma unroll
+  for (int m = 1; m < 64; m <<= 1) {
+    const float y = __shfl_xor(x, m);
+    x = MAX ? fmaxf(x, y) : x + y;
+  }
+  if ((threadIdx.x & 63) == 0) buf[threadIdx.x >> 6] = x;
+  __syncthreads();
+  float r = buf[0];
+#pragma unroll
+  for (int w = 1; w < kWideThreads / 64; ++w) r = MAX ? fmaxf(r, buf[w]) : r + buf[w];
+  __syncthreads();
+  return r;
+}
+template <int VEC>
+__global__ __launch_bounds__(kWideThreads) void softmax_rows_regs_kernel(const float* scores, float* probs, int n4) {
+  __shared__ float buf[kWideThreads / 64];
+  const f32x4* s = reinterpret_cast<const f32x4*>(scores) + (int64_t)blockIdx.x * n4;
+  f32x4* p = reinterpret_cast<f32x4*>(probs) + (int64_t)blockIdx.x * n4;
+  f32x4 v[VEC];
+  float m = -INFINITY;
+#pragma unroll
+  for (int k = 0; k < VEC; ++k) {
+    const int i = threadIdx.x + k * kWideThreads;
+    if (i < n4) {
+      v[k] = s[i];
+      m = fmaxf(fmaxf(m, fmaxf(v[k].x, v[k].y)), fmaxf(v[k].z, v[k].w));
+    }
+  }
+  m = wide_reduce<true>(m, buf);
+  float sum = 0.f;
+#pragma unroll
+  for (int k = 0; k < VEC; ++k) {
+    const int i = threadIdx.x + k * kWideThreads;
+    if (i < n4) {
+      v[k].x = expf(v[k].x - m); v[k].y = expf(v[k].y - m); v[k].z = expf(v[k].z - m); v[k].w = expf(v[k].w - m);
+      sum += (v[k].x + v[k].y) + (v[k].z + v[k].w);
+    }
+  }
+  sum = wide_reduce<false>(sum, buf);
+  const float inv = 1.0f / sum;
+#pragma unroll
+  for (int k = 0; k < VEC; ++k) {
+    const int i = threadIdx.x + k * kWideThreads;
+    if (i < n4) {
+      f32x4 o;
+      o.x = v[k].x * inv; o.y = v[k].y * inv; o.z = v[k].z * inv; o.w = v[k].w * inv;
+      p[i] = o;
+    }
+  }
 }
 
 template <typename T> __device__ __forceinline__ void load8(const T* p, float (&v)[8]);
@@ -92,23 +148,50 @@ __global__ __launch_bounds__(kThreads) void weighted_values_kernel(const T* __re
   }
 }
 
-// out[b, qh, d] = chunk sums added in chunk order
+// out[b, qh, d] = sum of the chunk sums, in a fixed order.  A workgroup owns 32 consecutive outputs; thread
+// (k = tid / 32, j = tid % 32) adds the chunks c = k, k + 8, ... of output j (so every load of a wavefront is
+// two full 128-byte lines and the loads of a thread do not wait for each other), and the 8 running sums are
+// added in k order through LDS.
 __global__ __launch_bounds__(kThreads) void combine_weighted_kernel(const float* __restrict__ part, float* __restrict__ out,
                                                                     int chunks_per_seq, int row, int64_t total) {
-  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;       // index into out[batch][row], row = q_heads * 128
-  if (i >= total) return;
-  const int64_t b = i / row, j = i % row;
-  const float* src = part + b * chunks_per_seq * row + j;
-  float sum = 0.f;
-  for (int c = 0; c < chunks_per_seq; ++c) sum += src[(int64_t)c * row];
-  out[i] = sum;
+  __shared__ float red[8][32];
+  const int k = threadIdx.x >> 5, j32 = threadIdx.x & 31;
+  const int64_t i = (int64_t)blockIdx.x * 32 + j32;                     // index into out[batch][row], row = q_heads * 128
+  float acc = 0.f;
+  if (i < total) {
+    const int64_t b = i / row, j = i % row;
+    const float* src = part + b * chunks_per_seq * row + j;
+    int c = k;
+    for (; c + 24 < chunks_per_seq; c += 32) {
+      const float a0 = src[(int64_t)c * row], a1 = src[(int64_t)(c + 8) * row], a2 = src[(int64_t)(c + 16) * row],
+                  a3 = src[(int64_t)(c + 24) * row];
+      acc = (((acc + a0) + a1) + a2) + a3;
+    }
+    for (; c < chunks_per_seq; c += 8) acc += src[(int64_t)c * row];
+  }
+  red[k][j32] = acc;
+  __syncthreads();
+  if (k == 0 && i < total) {
+    float sum = red[0][j32];
+#pragma unroll
+    for (int w = 1; w < 8; ++w) sum += red[w][j32];
+    out[i] = sum;
+  }
 }
 
 }  // namespace
 
 hipError_t launch_softmax_rows(const float* scores, float* probs, int64_t rows, int64_t n, hipStream_t stream) {
   if (rows == 0 || n == 0) return hipSuccess;
-  softmax_rows_kernel<<<(unsigned)rows, kThreads, 0, stream>>>(scores, probs, n);
+  const bool vec = n % 4 == 0 && n <= 4 * 4 * kWideThreads;
+  if (vec && n <= 4 * kWideThreads)
+    softmax_rows_regs_kernel<1><<<(unsigned)rows, kWideThreads, 0, stream>>>(scores, probs, (int)(n / 4));
+  else if (vec && n <= 2 * 4 * kWideThreads)
+    softmax_rows_regs_kernel<2><<<(unsigned)rows, kWideThreads, 0, stream>>>(scores, probs, (int)(n / 4));
+  else if (vec)
+    softmax_rows_regs_kernel<4><<<(unsigned)rows, kWideThreads, 0, stream>>>(scores, probs, (int)(n / 4));
+  else
+    softmax_rows_kernel<<<(unsigned)rows, kThreads, 0, stream>>>(scores, probs, n);
   return hipGetLastError();
 }
 
@@ -131,7 +214,7 @@ hipError_t launch_combine_weighted(const float* part, float* out, int batch, int
   const int chunks = (seq_len + kWeightedChunk - 1) / kWeightedChunk;
   const int row = q_heads * kGroup;
   const int64_t total = (int64_t)batch * row;
-  combine_weighted_kernel<<<(unsigned)((total + kThreads - 1) / kThreads), kThreads, 0, stream>>>(part, out, chunks, row, total);
+  combine_weighted_kernel<<<(unsigned)((total + 31) / 32), kThreads, 0, stream>>>(part, out, chunks, row, total);
   return hipGetLastError();
 }
 

@@ -24,7 +24,7 @@ def sync():
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("rows,n", [(1, 1), (7, 5), (3, 300), (24, 8192), (2, 20001)])
+@pytest.mark.parametrize("rows,n", [(1, 1), (7, 5), (3, 300), (5, 4096), (24, 8192), (3, 16384), (2, 16388), (2, 20001)])
 def test_softmax_rows(B, rows, n):
     print(f"case softmax rows={rows} n={n}", flush=True)
     g = torch.Generator().manual_seed(rows * 100003 + n)
