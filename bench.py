@@ -156,14 +156,15 @@ def decode_sweep_with_scores(B, layers, buf, q, T, q_heads):
 
 def decode_sweep_with_attention(B, layers, buf, q, T, q_heads):
     """The decode sweep with the whole attention of one query over the cache as a by-product: scores from the key
-    half, soft-max over the sequence, and the value half with the weighted sum over tokens taken in its epilogue."""
+    half, and the value half with the soft-max-weighted sum over tokens taken in its epilogue (soft-max per 256
+    tokens, merged by the combine step): three launches per predicted layer."""
     prev = (None, None)
     for l, lay in enumerate(layers):
         (kc, ks), (vc, vs) = buf.codes[l]
         Kh, Vh = buf.hat[l & 1]
         B.aquakv_decode_attn_scores(lay, 1, T, q_heads, kc, ks, prev[0], q, SCORE_SCALE, buf.scores, Kh, buf.ws)
-        B.aquakv_softmax(q_heads, T, buf.scores, buf.scores)
-        B.aquakv_decode_values_weighted(lay, 1, T, q_heads, vc, vs, prev[1], Kh, buf.scores, Vh, buf.attn_out, buf.ws_weighted)
+        B.aquakv_decode_values_attend(lay, 1, T, q_heads, vc, vs, prev[1], Kh, buf.scores, Vh, buf.attn_out, None,
+                                      buf.ws_weighted)
         prev = (Kh, Vh)
 
 

@@ -278,9 +278,18 @@ int aquakv_decode_attn_scores_rope(const aquakv_layer* layer, int32_t batch, int
  *   fp32), and Vhat may then be NULL: nothing but `out` is written (the last layer of a sweep).
  *   Otherwise Vhat is required, the values are decoded to it first and summed from there in fp32.
  *   q_heads must be a multiple of H with q_heads / H <= 8.  `workspace`: at least
- *   aquakv_weighted_workspace_bytes() bytes, holding the per-256-token partial sums (added in token
- *   order: the result does not depend on scheduling) and, for layers that are not fused, the fp32
- *   prediction.  Errors as for aquakv_decode_values.
+ *   aquakv_weighted_workspace_bytes() bytes, holding the per-256-token partial sums (added in a fixed
+ *   order: the result does not depend on scheduling), their soft-max statistics and, for layers that
+ *   are not fused, the fp32 prediction.  Errors as for aquakv_decode_values.
+ *
+ * aquakv_decode_values_attend -- the same call with the soft-max inside: `scores` (device, fp32
+ *   [batch, q_heads, seq_len], finite; what aquakv_decode_attn_scores wrote) takes the place of the weights and
+ *   out[b, qh, :] = sum_t softmax(scores[b, qh, :])[t] * Vhat[...].  Every 256 tokens are summed with weights
+ *   exp(score - their own maximum); the pieces are then rescaled to the row maximum M and divided by
+ *   L = sum_t exp(score - M) (the scheme of split-sequence attention kernels), so no separate soft-max pass
+ *   runs.  row_stats (nullable; device, fp32 [batch, q_heads, 2]) receives (M, L): a caller that also attends
+ *   to tokens outside the compressed cache merges its own (max, sum, weighted values) with (M, L, out).
+ *   Same conditions for the sums inside the decode kernel, same workspace.
  */
 int aquakv_softmax(int64_t rows, int64_t n, const float* scores, float* probs, void* stream);
 size_t aquakv_weighted_workspace_bytes(const aquakv_layer* layer, int32_t batch, int32_t seq_len, int32_t q_heads);
@@ -289,6 +298,11 @@ int aquakv_decode_values_weighted(const aquakv_layer* layer, int32_t batch, int3
                                   const void* Vhat_prev, const void* Khat, const float* weights,
                                   void* Vhat, float* out,
                                   void* workspace, size_t workspace_bytes, void* stream);
+int aquakv_decode_values_attend(const aquakv_layer* layer, int32_t batch, int32_t seq_len, int32_t q_heads,
+                                const uint8_t* v_codes, const uint16_t* v_scales,
+                                const void* Vhat_prev, const void* Khat, const float* scores,
+                                void* Vhat, float* out, float* row_stats,
+                                void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * aquakv_fit_predictor -- calibration of one predictor (Alg. "Calibration", Sect. 3.2): the linear map that best

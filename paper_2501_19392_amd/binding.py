@@ -35,7 +35,7 @@ EXPORTS = [
     "aquakv_scores_workspace_bytes", "aquakv_decode_attn_scores_rope",
     "aquakv_encode_keys", "aquakv_encode_values", "aquakv_decode_values",
     "aquakv_fit_workspace_bytes", "aquakv_fit_predictor",
-    "aquakv_softmax", "aquakv_weighted_workspace_bytes", "aquakv_decode_values_weighted",
+    "aquakv_softmax", "aquakv_weighted_workspace_bytes", "aquakv_decode_values_weighted", "aquakv_decode_values_attend",
 ]
 
 
@@ -84,7 +84,8 @@ _lib.aquakv_softmax.argtypes = [ctypes.c_int64, ctypes.c_int64, _P, _P, _P]
 _lib.aquakv_weighted_workspace_bytes.restype = ctypes.c_size_t
 _lib.aquakv_weighted_workspace_bytes.argtypes = [_LP, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
 _lib.aquakv_decode_values_weighted.argtypes = [_LP, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32] + [_P] * 8 + [ctypes.c_size_t, _P]
-for _n in ("aquakv_softmax", "aquakv_decode_values_weighted", "aquakv_predict", "aquakv_quantize", "aquakv_dequantize", "aquakv_encode_layer", "aquakv_decode_layer",
+_lib.aquakv_decode_values_attend.argtypes = [_LP, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32] + [_P] * 9 + [ctypes.c_size_t, _P]
+for _n in ("aquakv_softmax", "aquakv_decode_values_weighted", "aquakv_decode_values_attend", "aquakv_predict", "aquakv_quantize", "aquakv_dequantize", "aquakv_encode_layer", "aquakv_decode_layer",
            "aquakv_decode_attn_scores", "aquakv_decode_attn_scores_rope", "aquakv_encode_keys", "aquakv_encode_values",
            "aquakv_decode_values", "aquakv_fit_predictor"):
     getattr(_lib, _n).restype = ctypes.c_int
@@ -204,7 +205,7 @@ class Layer:
         return torch.empty(max(aquakv_scores_workspace_bytes(self, batch, q_heads), 16), dtype=torch.uint8, device=device)
 
     def alloc_weighted_workspace(self, batch: int, seq_len: int, q_heads: int, device="cuda"):
-        """Workspace of aquakv_decode_values_weighted."""
+        """Workspace of aquakv_decode_values_weighted / aquakv_decode_values_attend."""
         return torch.empty(max(aquakv_weighted_workspace_bytes(self, batch, seq_len, q_heads), 16), dtype=torch.uint8,
                            device=device)
 
@@ -320,6 +321,14 @@ def aquakv_decode_values_weighted(layer, batch: int, seq_len: int, q_heads: int,
     _check(_lib.aquakv_decode_values_weighted(_layer_ref(layer), batch, seq_len, q_heads, _ptr(v_codes), _ptr(v_scales),
                                               _ptr(Vhat_prev), _ptr(Khat), _ptr(weights), _ptr(Vhat), _ptr(out), ws,
                                               nbytes, _stream(stream)))
+
+
+def aquakv_decode_values_attend(layer, batch: int, seq_len: int, q_heads: int, v_codes, v_scales, Vhat_prev, Khat,
+                                scores, Vhat, out, row_stats, workspace, stream=None) -> None:
+    ws, nbytes = _ws(workspace)
+    _check(_lib.aquakv_decode_values_attend(_layer_ref(layer), batch, seq_len, q_heads, _ptr(v_codes), _ptr(v_scales),
+                                            _ptr(Vhat_prev), _ptr(Khat), _ptr(scores), _ptr(Vhat), _ptr(out),
+                                            _ptr(row_stats), ws, nbytes, _stream(stream)))
 
 
 def aquakv_fit_workspace_bytes(d_in: int, d_out: int) -> int:

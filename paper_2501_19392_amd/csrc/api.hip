@@ -490,6 +490,11 @@ size_t weighted_part_bytes(int32_t batch, int32_t seq_len, int32_t q_heads) {
   const size_t bytes = (size_t)batch * chunks * q_heads * 128 * sizeof(float);
   return (bytes + 255) & ~(size_t)255;
 }
+size_t weighted_stat_bytes(int32_t batch, int32_t seq_len, int32_t q_heads) {
+  const size_t chunks = ((size_t)seq_len + aquakv::kWeightedChunk - 1) / aquakv::kWeightedChunk;
+  const size_t bytes = (size_t)batch * chunks * q_heads * 2 * sizeof(float);
+  return (bytes + 255) & ~(size_t)255;
+}
 bool weighted_fused(const aquakv_layer* L, const Plan& pl, int32_t seq_len) {
   return L->d_in_v != 0 && pl.fused && seq_len % aquakv::kWeightedChunk == 0;
 }
@@ -506,13 +511,15 @@ int aquakv_softmax(int64_t rows, int64_t n, const float* scores, float* probs, v
 size_t aquakv_weighted_workspace_bytes(const aquakv_layer* L, int32_t batch, int32_t seq_len, int32_t q_heads) {
   if (check_layer(L) != AQUAKV_OK || batch < 1 || seq_len < 1 || q_heads < 1) return 0;
   const Plan pl = make_plan(L, (int64_t)batch * seq_len);
-  return weighted_part_bytes(batch, seq_len, q_heads) + pl.p_bytes;
+  return weighted_part_bytes(batch, seq_len, q_heads) + weighted_stat_bytes(batch, seq_len, q_heads) + pl.p_bytes;
 }
 
-int aquakv_decode_values_weighted(const aquakv_layer* L, int32_t batch, int32_t seq_len, int32_t q_heads,
-                                  const uint8_t* v_codes, const uint16_t* v_scales, const void* Vhat_prev,
-                                  const void* Khat, const float* weights, void* Vhat, float* out, void* workspace,
-                                  size_t workspace_bytes, void* stream_) {
+namespace {
+// shared body: softmax = false: `weights` are the weights; true: they are raw scores (soft-max taken per chunk and merged)
+int decode_values_weighted(const aquakv_layer* L, int32_t batch, int32_t seq_len, int32_t q_heads, const uint8_t* v_codes,
+                           const uint16_t* v_scales, const void* Vhat_prev, const void* Khat, const float* weights,
+                           bool softmax, void* Vhat, float* out, float* row_stats, void* workspace, size_t workspace_bytes,
+                           void* stream_) {
   CHECK(check_layer(L));
   if (batch < 0 || seq_len < 0) return fail(AQUAKV_EINVAL, "batch=%d seq_len=%d", batch, seq_len);
   if (q_heads < 1 || q_heads % L->kv_heads || q_heads / L->kv_heads > 8)
@@ -522,9 +529,11 @@ int aquakv_decode_values_weighted(const aquakv_layer* L, int32_t batch, int32_t 
   CHECK(check_scales(L, v_scales, "v_scales", true));
   CHECK(check_ptr(Vhat_prev, "Vhat_prev", has_v));
   CHECK(check_ptr(Khat, "Khat", has_v));
-  CHECK(check_ptr(weights, "weights", true));
+  CHECK(check_ptr(weights, softmax ? "scores" : "weights", true));
   CHECK(check_ptr(Vhat, "Vhat", false));
   CHECK(check_ptr(out, "out", true));
+  if (row_stats != nullptr && (reinterpret_cast<uintptr_t>(row_stats) & 3u))
+    return fail(AQUAKV_EALIGN, "row_stats is not 4-byte aligned");
   const int64_t tokens = (int64_t)batch * seq_len;
   if (tokens == 0) return AQUAKV_OK;
   const Plan pl = make_plan(L, tokens);
@@ -534,26 +543,47 @@ int aquakv_decode_values_weighted(const aquakv_layer* L, int32_t batch, int32_t 
                               "groups of one head, a value predictor, seq_len a multiple of %d)",
                 aquakv::kWeightedChunk);
   const size_t part_bytes = weighted_part_bytes(batch, seq_len, q_heads);
-  const size_t need = part_bytes + (fused ? 0 : pl.p_bytes);
+  const size_t stat_bytes = weighted_stat_bytes(batch, seq_len, q_heads);
+  const size_t need = part_bytes + stat_bytes + (fused ? 0 : pl.p_bytes);
   CHECK(check_ptr(workspace, "workspace", true));
   if (workspace_bytes < need) return fail(AQUAKV_EWORKSPACE, "workspace %zu B < required %zu B", workspace_bytes, need);
   hipStream_t stream = static_cast<hipStream_t>(stream_);
-  float* part = static_cast<float*>(workspace);
-  float* Pbuf = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + part_bytes);
+  unsigned char* wsb = static_cast<unsigned char*>(workspace);
+  float* part = reinterpret_cast<float*>(wsb);
+  float* pstats = softmax ? reinterpret_cast<float*>(wsb + part_bytes) : nullptr;
+  float* Pbuf = reinterpret_cast<float*>(wsb + part_bytes + stat_bytes);
   if (fused) {
     const int D = pl.D;
     HIP_TRY(aquakv::launch_fused_weighted(quantizer_id(L), Vhat_prev, L->d_in_v - D, Khat, D, L->w_v, L->b_v, L->signs_v,
-                                          L->codebook, v_codes, v_scales, Vhat, weights, part, seq_len, q_heads, tokens, D,
-                                          stream));
+                                          L->codebook, v_codes, v_scales, Vhat, weights, part, pstats, seq_len, q_heads,
+                                          tokens, D, stream));
   } else {
     for (int64_t r0 = 0; r0 < tokens; r0 += pl.chunk) {
       const int64_t n = tokens - r0 < pl.chunk ? tokens - r0 : pl.chunk;
       CHECK(decode_values_chunk(L, pl, r0, n, v_codes, v_scales, Vhat_prev, Khat, Vhat, Pbuf, stream));
     }
-    HIP_TRY(aquakv::launch_weighted_values(L->dtype, Vhat, weights, part, batch, seq_len, L->kv_heads, q_heads, stream));
+    HIP_TRY(aquakv::launch_weighted_values(L->dtype, Vhat, weights, part, pstats, batch, seq_len, L->kv_heads, q_heads,
+                                           stream));
   }
-  HIP_TRY(aquakv::launch_combine_weighted(part, out, batch, seq_len, q_heads, stream));
+  HIP_TRY(aquakv::launch_combine_weighted(part, pstats, out, softmax ? row_stats : nullptr, batch, seq_len, q_heads, stream));
   return AQUAKV_OK;
+}
+}  // namespace
+
+int aquakv_decode_values_weighted(const aquakv_layer* L, int32_t batch, int32_t seq_len, int32_t q_heads,
+                                  const uint8_t* v_codes, const uint16_t* v_scales, const void* Vhat_prev,
+                                  const void* Khat, const float* weights, void* Vhat, float* out, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
+  return decode_values_weighted(L, batch, seq_len, q_heads, v_codes, v_scales, Vhat_prev, Khat, weights, false, Vhat, out,
+                                nullptr, workspace, workspace_bytes, stream);
+}
+
+int aquakv_decode_values_attend(const aquakv_layer* L, int32_t batch, int32_t seq_len, int32_t q_heads,
+                                const uint8_t* v_codes, const uint16_t* v_scales, const void* Vhat_prev, const void* Khat,
+                                const float* scores, void* Vhat, float* out, float* row_stats, void* workspace,
+                                size_t workspace_bytes, void* stream) {
+  return decode_values_weighted(L, batch, seq_len, q_heads, v_codes, v_scales, Vhat_prev, Khat, scores, true, Vhat, out,
+                                row_stats, workspace, workspace_bytes, stream);
 }
 
 // ---- calibration: ridge least-squares fit of one predictor (Alg. "Calibration") --------------------------------

@@ -39,11 +39,12 @@ enum Mode : int { kEncode = 0, kDecode = 1, kScores = 2, kWeighted = 3 };
 // kWeighted: a wave keeps the bf16 values it decodes (32 token rows x 128) in the part of its parked rows it has
 // already consumed, one row every kVRowBytes (264 B: rows 8 apart then sit 16 banks apart, which makes the
 // token-strided 2-byte reads of the matrix-core operand conflict free), followed by its share of the sums
-// (16 head slots x 128 fp32).
+// (16 head slots x 128 fp32) and, in the soft-max form, three rows of 16 head-slot statistics.
 constexpr int kVRowBytes = kGroup * 2 + 8;
 constexpr int kVBufBytes = 32 * kVRowBytes;          // 8448 = exactly 16 parked rows
 static_assert(kVBufBytes == 16 * kLdP * 4, "the decoded rows of both passes fill the first pass's parked rows");
-static_assert(kVBufBytes + 16 * kGroup * 4 <= 32 * kLdP * 4, "sums fit behind the decoded rows");
+constexpr int kStatBytes = kVBufBytes + 16 * kGroup * 4;    // wave's maxima [16], weight sums [16], tile maxima [16] (wave 0)
+static_assert(kStatBytes + 3 * 16 * 4 <= 32 * kLdP * 4, "sums and statistics fit behind the decoded rows");
 typedef unsigned int u32x2_alias __attribute__((ext_vector_type(2), may_alias));
 typedef unsigned short u16_alias __attribute__((may_alias));
 typedef float f32_alias __attribute__((may_alias));
@@ -244,13 +245,33 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_wave_barrier();
     const int rep = q_heads / H;
+    // Soft-max form (pstats given): `weights` holds raw scores.  The tile's maximum per head slot is taken over the
+    // 8 scores of a lane, the 4 lane groups of the slot and the 8 waves, the weights become exp(score - maximum),
+    // and maximum and weight sum go out with the sums so that the tiles of a sequence can be merged afterwards.
+    float* const pstats = scores;
+    unsigned char* const wregion = reinterpret_cast<unsigned char*>(wl);
+    float wf[8] = {__uint_as_float(wreg[0].x), __uint_as_float(wreg[0].y), __uint_as_float(wreg[0].z), __uint_as_float(wreg[0].w),
+                   __uint_as_float(wreg[1].x), __uint_as_float(wreg[1].y), __uint_as_float(wreg[1].z), __uint_as_float(wreg[1].w)};
+    if (pstats != nullptr) {
+      float mx = fmaxf(fmaxf(fmaxf(wf[0], wf[1]), fmaxf(wf[2], wf[3])), fmaxf(fmaxf(wf[4], wf[5]), fmaxf(wf[6], wf[7])));
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      if (lane < 16) reinterpret_cast<f32_alias*>(wregion + kStatBytes)[lane] = mx;
+      __syncthreads();
+      float mt = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < WAVES; ++w)
+        mt = fmaxf(mt, reinterpret_cast<const f32_alias*>(smem + (size_t)w * kRowsPerWave * kLdP * 4 + kStatBytes)[lane & 15]);
+      if (wave == 0 && lane < 16) reinterpret_cast<f32_alias*>(wregion + kStatBytes + 128)[lane] = mt;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) wf[j] = expf(wf[j] - mt);
+    }
     u32x4 whi, wlo;
     {
-      const uint32_t wb[8] = {wreg[0].x, wreg[0].y, wreg[0].z, wreg[0].w, wreg[1].x, wreg[1].y, wreg[1].z, wreg[1].w};
       uint32_t hi[4], lo[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const float a = __uint_as_float(wb[2 * j]), b = __uint_as_float(wb[2 * j + 1]);
+        const float a = wf[2 * j], b = wf[2 * j + 1];
         hi[j] = Storage<bf16_t>::pack2(a, b);
         lo[j] = Storage<bf16_t>::pack2(a - __uint_as_float(hi[j] << 16), b - __uint_as_float(hi[j] & 0xffff0000u));
       }
@@ -278,7 +299,20 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
       c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi, bfrag, c, 0, 0, 0);
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        red[(4 * kg + r) * kGroup + nb * 16 + n] = c[r];     // row 4 kg + r of the product; rows beyond rep are zero
+        red[(4 * kg + r) * kGroup + nb * 16 + n] = c[r];     // row 4 kg + r of the product; rows beyond rep are unused
+      }
+    }
+    if (pstats != nullptr) {
+      // sum of the wave's weights per head slot: one more block against a column of ones
+      u32x4 one;
+      one.x = one.y = one.z = one.w = 0x3F803F80u;
+      const bf16x8 ones = __builtin_bit_cast(bf16x8, one);
+      f32x4v c = {0.f, 0.f, 0.f, 0.f};
+      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo, ones, c, 0, 0, 0);
+      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi, ones, c, 0, 0, 0);
+      if (n == 0) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) reinterpret_cast<f32_alias*>(wregion + kStatBytes + 64)[4 * kg + r] = c[r];
       }
     }
     __syncthreads();
@@ -289,6 +323,15 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
       for (int w = 0; w < WAVES; ++w)
         sum += *reinterpret_cast<const f32_alias*>(smem + (size_t)w * kRowsPerWave * kLdP * 4 + kVBufBytes + idx * 4);
       part[((int64_t)tile_m * q_heads + head * rep + idx / kGroup) * kGroup + idx % kGroup] = sum;
+    }
+    if (pstats != nullptr && (int)threadIdx.x < rep) {
+      float l = 0.f;
+#pragma unroll
+      for (int w = 0; w < WAVES; ++w)
+        l += reinterpret_cast<const f32_alias*>(smem + (size_t)w * kRowsPerWave * kLdP * 4 + kStatBytes + 64)[threadIdx.x];
+      float* dst = pstats + ((int64_t)tile_m * q_heads + head * rep + threadIdx.x) * 2;
+      dst[0] = reinterpret_cast<const f32_alias*>(smem + kStatBytes + 128)[threadIdx.x];
+      dst[1] = l;
     }
   }
 }
@@ -354,10 +397,11 @@ hipError_t launch_fused_scores(int n_codewords, const void* x0, int d0, const vo
 
 hipError_t launch_fused_weighted(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W,
                                  const float* bias, const int8_t* signs, const float* codebook, const uint8_t* codes,
-                                 const uint16_t* scales, void* Xhat, const float* weights, float* part, int seq_len,
-                                 int q_heads, int64_t T, int D, hipStream_t stream) {
+                                 const uint16_t* scales, void* Xhat, const float* weights, float* part, float* pstats,
+                                 int seq_len, int q_heads, int64_t T, int D, hipStream_t stream) {
+  // pstats travels in the kernel's `scores` argument, which this mode does not use otherwise
   return launch<kWeighted>(n_codewords, x0, d0, x1, d1, W, bias, signs, codebook, nullptr, nullptr,
-                           const_cast<uint8_t*>(codes), const_cast<uint16_t*>(scales), Xhat, nullptr, 0.f, nullptr,
+                           const_cast<uint8_t*>(codes), const_cast<uint16_t*>(scales), Xhat, nullptr, 0.f, pstats,
                            seq_len, q_heads, T, D, nullptr, nullptr, weights, part, stream);
 }
 

@@ -53,16 +53,21 @@ hipError_t launch_fused_scores(int n_codewords, const void* x0, int d0, const vo
 // Value side of attention.  The sums over tokens are taken per chunk of kWeightedChunk tokens of one sequence
 // (part[batch * chunks_per_seq, q_heads, 128] fp32, chunks_per_seq = ceil(seq_len / kWeightedChunk)) and then added in
 // chunk order by launch_combine_weighted: out[b, qh, :] = sum_t weights[b, qh, t] * Vhat[b * seq_len + t, qh / rep, :].
+// Soft-max form (pstats given, [batch * chunks_per_seq, q_heads, 2] fp32): `weights` holds raw scores, a chunk's sums are
+// taken with exp(score - chunk maximum), pstats receives that maximum and the chunk's weight sum, and the combine step
+// rescales the chunks to the row maximum and divides by the row's weight sum (row_stats, nullable, [batch, q_heads, 2]:
+// row maximum and that denominator).
 constexpr int kWeightedChunk = 256;
 // decode of the values with the chunk sums taken in the epilogue (bf16, seq_len a multiple of kWeightedChunk); Xhat nullable
 hipError_t launch_fused_weighted(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W,
                                  const float* bias, const int8_t* signs, const float* codebook, const uint8_t* codes,
-                                 const uint16_t* scales, void* Xhat, const float* weights, float* part, int seq_len,
-                                 int q_heads, int64_t T, int D, hipStream_t stream);
+                                 const uint16_t* scales, void* Xhat, const float* weights, float* part, float* pstats,
+                                 int seq_len, int q_heads, int64_t T, int D, hipStream_t stream);
 // chunk sums over values already decoded to memory (any dtype, any seq_len)
-hipError_t launch_weighted_values(int dtype, const void* Vhat, const float* weights, float* part, int batch, int seq_len,
-                                  int H, int q_heads, hipStream_t stream);
-hipError_t launch_combine_weighted(const float* part, float* out, int batch, int seq_len, int q_heads, hipStream_t stream);
+hipError_t launch_weighted_values(int dtype, const void* Vhat, const float* weights, float* part, float* pstats, int batch,
+                                  int seq_len, int H, int q_heads, hipStream_t stream);
+hipError_t launch_combine_weighted(const float* part, const float* pstats, float* out, float* row_stats, int batch,
+                                   int seq_len, int q_heads, hipStream_t stream);
 // probs[r, :] = softmax(scores[r, :]) for `rows` rows of length n (in place allowed)
 hipError_t launch_softmax_rows(const float* scores, float* probs, int64_t rows, int64_t n, hipStream_t stream);
 

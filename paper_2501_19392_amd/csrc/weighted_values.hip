@@ -111,11 +111,14 @@ template <> __device__ __forceinline__ void load8<bf16_t>(const bf16_t* p, float
 // tsub, tsub + 16, ... of the chunk and owns dims 8 l .. 8 l + 7; the 16 token classes are added through LDS.
 // The chunk is re-read (from cache) once per query head of the group: this is the path for what the fused
 // kernel does not cover, not the fast one.
+// pstats (nullable): soft-max form, `weights` holds raw scores: the weights are exp(score - chunk maximum), and the
+// chunk's maximum and weight sum are written to pstats[chunk, qh, 2].
 template <typename T>
 __global__ __launch_bounds__(kThreads) void weighted_values_kernel(const T* __restrict__ Vhat, const float* __restrict__ weights,
-                                                                   float* __restrict__ part, int seq_len, int H, int q_heads,
-                                                                   int chunks_per_seq) {
+                                                                   float* __restrict__ part, float* __restrict__ pstats,
+                                                                   int seq_len, int H, int q_heads, int chunks_per_seq) {
   __shared__ float red[16][kGroup];
+  __shared__ float buf[kThreads];
   const int b = blockIdx.x / chunks_per_seq, chunk = blockIdx.x % chunks_per_seq, head = blockIdx.y;
   const int rep = q_heads / H;
   const int tsub = threadIdx.x >> 4, l = threadIdx.x & 15;
@@ -124,15 +127,33 @@ __global__ __launch_bounds__(kThreads) void weighted_values_kernel(const T* __re
   for (int r = 0; r < rep; ++r) {
     const int qh = head * rep + r;
     const float* w = weights + ((int64_t)b * q_heads + qh) * seq_len;
+    float shift = 0.f;
+    if (pstats != nullptr) {
+      float mx = -INFINITY;
+      for (int it = 0; it < kWeightedChunk / 16; ++it) {
+        const int t = t0 + it * 16 + tsub;
+        if (t < seq_len) mx = fmaxf(mx, w[t]);
+      }
+      shift = block_reduce<true>(mx, buf);
+    }
     float acc[8] = {};
+    float wsum = 0.f;
     for (int it = 0; it < kWeightedChunk / 16; ++it) {
       const int t = t0 + it * 16 + tsub;
       if (t < seq_len) {
         float v[8];
         load8<T>(vbase + (int64_t)t * H * kGroup, v);
-        const float wt = w[t];
+        const float wt = pstats != nullptr ? expf(w[t] - shift) : w[t];
+        wsum += wt;
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i] = __fmaf_rn(wt, v[i], acc[i]);
+      }
+    }
+    if (pstats != nullptr) {
+      const float total = block_reduce<false>(l == 0 ? wsum : 0.f, buf);      // every token counted once
+      if (threadIdx.x == 0) {
+        pstats[((int64_t)blockIdx.x * q_heads + qh) * 2] = shift;
+        pstats[((int64_t)blockIdx.x * q_heads + qh) * 2 + 1] = total;
       }
     }
 #pragma unroll
@@ -179,6 +200,50 @@ __global__ __launch_bounds__(kThreads) void combine_weighted_kernel(const float*
   }
 }
 
+// Soft-max form: chunk c carries sums taken with weights exp(score - m_c), its maximum m_c and weight sum l_c.
+// out = sum_c e^(m_c - M) part_c / sum_c e^(m_c - M) l_c with M = max_c m_c; row_stats (nullable) receives M and the
+// denominator.  Same thread layout as above; the three reductions over the chunks go through LDS in a fixed order.
+__global__ __launch_bounds__(kThreads) void combine_softmax_kernel(const float* __restrict__ part, const float* __restrict__ pstats,
+                                                                   float* __restrict__ out, float* __restrict__ row_stats,
+                                                                   int chunks_per_seq, int q_heads, int64_t total) {
+  __shared__ float red[8][32];
+  __shared__ float den[8];
+  const int row = q_heads * kGroup;
+  const int k = threadIdx.x >> 5, j32 = threadIdx.x & 31;
+  const int64_t i = (int64_t)blockIdx.x * 32 + j32;                     // total is a multiple of 128: never beyond the end
+  const int64_t b = i / row, j = i % row;
+  const int qh = (int)(j / kGroup);                                     // the same for the 32 outputs of a workgroup
+  const float* src = part + b * chunks_per_seq * row + j;
+  const float* st = pstats + (b * chunks_per_seq * q_heads + qh) * 2;
+  float mx = -INFINITY;
+  for (int c = k; c < chunks_per_seq; c += 8) mx = fmaxf(mx, st[(int64_t)c * q_heads * 2]);
+  red[k][j32] = mx;
+  __syncthreads();
+  float M = red[0][j32];
+#pragma unroll
+  for (int w = 1; w < 8; ++w) M = fmaxf(M, red[w][j32]);
+  __syncthreads();
+  float acc = 0.f, l = 0.f;
+  for (int c = k; c < chunks_per_seq; c += 8) {
+    const float e = expf(st[(int64_t)c * q_heads * 2] - M);
+    acc = __fmaf_rn(e, src[(int64_t)c * row], acc);
+    l = __fmaf_rn(e, st[(int64_t)c * q_heads * 2 + 1], l);
+  }
+  red[k][j32] = acc;
+  if (j32 == 0) den[k] = l;
+  __syncthreads();
+  if (k == 0) {
+    float sum = red[0][j32], d = den[0];
+#pragma unroll
+    for (int w = 1; w < 8; ++w) { sum += red[w][j32]; d += den[w]; }
+    out[i] = sum / d;
+    if (row_stats != nullptr && j % kGroup == 0) {
+      row_stats[(b * q_heads + qh) * 2] = M;
+      row_stats[(b * q_heads + qh) * 2 + 1] = d;
+    }
+  }
+}
+
 }  // namespace
 
 hipError_t launch_softmax_rows(const float* scores, float* probs, int64_t rows, int64_t n, hipStream_t stream) {
@@ -195,25 +260,30 @@ hipError_t launch_softmax_rows(const float* scores, float* probs, int64_t rows, 
   return hipGetLastError();
 }
 
-hipError_t launch_weighted_values(int dtype, const void* Vhat, const float* weights, float* part, int batch, int seq_len,
-                                  int H, int q_heads, hipStream_t stream) {
+hipError_t launch_weighted_values(int dtype, const void* Vhat, const float* weights, float* part, float* pstats, int batch,
+                                  int seq_len, int H, int q_heads, hipStream_t stream) {
   if (batch == 0 || seq_len == 0) return hipSuccess;
   const int chunks = (seq_len + kWeightedChunk - 1) / kWeightedChunk;
   const dim3 grid((unsigned)batch * chunks, (unsigned)H);
   if (dtype == kBF16)
-    weighted_values_kernel<bf16_t><<<grid, kThreads, 0, stream>>>(static_cast<const bf16_t*>(Vhat), weights, part, seq_len, H,
-                                                                  q_heads, chunks);
+    weighted_values_kernel<bf16_t><<<grid, kThreads, 0, stream>>>(static_cast<const bf16_t*>(Vhat), weights, part, pstats,
+                                                                  seq_len, H, q_heads, chunks);
   else
-    weighted_values_kernel<float><<<grid, kThreads, 0, stream>>>(static_cast<const float*>(Vhat), weights, part, seq_len, H,
-                                                                 q_heads, chunks);
+    weighted_values_kernel<float><<<grid, kThreads, 0, stream>>>(static_cast<const float*>(Vhat), weights, part, pstats,
+                                                                 seq_len, H, q_heads, chunks);
   return hipGetLastError();
 }
 
-hipError_t launch_combine_weighted(const float* part, float* out, int batch, int seq_len, int q_heads, hipStream_t stream) {
+hipError_t launch_combine_weighted(const float* part, const float* pstats, float* out, float* row_stats, int batch,
+                                   int seq_len, int q_heads, hipStream_t stream) {
   if (batch == 0) return hipSuccess;
   const int chunks = (seq_len + kWeightedChunk - 1) / kWeightedChunk;
   const int row = q_heads * kGroup;
   const int64_t total = (int64_t)batch * row;
+  if (pstats != nullptr) {
+    combine_softmax_kernel<<<(unsigned)(total / 32), kThreads, 0, stream>>>(part, pstats, out, row_stats, chunks, q_heads, total);
+    return hipGetLastError();
+  }
   combine_weighted_kernel<<<(unsigned)((total + 31) / 32), kThreads, 0, stream>>>(part, out, chunks, row, total);
   return hipGetLastError();
 }

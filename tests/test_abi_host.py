@@ -166,11 +166,12 @@ def test_weighted_values_call_validates_its_arguments():
     ws = (FAKE, 1 << 30)
     ok = [FAKE] * 7                       # v_codes v_scales Vhat_prev Khat weights Vhat out
     call = B.aquakv_decode_values_weighted
-    assert B.aquakv_weighted_workspace_bytes(L, 1, 8192, 24) == 32 * 24 * 128 * 4
-    assert B.aquakv_weighted_workspace_bytes(L, 3, 257, 8) == 3 * 2 * 8 * 128 * 4
-    assert B.aquakv_weighted_workspace_bytes(L, 1, 100, 8) == 8 * 128 * 4
+    # per chunk of 256 tokens and query head: 128 sums and 2 soft-max statistics (each block rounded up to 256 bytes)
+    assert B.aquakv_weighted_workspace_bytes(L, 1, 8192, 24) == 32 * 24 * 128 * 4 + 32 * 24 * 2 * 4
+    assert B.aquakv_weighted_workspace_bytes(L, 3, 257, 8) == 3 * 2 * 8 * 128 * 4 + 512
+    assert B.aquakv_weighted_workspace_bytes(L, 1, 100, 8) == 8 * 128 * 4 + 256
     L32 = layer(dtype=B.AQUAKV_FP32)
-    assert B.aquakv_weighted_workspace_bytes(L32, 1, 100, 8) == 8 * 128 * 4 + 100 * 1024 * 4
+    assert B.aquakv_weighted_workspace_bytes(L32, 1, 100, 8) == 8 * 128 * 4 + 256 + 100 * 1024 * 4
     assert B.aquakv_weighted_workspace_bytes(L, 0, 100, 8) == 0
     assert B.aquakv_weighted_workspace_bytes(layer(head_dim=64), 1, 100, 8) == 0
     assert status_of(call, L, 1, 256, 12, *ok, ws) == B.AQUAKV_EINVAL                 # not a multiple of kv heads
@@ -196,6 +197,17 @@ def test_weighted_values_call_validates_its_arguments():
     assert status_of(call, L, 1, 256, 8, *ok, None) == B.AQUAKV_ENULL                 # workspace
     call(L, 0, 256, 8, *ok, None)                                                   # no tokens: no-op
     call(L, 1, 0, 8, *ok, None)
+    att = B.aquakv_decode_values_attend                                             # same checks, plus row_stats
+    assert status_of(att, L, 1, 256, 12, *ok, None, ws) == B.AQUAKV_EINVAL
+    a = list(ok)
+    a[4] = None
+    assert status_of(att, L, 1, 256, 8, *a, None, ws) == B.AQUAKV_ENULL               # scores
+    a = list(ok)
+    a[5] = None
+    assert status_of(att, L32, 1, 256, 8, *a, FAKE, ws) == B.AQUAKV_ENULL             # Vhat needed
+    assert status_of(att, L, 1, 256, 8, *ok, FAKE + 2, ws) == B.AQUAKV_EALIGN
+    assert status_of(att, L, 1, 256, 8, *ok, None, (FAKE, 1024)) == B.AQUAKV_EWORKSPACE
+    att(L, 0, 256, 8, *ok, None, None)
     assert status_of(B.aquakv_softmax, 4, 10, None, FAKE) == B.AQUAKV_ENULL
     assert status_of(B.aquakv_softmax, 4, 10, FAKE, None) == B.AQUAKV_ENULL
     assert status_of(B.aquakv_softmax, -1, 10, FAKE, FAKE) == B.AQUAKV_EINVAL

@@ -1,5 +1,5 @@
 """The layer calls under HIP graph capture: the library allocates nothing, keeps no state and never synchronises, so a
-whole encode / decode / scoring sweep can be captured once and replayed.  Every replay is checked bit for bit
+whole encode / decode / scoring / attention sweep can be captured once and replayed.  Every replay is checked bit for bit
 against the eager calls on the same inputs, with eager work and synchronisations between the replays."""
 import pytest
 import torch
@@ -14,13 +14,13 @@ def bits_of(t):
     return t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32)
 
 
-@pytest.mark.parametrize("dtype,rtn_bits", [("bf16", None), ("fp32", None), ("bf16", 2)])
-def test_layer_sweeps_replay_from_a_graph(dtype, rtn_bits):
+@pytest.mark.parametrize("dtype,rtn_bits,T", [("bf16", None, 515), ("fp32", None, 515), ("bf16", 2, 515), ("bf16", None, 512)])
+def test_layer_sweeps_replay_from_a_graph(dtype, rtn_bits, T):
     if not torch.cuda.is_available():
         pytest.fail("no GPU visible: the gpu-marked tests must run on an MI355X")
     from paper_2501_19392_amd import binding as B
-    print(f"case graph capture dtype={dtype} rtn_bits={rtn_bits}", flush=True)
-    H, QH, T, L = 8, 24, 515, 3
+    print(f"case graph capture dtype={dtype} rtn_bits={rtn_bits} T={T}", flush=True)
+    H, QH, L = 8, 24, 3
     D = H * 128
     sd = synth.torch_dtype(dtype)
     layers = []
@@ -44,6 +44,11 @@ def test_layer_sweeps_replay_from_a_graph(dtype, rtn_bits):
             self.scores = [torch.empty(1, QH, T, dtype=torch.float32, device="cuda") for _ in layers]
             self.ws = max((lay.alloc_workspace(T) for lay in layers), key=lambda t: t.numel())
             self.ws_scores = [lay.alloc_scores_workspace(1, QH) for lay in layers]
+            self.probs = [torch.empty(1, QH, T, dtype=torch.float32, device="cuda") for _ in layers]
+            self.attn = [torch.empty(1, QH, 128, dtype=torch.float32, device="cuda") for _ in layers]
+            self.attn2 = [torch.empty(1, QH, 128, dtype=torch.float32, device="cuda") for _ in layers]
+            self.stats = [torch.empty(1, QH, 2, dtype=torch.float32, device="cuda") for _ in layers]
+            self.ws_weighted = [lay.alloc_weighted_workspace(1, T, QH) for lay in layers]
 
         def load(self, kv, q):
             for (K, V), (k, v) in zip(self.kv, kv):
@@ -55,7 +60,7 @@ def test_layer_sweeps_replay_from_a_graph(dtype, rtn_bits):
             for l in range(L):
                 (kc, ks), (vc, vs) = self.codes[l]
                 out += [kc, ks, vc, vs, bits_of(self.hat[l][0]), bits_of(self.hat[l][1]), bits_of(self.dec[l][0]),
-                        bits_of(self.dec[l][1]), self.scores[l]]
+                        bits_of(self.dec[l][1]), self.scores[l], self.probs[l], self.attn[l], self.attn2[l], self.stats[l]]
             return [t.clone() for t in out]
 
     def sweep(b):
@@ -72,6 +77,13 @@ def test_layer_sweeps_replay_from_a_graph(dtype, rtn_bits):
             folded = B.aquakv_scores_workspace_bytes(lay, 1, QH) > 0
             B.aquakv_decode_attn_scores(lay, 1, T, QH, kc, ks, Kp, b.q, 0.125, b.scores[l], None,
                                         b.ws_scores[l] if folded else b.ws)
+            # value side of attention: soft-max, then the value half of decode again with the weighted sums
+            # (in the fused kernel's epilogue when T is a multiple of 256, from the decoded values otherwise)
+            B.aquakv_softmax(QH, T, b.scores[l], b.probs[l])
+            B.aquakv_decode_values_weighted(lay, 1, T, QH, vc, vs, Vp, b.dec[l][0], b.probs[l], b.dec[l][1], b.attn[l],
+                                            b.ws_weighted[l])
+            B.aquakv_decode_values_attend(lay, 1, T, QH, vc, vs, Vp, b.dec[l][0], b.scores[l], b.dec[l][1], b.attn2[l],
+                                          b.stats[l], b.ws_weighted[l])
             Kp, Vp = b.dec[l]
 
     eager, graphed = Bufs(), Bufs()

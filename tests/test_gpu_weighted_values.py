@@ -42,6 +42,11 @@ def test_softmax_rows(B, rows, n):
     assert torch.equal(s, p)
 
 
+def group_rms(Vh):
+    """rms over the 128 values of every (sequence, token, head): [batch, S, H]."""
+    return np.sqrt(np.mean(Vh ** 2, axis=-1))
+
+
 def weights_for(batch, QH, S, seed, kind):
     g = torch.Generator().manual_seed(seed)
     if kind == "softmax":
@@ -73,7 +78,9 @@ def check_weighted(B, lo, lg, g, batch, S, QH, w, fused_expected, label):
     got = U.np64(out)
     rtol = U.RTOL[lo.dtype]
     err = np.abs(got - want)
-    assert np.all(err <= rtol * mag + 1e-30), f"{label}: {float(np.max(err / (mag + 1e-30))):.3g}"
+    # the decoded values agree with the oracle's within rtol (|v| + rms of the group); the sum inherits that weight by weight
+    bound = rtol * (mag + np.stack([np.einsum("bt,bt->b", wa[:, qh], group_rms(Vh)[:, :, qh // rep]) for qh in range(QH)], 1)[..., None])
+    assert np.all(err <= bound + 1e-30), f"{label}: {float(np.max(err / (bound + 1e-30))):.3g}"
     # against the sum over the GPU's own decoded values the only error is the summation's: weights carried
     # with 16 mantissa bits on the matrix cores (2^-17 relative per term), fp32 accumulation otherwise
     err_own = np.abs(got - own)
@@ -110,6 +117,76 @@ def test_weighted_values(B, dtype, n, layer, batch, S, QH, kind):
     w = weights_for(batch, QH, S, 5000 + S + QH, kind)
     fused = dtype == "bf16" and layer == 1 and S % 256 == 0
     check_weighted(B, lo_l[layer], lg_l[layer], g, batch, S, QH, w, fused, "weighted")
+
+
+@pytest.mark.parametrize("dtype,n,layer,batch,S,QH,spread", [
+    ("bf16", 16, 1, 2, 512, 24, 3.0),        # sums and soft-max pieces inside the decode kernel, 2 chunks per sequence
+    ("bf16", 64, 1, 1, 1024, 64, 12.0),      # 8 query heads per kv head, peaked rows
+    ("bf16", 16, 1, 1, 256, 8, 0.0),         # one chunk, all scores equal: the mean of the values
+    ("bf16", 16, 1, 2, 333, 32, 5.0),        # ragged: values decoded to memory first
+    ("bf16", 16, 0, 1, 512, 16, 3.0),        # first layer
+    ("fp32", 16, 1, 2, 300, 16, 8.0),
+])
+def test_attend_values(B, dtype, n, layer, batch, S, QH, spread):
+    """aquakv_decode_values_attend: soft-max of the scores taken per 256 tokens and merged, against the oracle's
+    soft-max rows and weighted sum."""
+    print(f"case attend dtype={dtype} n={n} layer={layer} batch={batch} S={S} QH={QH} spread={spread}", flush=True)
+    H = 8
+    cfg = synth.Config("av", layers=2, kv_heads=H, head_dim=128, tokens=batch * S, dtype=dtype, n_codewords=n)
+    Ks, Vs, lo_l, lg_l = P.build_stack(cfg)
+    g = P.run_gpu_layers(B, cfg, lg_l, Ks, Vs)[layer]
+    lo, lg = lo_l[layer], lg_l[layer]
+    gen = torch.Generator().manual_seed(7000 + S + QH)
+    # rows with different offsets (the shift must not matter) and a chunk-to-chunk drift so that chunk maxima differ
+    s = torch.randn(batch, QH, S, generator=gen) * spread + torch.randn(batch, QH, 1, generator=gen) * 20.0 \
+        + torch.linspace(0, spread, S)[None, None, :]
+    s = s.float().cuda()
+    T = batch * S
+    out = torch.full((batch, QH, 128), float("nan"), dtype=torch.float32, device="cuda")
+    stats = torch.full((batch, QH, 2), float("nan"), dtype=torch.float32, device="cuda")
+    Vout = lg.alloc_kv(T)
+    ws = lg.alloc_weighted_workspace(batch, S, QH)
+    B.aquakv_decode_values_attend(lg, batch, S, QH, g["v_codes"], g["v_scales"], g["Vp"], g["Khat"], s, Vout, out, stats, ws)
+    sync()
+    assert torch.equal(P.bits(Vout), P.bits(g["Vhat"]))
+    p = O.softmax_rows(U.np64(s))
+    vp = None if g["Vp"] is None else U.np64(g["Vp"])
+    want, _ = O.attn_values(lo, batch, S, p, g["v_codes"].cpu().numpy(), g["v_scales"].cpu().numpy().view(np.float16), vp,
+                            U.np64(g["Khat"]))
+    Vh = U.np64(g["Vhat"]).reshape(batch, S, H, 128)
+    rep = QH // H
+    mag = np.stack([np.einsum("bt,btd->bd", p[:, qh], np.abs(Vh[:, :, qh // rep])) for qh in range(QH)], 1)
+    own = np.stack([np.einsum("bt,btd->bd", p[:, qh], Vh[:, :, qh // rep]) for qh in range(QH)], 1)
+    got = U.np64(out)
+    err, err_own = np.abs(got - want), np.abs(got - own)
+    # fp32 exponentials of differences up to a few tens (1e-6 relative each), weights with 16 mantissa bits
+    assert np.all(err_own <= 3e-5 * mag + 1e-30), float(np.max(err_own / (mag + 1e-30)))
+    # against the oracle the decoded values themselves differ within their storage tolerance, rtol (|v| + rms of the
+    # group), and the sum inherits that bound weight by weight
+    bound = U.RTOL[dtype] * (mag + np.stack([np.einsum("bt,bt->b", p[:, qh], group_rms(Vh)[:, :, qh // rep]) for qh in range(QH)], 1)[..., None])
+    assert np.all(err <= bound + 1e-30), float(np.max(err / (bound + 1e-30)))
+    M = U.np64(s).max(axis=-1)
+    L = np.exp(U.np64(s) - M[..., None]).sum(axis=-1)
+    st = U.np64(stats)
+    assert np.array_equal(st[..., 0], M)
+    assert np.all(np.abs(st[..., 1] - L) <= 2e-5 * L), float(np.max(np.abs(st[..., 1] - L) / L))
+    print(f"   worst error / sum p|v| = {float(np.max(err / (mag + 1e-30))):.3g} against the oracle, "
+          f"{float(np.max(err_own / (mag + 1e-30))):.3g} against the sum over the decoded values", flush=True)
+    if spread == 0.0:
+        assert np.all(np.abs(got - np.stack([Vh[:, :, qh // rep].mean(axis=1) for qh in range(QH)], 1)) <= 3e-5 * mag + 1e-30)
+    # the two-call form gives the same result up to the summation
+    pr = torch.empty_like(s)
+    B.aquakv_softmax(batch * QH, S, s, pr)
+    out2 = torch.empty_like(out)
+    B.aquakv_decode_values_weighted(lg, batch, S, QH, g["v_codes"], g["v_scales"], g["Vp"], g["Khat"], pr, Vout, out2, ws)
+    sync()
+    assert np.all(np.abs(U.np64(out2) - got) <= 4e-5 * mag + 1e-30)
+    fused = dtype == "bf16" and layer == 1 and S % 256 == 0
+    if fused:
+        out3 = torch.full_like(out, float("nan"))
+        B.aquakv_decode_values_attend(lg, batch, S, QH, g["v_codes"], g["v_scales"], g["Vp"], g["Khat"], s, None, out3, None, ws)
+        sync()
+        assert torch.equal(out3, out)
 
 
 @pytest.mark.parametrize("bits,rht_group", [(2, None), (4, None), (None, 1024)])
@@ -158,6 +235,16 @@ def test_attention_over_the_compressed_cache_end_to_end(B):
     err = np.abs(U.np64(out) - want)
     assert err.max() <= U.RTOL["bf16"] * rms, (err.max(), rms)
     print(f"   worst |error| / rms(V) = {err.max() / rms:.3g}", flush=True)
+    # the three-launch form: scores with the keys, then the values with the soft-max inside
+    B.aquakv_decode_attn_scores(lg, batch, S, QH, g["k_codes"], g["k_scales"], g["Kp"], q, scale, scores, Kout,
+                                lg.alloc_workspace(cfg.tokens))
+    out2 = torch.empty_like(out)
+    B.aquakv_decode_values_attend(lg, batch, S, QH, g["v_codes"], g["v_scales"], g["Vp"], Kout, scores, Vout, out2, None,
+                                  lg.alloc_weighted_workspace(batch, S, QH))
+    sync()
+    err2 = np.abs(U.np64(out2) - want)
+    assert err2.max() <= U.RTOL["bf16"] * rms, (err2.max(), rms)
+    print(f"   soft-max inside: worst |error| / rms(V) = {err2.max() / rms:.3g}", flush=True)
 
 
 def test_weighted_values_at_the_bench_shape(B):
