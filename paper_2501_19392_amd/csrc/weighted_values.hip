@@ -98,19 +98,26 @@ __global__ __launch_bounds__(kWideThreads) void softmax_rows_regs_kernel(const f
   }
 }
 
-template <typename T> __device__ __forceinline__ void load8(const T* p, float (&v)[8]);
-template <> __device__ __forceinline__ void load8<float>(const float* p, float (&v)[8]) {
-  const f32x4 a = reinterpret_cast<const f32x4*>(p)[0], b = reinterpret_cast<const f32x4*>(p)[1];
-  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-}
-template <> __device__ __forceinline__ void load8<bf16_t>(const bf16_t* p, float (&v)[8]) {
-  unpack_bf16x8(*reinterpret_cast<const u32x4*>(p), v);
-}
+// 8 consecutive values of a row as they lie in memory, and their fp32 form
+template <typename T> struct Raw8;
+template <> struct Raw8<float> {
+  f32x4 a, b;
+  __device__ __forceinline__ void load(const float* p) { a = reinterpret_cast<const f32x4*>(p)[0]; b = reinterpret_cast<const f32x4*>(p)[1]; }
+  __device__ __forceinline__ void get(float (&v)[8]) const {
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+};
+template <> struct Raw8<bf16_t> {
+  u32x4 a;
+  __device__ __forceinline__ void load(const bf16_t* p) { a = *reinterpret_cast<const u32x4*>(p); }
+  __device__ __forceinline__ void get(float (&v)[8]) const { unpack_bf16x8(a, v); }
+};
 
-// One workgroup per (sequence, chunk of 256 tokens, kv head).  Thread (tsub = tid / 16, l = tid % 16) walks tokens
-// tsub, tsub + 16, ... of the chunk and owns dims 8 l .. 8 l + 7; the 16 token classes are added through LDS.
-// The chunk is re-read (from cache) once per query head of the group: this is the path for what the fused
-// kernel does not cover, not the fast one.
+// One workgroup per (sequence, chunk of 256 tokens, kv head).  Thread (tsub = tid / 16, l = tid % 16) owns tokens
+// tsub, tsub + 16, ... of the chunk and dims 8 l .. 8 l + 7; it reads its 16 row pieces once (all loads in flight
+// together), keeps them in registers for the query heads of the group, and the 16 token classes are added through
+// LDS.  This is the path for what the fused kernel does not cover (no predictor, fp32, groups of 1024, ragged
+// sequences).
 // pstats (nullable): soft-max form, `weights` holds raw scores: the weights are exp(score - chunk maximum), and the
 // chunk's maximum and weight sum are written to pstats[chunk, qh, 2].
 template <typename T>
@@ -119,42 +126,51 @@ __global__ __launch_bounds__(kThreads) void weighted_values_kernel(const T* __re
                                                                    int seq_len, int H, int q_heads, int chunks_per_seq) {
   __shared__ float red[16][kGroup];
   __shared__ float buf[kThreads];
+  constexpr int kIters = kWeightedChunk / 16;
   const int b = blockIdx.x / chunks_per_seq, chunk = blockIdx.x % chunks_per_seq, head = blockIdx.y;
   const int rep = q_heads / H;
   const int tsub = threadIdx.x >> 4, l = threadIdx.x & 15;
-  const int t0 = chunk * kWeightedChunk;
+  const int t0 = chunk * kWeightedChunk + tsub;
   const T* vbase = Vhat + ((int64_t)b * seq_len * H + head) * kGroup + l * 8;
+  Raw8<T> rows[kIters];
+#pragma unroll
+  for (int it = 0; it < kIters; ++it) {
+    const int t = t0 + it * 16;
+    rows[it].load(vbase + (int64_t)(t < seq_len ? t : seq_len - 1) * H * kGroup);     // beyond the end: weight 0 below
+  }
   for (int r = 0; r < rep; ++r) {
     const int qh = head * rep + r;
     const float* w = weights + ((int64_t)b * q_heads + qh) * seq_len;
-    float shift = 0.f;
-    if (pstats != nullptr) {
-      float mx = -INFINITY;
-      for (int it = 0; it < kWeightedChunk / 16; ++it) {
-        const int t = t0 + it * 16 + tsub;
-        if (t < seq_len) mx = fmaxf(mx, w[t]);
-      }
-      shift = block_reduce<true>(mx, buf);
-    }
-    float acc[8] = {};
-    float wsum = 0.f;
-    for (int it = 0; it < kWeightedChunk / 16; ++it) {
-      const int t = t0 + it * 16 + tsub;
-      if (t < seq_len) {
-        float v[8];
-        load8<T>(vbase + (int64_t)t * H * kGroup, v);
-        const float wt = pstats != nullptr ? expf(w[t] - shift) : w[t];
-        wsum += wt;
+    float wt[kIters];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] = __fmaf_rn(wt, v[i], acc[i]);
-      }
+    for (int it = 0; it < kIters; ++it) {
+      const int t = t0 + it * 16;
+      wt[it] = t < seq_len ? w[t] : (pstats != nullptr ? -INFINITY : 0.f);
     }
     if (pstats != nullptr) {
+      float mx = wt[0];
+#pragma unroll
+      for (int it = 1; it < kIters; ++it) mx = fmaxf(mx, wt[it]);
+      const float shift = block_reduce<true>(mx, buf);
+      float wsum = 0.f;
+#pragma unroll
+      for (int it = 0; it < kIters; ++it) {
+        wt[it] = expf(wt[it] - shift);                       // exp(-inf) = 0 for tokens beyond the end
+        wsum += wt[it];
+      }
       const float total = block_reduce<false>(l == 0 ? wsum : 0.f, buf);      // every token counted once
       if (threadIdx.x == 0) {
         pstats[((int64_t)blockIdx.x * q_heads + qh) * 2] = shift;
         pstats[((int64_t)blockIdx.x * q_heads + qh) * 2 + 1] = total;
       }
+    }
+    float acc[8] = {};
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) {
+      float v[8];
+      rows[it].get(v);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] = __fmaf_rn(wt[it], v[i], acc[i]);
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i) red[tsub][l * 8 + i] = acc[i];
