@@ -74,7 +74,8 @@ levels, the half-step error bound, 0 decoding to 0, group independence, the
 for the value side: soft-max against scipy's routine, shift invariance and rows
 summing to one, one-hot weights returning a decoded row, uniform weights the
 mean, brute-force triple loop with the grouped-query head map, linearity in the
-weights, and the full attention against torch's scaled_dot_product_attention.
+weights, and the full attention against torch's scaled_dot_product_attention
+(also for `attention` over given keys and values, with its row statistics).
 No function here is "parity unpinned".
 """
 from __future__ import annotations
@@ -553,3 +554,25 @@ def attn_values(layer: Layer, batch: int, seq_len: int, weights, v_codes, v_scal
     for qh in range(q_heads):
         out[:, qh, :] = np.einsum("bt,btd->bd", w[:, qh, :], Vhat[:, :, qh // rep, :])
     return out, Vhat.reshape(T, layer.kv_heads, layer.head_dim)
+
+
+def attention(q, K, V, score_scale=1.0):
+    """Attention of one query per sequence and query head over given keys and values (the block call of
+    Alg. "Inference" for one new token): scores s[b, qh, t] = score_scale * q[b, qh] . K[b, t, kvh(qh)],
+    out[b, qh] = sum_t softmax_t(s)[t] * V[b, t, kvh(qh)], query head qh reading kv head qh // (q_heads // kv_heads).
+    q: [batch, q_heads, g]; K, V: [batch, tokens, kv_heads, g].
+    Returns (out, M, L) with M the row maximum of s and L = sum_t exp(s - M).
+    """
+    q, K, V = (np.asarray(a, dtype=np.float64) for a in (q, K, V))
+    batch, q_heads, _ = q.shape
+    rep = q_heads // K.shape[2]
+    out = np.empty_like(q)
+    M = np.empty((batch, q_heads))
+    L = np.empty((batch, q_heads))
+    for qh in range(q_heads):
+        s = score_scale * np.einsum("bd,btd->bt", q[:, qh], K[:, :, qh // rep])
+        M[:, qh] = s.max(axis=1)
+        e = np.exp(s - M[:, qh, None])
+        L[:, qh] = e.sum(axis=1)
+        out[:, qh] = np.einsum("bt,btd->bd", e / L[:, qh, None], V[:, :, qh // rep])
+    return out, M, L

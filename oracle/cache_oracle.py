@@ -106,6 +106,16 @@ class CacheOracle:
                 parts_k.append(self.buf_k[l]); parts_v.append(self.buf_v[l])
             yield l, np.concatenate(parts_k, axis=0), np.concatenate(parts_v, axis=0)
 
+    def attend(self, queries, score_scale: float):
+        """Attention of one new token's queries over everything cached (Alg. "Inference", the block call with
+        K = [recovered past], one token): queries[l] is [q_heads, head_dim]; returns one [q_heads, head_dim] per layer.
+        The soft-max runs over sinks, recovered compressed tokens and buffered tokens alike."""
+        out = []
+        for l, K, V in self.sweep():
+            o, _, _ = O.attention(np.asarray(queries[l], dtype=np.float64)[None], K[None], V[None], score_scale)
+            out.append(o[0])
+        return out
+
     def stored_bytes(self, elem_bytes: int = 2) -> int:
         """Bytes held for all layers: uncompressed sinks and buffer, packed codes and fp16 scales."""
         some = next(l for l in self.layers if l is not None)

@@ -9,8 +9,14 @@ Sect. 4.1 (first-layer strategies): every layer brings its own grid (the paper's
 which has no predictor, with the 4-bit grid), and a layer given as None is kept in 16 bits (its flushed tokens are
 stored as they are and feed the next layer's predictors).
 
+`attend` is the block call of Alg. "Inference" for one new token as far as the cache is concerned: per layer the
+soft-max attention of that token's queries over everything cached.  The compressed range is scored and summed by the
+decode kernels themselves (`aquakv_decode_attn_scores` with the keys as output, `aquakv_decode_values_attend`), the
+sinks and the buffer by `aquakv_attend_raw`, which merges its share into the running result.
+
 This class is bookkeeping only: every number is produced by the C-ABI calls (`aquakv_encode_layer`,
-`aquakv_decode_layer`); torch tensors are the device memory they work on.  One sequence per cache.
+`aquakv_decode_layer`, the attention calls above); torch tensors are the device memory they work on.  One sequence per
+cache.
 """
 from __future__ import annotations
 
@@ -46,6 +52,8 @@ class AquaKVCache:
         self._view = [(raw(max_tokens), raw(max_tokens)) for _ in range(2)]
         self._view_ws = max((l.alloc_workspace(max(cap, 1), device) for l in coded), key=lambda t: t.numel())
         self.n_sink = self.n_compressed = self.n_buffered = 0
+        self._attend = None                 # buffers of attend(), sized on first use (they depend on the query heads)
+        self._device = device
 
     @property
     def n_tokens(self) -> int:
@@ -113,6 +121,56 @@ class AquaKVCache:
             if b:
                 K[s + c:s + c + b].copy_(self.buf[l][0][:b]); V[s + c:s + c + b].copy_(self.buf[l][1][:b])
             yield l, K[:s + c + b], V[:s + c + b]
+
+    def attend(self, queries: Sequence[torch.Tensor], score_scale: float) -> List[torch.Tensor]:
+        """queries[l]: [q_heads, head_dim] in the storage dtype, the new token's queries at layer l.  Returns one
+        fp32 [q_heads, head_dim] per layer: softmax(score_scale * q K^T) V over sinks, compressed past and buffer.
+        One sweep over the layers; the recovered tensors of layer l feed layer l + 1 as in `sweep`."""
+        s, c, b = self.n_sink, self.n_compressed, self.n_buffered
+        if s + c + b == 0:
+            raise ValueError("nothing cached")
+        lay0 = next(l for l in self.layers if l is not None)
+        H, g, dt = lay0.kv_heads, lay0.head_dim, lay0.dtype
+        QH = queries[0].shape[0]
+        if self._attend is None or self._attend["q_heads"] != QH:
+            cap = max(self.capacity, 1)
+            coded = [l for l in self.layers if l is not None]
+            self._attend = dict(
+                q_heads=QH,
+                scores=torch.empty(QH * cap, dtype=torch.float32, device=self._device),
+                out=[torch.empty(1, QH, g, dtype=torch.float32, device=self._device) for _ in self.layers],
+                stats=torch.empty(1, QH, 2, dtype=torch.float32, device=self._device),
+                ws=max((l.alloc_weighted_workspace(1, cap, QH, self._device) for l in coded), key=lambda t: t.numel()))
+        A = self._attend
+        step = 4096                                              # tokens per aquakv_attend_raw call
+        Kp = Vp = None
+        for l, lay in enumerate(self.layers):
+            q = queries[l].reshape(1, QH, g)
+            out, stats = A["out"][l], A["stats"]
+            have = False
+            if c and lay is None:                                # compressed range kept in 16 bits
+                Kp, Vp = self.raw[l][0][:c], self.raw[l][1][:c]
+                for r0 in range(0, c, step):
+                    n = min(step, c - r0)
+                    B.aquakv_attend_raw(dt, 1, n, H, QH, Kp[r0:r0 + n], Vp[r0:r0 + n], q, score_scale, out, stats, have)
+                    have = True
+            elif c:
+                (kc, ks), (vc, vs) = self.codes[l]
+                K, V = self._view[l & 1]
+                scores = A["scores"][:QH * c].view(1, QH, c)
+                B.aquakv_decode_attn_scores(lay, 1, c, QH, kc[:c], ks[:c], Kp, q, score_scale, scores, K[:c], self._view_ws)
+                B.aquakv_decode_values_attend(lay, 1, c, QH, vc[:c], vs[:c], Vp, K[:c], scores, V[:c], out, stats, A["ws"])
+                Kp, Vp = K[:c], V[:c]
+                have = True
+            if s:
+                B.aquakv_attend_raw(dt, 1, s, H, QH, self.sink[l][0][:s], self.sink[l][1][:s], q, score_scale, out, stats, have)
+                have = True
+            for r0 in range(0, b, step):
+                n = min(step, b - r0)
+                B.aquakv_attend_raw(dt, 1, n, H, QH, self.buf[l][0][r0:r0 + n], self.buf[l][1][r0:r0 + n], q, score_scale,
+                                    out, stats, have)
+                have = True
+        return [o[0] for o in A["out"]]
 
     def stored_bytes(self) -> int:
         """Bytes the cache content occupies (all layers): 16-bit sinks and buffer, packed codes and fp16 scales."""

@@ -586,6 +586,30 @@ int aquakv_decode_values_attend(const aquakv_layer* L, int32_t batch, int32_t se
                                 row_stats, workspace, workspace_bytes, stream);
 }
 
+int aquakv_attend_raw(int32_t dtype, int32_t batch, int32_t tokens, int32_t kv_heads, int32_t q_heads, const void* K,
+                      const void* V, const void* q, float score_scale, float* out, float* row_stats, int32_t accumulate,
+                      void* stream) {
+  if (dtype != AQUAKV_BF16 && dtype != AQUAKV_FP32) return fail(AQUAKV_EINVAL, "dtype=%d", dtype);
+  if (batch < 0 || tokens < 0) return fail(AQUAKV_EINVAL, "batch=%d tokens=%d", batch, tokens);
+  if (tokens > aquakv::kAttendRawMaxTokens)
+    return fail(AQUAKV_EUNSUPPORTED, "tokens=%d: at most %d uncompressed tokens per call", tokens, aquakv::kAttendRawMaxTokens);
+  if (kv_heads < 1 || q_heads < 1 || q_heads % kv_heads)
+    return fail(AQUAKV_EINVAL, "q_heads=%d must be a multiple of kv_heads=%d", q_heads, kv_heads);
+  CHECK(check_ptr(K, "K", tokens != 0));
+  CHECK(check_ptr(V, "V", tokens != 0));
+  CHECK(check_ptr(q, "q", true));
+  CHECK(check_ptr(out, "out", true));
+  CHECK(check_ptr(row_stats, "row_stats", true));
+  if (batch == 0) return AQUAKV_OK;
+  if (tokens == 0) {
+    if (!accumulate) return fail(AQUAKV_EINVAL, "tokens=0 leaves nothing to write without a result to merge into");
+    return AQUAKV_OK;
+  }
+  HIP_TRY(aquakv::launch_attend_raw(dtype, K, V, q, score_scale, out, row_stats, batch, tokens, kv_heads, q_heads,
+                                    accumulate != 0, static_cast<hipStream_t>(stream)));
+  return AQUAKV_OK;
+}
+
 // ---- calibration: ridge least-squares fit of one predictor (Alg. "Calibration") --------------------------------
 size_t aquakv_fit_workspace_bytes(int32_t d_in, int32_t d_out) {
   if (d_in < 64 || d_in > 8192 || d_in % 64 || d_out < 64 || d_out > 8192 || d_out % 64) return 0;

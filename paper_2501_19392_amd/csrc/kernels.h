@@ -68,6 +68,12 @@ hipError_t launch_weighted_values(int dtype, const void* Vhat, const float* weig
                                   int seq_len, int H, int q_heads, hipStream_t stream);
 hipError_t launch_combine_weighted(const float* part, const float* pstats, float* out, float* row_stats, int batch,
                                    int seq_len, int q_heads, hipStream_t stream);
+// Attention of one query per sequence over `tokens` (<= kAttendRawMaxTokens) keys / values in the storage dtype
+// ([batch * tokens, H, 128]), written to or merged into (accumulate != 0) out [batch, q_heads, 128] and the row
+// statistics [batch, q_heads, 2] (maximum, sum of exp(score - maximum)) that launch_combine_weighted hands out.
+constexpr int kAttendRawMaxTokens = 4096;
+hipError_t launch_attend_raw(int dtype, const void* K, const void* V, const void* q, float scale, float* out, float* stats,
+                             int batch, int tokens, int H, int q_heads, int accumulate, hipStream_t stream);
 // probs[r, :] = softmax(scores[r, :]) for `rows` rows of length n (in place allowed)
 hipError_t launch_softmax_rows(const float* scores, float* probs, int64_t rows, int64_t n, hipStream_t stream);
 

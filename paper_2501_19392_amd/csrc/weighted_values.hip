@@ -260,6 +260,69 @@ __global__ __launch_bounds__(kThreads) void combine_softmax_kernel(const float* 
   }
 }
 
+// Attention of one query per sequence and query head over `tokens` keys / values held in the storage dtype (the
+// attention sinks and the recent-token buffer of Sect. 3.3, which are not quantized), merged into a running result.
+// One workgroup per (sequence, query head): scores s_t = scale * q . k_t (a wave per token, 2 dims per lane), their
+// maximum m and l = sum exp(s_t - m) through the block reductions, o = sum exp(s_t - m) v_t (thread = dim and token
+// parity).  accumulate == 0: out = o / l, stats = (m, l).  Otherwise (out, stats) hold a result over other tokens,
+// out normalised by its own L: M' = max(M, m), L' = L e^(M - M') + l e^(m - M'),
+// out' = (out L e^(M - M') + o e^(m - M')) / L'.
+constexpr int kRawMaxTokens = kAttendRawMaxTokens;
+template <typename T>
+__global__ __launch_bounds__(kThreads) void attend_raw_kernel(const T* __restrict__ K, const T* __restrict__ V,
+                                                              const T* __restrict__ q, float scale, float* out,
+                                                              float* stats, int tokens, int H, int q_heads, int accumulate) {
+  __shared__ float sc[kRawMaxTokens];
+  __shared__ float buf[kThreads];
+  __shared__ float half_sum[kGroup];
+  const int b = blockIdx.x / q_heads, qh = blockIdx.x % q_heads;
+  const int head = qh / (q_heads / H);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const T* qp = q + ((int64_t)b * q_heads + qh) * kGroup;
+  const float q0 = static_cast<float>(qp[2 * lane]), q1 = static_cast<float>(qp[2 * lane + 1]);
+  const T* kb = K + ((int64_t)b * tokens * H + head) * kGroup;
+  const T* vb = V + ((int64_t)b * tokens * H + head) * kGroup;
+  for (int t = wave; t < tokens; t += kThreads / 64) {
+    const T* kp = kb + (int64_t)t * H * kGroup;
+    float d = __fmaf_rn(q1, static_cast<float>(kp[2 * lane + 1]), q0 * static_cast<float>(kp[2 * lane]));
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) d += __shfl_xor(d, m);
+    if (lane == 0) sc[t] = d * scale;
+  }
+  __syncthreads();
+  float mx = -INFINITY;
+  for (int t = threadIdx.x; t < tokens; t += kThreads) mx = fmaxf(mx, sc[t]);
+  const float m = block_reduce<true>(mx, buf);
+  float ls = 0.f;
+  for (int t = threadIdx.x; t < tokens; t += kThreads) {
+    const float e = expf(sc[t] - m);
+    sc[t] = e;                                  // each entry is touched by one thread only
+    ls += e;
+  }
+  const float l = block_reduce<false>(ls, buf);       // its barriers also publish the exponentials
+  const int d = threadIdx.x & (kGroup - 1), par = threadIdx.x >> 7;
+  float o = 0.f;
+  for (int t = par; t < tokens; t += 2) o = __fmaf_rn(sc[t], static_cast<float>(vb[(int64_t)t * H * kGroup + d]), o);
+  if (par == 1) half_sum[d] = o;
+  float* st = stats + ((int64_t)b * q_heads + qh) * 2;
+  float M = 0.f, L = 0.f;
+  if (accumulate) { M = st[0]; L = st[1]; }     // read by every thread before the barrier, rewritten after it
+  __syncthreads();
+  if (par == 0) {
+    o += half_sum[d];
+    float* op = out + ((int64_t)b * q_heads + qh) * kGroup + d;
+    float M2 = m, L2 = l, res = o / l;
+    if (accumulate) {
+      M2 = fmaxf(M, m);
+      const float ea = expf(M - M2), eb = expf(m - M2);
+      L2 = __fmaf_rn(L, ea, l * eb);
+      res = __fmaf_rn(*op * L, ea, o * eb) / L2;
+    }
+    *op = res;
+    if (d == 0) { st[0] = M2; st[1] = L2; }
+  }
+}
+
 }  // namespace
 
 hipError_t launch_softmax_rows(const float* scores, float* probs, int64_t rows, int64_t n, hipStream_t stream) {
@@ -301,6 +364,21 @@ hipError_t launch_combine_weighted(const float* part, const float* pstats, float
     return hipGetLastError();
   }
   combine_weighted_kernel<<<(unsigned)((total + 31) / 32), kThreads, 0, stream>>>(part, out, chunks, row, total);
+  return hipGetLastError();
+}
+
+hipError_t launch_attend_raw(int dtype, const void* K, const void* V, const void* q, float scale, float* out, float* stats,
+                             int batch, int tokens, int H, int q_heads, int accumulate, hipStream_t stream) {
+  if (batch == 0 || tokens == 0) return hipSuccess;
+  const unsigned grid = (unsigned)batch * q_heads;
+  if (dtype == kBF16)
+    attend_raw_kernel<bf16_t><<<grid, kThreads, 0, stream>>>(static_cast<const bf16_t*>(K), static_cast<const bf16_t*>(V),
+                                                             static_cast<const bf16_t*>(q), scale, out, stats, tokens, H,
+                                                             q_heads, accumulate);
+  else
+    attend_raw_kernel<float><<<grid, kThreads, 0, stream>>>(static_cast<const float*>(K), static_cast<const float*>(V),
+                                                            static_cast<const float*>(q), scale, out, stats, tokens, H,
+                                                            q_heads, accumulate);
   return hipGetLastError();
 }
 

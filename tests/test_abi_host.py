@@ -213,6 +213,15 @@ def test_weighted_values_call_validates_its_arguments():
     assert status_of(B.aquakv_softmax, -1, 10, FAKE, FAKE) == B.AQUAKV_EINVAL
     B.aquakv_softmax(0, 10, FAKE, FAKE)
     B.aquakv_softmax(4, 0, FAKE, FAKE)
+    raw = B.aquakv_attend_raw                                                       # dtype batch tokens H QH K V q scale out stats acc
+    assert status_of(raw, 7, 1, 8, 8, 8, FAKE, FAKE, FAKE, 1.0, FAKE, FAKE, False) == B.AQUAKV_EINVAL
+    assert status_of(raw, B.AQUAKV_BF16, 1, 8, 8, 12, FAKE, FAKE, FAKE, 1.0, FAKE, FAKE, False) == B.AQUAKV_EINVAL
+    assert status_of(raw, B.AQUAKV_BF16, 1, 4097, 8, 8, FAKE, FAKE, FAKE, 1.0, FAKE, FAKE, False) == B.AQUAKV_EUNSUPPORTED
+    assert status_of(raw, B.AQUAKV_BF16, 1, 8, 8, 8, None, FAKE, FAKE, 1.0, FAKE, FAKE, False) == B.AQUAKV_ENULL
+    assert status_of(raw, B.AQUAKV_BF16, 1, 8, 8, 8, FAKE, FAKE, FAKE, 1.0, FAKE, None, False) == B.AQUAKV_ENULL
+    assert status_of(raw, B.AQUAKV_BF16, 1, 0, 8, 8, None, None, FAKE, 1.0, FAKE, FAKE, False) == B.AQUAKV_EINVAL   # nothing to write
+    raw(B.AQUAKV_BF16, 1, 0, 8, 8, None, None, FAKE, 1.0, FAKE, FAKE, True)           # nothing to merge: no-op
+    raw(B.AQUAKV_BF16, 0, 8, 8, 8, FAKE, FAKE, FAKE, 1.0, FAKE, FAKE, False)
 
 
 def test_round_to_nearest_backbone_layer_validation():

@@ -228,3 +228,101 @@ def test_gpu_cache_manager_with_the_papers_first_layer_strategies(first):
     sync()
     (gkc, gks), (gvc, gvs) = gpu.codes[1]
     assert torch.equal(gkc[:n], kc1) and torch.equal(gks[:n], ks1) and torch.equal(gvc[:n], vc1) and torch.equal(gvs[:n], vs1)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("first,rht_group,r,pieces", [("2bit", None, 128, (5, 251, 256, 30)), ("4bit", 1024, 128, (3, 130, 127, 40)),
+                                                      ("bf16", 1024, 32, (4, 64, 1)), ("2bit", None, 64, (2,))])
+def test_gpu_cache_attention_of_a_new_token_over_everything_cached(first, rht_group, r, pieces):
+    """AquaKVCache.attend against the policy oracle's plain soft-max attention over [sinks | recovered past | buffer]:
+    the compressed range goes through the decode kernels (sums inside the kernel when its length is a multiple of
+    256), sinks and buffer through aquakv_attend_raw, merged by their row statistics."""
+    from paper_2501_19392_amd.cache import AquaKVCache
+    from tests import parity_utils as U
+    from tests.test_gpu_parity import sync
+    print(f"case cache attend first={first} rht_group={rht_group} r={r} pieces={pieces}", flush=True)
+    L, H, QH, sink = 3, 8, 24, 4
+    T = sum(pieces)
+    cfg = synth.Config("cache", layers=L, kv_heads=H, head_dim=128, tokens=T, dtype="bf16")
+    st = synth.KVStream(cfg, device="cpu", work=torch.float64)
+    Ks, Vs, lo_l, lg_l = [], [], [], []
+    for l in range(L):
+        K, V = st.next()
+        Ks.append(K.cuda()); Vs.append(V.cuda())
+        if l == 0:
+            lo, lg = (None, None) if first == "bf16" else U.make_layers(H, "bf16", 256 if first == "4bit" else 16, layer_idx=0,
+                                                                        rht_group=rht_group)
+        else:
+            wk, wv = synth.analytic_predictors(st, l)
+            lo, lg = U.make_layers(H, "bf16", 16, layer_idx=l, w_k=wk, w_v=wv, rht_group=rht_group)
+        lo_l.append(lo); lg_l.append(lg)
+    gpu = AquaKVCache(lg_l, max_tokens=T, sink_tokens=sink, buffer_tokens=r)
+    cpu = CacheOracle(lo_l, sink_tokens=sink, buffer_tokens=r)
+    pos = 0
+    for piece in pieces:
+        gpu.append([(K[pos:pos + piece], V[pos:pos + piece]) for K, V in zip(Ks, Vs)])
+        cpu.append([(U.np64(K[pos:pos + piece]), U.np64(V[pos:pos + piece])) for K, V in zip(Ks, Vs)])
+        pos += piece
+    assert (gpu.n_sink, gpu.n_compressed, gpu.n_buffered) == (cpu.n_sink, cpu.n_compressed, cpu.n_buffered)
+    scale = 128 ** -0.5
+    qs = [synth.random_queries(1, QH, 128, seed=900 + l, dtype="bf16", device="cuda")[0] * 3.0 for l in range(L)]
+    for rep in range(2):                                     # a second call reuses the buffers
+        got = [o.clone() for o in gpu.attend(qs, scale)]
+        sync()
+        # (a) against the plain soft-max attention over the tensors the manager itself recovers (its sweep is checked
+        # against the policy oracle by the tests above): what is left is the arithmetic of the attention calls
+        forced = {}
+        for l, K, V in gpu.sweep():
+            sync()
+            forced[l], _, _ = O.attention(U.np64(qs[l])[None], U.np64(K)[None], U.np64(V)[None], scale)
+        # (b) free-running against the policy oracle, whose own encoder may take the other side of a tie: a changed
+        # code moves a key by a fraction of its size and a peaked soft-max amplifies that, so this comparison uses
+        # queries scaled down to flat attention rows
+        flat = [q * 0.125 for q in qs]
+        got_flat = [o.clone() for o in gpu.attend(flat, scale)]
+        sync()
+        want = cpu.attend([U.np64(q) for q in flat], scale)
+        for l in range(L):
+            rms = float(np.sqrt(np.mean(U.np64(Vs[l]) ** 2)))
+            err = float(np.abs(U.np64(got[l]) - forced[l][0]).max())
+            assert err <= 1e-3 * rms, (l, err, rms)
+            err_free = float(np.abs(U.np64(got_flat[l]) - want[l]).max())
+            assert err_free <= U.RTOL["bf16"] * rms, (l, err_free, rms)
+            if rep == 0:
+                print(f"   layer {l}: {gpu.n_sink} + {gpu.n_compressed} + {gpu.n_buffered} tokens, worst |error| / rms(V) = "
+                      f"{err / rms:.3g} on the manager's own tensors, {err_free / rms:.3g} free-running against the oracle (flat rows)", flush=True)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_gpu_attend_raw_and_its_merge(dtype):
+    """aquakv_attend_raw on its own: attention over tokens held in the storage dtype, then a second token set merged in."""
+    from paper_2501_19392_amd import binding as B
+    from tests import parity_utils as U
+    from tests.test_gpu_parity import storage_randn, sync
+    print(f"case attend_raw dtype={dtype}", flush=True)
+    batch, H, QH, n1, n2 = 3, 8, 32, 133, 700
+    sd = synth.torch_dtype(dtype)
+    K = storage_randn((batch, n1 + n2, H, 128), dtype, 31)
+    V = storage_randn((batch, n1 + n2, H, 128), dtype, 32)
+    q = storage_randn((batch, QH, 128), dtype, 33, scale=2.0)
+    scale = 0.11
+    out = torch.full((batch, QH, 128), float("nan"), dtype=torch.float32, device="cuda")
+    stats = torch.full((batch, QH, 2), float("nan"), dtype=torch.float32, device="cuda")
+    Ka, Va = K[:, :n1].contiguous(), V[:, :n1].contiguous()
+    Kb, Vb = K[:, n1:].contiguous(), V[:, n1:].contiguous()
+    B.aquakv_attend_raw(sd, batch, n1, H, QH, Ka, Va, q, scale, out, stats, False)
+    sync()
+    tol = 2e-5                       # fp32 dot products of 128 terms, exponentials, sums of a few hundred terms
+    for (Kx, Vx) in ((Ka, Va), (K, V)):
+        want, M, Lw = O.attention(U.np64(q), U.np64(Kx), U.np64(Vx), scale)
+        mag = np.abs(U.np64(Vx)).max()
+        assert np.abs(U.np64(out) - want).max() <= tol * mag
+        assert np.abs(U.np64(stats[..., 0]) - M).max() <= 1e-5 * np.abs(M).max()
+        assert np.all(np.abs(U.np64(stats[..., 1]) - Lw) <= 1e-4 * Lw)
+        if Kx is Ka:
+            B.aquakv_attend_raw(sd, batch, n2, H, QH, Kb, Vb, q, scale, out, stats, True)     # merge the second set
+            sync()
+    B.aquakv_attend_raw(sd, batch, 0, H, QH, None, None, q, scale, out, stats, True)          # nothing to merge: no-op
+    with pytest.raises(B.AquaKVError):
+        B.aquakv_attend_raw(sd, batch, 4097, H, QH, K, V, q, scale, out, stats, False)

@@ -391,6 +391,27 @@ def test_scores_softmax_values_are_torch_attention_over_the_decoded_cache():
     assert np.allclose(out, want[:, :, 0, :].numpy(), rtol=1e-12, atol=1e-13)
 
 
+def test_attention_over_given_tokens_is_torch_attention_and_its_statistics_are_the_log_sum_exp():
+    B_, S, H, QH, g = 2, 11, 2, 6, 128
+    q = rng(61).standard_normal((B_, QH, g))
+    K, V = rng(62).standard_normal((2, B_, S, H, g))
+    scale = 0.3
+    out, M, L = O.attention(q, K, V, scale)
+    Kt, Vt = (torch.from_numpy(a).permute(0, 2, 1, 3).repeat_interleave(QH // H, dim=1) for a in (K, V))
+    want = torch.nn.functional.scaled_dot_product_attention(torch.from_numpy(q)[:, :, None, :], Kt, Vt, scale=scale)
+    assert np.allclose(out, want[:, :, 0, :].numpy(), rtol=1e-12, atol=1e-13)
+    s = scale * torch.einsum("bhd,bhtd->bht", torch.from_numpy(q), Kt)
+    assert np.allclose(M + np.log(L), torch.logsumexp(s, dim=-1).numpy(), rtol=1e-13)
+    assert np.allclose(M, s.max(dim=-1).values.numpy(), rtol=1e-14)       # summation order of the dot product aside
+    # splitting the tokens and merging by the statistics gives the same attention (what callers of the library do)
+    oa, Ma, La = O.attention(q, K[:, :4], V[:, :4], scale)
+    ob, Mb, Lb = O.attention(q, K[:, 4:], V[:, 4:], scale)
+    Mm = np.maximum(Ma, Mb)
+    wa, wb = La * np.exp(Ma - Mm), Lb * np.exp(Mb - Mm)
+    merged = (oa * wa[..., None] + ob * wb[..., None]) / (wa + wb)[..., None]
+    assert np.allclose(merged, out, rtol=1e-12, atol=1e-13)
+
+
 # ------------------------------------------------------------------ rotary embedding of the decoded keys
 def test_rope_is_a_rotation_by_the_token_angle():
     g, S = 128, 37
