@@ -247,26 +247,41 @@ def test_attention_over_the_compressed_cache_end_to_end(B):
     print(f"   soft-max inside: worst |error| / rms(V) = {err2.max() / rms:.3g}", flush=True)
 
 
-def test_weighted_values_at_the_bench_shape(B):
-    """The launch configuration the benchmark times (8192 tokens, 8 kv heads, 24 query heads, n = 16): sums against
-    the fp64 sum over the values the same call wrote, whose rows other tests check against the oracle."""
-    print("case weighted at 8192 tokens", flush=True)
-    H, QH, batch, S = 8, 24, 1, 8192
+@pytest.mark.parametrize("S,QH", [(8192, 24), (32768, 32)])
+def test_weighted_values_at_the_bench_shapes(B, S, QH):
+    """The launch configurations the benchmark times (8192 tokens with 24 query heads, 32768 with 32; 8 kv heads,
+    n = 16): both forms against the fp64 sums over the values the same call wrote, whose rows other tests check
+    against the oracle."""
+    print(f"case weighted at {S} tokens, {QH} query heads", flush=True)
+    H, batch = 8, 1
+    rep = QH // H
     cfg = synth.Config("wb", layers=2, kv_heads=H, head_dim=128, tokens=S, dtype="bf16", n_codewords=16)
     Ks, Vs, lo_l, lg_l = P.build_stack(cfg)
     g = P.run_gpu_layers(B, cfg, lg_l, Ks, Vs)[1]
     lg = lg_l[1]
-    w = weights_for(batch, QH, S, 17, "softmax")
+    gen = torch.Generator().manual_seed(17)
+    scores = (torch.randn(batch, QH, S, generator=gen) * 4.0 + torch.linspace(-3, 3, S)[None, None, :]).float().cuda()
+    w = torch.softmax(scores, dim=-1)
     out = torch.empty(batch, QH, 128, dtype=torch.float32, device="cuda")
+    out2 = torch.empty_like(out)
+    stats = torch.empty(batch, QH, 2, dtype=torch.float32, device="cuda")
     Vout = lg.alloc_kv(S)
-    B.aquakv_decode_values_weighted(lg, batch, S, QH, g["v_codes"], g["v_scales"], g["Vp"], g["Khat"], w, Vout, out,
-                                    lg.alloc_weighted_workspace(batch, S, QH))
+    ws = lg.alloc_weighted_workspace(batch, S, QH)
+    B.aquakv_decode_values_weighted(lg, batch, S, QH, g["v_codes"], g["v_scales"], g["Vp"], g["Khat"], w, Vout, out, ws)
+    sync()
+    assert torch.equal(P.bits(Vout), P.bits(g["Vhat"]))
+    Vout.zero_()
+    B.aquakv_decode_values_attend(lg, batch, S, QH, g["v_codes"], g["v_scales"], g["Vp"], g["Khat"], scores, Vout, out2, stats, ws)
     sync()
     assert torch.equal(P.bits(Vout), P.bits(g["Vhat"]))
     Vh = U.np64(Vout).reshape(S, H, 128)
-    wd = U.np64(w)[0]
-    own = np.stack([wd[qh] @ Vh[:, qh // 3] for qh in range(QH)])
-    mag = np.stack([np.abs(wd[qh]) @ np.abs(Vh[:, qh // 3]) for qh in range(QH)])
-    err = np.abs(U.np64(out)[0] - own)
-    assert np.all(err <= 2e-5 * mag), float(np.max(err / mag))
-    print(f"   worst error / sum|w||v| = {float(np.max(err / mag)):.3g}", flush=True)
+    for got, wd, tol in ((out, U.np64(w)[0], 2e-5), (out2, O.softmax_rows(U.np64(scores))[0], 3e-5)):
+        own = np.stack([wd[qh] @ Vh[:, qh // rep] for qh in range(QH)])
+        mag = np.stack([np.abs(wd[qh]) @ np.abs(Vh[:, qh // rep]) for qh in range(QH)])
+        err = np.abs(U.np64(got)[0] - own)
+        assert np.all(err <= tol * mag), float(np.max(err / mag))
+        print(f"   worst error / sum|w||v| = {float(np.max(err / mag)):.3g}", flush=True)
+    sd = U.np64(scores)[0]
+    assert np.array_equal(U.np64(stats)[0, :, 0], sd.max(axis=1))
+    Lw = np.exp(sd - sd.max(axis=1, keepdims=True)).sum(axis=1)
+    assert np.all(np.abs(U.np64(stats)[0, :, 1] - Lw) <= 2e-5 * Lw)
