@@ -694,6 +694,20 @@ def test_full_size_layers_on_sampled_rows(B, name, T, n_per_layer):
         mag = 0.088388 * np.einsum("qd,tqd->qt", np.abs(U.np64(q)[0]), np.abs(k64))
         got = U.np64(scores[0][:, rows])
         assert np.all(np.abs(got - want) <= U.RTOL["bf16"] * mag + 1e-30), float(np.max(np.abs(got - want) / (mag + 1e-30)))
+        # the value half with the attention output (soft-max of those scores inside): same values, and the output is
+        # the oracle's soft-max-weighted sum over the values the call wrote (every output depends on all rows)
+        out = torch.empty(1, QH, 128, dtype=torch.float32, device="cuda")
+        Vd3 = lg.alloc_kv(T)
+        B.aquakv_decode_values_attend(lg, 1, T, QH, vc, vs, Vp, Kd2, scores, Vd3, out, None, lg.alloc_weighted_workspace(1, T, QH))
+        sync()
+        assert torch.equal(bits(Vd3), bits(Vh))
+        p_rows = O.softmax_rows(U.np64(scores))[0]
+        v64 = U.np64(Vh)
+        own = np.stack([p_rows[qh] @ v64[:, qh // (QH // 8)] for qh in range(QH)])
+        mag_v = np.stack([p_rows[qh] @ np.abs(v64[:, qh // (QH // 8)]) for qh in range(QH)])
+        err_v = np.abs(U.np64(out)[0] - own)
+        assert np.all(err_v <= 3e-5 * mag_v), float(np.max(err_v / mag_v))
+        del v64
         # properties that hold at any size: every scale is a finite non-negative fp16, the relative
         # reconstruction error of the whole tensor is what the grid and the predictor allow
         s = ks.view(torch.float16).float()
