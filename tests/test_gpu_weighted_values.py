@@ -189,6 +189,34 @@ def test_attend_values(B, dtype, n, layer, batch, S, QH, spread):
         assert torch.equal(out3, out)
 
 
+def test_attend_every_group_size_of_query_heads(B):
+    """1 to 8 query heads per kv head in the decode kernel's epilogue (the head slots of its small matrix product)."""
+    H, batch, S = 8, 2, 512
+    cfg = synth.Config("gq", layers=2, kv_heads=H, head_dim=128, tokens=batch * S, dtype="bf16", n_codewords=16)
+    Ks, Vs, lo_l, lg_l = P.build_stack(cfg)
+    g = P.run_gpu_layers(B, cfg, lg_l, Ks, Vs)[1]
+    lg = lg_l[1]
+    Vh = U.np64(g["Vhat"]).reshape(batch, S, H, 128)
+    for rep in range(1, 9):
+        QH = H * rep
+        print(f"case attend rep={rep}", flush=True)
+        gen = torch.Generator().manual_seed(300 + rep)
+        s = (torch.randn(batch, QH, S, generator=gen) * 5.0).float().cuda()
+        out = torch.full((batch, QH, 128), float("nan"), dtype=torch.float32, device="cuda")
+        out_w = torch.full_like(out, float("nan"))
+        ws = lg.alloc_weighted_workspace(batch, S, QH)
+        B.aquakv_decode_values_attend(lg, batch, S, QH, g["v_codes"], g["v_scales"], g["Vp"], g["Khat"], s, None, out, None, ws)
+        w = torch.softmax(s, dim=-1)
+        B.aquakv_decode_values_weighted(lg, batch, S, QH, g["v_codes"], g["v_scales"], g["Vp"], g["Khat"], w, None, out_w, ws)
+        sync()
+        p = O.softmax_rows(U.np64(s))
+        own = np.stack([np.einsum("bt,btd->bd", p[:, qh], Vh[:, :, qh // rep]) for qh in range(QH)], 1)
+        mag = np.stack([np.einsum("bt,btd->bd", p[:, qh], np.abs(Vh[:, :, qh // rep])) for qh in range(QH)], 1)
+        for got in (out, out_w):
+            err = np.abs(U.np64(got) - own)
+            assert np.all(err <= 3e-5 * mag), (rep, float(np.max(err / mag)))
+
+
 @pytest.mark.parametrize("bits,rht_group", [(2, None), (4, None), (None, 1024)])
 def test_weighted_values_other_quantizers(B, bits, rht_group):
     print(f"case weighted rtn_bits={bits} rht_group={rht_group}", flush=True)
