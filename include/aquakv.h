@@ -296,7 +296,12 @@ int aquakv_decode_attn_scores_rope(const aquakv_layer* layer, int32_t batch, int
  *   4096); q [batch, q_heads, 128] (dtype).  accumulate = 0 writes out = softmax(score_scale * q.K^T) V and
  *   row_stats = (maximum, sum of exp(score - maximum)); accumulate != 0 merges that with the result (out, row_stats)
  *   already there -- from aquakv_decode_values_attend or an earlier aquakv_attend_raw call on the same queries --
- *   into the attention over the union of the token sets.  tokens = 0 with accumulate != 0 is a no-op.
+ *   into the attention over the union of the token sets.  tokens = 0 with accumulate != 0 is a no-op;
+ *   more than 4096 tokens per call is AQUAKV_EUNSUPPORTED (call again with accumulate != 0 for the rest).
+ *
+ * All buffers are the caller's and stay so; outputs (Vhat, out, row_stats, probs other than in place) may not
+ * alias inputs or the workspace.  Calls on one stream run in order; a call reads `scores` / `weights` while it
+ * runs, so they must not be overwritten by work on another stream before it has finished.
  */
 int aquakv_softmax(int64_t rows, int64_t n, const float* scores, float* probs, void* stream);
 int aquakv_attend_raw(int32_t dtype, int32_t batch, int32_t tokens, int32_t kv_heads, int32_t q_heads,
