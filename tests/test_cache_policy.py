@@ -79,6 +79,33 @@ def test_cache_oracle_before_the_first_flush_everything_is_exact():
         assert np.array_equal(K, kv[l][0]) and np.array_equal(V, kv[l][1])
 
 
+def test_cache_oracle_attention_is_torch_attention_over_its_own_sweep_and_exact_before_a_flush():
+    """CacheOracle.attend pinned: torch's scaled_dot_product_attention over [sinks | recovered | buffer]; before
+    the first flush nothing is compressed, so it is the attention over the raw tokens."""
+    L, H, g, QH = 3, 2, 128, 6
+    layers = small_stack(L, H, g)
+    kv = token_stream(L, 50, H, g, 8)
+    qs = [O.round_fp32(rng(70 + l).standard_normal((QH, g))) for l in range(L)]
+    scale = 0.1
+
+    def torch_attention(q, K, V):
+        Kt, Vt = (torch.from_numpy(a).permute(1, 0, 2).repeat_interleave(QH // H, dim=0)[None] for a in (K, V))
+        o = torch.nn.functional.scaled_dot_product_attention(torch.from_numpy(q)[None, :, None, :], Kt, Vt, scale=scale)
+        return o[0, :, 0, :].numpy()
+
+    cache = CacheOracle(layers, sink_tokens=4, buffer_tokens=16)
+    cache.append([(K[:12], V[:12]) for K, V in kv])                       # 4 sinks + 8 buffered: nothing compressed
+    got = cache.attend(qs, scale)
+    for l in range(L):
+        assert np.allclose(got[l], torch_attention(qs[l], kv[l][0][:12], kv[l][1][:12]), rtol=1e-12, atol=1e-13)
+    cache.append([(K[12:], V[12:]) for K, V in kv])                       # 4 + 32 compressed + 14 buffered
+    assert (cache.n_sink, cache.n_compressed, cache.n_buffered) == (4, 32, 14)
+    got = cache.attend(qs, scale)
+    for l, K, V in cache.sweep():
+        assert np.allclose(got[l], torch_attention(qs[l], K, V), rtol=1e-12, atol=1e-13)
+        assert not np.allclose(got[l], torch_attention(qs[l], kv[l][0], kv[l][1]), rtol=1e-3)   # compression is visible
+
+
 def test_first_layer_strategies_reproduce_the_papers_bit_counts():
     """Table 1, "1st Layer Keys & Values" (28 layers, backbone groups of 1024): keeping the first layer in 16 bits,
     or quantizing it with the 4- / 3- / 2-bit grid, is printed as 2.59 / 2.16 / 2.13 / 2.09 average bits.  The
