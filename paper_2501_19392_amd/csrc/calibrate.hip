@@ -181,7 +181,7 @@ __global__ __launch_bounds__(kFitThreads) void ridge_kernel(double* __restrict__
   part[threadIdx.x] = s;
   __syncthreads();
   for (int w = kFitThreads / 2; w > 0; w >>= 1) {
-    if (threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
+    if ((int)threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
     __syncthreads();
   }
   const double lam = rate * part[0] / d;

@@ -1,7 +1,9 @@
-// Value side of attention over the decoded cache (Alg. "Inference" of the AQUA-KV paper: the block call attends over
-// the recovered keys and values; its output is the weighted sum of the values): soft-max of the score rows, the weighted sum over values
-// that already sit in memory, and the reduction of the per-chunk sums that both this kernel and the fused
-// decode kernel leave behind.  All sums run in a fixed order, so a call gives the same bits every time.
+// Value side of attention over the decoded cache (Alg. "Inference" of the AQUA-KV paper: the block call attends
+// over the recovered keys and values; its output is the weighted sum of the values): soft-max of score rows, the
+// weighted sum over values that already sit in memory (plain weights, or raw scores with the soft-max taken per
+// chunk), the merge of the per-chunk results that both that kernel and the fused decode kernel leave behind, and the
+// attention over tokens held in the storage dtype (sinks, recent buffer) with its merge into a running result.
+// All sums run in a fixed order, so a call gives the same bits every time.
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -221,12 +223,12 @@ __global__ __launch_bounds__(kThreads) void combine_weighted_kernel(const float*
 // denominator.  Same thread layout as above; the three reductions over the chunks go through LDS in a fixed order.
 __global__ __launch_bounds__(kThreads) void combine_softmax_kernel(const float* __restrict__ part, const float* __restrict__ pstats,
                                                                    float* __restrict__ out, float* __restrict__ row_stats,
-                                                                   int chunks_per_seq, int q_heads, int64_t total) {
+                                                                   int chunks_per_seq, int q_heads) {
   __shared__ float red[8][32];
   __shared__ float den[8];
   const int row = q_heads * kGroup;
   const int k = threadIdx.x >> 5, j32 = threadIdx.x & 31;
-  const int64_t i = (int64_t)blockIdx.x * 32 + j32;                     // total is a multiple of 128: never beyond the end
+  const int64_t i = (int64_t)blockIdx.x * 32 + j32;                     // the grid covers batch * q_heads * 128 outputs exactly
   const int64_t b = i / row, j = i % row;
   const int qh = (int)(j / kGroup);                                     // the same for the 32 outputs of a workgroup
   const float* src = part + b * chunks_per_seq * row + j;
@@ -360,7 +362,7 @@ hipError_t launch_combine_weighted(const float* part, const float* pstats, float
   const int row = q_heads * kGroup;
   const int64_t total = (int64_t)batch * row;
   if (pstats != nullptr) {
-    combine_softmax_kernel<<<(unsigned)(total / 32), kThreads, 0, stream>>>(part, pstats, out, row_stats, chunks, q_heads, total);
+    combine_softmax_kernel<<<(unsigned)(total / 32), kThreads, 0, stream>>>(part, pstats, out, row_stats, chunks, q_heads);
     return hipGetLastError();
   }
   combine_weighted_kernel<<<(unsigned)((total + 31) / 32), kThreads, 0, stream>>>(part, out, chunks, row, total);
