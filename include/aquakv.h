@@ -293,7 +293,10 @@ int aquakv_decode_attn_scores_rope(const aquakv_layer* layer, int32_t batch, int
  *
  * aquakv_attend_raw -- attention of the same queries over tokens that are held in 16 bits (Sect. 3.3: the attention
  *   sinks and the recent-token buffer are not quantized): K, V device, dtype, [batch*tokens, kv_heads, 128] (tokens <=
- *   4096); q [batch, q_heads, 128] (dtype).  accumulate = 0 writes out = softmax(score_scale * q.K^T) V and
+ *   4096); q [batch, q_heads, 128] (dtype).  rope_cos / rope_sin (both NULL, or device fp32 [tokens, 64], the angles
+ *   of this call's tokens, 16-byte aligned): the keys are held from before the rotary embedding and token t of every
+ *   sequence is rotated by row t of the tables before the dot product, as in aquakv_decode_attn_scores_rope (a caller
+ *   whose tokens start at position p passes the tables offset by p rows).  accumulate = 0 writes out = softmax(score_scale * q.K^T) V and
  *   row_stats = (maximum, sum of exp(score - maximum)); accumulate != 0 merges that with the result (out, row_stats)
  *   already there -- from aquakv_decode_values_attend or an earlier aquakv_attend_raw call on the same queries --
  *   into the attention over the union of the token sets.  tokens = 0 with accumulate != 0 is a no-op;
@@ -305,7 +308,8 @@ int aquakv_decode_attn_scores_rope(const aquakv_layer* layer, int32_t batch, int
  */
 int aquakv_softmax(int64_t rows, int64_t n, const float* scores, float* probs, void* stream);
 int aquakv_attend_raw(int32_t dtype, int32_t batch, int32_t tokens, int32_t kv_heads, int32_t q_heads,
-                      const void* K, const void* V, const void* q, float score_scale,
+                      const void* K, const void* V, const void* q,
+                      const float* rope_cos, const float* rope_sin, float score_scale,
                       float* out, float* row_stats, int32_t accumulate, void* stream);
 size_t aquakv_weighted_workspace_bytes(const aquakv_layer* layer, int32_t batch, int32_t seq_len, int32_t q_heads);
 int aquakv_decode_values_weighted(const aquakv_layer* layer, int32_t batch, int32_t seq_len, int32_t q_heads,

@@ -556,14 +556,18 @@ def attn_values(layer: Layer, batch: int, seq_len: int, weights, v_codes, v_scal
     return out, Vhat.reshape(T, layer.kv_heads, layer.head_dim)
 
 
-def attention(q, K, V, score_scale=1.0):
+def attention(q, K, V, score_scale=1.0, rope=None):
     """Attention of one query per sequence and query head over given keys and values (the block call of
     Alg. "Inference" for one new token): scores s[b, qh, t] = score_scale * q[b, qh] . K[b, t, kvh(qh)],
     out[b, qh] = sum_t softmax_t(s)[t] * V[b, t, kvh(qh)], query head qh reading kv head qh // (q_heads // kv_heads).
     q: [batch, q_heads, g]; K, V: [batch, tokens, kv_heads, g].
+    rope = (cos, sin), each [tokens, g/2]: the keys are held from before the rotary embedding (Sect. 3.3) and key t is
+    rotated by row t of the tables first (apply_rope); q is taken as already rotated.
     Returns (out, M, L) with M the row maximum of s and L = sum_t exp(s - M).
     """
     q, K, V = (np.asarray(a, dtype=np.float64) for a in (q, K, V))
+    if rope is not None:
+        K = apply_rope(K, rope[0], rope[1])
     batch, q_heads, _ = q.shape
     rep = q_heads // K.shape[2]
     out = np.empty_like(q)

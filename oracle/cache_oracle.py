@@ -106,13 +106,16 @@ class CacheOracle:
                 parts_k.append(self.buf_k[l]); parts_v.append(self.buf_v[l])
             yield l, np.concatenate(parts_k, axis=0), np.concatenate(parts_v, axis=0)
 
-    def attend(self, queries, score_scale: float):
+    def attend(self, queries, score_scale: float, rope=None):
         """Attention of one new token's queries over everything cached (Alg. "Inference", the block call with
         K = [recovered past], one token): queries[l] is [q_heads, head_dim]; returns one [q_heads, head_dim] per layer.
-        The soft-max runs over sinks, recovered compressed tokens and buffered tokens alike."""
+        The soft-max runs over sinks, recovered compressed tokens and buffered tokens alike.  rope = (cos, sin), each
+        [>= n_tokens, head_dim/2]: the cache holds keys from before the rotary embedding; token t is rotated by row t."""
         out = []
+        n = self.n_tokens
         for l, K, V in self.sweep():
-            o, _, _ = O.attention(np.asarray(queries[l], dtype=np.float64)[None], K[None], V[None], score_scale)
+            o, _, _ = O.attention(np.asarray(queries[l], dtype=np.float64)[None], K[None], V[None], score_scale,
+                                  None if rope is None else (np.asarray(rope[0])[:n], np.asarray(rope[1])[:n]))
             out.append(o[0])
         return out
 

@@ -86,7 +86,7 @@ _lib.aquakv_weighted_workspace_bytes.restype = ctypes.c_size_t
 _lib.aquakv_weighted_workspace_bytes.argtypes = [_LP, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
 _lib.aquakv_decode_values_weighted.argtypes = [_LP, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32] + [_P] * 8 + [ctypes.c_size_t, _P]
 _lib.aquakv_decode_values_attend.argtypes = [_LP, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32] + [_P] * 9 + [ctypes.c_size_t, _P]
-_lib.aquakv_attend_raw.argtypes = [ctypes.c_int32] * 5 + [_P, _P, _P, ctypes.c_float, _P, _P, ctypes.c_int32, _P]
+_lib.aquakv_attend_raw.argtypes = [ctypes.c_int32] * 5 + [_P, _P, _P, _P, _P, ctypes.c_float, _P, _P, ctypes.c_int32, _P]
 for _n in ("aquakv_attend_raw", "aquakv_softmax", "aquakv_decode_values_weighted", "aquakv_decode_values_attend", "aquakv_predict", "aquakv_quantize", "aquakv_dequantize", "aquakv_encode_layer", "aquakv_decode_layer",
            "aquakv_decode_attn_scores", "aquakv_decode_attn_scores_rope", "aquakv_encode_keys", "aquakv_encode_values",
            "aquakv_decode_values", "aquakv_fit_predictor"):
@@ -334,11 +334,11 @@ def aquakv_decode_values_attend(layer, batch: int, seq_len: int, q_heads: int, v
 
 
 def aquakv_attend_raw(dtype, batch: int, tokens: int, kv_heads: int, q_heads: int, K, V, q, score_scale: float, out,
-                      row_stats, accumulate: bool, stream=None) -> None:
+                      row_stats, accumulate: bool, stream=None, rope_cos=None, rope_sin=None) -> None:
     code = dtype if isinstance(dtype, int) else _dtype_code(dtype)
-    _check(_lib.aquakv_attend_raw(code, batch, tokens, kv_heads, q_heads, _ptr(K), _ptr(V), _ptr(q),
-                                  ctypes.c_float(score_scale), _ptr(out), _ptr(row_stats), int(bool(accumulate)),
-                                  _stream(stream)))
+    _check(_lib.aquakv_attend_raw(code, batch, tokens, kv_heads, q_heads, _ptr(K), _ptr(V), _ptr(q), _ptr(rope_cos),
+                                  _ptr(rope_sin), ctypes.c_float(score_scale), _ptr(out), _ptr(row_stats),
+                                  int(bool(accumulate)), _stream(stream)))
 
 
 def aquakv_fit_workspace_bytes(d_in: int, d_out: int) -> int:

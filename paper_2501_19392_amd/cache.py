@@ -122,10 +122,13 @@ class AquaKVCache:
                 K[s + c:s + c + b].copy_(self.buf[l][0][:b]); V[s + c:s + c + b].copy_(self.buf[l][1][:b])
             yield l, K[:s + c + b], V[:s + c + b]
 
-    def attend(self, queries: Sequence[torch.Tensor], score_scale: float) -> List[torch.Tensor]:
+    def attend(self, queries: Sequence[torch.Tensor], score_scale: float, rope=None) -> List[torch.Tensor]:
         """queries[l]: [q_heads, head_dim] in the storage dtype, the new token's queries at layer l.  Returns one
         fp32 [q_heads, head_dim] per layer: softmax(score_scale * q K^T) V over sinks, compressed past and buffer.
-        One sweep over the layers; the recovered tensors of layer l feed layer l + 1 as in `sweep`."""
+        One sweep over the layers; the recovered tensors of layer l feed layer l + 1 as in `sweep`.
+        rope = (cos, sin), device fp32 [>= n_tokens, head_dim / 2]: the cache holds keys from before the rotary
+        embedding (Sect. 3.3, the paper's default); the key of token t is rotated by row t on the fly, the queries
+        are taken as already rotated, and what is recovered for the next layer stays unrotated."""
         s, c, b = self.n_sink, self.n_compressed, self.n_buffered
         if s + c + b == 0:
             raise ValueError("nothing cached")
@@ -143,6 +146,8 @@ class AquaKVCache:
                 ws=max((l.alloc_weighted_workspace(1, cap, QH, self._device) for l in coded), key=lambda t: t.numel()))
         A = self._attend
         step = 4096                                              # tokens per aquakv_attend_raw call
+        cos, sin = rope if rope is not None else (None, None)
+        rows = lambda t, a, n: None if t is None else t[a:a + n]  # the angles of tokens a ... a + n - 1
         Kp = Vp = None
         for l, lay in enumerate(self.layers):
             q = queries[l].reshape(1, QH, g)
@@ -152,23 +157,29 @@ class AquaKVCache:
                 Kp, Vp = self.raw[l][0][:c], self.raw[l][1][:c]
                 for r0 in range(0, c, step):
                     n = min(step, c - r0)
-                    B.aquakv_attend_raw(dt, 1, n, H, QH, Kp[r0:r0 + n], Vp[r0:r0 + n], q, score_scale, out, stats, have)
+                    B.aquakv_attend_raw(dt, 1, n, H, QH, Kp[r0:r0 + n], Vp[r0:r0 + n], q, score_scale, out, stats, have,
+                                        rope_cos=rows(cos, s + r0, n), rope_sin=rows(sin, s + r0, n))
                     have = True
             elif c:
                 (kc, ks), (vc, vs) = self.codes[l]
                 K, V = self._view[l & 1]
                 scores = A["scores"][:QH * c].view(1, QH, c)
-                B.aquakv_decode_attn_scores(lay, 1, c, QH, kc[:c], ks[:c], Kp, q, score_scale, scores, K[:c], self._view_ws)
+                if rope is None:
+                    B.aquakv_decode_attn_scores(lay, 1, c, QH, kc[:c], ks[:c], Kp, q, score_scale, scores, K[:c], self._view_ws)
+                else:
+                    B.aquakv_decode_attn_scores_rope(lay, 1, c, QH, kc[:c], ks[:c], Kp, q, rows(cos, s, c), rows(sin, s, c),
+                                                     score_scale, scores, K[:c], self._view_ws)
                 B.aquakv_decode_values_attend(lay, 1, c, QH, vc[:c], vs[:c], Vp, K[:c], scores, V[:c], out, stats, A["ws"])
                 Kp, Vp = K[:c], V[:c]
                 have = True
             if s:
-                B.aquakv_attend_raw(dt, 1, s, H, QH, self.sink[l][0][:s], self.sink[l][1][:s], q, score_scale, out, stats, have)
+                B.aquakv_attend_raw(dt, 1, s, H, QH, self.sink[l][0][:s], self.sink[l][1][:s], q, score_scale, out, stats, have,
+                                    rope_cos=rows(cos, 0, s), rope_sin=rows(sin, 0, s))
                 have = True
             for r0 in range(0, b, step):
                 n = min(step, b - r0)
                 B.aquakv_attend_raw(dt, 1, n, H, QH, self.buf[l][0][r0:r0 + n], self.buf[l][1][r0:r0 + n], q, score_scale,
-                                    out, stats, have)
+                                    out, stats, have, rope_cos=rows(cos, s + c + r0, n), rope_sin=rows(sin, s + c + r0, n))
                 have = True
         return [o[0] for o in A["out"]]
 

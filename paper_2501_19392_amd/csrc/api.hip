@@ -587,8 +587,8 @@ int aquakv_decode_values_attend(const aquakv_layer* L, int32_t batch, int32_t se
 }
 
 int aquakv_attend_raw(int32_t dtype, int32_t batch, int32_t tokens, int32_t kv_heads, int32_t q_heads, const void* K,
-                      const void* V, const void* q, float score_scale, float* out, float* row_stats, int32_t accumulate,
-                      void* stream) {
+                      const void* V, const void* q, const float* rope_cos, const float* rope_sin, float score_scale,
+                      float* out, float* row_stats, int32_t accumulate, void* stream) {
   if (dtype != AQUAKV_BF16 && dtype != AQUAKV_FP32) return fail(AQUAKV_EINVAL, "dtype=%d", dtype);
   if (batch < 0 || tokens < 0) return fail(AQUAKV_EINVAL, "batch=%d tokens=%d", batch, tokens);
   if (tokens > aquakv::kAttendRawMaxTokens)
@@ -600,13 +600,16 @@ int aquakv_attend_raw(int32_t dtype, int32_t batch, int32_t tokens, int32_t kv_h
   CHECK(check_ptr(q, "q", true));
   CHECK(check_ptr(out, "out", true));
   CHECK(check_ptr(row_stats, "row_stats", true));
+  if ((rope_cos == nullptr) != (rope_sin == nullptr)) return fail(AQUAKV_ENULL, "rope_cos and rope_sin go together");
+  CHECK(check_ptr(rope_cos, "rope_cos", false));
+  CHECK(check_ptr(rope_sin, "rope_sin", false));
   if (batch == 0) return AQUAKV_OK;
   if (tokens == 0) {
     if (!accumulate) return fail(AQUAKV_EINVAL, "tokens=0 leaves nothing to write without a result to merge into");
     return AQUAKV_OK;
   }
-  HIP_TRY(aquakv::launch_attend_raw(dtype, K, V, q, score_scale, out, row_stats, batch, tokens, kv_heads, q_heads,
-                                    accumulate != 0, static_cast<hipStream_t>(stream)));
+  HIP_TRY(aquakv::launch_attend_raw(dtype, K, V, q, rope_cos, rope_sin, score_scale, out, row_stats, batch, tokens, kv_heads,
+                                    q_heads, accumulate != 0, static_cast<hipStream_t>(stream)));
   return AQUAKV_OK;
 }
 

@@ -72,8 +72,10 @@ hipError_t launch_combine_weighted(const float* part, const float* pstats, float
 // ([batch * tokens, H, 128]), written to or merged into (accumulate != 0) out [batch, q_heads, 128] and the row
 // statistics [batch, q_heads, 2] (maximum, sum of exp(score - maximum)) that launch_combine_weighted hands out.
 constexpr int kAttendRawMaxTokens = 4096;
-hipError_t launch_attend_raw(int dtype, const void* K, const void* V, const void* q, float scale, float* out, float* stats,
-                             int batch, int tokens, int H, int q_heads, int accumulate, hipStream_t stream);
+// rope_cos / rope_sin (nullable, fp32 [tokens, 64]): rotate key t by its position before the dot product.
+hipError_t launch_attend_raw(int dtype, const void* K, const void* V, const void* q, const float* rope_cos,
+                             const float* rope_sin, float scale, float* out, float* stats, int batch, int tokens, int H,
+                             int q_heads, int accumulate, hipStream_t stream);
 // probs[r, :] = softmax(scores[r, :]) for `rows` rows of length n (in place allowed)
 hipError_t launch_softmax_rows(const float* scores, float* probs, int64_t rows, int64_t n, hipStream_t stream);
 

@@ -264,7 +264,10 @@ __global__ __launch_bounds__(kThreads) void combine_softmax_kernel(const float* 
 
 // Attention of one query per sequence and query head over `tokens` keys / values held in the storage dtype (the
 // attention sinks and the recent-token buffer of Sect. 3.3, which are not quantized), merged into a running result.
-// One workgroup per (sequence, query head): scores s_t = scale * q . k_t (a wave per token, 2 dims per lane), their
+// rope_cos / rope_sin (nullable, fp32 [tokens, 64]: the angles of this call's tokens): the cache holds keys from
+// before the rotary embedding (Sect. 3.3), so key t is rotated by its position first, coordinate d paired with d + 64.
+// One workgroup per (sequence, query head): scores s_t = scale * q . k_t (a wave per token, lane l holds the
+// coordinate pair (l, l + 64)), their
 // maximum m and l = sum exp(s_t - m) through the block reductions, o = sum exp(s_t - m) v_t (thread = dim and token
 // parity).  accumulate == 0: out = o / l, stats = (m, l).  Otherwise (out, stats) hold a result over other tokens,
 // out normalised by its own L: M' = max(M, m), L' = L e^(M - M') + l e^(m - M'),
@@ -272,7 +275,8 @@ __global__ __launch_bounds__(kThreads) void combine_softmax_kernel(const float* 
 constexpr int kRawMaxTokens = kAttendRawMaxTokens;
 template <typename T>
 __global__ __launch_bounds__(kThreads) void attend_raw_kernel(const T* __restrict__ K, const T* __restrict__ V,
-                                                              const T* __restrict__ q, float scale, float* out,
+                                                              const T* __restrict__ q, const float* __restrict__ rope_cos,
+                                                              const float* __restrict__ rope_sin, float scale, float* out,
                                                               float* stats, int tokens, int H, int q_heads, int accumulate) {
   __shared__ float sc[kRawMaxTokens];
   __shared__ float buf[kThreads];
@@ -281,12 +285,18 @@ __global__ __launch_bounds__(kThreads) void attend_raw_kernel(const T* __restric
   const int head = qh / (q_heads / H);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const T* qp = q + ((int64_t)b * q_heads + qh) * kGroup;
-  const float q0 = static_cast<float>(qp[2 * lane]), q1 = static_cast<float>(qp[2 * lane + 1]);
+  const float q0 = static_cast<float>(qp[lane]), q1 = static_cast<float>(qp[lane + 64]);
   const T* kb = K + ((int64_t)b * tokens * H + head) * kGroup;
   const T* vb = V + ((int64_t)b * tokens * H + head) * kGroup;
   for (int t = wave; t < tokens; t += kThreads / 64) {
     const T* kp = kb + (int64_t)t * H * kGroup;
-    float d = __fmaf_rn(q1, static_cast<float>(kp[2 * lane + 1]), q0 * static_cast<float>(kp[2 * lane]));
+    float k0 = static_cast<float>(kp[lane]), k1 = static_cast<float>(kp[lane + 64]);
+    if (rope_cos != nullptr) {
+      const float cs = rope_cos[t * 64 + lane], sn = rope_sin[t * 64 + lane];
+      const float r0 = __fmaf_rn(k0, cs, -(k1 * sn)), r1 = __fmaf_rn(k1, cs, k0 * sn);
+      k0 = r0; k1 = r1;
+    }
+    float d = __fmaf_rn(q1, k1, q0 * k0);
 #pragma unroll
     for (int m = 1; m < 64; m <<= 1) d += __shfl_xor(d, m);
     if (lane == 0) sc[t] = d * scale;
@@ -369,18 +379,19 @@ hipError_t launch_combine_weighted(const float* part, const float* pstats, float
   return hipGetLastError();
 }
 
-hipError_t launch_attend_raw(int dtype, const void* K, const void* V, const void* q, float scale, float* out, float* stats,
-                             int batch, int tokens, int H, int q_heads, int accumulate, hipStream_t stream) {
+hipError_t launch_attend_raw(int dtype, const void* K, const void* V, const void* q, const float* rope_cos,
+                             const float* rope_sin, float scale, float* out, float* stats, int batch, int tokens, int H,
+                             int q_heads, int accumulate, hipStream_t stream) {
   if (batch == 0 || tokens == 0) return hipSuccess;
   const unsigned grid = (unsigned)batch * q_heads;
   if (dtype == kBF16)
     attend_raw_kernel<bf16_t><<<grid, kThreads, 0, stream>>>(static_cast<const bf16_t*>(K), static_cast<const bf16_t*>(V),
-                                                             static_cast<const bf16_t*>(q), scale, out, stats, tokens, H,
-                                                             q_heads, accumulate);
+                                                             static_cast<const bf16_t*>(q), rope_cos, rope_sin, scale, out, stats,
+                                                             tokens, H, q_heads, accumulate);
   else
     attend_raw_kernel<float><<<grid, kThreads, 0, stream>>>(static_cast<const float*>(K), static_cast<const float*>(V),
-                                                            static_cast<const float*>(q), scale, out, stats, tokens, H,
-                                                            q_heads, accumulate);
+                                                            static_cast<const float*>(q), rope_cos, rope_sin, scale, out, stats,
+                                                            tokens, H, q_heads, accumulate);
   return hipGetLastError();
 }
 

@@ -258,16 +258,17 @@ def test_gpu_cache_manager_with_the_papers_first_layer_strategies(first):
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("first,rht_group,r,pieces", [("2bit", None, 128, (5, 251, 256, 30)), ("4bit", 1024, 128, (3, 130, 127, 40)),
-                                                      ("bf16", 1024, 32, (4, 64, 1)), ("2bit", None, 64, (2,))])
-def test_gpu_cache_attention_of_a_new_token_over_everything_cached(first, rht_group, r, pieces):
+@pytest.mark.parametrize("first,rht_group,r,pieces,with_rope", [
+    ("2bit", None, 128, (5, 251, 256, 30), False), ("4bit", 1024, 128, (3, 130, 127, 40), True),
+    ("bf16", 1024, 32, (4, 64, 1), True), ("2bit", None, 64, (2,), False), ("2bit", None, 128, (5, 251, 256, 30), True)])
+def test_gpu_cache_attention_of_a_new_token_over_everything_cached(first, rht_group, r, pieces, with_rope):
     """AquaKVCache.attend against the policy oracle's plain soft-max attention over [sinks | recovered past | buffer]:
     the compressed range goes through the decode kernels (sums inside the kernel when its length is a multiple of
     256), sinks and buffer through aquakv_attend_raw, merged by their row statistics."""
     from paper_2501_19392_amd.cache import AquaKVCache
     from tests import parity_utils as U
     from tests.test_gpu_parity import sync
-    print(f"case cache attend first={first} rht_group={rht_group} r={r} pieces={pieces}", flush=True)
+    print(f"case cache attend first={first} rht_group={rht_group} r={r} pieces={pieces} rope={with_rope}", flush=True)
     L, H, QH, sink = 3, 8, 24, 4
     T = sum(pieces)
     cfg = synth.Config("cache", layers=L, kv_heads=H, head_dim=128, tokens=T, dtype="bf16")
@@ -293,22 +294,24 @@ def test_gpu_cache_attention_of_a_new_token_over_everything_cached(first, rht_gr
     assert (gpu.n_sink, gpu.n_compressed, gpu.n_buffered) == (cpu.n_sink, cpu.n_compressed, cpu.n_buffered)
     scale = 128 ** -0.5
     qs = [synth.random_queries(1, QH, 128, seed=900 + l, dtype="bf16", device="cuda")[0] * 3.0 for l in range(L)]
+    rope_cpu = O.rope_tables(T, 128) if with_rope else None          # keys cached before the rotary embedding
+    rope_gpu = tuple(torch.from_numpy(t).float().cuda() for t in rope_cpu) if with_rope else None
     for rep in range(2):                                     # a second call reuses the buffers
-        got = [o.clone() for o in gpu.attend(qs, scale)]
+        got = [o.clone() for o in gpu.attend(qs, scale, rope_gpu)]
         sync()
         # (a) against the plain soft-max attention over the tensors the manager itself recovers (its sweep is checked
         # against the policy oracle by the tests above): what is left is the arithmetic of the attention calls
         forced = {}
         for l, K, V in gpu.sweep():
             sync()
-            forced[l], _, _ = O.attention(U.np64(qs[l])[None], U.np64(K)[None], U.np64(V)[None], scale)
+            forced[l], _, _ = O.attention(U.np64(qs[l])[None], U.np64(K)[None], U.np64(V)[None], scale, rope_cpu)
         # (b) free-running against the policy oracle, whose own encoder may take the other side of a tie: a changed
         # code moves a key by a fraction of its size and a peaked soft-max amplifies that, so this comparison uses
         # queries scaled down to flat attention rows
         flat = [q * 0.125 for q in qs]
-        got_flat = [o.clone() for o in gpu.attend(flat, scale)]
+        got_flat = [o.clone() for o in gpu.attend(flat, scale, rope_gpu)]
         sync()
-        want = cpu.attend([U.np64(q) for q in flat], scale)
+        want = cpu.attend([U.np64(q) for q in flat], scale, rope_cpu)
         for l in range(L):
             rms = float(np.sqrt(np.mean(U.np64(Vs[l]) ** 2)))
             err = float(np.abs(U.np64(got[l]) - forced[l][0]).max())
@@ -350,6 +353,15 @@ def test_gpu_attend_raw_and_its_merge(dtype):
         if Kx is Ka:
             B.aquakv_attend_raw(sd, batch, n2, H, QH, Kb, Vb, q, scale, out, stats, True)     # merge the second set
             sync()
+    # keys held from before the rotary embedding: both token sets again, each with the angles of its own positions
+    cos, sin = O.rope_tables(n1 + n2, 128)
+    cg, sg = torch.from_numpy(cos).float().cuda(), torch.from_numpy(sin).float().cuda()
+    B.aquakv_attend_raw(sd, batch, n1, H, QH, Ka, Va, q, scale, out, stats, False, rope_cos=cg[:n1], rope_sin=sg[:n1])
+    B.aquakv_attend_raw(sd, batch, n2, H, QH, Kb, Vb, q, scale, out, stats, True, rope_cos=cg[n1:], rope_sin=sg[n1:])
+    sync()
+    want, M, Lw = O.attention(U.np64(q), U.np64(K), U.np64(V), scale, (cos, sin))
+    assert np.abs(U.np64(out) - want).max() <= tol * np.abs(U.np64(V)).max()
+    assert np.abs(U.np64(stats[..., 0]) - M).max() <= 1e-5 * np.abs(M).max()
     B.aquakv_attend_raw(sd, batch, 0, H, QH, None, None, q, scale, out, stats, True)          # nothing to merge: no-op
     with pytest.raises(B.AquaKVError):
         B.aquakv_attend_raw(sd, batch, 4097, H, QH, K, V, q, scale, out, stats, False)

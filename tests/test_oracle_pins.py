@@ -410,6 +410,16 @@ def test_attention_over_given_tokens_is_torch_attention_and_its_statistics_are_t
     wa, wb = La * np.exp(Ma - Mm), Lb * np.exp(Mb - Mm)
     merged = (oa * wa[..., None] + ob * wb[..., None]) / (wa + wb)[..., None]
     assert np.allclose(merged, out, rtol=1e-12, atol=1e-13)
+    # keys held from before the rotary embedding: rotating them by their positions first is the same attention, and
+    # with the query rotated by its own position p the scores see only p - t (so a common shift changes nothing)
+    cos, sin = O.rope_tables(S + 7, g)
+    o_r, _, _ = O.attention(q, K, V, scale, (cos[:S], sin[:S]))
+    o_pre, _, _ = O.attention(q, O.apply_rope(K, cos[:S], sin[:S]), V, scale)
+    assert np.allclose(o_r, o_pre, rtol=0, atol=0)
+    rot_q = lambda p: O.apply_rope(q[:, None, :, :], cos[p:p + 1], sin[p:p + 1])[:, 0]
+    o_a, _, _ = O.attention(rot_q(S), K, V, scale, (cos[:S], sin[:S]))
+    o_b, _, _ = O.attention(rot_q(S + 5), K, V, scale, (cos[5:S + 5], sin[5:S + 5]))
+    assert np.allclose(o_a, o_b, rtol=1e-5, atol=1e-6)            # the tables are rounded to fp32
 
 
 # ------------------------------------------------------------------ rotary embedding of the decoded keys
