@@ -125,7 +125,8 @@ struct Plan {
   size_t eb;          // bytes per element of the storage dtype
   size_t code_row;    // bytes of codes per token row
   int64_t chunk;      // rows per pass
-  bool fused;         // bf16: predictor fused with the quantizer kernels
+  bool fused;         // bf16, groups of one head: predictor fused with the quantizer kernels
+  bool fused_dec;     // bf16: predictor fused with the inverse quantizer (also for groups across the 8 heads)
   size_t p_bytes;     // fp32 predictions of one chunk
   size_t khat_bytes;  // temporary Khat of one chunk
 };
@@ -136,6 +137,7 @@ Plan make_plan(const aquakv_layer* L, int64_t tokens) {
   pl.eb = elem_bytes(L->dtype);
   pl.code_row = (size_t)L->kv_heads * (L->head_dim / 2) * code_bits(L) / 8;
   pl.fused = L->dtype == AQUAKV_BF16 && !is_wide(L);   // a fused tile is one head wide
+  pl.fused_dec = L->dtype == AQUAKV_BF16;              // decoding needs no statistic of the whole group
   const int64_t cap = pl.fused ? kChunkRowsFused : kChunkRowsSplit;
   pl.chunk = tokens < cap ? tokens : cap;
   pl.p_bytes = pl.fused ? 0 : (size_t)pl.chunk * pl.D * sizeof(float);
@@ -202,12 +204,12 @@ int decode_keys_chunk(const aquakv_layer* L, const Plan& pl, int64_t r0, int64_t
                       const uint16_t* k_scales, const void* Khat_prev, void* Khat, float* Pbuf, hipStream_t stream) {
   const bool has_k = L->d_in_k != 0;
   const size_t row = (size_t)pl.D * pl.eb, srow = scale_row_bytes(L);
-  if (has_k && pl.fused) {
+  if (has_k && pl.fused_dec) {
     HIP_TRY(aquakv::launch_fused_decode(quantizer_id(L), at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k, nullptr, 0,
                                         L->w_k, L->b_k, L->signs_k, L->codebook,
                                         static_cast<const uint8_t*>(at(k_codes, r0, pl.code_row)),
                                         static_cast<const uint16_t*>(at(k_scales, r0, srow)), at(Khat, r0, row), n, pl.D,
-                                        stream));
+                                        is_wide(L), stream));
     return AQUAKV_OK;
   }
   if (has_k)
@@ -226,12 +228,12 @@ int decode_values_chunk(const aquakv_layer* L, const Plan& pl, int64_t r0, int64
   const bool has_v = L->d_in_v != 0;
   const int D = pl.D;
   const size_t row = (size_t)D * pl.eb, srow = scale_row_bytes(L);
-  if (has_v && pl.fused) {
+  if (has_v && pl.fused_dec) {
     HIP_TRY(aquakv::launch_fused_decode(quantizer_id(L), at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb), L->d_in_v - D,
                                         at(Khat, r0, row), D, L->w_v, L->b_v, L->signs_v, L->codebook,
                                         static_cast<const uint8_t*>(at(v_codes, r0, pl.code_row)),
                                         static_cast<const uint16_t*>(at(v_scales, r0, srow)), at(Vhat, r0, row), n, D,
-                                        stream));
+                                        is_wide(L), stream));
     return AQUAKV_OK;
   }
   if (has_v)
@@ -496,7 +498,7 @@ size_t weighted_stat_bytes(int32_t batch, int32_t seq_len, int32_t q_heads) {
   return (bytes + 255) & ~(size_t)255;
 }
 bool weighted_fused(const aquakv_layer* L, const Plan& pl, int32_t seq_len) {
-  return L->d_in_v != 0 && pl.fused && seq_len % aquakv::kWeightedChunk == 0;
+  return L->d_in_v != 0 && pl.fused_dec && seq_len % aquakv::kWeightedChunk == 0;
 }
 }  // namespace
 
@@ -539,8 +541,8 @@ int decode_values_weighted(const aquakv_layer* L, int32_t batch, int32_t seq_len
   const Plan pl = make_plan(L, tokens);
   const bool fused = weighted_fused(L, pl, seq_len);
   if (!fused && Vhat == nullptr)
-    return fail(AQUAKV_ENULL, "Vhat may be NULL only when the sums are taken inside the decode kernel (bf16, rotation "
-                              "groups of one head, a value predictor, seq_len a multiple of %d)",
+    return fail(AQUAKV_ENULL, "Vhat may be NULL only when the sums are taken inside the decode kernel (bf16, "
+                              "a value predictor, seq_len a multiple of %d)",
                 aquakv::kWeightedChunk);
   const size_t part_bytes = weighted_part_bytes(batch, seq_len, q_heads);
   const size_t stat_bytes = weighted_stat_bytes(batch, seq_len, q_heads);
@@ -556,7 +558,7 @@ int decode_values_weighted(const aquakv_layer* L, int32_t batch, int32_t seq_len
     const int D = pl.D;
     HIP_TRY(aquakv::launch_fused_weighted(quantizer_id(L), Vhat_prev, L->d_in_v - D, Khat, D, L->w_v, L->b_v, L->signs_v,
                                           L->codebook, v_codes, v_scales, Vhat, weights, part, pstats, seq_len, q_heads,
-                                          tokens, D, stream));
+                                          tokens, D, is_wide(L), stream));
   } else {
     for (int64_t r0 = 0; r0 < tokens; r0 += pl.chunk) {
       const int64_t n = tokens - r0 < pl.chunk ? tokens - r0 : pl.chunk;
@@ -680,11 +682,11 @@ int decode_attn_scores(const aquakv_layer* L, int32_t batch, int32_t seq_len, in
                                          static_cast<hipStream_t>(stream_)));
     return AQUAKV_OK;
   }
-  if (has_k && pl.fused) {
+  if (has_k && pl.fused_dec) {
     // one fused launch over all rows: prediction, inverse quantizer and dot products
     HIP_TRY(aquakv::launch_fused_scores(quantizer_id(L), Khat_prev, L->d_in_k, L->w_k, L->b_k, L->signs_k, L->codebook,
                                         k_codes, k_scales, q, score_scale, scores, Khat_out, seq_len, q_heads, tokens,
-                                        pl.D, rope_cos, rope_sin, static_cast<hipStream_t>(stream_)));
+                                        pl.D, rope_cos, rope_sin, is_wide(L), static_cast<hipStream_t>(stream_)));
     return AQUAKV_OK;
   }
   if (has_k) {

@@ -207,6 +207,13 @@ template <bool WIDE> struct Rot {
     wht128(v, l & 3);
     if constexpr (WIDE) wht1024_tail(v, l);
   }
+  // The same transform (H_8 (x) H_128 is symmetric) with the stages across the heads first, used for the inverse:
+  // a kernel that holds one head of a token per quad and fetches the other heads' grid points itself can then
+  // reproduce it bit for bit by adding the 8 heads in the same tree, ((0 1)(2 3))((4 5)(6 7)), before its own wht128.
+  static __device__ __forceinline__ void iwht(float (&v)[32], int l) {
+    if constexpr (WIDE) wht1024_tail(v, l);
+    wht128(v, l & 3);
+  }
   // sign pending on the lane's values after wht(): -1 for every cross-lane stage in which the lane was the upper one
   static __device__ __forceinline__ float sign(int l) {
     const int bits = WIDE ? (l & 31) : (l & 3);
@@ -234,7 +241,7 @@ __device__ __forceinline__ void load_sign_bits(const int8_t* signs, int head, in
 // three produce bit-identical keys/values.
 template <bool WIDE = false>
 __device__ __forceinline__ void reconstruct(float (&z)[32], int l, const uint32_t (&sb)[32], const float (&p)[32]) {
-  Rot<WIDE>::wht(z, l);
+  Rot<WIDE>::iwht(z, l);
   const float norm = Rot<WIDE>::sign(l) * Rot<WIDE>::kNorm;
 #pragma unroll
   for (int r = 0; r < 32; ++r) {

@@ -49,7 +49,11 @@ typedef unsigned int u32x2_alias __attribute__((ext_vector_type(2), may_alias));
 typedef unsigned short u16_alias __attribute__((may_alias));
 typedef float f32_alias __attribute__((may_alias));
 
-template <int NCW, int MODE, int WAVES>
+// WIDE (decode, scores, weighted; 8 heads): rotation groups of 1024 = the whole token.  The tile is still one head of
+// 256 tokens, so the inverse rotation's stages across the heads are taken on the grid points of all 8 heads, which
+// the lane fetches itself, added in the tree the stand-alone kernels use (Rot<true>::iwht), before its own 128-point
+// stages; the round-to-nearest backbone has no rotation and only reads its step and zero point per token.
+template <int NCW, int MODE, int WAVES, bool WIDE = false>
 __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
     const bf16_t* __restrict__ x0, int d0, const bf16_t* __restrict__ x1, int d1, const bf16_t* __restrict__ W,
     const float* __restrict__ bias, const int8_t* __restrict__ signs, const float* __restrict__ codebook,
@@ -57,6 +61,7 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
     const bf16_t* __restrict__ qv, float score_scale, float* __restrict__ scores, int seq_len, int q_heads, int64_t T,
     int D, const float* __restrict__ rope_cos, const float* __restrict__ rope_sin, const float* __restrict__ weights,
     float* __restrict__ part) {
+  static_assert(!WIDE || MODE != kEncode, "the quantizer needs the whole group: groups across the heads are not fused");
   __shared__ __attribute__((aligned(16))) unsigned char smem[kFusedLdsBytes];
   Lds& cl = *reinterpret_cast<Lds*>(smem + kPredBytes);
   const bool use_table = MODE == kEncode && table != nullptr;
@@ -118,10 +123,31 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
       } else {
         in.code = *reinterpret_cast<const u32x4*>(src);
       }
-      if constexpr (is_rtn(NCW)) in.scale = rtn_load_meta<false>(scales, gid, q);
-      else in.scale = scales[gid];
+      if constexpr (is_rtn(NCW)) in.scale = rtn_load_meta<WIDE>(scales, gid, q);
+      else in.scale = scales[WIDE ? row : gid];
     }
   };
+  // WIDE, grids: the code bytes of this lane's 16 sub-vector slots in each of the 8 heads of its token
+  constexpr bool kWideGrid = WIDE && !is_rtn(NCW);
+  struct WideCodes { u32x4 h[kWideGrid ? 8 : 1]; };
+  const auto fetch_wide = [&](int pass, WideCodes& wc) {
+    int64_t row = m0 + wave * kRowsPerWave + pass * 16 + (lane >> 2);
+    row = row < T ? row : T - 1;
+#pragma unroll
+    for (int hh = 0; hh < 8; ++hh) {
+      const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + (row * H + hh) * (kGroup / 2 * c / 8) + q * (2 * c));
+      wc.h[hh] = u32x4{0, 0, 0, 0};
+      if constexpr (c == 4) {
+        const u32x2 v2 = *reinterpret_cast<const u32x2*>(src);
+        wc.h[hh].x = v2.x; wc.h[hh].y = v2.y;
+      } else if constexpr (c == 6) {
+        wc.h[hh].x = src[0]; wc.h[hh].y = src[1]; wc.h[hh].z = src[2];
+      } else {
+        wc.h[hh] = *reinterpret_cast<const u32x4*>(src);
+      }
+    }
+  };
+  WideCodes wide_codes;                                  // of the pass at hand; the next pass's are fetched while it runs
 
   // kWeighted: the attention weights of query head slot lane % 16 (of this kv head) for 8 of the wave's 32 token rows,
   // in the layout of the A operand of the 16x16x32 matrix instruction; slots beyond the group's heads stay zero.
@@ -131,6 +157,7 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
   gemm_mainloop<WAVES>(smem, x0, d0, x1, d1, W, T, m0, n0, acc, [&] {
 #pragma unroll
     for (int pass = 0; pass < kPasses; ++pass) fetch(pass, in[pass]);
+    if constexpr (kWideGrid) fetch_wide(0, wide_codes);
     if constexpr (MODE == kWeighted) {
       static_assert(MODE != kWeighted || kRowsPerWave == 32, "one 32-token contraction per wave");
       const int rep = q_heads / H, slot = lane & 15;
@@ -192,6 +219,48 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
     } else {
       if constexpr (is_rtn(NCW)) {
         rtn_reconstruct<NCW>(in.code, in.scale, p, v);
+      } else if constexpr (WIDE) {
+        // zhat of the 8 heads, added as the stages across the heads of the 1024-point transform add them for head
+        // `head`: ((0 +- 1) +- (2 +- 3)) +- ((4 +- 5) +- (6 +- 7)), minus where the head's bit of that level is set
+        const float s16 = half_bits_to_float((uint16_t)in.scale);
+        const float g0 = (head & 1) ? -1.0f : 1.0f, g1 = (head & 2) ? -1.0f : 1.0f, g2 = (head & 4) ? -1.0f : 1.0f;
+        const WideCodes wc = wide_codes;
+        if (pass + 1 < kPasses) fetch_wide(pass + 1, wide_codes);
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          const auto zhat_half = [&](int hh, float (&z)[16]) {
+            int idx[16];
+            unpack_codes<NCW>(wc.h[hh], idx);
+#pragma unroll
+            for (int m = 0; m < 8; ++m) {
+              const float2 cw = *reinterpret_cast<const float2*>(&cl.cb[idx[8 * half + m]]);
+              z[2 * m] = cw.x * s16;
+              z[2 * m + 1] = cw.y * s16;
+            }
+          };
+          const auto pair_of = [&](int hh, float (&t)[16]) {        // z[hh] +- z[hh + 1]
+            float b[16];
+            zhat_half(hh, t);
+            zhat_half(hh + 1, b);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) t[i] = __fmaf_rn(b[i], g0, t[i]);
+          };
+          float u0[16], u1[16], t[16];
+          pair_of(0, u0);
+          pair_of(2, t);
+#pragma unroll
+          for (int i = 0; i < 16; ++i) u0[i] = __fmaf_rn(t[i], g1, u0[i]);
+          pair_of(4, u1);
+          pair_of(6, t);
+#pragma unroll
+          for (int i = 0; i < 16; ++i) u1[i] = __fmaf_rn(t[i], g1, u1[i]);
+#pragma unroll
+          for (int i = 0; i < 16; ++i) v[16 * half + i] = __fmaf_rn(u1[i], g2, u0[i]);
+        }
+        wht128(v, q);
+        const float norm = quad_sign(q) * Rot<true>::kNorm;
+#pragma unroll
+        for (int r = 0; r < 32; ++r) v[r] = __uint_as_float(__float_as_uint(v[r] * norm) ^ sb[r]) + p[r];
       } else {
         int idx[16];
         unpack_codes<NCW>(in.code, idx);
@@ -342,8 +411,9 @@ hipError_t launch(int n_codewords, const void* x0, int d0, const void* x1, int d
                   const int8_t* signs, const float* codebook, const void* table, const void* X, uint8_t* codes,
                   uint16_t* scales, void* Xhat, const void* q, float score_scale, float* scores, int seq_len,
                   int q_heads, int64_t T, int D, const float* rope_cos, const float* rope_sin, const float* weights,
-                  float* part, hipStream_t stream) {
+                  float* part, bool wide, hipStream_t stream) {
   if (T == 0) return hipSuccess;
+  if (wide && (MODE == kEncode || D != 8 * BN)) return hipErrorInvalidValue;
   const unsigned blocks = (unsigned)(((T + BM - 1) / BM) * (D / BN));
   // 8 wavefronts per tile (two per SIMD): the main loop is bound by L2 -> LDS traffic either
   // way, and the second wave fills the issue slots the first leaves in the VALU-heavy epilogue
@@ -352,18 +422,26 @@ hipError_t launch(int n_codewords, const void* x0, int d0, const void* x1, int d
 #define AQUAKV_FUSED_WAVES 8
 #endif
   constexpr int kWaves = AQUAKV_FUSED_WAVES;
-#define AQUAKV_FUSED(N)                                                                                          \
-  fused_kernel<N, MODE, kWaves><<<blocks, kWaves * 64, 0, stream>>>(                                             \
+#define AQUAKV_FUSED_W(N, WIDE)                                                                                  \
+  fused_kernel<N, MODE, kWaves, WIDE><<<blocks, kWaves * 64, 0, stream>>>(                                       \
       static_cast<const bf16_t*>(x0), d0, static_cast<const bf16_t*>(x1), d1, static_cast<const bf16_t*>(W), bias, \
       signs, codebook, static_cast<const uint32_t*>(table), static_cast<const bf16_t*>(X), codes, scales,         \
       static_cast<bf16_t*>(Xhat), static_cast<const bf16_t*>(q), score_scale, scores, seq_len, q_heads, T, D, rope_cos,  \
       rope_sin, weights, part)
+#define AQUAKV_FUSED(N)                                            \
+  do {                                                             \
+    if constexpr (MODE != kEncode) {                               \
+      if (wide) { AQUAKV_FUSED_W(N, true); break; }                \
+    }                                                              \
+    AQUAKV_FUSED_W(N, false);                                      \
+  } while (0)
   if (n_codewords == kRtn2) AQUAKV_FUSED(kRtn2);
   else if (n_codewords == kRtn4) AQUAKV_FUSED(kRtn4);
   else if (n_codewords == 16) AQUAKV_FUSED(16);
   else if (n_codewords == 64) AQUAKV_FUSED(64);
   else AQUAKV_FUSED(256);
 #undef AQUAKV_FUSED
+#undef AQUAKV_FUSED_W
   return hipGetLastError();
 }
 
@@ -374,35 +452,35 @@ hipError_t launch_fused_encode(int n_codewords, const void* x0, int d0, const vo
                                const void* X, uint8_t* codes, uint16_t* scales, void* Xhat, int64_t T, int D,
                                hipStream_t stream) {
   return launch<kEncode>(n_codewords, x0, d0, x1, d1, W, bias, signs, codebook, table, X, codes, scales, Xhat, nullptr,
-                         0.f, nullptr, 1, 1, T, D, nullptr, nullptr, nullptr, nullptr, stream);
+                         0.f, nullptr, 1, 1, T, D, nullptr, nullptr, nullptr, nullptr, false, stream);
 }
 
 hipError_t launch_fused_decode(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W,
                                const float* bias, const int8_t* signs, const float* codebook, const uint8_t* codes,
-                               const uint16_t* scales, void* Xhat, int64_t T, int D, hipStream_t stream) {
+                               const uint16_t* scales, void* Xhat, int64_t T, int D, bool wide, hipStream_t stream) {
   return launch<kDecode>(n_codewords, x0, d0, x1, d1, W, bias, signs, codebook, nullptr, nullptr,
                          const_cast<uint8_t*>(codes), const_cast<uint16_t*>(scales), Xhat, nullptr, 0.f, nullptr, 1, 1,
-                         T, D, nullptr, nullptr, nullptr, nullptr, stream);
+                         T, D, nullptr, nullptr, nullptr, nullptr, wide, stream);
 }
 
 hipError_t launch_fused_scores(int n_codewords, const void* x0, int d0, const void* W, const float* bias,
                                const int8_t* signs, const float* codebook, const uint8_t* codes,
                                const uint16_t* scales, const void* q, float score_scale, float* scores, void* Khat_out,
                                int seq_len, int q_heads, int64_t T, int D, const float* rope_cos, const float* rope_sin,
-                               hipStream_t stream) {
+                               bool wide, hipStream_t stream) {
   return launch<kScores>(n_codewords, x0, d0, nullptr, 0, W, bias, signs, codebook, nullptr, nullptr,
                          const_cast<uint8_t*>(codes), const_cast<uint16_t*>(scales), Khat_out, q, score_scale, scores,
-                         seq_len, q_heads, T, D, rope_cos, rope_sin, nullptr, nullptr, stream);
+                         seq_len, q_heads, T, D, rope_cos, rope_sin, nullptr, nullptr, wide, stream);
 }
 
 hipError_t launch_fused_weighted(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W,
                                  const float* bias, const int8_t* signs, const float* codebook, const uint8_t* codes,
                                  const uint16_t* scales, void* Xhat, const float* weights, float* part, float* pstats,
-                                 int seq_len, int q_heads, int64_t T, int D, hipStream_t stream) {
+                                 int seq_len, int q_heads, int64_t T, int D, bool wide, hipStream_t stream) {
   // pstats travels in the kernel's `scores` argument, which this mode does not use otherwise
   return launch<kWeighted>(n_codewords, x0, d0, x1, d1, W, bias, signs, codebook, nullptr, nullptr,
                            const_cast<uint8_t*>(codes), const_cast<uint16_t*>(scales), Xhat, nullptr, 0.f, pstats,
-                           seq_len, q_heads, T, D, nullptr, nullptr, weights, part, stream);
+                           seq_len, q_heads, T, D, nullptr, nullptr, weights, part, wide, stream);
 }
 
 }  // namespace aquakv

@@ -37,18 +37,19 @@ hipError_t launch_attn_scores(int dtype, int n_codewords, const uint8_t* codes, 
 
 // Fused bf16 forms: prediction [x0 | x1] W^T + bias on the matrix cores, consumed in the same
 // kernel by the quantizer (encode), its inverse (decode) or its inverse plus q.k (scores).
+// wide (decode, scores, weighted; D = 1024): rotation groups of 1024 = the whole token, one scale per token.
 hipError_t launch_fused_encode(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W,
                                const float* bias, const int8_t* signs, const float* codebook, const void* table,
                                const void* X, uint8_t* codes, uint16_t* scales, void* Xhat, int64_t T, int D,
                                hipStream_t stream);
 hipError_t launch_fused_decode(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W,
                                const float* bias, const int8_t* signs, const float* codebook, const uint8_t* codes,
-                               const uint16_t* scales, void* Xhat, int64_t T, int D, hipStream_t stream);
+                               const uint16_t* scales, void* Xhat, int64_t T, int D, bool wide, hipStream_t stream);
 hipError_t launch_fused_scores(int n_codewords, const void* x0, int d0, const void* W, const float* bias,
                                const int8_t* signs, const float* codebook, const uint8_t* codes,
                                const uint16_t* scales, const void* q, float score_scale, float* scores, void* Khat_out,
                                int seq_len, int q_heads, int64_t T, int D, const float* rope_cos, const float* rope_sin,
-                               hipStream_t stream);
+                               bool wide, hipStream_t stream);
 
 // Value side of attention.  The sums over tokens are taken per chunk of kWeightedChunk tokens of one sequence
 // (part[batch * chunks_per_seq, q_heads, 128] fp32, chunks_per_seq = ceil(seq_len / kWeightedChunk)) and then added in
@@ -62,7 +63,7 @@ constexpr int kWeightedChunk = 256;
 hipError_t launch_fused_weighted(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W,
                                  const float* bias, const int8_t* signs, const float* codebook, const uint8_t* codes,
                                  const uint16_t* scales, void* Xhat, const float* weights, float* part, float* pstats,
-                                 int seq_len, int q_heads, int64_t T, int D, hipStream_t stream);
+                                 int seq_len, int q_heads, int64_t T, int D, bool wide, hipStream_t stream);
 // chunk sums over values already decoded to memory (any dtype, any seq_len)
 hipError_t launch_weighted_values(int dtype, const void* Vhat, const float* weights, float* part, float* pstats, int batch,
                                   int seq_len, int H, int q_heads, hipStream_t stream);

@@ -190,7 +190,7 @@ def test_weighted_values_call_validates_its_arguments():
     a[5] = None                                                                     # no Vhat: only where the sums are fused
     assert status_of(call, L, 1, 255, 8, *a, ws) == B.AQUAKV_ENULL                    # ragged sequence
     assert status_of(call, L32, 1, 256, 8, *a, ws) == B.AQUAKV_ENULL
-    assert status_of(call, layer(rht_group=1024), 1, 256, 8, *a, ws) == B.AQUAKV_ENULL
+    assert status_of(call, layer(rht_group=1024, dtype=B.AQUAKV_FP32), 1, 256, 8, *a, ws) == B.AQUAKV_ENULL
     assert status_of(call, layer(d_in_k=0, d_in_v=0, w_k=None, w_v=None), 1, 256, 8, FAKE, FAKE, None, None, FAKE, None,
                      FAKE, ws) == B.AQUAKV_ENULL                                    # first layer
     assert status_of(call, L, 1, 256, 8, *ok, (FAKE, 1024)) == B.AQUAKV_EWORKSPACE

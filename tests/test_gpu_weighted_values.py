@@ -230,7 +230,7 @@ def test_weighted_values_other_quantizers(B, bits, rht_group):
     cfg = synth.Config("wq", layers=2, kv_heads=H, head_dim=128, tokens=T, dtype="bf16", n_codewords=16)
     g = P.run_gpu_layers(B, cfg, [lg0, lg1], [K0, K1], [V0, V1])[1]
     w = weights_for(batch, QH, S, 91, "softmax")
-    check_weighted(B, lo1, lg1, g, batch, S, QH, w, fused_expected=rht_group is None, label="weighted")
+    check_weighted(B, lo1, lg1, g, batch, S, QH, w, fused_expected=True, label="weighted")   # groups of 1024 decode fused too
 
 
 def test_attention_over_the_compressed_cache_end_to_end(B):
