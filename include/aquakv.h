@@ -92,9 +92,10 @@ typedef struct aquakv_layer {
                            with one scale, scales [tokens] (the grouping of the paper's
                            experiments, Sect. 4.1: 1024 values, 2.02 stored bits per
                            value; built for 8 heads of 128).  The code bytes have the
-                           same layout either way.  Groups across heads are not
-                           fused with the predictor: the calls then need the fp32
-                           prediction workspace also in bf16.  With vq_dim = 1: 0 or
+                           same layout either way.  Encoding groups across heads is
+                           not fused with the predictor (the scale is a statistic of
+                           the whole group): the calls keep the fp32 prediction
+                           workspace also in bf16; decoding them is fused.  With vq_dim = 1: 0 or
                            64, the group of the round-to-nearest backbone, or 1024 =
                            the whole token of 8 heads (one (step, zero) per token).  */
   const float* codebook;   /* [n, 2] fp32 grid points (ignored when vq_dim = 1, like
@@ -272,7 +273,7 @@ int aquakv_decode_attn_scores_rope(const aquakv_layer* layer, int32_t batch, int
  *   a caller that also attends to tokens outside the compressed cache normalises over all of them
  *   and adds their share itself).  out: device, fp32 [batch, q_heads, g].  Vhat (dtype,
  *   [batch*seq_len, H, g]) receives the decoded values, which the next layer's predictor reads.
- *   For bf16 layers with a value predictor, rotation groups of one head and seq_len a multiple of 256
+ *   For bf16 layers with a value predictor and seq_len a multiple of 256
  *   the sums are taken inside the decode kernel from the values it holds
  *   on chip (weights enter as bf16 pairs hi + lo, i.e. with 16 mantissa bits; products accumulate in
  *   fp32), and Vhat may then be NULL: nothing but `out` is written (the last layer of a sweep).
