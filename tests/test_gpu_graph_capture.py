@@ -14,12 +14,13 @@ def bits_of(t):
     return t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32)
 
 
-@pytest.mark.parametrize("dtype,rtn_bits,T", [("bf16", None, 515), ("fp32", None, 515), ("bf16", 2, 515), ("bf16", None, 512)])
-def test_layer_sweeps_replay_from_a_graph(dtype, rtn_bits, T):
+@pytest.mark.parametrize("dtype,rtn_bits,T,rht_group", [("bf16", None, 515, None), ("fp32", None, 515, None), ("bf16", 2, 515, None),
+                                                       ("bf16", None, 512, None), ("bf16", None, 512, 1024)])
+def test_layer_sweeps_replay_from_a_graph(dtype, rtn_bits, T, rht_group):
     if not torch.cuda.is_available():
         pytest.fail("no GPU visible: the gpu-marked tests must run on an MI355X")
     from paper_2501_19392_amd import binding as B
-    print(f"case graph capture dtype={dtype} rtn_bits={rtn_bits} T={T}", flush=True)
+    print(f"case graph capture dtype={dtype} rtn_bits={rtn_bits} T={T} rht_group={rht_group}", flush=True)
     H, QH, L = 8, 24, 3
     D = H * 128
     sd = synth.torch_dtype(dtype)
@@ -27,7 +28,7 @@ def test_layer_sweeps_replay_from_a_graph(dtype, rtn_bits, T):
     for l in range(L):
         kw = {} if l == 0 else dict(w_k=U.random_weights(D, D, 400 + l, 0.7), w_v=U.random_weights(D, 2 * D, 500 + l, 0.7),
                                     b_k=torch.randn(D, generator=torch.Generator().manual_seed(600 + l)) * 0.1)
-        layers.append(U.make_layers(H, dtype, 16, layer_idx=l, rtn_bits=rtn_bits, **kw)[1])
+        layers.append(U.make_layers(H, dtype, 16, layer_idx=l, rtn_bits=rtn_bits, rht_group=rht_group, **kw)[1])
 
     def inputs(seed):
         g = torch.Generator().manual_seed(seed)
