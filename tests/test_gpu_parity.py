@@ -808,3 +808,37 @@ def test_decode_read_path_batch_of_long_sequences(B):
     sync()
     assert torch.equal(kc2, cut(kc)) and torch.equal(ks2, cut(ks)) and torch.equal(vc2, cut(vc))
     assert torch.equal(bits(Kh2), bits(cut(Kh))) and torch.equal(bits(Vh2), bits(cut(Vh)))
+
+
+def test_group_1024_at_the_bench_shape(B):
+    """Rotation groups of 1024 at 8192 tokens (the launch shape of `bench.py --rht-group 1024`): the fused decode,
+    scores and attention forms reproduce what the (unfused) encoder reconstructed, bit for bit, and the scores and
+    sums are those of the tensors written."""
+    print("case group 1024 at 8192 tokens", flush=True)
+    H, T, QH = 8, 8192, 24
+    cfg = synth.Config("wide8k", layers=2, kv_heads=H, head_dim=128, tokens=T, dtype="bf16", n_codewords=16)
+    Ks, Vs, lo_l, lg_l = build_stack(cfg, rht_group=H * 128)
+    g = run_gpu_layers(B, cfg, lg_l, Ks, Vs)[1]
+    lg = lg_l[1]
+    ws = lg.alloc_workspace(T)
+    Kd, Vd = lg.alloc_kv(T), lg.alloc_kv(T)
+    B.aquakv_decode_layer(lg, T, g["k_codes"], g["k_scales"], g["v_codes"], g["v_scales"], g["Kp"], g["Vp"], Kd, Vd, ws)
+    sync()
+    assert torch.equal(bits(Kd), bits(g["Khat"])) and torch.equal(bits(Vd), bits(g["Vhat"]))
+    q = synth.random_queries(1, QH, 128, seed=4, dtype="bf16", device="cuda")
+    scores = torch.empty(1, QH, T, dtype=torch.float32, device="cuda")
+    out = torch.empty(1, QH, 128, dtype=torch.float32, device="cuda")
+    Kd.zero_(); Vd.zero_()
+    B.aquakv_decode_attn_scores(lg, 1, T, QH, g["k_codes"], g["k_scales"], g["Kp"], q, 0.088388, scores, Kd, ws)
+    B.aquakv_decode_values_attend(lg, 1, T, QH, g["v_codes"], g["v_scales"], g["Vp"], Kd, scores, Vd, out, None,
+                                  lg.alloc_weighted_workspace(1, T, QH))
+    sync()
+    assert torch.equal(bits(Kd), bits(g["Khat"])) and torch.equal(bits(Vd), bits(g["Vhat"]))
+    k64, v64, q64 = U.np64(Kd), U.np64(Vd), U.np64(q)[0]
+    want_s = 0.088388 * np.stack([k64[:, qh // 3] @ q64[qh] for qh in range(QH)])
+    mag_s = 0.088388 * np.stack([np.abs(k64[:, qh // 3]) @ np.abs(q64[qh]) for qh in range(QH)])
+    assert np.all(np.abs(U.np64(scores)[0] - want_s) <= 1e-5 * mag_s + 1e-30)
+    p_rows = O.softmax_rows(U.np64(scores))[0]
+    own = np.stack([p_rows[qh] @ v64[:, qh // 3] for qh in range(QH)])
+    mag_v = np.stack([p_rows[qh] @ np.abs(v64[:, qh // 3]) for qh in range(QH)])
+    assert np.all(np.abs(U.np64(out)[0] - own) <= 3e-5 * mag_v)
