@@ -2,13 +2,17 @@
 """Benchmark of the AQUA-KV per-layer encode / decode path on one MI355X.
 
 A step = one pass of the whole hot path over one batch of synthetic KV shaped like
-the Llama-3.2-3B cache (28 layers, 8 KV heads x 128, 8192 tokens, bf16, 2 bits per
-value): for every layer `aquakv_encode_layer`, then for every layer
-`aquakv_decode_layer`, then for every layer `aquakv_decode_attn_scores` (24 query
-heads).  Inputs are resident in HBM before the timed region.  The printed JSON line
-reports tokens/s per layer (tokens * layers / step time), the roofline position of
-the dominant kernel (the fused bf16 MFMA predictor + quantizer kernel) from HIP events, and the CPU
-oracle timed on a bounded sample of the same workload.
+the Llama-3.1-8B cache (32 layers, 8 KV heads x 128, 32768 tokens, bf16, 2 bits per
+value): for every layer `aquakv_encode_layer`, then the decode sweep that also yields
+the q.k scores (32 query heads).  Inputs are resident in HBM before the timed region.
+The printed JSON line reports tokens/s per layer (tokens * layers / step time), the
+roofline position of the dominant kernel (the fused bf16 MFMA predictor + quantizer
+kernel) from HIP events, one roofline entry per stage (`roofline_stages`), the CPU
+oracle timed on a bounded sample of the same workload and, under `other_workloads`,
+the same measurements at the Llama-3.1-70B shape (80 x 131072 tokens, mixed 2 / 3
+bits), the Llama-3.2-3B shape, the 3-bit grid and the decode read path (64 x 16384
+cached tokens: scoring call and one-token append apart).  `--no-extras` keeps the
+headline workload only; `--config` picks another headline.
 """
 from __future__ import annotations
 
@@ -33,12 +37,13 @@ PEAK_HBM_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = {("llama3.2-3b", 16): (2.0 * 33035.0 + 1.0 * 18560.0) * 1024.0}
 
 
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", default="llama3.2-3b",
+    ap.add_argument("--config", default="llama3.1-8b",
                     choices=["llama3.2-3b", "llama3.1-8b", "llama3.1-70b", "decode-read", "calibrate", "tiny"],
                     help="llama3.1-70b: 80 layers x 131072 tokens, grid of 16 or 64 points per layer (seeded coin); "
                          "decode-read: 64 sequences x 16384 cached tokens, scoring call + one-token append per layer; "
@@ -53,6 +58,9 @@ def parse():
                     help="2 or 4: the uniform round-to-nearest backbone (groups of 64) instead of the grid (0)")
     ap.add_argument("--q-heads", type=int, default=0, help="query heads for the scoring call (0: model default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the other workloads (70B shape, 3B shape, 3-bit grid, decode read path) that the default "
+                         "run appends under `other_workloads`")
     ap.add_argument("--no-kernel-events", action="store_true", help="skip the instrumented replay")
     ap.add_argument("--cpu-rows", type=int, default=8192, help="token rows of the oracle sample")
     ap.add_argument("--cpu-layers", type=int, default=8, help="predicted layers of the oracle sample")
@@ -128,17 +136,20 @@ class Buffers:
         self.attn_out = torch.empty(1, q_heads, lay.head_dim, dtype=torch.float32, device=device)
         self.ws_weighted = lay.alloc_weighted_workspace(1, T, q_heads, device)
         self.P = torch.empty(T, lay.d, dtype=torch.float32, device=device)
-        # the scoring call folds the predictor into the query iff it is handed this workspace
-        from paper_2501_19392_amd import binding as B
-        if B.aquakv_scores_workspace_bytes(layers[-1], 1, q_heads) == 0:
-            self.ws_scores = self.ws                      # no folded form for this layer type (fp32): prediction workspace
-        elif scores_form == "folded":
-            self.ws_scores = layers[-1].alloc_scores_workspace(1, q_heads, device)
-        else:
-            self.ws_scores = torch.empty(16, dtype=torch.uint8, device=device)
+        # scoring calls of their own take the folded form (aquakv_decode_attn_scores_folded) where it exists
+        self.folded = scores_form == "folded"
+        self.ws_scores = layers[-1].alloc_scores_workspace(1, q_heads, device)
 
 
 SCORE_SCALE = 0.088388          # 1 / sqrt(128)
+
+
+def scoring_call(B, lay, batch, S, q_heads, kc, ks, kp, q, scores, ws_scores, folded, ws):
+    """A scoring call of its own (no keys out): the folded form where it exists and is asked for, else the definition."""
+    if folded and kp is not None and B.aquakv_scores_workspace_bytes(lay, batch, q_heads) > 0:
+        B.aquakv_decode_attn_scores_folded(lay, batch, S, q_heads, kc, ks, kp, q, SCORE_SCALE, scores, ws_scores)
+    else:
+        B.aquakv_decode_attn_scores(lay, batch, S, q_heads, kc, ks, kp, q, SCORE_SCALE, scores, None, ws)
 
 
 def decode_sweep_with_scores(B, layers, buf, q, T, q_heads):
@@ -190,7 +201,7 @@ def run_step(B, layers, Ks, Vs, buf, q, T, q_heads, scores_in_sweep=True):
     for l, lay in enumerate(layers):
         (kc, ks), _ = buf.codes[l]
         kp = None if l == 0 else buf.hat[(l - 1) & 1][0]
-        B.aquakv_decode_attn_scores(lay, 1, T, q_heads, kc, ks, kp, q, SCORE_SCALE, buf.scores, None, buf.ws_scores)
+        scoring_call(B, lay, 1, T, q_heads, kc, ks, kp, q, buf.scores, buf.ws_scores, buf.folded, buf.ws)
 
 
 def chains_on_two_streams(B, layers, Ks, Vs, buf, T, phase):
@@ -232,10 +243,10 @@ def run_step_two_streams(B, layers, Ks, Vs, buf, q, T, q_heads, scores_in_sweep=
     for l, lay in enumerate(layers):
         (kc, ks), _ = buf.codes[l]
         kp = None if l == 0 else buf.hat4[(l - 1) & 3][0]
-        B.aquakv_decode_attn_scores(lay, 1, T, q_heads, kc, ks, kp, q, SCORE_SCALE, buf.scores, None, buf.ws_scores)
+        scoring_call(B, lay, 1, T, q_heads, kc, ks, kp, q, buf.scores, buf.ws_scores, buf.folded, buf.ws)
 
 
-def timed_phases(B, layers, Ks, Vs, buf, q, T, q_heads, reps, streams=1, scores_in_sweep=False):
+def timed_phases(B, layers, Ks, Vs, buf, q, T, q_heads, reps, streams=1, scores_in_sweep=False, reference=True):
     """Per-phase GPU time (ms per step) from stream events: encode / decode / scores (scoring calls of their own),
     and, when that is the step's form, decode+scores (the decode sweep that also yields the scores) and, for
     reference only, decode+attention (that sweep with soft-max and the weighted sum over the values as well)."""
@@ -262,10 +273,11 @@ def timed_phases(B, layers, Ks, Vs, buf, q, T, q_heads, reps, streams=1, scores_
                 B.aquakv_decode_layer(lay, T, kc, ks, vc, vs, prev[0], prev[1], Kh, Vh, buf.ws)
             else:
                 kp = None if l == 0 else buf.hat[(l - 1) & 1][0]
-                B.aquakv_decode_attn_scores(lay, 1, T, q_heads, kc, ks, kp, q, SCORE_SCALE, buf.scores, None, buf.ws_scores)
+                scoring_call(B, lay, 1, T, q_heads, kc, ks, kp, q, buf.scores, buf.ws_scores, buf.folded, buf.ws)
             prev = (Kh, Vh)
 
-    for phase in ("encode", "decode", "scores") + (("decode+scores", "decode+attention") if scores_in_sweep else ()):
+    extra = ("decode+scores",) + (("decode+attention",) if reference else ())
+    for phase in ("encode", "decode", "scores") + (extra if scores_in_sweep else ()):
         run_phase(phase)                          # untimed: the first call of a kernel loads its code
         a, b = ev(), ev()
         torch.cuda.synchronize()
@@ -491,8 +503,8 @@ def decode_read_path(args, device):
 
     def score_all():
         for l, lay in enumerate(layers):
-            B.aquakv_decode_attn_scores(lay, batch, S, q_heads, codes[l][0], codes[l][1], None if l == 0 else khat[l - 1], q,
-                                        0.088388, scores, None, ws_scores)
+            scoring_call(B, lay, batch, S, q_heads, codes[l][0], codes[l][1], None if l == 0 else khat[l - 1], q, scores,
+                         ws_scores, folded, ws)
 
     def append_all():
         (kc, ks), (vc, vs), Kh, Vh = app[0]
@@ -528,8 +540,8 @@ def decode_read_path(args, device):
     a.record()
     for _ in range(reps):
         for l in range(1, L):
-            B.aquakv_decode_attn_scores(layers[l], batch, S, q_heads, codes[l][0], codes[l][1], khat[l - 1], q, 0.088388,
-                                        scores, None, ws_scores)
+            scoring_call(B, layers[l], batch, S, q_heads, codes[l][0], codes[l][1], khat[l - 1], q, scores, ws_scores,
+                         folded, ws)
     b.record()
     torch.cuda.synchronize()
     call_ms = a.elapsed_time(b) / (reps * pred_layers)
@@ -551,53 +563,127 @@ def decode_read_path(args, device):
     }
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (--gpus 1); the path shards along tokens with no "
-              "exchange between GPUs, so N GPUs are N independent copies of this run", file=sys.stderr)
-        sys.exit(2)
+def stage_rooflines(B, layers, Ks, Vs, buf, q, T, q_heads, reps):
+    """One roofline entry per stage of the path, each against its own bound, from HIP events on the launch
+    stream around the calls of that stage alone (a layer-level call of a predicted bf16 layer is two launches of
+    the same kernel, keys then values; a layer-0 call is two launches of the stand-alone kernel)."""
+    import torch
+    lay0, lay1 = layers[0], layers[-1]
+    D = lay0.d
+    eb = 2
+    n_pred = len(layers) - 1
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, n):
+        fn()
+        a, b = ev(), ev()
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(n):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+
+    def code_bytes(lay):          # codes + scales of one tensor, per token
+        return lay.kv_heads * lay.code_bytes_per_group + 2 * (D // lay.rht_group) * lay.scale_words_per_group
+
+    out = []
+
+    def entry(stage, kernel, bound, work, ms, launches, note=None):
+        per_launch = work / launches
+        us = 1e3 * ms / launches
+        if bound == "mfma":
+            achieved, peak, unit = per_launch / (us * 1e-6) / 1e12, PEAK_BF16_TFLOPS, "TFLOP/s"
+            key = "algorithmic_flops_per_launch"
+        else:
+            achieved, peak, unit = per_launch / (us * 1e-6) / 1e9, PEAK_HBM_GBS, "GB/s"
+            key = "algorithmic_bytes_per_launch"
+        e = {"stage": stage, "kernel": kernel, "bound": bound, "achieved": round(achieved, 2), "peak": peak, "unit": unit,
+             "frac": round(achieved / peak, 4), "traffic": None, "launches": launches, "avg_launch_us": round(us, 2),
+             key: round(per_launch, 1)}
+        if note:
+            e["note"] = note
+        out.append(e)
+
+    (kc0, ks0), (vc0, vs0) = buf.codes[0]
+    Kh, Vh = buf.hat[0]
+    # stand-alone quantize / dequantize (layer 0: no predictor), HBM-bound: x in, xhat + codes + scale out
+    ms = timed(lambda: B.aquakv_encode_layer(lay0, T, Ks[0], Vs[0], None, None, kc0, ks0, vc0, vs0, Kh, Vh, buf.ws), reps)
+    entry("quantize (layer 0)", "quantize_kernel", "hbm", 2 * T * (2 * D * eb + code_bytes(lay0)), ms, 2)
+    ms = timed(lambda: B.aquakv_decode_layer(lay0, T, kc0, ks0, vc0, vs0, None, None, Kh, Vh, buf.ws), reps)
+    entry("dequantize (layer 0)", "dequantize_kernel", "hbm", 2 * T * (D * eb + code_bytes(lay0)), ms, 2)
+    if n_pred == 0 or lay1.dtype != torch.bfloat16:
+        return out
+    wide = lay1.rht_group == D
+
+    def sweep(kind):
+        prev = buf.hat[0]
+        for l in range(1, len(layers)):
+            lay = layers[l]
+            (kc, ks), (vc, vs) = buf.codes[l]
+            Kh, Vh = buf.hat[l & 1]
+            if kind == "encode":
+                B.aquakv_encode_layer(lay, T, Ks[l], Vs[l], prev[0], prev[1], kc, ks, vc, vs, Kh, Vh, buf.ws)
+            elif kind == "decode":
+                B.aquakv_decode_layer(lay, T, kc, ks, vc, vs, prev[0], prev[1], Kh, Vh, buf.ws)
+            else:
+                scoring_call(B, lay, 1, T, q_heads, kc, ks, prev[0], q, buf.scores, buf.ws_scores, buf.folded, buf.ws)
+            prev = (Kh, Vh)
+
+    flops = sum(2.0 * T * D * (lay.c.d_in_k + lay.c.d_in_v) for lay in layers[1:])
+    ms = timed(lambda: sweep("encode"), reps)
+    entry("encode (predicted layers)", "predict_bf16_kernel + quantize_kernel (groups across heads)" if wide and not getattr(B, "WIDE_ENCODE_FUSED", False)
+          else "fused_kernel<encode>", "mfma", flops, ms, 2 * n_pred)
+    ms = timed(lambda: sweep("decode"), reps)
+    entry("decode (predicted layers)", "fused_kernel<decode>", "mfma", flops, ms, 2 * n_pred)
+    folded = B.aquakv_scores_workspace_bytes(lay1, 1, q_heads) > 0
+    ms = timed(lambda: sweep("scores"), reps)
+    passes = 1 if q_heads <= 32 else 2
+    if folded:
+        nbytes = n_pred * (passes * T * (D * eb + code_bytes(lay1)) + q_heads * T * 4)
+        entry("q.k scores of their own (predictor folded into the query)", "fold_query_kernel + folded_scores_kernel", "hbm", nbytes, ms,
+              n_pred, note="one call = both launches; the cache is read once per 4 query heads of a kv head (%d pass%s)" % (passes, "" if passes == 1 else "es"))
+    else:
+        entry("q.k scores of their own (prediction recomputed)", "fused_kernel<scores>", "mfma",
+              sum(2.0 * T * D * lay.c.d_in_k for lay in layers[1:]), ms, n_pred)
+    return out
+
+
+def layer_workload(args, config, device, steps, warmup, n_codewords=None, rht_group=0, rtn_bits=0, q_heads_arg=0,
+                   with_cpu_baseline=True, reference_phases=True):
+    """Builds one layer-stack workload, times `steps` steps of it and returns the JSON line as a dict."""
     import torch
     from paper_2501_19392_amd import binding as B
     from paper_2501_19392_amd import synth
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    device = "cuda:0"
-    torch.cuda.set_device(0)
-    if args.config == "decode-read":
-        print(json.dumps(decode_read_path(args, device)))
-        return
-    if args.config == "calibrate":
-        print(json.dumps(calibration_path(args, device)))
-        return
+    n_codewords = n_codewords or args.n_codewords
     cfg = {"llama3.2-3b": synth.LLAMA32_3B, "llama3.1-8b": synth.LLAMA31_8B, "llama3.1-70b": synth.LLAMA31_70B,
-           "tiny": synth.TINY}[args.config]
+           "tiny": synth.TINY}[config]
     if args.layers:
         cfg = dataclasses.replace(cfg, layers=min(args.layers, cfg.layers))
-    q_heads = args.q_heads or {"llama3.2-3b": 24, "llama3.1-8b": 32, "llama3.1-70b": 64, "tiny": 8}[args.config]
+    q_heads = q_heads_arg or {"llama3.2-3b": 24, "llama3.1-8b": 32, "llama3.1-70b": 64, "tiny": 8}[config]
     T = cfg.tokens
-    if args.config == "llama3.1-70b":
+    if config == "llama3.1-70b":
         # grid of 16 or 64 points per layer by a seeded fair coin (2 or 3 code bits per value, 2.5 on average)
         coin = np.random.Generator(np.random.PCG64(synth.BASE_SEED + 99)).integers(0, 2, size=cfg.layers)
         n_per_layer = [16 if c == 0 else 64 for c in coin]
         bits_label = "%.2f (grid of 16 or 64 points per layer)" % (sum(n.bit_length() // 2 for n in n_per_layer) / cfg.layers)
         grid_label = "n=16|64 per layer"
     else:
-        n_per_layer = [args.n_codewords] * cfg.layers
-        bits_label = "%d" % (args.n_codewords.bit_length() // 2)
-        grid_label = f"n={args.n_codewords}"
-    if args.rtn_bits:
-        if args.config == "llama3.1-70b" or args.rht_group:
+        n_per_layer = [n_codewords] * cfg.layers
+        bits_label = "%d" % (n_codewords.bit_length() // 2)
+        grid_label = f"n={n_codewords}"
+    if rtn_bits:
+        if config == "llama3.1-70b" or rht_group:
             sys.exit("bench.py: --rtn-bits goes with one backbone for all layers and its own groups of 64")
-        bits_label = "%d (uniform round-to-nearest backbone, groups of 64: %.2f stored)" % (args.rtn_bits, args.rtn_bits + 0.5)
+        bits_label = "%d (uniform round-to-nearest backbone, groups of 64: %.2f stored)" % (rtn_bits, rtn_bits + 0.5)
         grid_label = ""
 
-    layers, Ks, Vs = build_workload(cfg, device, n_per_layer, args.rht_group, args.rtn_bits)
-    wide = args.rht_group not in (0, cfg.head_dim)
+    layers, Ks, Vs = build_workload(cfg, device, n_per_layer, rht_group, rtn_bits)
+    wide = rht_group not in (0, cfg.head_dim)
     if wide:
-        grid_label += f", rotation groups of {args.rht_group} (one scale per token)"
-    quantizer_label = (f"uniform round-to-nearest with {1 << args.rtn_bits} levels, groups of 64" if args.rtn_bits
+        grid_label += f", rotation groups of {rht_group} (one scale per token)"
+    quantizer_label = (f"uniform round-to-nearest with {1 << rtn_bits} levels, groups of 64" if rtn_bits
                        else f"{grid_label} codewords (p=2)")
     # the two-stream schedule keeps scoring calls of their own (folded where the form exists)
     sweep = args.scores_form == "sweep" and args.streams == 1
@@ -612,18 +698,19 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     step = run_step_two_streams if args.streams == 2 else run_step
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step(B, layers, Ks, Vs, buf, q, T, q_heads, sweep)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step(B, layers, Ks, Vs, buf, q, T, q_heads, sweep)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    ms_per_step = 1e3 * dt / args.steps
-    value = T * cfg.layers / (dt / args.steps)
+    ms_per_step = 1e3 * dt / steps
+    value = T * cfg.layers / (dt / steps)
 
-    phases = timed_phases(B, layers, Ks, Vs, buf, q, T, q_heads, max(1, min(args.steps, 5)), args.streams, sweep)
+    reps = max(1, min(steps, 5 if T <= 32768 else 2))
+    phases = timed_phases(B, layers, Ks, Vs, buf, q, T, q_heads, reps, args.streams, sweep, reference_phases)
     l0 = layer0_times(B, layers, Ks, Vs, buf, T, 5)
     eb = 2 if cfg.dtype == "bf16" else 4
     D = cfg.kv_heads * cfg.head_dim
@@ -634,24 +721,31 @@ def main():
     n_pred = max(cfg.layers - 1, 1)
     pred_ms = {k: (phases[k] - l0[k]) / n_pred for k in ("encode", "decode")}
     roofline = None
+    stages = None
     if cfg.dtype == "bf16" and not args.no_kernel_events:
-        flops, nbytes, ms, launches = encode_kernel_events(B, layers, Ks, Vs, buf, T, max(1, min(args.steps, 3)))
+        flops, nbytes, ms, launches = encode_kernel_events(B, layers, Ks, Vs, buf, T, max(1, min(steps, 3 if T <= 32768 else 1)))
         achieved = flops / (ms * 1e-3) / 1e12
-        if wide:
+        fused_wide = wide and getattr(B, "WIDE_ENCODE_FUSED", False)
+        if wide and not fused_wide:
             launches *= 2
-        roofline = {"kernel": "predict_bf16_kernel + quantize_kernel per tensor (groups across heads are not fused)" if wide
+        roofline = {"kernel": "predict_bf16_kernel + quantize_kernel per tensor (groups across heads are not fused)" if wide and not fused_wide
                     else "fused_kernel<encode> (bf16 MFMA predictor + quantizer epilogue)", "bound": "mfma",
                     "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                    "traffic": None if wide or args.rtn_bits else MEASURED_TRAFFIC_BYTES.get((args.config, args.n_codewords)), "launches": launches,
+                    # not measured in this run: a constant from the rocprofv3 --pmc summary under profiles/, or null
+                    "traffic": None if wide or rtn_bits else MEASURED_TRAFFIC_BYTES.get((config, n_codewords)),
+                    "traffic_source": "constant from profiles/ (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE of an earlier run of this command)"
+                    if not (wide or rtn_bits) and (config, n_codewords) in MEASURED_TRAFFIC_BYTES else None,
+                    "launches": launches,
                     "algorithmic_bytes_per_launch": round(nbytes / launches, 1),
                     "avg_launch_us": round(1e3 * ms / launches, 2),
                     "algorithmic_hbm_GBs": round(nbytes / (ms * 1e-3) / 1e9, 1),
                     "algorithmic_hbm_frac": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+        stages = stage_rooflines(B, layers, Ks, Vs, buf, q, T, q_heads, reps)
 
     line = {
         "metric": "KV encode+decode tokens/s per layer at %s bits/value" % bits_label,
-        "value": round(value, 1), "unit": "tokens/s per layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": round(value, 1), "unit": "tokens/s per layer", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.layers} layers x {T} tokens x {cfg.kv_heads} kv heads x {cfg.head_dim}, "
@@ -673,12 +767,72 @@ def main():
         "layer0": {"encode_ms": round(l0["encode"], 4), "decode_ms": round(l0["decode"], 4),
                    "encode_GBs": round(l0_bytes["encode"] / (l0["encode"] * 1e-3) / 1e9, 1),
                    "decode_GBs": round(l0_bytes["decode"] / (l0["decode"] * 1e-3) / 1e9, 1),
-                   "bound": "alu (VALU issue; HBM peak %.0f GB/s)" % PEAK_HBM_GBS},
+                   "bound": "hbm"},
         "roofline": roofline,
+        "roofline_stages": stages,
     }
-    if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(cfg, args.n_codewords, min(args.cpu_rows, T), q_heads, min(args.cpu_layers, cfg.layers - 1),
-                                            args.rtn_bits)
+    if with_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(cfg, n_codewords, min(args.cpu_rows, T), q_heads, min(args.cpu_layers, cfg.layers - 1),
+                                            rtn_bits)
+    del layers, Ks, Vs, buf
+    torch.cuda.empty_cache()
+    return line
+
+
+def brief(line):
+    """What an `other_workloads` entry keeps of a full line."""
+    keep = ("metric", "value", "unit", "steps", "warmup", "ms_per_step", "phases_ms_per_step", "roofline", "roofline_stages")
+    out = {k: line[k] for k in keep if k in line}
+    out["workload"] = line["config"]["workload"]
+    return out
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (--gpus 1); the path shards along tokens with no "
+              "exchange between GPUs, so N GPUs are N independent copies of this run", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    device = "cuda:0"
+    torch.cuda.set_device(0)
+    if args.config == "decode-read":
+        print(json.dumps(decode_read_path(args, device)))
+        return
+    if args.config == "calibrate":
+        print(json.dumps(calibration_path(args, device)))
+        return
+    log = lambda msg: print("bench.py: " + msg, file=sys.stderr, flush=True)
+    t_start = time.perf_counter()
+    line = layer_workload(args, args.config, device, args.steps, args.warmup, rht_group=args.rht_group, rtn_bits=args.rtn_bits,
+                          q_heads_arg=args.q_heads, with_cpu_baseline=not args.no_cpu_baseline)
+    log("headline workload done after %.0f s" % (time.perf_counter() - t_start))
+    plain = not (args.rht_group or args.rtn_bits or args.layers or args.streams != 1 or args.scores_form != "sweep"
+                 or args.n_codewords != 16 or args.q_heads)
+    if args.config == "llama3.1-8b" and plain and not args.no_extras:
+        # the other workloads of the workload list, in the same process and under the same clock; fewer steps each
+        # so that the whole run stays within a few minutes
+        others = {}
+        for name, kw, st, wu in (
+                ("llama3.1-8b, 3 bits (n=64)", dict(config="llama3.1-8b", n_codewords=64), min(args.steps, 5), 1),
+                ("llama3.1-70b, mixed 2/3 bits", dict(config="llama3.1-70b"), min(args.steps, 2), 1),
+                ("llama3.2-3b, 2 bits", dict(config="llama3.2-3b"), min(args.steps, 10), 2),
+                ("llama3.1-8b, 2 bits, rotation groups of 1024 (the paper's grouping)",
+                 dict(config="llama3.1-8b", rht_group=1024), min(args.steps, 5), 1)):
+            others[name] = brief(layer_workload(args, device=device, steps=st, warmup=wu, with_cpu_baseline=False,
+                                                reference_phases=False, **kw))
+            log("%s done after %.0f s" % (name, time.perf_counter() - t_start))
+        dr_args = argparse.Namespace(**vars(args))
+        dr_args.steps, dr_args.warmup, dr_args.layers = min(args.steps, 3), 1, 0
+        dr = decode_read_path(dr_args, device)
+        others["decode-read (64 x 16384 cached tokens, 32 query heads)"] = {
+            k: dr[k] for k in ("metric", "value", "unit", "steps", "warmup", "ms_per_step", "phases_ms_per_step", "roofline")}
+        others["decode-read (64 x 16384 cached tokens, 32 query heads)"]["workload"] = dr["config"]["workload"]
+        log("decode-read done after %.0f s" % (time.perf_counter() - t_start))
+        line["other_workloads"] = others
     print(json.dumps(line))
 
 
