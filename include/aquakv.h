@@ -102,7 +102,11 @@ typedef struct aquakv_layer {
                               signs_k, signs_v and search_table)                  */
   const int8_t* signs_k;   /* [H*g] entries +1 / -1: RHT signs for keys           */
   const int8_t* signs_v;   /* [H*g] same for values                               */
-  const void* w_k;      /* [D, d_in_k] row-major, dtype: K_pred = Khat_prev w_k^T */
+  const void* w_k;      /* [D, d_in_k] row-major, dtype: K_pred = Khat_prev w_k^T.  A departure
+                           from the order of the REQUIRE lines of Alg. "encode", which read as
+                           K_pred = Khat_prev W with W [d_in, D]: the weights are stored
+                           transposed, input index contiguous, which is how both operands of
+                           the matrix instructions want them                              */
   const float* b_k;     /* [D] fp32 bias or NULL                                  */
   const void* w_v;      /* [D, d_in_v] row-major; input columns: Vhat_prev first,
                            then this layer's Khat (Alg. "encode": [Vhat_prev; Khat]) */
@@ -165,7 +169,9 @@ int aquakv_dequantize(const aquakv_layer* layer, int which, int64_t tokens,
  * Khat_prev / Vhat_prev: required iff the layer has the respective predictor.
  * Khat, Vhat: outputs (nullable).  They are what Alg. "Inference" feeds to the
  * next layer; the stored (rounded) Khat is also what f_value reads.
- * Khat may alias K and Vhat may alias V (reconstruction in place); nothing else may alias.
+ * Khat may coincide with K and Vhat with V (reconstruction in place: the same address); any other
+ * overlap between an output (or the workspace) and an input or another output is refused with
+ * AQUAKV_EINVAL before anything is launched (the same holds for the decode call and the halves below).
  * tokens == 0 is a no-op.
  */
 int aquakv_encode_layer(const aquakv_layer* layer, int64_t tokens,
@@ -221,16 +227,21 @@ int aquakv_decode_values(const aquakv_layer* layer, int64_t tokens, const uint8_
  * Khat_out (nullable, dtype, [batch*seq_len, H, g]) also receives the keys.
  * q_heads must be a multiple of H with q_heads / H <= 8.
  *
- * Folded form.  A score is linear in the key, so with a key predictor (Sect. 3.2)
+ * Always the definition above (the storage-rounded key is scored); `workspace`: the fp32 prediction part of
+ * aquakv_workspace_bytes() for layers that do not run fused (fp32), unused otherwise.
+ *
+ * aquakv_decode_attn_scores_folded -- the same scores in the folded form, a call of its own so that the
+ * arithmetic a caller gets never depends on the size of a workspace.  A score is linear in the key, so with
+ * a key predictor (Sect. 3.2)
  *   q . Khat[t] = Khat_prev[t] . (W_h^T q) + q . b_h + sigma[t] * (R q) . C[codes[t]],
  * R q the rotated query: one 1024-long dot product per token and query head instead of the
- * predictor product, bound by reading Khat_prev and the codes once.  The call takes this form
- * when Khat_out is NULL and `workspace` holds at least aquakv_scores_workspace_bytes() bytes
- * (a nonzero value says the form exists for this layer and shape: bf16, 8 kv heads, key
- * predictor with 1024 inputs, q_heads <= 64: one pass over the cache per 4 query heads of a kv
- * head, so two passes above 32 query heads); otherwise it recomputes the prediction.  The
- * folded scores use the unrounded keys and agree with the definition above to the storage
- * precision of Khat (2^-9 relative per term in bf16).
+ * predictor product, bound by reading Khat_prev and the codes once.  The keys are never formed, so there
+ * is no Khat_out, and the scores are those of the UNROUNDED keys: they agree with the definition to the
+ * storage precision of Khat (2^-9 relative per term in bf16).  Built for bf16 layers with 8 kv heads, a key
+ * predictor with 1024 inputs, rotation groups of one head and q_heads <= 64 (one pass over the cache per 4
+ * query heads of a kv head, so two passes above 32 query heads); AQUAKV_EUNSUPPORTED otherwise, and
+ * aquakv_scores_workspace_bytes() is then 0.  `workspace`: at least aquakv_scores_workspace_bytes() bytes
+ * (the folded queries of this call; AQUAKV_EWORKSPACE if smaller).
  */
 size_t aquakv_scores_workspace_bytes(const aquakv_layer* layer, int32_t batch, int32_t q_heads);
 int aquakv_decode_attn_scores(const aquakv_layer* layer, int32_t batch, int32_t seq_len, int32_t q_heads,
@@ -238,6 +249,10 @@ int aquakv_decode_attn_scores(const aquakv_layer* layer, int32_t batch, int32_t 
                               const void* Khat_prev, const void* q, float score_scale,
                               float* scores, void* Khat_out,
                               void* workspace, size_t workspace_bytes, void* stream);
+int aquakv_decode_attn_scores_folded(const aquakv_layer* layer, int32_t batch, int32_t seq_len, int32_t q_heads,
+                                     const uint8_t* k_codes, const uint16_t* k_scales,
+                                     const void* Khat_prev, const void* q, float score_scale,
+                                     float* scores, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * aquakv_decode_attn_scores_rope -- the same call for caches that hold the keys from BEFORE the

@@ -75,9 +75,14 @@ int check_layer(const aquakv_layer* L) {
   }
   if (L->d_in_k && L->w_k == nullptr) return fail(AQUAKV_ENULL, "w_k is NULL but d_in_k=%d", L->d_in_k);
   if (L->d_in_v && L->w_v == nullptr) return fail(AQUAKV_ENULL, "w_v is NULL but d_in_v=%d", L->d_in_v);
-  const void* ptrs[] = {L->codebook, L->signs_k, L->signs_v, L->w_k, L->b_k, L->w_v, L->b_v, L->search_table};
-  for (const void* p : ptrs)
+  const void* used[] = {L->w_k, L->b_k, L->w_v, L->b_v};
+  for (const void* p : used)
     if (p != nullptr && misaligned(p)) return fail(AQUAKV_EALIGN, "a pointer in aquakv_layer is not 16-byte aligned");
+  if (!is_rtn(L)) {      // ignored (never read, whatever they hold) by the round-to-nearest backbone
+    const void* grid[] = {L->codebook, L->signs_k, L->signs_v, L->search_table};
+    for (const void* p : grid)
+      if (p != nullptr && misaligned(p)) return fail(AQUAKV_EALIGN, "a pointer in aquakv_layer is not 16-byte aligned");
+  }
   return AQUAKV_OK;
 }
 
@@ -105,6 +110,29 @@ int check_scales(const aquakv_layer* L, const void* p, const char* name, bool re
   if (p == nullptr) return required ? fail(AQUAKV_ENULL, "%s is NULL", name) : AQUAKV_OK;
   const unsigned need = is_rtn(L) ? 4u : 2u;
   if (reinterpret_cast<uintptr_t>(p) & (need - 1u)) return fail(AQUAKV_EALIGN, "%s is not %u-byte aligned", name, need);
+  return AQUAKV_OK;
+}
+
+// Byte ranges [p, p + n) of the buffers of one call.  The kernels of a call read whole rows of their inputs
+// while other workgroups write outputs for the same rows, so an output that overlaps an input it may not
+// alias (or another output, or the workspace) is a race; it is refused before anything is launched.
+struct Range { const void* p; size_t n; const char* name; };
+inline bool overlap(const Range& a, const Range& b) {
+  if (a.p == nullptr || b.p == nullptr || a.n == 0 || b.n == 0) return false;
+  const uintptr_t a0 = reinterpret_cast<uintptr_t>(a.p), b0 = reinterpret_cast<uintptr_t>(b.p);
+  return a0 < b0 + b.n && b0 < a0 + a.n;
+}
+// every output against every input and against the other outputs; `inplace` (nullable, one entry per output)
+// names the one input an output may coincide with exactly (reconstruction in place)
+int check_no_alias(const Range* outs, int n_out, const Range* ins, int n_in, const void* const* inplace = nullptr) {
+  for (int i = 0; i < n_out; ++i) {
+    for (int j = 0; j < n_in; ++j) {
+      if (inplace != nullptr && inplace[i] != nullptr && inplace[i] == ins[j].p && outs[i].p == ins[j].p) continue;
+      if (overlap(outs[i], ins[j])) return fail(AQUAKV_EINVAL, "%s overlaps %s", outs[i].name, ins[j].name);
+    }
+    for (int j = i + 1; j < n_out; ++j)
+      if (overlap(outs[i], outs[j])) return fail(AQUAKV_EINVAL, "%s overlaps %s", outs[i].name, outs[j].name);
+  }
   return AQUAKV_OK;
 }
 
@@ -360,10 +388,21 @@ int aquakv_encode_layer(const aquakv_layer* L, int64_t tokens, const void* K, co
   if (workspace_bytes < pl.p_bytes + pl.khat_bytes)
     return fail(AQUAKV_EWORKSPACE, "workspace %zu B < required %zu B", workspace_bytes, pl.p_bytes + pl.khat_bytes);
 
+  const size_t row = (size_t)pl.D * pl.eb;
+  {
+    const size_t t = (size_t)tokens, crow = pl.code_row, srow = scale_row_bytes(L);
+    const Range outs[] = {{Khat, t * row, "Khat"}, {Vhat, t * row, "Vhat"}, {k_codes, t * crow, "k_codes"},
+                          {v_codes, t * crow, "v_codes"}, {k_scales, t * srow, "k_scales"}, {v_scales, t * srow, "v_scales"},
+                          {workspace, pl.p_bytes + pl.khat_bytes, "workspace"}};
+    const Range ins[] = {{K, t * row, "K"}, {V, t * row, "V"}, {Khat_prev, t * L->d_in_k * pl.eb, "Khat_prev"},
+                         {Vhat_prev, has_v ? t * (L->d_in_v - pl.D) * pl.eb : 0, "Vhat_prev"}};
+    const void* const inplace[] = {K, V, nullptr, nullptr, nullptr, nullptr, nullptr};
+    CHECK(check_no_alias(outs, 7, ins, 4, inplace));
+  }
+
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   float* Pbuf = static_cast<float*>(workspace);
   void* khat_tmp = static_cast<unsigned char*>(workspace) + pl.p_bytes;
-  const size_t row = (size_t)pl.D * pl.eb;
 
   for (int64_t r0 = 0; r0 < tokens; r0 += pl.chunk) {
     const int64_t n = tokens - r0 < pl.chunk ? tokens - r0 : pl.chunk;
@@ -395,6 +434,15 @@ int aquakv_decode_layer(const aquakv_layer* L, int64_t tokens, const uint8_t* k_
   if (workspace_bytes < pl.p_bytes + pl.khat_bytes)
     return fail(AQUAKV_EWORKSPACE, "workspace %zu B < required %zu B", workspace_bytes, pl.p_bytes + pl.khat_bytes);
 
+  {
+    const size_t t = (size_t)tokens, row = (size_t)pl.D * pl.eb, crow = pl.code_row, srow = scale_row_bytes(L);
+    const Range outs[] = {{Khat, t * row, "Khat"}, {Vhat, t * row, "Vhat"}, {workspace, pl.p_bytes, "workspace"}};
+    const Range ins[] = {{Khat_prev, t * L->d_in_k * pl.eb, "Khat_prev"},
+                         {Vhat_prev, has_v ? t * (L->d_in_v - pl.D) * pl.eb : 0, "Vhat_prev"},
+                         {k_codes, t * crow, "k_codes"}, {v_codes, want_v ? t * crow : 0, "v_codes"},
+                         {k_scales, t * srow, "k_scales"}, {v_scales, want_v ? t * srow : 0, "v_scales"}};
+    CHECK(check_no_alias(outs, 3, ins, 6));
+  }
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   float* Pbuf = static_cast<float*>(workspace);
 
@@ -425,6 +473,14 @@ int aquakv_encode_keys(const aquakv_layer* L, int64_t tokens, const void* K, con
     if (workspace_bytes < pl.p_bytes) return fail(AQUAKV_EWORKSPACE, "workspace %zu B < required %zu B", workspace_bytes, pl.p_bytes);
   }
   const size_t row = (size_t)pl.D * pl.eb;
+  {
+    const size_t t = (size_t)tokens;
+    const Range outs[] = {{Khat, t * row, "Khat"}, {k_codes, t * pl.code_row, "k_codes"},
+                          {k_scales, t * scale_row_bytes(L), "k_scales"}, {workspace, pl.p_bytes, "workspace"}};
+    const Range ins[] = {{K, t * row, "K"}, {Khat_prev, t * L->d_in_k * pl.eb, "Khat_prev"}};
+    const void* const inplace[] = {K, nullptr, nullptr, nullptr};
+    CHECK(check_no_alias(outs, 4, ins, 2, inplace));
+  }
   for (int64_t r0 = 0; r0 < tokens; r0 += pl.chunk) {
     const int64_t n = tokens - r0 < pl.chunk ? tokens - r0 : pl.chunk;
     CHECK(encode_keys_chunk(L, pl, r0, n, K, Khat_prev, k_codes, k_scales, at(Khat, r0, row), static_cast<float*>(workspace),
@@ -452,6 +508,15 @@ int aquakv_encode_values(const aquakv_layer* L, int64_t tokens, const void* V, c
     if (workspace_bytes < pl.p_bytes) return fail(AQUAKV_EWORKSPACE, "workspace %zu B < required %zu B", workspace_bytes, pl.p_bytes);
   }
   const size_t row = (size_t)pl.D * pl.eb;
+  {
+    const size_t t = (size_t)tokens;
+    const Range outs[] = {{Vhat, t * row, "Vhat"}, {v_codes, t * pl.code_row, "v_codes"},
+                          {v_scales, t * scale_row_bytes(L), "v_scales"}, {workspace, pl.p_bytes, "workspace"}};
+    const Range ins[] = {{V, t * row, "V"}, {Vhat_prev, has_v ? t * (L->d_in_v - pl.D) * pl.eb : 0, "Vhat_prev"},
+                         {Khat, has_v ? t * row : 0, "Khat"}};
+    const void* const inplace[] = {V, nullptr, nullptr, nullptr};
+    CHECK(check_no_alias(outs, 4, ins, 3, inplace));
+  }
   for (int64_t r0 = 0; r0 < tokens; r0 += pl.chunk) {
     const int64_t n = tokens - r0 < pl.chunk ? tokens - r0 : pl.chunk;
     CHECK(encode_values_chunk(L, pl, r0, n, V, Vhat_prev, at(Khat, r0, row), v_codes, v_scales, Vhat,
@@ -476,6 +541,13 @@ int aquakv_decode_values(const aquakv_layer* L, int64_t tokens, const uint8_t* v
   if (pl.p_bytes != 0) {
     CHECK(check_ptr(workspace, "workspace", true));
     if (workspace_bytes < pl.p_bytes) return fail(AQUAKV_EWORKSPACE, "workspace %zu B < required %zu B", workspace_bytes, pl.p_bytes);
+  }
+  {
+    const size_t t = (size_t)tokens, row = (size_t)pl.D * pl.eb;
+    const Range outs[] = {{Vhat, t * row, "Vhat"}, {workspace, pl.p_bytes, "workspace"}};
+    const Range ins[] = {{Vhat_prev, has_v ? t * (L->d_in_v - pl.D) * pl.eb : 0, "Vhat_prev"}, {Khat, has_v ? t * row : 0, "Khat"},
+                         {v_codes, t * pl.code_row, "v_codes"}, {v_scales, t * scale_row_bytes(L), "v_scales"}};
+    CHECK(check_no_alias(outs, 2, ins, 4));
   }
   for (int64_t r0 = 0; r0 < tokens; r0 += pl.chunk) {
     const int64_t n = tokens - r0 < pl.chunk ? tokens - r0 : pl.chunk;
@@ -653,11 +725,13 @@ size_t aquakv_scores_workspace_bytes(const aquakv_layer* L, int32_t batch, int32
 }  // extern "C"
 
 namespace {
-// shared body of the two scoring entry points; rope_cos / rope_sin both NULL: no rotary embedding
+enum ScoresForm { kFormDefinition = 0, kFormFolded = 1 };
+
+// shared body of the scoring entry points; rope_cos / rope_sin both NULL: no rotary embedding
 int decode_attn_scores(const aquakv_layer* L, int32_t batch, int32_t seq_len, int32_t q_heads, const uint8_t* k_codes,
                        const uint16_t* k_scales, const void* Khat_prev, const void* q, const float* rope_cos,
                        const float* rope_sin, float score_scale, float* scores, void* Khat_out, void* workspace,
-                       size_t workspace_bytes, void* stream_) {
+                       size_t workspace_bytes, void* stream_, int form) {
   CHECK(check_layer(L));
   if (batch < 0 || seq_len < 0) return fail(AQUAKV_EINVAL, "batch=%d seq_len=%d", batch, seq_len);
   if (q_heads < 1 || q_heads % L->kv_heads || q_heads / L->kv_heads > 8)
@@ -670,18 +744,23 @@ int decode_attn_scores(const aquakv_layer* L, int32_t batch, int32_t seq_len, in
   CHECK(check_ptr(scores, "scores", true));
   CHECK(check_ptr(Khat_out, "Khat_out", false));
   const int64_t tokens = (int64_t)batch * seq_len;
-  if (tokens == 0) return AQUAKV_OK;
-  const Plan pl = make_plan(L, tokens);
-  if (has_k && pl.fused && Khat_out == nullptr && rope_cos == nullptr && workspace != nullptr &&
-      aquakv::folded_scores_supported(L->kv_heads, L->d_in_k, q_heads) &&
-      workspace_bytes >= aquakv::folded_scores_workspace_bytes(batch, q_heads)) {
+  const Plan pl = make_plan(L, tokens > 0 ? tokens : 1);
+  if (form == kFormFolded) {
+    if (!(has_k && pl.fused && aquakv::folded_scores_supported(L->kv_heads, L->d_in_k, q_heads)))
+      return fail(AQUAKV_EUNSUPPORTED, "the folded form is built for bf16 layers with 8 kv heads, a key predictor with 1024 "
+                                       "inputs, rotation groups of one head and at most 64 query heads");
+    if (tokens == 0) return AQUAKV_OK;
     // predictor folded into the query: Khat_prev and the codes are read once, nothing is recomputed
     CHECK(check_ptr(workspace, "workspace", true));
-    HIP_TRY(aquakv::launch_folded_scores(quantizer_id(L), Khat_prev, L->w_k, L->b_k, L->signs_k, L->codebook, k_codes,
-                                         k_scales, q, score_scale, scores, workspace, batch, seq_len, q_heads,
-                                         static_cast<hipStream_t>(stream_)));
+    const size_t need = aquakv::folded_scores_workspace_bytes(batch, q_heads);
+    if (workspace_bytes < need) return fail(AQUAKV_EWORKSPACE, "workspace %zu B < required %zu B", workspace_bytes, need);
+    // the round-to-nearest backbone has neither rotation nor grid: whatever the layer holds there is not passed on
+    HIP_TRY(aquakv::launch_folded_scores(quantizer_id(L), Khat_prev, L->w_k, L->b_k, is_rtn(L) ? nullptr : L->signs_k,
+                                         is_rtn(L) ? nullptr : L->codebook, k_codes, k_scales, q, score_scale, scores,
+                                         workspace, batch, seq_len, q_heads, static_cast<hipStream_t>(stream_)));
     return AQUAKV_OK;
   }
+  if (tokens == 0) return AQUAKV_OK;
   if (has_k && pl.fused_dec) {
     // one fused launch over all rows: prediction, inverse quantizer and dot products
     HIP_TRY(aquakv::launch_fused_scores(quantizer_id(L), Khat_prev, L->d_in_k, L->w_k, L->b_k, L->signs_k, L->codebook,
@@ -719,7 +798,15 @@ int aquakv_decode_attn_scores(const aquakv_layer* L, int32_t batch, int32_t seq_
                               float score_scale, float* scores, void* Khat_out, void* workspace,
                               size_t workspace_bytes, void* stream_) {
   return decode_attn_scores(L, batch, seq_len, q_heads, k_codes, k_scales, Khat_prev, q, nullptr, nullptr, score_scale,
-                            scores, Khat_out, workspace, workspace_bytes, stream_);
+                            scores, Khat_out, workspace, workspace_bytes, stream_, kFormDefinition);
+}
+
+int aquakv_decode_attn_scores_folded(const aquakv_layer* L, int32_t batch, int32_t seq_len, int32_t q_heads,
+                                     const uint8_t* k_codes, const uint16_t* k_scales, const void* Khat_prev,
+                                     const void* q, float score_scale, float* scores, void* workspace,
+                                     size_t workspace_bytes, void* stream_) {
+  return decode_attn_scores(L, batch, seq_len, q_heads, k_codes, k_scales, Khat_prev, q, nullptr, nullptr, score_scale,
+                            scores, nullptr, workspace, workspace_bytes, stream_, kFormFolded);
 }
 
 int aquakv_decode_attn_scores_rope(const aquakv_layer* L, int32_t batch, int32_t seq_len, int32_t q_heads,
@@ -730,7 +817,7 @@ int aquakv_decode_attn_scores_rope(const aquakv_layer* L, int32_t batch, int32_t
   CHECK(check_ptr(rope_cos, "rope_cos", true));
   CHECK(check_ptr(rope_sin, "rope_sin", true));
   return decode_attn_scores(L, batch, seq_len, q_heads, k_codes, k_scales, Khat_prev, q, rope_cos, rope_sin, score_scale,
-                            scores, Khat_out, workspace, workspace_bytes, stream_);
+                            scores, Khat_out, workspace, workspace_bytes, stream_, kFormDefinition);
 }
 
 }  // extern "C"

@@ -40,6 +40,7 @@ constexpr int kUBytesPerBatch = 8 * 2 * 8 * kUFragBytes;      // [wave][high, lo
 
 // workspace layout per batch entry: u operands, rotated queries [32][128] fp32, q . b [32] fp32
 constexpr size_t kFoldBytesPerBatch = (size_t)kUBytesPerBatch + kFoldQ * 128 * 4 + kFoldQ * 4;
+static_assert(kFoldBytesPerBatch == kFoldedBytesPerBatch, "the size the C-ABI layer plans with");
 
 // ------------------------------------------------------------------ query folding
 // grid = batch * kv_heads * 8, 256 threads: block (b, h, cc) owns input channels 128 cc ... + 127 for the

@@ -83,6 +83,9 @@ hipError_t launch_softmax_rows(const float* scores, float* probs, int64_t rows, 
 // Scores with the key predictor folded into the query (bf16, 8 kv heads, 1024 predictor inputs,
 // q_heads <= 64): reads Khat_prev and the codes once per 4 query heads of a kv head (one pass up to 32 query
 // heads, two up to 64).  `workspace`: folded_scores_workspace_bytes(batch, q_heads).
+// bytes of folded query operands per batch entry and pass: u as bf16 high / low MFMA operands (8 waves x 2 x 8 k
+// steps x 1 KiB), the rotated queries [32][128] fp32, q . b [32] fp32
+constexpr size_t kFoldedBytesPerBatch = (size_t)8 * 2 * 8 * 1024 + 32 * 128 * 4 + 32 * 4;
 bool folded_scores_supported(int kv_heads, int d_in_k, int q_heads);
 size_t folded_scores_workspace_bytes(int batch, int q_heads);
 hipError_t launch_folded_scores(int n_codewords, const void* Khat_prev, const void* W, const float* bias,

@@ -109,17 +109,6 @@ def random_orthogonal(d: int, seed: int, device="cpu", dtype=torch.float64) -> t
     return q.to(device=device, dtype=dtype)
 
 
-def ridge_fit(X: torch.Tensor, Y: torch.Tensor, rate: float = 1e-3) -> torch.Tensor:
-    """Closed-form least squares with a small ridge: returns W [d_out, d_in] with
-    Y ~ X @ W.T.  lambda = rate * trace(X^T X) / d_in (Appendix B's regularizer rate)."""
-    X = X.double()
-    Y = Y.double()
-    G = X.T @ X
-    lam = rate * torch.trace(G) / X.shape[1]
-    W = torch.linalg.solve(G + lam * torch.eye(X.shape[1], dtype=X.dtype, device=X.device), X.T @ Y)
-    return W.T.contiguous()
-
-
 # ---------------------------------------------------------------- KV streams
 class KVStream:
     """Generates (K_l, V_l) layer by layer on `device`, never holding more than

@@ -265,3 +265,87 @@ def test_fit_predictor_validates_its_arguments():
     assert call(Y=FAKE + 8) == B.AQUAKV_EALIGN
     assert status_of(lambda: B.aquakv_fit_predictor(*ok.values(), (FAKE, 100))) == B.AQUAKV_EWORKSPACE
     assert status_of(lambda: B.aquakv_fit_predictor(*{**ok, "x1": None, "d1": 0}.values(), None)) == B.AQUAKV_ENULL   # x1 optional, workspace not
+
+
+def test_overlapping_buffers_are_refused_before_any_launch():
+    """Aliasing contract of the layer calls: an output may coincide with the tensor it reconstructs (Khat with K,
+    Vhat with V); any other overlap of an output or the workspace with an input or another output is a race
+    between workgroups and is refused (every case here is one, so nothing is ever launched)."""
+    L = layer()
+    T = 300
+    row, crow, srow = 1024 * 2, 8 * 32, 8 * 2
+    base = 0x10000000
+    names = ["K", "V", "Khat_prev", "Vhat_prev", "k_codes", "k_scales", "v_codes", "v_scales", "Khat", "Vhat"]
+    addr = {n: base + i * 0x1000000 for i, n in enumerate(names)}          # 16 MiB apart: disjoint for 300 rows
+    ws = (base + 0x20000000, B.aquakv_workspace_bytes(L, T))
+
+    def enc(ws_=ws, **kw):
+        a = dict(addr)
+        a.update(kw)
+        with pytest.raises(B.AquaKVError) as e:
+            B.aquakv_encode_layer(L, T, *[a[n] for n in names], ws_)
+        assert e.value.status == B.AQUAKV_EINVAL, str(e.value)
+        return str(e.value)
+
+    assert "Vhat overlaps Vhat_prev" in enc(Vhat=addr["Vhat_prev"])
+    assert "Khat overlaps Khat_prev" in enc(Khat=addr["Khat_prev"])
+    assert "Khat overlaps Vhat" in enc(Vhat=addr["Khat"])
+    assert "Khat overlaps K" in enc(Khat=addr["K"] + row)                 # shifted by one row: not "in place"
+    assert "Vhat overlaps K" in enc(Vhat=addr["K"])                       # in place is for the tensor's own input only
+    assert "Khat overlaps V" in enc(Khat=addr["V"] + (T - 1) * row)       # last row of V
+    assert "k_codes overlaps v_codes" in enc(v_codes=addr["k_codes"] + (T - 1) * crow)
+    assert "k_scales overlaps" in enc(k_scales=addr["K"] + 16)
+    assert "workspace overlaps" in enc(ws_=(addr["Vhat_prev"] + 64, ws[1]))
+    # reconstruction in place is allowed: the error below is about the codes, not about Khat / Vhat
+    msg = enc(Khat=addr["K"], Vhat=addr["V"], v_codes=addr["k_codes"])
+    assert "k_codes overlaps v_codes" in msg
+    # just past the end is not an overlap for the buffer it follows: only the next check trips
+    msg = enc(Khat=addr["K"] + T * row, Vhat=addr["Khat_prev"])
+    assert "Vhat overlaps Khat_prev" in msg
+
+    def st(fn, *a):
+        with pytest.raises(B.AquaKVError) as e:
+            fn(*a)
+        assert e.value.status == B.AQUAKV_EINVAL, str(e.value)
+        return str(e.value)
+
+    A = addr
+    assert "Khat overlaps Khat_prev" in st(B.aquakv_decode_layer, L, T, A["k_codes"], A["k_scales"], A["v_codes"], A["v_scales"],
+                                           A["Khat_prev"], A["Vhat_prev"], A["Khat_prev"], A["Vhat"], ws)
+    assert "Vhat overlaps v_codes" in st(B.aquakv_decode_layer, L, T, A["k_codes"], A["k_scales"], A["v_codes"], A["v_scales"],
+                                         A["Khat_prev"], A["Vhat_prev"], A["Khat"], A["v_codes"], ws)
+    assert "Khat overlaps Khat_prev" in st(B.aquakv_encode_keys, L, T, A["K"], A["Khat_prev"], A["k_codes"], A["k_scales"],
+                                           A["Khat_prev"], ws)
+    assert "Vhat overlaps Khat" in st(B.aquakv_encode_values, L, T, A["V"], A["Vhat_prev"], A["Khat"], A["v_codes"], A["v_scales"],
+                                      A["Khat"], ws)
+    assert "Vhat overlaps Vhat_prev" in st(B.aquakv_decode_values, L, T, A["v_codes"], A["v_scales"], A["Vhat_prev"], A["Khat"],
+                                           A["Vhat_prev"], ws)
+    _ = srow
+
+
+def test_folded_scoring_calls_validate_their_arguments():
+    """The folded form is a call of its own: EUNSUPPORTED where it is not built, its own workspace size, """
+    L = layer()
+    sc = [FAKE, FAKE, FAKE, FAKE, 1.0, FAKE]        # k_codes k_scales Khat_prev q scale scores
+    need = B.aquakv_scores_workspace_bytes(L, 2, 32)
+    f = B.aquakv_decode_attn_scores_folded
+    assert status_of(f, L, 2, 16, 32, *sc, (FAKE, need - 1)) == B.AQUAKV_EWORKSPACE
+    assert status_of(f, L, 2, 16, 32, *sc, None) == B.AQUAKV_ENULL
+    assert status_of(f, L, 2, 16, 12, *sc, (FAKE, need)) == B.AQUAKV_EINVAL
+    assert status_of(f, layer(dtype=B.AQUAKV_FP32), 2, 16, 32, *sc, (FAKE, need)) == B.AQUAKV_EUNSUPPORTED
+    assert status_of(f, layer(rht_group=1024), 2, 16, 32, *sc, (FAKE, need)) == B.AQUAKV_EUNSUPPORTED
+    assert status_of(f, layer(kv_heads=4, d_in_k=512, d_in_v=1024), 2, 16, 32, *sc, (FAKE, need)) == B.AQUAKV_EUNSUPPORTED
+    L0 = layer(d_in_k=0, d_in_v=0, w_k=None, w_v=None)
+    assert status_of(f, L0, 2, 16, 32, FAKE, FAKE, None, FAKE, 1.0, FAKE, (FAKE, need)) == B.AQUAKV_EUNSUPPORTED
+    bad = list(sc)
+    bad[2] = None
+    assert status_of(f, L, 2, 16, 32, *bad, (FAKE, need)) == B.AQUAKV_ENULL          # Khat_prev
+    f(L, 0, 16, 32, *sc, None)                                                      # no tokens: no-op
+
+
+def test_round_to_nearest_backbone_ignores_grid_pointers():
+    """vq_dim = 1 reads neither grid nor signs nor table: whatever the struct holds there is not even checked for alignment."""
+    L = layer(vq_dim=1, n_codewords=4, codebook=FAKE + 4, signs_k=FAKE + 1, signs_v=FAKE + 2, search_table=FAKE + 8)
+    assert B.aquakv_workspace_bytes(L, 300) == 300 * 1024 * 2
+    B.aquakv_encode_layer(L, 0, *ENC_OK, None)
+    assert status_of(B.aquakv_encode_layer, layer(vq_dim=1, n_codewords=4, w_k=FAKE + 4), 8, *ENC_OK, (FAKE, 1 << 30)) == B.AQUAKV_EALIGN

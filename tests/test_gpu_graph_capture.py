@@ -76,8 +76,10 @@ def test_layer_sweeps_replay_from_a_graph(dtype, rtn_bits, T, rht_group):
             B.aquakv_decode_layer(lay, T, kc, ks, vc, vs, Kp, Vp, b.dec[l][0], b.dec[l][1], b.ws)
             # layers with a folded form take it (their own workspace); the others recompute the prediction
             folded = B.aquakv_scores_workspace_bytes(lay, 1, QH) > 0
-            B.aquakv_decode_attn_scores(lay, 1, T, QH, kc, ks, Kp, b.q, 0.125, b.scores[l], None,
-                                        b.ws_scores[l] if folded else b.ws)
+            if folded:
+                B.aquakv_decode_attn_scores_folded(lay, 1, T, QH, kc, ks, Kp, b.q, 0.125, b.scores[l], b.ws_scores[l])
+            else:
+                B.aquakv_decode_attn_scores(lay, 1, T, QH, kc, ks, Kp, b.q, 0.125, b.scores[l], None, b.ws)
             # value side of attention: soft-max, then the value half of decode again with the weighted sums
             # (in the fused kernel's epilogue when T is a multiple of 256, from the decoded values otherwise)
             B.aquakv_softmax(QH, T, b.scores[l], b.probs[l])

@@ -168,15 +168,30 @@ def test_rtn_layer_stack(B, dtype, bits, T):
         # without the by-product: layers with a key predictor take the folded form in bf16 (predictor folded into the
         # query, code term step * sum q (code - zero) per group), everything else recomputes as above
         s2 = torch.full_like(scores, float("nan"))
-        B.aquakv_decode_attn_scores(lg, 1, T, QH, kc, km, Kp, q, 0.25, s2, None, ws)
-        torch.cuda.synchronize()
         folded = l > 0 and dtype == "bf16"
         assert (B.aquakv_scores_workspace_bytes(lg, 1, QH) > 0) == folded
+        if folded:
+            B.aquakv_decode_attn_scores_folded(lg, 1, T, QH, kc, km, Kp, q, 0.25, s2, lg.alloc_scores_workspace(1, QH))
+        else:
+            B.aquakv_decode_attn_scores(lg, 1, T, QH, kc, km, Kp, q, 0.25, s2, None, ws)
+        torch.cuda.synchronize()
         if folded:
             worst = float(np.max(np.abs(U.np64(s2)[0] - want) / (mag + 1e-30)))
             print(f"   layer {l}: folded scores, worst error / (sum|q||k|) = {worst:.3g}", flush=True)
             assert np.all(np.abs(U.np64(s2)[0] - want) <= U.RTOL["bf16"] * mag + 1e-30), worst
             assert not torch.equal(s2, scores)                 # (it really is another path)
+            # this backbone has neither rotation nor grid: whatever a C caller left in those fields of the struct
+            # (here: a sign vector of -1s, misaligned grid and table pointers) is ignored, also by the folded form
+            junk = torch.full((2048,), -1, dtype=torch.int8, device="cuda")
+            c2 = B.aquakv_layer.from_buffer_copy(lg.c)
+            c2.signs_k, c2.signs_v = junk.data_ptr(), junk.data_ptr() + 1024
+            c2.codebook, c2.search_table = junk.data_ptr() + 4, junk.data_ptr() + 8
+            s3 = torch.full_like(scores, float("nan"))
+            B.aquakv_decode_attn_scores_folded(c2, 1, T, QH, kc, km, Kp, q, 0.25, s3, lg.alloc_scores_workspace(1, QH))
+            s4 = torch.full_like(scores, float("nan"))
+            B.aquakv_decode_attn_scores(c2, 1, T, QH, kc, km, Kp, q, 0.25, s4, None, ws)
+            torch.cuda.synchronize()
+            assert torch.equal(s3, s2) and torch.equal(s4, scores)
         else:
             assert torch.equal(s2, scores)
         outs.append((kc, km, vc, vm))
