@@ -15,7 +15,7 @@ function cites the passage of the AQUA-KV paper (arxiv 2501.19392) it follows:
     f_value (previous layer's reconstructed values, then this layer's
     reconstructed keys).
   * Appendix, Alg. "encode" and Alg. "decode": order of the steps per layer.
-  * Sect. 3.1 footnote: Q is scale independent "due to the use of scales".
+  * Sect. 3.1 footnote: Q does not depend on the scale of its input, because every group is normalised.
   * Sect. 4.1 "Backbone quantization": the second backbone, uniform round-to-nearest
     with per-group normalisation (groups of 64 channels of a token), rtn_quantize.
 
@@ -61,7 +61,7 @@ Kronecker recursion, fast-butterfly agreement, inverse round trip, exact
 power-of-two scale covariance (the footnote of Sect. 3.1), zero residual round
 trip, brute-force nearest codeword against the expanded inner-product form and
 the Voronoi self-map, the grid's mean squared error on N(0,1) samples against
-the paper's "2-bit explains about 0.89 of the variance" and the textbook
+the paper's figure for a 2-bit quantizer (about 0.89 of the variance explained) and the textbook
 Lloyd-Max / rate-distortion bounds, bit accounting 2 + 16/1024 = 2.02 and the
 predictor storage sizes of Table 1, bf16 / fp16 rounding against torch's
 conversions, the predictor against identity / zero weights, closed loop

@@ -5,14 +5,14 @@ package).
 
 What it follows (AQUA-KV paper, arxiv 2501.19392):
   * Sect. 3.2: the predictors are linear regressions, trained one layer at a time, each set on the previous layer's
-    *reconstructed* keys / values "reflecting the way these predictors are used during inference".
+    *reconstructed* keys / values, because reconstructions are what the predictors will see at inference time.
   * Alg. "Calibration": per layer, f_key = argmin || f(K_old) - K ||^2; K_rec = f_key(K_old) + Q^-1(Q(K - f_key(K_old)));
     f_value = argmin || f([V_old; K_rec]) - V ||^2; V_rec likewise; then (K_old, V_old) <- (K_rec, V_rec).
 
 Readings taken where the paper is silent or at odds with itself:
   * The least-squares problem is solved through its normal equations with a ridge term,
     W = (X^T X + lambda I)^-1 X^T Y, lambda = rate * trace(X^T X) / d_in; rate = 0 is the plain argmin of the
-    algorithm (needs X of full column rank).  The appendix quotes a "regularizer rate" of 1e-3 for its linear
+    algorithm (needs X of full column rank).  The appendix gives a regulariser rate of 1e-3 for its linear
     probes without saying relative to what; relative to the mean diagonal of X^T X makes it scale free.
   * The fit has an optional intercept (centred regression; Sect. 4.1 lists a bias-only predictor among its
     ablations, so the predictors carry a bias).  The layer-by-layer procedure here fits none: the synthetic
@@ -20,7 +20,7 @@ Readings taken where the paper is silent or at odds with itself:
   * The weights are rounded to the storage dtype before they are used to encode the layer: it is the rounded
     predictor that inference runs, so the next layer is fitted on what that predictor reconstructs.
   * The first layer: the algorithm's listing hands its raw K, V to the second layer's fit, the text says the
-    first layer "is compressed as is" and that predictors see reconstructions.  Here the first layer's entry is a
+    first layer goes through the backbone quantizer alone and that predictors see reconstructions.  Here the first layer's entry is a
     Layer without predictors (its reconstruction under that layer's backbone is what the second layer is fitted
     on) or None (kept in 16 bits: the raw tensors, the listing's reading).
 

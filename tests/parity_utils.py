@@ -120,6 +120,79 @@ def compare_quantizer_outputs(residual, signs, codebook, gpu_codes, gpu_scales, 
     return rep
 
 
+@dataclass
+class FreeRunReport:
+    """Free-running comparison (no teacher forcing): every disagreement with the oracle's own sweep, by cause."""
+    groups: int
+    subvectors: int
+    scale_mismatch: int = 0
+    scale_ties: int = 0          # the oracle's fp64 sigma sits on an fp16 rounding boundary
+    scale_from_inputs: int = 0   # the library's own residual has the scale the library stored
+    code_mismatch: int = 0
+    distance_ties: int = 0       # the library's grid point is within TIE_GAP of the oracle's, on the oracle's input
+    scale_tie_codes: int = 0     # the oracle gives the library's code under the library's (tied) scale
+    from_inputs: int = 0         # the gap on the oracle's input is covered by the measured difference of the inputs
+    other: int = 0
+    max_input_diff: float = 0.0  # largest |y_library - y_oracle| (normalised rotated units) over groups with equal scales
+
+    def __str__(self):
+        return (f"groups={self.groups} subvectors={self.subvectors} scale_mismatch={self.scale_mismatch} (boundary ties "
+                f"{self.scale_ties}, from inputs {self.scale_from_inputs}) code_mismatch={self.code_mismatch} (distance ties "
+                f"{self.distance_ties}, scale ties {self.scale_tie_codes}, from inputs {self.from_inputs}) other={self.other} "
+                f"max input difference={self.max_input_diff:.3g}")
+
+
+def classify_free_run(x, p_oracle, p_gpu, signs, codebook, gpu_codes, gpu_scales, n) -> FreeRunReport:
+    """The library's codes and scales against the oracle's OWN sweep for the same raw tensor x [T, G, g].
+
+    The two quantizers did not see the same residual: p_oracle is the prediction the oracle formed from its own
+    earlier reconstructions, p_gpu the one the library formed from its own (fp32 accumulation, possibly other
+    reconstructions upstream).  Every disagreement is put down to a cause, measured on the oracle's own input y_o:
+      distance tie  - gap = d(y_o, C[code_gpu]) - d(y_o, C[code_oracle]) <= TIE_GAP;
+      scale tie     - the group's scales are neighbours in fp16, the oracle's sigma lies within SCALE_TIE_REL of the
+                      rounding boundary, and under the library's scale the oracle picks the library's code;
+      from inputs   - the library minimised over y_g = y_o + dy.  d(y, C_a) - d(y, C_b) is linear in y with
+                      gradient 2 (C_b - C_a), so choosing code_gpu at y_g is consistent iff
+                      gap <= 2 |dy| |C[code_gpu] - C[code_oracle]| (+ TIE_GAP); dy is measured, not assumed;
+      other         - none of these: a real disagreement.  Callers assert it is zero."""
+    x = np.asarray(x, dtype=np.float64)
+    C = np.asarray(codebook, dtype=np.float64)
+    r_o, r_g = x - p_oracle, x - p_gpu
+    idx_o, s16_o, d_o = O.quantize(r_o, signs, codebook)
+    g_s16 = np.ascontiguousarray(gpu_scales).view(np.float16).reshape(s16_o.shape)
+    g_idx = O.unpack_codes(gpu_codes, n)
+    _, s16_own, d_own = O.quantize(r_g, signs, codebook)                      # the library's residual, the oracle's scale rule
+    _, _, d_g = O.quantize(r_g, signs, codebook, sigma16_override=g_s16)      # ... normalised by the scale the library stored
+    rep = FreeRunReport(groups=s16_o.size, subvectors=idx_o.size)
+    bits16 = lambda a: a.view(np.uint16).astype(np.int64)
+    sm = bits16(g_s16) != bits16(s16_o)
+    rep.scale_mismatch = int(sm.sum())
+    s_tie = sm & (fp16_boundary_distance(d_o.sigma) <= SCALE_TIE_REL) & (np.abs(bits16(g_s16) - bits16(s16_o)) == 1)
+    own_ok = (bits16(s16_own) == bits16(g_s16)) | ((fp16_boundary_distance(d_own.sigma) <= SCALE_TIE_REL) &
+                                                   (np.abs(bits16(g_s16) - bits16(s16_own)) == 1))
+    s_in = sm & ~s_tie & own_ok
+    rep.scale_ties, rep.scale_from_inputs = int(s_tie.sum()), int(s_in.sum())
+    rep.other += int((sm & ~s_tie & ~s_in).sum())
+    sub = lambda y: y.reshape(y.shape[:-1] + (y.shape[-1] // 2, 2))
+    yo, yg = sub(d_o.y), sub(d_g.y)
+    cm = g_idx != idx_o
+    rep.code_mismatch = int(cm.sum())
+    gap = ((yo - C[g_idx]) ** 2).sum(-1) - ((yo - C[idx_o]) ** 2).sum(-1)
+    assert gap.min() >= -1e-12                                                 # the oracle's choice is the argmin
+    d_tie = cm & (gap <= TIE_GAP)
+    idx_t, _, _ = O.quantize(r_o, signs, codebook, sigma16_override=np.where(s_tie, g_s16, s16_o))
+    st_codes = cm & ~d_tie & s_tie[..., None] & (idx_t == g_idx)
+    dy = np.sqrt(((yg - yo) ** 2).sum(-1))
+    reach = 2.0 * dy * np.sqrt(((C[g_idx] - C[idx_o]) ** 2).sum(-1)) + TIE_GAP
+    f_in = cm & ~d_tie & ~st_codes & (gap <= reach)
+    rep.distance_ties, rep.scale_tie_codes, rep.from_inputs = int(d_tie.sum()), int(st_codes.sum()), int(f_in.sum())
+    rep.other += int((cm & ~d_tie & ~st_codes & ~f_in).sum())
+    # over the groups whose scales agree (where they differ, y carries the other scale: half an fp16 ulp times |y|)
+    same = ~sm
+    rep.max_input_diff = float(np.abs(yg - yo)[same].max()) if same.any() else 0.0
+    return rep
+
+
 RTN_TIE = 1e-5         # distance of value / step (or -lo / step) to x.5 below which a rounding counts as tied
 
 

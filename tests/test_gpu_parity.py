@@ -271,6 +271,44 @@ def check_layer_against_oracle(B, lo, lg, K, V, g, rows=None):
     return reports
 
 
+def free_run_layers(B, lo_l, lg_l, Ks, Vs, out, rows=None):
+    """The oracle's own sweep over the layers (its reconstructions feeding its next predictions, no teacher forcing)
+    beside the library's, on the token rows `rows` (tokens are independent): [(layer, "k" | "v", FreeRunReport)]."""
+    sel = slice(None) if rows is None else rows
+    reports = []
+    free_run_layers.last_oracle = []
+    Kp = Vp = None
+    for l, (lo, lg) in enumerate(zip(lo_l, lg_l)):
+        g = out[l]
+        T = Ks[l].shape[0]
+        D = lo.kv_heads * lo.head_dim
+        K64, V64 = U.np64(Ks[l][sel]), U.np64(Vs[l][sel])
+        e = O.encode_layer(lo, K64, V64, Kp, Vp)
+        free_run_layers.last_oracle.append(e)
+        shape = (-1, lo.groups_per_token, lo.group)
+        for which, X64, codes, scales, signs in (("k", K64, g["k_codes"], g["k_scales"], lo.signs_k),
+                                                 ("v", V64, g["v_codes"], g["v_scales"], lo.signs_v)):
+            has = (lo.w_k if which == "k" else lo.w_v) is not None
+            if has:
+                # the library's own prediction (same main loop as its fused kernels) and the oracle's from its own sweep
+                P = torch.empty(T, D, dtype=torch.float32, device="cuda")
+                if which == "k":
+                    B.aquakv_predict(lg, B.AQUAKV_KEY, T, g["Kp"], None, P)
+                else:
+                    B.aquakv_predict(lg, B.AQUAKV_VALUE, T, g["Vp"], g["Khat"], P)
+                sync()
+                p_g = U.np64(P[sel]).reshape(shape)
+                p_o = e["P_k" if which == "k" else "P_v"].reshape(shape)
+            else:
+                p_g = p_o = np.zeros(X64.reshape(shape).shape)
+            c = codes[sel].cpu().numpy().reshape(p_g.shape[0], lo.groups_per_token, -1)
+            rep = U.classify_free_run(X64.reshape(shape), p_o, p_g, np.asarray(signs).reshape(lo.groups_per_token, lo.group),
+                                      lo.codebook, c, scales[sel].cpu().numpy(), lo.n_codewords)
+            reports.append((l, which, rep))
+        Kp, Vp = e["Khat"], e["Vhat"]
+    return reports
+
+
 @pytest.mark.parametrize("predictors", ["analytic", "random"])
 def test_tiny_config_fp32_end_to_end(B, predictors):
     """Config 'Tiny' in full: every stage of every layer against the oracle, then the free-running
@@ -282,19 +320,21 @@ def test_tiny_config_fp32_end_to_end(B, predictors):
     for l in range(cfg.layers):
         for rep in check_layer_against_oracle(B, lo_l[l], lg_l[l], Ks[l], Vs[l], out[l]):
             print(f"   layer {l}: {rep}", flush=True)
-    # free-running oracle over both layers
-    Kp = Vp = None
+    # free-running oracle over both layers: every disagreement is put down to a cause, none may be left over
+    reports = free_run_layers(B, lo_l, lg_l, Ks, Vs, out)
+    for l, which, rep in reports:
+        print(f"   free-run layer {l} {which}: {rep}", flush=True)
+        assert rep.other == 0, f"layer {l} {which}: {rep}"
+        # fp32 mode: the inputs of the two quantizers differ by fp32 accumulation (<= 4e-6 sum |x||w| per prediction)
+        # and by the fp32 rounding of the reconstructions upstream; in normalised units that stays below 1e-3
+        # (256 .. 512 products of about 0.04 |x|, residual rms about 0.4 |x|), and disagreements are rare
+        assert rep.max_input_diff <= 1e-3, str(rep)
+        assert rep.code_mismatch <= max(2, rep.subvectors // 2000) and rep.scale_mismatch <= max(1, rep.groups // 200), str(rep)
     for l in range(cfg.layers):
-        e = O.encode_layer(lo_l[l], U.np64(Ks[l]), U.np64(Vs[l]), Kp, Vp)
-        for name, codes_name, scales_name in (("Khat", "k_codes", "k_scales"), ("Vhat", "v_codes", "v_scales")):
-            same_codes = np.array_equal(e[codes_name], out[l][codes_name].cpu().numpy())
-            same_scales = np.array_equal(e[scales_name].view(np.int16), out[l][scales_name].cpu().numpy())
-            print(f"   free-run layer {l} {name}: codes identical={same_codes} scales identical={same_scales}", flush=True)
-            if same_codes and same_scales:
-                U.assert_close_storage(out[l][name], e[name], cfg.dtype, f"free-run {name}")
+        e = free_run_layers.last_oracle[l]
+        for name in ("Khat", "Vhat"):
             rel = np.linalg.norm(U.np64(out[l][name]) - e[name]) / np.linalg.norm(e[name])
             assert rel < 2e-3, rel
-        Kp, Vp = e["Khat"], e["Vhat"]
     # closed loop
     for l in range(cfg.layers):
         g, lg = out[l], lg_l[l]
@@ -527,19 +567,22 @@ def test_attn_scores(B, dtype, n, with_pred):
     rtol = U.RTOL[dtype]
     assert np.all(err <= rtol * 0.125 * mag + 1e-30), float(np.max(err / (0.125 * mag + 1e-30)))
     print(f"   worst score error / (sum|q||k|) = {float(np.max(err / (0.125 * mag + 1e-30))):.3g}", flush=True)
-    # without Khat_out (and without the workspace of the folded form) the scores are the same bits
-    s2 = torch.empty_like(scores)
-    small_ws = torch.empty(16, dtype=torch.uint8, device="cuda") if dtype == "bf16" else lg.alloc_workspace(cfg.tokens)
-    B.aquakv_decode_attn_scores(lg, batch, S, QH, g["k_codes"], g["k_scales"], g["Kp"], q, 0.125, s2, None, small_ws)
-    sync()
-    assert torch.equal(s2, scores)
+    # without Khat_out the scores are the same bits, whatever the size of the workspace (the folded form is a
+    # call of its own: a large workspace must not switch the arithmetic)
+    for ws2 in ((torch.empty(16, dtype=torch.uint8, device="cuda") if dtype == "bf16" else lg.alloc_workspace(cfg.tokens)),
+                torch.empty(max(B.aquakv_scores_workspace_bytes(lg, batch, QH), lg.alloc_workspace(cfg.tokens).numel()) + 4096,
+                            dtype=torch.uint8, device="cuda")):
+        s2 = torch.empty_like(scores)
+        B.aquakv_decode_attn_scores(lg, batch, S, QH, g["k_codes"], g["k_scales"], g["Kp"], q, 0.125, s2, None, ws2)
+        sync()
+        assert torch.equal(s2, scores)
     # folded form (predictor folded into the query): same definition, unrounded keys
     need = B.aquakv_scores_workspace_bytes(lg, batch, QH)
     assert (need > 0) == (dtype == "bf16" and with_pred)
     if need:
         s3 = torch.full_like(scores, float("nan"))
-        B.aquakv_decode_attn_scores(lg, batch, S, QH, g["k_codes"], g["k_scales"], g["Kp"], q, 0.125, s3, None,
-                                    lg.alloc_scores_workspace(batch, QH))
+        B.aquakv_decode_attn_scores_folded(lg, batch, S, QH, g["k_codes"], g["k_scales"], g["Kp"], q, 0.125, s3,
+                                           lg.alloc_scores_workspace(batch, QH))
         sync()
         err3 = np.abs(U.np64(s3) - want)
         assert np.all(err3 <= rtol * 0.125 * mag + 1e-30), float(np.max(err3 / (0.125 * mag + 1e-30)))
@@ -550,7 +593,7 @@ def test_attn_scores(B, dtype, n, with_pred):
 @pytest.mark.parametrize("n,QH,batch,S,bias", [(16, 24, 2, 100, True), (64, 32, 1, 1000, False), (256, 8, 3, 33, True),
                                               (16, 16, 5, 31, False), (16, 64, 2, 70, True), (64, 40, 1, 130, False)])
 def test_folded_scores_against_definition(B, n, QH, batch, S, bias):
-    """aquakv_decode_attn_scores in its folded form against the oracle's plain definition
+    """aquakv_decode_attn_scores_folded against the oracle's plain definition
     (decode the keys, round them to storage, dot with q): query heads per kv head 1..4 (one pass), 5 and 8
     (two passes), all three grids, predictor bias, ragged last tile, sequences shorter than one tile."""
     print(f"case folded scores n={n} QH={QH} batch={batch} S={S} bias={bias}", flush=True)
@@ -564,7 +607,7 @@ def test_folded_scores_against_definition(B, n, QH, batch, S, bias):
     assert need > 0
     ws = torch.empty(need, dtype=torch.uint8, device="cuda")
     scores = torch.full((batch, QH, S), float("nan"), dtype=torch.float32, device="cuda")
-    B.aquakv_decode_attn_scores(lg, batch, S, QH, g["k_codes"], g["k_scales"], g["Kp"], q, 0.25, scores, None, ws)
+    B.aquakv_decode_attn_scores_folded(lg, batch, S, QH, g["k_codes"], g["k_scales"], g["Kp"], q, 0.25, scores, ws)
     sync()
     want = O.attn_scores(lo, batch, S, U.np64(q), g["k_codes"].cpu().numpy(), g["k_scales"].cpu().numpy().view(np.float16),
                          U.np64(g["Kp"]), 0.25)
@@ -578,7 +621,7 @@ def test_folded_scores_against_definition(B, n, QH, batch, S, bias):
     QH2 = 8
     q2 = synth.random_queries(batch, QH2, 128, seed=6, dtype="bf16", device="cuda")
     sc2 = torch.empty(batch, QH2, S, dtype=torch.float32, device="cuda")
-    B.aquakv_decode_attn_scores(lg, batch, S, QH2, g["k_codes"], g["k_scales"], g["Kp"], q2, 0.25, sc2, None, ws)
+    B.aquakv_decode_attn_scores_folded(lg, batch, S, QH2, g["k_codes"], g["k_scales"], g["Kp"], q2, 0.25, sc2, ws)
     sync()
     want2 = O.attn_scores(lo, batch, S, U.np64(q2), g["k_codes"].cpu().numpy(),
                           g["k_scales"].cpu().numpy().view(np.float16), U.np64(g["Kp"]), 0.25)
@@ -655,6 +698,7 @@ def stream_layers(cfg, n_layers, n_per_layer, device="cuda"):
 
 @pytest.mark.parametrize("name,T,n_per_layer", [
     ("llama3.2-3b bench shape", 8192, [16, 16, 16]),
+    ("llama3.1-8b shape, 2-bit (the headline workload of bench.py)", 32768, [16, 16, 16]),
     ("llama3.1-8b shape, 3-bit", 32768, [64, 64]),
     ("llama3.1-70b shape, mixed 2/3-bit", 131072, [16, 64, 16]),
 ])
@@ -665,6 +709,7 @@ def test_full_size_layers_on_sampled_rows(B, name, T, n_per_layer):
     cfg = synth.Config(name, layers=len(n_per_layer), kv_heads=8, head_dim=128, tokens=T, dtype="bf16")
     rows = sampled_rows(T, 160, 5)
     Kp = Vp = None
+    kept = dict(lo=[], lg=[], K=[], V=[], out=[])
     for l, K, V, lo, lg in stream_layers(cfg, len(n_per_layer), n_per_layer):
         kc, ks = lg.alloc_codes(T)
         vc, vs = lg.alloc_codes(T)
@@ -673,6 +718,8 @@ def test_full_size_layers_on_sampled_rows(B, name, T, n_per_layer):
         B.aquakv_encode_layer(lg, T, K, V, Kp, Vp, kc, ks, vc, vs, Kh, Vh, ws)
         sync()
         g = dict(k_codes=kc, k_scales=ks, v_codes=vc, v_scales=vs, Khat=Kh, Vhat=Vh, Kp=Kp, Vp=Vp)
+        for name, item in (("lo", lo), ("lg", lg), ("K", K), ("V", V), ("out", g)):
+            kept[name].append(item)
         for rep in check_layer_against_oracle(B, lo, lg, K, V, g, rows=rows):
             print(f"   layer {l}: {rep}", flush=True)
         Kd, Vd = lg.alloc_kv(T), lg.alloc_kv(T)
@@ -716,6 +763,11 @@ def test_full_size_layers_on_sampled_rows(B, name, T, n_per_layer):
         bound = {16: 0.13, 64: 0.04}[n_per_layer[l]] if l == 0 else {16: 0.06, 64: 0.02}[n_per_layer[l]]
         assert rel < bound, (l, rel)
         Kp, Vp = Kh, Vh
+    # free-running: the oracle follows the sampled rows through all layers on its own reconstructions; every
+    # disagreement with the library's codes and scales must have a cause (tie, or the measured difference of inputs)
+    for l, which, rep in free_run_layers(B, kept["lo"], kept["lg"], kept["K"], kept["V"], kept["out"], rows=rows):
+        print(f"   free-run layer {l} {which}: {rep}", flush=True)
+        assert rep.other == 0, f"layer {l} {which}: {rep}"
 
 
 def test_folded_scores_at_the_full_decode_read_shape(B):
@@ -736,8 +788,8 @@ def test_folded_scores_at_the_full_decode_read_shape(B):
     need = B.aquakv_scores_workspace_bytes(lg, batch, QH)
     assert need > 0
     scores = torch.full((batch, QH, S), float("nan"), dtype=torch.float32, device="cuda")
-    B.aquakv_decode_attn_scores(lg, batch, S, QH, kc, ks, Kprev, q, 0.0883883, scores, None,
-                                torch.empty(need, dtype=torch.uint8, device="cuda"))
+    B.aquakv_decode_attn_scores_folded(lg, batch, S, QH, kc, ks, Kprev, q, 0.0883883, scores,
+                                       torch.empty(need, dtype=torch.uint8, device="cuda"))
     sync()
     assert torch.isfinite(scores).all()
     rng = np.random.Generator(np.random.PCG64(91))
@@ -758,12 +810,14 @@ def test_folded_scores_at_the_full_decode_read_shape(B):
     print(f"   worst score error / sum|q||k| = {worst:.2e}", flush=True)
 
 
-def test_decode_read_path_batch_of_long_sequences(B):
+@pytest.mark.parametrize("batch", [8, 64])
+def test_decode_read_path_batch_of_long_sequences(B, batch):
     """The decode-phase read path (batched sequences of 16384 cached tokens, 32 query heads on 8 kv
-    heads): fused dequantize + q.k against the oracle on sampled (sequence, token) pairs, plus the
+    heads; batch 64 is the full shape of the workload list): fused dequantize + q.k (the definition: prediction
+    recomputed, rounded keys scored) against the oracle on sampled (sequence, token) pairs, plus the
     one-new-token-per-sequence append through aquakv_encode_layer."""
-    print("case decode read path", flush=True)
-    batch, S, H, QH, n = 8, 16384, 8, 32, 16
+    print(f"case decode read path batch={batch}", flush=True)
+    S, H, QH, n = 16384, 8, 32, 16
     T = batch * S
     cfg = synth.Config("read-path", layers=2, kv_heads=H, head_dim=128, tokens=T, dtype="bf16")
     outs = []
