@@ -255,6 +255,23 @@ int aquakv_decode_attn_scores_folded(const aquakv_layer* layer, int32_t batch, i
                                      float* scores, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * aquakv_decode_attn_scores_folded_static -- aquakv_decode_attn_scores_folded for callers that cannot
+ * allocate device memory and so have no workspace to pass (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid allocation).  Same arguments without the workspace, same kernels, same
+ * bits.  The folded queries live in a buffer built into the library (about 9 MiB of device memory per
+ * GPU the library runs on, held until the process ends), so the call allocates nothing; it serves
+ * batch x passes <= 64 (passes = 1 up to 32 query heads, 2 above) and returns AQUAKV_EUNSUPPORTED with
+ * a text beyond that.  Every call on a GPU uses that GPU's one buffer: calls on the same GPU must not
+ * overlap in time (different streams without an ordering between them, or several host threads) or
+ * they race on it; calls on one stream are ordered and safe.  Nothing in the buffer needs clearing
+ * between calls: each call writes every byte it later reads.
+ */
+int aquakv_decode_attn_scores_folded_static(const aquakv_layer* layer, int32_t batch, int32_t seq_len, int32_t q_heads,
+                                            const uint8_t* k_codes, const uint16_t* k_scales,
+                                            const void* Khat_prev, const void* q, float score_scale,
+                                            float* scores, void* stream);
+
+/*
  * aquakv_decode_attn_scores_rope -- the same call for caches that hold the keys from BEFORE the
  * rotary positional embedding (Sect. 3.3 "Positional embeddings": predictors and quantizer work
  * best there).  The decoded (storage-rounded) key of token t of every sequence is rotated by

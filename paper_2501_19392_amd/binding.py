@@ -33,7 +33,7 @@ EXPORTS = [
     "aquakv_predict", "aquakv_quantize", "aquakv_dequantize",
     "aquakv_encode_layer", "aquakv_decode_layer", "aquakv_decode_attn_scores",
     "aquakv_scores_workspace_bytes", "aquakv_decode_attn_scores_rope",
-    "aquakv_decode_attn_scores_folded",
+    "aquakv_decode_attn_scores_folded", "aquakv_decode_attn_scores_folded_static",
     "aquakv_encode_keys", "aquakv_encode_values", "aquakv_decode_values",
     "aquakv_fit_workspace_bytes", "aquakv_fit_predictor",
     "aquakv_softmax", "aquakv_weighted_workspace_bytes", "aquakv_decode_values_weighted", "aquakv_decode_values_attend",
@@ -77,6 +77,8 @@ _lib.aquakv_decode_attn_scores_rope.argtypes = ([_LP, ctypes.c_int32, ctypes.c_i
                                                  ctypes.c_float, _P, _P, _P, ctypes.c_size_t, _P])
 _lib.aquakv_decode_attn_scores_folded.argtypes = ([_LP, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _P, _P, _P, _P,
                                                    ctypes.c_float, _P, _P, ctypes.c_size_t, _P])
+_lib.aquakv_decode_attn_scores_folded_static.argtypes = ([_LP, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _P, _P, _P, _P,
+                                                          ctypes.c_float, _P, _P])
 _lib.aquakv_encode_keys.argtypes = [_LP, ctypes.c_int64] + [_P] * 6 + [ctypes.c_size_t, _P]
 _lib.aquakv_encode_values.argtypes = [_LP, ctypes.c_int64] + [_P] * 7 + [ctypes.c_size_t, _P]
 _lib.aquakv_decode_values.argtypes = [_LP, ctypes.c_int64] + [_P] * 6 + [ctypes.c_size_t, _P]
@@ -92,7 +94,7 @@ _lib.aquakv_decode_values_attend.argtypes = [_LP, ctypes.c_int32, ctypes.c_int32
 _lib.aquakv_attend_raw.argtypes = [ctypes.c_int32] * 5 + [_P, _P, _P, _P, _P, ctypes.c_float, _P, _P, ctypes.c_int32, _P]
 for _n in ("aquakv_attend_raw", "aquakv_softmax", "aquakv_decode_values_weighted", "aquakv_decode_values_attend", "aquakv_predict", "aquakv_quantize", "aquakv_dequantize", "aquakv_encode_layer", "aquakv_decode_layer",
            "aquakv_decode_attn_scores", "aquakv_decode_attn_scores_rope", "aquakv_decode_attn_scores_folded",
-           "aquakv_encode_keys", "aquakv_encode_values",
+           "aquakv_decode_attn_scores_folded_static", "aquakv_encode_keys", "aquakv_encode_values",
            "aquakv_decode_values", "aquakv_fit_predictor"):
     getattr(_lib, _n).restype = ctypes.c_int
 
@@ -382,3 +384,9 @@ def aquakv_decode_attn_scores_folded(layer, batch: int, seq_len: int, q_heads: i
                                                  _ptr(Khat_prev), _ptr(q), ctypes.c_float(score_scale), _ptr(scores),
                                                  ws, nbytes, _stream(stream)))
 
+
+def aquakv_decode_attn_scores_folded_static(layer, batch: int, seq_len: int, q_heads: int, k_codes, k_scales, Khat_prev,
+                                            q, score_scale: float, scores, stream=None) -> None:
+    _check(_lib.aquakv_decode_attn_scores_folded_static(_layer_ref(layer), batch, seq_len, q_heads, _ptr(k_codes),
+                                                        _ptr(k_scales), _ptr(Khat_prev), _ptr(q),
+                                                        ctypes.c_float(score_scale), _ptr(scores), _stream(stream)))

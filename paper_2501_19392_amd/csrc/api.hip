@@ -5,6 +5,8 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "../../include/aquakv.h"
 #include "kernels.h"
 
@@ -725,6 +727,33 @@ size_t aquakv_scores_workspace_bytes(const aquakv_layer* L, int32_t batch, int32
 }  // extern "C"
 
 namespace {
+// The folded form keeps per-call operands (the folded queries) in device memory.  Callers that cannot allocate
+// take them from this array instead of a workspace of their own: aquakv_decode_attn_scores_folded_static.
+// Host code never uses the array's name as an address: the device address is asked for once per device
+// (hipGetSymbolAddress, with that device current) and kept.
+constexpr int kStaticFoldBatches = 64;                                    // batch x passes of one call
+constexpr size_t kStaticFoldBytes = (size_t)kStaticFoldBatches * aquakv::kFoldedBytesPerBatch;   // about 9 MiB
+__device__ __align__(256) unsigned char scratch[kStaticFoldBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// device address of `scratch` on the current device (looked up on the first call per device)
+int static_scratch(void** out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(AQUAKV_EUNSUPPORTED, "device ordinal %d: at most %d devices", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (ptr == nullptr) return fail(AQUAKV_EHIP, "hipGetSymbolAddress returned a null address");
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return AQUAKV_OK;
+}
+
 enum ScoresForm { kFormDefinition = 0, kFormFolded = 1 };
 
 // shared body of the scoring entry points; rope_cos / rope_sin both NULL: no rotary embedding
@@ -807,6 +836,23 @@ int aquakv_decode_attn_scores_folded(const aquakv_layer* L, int32_t batch, int32
                                      size_t workspace_bytes, void* stream_) {
   return decode_attn_scores(L, batch, seq_len, q_heads, k_codes, k_scales, Khat_prev, q, nullptr, nullptr, score_scale,
                             scores, nullptr, workspace, workspace_bytes, stream_, kFormFolded);
+}
+
+int aquakv_decode_attn_scores_folded_static(const aquakv_layer* L, int32_t batch, int32_t seq_len, int32_t q_heads,
+                                            const uint8_t* k_codes, const uint16_t* k_scales, const void* Khat_prev,
+                                            const void* q, float score_scale, float* scores, void* stream_) {
+  CHECK(check_layer(L));
+  if (batch < 0 || q_heads < 1) return fail(AQUAKV_EINVAL, "batch=%d q_heads=%d", batch, q_heads);
+  const size_t need = aquakv::folded_scores_workspace_bytes(batch, q_heads);
+  if (need > kStaticFoldBytes)
+    return fail(AQUAKV_EUNSUPPORTED, "batch=%d with %d query heads needs %zu B of folded queries; the built-in buffer holds "
+                                     "%zu B (batch x passes <= %d, one pass per 32 query heads): use "
+                                     "aquakv_decode_attn_scores_folded with a workspace",
+                batch, q_heads, need, kStaticFoldBytes, kStaticFoldBatches);
+  void* ptr = nullptr;
+  CHECK(static_scratch(&ptr));
+  return decode_attn_scores(L, batch, seq_len, q_heads, k_codes, k_scales, Khat_prev, q, nullptr, nullptr, score_scale,
+                            scores, nullptr, ptr, kStaticFoldBytes, stream_, kFormFolded);
 }
 
 int aquakv_decode_attn_scores_rope(const aquakv_layer* L, int32_t batch, int32_t seq_len, int32_t q_heads,

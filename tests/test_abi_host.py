@@ -324,7 +324,8 @@ def test_overlapping_buffers_are_refused_before_any_launch():
 
 
 def test_folded_scoring_calls_validate_their_arguments():
-    """The folded form is a call of its own: EUNSUPPORTED where it is not built, its own workspace size, """
+    """The folded form is a call of its own: EUNSUPPORTED where it is not built, its own workspace size, and the
+    variant with the built-in buffer refuses shapes beyond that buffer with a text that names the other call."""
     L = layer()
     sc = [FAKE, FAKE, FAKE, FAKE, 1.0, FAKE]        # k_codes k_scales Khat_prev q scale scores
     need = B.aquakv_scores_workspace_bytes(L, 2, 32)
@@ -341,6 +342,11 @@ def test_folded_scoring_calls_validate_their_arguments():
     bad[2] = None
     assert status_of(f, L, 2, 16, 32, *bad, (FAKE, need)) == B.AQUAKV_ENULL          # Khat_prev
     f(L, 0, 16, 32, *sc, None)                                                      # no tokens: no-op
+    g = B.aquakv_decode_attn_scores_folded_static
+    assert status_of(g, L, 65, 16, 32, *sc) == B.AQUAKV_EUNSUPPORTED                # batch x passes > 64
+    assert "aquakv_decode_attn_scores_folded" in B.aquakv_last_error()
+    assert status_of(g, L, 33, 16, 64, *sc) == B.AQUAKV_EUNSUPPORTED                # two passes
+    assert status_of(g, layer(head_dim=64), 1, 16, 32, *sc) == B.AQUAKV_EUNSUPPORTED  # invalid layer first
 
 
 def test_round_to_nearest_backbone_ignores_grid_pointers():
