@@ -2,18 +2,23 @@
 // P = [x0 | x1] W^T + b written to memory in fp32.
 //
 // bf16 path: a dense contraction, so it runs on the gfx950 matrix cores (main loop in
-// gemm_core.h).  fp32 path: plain FMA tiles (parity mode for the small fp32 configuration).
+// gemm_team.h).  fp32 path: plain FMA tiles (parity mode for the small fp32 configuration).
 #include "gemm_core.h"
+#include "gemm_team.h"
 #include "kernels.h"
 
 namespace aquakv {
 namespace {
 
-__global__ __launch_bounds__(kGemmThreads) void predict_bf16_kernel(
+// Four-wave main loop with swapped operands (gemm_team.h): a lane holds 64 consecutive outputs of one token, so the
+// stores are 16 bytes each and 256 contiguous bytes per lane.
+__global__ __launch_bounds__(kTeamThreads) void predict_bf16_kernel(
     const bf16_t* __restrict__ x0, int d0, const bf16_t* __restrict__ x1, int d1, const bf16_t* __restrict__ W,
     const float* __restrict__ bias, float* __restrict__ P, int64_t T, int D) {
-  __shared__ __attribute__((aligned(16))) unsigned char lds[kMainLoopLdsBytes];
-
+  __shared__ __attribute__((aligned(16))) unsigned char lds[kMainLoopLdsBytes + sizeof(TeamFlags)];
+  TeamFlags& flags = *reinterpret_cast<TeamFlags*>(lds + kMainLoopLdsBytes);
+  if (threadIdx.x < sizeof(TeamFlags) / 4) reinterpret_cast<uint32_t*>(&flags)[threadIdx.x] = 0;
+  __syncthreads();
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int n_tiles = D / BN;
@@ -21,25 +26,26 @@ __global__ __launch_bounds__(kGemmThreads) void predict_bf16_kernel(
   const int tile_m = logical / n_tiles, tile_n = logical % n_tiles;
   const int64_t m0 = (int64_t)tile_m * BM;
   const int n0 = tile_n * BN;
-  const int frow = lane & 31, fk = lane >> 5;
-
-  f32x16 acc[2][4];
-  gemm_mainloop<4>(lds, x0, d0, x1, d1, W, T, m0, n0, acc, [] {});
-
-  // accumulator layout of the 32x32 tile: lane holds column lane%32 and rows
-  // 8*blk + 4*(lane/32) + j for register 4*blk + j.
+  f32x16 acc[4][2];
+  uint32_t epoch = 0;
+  gemm_team_mainloop(lds, flags.arrive, epoch, x0, d0, x1, d1, W, T, m0, n0, acc, [] {});
+  const int tok = lane & 31, hf = lane >> 5;
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
+    const int64_t row = m0 + wave * 64 + i * 32 + tok;
+    if (row >= T) continue;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int col = n0 + j * 32 + frow;
-      const float bv = bias != nullptr ? bias[col] : 0.f;
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int64_t row = m0 + wave * 64 + i * 32 + (r >> 2) * 8 + fk * 4 + (r & 3);
-        if (row < T) P[row * D + col] = acc[i][j][r] + bv;
+      for (int blk = 0; blk < 4; ++blk) {
+        const int col = n0 + 64 * hf + 16 * j + 4 * blk;
+        f32x4 o;
+        o.x = acc[j][i][4 * blk] + (bias != nullptr ? bias[col] : 0.f);
+        o.y = acc[j][i][4 * blk + 1] + (bias != nullptr ? bias[col + 1] : 0.f);
+        o.z = acc[j][i][4 * blk + 2] + (bias != nullptr ? bias[col + 2] : 0.f);
+        o.w = acc[j][i][4 * blk + 3] + (bias != nullptr ? bias[col + 3] : 0.f);
+        *reinterpret_cast<f32x4*>(P + row * D + col) = o;
       }
-    }
   }
 }
 
@@ -104,7 +110,7 @@ hipError_t launch_predict(int dtype, const void* x0, int d0, const void* x1, int
   if (T == 0) return hipSuccess;
   if (dtype == kBF16) {
     const int64_t blocks = ((T + BM - 1) / BM) * (D / BN);
-    predict_bf16_kernel<<<(unsigned)blocks, kGemmThreads, 0, stream>>>(
+    predict_bf16_kernel<<<(unsigned)blocks, kTeamThreads, 0, stream>>>(
         static_cast<const bf16_t*>(x0), d0, static_cast<const bf16_t*>(x1), d1, static_cast<const bf16_t*>(W), bias, P,
         T, D);
   } else {
