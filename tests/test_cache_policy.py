@@ -324,6 +324,111 @@ def test_gpu_cache_attention_of_a_new_token_over_everything_cached(first, rht_gr
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("first,rht_group,with_rope", [("2bit", None, False), ("bf16", 1024, True)])
+def test_gpu_batched_cache_manager_with_ragged_lengths(first, rht_group, with_rope, monkeypatch):
+    """Four sequences of different lengths in one AquaKVCache (Sect. 3.3, Alg. "Inference" per sequence).  Quantization
+    is per token, so batching may not change a bit: every sequence must hold exactly the codes, and recover exactly
+    the tensors, of a cache of its own fed the same tokens; all buffers that fill in one append are quantized by ONE
+    aquakv_encode_layer call per layer; each sequence is checked against its own policy oracle."""
+    from paper_2501_19392_amd import binding as B
+    from paper_2501_19392_amd.cache import AquaKVCache
+    from tests import parity_utils as U
+    from tests.test_gpu_parity import bits, sync
+    print(f"case batched cache first={first} rht_group={rht_group} rope={with_rope}", flush=True)
+    L, H, QH, NB, T, sink, r = 3, 8, 16, 4, 200, 4, 32
+    cfg = synth.Config("cache", layers=L, kv_heads=H, head_dim=128, tokens=NB * T, dtype="bf16")
+    st = synth.KVStream(cfg, device="cpu", work=torch.float64)
+    Ks, Vs, lo_l, lg_l = [], [], [], []
+    for l in range(L):
+        K, V = st.next()                                  # rows are independent draws: sequence b = rows [b T, (b + 1) T)
+        Ks.append(K.cuda().view(NB, T, H, 128)); Vs.append(V.cuda().view(NB, T, H, 128))
+        if l == 0:
+            lo, lg = (None, None) if first == "bf16" else U.make_layers(H, "bf16", 16, layer_idx=0, rht_group=rht_group)
+        else:
+            wk, wv = synth.analytic_predictors(st, l)
+            lo, lg = U.make_layers(H, "bf16", 16, layer_idx=l, w_k=wk, w_v=wv, rht_group=rht_group)
+        lo_l.append(lo); lg_l.append(lg)
+    coded = sum(l is not None for l in lg_l)
+    calls = []
+    real = B.aquakv_encode_layer
+    monkeypatch.setattr(B, "aquakv_encode_layer", lambda layer, tokens, *a, **k: (calls.append(tokens), real(layer, tokens, *a, **k))[1])
+    gpu = AquaKVCache(lg_l, max_tokens=T, sink_tokens=sink, buffer_tokens=r, batch=NB)
+    own = [AquaKVCache(lg_l, max_tokens=T, sink_tokens=sink, buffer_tokens=r) for _ in range(NB)]
+    cpu = [CacheOracle(lo_l, sink_tokens=sink, buffer_tokens=r) for _ in range(NB)]
+    pos = [0] * NB
+    scale = 128 ** -0.5
+    qs = [synth.random_queries(NB, QH, 128, seed=700 + l, dtype="bf16", device="cuda") * 3.0 for l in range(L)]
+    rope_cpu = O.rope_tables(T, 128) if with_rope else None
+    rope_gpu = tuple(torch.from_numpy(t).float().cuda() for t in rope_cpu) if with_rope else None
+
+    def check_attend(label):
+        """attention of one new token per sequence: the batched call against each sequence's own cache and oracle"""
+        for rep in range(2):                                  # a second call reuses the buffers
+            got = [o.clone() for o in gpu.attend(qs, scale, rope_gpu)]
+            got_flat = [o.clone() for o in gpu.attend([q * 0.125 for q in qs], scale, rope_gpu)]
+            sync()
+            for b in range(NB):
+                single = [o.clone() for o in own[b].attend([q[b] for q in qs], scale, rope_gpu)]
+                sync()
+                want = cpu[b].attend([U.np64(q[b]) * 0.125 for q in qs], scale, rope_cpu)
+                for l in range(L):
+                    rms = float(np.sqrt(np.mean(U.np64(Vs[l][b]) ** 2)))
+                    err = float(np.abs(U.np64(got[l][b]) - U.np64(single[l])).max())
+                    assert err <= 1e-5 * rms, (b, l, err, rms)        # same kernels on the same rows: summation order at most
+                    err_free = float(np.abs(U.np64(got_flat[l][b]) - want[l]).max())
+                    assert err_free <= U.RTOL["bf16"] * rms, (b, l, err_free, rms)
+                if rep == 0:
+                    print(f"   {label}, sequence {b}: attend = single-sequence attend to {err / rms:.1e} rms(V), "
+                          f"vs oracle (flat rows) {err_free / rms:.3g}", flush=True)
+
+    rounds = [(36, 36, 36, 36), (1, 4, 0, 7), (40, 3, 33, 64), (32, 32, 32, 32), (29, 100, 5, 1), (0, 0, 50, 0), (7, 7, 7, 7)]
+    for step, lens in enumerate(rounds):
+        t = max(lens)
+        kv = []
+        for K, V in zip(Ks, Vs):
+            Kin, Vin = torch.zeros(NB, t, H, 128, dtype=K.dtype, device="cuda"), torch.zeros(NB, t, H, 128, dtype=K.dtype, device="cuda")
+            for b, n in enumerate(lens):
+                Kin[b, :n] = K[b, pos[b]:pos[b] + n]; Vin[b, :n] = V[b, pos[b]:pos[b] + n]
+            kv.append((Kin, Vin))
+        calls.clear()
+        gpu.append(kv, lengths=lens)
+        if step == 0:       # lock step: 4 sinks, then the four buffers fill together: one call per quantized layer
+            assert calls == [NB * r] * coded, calls
+        for b, n in enumerate(lens):
+            piece = [(K[b, pos[b]:pos[b] + n], V[b, pos[b]:pos[b] + n]) for K, V in zip(Ks, Vs)]
+            own[b].append(piece)
+            cpu[b].append([(U.np64(K), U.np64(V)) for K, V in piece])
+            pos[b] += n
+        assert gpu.n_sink == tuple(c.n_sink for c in cpu) and gpu.n_compressed == tuple(c.n_compressed for c in cpu)
+        assert gpu.n_buffered == tuple(c.n_buffered for c in cpu)
+        if step == 0:
+            check_attend("whole batch as one group")
+    sync()
+    assert gpu.n_compressed == (128, 160, 128, 128) and len(set(gpu.n_buffered)) > 1  # ragged: groups {0, 2, 3} and {1}
+    assert gpu.stored_bytes() == sum(c.stored_bytes(elem_bytes=2) for c in cpu)
+    C = gpu.capacity
+    for b in range(NB):
+        c = gpu.n_compressed[b]
+        for l in range(L):
+            if lg_l[l] is None:
+                assert torch.equal(bits(gpu.raw[l][0][b * C:b * C + c]), bits(own[b].raw[l][0][:c]))
+                continue
+            for mine, single in zip(gpu.codes[l], own[b].codes[l]):
+                assert torch.equal(mine[0][b * C:b * C + c], single[0][:c]) and torch.equal(mine[1][b * C:b * C + c], single[1][:c])
+        want = {l: (K, V) for l, K, V in cpu[b].sweep()}
+        for (l, K, V), (_, K1, V1) in zip(gpu.sweep(b), own[b].sweep()):
+            sync()
+            assert K.shape == (pos[b], H, 128)
+            assert torch.equal(bits(K), bits(K1)) and torch.equal(bits(V), bits(V1))
+            for got, ref in ((K, want[l][0]), (V, want[l][1])):
+                rel = np.linalg.norm(U.np64(got) - ref) / np.linalg.norm(ref)
+                assert rel < 2e-2, (b, l, rel)
+        print(f"   sequence {b}: {gpu.n_sink[b]} + {c} + {gpu.n_buffered[b]} tokens, codes and recovered tensors = those of a "
+              f"cache of its own; vs oracle rel {rel:.2e}", flush=True)
+    check_attend("ragged groups")
+
+
+@pytest.mark.gpu
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
 def test_gpu_attend_raw_and_its_merge(dtype):
     """aquakv_attend_raw on its own: attention over tokens held in the storage dtype, then a second token set merged in."""
