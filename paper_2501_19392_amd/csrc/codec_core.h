@@ -10,6 +10,10 @@
 // cell is marked and the lane falls back to the full search.  Only the listed points are
 // scored, with the same fp32 expression and the same lowest-index tie rule as the full
 // search, so both give identical codes.
+//
+// Inside the kernels a grid point is named by its "slot" (Slot<NCW>): for n = 16 the byte offset 16 j of its
+// entry in the LDS copy of the grid, which still fits a byte of a table entry and is the address the look-up
+// needs; for the larger grids the index j itself.
 #pragma once
 #include "device_utils.h"
 
@@ -47,47 +51,42 @@ __device__ __forceinline__ float score(float y0, float y1, const float4 c) {
   return __fmaf_rn(y0, c.x, __fmaf_rn(y1, c.y, c.z));
 }
 
-// Full search over all grid points; lowest index wins ties.
-template <int NCW>
-__device__ __forceinline__ int search_full(float y0, float y1, const float4* cb) {
-  float best = score(y0, y1, cb[0]);
-  int idx = 0;
-#pragma unroll 8
-  for (int j = 1; j < NCW; ++j) {
-    const float s = score(y0, y1, cb[j]);
-    const bool better = s > best;
-    best = better ? s : best;
-    idx = better ? j : idx;
-  }
-  return idx;
+template <int NCW> struct Slot {
+  static constexpr int kShift = NCW == 16 ? 4 : 0;          // slot = j << kShift
+};
+// the LDS entry of a grid point from its slot (SHIFT = 4: the slot is the byte offset itself)
+template <int SHIFT> __device__ __forceinline__ float4 grid_entry(const float4* cb, int slot) {
+  return *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(cb) + ((uint32_t)slot << (4 - SHIFT)));
 }
 
-// Table search: score the (up to 4, ascending, last one repeated) candidates of the cell.
+// Table search: score the (up to 4, ascending, last one repeated) candidates of the cell; returns the winner's slot.
 // Sets `crowded` if the cell lists too many points; the caller then redoes the lane's
 // sub-vectors with the full search in one compact rolled loop (rare; keeps the hot path small).
 template <int NCW>
 __device__ __forceinline__ int search_cell(float y0, float y1, const float4* cb, const uint32_t* table,
                                            bool& crowded) {
+  constexpr int SH = Slot<NCW>::kShift;
   const float fx = __builtin_amdgcn_fmed3f(__fmaf_rn(y0, kCellScale, 0.5f * kCells), 0.0f, kCells - 0.5f);
   const float fy = __builtin_amdgcn_fmed3f(__fmaf_rn(y1, kCellScale, 0.5f * kCells), 0.0f, kCells - 0.5f);
   const uint32_t e = table[(int)fy * kCells + (int)fx];
   crowded = e == kCellFull;
-  int idx = e & 0xff;
-  float best = score(y0, y1, cb[idx]);
+  int slot = e & 0xff;
+  float best = score(y0, y1, grid_entry<SH>(cb, slot));
   constexpr int kCand = NCW == 16 ? 3 : 4;       // the builder marks cells of a 16-point grid with more than 3
 #pragma unroll
   for (int k = 1; k < kCand; ++k) {
     const int j = (e >> (8 * k)) & 0xff;
-    const float s = score(y0, y1, cb[j]);
+    const float s = score(y0, y1, grid_entry<SH>(cb, j));
     const bool better = s > best;                // duplicates of the last candidate never win
     best = better ? s : best;
-    idx = better ? j : idx;
+    slot = better ? j : slot;
   }
-  return idx;
+  return slot;
 }
 
-// Full search for the sub-vectors of this lane whose bit is set in `mask` (grid points in the
-// outer, rolled loop and 8 sub-vectors at a time, so that code and live registers stay small).
+// Full search (the definition: all n points, lowest index wins ties) for the sub-vectors of this lane whose bit is
+// set in `mask`; writes their slots (grid points in the outer, rolled loop and 8 sub-vectors at a time, so that code
+// and live registers stay small).
 template <int NCW>
 __device__ __forceinline__ void search_full_masked(const float (&v)[32], float inv, const float4* cb, uint32_t mask,
                                                    int (&idx)[16]) {
@@ -112,7 +111,7 @@ __device__ __forceinline__ void search_full_masked(const float (&v)[32], float i
         const float s = score(y[2 * m], y[2 * m + 1], cj);
         const bool better = s > best[m];
         best[m] = better ? s : best[m];
-        bi[m] = better ? j : bi[m];
+        bi[m] = better ? (j << Slot<NCW>::kShift) : bi[m];
       }
     }
 #pragma unroll
@@ -124,33 +123,39 @@ __device__ __forceinline__ void search_full_masked(const float (&v)[32], float i
   }
 }
 
-// 16 codes of c bits per lane = 4c contiguous bytes of the group's little-endian bit string.
+// 16 codes of c bits per lane = 4c contiguous bytes of the group's little-endian bit string.  `slot`: the 16 slots.
 template <int NCW>
-__device__ __forceinline__ void store_codes(uint8_t* __restrict__ codes, int64_t gid, int q, const int (&idx)[16]) {
+__device__ __forceinline__ void store_codes(uint8_t* __restrict__ codes, int64_t gid, int q, const int (&slot)[16]) {
   constexpr int c = CodeBits<NCW>::c;
+  constexpr int SH = Slot<NCW>::kShift;
   uint32_t* dst = reinterpret_cast<uint32_t*>(codes + gid * (kGroup / 2 * c / 8) + q * (2 * c));
   if constexpr (c == 4) {
     uint32_t d[2] = {0, 0};
 #pragma unroll
-    for (int m = 0; m < 16; ++m) d[m >> 3] |= (uint32_t)idx[m] << (4 * (m & 7));
+    for (int m = 0; m < 16; ++m) {
+      const int pos = 4 * (m & 7);                   // the index j = slot >> SH goes to bit `pos`
+      d[m >> 3] |= pos >= SH ? (uint32_t)slot[m] << (pos - SH) : (uint32_t)slot[m] >> (SH - pos);
+    }
     u32x2 v; v.x = d[0]; v.y = d[1];
     *reinterpret_cast<u32x2*>(dst) = v;
   } else if constexpr (c == 6) {
+    static_assert(c != 6 || SH == 0, "slots of the larger grids are indices");
     uint32_t d[3] = {0, 0, 0};
 #pragma unroll
     for (int m = 0; m < 16; ++m) {
       const int bit = 6 * m, w = bit >> 5, sh = bit & 31;
-      d[w] |= (uint32_t)idx[m] << sh;
-      if (sh > 26) d[w + 1] |= (uint32_t)idx[m] >> (32 - sh);
+      d[w] |= (uint32_t)slot[m] << sh;
+      if (sh > 26) d[w + 1] |= (uint32_t)slot[m] >> (32 - sh);
     }
     dst[0] = d[0]; dst[1] = d[1]; dst[2] = d[2];
   } else {
+    static_assert(c != 8 || SH == 0, "slots of the larger grids are indices");
     u32x4 v;
     uint32_t d[4];
 #pragma unroll
     for (int w = 0; w < 4; ++w)
-      d[w] = (uint32_t)idx[4 * w] | ((uint32_t)idx[4 * w + 1] << 8) | ((uint32_t)idx[4 * w + 2] << 16) |
-             ((uint32_t)idx[4 * w + 3] << 24);
+      d[w] = (uint32_t)slot[4 * w] | ((uint32_t)slot[4 * w + 1] << 8) | ((uint32_t)slot[4 * w + 2] << 16) |
+             ((uint32_t)slot[4 * w + 3] << 24);
     v.x = d[0]; v.y = d[1]; v.z = d[2]; v.w = d[3];
     *reinterpret_cast<u32x4*>(dst) = v;
   }
@@ -198,13 +203,15 @@ __device__ __forceinline__ float half_bits_to_float(uint16_t h) {
   return static_cast<float>(__builtin_bit_cast(_Float16, h));
 }
 
-// codes + scale of one lane's part of a group -> zhat (rotated, scaled by sigma16)
-__device__ __forceinline__ void gather_zhat(const int (&idx)[16], float s16, const float4* cb, float (&z)[32]) {
+// slots (SHIFT = Slot<NCW>::kShift) or indices (SHIFT = 0) of the lane's 16 grid points -> the points times `scale`
+// (recon_scale(sigma16, lane): the input of the inverse transform)
+template <int SHIFT = 0>
+__device__ __forceinline__ void gather_zhat(const int (&slot)[16], float scale, const float4* cb, float (&z)[32]) {
 #pragma unroll
   for (int m = 0; m < 16; ++m) {
-    const float4 cw = cb[idx[m]];
-    z[2 * m] = cw.x * s16;
-    z[2 * m + 1] = cw.y * s16;
+    const float4 cw = grid_entry<SHIFT>(cb, slot[m]);
+    z[2 * m] = cw.x * scale;
+    z[2 * m + 1] = cw.y * scale;
   }
 }
 
@@ -338,7 +345,7 @@ __device__ __forceinline__ void rtn_quantize_group(float (&v)[32], const float (
 // scale per head group), lane % 32 for groups of 1024 = the whole token (WIDE = true, kv_heads = 8, one
 // scale per token at scales[gid / 8]).  The code bytes have the same layout in both cases.
 template <int NCW, bool WIDE = false>
-__device__ __forceinline__ void quantize_group(float (&v)[32], const float (&p)[32], const uint32_t (&sb)[32], int l,
+__device__ __forceinline__ void quantize_group(float (&v)[32], const float (&p)[32], const float (&sf)[32], int l,
                                                const float4* cb, const uint32_t* table, bool active, int64_t gid,
                                                uint8_t* __restrict__ codes, uint16_t* __restrict__ scales,
                                                bool want_hat) {
@@ -347,7 +354,7 @@ __device__ __forceinline__ void quantize_group(float (&v)[32], const float (&p)[
     return;
   }
 #pragma unroll
-  for (int r = 0; r < 32; ++r) v[r] = __uint_as_float(__float_as_uint(v[r] - p[r]) ^ sb[r]);   // s * (x - p)
+  for (int r = 0; r < 32; ++r) v[r] = (v[r] - p[r]) * sf[r];                              // s * (x - p), exact product
   const int q = l & 3;
   Rot<WIDE>::wht(v, l);                                   // w = +-H u (unnormalised, lane sign pending)
 
@@ -362,7 +369,7 @@ __device__ __forceinline__ void quantize_group(float (&v)[32], const float (&p)[
   const float s16 = static_cast<float>(s16h);
   const float inv = s16 > 0.f ? Rot<WIDE>::sign(l) * __fdiv_rn(Rot<WIDE>::kNorm, s16) : 0.f;   // also undoes the lane sign
 
-  int idx[16];
+  int idx[16];                                            // slots (Slot<NCW>)
   if (table != nullptr) {
     uint32_t crowded_mask = 0;
 #pragma unroll
@@ -383,14 +390,14 @@ __device__ __forceinline__ void quantize_group(float (&v)[32], const float (&p)[
     if (l == 0) scales[WIDE ? gid >> 3 : gid] = __builtin_bit_cast(uint16_t, s16h);
   }
   if (want_hat) {
-    gather_zhat(idx, s16, cb, v);
-    reconstruct<WIDE>(v, l, sb, p);
+    gather_zhat<Slot<NCW>::kShift>(idx, recon_scale<WIDE>(s16, l), cb, v);
+    reconstruct<WIDE>(v, l, sf, p);
   }
 }
 
 // Q^-1(codes) + p for the 32 coordinates this lane holds of group `gid` (unrounded, in z).
 template <int NCW, bool WIDE = false>
-__device__ __forceinline__ void dequantize_group(float (&z)[32], const float (&p)[32], const uint32_t (&sb)[32], int l,
+__device__ __forceinline__ void dequantize_group(float (&z)[32], const float (&p)[32], const float (&sf)[32], int l,
                                                  const float4* cb, int64_t gid, const uint8_t* __restrict__ codes,
                                                  const uint16_t* __restrict__ scales) {
   if constexpr (is_rtn(NCW)) {
@@ -400,8 +407,8 @@ __device__ __forceinline__ void dequantize_group(float (&z)[32], const float (&p
   int idx[16];
   load_codes<NCW>(codes, gid, l & 3, idx);
   const float s16 = half_bits_to_float(scales[WIDE ? gid >> 3 : gid]);
-  gather_zhat(idx, s16, cb, z);
-  reconstruct<WIDE>(z, l, sb, p);
+  gather_zhat(idx, recon_scale<WIDE>(s16, l), cb, z);
+  reconstruct<WIDE>(z, l, sf, p);
 }
 
 }  // namespace aquakv

@@ -29,6 +29,13 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const T* X, const fl
   __shared__ Lds lds;
   stage_lds<NCW>(lds, codebook, table);
   const int q = threadIdx.x & 3;
+  // A thread meets the same head in every round of the grid-stride loop when the stride is a multiple of H (it is
+  // for the power-of-two head counts in use): the signs are then fetched once.
+  float sf[32] = {};
+  const bool fixed_head = kGroupsPerBlock % H == 0;
+  if constexpr (!is_rtn(NCW)) {
+    if (fixed_head) load_signs(signs, (int)(((int64_t)blockIdx.x * kGroupsPerBlock + (threadIdx.x >> 2)) % H), q, sf);
+  }
   for (int64_t g0 = (int64_t)blockIdx.x * kGroupsPerBlock; g0 < n_groups; g0 += (int64_t)gridDim.x * kGroupsPerBlock) {
     int64_t gid = g0 + (threadIdx.x >> 2);
     const bool active = gid < n_groups;
@@ -37,7 +44,6 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const T* X, const fl
     const int64_t off = gid * kGroup + q * kValsPerLane;
 
     float v[32], p[32];
-    uint32_t sb[32] = {};
     Storage<T>::load32(X + off, v);
     if (P != nullptr) {
       load32_f32(P + off, p);
@@ -45,8 +51,10 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const T* X, const fl
 #pragma unroll
       for (int r = 0; r < 32; ++r) p[r] = 0.f;
     }
-    if constexpr (!is_rtn(NCW)) load_sign_bits(signs, head, q, sb);
-    quantize_group<NCW, WIDE>(v, p, sb, WIDE ? (int)(threadIdx.x & 31) : q, lds.cb, table != nullptr ? lds.table : nullptr,
+    if constexpr (!is_rtn(NCW)) {
+      if (!fixed_head) load_signs(signs, head, q, sf);
+    }
+    quantize_group<NCW, WIDE>(v, p, sf, WIDE ? (int)(threadIdx.x & 31) : q, lds.cb, table != nullptr ? lds.table : nullptr,
                               active, gid, codes, scales, Xhat != nullptr);
     if (Xhat != nullptr && active) Storage<T>::store32(Xhat + off, v);
   }
@@ -64,6 +72,13 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint8_t* __r
   load_codebook<NCW>(codebook, cb);
   __syncthreads();
   const int q = threadIdx.x & 3;
+  // A thread meets the same head in every round of the grid-stride loop when the stride is a multiple of H (it is
+  // for the power-of-two head counts in use): the signs are then fetched once.
+  float sf[32] = {};
+  const bool fixed_head = kGroupsPerBlock % H == 0;
+  if constexpr (!is_rtn(NCW)) {
+    if (fixed_head) load_signs(signs, (int)(((int64_t)blockIdx.x * kGroupsPerBlock + (threadIdx.x >> 2)) % H), q, sf);
+  }
   for (int64_t g0 = (int64_t)blockIdx.x * kGroupsPerBlock; g0 < n_groups; g0 += (int64_t)gridDim.x * kGroupsPerBlock) {
     int64_t gid = g0 + (threadIdx.x >> 2);
     const bool active = gid < n_groups;
@@ -72,15 +87,16 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint8_t* __r
     const int64_t off = gid * kGroup + q * kValsPerLane;
 
     float p[32], z[32];
-    uint32_t sb[32] = {};
     if (P != nullptr) {
       load32_f32(P + off, p);
     } else {
 #pragma unroll
       for (int r = 0; r < 32; ++r) p[r] = 0.f;
     }
-    if constexpr (!is_rtn(NCW)) load_sign_bits(signs, head, q, sb);
-    dequantize_group<NCW, WIDE>(z, p, sb, WIDE ? (int)(threadIdx.x & 31) : q, cb, gid, codes, scales);
+    if constexpr (!is_rtn(NCW)) {
+      if (!fixed_head) load_signs(signs, head, q, sf);
+    }
+    dequantize_group<NCW, WIDE>(z, p, sf, WIDE ? (int)(threadIdx.x & 31) : q, cb, gid, codes, scales);
     if (active) Storage<T>::store32(Xhat + off, z);
   }
 }
@@ -97,6 +113,13 @@ __global__ __launch_bounds__(kThreads) void attn_scores_kernel(
   load_codebook<NCW>(codebook, cb);
   __syncthreads();
   const int q = threadIdx.x & 3;
+  // A thread meets the same head in every round of the grid-stride loop when the stride is a multiple of H (it is
+  // for the power-of-two head counts in use): the signs are then fetched once.
+  float sf[32] = {};
+  const bool fixed_head = kGroupsPerBlock % H == 0;
+  if constexpr (!is_rtn(NCW)) {
+    if (fixed_head) load_signs(signs, (int)(((int64_t)blockIdx.x * kGroupsPerBlock + (threadIdx.x >> 2)) % H), q, sf);
+  }
   const int rep = q_heads / H;
   for (int64_t g0 = (int64_t)blockIdx.x * kGroupsPerBlock; g0 < n_groups; g0 += (int64_t)gridDim.x * kGroupsPerBlock) {
     int64_t gid = g0 + (threadIdx.x >> 2);
@@ -109,15 +132,16 @@ __global__ __launch_bounds__(kThreads) void attn_scores_kernel(
     const int64_t off = gid * kGroup + q * kValsPerLane;
 
     float p[32], z[32];
-    uint32_t sb[32] = {};
     if (P != nullptr) {
       load32_f32(P + off, p);
     } else {
 #pragma unroll
       for (int r = 0; r < 32; ++r) p[r] = 0.f;
     }
-    if constexpr (!is_rtn(NCW)) load_sign_bits(signs, head, q, sb);
-    dequantize_group<NCW, WIDE>(z, p, sb, WIDE ? (int)(threadIdx.x & 31) : q, cb, gid, codes, scales);
+    if constexpr (!is_rtn(NCW)) {
+      if (!fixed_head) load_signs(signs, head, q, sf);
+    }
+    dequantize_group<NCW, WIDE>(z, p, sf, WIDE ? (int)(threadIdx.x & 31) : q, cb, gid, codes, scales);
     if (Khat_out != nullptr && active) Storage<T>::store32(Khat_out + off, z);
 #pragma unroll
     for (int r = 0; r < 32; ++r) z[r] = Storage<T>::round(z[r]);      // score the stored keys
@@ -154,6 +178,7 @@ __global__ void build_table_kernel(const float* __restrict__ codebook, int n, ui
   double y0 = cy == 0 ? -far : -kCellHalfRange + cy * h, y1 = cy == kCells - 1 ? far : -kCellHalfRange + (cy + 1) * h;
   x0 -= delta; y0 -= delta; x1 += delta; y1 += delta;
   const double cxs[4] = {x0, x1, x0, x1}, cys[4] = {y0, y0, y1, y1};
+  const int shift = n == 16 ? Slot<16>::kShift : 0;      // entries hold slots (codec_core.h)
   uint32_t entry = 0;
   int count = 0, last = 0;
   for (int j = 0; j < n; ++j) {
@@ -169,8 +194,8 @@ __global__ void build_table_kernel(const float* __restrict__ codebook, int n, ui
       dominated = mn > eps;
     }
     if (!dominated) {
-      if (count < 4) entry |= (uint32_t)j << (8 * count);
-      last = j;
+      if (count < 4) entry |= (uint32_t)(j << shift) << (8 * count);
+      last = j << shift;
       ++count;
     }
   }

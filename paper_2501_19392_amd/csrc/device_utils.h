@@ -151,7 +151,12 @@ template <int MASK> __device__ __forceinline__ void wht_quad_stage(float (&v)[32
 
 __device__ __forceinline__ float quad_sign(int q) { return (q == 1 || q == 2) ? -1.0f : 1.0f; }
 
-__device__ __forceinline__ void wht128(float (&v)[32], int q) {
+// INV: the inverse-side convention.  The caller has multiplied the lane's INPUT by the parity sign of its lane bits
+// (Rot::sign; free when the input is built with a per-lane scale anyway); with s = -1 on the lower and +1 on the upper
+// lane of a cross-lane stage, v + s * partner is then the true butterfly on both lanes, (-a) + s (-b) being -(a + s b)
+// exactly, and nothing is left pending on the output.
+template <bool INV = false> __device__ __forceinline__ void wht128(float (&v)[32], int q) {
+  constexpr float up = INV ? 1.0f : -1.0f;               // s on the lane that holds the 1-bit
 #pragma unroll
   for (int h = 1; h < 32; h <<= 1) {
 #pragma unroll
@@ -163,8 +168,8 @@ __device__ __forceinline__ void wht128(float (&v)[32], int q) {
       }
     }
   }
-  wht_quad_stage<1>(v, (q & 1) ? -1.0f : 1.0f);
-  wht_quad_stage<2>(v, (q & 2) ? -1.0f : 1.0f);
+  wht_quad_stage<1>(v, (q & 1) ? up : -up);
+  wht_quad_stage<2>(v, (q & 2) ? up : -up);
 }
 
 // ---------------------------------------------------------------- 1024-point WHT (rotation group = whole token)
@@ -180,8 +185,9 @@ template <int XOR_MASK> __device__ __forceinline__ float swizzle_xor(float x) {
 __device__ __forceinline__ float row_xor8(float x) {     // value of lane ^ 8 (rotation by 8 within a row of 16)
   return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(x), 0x128 /* row_ror:8 */, 0xF, 0xF, true));
 }
-__device__ __forceinline__ void wht1024_tail(float (&v)[32], int lane32) {
-  const float s4 = (lane32 & 4) ? -1.0f : 1.0f, s8 = (lane32 & 8) ? -1.0f : 1.0f, s16 = (lane32 & 16) ? -1.0f : 1.0f;
+template <bool INV = false> __device__ __forceinline__ void wht1024_tail(float (&v)[32], int lane32) {
+  constexpr float up = INV ? 1.0f : -1.0f;               // as in wht128
+  const float s4 = (lane32 & 4) ? up : -up, s8 = (lane32 & 8) ? up : -up, s16 = (lane32 & 16) ? up : -up;
 #pragma unroll
   for (int r = 0; r < 32; ++r) v[r] = __fmaf_rn(swizzle_xor<4>(v[r]), s4, v[r]);
 #pragma unroll
@@ -210,9 +216,10 @@ template <bool WIDE> struct Rot {
   // The same transform (H_8 (x) H_128 is symmetric) with the stages across the heads first, used for the inverse:
   // a kernel that holds one head of a token per quad and fetches the other heads' grid points itself can then
   // reproduce it bit for bit by adding the 8 heads in the same tree, ((0 1)(2 3))((4 5)(6 7)), before its own wht128.
+  // Inverse-side convention (see wht128): input pre-multiplied by sign(l), true output.
   static __device__ __forceinline__ void iwht(float (&v)[32], int l) {
-    if constexpr (WIDE) wht1024_tail(v, l);
-    wht128(v, l & 3);
+    if constexpr (WIDE) wht1024_tail<true>(v, l);
+    wht128<true>(v, l & 3);
   }
   // sign pending on the lane's values after wht(): -1 for every cross-lane stage in which the lane was the upper one
   static __device__ __forceinline__ float sign(int l) {
@@ -222,8 +229,9 @@ template <bool WIDE> struct Rot {
   static __device__ __forceinline__ float sum(float x) { return WIDE ? token_sum(x) : quad_sum(x); }
 };
 
-// sign bits of the 32 RHT signs this lane needs (+1 -> 0, -1 -> 0x80000000)
-__device__ __forceinline__ void load_sign_bits(const int8_t* signs, int head, int q, uint32_t (&sb)[32]) {
+// the 32 RHT signs this lane needs as +-1.0f: multiplying by them is exact, so s * x costs one multiplication and
+// s * w + p one fused multiply-add that rounds exactly like the addition p +- w
+__device__ __forceinline__ void load_signs(const int8_t* signs, int head, int q, float (&sf)[32]) {
   const u32x4* src = reinterpret_cast<const u32x4*>(signs + head * kGroup + q * kValsPerLane);
 #pragma unroll
   for (int c = 0; c < 2; ++c) {
@@ -232,22 +240,26 @@ __device__ __forceinline__ void load_sign_bits(const int8_t* signs, int head, in
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int b = 0; b < 4; ++b) sb[16 * c + 4 * i + b] = ((w[i] >> (8 * b)) & 0x80u) << 24;
+      for (int b = 0; b < 4; ++b)
+        sf[16 * c + 4 * i + b] = __uint_as_float(0x3f800000u | (((w[i] >> (8 * b)) & 0x80u) << 24));
   }
 }
 
-// Reconstruction tail: zhat (rotated, already scaled by sigma16) -> s*H(zhat)/sqrt(g) + p.
-// Used unchanged by the quantize, dequantize and scoring kernels so that all
-// three produce bit-identical keys/values.
+// Reconstruction: Q^-1(codes) = s * H(sigma16 * C[codes]) / sqrt(g).  The transform is linear, so the factor
+// 1 / sqrt(g) goes into the scale once per group, together with the lane's parity sign that the inverse-side
+// convention of the cross-lane stages wants on its input: the grid points are multiplied by recon_scale(sigma16, l)
+// when they are fetched, and after the inverse transform one fused multiply-add per value applies the RHT sign and
+// adds the prediction.  Used unchanged by the quantize,
+// dequantize, scoring and fused kernels so that all of them produce bit-identical keys / values.
+template <bool WIDE = false> __device__ __forceinline__ float recon_scale(float s16, int l) {
+  return s16 * (Rot<WIDE>::sign(l) * Rot<WIDE>::kNorm);
+}
+// z: grid points scaled by recon_scale (rotated domain) -> p + Q^-1(codes)
 template <bool WIDE = false>
-__device__ __forceinline__ void reconstruct(float (&z)[32], int l, const uint32_t (&sb)[32], const float (&p)[32]) {
+__device__ __forceinline__ void reconstruct(float (&z)[32], int l, const float (&sf)[32], const float (&p)[32]) {
   Rot<WIDE>::iwht(z, l);
-  const float norm = Rot<WIDE>::sign(l) * Rot<WIDE>::kNorm;
 #pragma unroll
-  for (int r = 0; r < 32; ++r) {
-    const float x = __uint_as_float(__float_as_uint(z[r] * norm) ^ sb[r]);
-    z[r] = x + p[r];
-  }
+  for (int r = 0; r < 32; ++r) z[r] = __fmaf_rn(z[r], sf[r], p[r]);
 }
 
 // Rotary embedding (RoFormer) of the 32 coordinates this lane holds of a 128-long head vector.  Coordinate d is

@@ -145,10 +145,10 @@ __global__ __launch_bounds__(256) void fold_query_kernel(const bf16_t* __restric
     const int r = (tid - 64) >> 2, qd = tid & 3;
     float v[32];
     if (signs != nullptr) {
-      uint32_t sb[32];
-      load_sign_bits(signs, h, qd, sb);
+      float sf[32];
+      load_signs(signs, h, qd, sf);
 #pragma unroll
-      for (int k = 0; k < 32; ++k) v[k] = __uint_as_float(__float_as_uint(qs[r][32 * qd + k]) ^ sb[k]);
+      for (int k = 0; k < 32; ++k) v[k] = qs[r][32 * qd + k] * sf[k];
       wht128(v, qd);
       const float norm = quad_sign(qd) * kRsqrtG;
 #pragma unroll

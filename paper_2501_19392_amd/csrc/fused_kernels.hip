@@ -28,8 +28,9 @@ __device__ __forceinline__ constexpr int park_col(int col) {
   return (((slot & 16) ? (slot ^ 4) : slot) << 2) | (col & 3);
 }
 constexpr int kPredBytes = BM * kLdP * 4;           // 135168
-// LDS use over time: the main loop's ring of k-tiles (3 x 48 KiB), then the parked prediction
-// tile followed by the grid and the cell table, which are written once the main loop is done.
+// LDS use over time: the main loop's ring of k-tiles (3 x 48 KiB), then the grid and the cell table (at the start
+// of the array, so that a grid point's slot is its LDS address) followed by the parked prediction tile, all written
+// once the main loop is done.
 constexpr int kEpilogueLdsBytes = kPredBytes + (int)sizeof(Lds);
 constexpr int kFusedLdsBytes = kEpilogueLdsBytes > kMainLoopLdsBytes ? kEpilogueLdsBytes : kMainLoopLdsBytes;
 static_assert(kFusedLdsBytes <= 160 * 1024, "LDS of one CU");
@@ -63,7 +64,8 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
     float* __restrict__ part) {
   static_assert(!WIDE || MODE != kEncode, "the quantizer needs the whole group: groups across the heads are not fused");
   __shared__ __attribute__((aligned(16))) unsigned char smem[kFusedLdsBytes];
-  Lds& cl = *reinterpret_cast<Lds*>(smem + kPredBytes);
+  Lds& cl = *reinterpret_cast<Lds*>(smem);
+  unsigned char* const park = smem + sizeof(Lds);          // the parked tile, each wave its own rows
   const bool use_table = MODE == kEncode && table != nullptr;
   // grid and cell table: requested now, kept in registers while the main loop owns the LDS
   constexpr int kTableChunks = kCells * kCells / 4 / (WAVES * 64);
@@ -172,7 +174,7 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
 
   // the LDS is free again: grid and table, then the tile (+ bias) parked row-major in fp32, each wave its own rows
   stage_tables();
-  float* wl = reinterpret_cast<float*>(smem) + wave * kRowsPerWave * kLdP;
+  float* wl = reinterpret_cast<float*>(park) + wave * kRowsPerWave * kLdP;
   {
     const int frow = lane & 31, fk = lane >> 5;
 #pragma unroll
@@ -191,8 +193,8 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
   __syncthreads();
 
   // Epilogue: passes of 16 groups per wave, one group per quad.
-  uint32_t sb[32] = {};
-  if constexpr (!is_rtn(NCW)) load_sign_bits(signs, head, q, sb);
+  float sf[32] = {};
+  if constexpr (!is_rtn(NCW)) load_signs(signs, head, q, sf);
   // one pass: 16 groups of this wave (rows pass*16 .. +15), inputs already in `in`
   const auto do_pass = [&](int pass, const In& in) {
     const int lrow = pass * 16 + (lane >> 2);
@@ -213,7 +215,7 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
     if constexpr (MODE == kEncode) {
 #pragma unroll
       for (int k = 0; k < 4; ++k) unpack_bf16x8(in.x[k], &v[8 * k]);
-      quantize_group<NCW>(v, p, sb, q, cl.cb, use_table ? cl.table : nullptr, active, gid, codes, scales,
+      quantize_group<NCW>(v, p, sf, q, cl.cb, use_table ? cl.table : nullptr, active, gid, codes, scales,
                           Xhat != nullptr);
       if (Xhat != nullptr && active) Storage<bf16_t>::store32(Xhat + off, v);
     } else {
@@ -222,7 +224,7 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
       } else if constexpr (WIDE) {
         // zhat of the 8 heads, added as the stages across the heads of the 1024-point transform add them for head
         // `head`: ((0 +- 1) +- (2 +- 3)) +- ((4 +- 5) +- (6 +- 7)), minus where the head's bit of that level is set
-        const float s16 = half_bits_to_float((uint16_t)in.scale);
+        const float s16 = recon_scale<true>(half_bits_to_float((uint16_t)in.scale), q);   // the quad's two lane bits only
         const float g0 = (head & 1) ? -1.0f : 1.0f, g1 = (head & 2) ? -1.0f : 1.0f, g2 = (head & 4) ? -1.0f : 1.0f;
         const WideCodes wc = wide_codes;
         if (pass + 1 < kPasses) fetch_wide(pass + 1, wide_codes);
@@ -257,15 +259,14 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
 #pragma unroll
           for (int i = 0; i < 16; ++i) v[16 * half + i] = __fmaf_rn(u1[i], g2, u0[i]);
         }
-        wht128(v, q);
-        const float norm = quad_sign(q) * Rot<true>::kNorm;
+        wht128<true>(v, q);
 #pragma unroll
-        for (int r = 0; r < 32; ++r) v[r] = __uint_as_float(__float_as_uint(v[r] * norm) ^ sb[r]) + p[r];
+        for (int r = 0; r < 32; ++r) v[r] = __fmaf_rn(v[r], sf[r], p[r]);
       } else {
         int idx[16];
         unpack_codes<NCW>(in.code, idx);
-        gather_zhat(idx, half_bits_to_float((uint16_t)in.scale), cl.cb, v);
-        reconstruct(v, q, sb, p);
+        gather_zhat(idx, recon_scale(half_bits_to_float((uint16_t)in.scale), q), cl.cb, v);
+        reconstruct(v, q, sf, p);
       }
       if (Xhat != nullptr && active) Storage<bf16_t>::store32(Xhat + off, v);
       if constexpr (MODE == kWeighted) {
@@ -330,7 +331,7 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
       float mt = -INFINITY;
 #pragma unroll
       for (int w = 0; w < WAVES; ++w)
-        mt = fmaxf(mt, reinterpret_cast<const f32_alias*>(smem + (size_t)w * kRowsPerWave * kLdP * 4 + kStatBytes)[lane & 15]);
+        mt = fmaxf(mt, reinterpret_cast<const f32_alias*>(park + (size_t)w * kRowsPerWave * kLdP * 4 + kStatBytes)[lane & 15]);
       if (wave == 0 && lane < 16) reinterpret_cast<f32_alias*>(wregion + kStatBytes + 128)[lane] = mt;
 #pragma unroll
       for (int j = 0; j < 8; ++j) wf[j] = expf(wf[j] - mt);
@@ -390,16 +391,16 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
       float sum = 0.f;
 #pragma unroll
       for (int w = 0; w < WAVES; ++w)
-        sum += *reinterpret_cast<const f32_alias*>(smem + (size_t)w * kRowsPerWave * kLdP * 4 + kVBufBytes + idx * 4);
+        sum += *reinterpret_cast<const f32_alias*>(park + (size_t)w * kRowsPerWave * kLdP * 4 + kVBufBytes + idx * 4);
       part[((int64_t)tile_m * q_heads + head * rep + idx / kGroup) * kGroup + idx % kGroup] = sum;
     }
     if (pstats != nullptr && (int)threadIdx.x < rep) {
       float l = 0.f;
 #pragma unroll
       for (int w = 0; w < WAVES; ++w)
-        l += reinterpret_cast<const f32_alias*>(smem + (size_t)w * kRowsPerWave * kLdP * 4 + kStatBytes + 64)[threadIdx.x];
+        l += reinterpret_cast<const f32_alias*>(park + (size_t)w * kRowsPerWave * kLdP * 4 + kStatBytes + 64)[threadIdx.x];
       float* dst = pstats + ((int64_t)tile_m * q_heads + head * rep + threadIdx.x) * 2;
-      dst[0] = reinterpret_cast<const f32_alias*>(smem + kStatBytes + 128)[threadIdx.x];
+      dst[0] = reinterpret_cast<const f32_alias*>(park + kStatBytes + 128)[threadIdx.x];
       dst[1] = l;
     }
   }
