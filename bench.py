@@ -31,10 +31,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
-# HBM-side bytes per fused encode launch measured with rocprofv3 --pmc (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the
-# factors being what the same counters read for a 256 MiB device copy): profiles/bench_llama32_3b_pmc_counters.md.
-# Keyed by (config, n_codewords); other workloads report null.
-MEASURED_TRAFFIC_BYTES = {("llama3.2-3b", 16): (2.0 * 33035.0 + 1.0 * 18560.0) * 1024.0}
+# HBM-side bytes per fused encode launch measured with rocprofv3 --pmc (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB, the
+# factors being what the same counters read for a 256 MiB device copy): profiles/bench_llama31_8b_pmc_counters.md.
+# A constant taken from that profile, keyed by (config, n_codewords); other workloads report null.
+MEASURED_TRAFFIC_BYTES = {("llama3.1-8b", 16): (2.0 * 131530.9 + 1.0 * 74240.0) * 1024.0}
 
 
 

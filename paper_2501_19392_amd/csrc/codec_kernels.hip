@@ -34,13 +34,12 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const T* X, const fl
   float sf[32] = {};
   const bool fixed_head = kGroupsPerBlock % H == 0;
   if constexpr (!is_rtn(NCW)) {
-    if (fixed_head) load_signs(signs, (int)(((int64_t)blockIdx.x * kGroupsPerBlock + (threadIdx.x >> 2)) % H), q, sf);
+    if (fixed_head) load_signs(signs, (int)((blockIdx.x * (unsigned)kGroupsPerBlock + (threadIdx.x >> 2)) % (unsigned)H), q, sf);
   }
   for (int64_t g0 = (int64_t)blockIdx.x * kGroupsPerBlock; g0 < n_groups; g0 += (int64_t)gridDim.x * kGroupsPerBlock) {
     int64_t gid = g0 + (threadIdx.x >> 2);
     const bool active = gid < n_groups;
     if (!active) gid = n_groups - 1;                      // keep every lane in the DPP exchanges
-    const int head = (int)(gid % H);
     const int64_t off = gid * kGroup + q * kValsPerLane;
 
     float v[32], p[32];
@@ -52,7 +51,7 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const T* X, const fl
       for (int r = 0; r < 32; ++r) p[r] = 0.f;
     }
     if constexpr (!is_rtn(NCW)) {
-      if (!fixed_head) load_signs(signs, head, q, sf);
+      if (!fixed_head) load_signs(signs, (int)(gid % H), q, sf);     // (a 64-bit remainder: kept off the common path)
     }
     quantize_group<NCW, WIDE>(v, p, sf, WIDE ? (int)(threadIdx.x & 31) : q, lds.cb, table != nullptr ? lds.table : nullptr,
                               active, gid, codes, scales, Xhat != nullptr);
@@ -77,13 +76,12 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint8_t* __r
   float sf[32] = {};
   const bool fixed_head = kGroupsPerBlock % H == 0;
   if constexpr (!is_rtn(NCW)) {
-    if (fixed_head) load_signs(signs, (int)(((int64_t)blockIdx.x * kGroupsPerBlock + (threadIdx.x >> 2)) % H), q, sf);
+    if (fixed_head) load_signs(signs, (int)((blockIdx.x * (unsigned)kGroupsPerBlock + (threadIdx.x >> 2)) % (unsigned)H), q, sf);
   }
   for (int64_t g0 = (int64_t)blockIdx.x * kGroupsPerBlock; g0 < n_groups; g0 += (int64_t)gridDim.x * kGroupsPerBlock) {
     int64_t gid = g0 + (threadIdx.x >> 2);
     const bool active = gid < n_groups;
     if (!active) gid = n_groups - 1;
-    const int head = (int)(gid % H);
     const int64_t off = gid * kGroup + q * kValsPerLane;
 
     float p[32], z[32];
@@ -94,7 +92,7 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint8_t* __r
       for (int r = 0; r < 32; ++r) p[r] = 0.f;
     }
     if constexpr (!is_rtn(NCW)) {
-      if (!fixed_head) load_signs(signs, head, q, sf);
+      if (!fixed_head) load_signs(signs, (int)(gid % H), q, sf);     // (a 64-bit remainder: kept off the common path)
     }
     dequantize_group<NCW, WIDE>(z, p, sf, WIDE ? (int)(threadIdx.x & 31) : q, cb, gid, codes, scales);
     if (active) Storage<T>::store32(Xhat + off, z);
@@ -118,7 +116,7 @@ __global__ __launch_bounds__(kThreads) void attn_scores_kernel(
   float sf[32] = {};
   const bool fixed_head = kGroupsPerBlock % H == 0;
   if constexpr (!is_rtn(NCW)) {
-    if (fixed_head) load_signs(signs, (int)(((int64_t)blockIdx.x * kGroupsPerBlock + (threadIdx.x >> 2)) % H), q, sf);
+    if (fixed_head) load_signs(signs, (int)((blockIdx.x * (unsigned)kGroupsPerBlock + (threadIdx.x >> 2)) % (unsigned)H), q, sf);
   }
   const int rep = q_heads / H;
   for (int64_t g0 = (int64_t)blockIdx.x * kGroupsPerBlock; g0 < n_groups; g0 += (int64_t)gridDim.x * kGroupsPerBlock) {
@@ -139,7 +137,7 @@ __global__ __launch_bounds__(kThreads) void attn_scores_kernel(
       for (int r = 0; r < 32; ++r) p[r] = 0.f;
     }
     if constexpr (!is_rtn(NCW)) {
-      if (!fixed_head) load_signs(signs, head, q, sf);
+      if (!fixed_head) load_signs(signs, (int)(gid % H), q, sf);     // (a 64-bit remainder: kept off the common path)
     }
     dequantize_group<NCW, WIDE>(z, p, sf, WIDE ? (int)(threadIdx.x & 31) : q, cb, gid, codes, scales);
     if (Khat_out != nullptr && active) Storage<T>::store32(Khat_out + off, z);
