@@ -117,6 +117,11 @@ def build_workload(cfg, device, n_per_layer, rht_group=0, rtn_bits=0):
     return layers, Ks, Vs
 
 
+def B_workspace_bytes(layer, tokens):
+    from paper_2501_19392_amd import binding as B
+    return B.aquakv_workspace_bytes(layer, tokens)
+
+
 class Buffers:
     def __init__(self, layers, T, q_heads, device, scores_form="folded"):
         import torch
@@ -124,11 +129,12 @@ class Buffers:
         lay = layers[0]
         # reconstructions: two ping-pong pairs are all the path needs (layer l-1 and l)
         self.hat = [(lay.alloc_kv(T, device), lay.alloc_kv(T, device)) for _ in range(2)]
-        self.ws = lay.alloc_workspace(T, device)
+        big = max(layers, key=lambda l: B_workspace_bytes(l, T))          # layers differ (a first layer has no predictor)
+        self.ws = big.alloc_workspace(T, device)
         # two-stream schedule: the key chain may run ahead of the value chain, so 4 rotating pairs, one workspace
         # per chain, one event pair per layer
         self.hat4 = self.hat + [(lay.alloc_kv(T, device), lay.alloc_kv(T, device)) for _ in range(2)]
-        self.ws_v = lay.alloc_workspace(T, device)
+        self.ws_v = big.alloc_workspace(T, device)
         self.sk, self.sv = torch.cuda.Stream(device=device), torch.cuda.Stream(device=device)
         self.ev_k = [torch.cuda.Event() for _ in layers]
         self.ev_v = [torch.cuda.Event() for _ in layers]
@@ -633,7 +639,9 @@ def stage_rooflines(B, layers, Ks, Vs, buf, q, T, q_heads, reps):
 
     flops = sum(2.0 * T * D * (lay.c.d_in_k + lay.c.d_in_v) for lay in layers[1:])
     ms = timed(lambda: sweep("encode"), reps)
-    entry("encode (predicted layers)", "predict_bf16_kernel + quantize_kernel (groups across heads)" if wide and not getattr(B, "WIDE_ENCODE_FUSED", False)
+    fused_wide = wide and getattr(B, "WIDE_ENCODE_FUSED", False)
+    entry("encode (predicted layers)", "predict_bf16_kernel + quantize_kernel (groups across heads)" if wide and not fused_wide
+          else "fused_wide_encode_kernel (64 tokens x 8 heads per workgroup; + retile_w_kernel, a few us)" if fused_wide
           else "fused_kernel<encode>", "mfma", flops, ms, 2 * n_pred)
     ms = timed(lambda: sweep("decode"), reps)
     entry("decode (predicted layers)", "fused_kernel<decode>", "mfma", flops, ms, 2 * n_pred)
@@ -729,6 +737,7 @@ def layer_workload(args, config, device, steps, warmup, n_codewords=None, rht_gr
         if wide and not fused_wide:
             launches *= 2
         roofline = {"kernel": "predict_bf16_kernel + quantize_kernel per tensor (groups across heads are not fused)" if wide and not fused_wide
+                    else "fused_wide_encode_kernel (bf16 MFMA predictor + quantizer epilogue over whole tokens)" if fused_wide
                     else "fused_kernel<encode> (bf16 MFMA predictor + quantizer epilogue)", "bound": "mfma",
                     "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4),

@@ -92,10 +92,12 @@ typedef struct aquakv_layer {
                            with one scale, scales [tokens] (the grouping of the paper's
                            experiments, Sect. 4.1: 1024 values, 2.02 stored bits per
                            value; built for 8 heads of 128).  The code bytes have the
-                           same layout either way.  Encoding groups across heads is
-                           not fused with the predictor (the scale is a statistic of
-                           the whole group): the calls keep the fp32 prediction
-                           workspace also in bf16; decoding them is fused.  With vq_dim = 1: 0 or
+                           same layout either way.  In bf16 both groupings run the
+                           predictor fused with the quantizer; for groups across
+                           heads the encoder reads the predictor weights from a
+                           re-tiled copy it writes into the workspace first
+                           (kv_heads * head_dim * max(d_in_k, d_in_v) elements at
+                           the front of the workspace).  With vq_dim = 1: 0 or
                            64, the group of the round-to-nearest backbone, or 1024 =
                            the whole token of 8 heads (one (step, zero) per token).  */
   const float* codebook;   /* [n, 2] fp32 grid points (ignored when vq_dim = 1, like
@@ -132,8 +134,10 @@ int aquakv_build_search_table(const float* codebook, int32_t vq_dim, int32_t n_c
                               void* table, void* stream);
 
 /* Bytes of device workspace the three layer-level calls below need for `tokens`
- * rows (0 on invalid arguments).  It holds fp32 predictions (and a temporary
- * Khat when the caller does not ask for one) for one chunk of rows. */
+ * rows (0 on invalid arguments).  Its front part holds the fp32 predictions of one
+ * chunk of rows (fp32 layers) or the re-tiled predictor weights (bf16 layers with
+ * rotation groups across the heads; nothing for the other bf16 layers); behind it
+ * a temporary Khat for one chunk of rows when the caller does not ask for one. */
 size_t aquakv_workspace_bytes(const aquakv_layer* layer, int64_t tokens);
 
 /*
@@ -206,7 +210,8 @@ int aquakv_decode_layer(const aquakv_layer* layer, int64_t tokens,
  *                          the layer has a value predictor); Vhat (nullable) = reconstruction.
  *   aquakv_decode_values : Vhat = Q^-1(V_q) + f_value([Vhat_prev; Khat]); Khat is an INPUT.
  *   (keys only of Alg. "decode": aquakv_decode_layer with Vhat = NULL.)
- * Workspace: the fp32 prediction part of aquakv_workspace_bytes() suffices (none for fused bf16 layers).
+ * Workspace: the front part of aquakv_workspace_bytes() suffices (none for bf16 layers with groups of one head).  Two
+ * calls that run at the same time (two streams) need a workspace each.
  */
 int aquakv_encode_keys(const aquakv_layer* layer, int64_t tokens, const void* K, const void* Khat_prev,
                        uint8_t* k_codes, uint16_t* k_scales, void* Khat,

@@ -27,6 +27,9 @@ AQUAKV_OK, AQUAKV_EINVAL, AQUAKV_ENULL, AQUAKV_EALIGN, AQUAKV_EUNSUPPORTED, AQUA
 AQUAKV_BF16, AQUAKV_FP32 = 0, 1
 AQUAKV_KEY, AQUAKV_VALUE = 0, 1
 
+# rotation groups of 1024: predictor and quantizer of the encoder run as one kernel (bench.py labels its entries by it)
+WIDE_ENCODE_FUSED = True
+
 EXPORTS = [
     "aquakv_version", "aquakv_status_string", "aquakv_last_error", "aquakv_workspace_bytes",
     "aquakv_search_table_bytes", "aquakv_build_search_table",

@@ -155,9 +155,9 @@ struct Plan {
   size_t eb;          // bytes per element of the storage dtype
   size_t code_row;    // bytes of codes per token row
   int64_t chunk;      // rows per pass
-  bool fused;         // bf16, groups of one head: predictor fused with the quantizer kernels
+  bool fused;         // bf16: predictor fused with the quantizer kernels
   bool fused_dec;     // bf16: predictor fused with the inverse quantizer (also for groups across the 8 heads)
-  size_t p_bytes;     // fp32 predictions of one chunk
+  size_t p_bytes;     // front of the workspace: fp32 predictions of one chunk, or re-tiled predictor weights
   size_t khat_bytes;  // temporary Khat of one chunk
 };
 
@@ -166,11 +166,15 @@ Plan make_plan(const aquakv_layer* L, int64_t tokens) {
   pl.D = L->kv_heads * L->head_dim;
   pl.eb = elem_bytes(L->dtype);
   pl.code_row = (size_t)L->kv_heads * (L->head_dim / 2) * code_bits(L) / 8;
-  pl.fused = L->dtype == AQUAKV_BF16 && !is_wide(L);   // a fused tile is one head wide
+  pl.fused = L->dtype == AQUAKV_BF16;                  // predictor fused with the quantizer (groups of one head: a tile of one
+                                                       // head; groups across the 8 heads: a slab of 64 tokens x all heads)
   pl.fused_dec = L->dtype == AQUAKV_BF16;              // decoding needs no statistic of the whole group
   const int64_t cap = pl.fused ? kChunkRowsFused : kChunkRowsSplit;
   pl.chunk = tokens < cap ? tokens : cap;
-  pl.p_bytes = pl.fused ? 0 : (size_t)pl.chunk * pl.D * sizeof(float);
+  // front of the workspace: the fp32 predictions of a chunk (split path), or (bf16, groups across the heads) the
+  // predictor weights re-tiled for the encoder's main loop
+  const int d_in_max = L->d_in_k > L->d_in_v ? L->d_in_k : L->d_in_v;
+  pl.p_bytes = !pl.fused ? (size_t)pl.chunk * pl.D * sizeof(float) : (is_wide(L) ? (size_t)pl.D * d_in_max * pl.eb : 0);
   pl.khat_bytes = (size_t)pl.chunk * pl.D * pl.eb;
   return pl;
 }
@@ -189,10 +193,15 @@ int encode_keys_chunk(const aquakv_layer* L, const Plan& pl, int64_t r0, int64_t
   const bool has_k = L->d_in_k != 0;
   const size_t row = (size_t)pl.D * pl.eb, srow = scale_row_bytes(L);
   if (has_k && pl.fused) {
-    HIP_TRY(aquakv::launch_fused_encode(quantizer_id(L), at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb), L->d_in_k, nullptr, 0,
-                                        L->w_k, L->b_k, L->signs_k, L->codebook, L->search_table, at(K, r0, row),
-                                        static_cast<uint8_t*>(at(k_codes, r0, pl.code_row)),
-                                        static_cast<uint16_t*>(at(k_scales, r0, srow)), khat_dst, n, pl.D, stream));
+    const void* x0 = at(Khat_prev, r0, (size_t)L->d_in_k * pl.eb);
+    uint8_t* const kc = static_cast<uint8_t*>(at(k_codes, r0, pl.code_row));
+    uint16_t* const ks = static_cast<uint16_t*>(at(k_scales, r0, srow));
+    if (is_wide(L))
+      HIP_TRY(aquakv::launch_fused_encode_wide(quantizer_id(L), x0, L->d_in_k, nullptr, 0, L->w_k, Pbuf, L->b_k, L->signs_k,
+                                               L->codebook, L->search_table, at(K, r0, row), kc, ks, khat_dst, n, pl.D, stream));
+    else
+      HIP_TRY(aquakv::launch_fused_encode(quantizer_id(L), x0, L->d_in_k, nullptr, 0, L->w_k, L->b_k, L->signs_k, L->codebook,
+                                          L->search_table, at(K, r0, row), kc, ks, khat_dst, n, pl.D, stream));
     return AQUAKV_OK;
   }
   if (has_k)
@@ -213,10 +222,16 @@ int encode_values_chunk(const aquakv_layer* L, const Plan& pl, int64_t r0, int64
   const int D = pl.D;
   const size_t row = (size_t)D * pl.eb, srow = scale_row_bytes(L);
   if (has_v && pl.fused) {
-    HIP_TRY(aquakv::launch_fused_encode(quantizer_id(L), at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb), L->d_in_v - D,
-                                        khat_src, D, L->w_v, L->b_v, L->signs_v, L->codebook, L->search_table, at(V, r0, row),
-                                        static_cast<uint8_t*>(at(v_codes, r0, pl.code_row)),
-                                        static_cast<uint16_t*>(at(v_scales, r0, srow)), at(Vhat, r0, row), n, D, stream));
+    const void* x0 = at(Vhat_prev, r0, (size_t)(L->d_in_v - D) * pl.eb);
+    uint8_t* const vc = static_cast<uint8_t*>(at(v_codes, r0, pl.code_row));
+    uint16_t* const vs = static_cast<uint16_t*>(at(v_scales, r0, srow));
+    if (is_wide(L))
+      HIP_TRY(aquakv::launch_fused_encode_wide(quantizer_id(L), x0, L->d_in_v - D, khat_src, D, L->w_v, Pbuf, L->b_v,
+                                               L->signs_v, L->codebook, L->search_table, at(V, r0, row), vc, vs,
+                                               at(Vhat, r0, row), n, D, stream));
+    else
+      HIP_TRY(aquakv::launch_fused_encode(quantizer_id(L), x0, L->d_in_v - D, khat_src, D, L->w_v, L->b_v, L->signs_v,
+                                          L->codebook, L->search_table, at(V, r0, row), vc, vs, at(Vhat, r0, row), n, D, stream));
     return AQUAKV_OK;
   }
   if (has_v)
@@ -775,7 +790,7 @@ int decode_attn_scores(const aquakv_layer* L, int32_t batch, int32_t seq_len, in
   const int64_t tokens = (int64_t)batch * seq_len;
   const Plan pl = make_plan(L, tokens > 0 ? tokens : 1);
   if (form == kFormFolded) {
-    if (!(has_k && pl.fused && aquakv::folded_scores_supported(L->kv_heads, L->d_in_k, q_heads)))
+    if (!(has_k && pl.fused && !is_wide(L) && aquakv::folded_scores_supported(L->kv_heads, L->d_in_k, q_heads)))
       return fail(AQUAKV_EUNSUPPORTED, "the folded form is built for bf16 layers with 8 kv heads, a key predictor with 1024 "
                                        "inputs, rotation groups of one head and at most 64 query heads");
     if (tokens == 0) return AQUAKV_OK;

@@ -42,6 +42,12 @@ hipError_t launch_fused_encode(int n_codewords, const void* x0, int d0, const vo
                                const float* bias, const int8_t* signs, const float* codebook, const void* table,
                                const void* X, uint8_t* codes, uint16_t* scales, void* Xhat, int64_t T, int D,
                                hipStream_t stream);
+// The same for rotation groups of 1024 (8 heads): a workgroup owns 64 tokens x all heads.  `w_retiled`: device scratch of
+// 1024 * (d0 + d1) * 2 bytes, 16-byte aligned, that the call fills with the weights in the order its main loop reads them.
+hipError_t launch_fused_encode_wide(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W,
+                                    void* w_retiled, const float* bias, const int8_t* signs, const float* codebook,
+                                    const void* table, const void* X, uint8_t* codes, uint16_t* scales, void* Xhat,
+                                    int64_t T, int D, hipStream_t stream);
 hipError_t launch_fused_decode(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W,
                                const float* bias, const int8_t* signs, const float* codebook, const uint8_t* codes,
                                const uint16_t* scales, void* Xhat, int64_t T, int D, bool wide, hipStream_t stream);

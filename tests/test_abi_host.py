@@ -76,8 +76,8 @@ def test_bad_call_arguments_are_rejected_without_launching():
     L32 = layer(dtype=B.AQUAKV_FP32)
     assert B.aquakv_workspace_bytes(L32, 300) == 300 * 1024 * (4 + 4)        # fp32: predictions + Khat
     assert B.aquakv_workspace_bytes(L32, 1 << 20) == 16384 * 1024 * 8
-    Lw = layer(rht_group=1024)                                               # groups across heads: predictor not fused
-    assert B.aquakv_workspace_bytes(Lw, 300) == 300 * 1024 * (4 + 2)
+    Lw = layer(rht_group=1024)                 # groups across heads: the larger predictor's weights re-tiled + a temporary Khat
+    assert B.aquakv_workspace_bytes(Lw, 300) == 1024 * 2048 * 2 + 300 * 1024 * 2
     args = list(ENC_OK)
     assert status_of(B.aquakv_encode_layer, L, -1, *args, (FAKE, need)) == B.AQUAKV_EINVAL
     assert status_of(B.aquakv_encode_layer, L, 300, *args, (FAKE, need - 1)) == B.AQUAKV_EWORKSPACE
@@ -232,7 +232,7 @@ def test_round_to_nearest_backbone_layer_validation():
     assert B.aquakv_workspace_bytes(L, 300) == 300 * 1024 * 2                # bf16: fused like the grids
     assert B.aquakv_workspace_bytes(layer(**dict(rtn, n_codewords=16, rht_group=64)), 300) == 300 * 1024 * 2
     assert B.aquakv_workspace_bytes(layer(**dict(rtn, dtype=B.AQUAKV_FP32)), 300) == 300 * 1024 * 8
-    assert B.aquakv_workspace_bytes(layer(**dict(rtn, rht_group=1024)), 300) == 300 * 1024 * (4 + 2)   # whole-token groups: not fused
+    assert B.aquakv_workspace_bytes(layer(**dict(rtn, rht_group=1024)), 300) == 1024 * 2048 * 2 + 300 * 1024 * 2   # whole-token groups: + re-tiled weights
     assert B.aquakv_scores_workspace_bytes(layer(**dict(rtn, rht_group=1024)), 1, 32) == 0
     assert B.aquakv_scores_workspace_bytes(L, 1, 32) == 8 * 2 * 8 * 1024 + 32 * 128 * 4 + 32 * 4      # folded form as for the grids
     ws = (FAKE, 1 << 30)
