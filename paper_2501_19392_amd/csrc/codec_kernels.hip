@@ -36,19 +36,48 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const T* X, const fl
   if constexpr (!is_rtn(NCW)) {
     if (fixed_head) load_signs(signs, (int)((blockIdx.x * (unsigned)kGroupsPerBlock + (threadIdx.x >> 2)) % (unsigned)H), q, sf);
   }
-  for (int64_t g0 = (int64_t)blockIdx.x * kGroupsPerBlock; g0 < n_groups; g0 += (int64_t)gridDim.x * kGroupsPerBlock) {
+  // The rows (and the fp32 prediction) of the next round are requested before the current round is worked on: with two
+  // waves per SIMD nothing else hides the latency of these loads.
+  constexpr int kXQuads = sizeof(T) == 2 ? 4 : 8;
+  struct Rows { u32x4 x[kXQuads]; f32x4 p[8]; };
+  const auto request = [&](int64_t g0, Rows& r) {
+    int64_t gid = g0 + (threadIdx.x >> 2);
+    gid = gid < n_groups ? gid : n_groups - 1;
+    const int64_t off = gid * kGroup + q * kValsPerLane;
+    const u32x4* src = reinterpret_cast<const u32x4*>(X + off);
+#pragma unroll
+    for (int k = 0; k < kXQuads; ++k) r.x[k] = src[k];
+    if (P != nullptr) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) r.p[k] = reinterpret_cast<const f32x4*>(P + off)[k];
+    }
+  };
+  const int64_t stride = (int64_t)gridDim.x * kGroupsPerBlock;
+  Rows cur;
+  if ((int64_t)blockIdx.x * kGroupsPerBlock < n_groups) request((int64_t)blockIdx.x * kGroupsPerBlock, cur);
+  for (int64_t g0 = (int64_t)blockIdx.x * kGroupsPerBlock; g0 < n_groups; g0 += stride) {
+    Rows nxt;
+    if (g0 + stride < n_groups) request(g0 + stride, nxt);
     int64_t gid = g0 + (threadIdx.x >> 2);
     const bool active = gid < n_groups;
     if (!active) gid = n_groups - 1;                      // keep every lane in the DPP exchanges
     const int64_t off = gid * kGroup + q * kValsPerLane;
 
     float v[32], p[32];
-    Storage<T>::load32(X + off, v);
-    if (P != nullptr) {
-      load32_f32(P + off, p);
+    if constexpr (sizeof(T) == 2) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) unpack_bf16x8(cur.x[k], &v[8 * k]);
     } else {
 #pragma unroll
-      for (int r = 0; r < 32; ++r) p[r] = 0.f;
+      for (int k = 0; k < 8; ++k) {
+        v[4 * k] = __uint_as_float(cur.x[k].x); v[4 * k + 1] = __uint_as_float(cur.x[k].y);
+        v[4 * k + 2] = __uint_as_float(cur.x[k].z); v[4 * k + 3] = __uint_as_float(cur.x[k].w);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const f32x4 a = P != nullptr ? cur.p[k] : f32x4{0.f, 0.f, 0.f, 0.f};
+      p[4 * k] = a.x; p[4 * k + 1] = a.y; p[4 * k + 2] = a.z; p[4 * k + 3] = a.w;
     }
     if constexpr (!is_rtn(NCW)) {
       if (!fixed_head) load_signs(signs, (int)(gid % H), q, sf);     // (a 64-bit remainder: kept off the common path)
@@ -56,6 +85,7 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const T* X, const fl
     quantize_group<NCW, WIDE>(v, p, sf, WIDE ? (int)(threadIdx.x & 31) : q, lds.cb, table != nullptr ? lds.table : nullptr,
                               active, gid, codes, scales, Xhat != nullptr);
     if (Xhat != nullptr && active) Storage<T>::store32(Xhat + off, v);
+    cur = nxt;
   }
 }
 

@@ -539,6 +539,54 @@ def test_rotation_group_1024_across_heads(B, dtype, n):
     assert np.all(np.abs(U.np64(scores) - want) <= U.RTOL[dtype] * 0.5 * mag + 1e-30)
 
 
+@pytest.mark.parametrize("quantizer", ["n16", "n64", "n256", "rtn2", "rtn4"])
+def test_fused_encoder_for_groups_of_1024_equals_the_stage_calls(B, quantizer):
+    """Groups across the heads (Sect. 4.1): the layer-level encode runs predictor and whole-token quantizer in one
+    kernel (64 tokens x 8 heads per workgroup, the predictor weights read from a re-tiled copy in the workspace).  It
+    must give, bit for bit, what the stage calls give (aquakv_predict -> fp32 prediction -> aquakv_quantize, the route
+    the oracle comparison of test_rotation_group_1024_across_heads teacher-forces), for token counts around the 64-row
+    slab and its 32-row halves, with a bias, without the Khat output, and in place."""
+    print(f"case fused encoder, groups of 1024, {quantizer}", flush=True)
+    H, D = 8, 1024
+    kw = dict(rtn_bits=int(quantizer[3:])) if quantizer.startswith("rtn") else {}
+    n = 16 if quantizer.startswith("rtn") else int(quantizer[1:])
+    gb = torch.Generator().manual_seed(5)
+    bk, bv = torch.randn(D, generator=gb) * 0.3, torch.randn(D, generator=gb) * 0.3
+    _, lg = U.make_layers(H, "bf16", n, layer_idx=1, w_k=U.random_weights(D, D, 11, 0.7), w_v=U.random_weights(D, 2 * D, 12, 0.7),
+                          b_k=bk, b_v=bv, rht_group=1024, **kw)
+    for T in (1, 31, 32, 33, 63, 64, 65, 130, 257):
+        g = torch.Generator(device="cuda").manual_seed(100 + T)
+        mk = lambda: torch.randn(T, H, 128, generator=g, device="cuda").bfloat16()
+        K, V, Kp, Vp = mk(), mk(), mk(), mk()
+        kc, ks = lg.alloc_codes(T); vc, vs = lg.alloc_codes(T)
+        Kh, Vh = lg.alloc_kv(T), lg.alloc_kv(T)
+        for t in (kc, ks, vc, vs, Kh, Vh):
+            t.view(torch.uint8).fill_(0xAB)
+        B.aquakv_encode_layer(lg, T, K, V, Kp, Vp, kc, ks, vc, vs, Kh, Vh, lg.alloc_workspace(T))
+        # the same through the stage calls
+        P = torch.empty(T, D, dtype=torch.float32, device="cuda")
+        kc2, ks2 = lg.alloc_codes(T); vc2, vs2 = lg.alloc_codes(T)
+        Kh2, Vh2 = lg.alloc_kv(T), lg.alloc_kv(T)
+        B.aquakv_predict(lg, B.AQUAKV_KEY, T, Kp, None, P)
+        B.aquakv_quantize(lg, B.AQUAKV_KEY, T, K, P, kc2, ks2, Kh2)
+        B.aquakv_predict(lg, B.AQUAKV_VALUE, T, Vp, Kh2, P)
+        B.aquakv_quantize(lg, B.AQUAKV_VALUE, T, V, P, vc2, vs2, Vh2)
+        sync()
+        for name, a, b in (("k_codes", kc, kc2), ("k_scales", ks, ks2), ("v_codes", vc, vc2), ("v_scales", vs, vs2)):
+            assert torch.equal(a, b), (T, name)
+        assert torch.equal(bits(Kh), bits(Kh2)) and torch.equal(bits(Vh), bits(Vh2)), T
+        # without the reconstructions as outputs (the keys' then go through the workspace), and in place
+        kc3, ks3 = lg.alloc_codes(T); vc3, vs3 = lg.alloc_codes(T)
+        B.aquakv_encode_layer(lg, T, K, V, Kp, Vp, kc3, ks3, vc3, vs3, None, None, lg.alloc_workspace(T))
+        K2, V2 = K.clone(), V.clone()
+        kc4, ks4 = lg.alloc_codes(T); vc4, vs4 = lg.alloc_codes(T)
+        B.aquakv_encode_layer(lg, T, K2, V2, Kp, Vp, kc4, ks4, vc4, vs4, K2, V2, lg.alloc_workspace(T))
+        sync()
+        assert torch.equal(kc3, kc) and torch.equal(ks3, ks) and torch.equal(vc3, vc) and torch.equal(vs3, vs), T
+        assert torch.equal(kc4, kc) and torch.equal(vs4, vs) and torch.equal(bits(K2), bits(Kh)) and torch.equal(bits(V2), bits(Vh)), T
+    print("   token counts 1 .. 257: codes, scales and reconstructions equal those of the stage calls bit for bit", flush=True)
+
+
 # ------------------------------------------------------------------ fused dequant + q.k
 @pytest.mark.parametrize("dtype,n,with_pred", [("fp32", 16, True), ("bf16", 16, True), ("bf16", 64, False),
                                                ("bf16", 16, False)])
