@@ -644,7 +644,9 @@ def stage_rooflines(B, layers, Ks, Vs, buf, q, T, q_heads, reps):
           else "fused_wide_encode_kernel (64 tokens x 8 heads per workgroup; + retile_w_kernel, a few us)" if fused_wide
           else "fused_kernel<encode>", "mfma", flops, ms, 2 * n_pred)
     ms = timed(lambda: sweep("decode"), reps)
-    entry("decode (predicted layers)", "fused_kernel<decode>", "mfma", flops, ms, 2 * n_pred)
+    two = B.aquakv_decode_tile_heads(lay1, T) == 2
+    entry("decode (predicted layers)", "fused_two_heads_kernel<decode> (256 tokens x 2 heads per workgroup)" if two
+          else "fused_kernel<decode>", "mfma", flops, ms, 2 * n_pred)
     folded = B.aquakv_scores_workspace_bytes(lay1, 1, q_heads) > 0
     ms = timed(lambda: sweep("scores"), reps)
     passes = 1 if q_heads <= 32 else 2
@@ -653,7 +655,7 @@ def stage_rooflines(B, layers, Ks, Vs, buf, q, T, q_heads, reps):
         entry("q.k scores of their own (predictor folded into the query)", "fold_query_kernel + folded_scores_kernel", "hbm", nbytes, ms,
               n_pred, note="one call = both launches; the cache is read once per 4 query heads of a kv head (%d pass%s)" % (passes, "" if passes == 1 else "es"))
     else:
-        entry("q.k scores of their own (prediction recomputed)", "fused_kernel<scores>", "mfma",
+        entry("q.k scores of their own (prediction recomputed)", "fused_two_heads_kernel<scores>" if two else "fused_kernel<scores>", "mfma",
               sum(2.0 * T * D * lay.c.d_in_k for lay in layers[1:]), ms, n_pred)
     return out
 

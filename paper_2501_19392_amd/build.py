@@ -10,7 +10,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libaquakv.so")
-SOURCES = ["api.hip", "predict_gemm.hip", "codec_kernels.hip", "fused_kernels.hip", "fused_wide_encode.hip", "folded_scores.hip", "calibrate.hip",
+SOURCES = ["api.hip", "predict_gemm.hip", "codec_kernels.hip", "fused_kernels.hip", "fused_wide_encode.hip", "fused_two_heads.hip", "folded_scores.hip", "calibrate.hip",
            "weighted_values.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",

@@ -331,6 +331,13 @@ size_t aquakv_workspace_bytes(const aquakv_layer* layer, int64_t tokens) {
   return pl.p_bytes + pl.khat_bytes;
 }
 
+int aquakv_decode_tile_heads(const aquakv_layer* layer, int64_t tokens) {
+  if (check_layer(layer) != AQUAKV_OK || tokens <= 0) return 0;
+  const Plan pl = make_plan(layer, tokens);
+  if (!pl.fused_dec || layer->d_in_k == 0) return 0;
+  return !is_wide(layer) && aquakv::two_heads_pays(pl.chunk, pl.D) ? 2 : 1;
+}
+
 int aquakv_predict(const aquakv_layer* L, int which, int64_t tokens, const void* x0, const void* x1, float* P,
                    void* stream) {
   CHECK(check_layer(L));

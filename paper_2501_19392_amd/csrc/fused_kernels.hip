@@ -459,6 +459,9 @@ hipError_t launch_fused_encode(int n_codewords, const void* x0, int d0, const vo
 hipError_t launch_fused_decode(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W,
                                const float* bias, const int8_t* signs, const float* codebook, const uint8_t* codes,
                                const uint16_t* scales, void* Xhat, int64_t T, int D, bool wide, hipStream_t stream) {
+  if (!wide && two_heads_pays(T, D))
+    return launch_fused_decode_two_heads(n_codewords, x0, d0, x1, d1, W, bias, signs, codebook, codes, scales, Xhat, T, D,
+                                         stream);
   return launch<kDecode>(n_codewords, x0, d0, x1, d1, W, bias, signs, codebook, nullptr, nullptr,
                          const_cast<uint8_t*>(codes), const_cast<uint16_t*>(scales), Xhat, nullptr, 0.f, nullptr, 1, 1,
                          T, D, nullptr, nullptr, nullptr, nullptr, wide, stream);
@@ -469,6 +472,9 @@ hipError_t launch_fused_scores(int n_codewords, const void* x0, int d0, const vo
                                const uint16_t* scales, const void* q, float score_scale, float* scores, void* Khat_out,
                                int seq_len, int q_heads, int64_t T, int D, const float* rope_cos, const float* rope_sin,
                                bool wide, hipStream_t stream) {
+  if (!wide && two_heads_pays(T, D))
+    return launch_fused_scores_two_heads(n_codewords, x0, d0, W, bias, signs, codebook, codes, scales, q, score_scale,
+                                         scores, Khat_out, seq_len, q_heads, T, D, rope_cos, rope_sin, stream);
   return launch<kScores>(n_codewords, x0, d0, nullptr, 0, W, bias, signs, codebook, nullptr, nullptr,
                          const_cast<uint8_t*>(codes), const_cast<uint16_t*>(scales), Khat_out, q, score_scale, scores,
                          seq_len, q_heads, T, D, rope_cos, rope_sin, nullptr, nullptr, wide, stream);

@@ -1,0 +1,222 @@
+// Fused predictor + inverse quantizer (Alg. "decode" of the AQUA-KV paper: predictor of Sect. 3.2, backbone of
+// Sect. 2) on tiles of 256 token rows x 256 outputs = two kv heads: the shape for long token ranges.
+//
+// Same arithmetic as fused_kernels.hip (same matrix instruction and K order per output, same group bodies), hence the
+// same bits; what differs is the tile.  A workgroup of 8 wavefronts multiplies 256 x 256 (main loop in
+// gemm_two_heads.h: a third less L2 -> LDS traffic and 0.75 instead of 1.25 operand reads per matrix instruction),
+// wave w owning the 64 token rows 64 (w / 2) ... of head w % 2 of the pair.  A wave's accumulators are two blocks of
+// 32 rows; the epilogue parks one block at a time in the wave's own 32 LDS rows and decodes it in two passes of 16
+// groups (one per quad of lanes), so the LDS footprint is that of the one-head kernel.
+//
+// Half as many, twice as large workgroups: worth it when the token range still gives every CU the same number of
+// rounds (two_heads_pays).
+#include "codec_core.h"
+#include "gemm_two_heads.h"
+#include "kernels.h"
+
+namespace aquakv {
+namespace {
+
+constexpr int kLdP2 = 128 + 4;                       // padded fp32 row of a parked block
+// as in fused_kernels.hip: the upper half of a parked row has its 16-byte slots XOR-ed by 4
+__device__ __forceinline__ constexpr int park_col2(int col) {
+  const int slot = col >> 2;
+  return (((slot & 16) ? (slot ^ 4) : slot) << 2) | (col & 3);
+}
+constexpr int kPark2Bytes = kWaves2 * 32 * kLdP2 * 4;                     // 135168
+constexpr int kEpilogue2Bytes = (int)sizeof(Lds) + kPark2Bytes;
+constexpr int kFused2LdsBytes = kEpilogue2Bytes > kMainLoop2LdsBytes ? kEpilogue2Bytes : kMainLoop2LdsBytes;
+static_assert(kFused2LdsBytes <= 160 * 1024, "LDS of one CU");
+
+enum Mode2 : int { kDecode2 = 1, kScores2 = 2 };
+
+template <int NCW, int MODE>
+__global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
+    const bf16_t* __restrict__ x0, int d0, const bf16_t* __restrict__ x1, int d1, const bf16_t* __restrict__ W,
+    const float* __restrict__ bias, const int8_t* __restrict__ signs, const float* __restrict__ codebook,
+    const uint8_t* __restrict__ codes, const uint16_t* __restrict__ scales, bf16_t* Xhat,
+    const bf16_t* __restrict__ qv, float score_scale, float* __restrict__ scores, int seq_len, int q_heads, int64_t T,
+    int D, const float* __restrict__ rope_cos, const float* __restrict__ rope_sin) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[kFused2LdsBytes];
+  Lds& cl = *reinterpret_cast<Lds*>(smem);
+  constexpr int kGridPoints = is_rtn(NCW) ? 0 : NCW;
+  static_assert(kGridPoints <= kWaves2 * 64, "one grid point per thread");
+  float cb_a = 0.f, cb_b = 0.f;                      // kept in registers while the main loop owns the LDS
+  if ((int)threadIdx.x < kGridPoints) { cb_a = codebook[2 * threadIdx.x]; cb_b = codebook[2 * threadIdx.x + 1]; }
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int H = D / kGroup, H2 = D / BN2;
+  const int logical = remap_block(blockIdx.x, gridDim.x);
+  const int tile_m = logical / H2, pair = logical % H2;
+  const int64_t m0 = (int64_t)tile_m * BM2;
+  const int head = 2 * pair + (wave & 1);            // this wave's kv head
+  const int nw = head * kGroup;                      // its first output column
+  const int64_t mw = m0 + (wave >> 1) * 64;          // its first token row
+  const int q = lane & 3;                            // position in the quad that owns a group
+
+  constexpr int c = CodeBits<NCW>::c;
+  struct In { u32x4 code; uint32_t scale; };         // scale: fp16 bits (grids) or (step, zero point) (round-to-nearest)
+  constexpr int kPasses = 4;                         // 2 blocks x 2 passes of 16 groups
+  In in[kPasses];
+  const auto fetch = [&](int pi, In& in) {
+    int64_t row = mw + pi * 16 + (lane >> 2);
+    row = row < T ? row : T - 1;
+    const int64_t gid = row * H + head;
+    const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + gid * (kGroup / 2 * c / 8) + q * (2 * c));
+    in.code = u32x4{0, 0, 0, 0};
+    if constexpr (c == 4) {
+      const u32x2 v2 = *reinterpret_cast<const u32x2*>(src);
+      in.code.x = v2.x; in.code.y = v2.y;
+    } else if constexpr (c == 6) {
+      in.code.x = src[0]; in.code.y = src[1]; in.code.z = src[2];
+    } else {
+      in.code = *reinterpret_cast<const u32x4*>(src);
+    }
+    if constexpr (is_rtn(NCW)) in.scale = rtn_load_meta<false>(scales, gid, q);
+    else in.scale = scales[gid];
+  };
+
+  f32x16 acc[2][4];
+  gemm_mainloop_two_heads(smem, x0, d0, x1, d1, W, T, m0, pair * BN2, acc, [&] {
+#pragma unroll
+    for (int pi = 0; pi < kPasses; ++pi) fetch(pi, in[pi]);
+  });
+
+  // the LDS is free again: the grid, then block after block of the tile (+ bias) parked row-major in fp32
+  if ((int)threadIdx.x < kGridPoints)
+    cl.cb[threadIdx.x] = make_float4(cb_a, cb_b, -0.5f * (cb_a * cb_a + cb_b * cb_b), 0.f);
+  float* const wl = reinterpret_cast<float*>(smem + sizeof(Lds)) + wave * 32 * kLdP2;
+  float sf[32] = {};
+  if constexpr (!is_rtn(NCW)) load_signs(signs, head, q, sf);
+  float bv[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) bv[j] = bias != nullptr ? bias[nw + j * 32 + (lane & 31)] : 0.f;
+
+#pragma unroll
+  for (int blk = 0; blk < 2; ++blk) {
+    {
+      const int frow = lane & 31, fk = lane >> 5;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int lrow = (r >> 2) * 8 + fk * 4 + (r & 3);
+          wl[lrow * kLdP2 + park_col2(j * 32 + frow)] = acc[blk][j][r] + bv[j];
+        }
+      }
+    }
+    // The parked rows are the wave's own: block 1 only needs the wave's writes to have landed.  Block 0 also waits
+    // for the grid, which other waves stage.
+    if (blk == 0) {
+      __syncthreads();
+    } else {
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_wave_barrier();
+    }
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+      const In& ip = in[2 * blk + pass];
+      const int lrow = pass * 16 + (lane >> 2);
+      const int64_t row = mw + blk * 32 + lrow;
+      const bool active = row < T;
+      const int64_t rowc = active ? row : T - 1;
+      const int64_t off = rowc * D + nw + q * kValsPerLane;
+      float p[32], v[32];
+      {
+        const float* rowp = wl + lrow * kLdP2;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const f32x4 a = *reinterpret_cast<const f32x4*>(rowp + park_col2(q * kValsPerLane + 4 * k));
+          p[4 * k] = a.x; p[4 * k + 1] = a.y; p[4 * k + 2] = a.z; p[4 * k + 3] = a.w;
+        }
+      }
+      if constexpr (is_rtn(NCW)) {
+        rtn_reconstruct<NCW>(ip.code, ip.scale, p, v);
+      } else {
+        int idx[16];
+        unpack_codes<NCW>(ip.code, idx);
+        gather_zhat(idx, recon_scale(half_bits_to_float((uint16_t)ip.scale), q), cl.cb, v);
+        reconstruct(v, q, sf, p);
+      }
+      if (Xhat != nullptr && active) Storage<bf16_t>::store32(Xhat + off, v);
+      if constexpr (MODE == kScores2) {
+#pragma unroll
+        for (int r = 0; r < 32; ++r) v[r] = Storage<bf16_t>::round(v[r]);      // score the stored keys
+        const int rep = q_heads / H;
+        const int64_t b = rowc / seq_len, t = rowc % seq_len;
+        if (rope_cos != nullptr) rope128(v, q, rope_cos + t * (kGroup / 2), rope_sin + t * (kGroup / 2));   // cached before RoPE
+        for (int r = 0; r < rep; ++r) {
+          const int qh = head * rep + r;
+          float qf[32];
+          Storage<bf16_t>::load32(qv + (b * q_heads + qh) * kGroup + q * kValsPerLane, qf);
+          float s = 0.f;
+#pragma unroll
+          for (int i = 0; i < 32; ++i) s = __fmaf_rn(qf[i], v[i], s);
+          s = quad_sum(s);
+          if (active && q == 0) scores[(b * q_heads + qh) * seq_len + t] = s * score_scale;
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // every lane's reads of this block have returned before the next block overwrites the rows
+    if (blk == 0) {
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_wave_barrier();
+    }
+  }
+}
+
+template <int MODE>
+hipError_t launch2(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W, const float* bias,
+                   const int8_t* signs, const float* codebook, const uint8_t* codes, const uint16_t* scales, void* Xhat,
+                   const void* q, float score_scale, float* scores, int seq_len, int q_heads, int64_t T, int D,
+                   const float* rope_cos, const float* rope_sin, hipStream_t stream) {
+  if (T == 0) return hipSuccess;
+  if (D % BN2 != 0) return hipErrorInvalidValue;
+  const unsigned blocks = (unsigned)(((T + BM2 - 1) / BM2) * (D / BN2));
+#define AQUAKV_FUSED2(N)                                                                                              \
+  fused_two_heads_kernel<N, MODE><<<blocks, kWaves2 * 64, 0, stream>>>(                                               \
+      static_cast<const bf16_t*>(x0), d0, static_cast<const bf16_t*>(x1), d1, static_cast<const bf16_t*>(W), bias,    \
+      signs, codebook, codes, scales, static_cast<bf16_t*>(Xhat), static_cast<const bf16_t*>(q), score_scale, scores, \
+      seq_len, q_heads, T, D, rope_cos, rope_sin)
+  if (n_codewords == kRtn2) AQUAKV_FUSED2(kRtn2);
+  else if (n_codewords == kRtn4) AQUAKV_FUSED2(kRtn4);
+  else if (n_codewords == 16) AQUAKV_FUSED2(16);
+  else if (n_codewords == 64) AQUAKV_FUSED2(64);
+  else AQUAKV_FUSED2(256);
+#undef AQUAKV_FUSED2
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// A CU holds one workgroup of either kernel (LDS), so a launch takes ceil(tiles / CUs) rounds.  The 256 x 256 tile
+// does twice the work per round at a better rate (measured 9 - 13 % on the main loop), the 256 x 128 tile wastes less
+// of the last round: take the large tile when its rounds cost at most as much as the small tile's.
+bool two_heads_pays(int64_t T, int D) {
+  constexpr int64_t kCUs = 256;                      // MI355X
+  if (D % BN2 != 0) return false;
+  const int64_t big = ((T + BM2 - 1) / BM2) * (D / BN2);
+  const int64_t rounds_big = (big + kCUs - 1) / kCUs, rounds_small = (2 * big + kCUs - 1) / kCUs;
+  return 2 * rounds_big <= rounds_small;
+}
+
+hipError_t launch_fused_decode_two_heads(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W,
+                                         const float* bias, const int8_t* signs, const float* codebook,
+                                         const uint8_t* codes, const uint16_t* scales, void* Xhat, int64_t T, int D,
+                                         hipStream_t stream) {
+  return launch2<kDecode2>(n_codewords, x0, d0, x1, d1, W, bias, signs, codebook, codes, scales, Xhat, nullptr, 0.f,
+                           nullptr, 1, 1, T, D, nullptr, nullptr, stream);
+}
+
+hipError_t launch_fused_scores_two_heads(int n_codewords, const void* x0, int d0, const void* W, const float* bias,
+                                         const int8_t* signs, const float* codebook, const uint8_t* codes,
+                                         const uint16_t* scales, const void* q, float score_scale, float* scores,
+                                         void* Khat_out, int seq_len, int q_heads, int64_t T, int D,
+                                         const float* rope_cos, const float* rope_sin, hipStream_t stream) {
+  return launch2<kScores2>(n_codewords, x0, d0, nullptr, 0, W, bias, signs, codebook, codes, scales, Khat_out, q,
+                           score_scale, scores, seq_len, q_heads, T, D, rope_cos, rope_sin, stream);
+}
+
+}  // namespace aquakv

@@ -587,6 +587,81 @@ def test_fused_encoder_for_groups_of_1024_equals_the_stage_calls(B, quantizer):
     print("   token counts 1 .. 257: codes, scales and reconstructions equal those of the stage calls bit for bit", flush=True)
 
 
+@pytest.mark.parametrize("H,T,quantizer", [(8, 8200, "n16"), (8, 8449, "rtn2"), (6, 11010, "n64"), (16, 4100, "n256"),
+                                           (4, 16390, "rtn4"), (8, 16384, "n64")])
+def test_two_head_tiles_give_the_bits_of_one_head_tiles(B, H, T, quantizer):
+    """Decode and the scoring call switch to tiles of 256 tokens x two heads once that costs no extra round over the
+    CUs (the token counts here; the encoder and short ranges stay on tiles of one head).  The large tile must
+    reproduce the encoder's reconstructions bit for bit (ragged last tile, workgroup counts that are and are not a
+    multiple of the 8 XCDs, with bias, all five quantizers), give the scores of the small tile bit for bit -- taken
+    from a short range of the same rows, plain and with the rotary embedding -- and the encoder itself is checked
+    against the oracle on sampled rows (grids)."""
+    print(f"case two-head tiles H={H} T={T} {quantizer}", flush=True)
+    D = H * 128
+    kw = dict(rtn_bits=int(quantizer[3:])) if quantizer.startswith("rtn") else {}
+    n = 16 if quantizer.startswith("rtn") else int(quantizer[1:])
+    gb = torch.Generator().manual_seed(6)
+    bk, bv = torch.randn(D, generator=gb) * 0.3, torch.randn(D, generator=gb) * 0.3
+    lo, lg = U.make_layers(H, "bf16", n, layer_idx=1, w_k=U.random_weights(D, D, 21, 0.7),
+                           w_v=U.random_weights(D, 2 * D, 22, 0.7), b_k=bk, b_v=bv, **kw)
+    g = torch.Generator(device="cuda").manual_seed(300 + T)
+    mk = lambda: torch.randn(T, H, 128, generator=g, device="cuda").bfloat16()
+    K, V, Kp, Vp = mk(), mk(), mk(), mk()
+    kc, ks = lg.alloc_codes(T); vc, vs = lg.alloc_codes(T)
+    Kh, Vh = lg.alloc_kv(T), lg.alloc_kv(T)
+    ws = lg.alloc_workspace(T)
+    B.aquakv_encode_layer(lg, T, K, V, Kp, Vp, kc, ks, vc, vs, Kh, Vh, ws)
+    sync()
+    out = dict(k_codes=kc, k_scales=ks, v_codes=vc, v_scales=vs, Khat=Kh, Vhat=Vh, Kp=Kp, Vp=Vp)
+    if not kw:               # (the round-to-nearest encoder has its oracle comparison in test_gpu_rtn_backbone.py)
+        for rep in check_layer_against_oracle(B, lo, lg, K, V, out, rows=sampled_rows(T, 48, 4)):
+            print(f"   {rep}", flush=True)
+    Kd, Vd = lg.alloc_kv(T), lg.alloc_kv(T)
+    for t in (Kd, Vd):
+        t.view(torch.uint8).fill_(0xAB)
+    B.aquakv_decode_layer(lg, T, kc, ks, vc, vs, Kp, Vp, Kd, Vd, ws)
+    sync()
+    assert torch.equal(bits(Kd), bits(Kh)) and torch.equal(bits(Vd), bits(Vh))
+    # scores: the whole range (large tile) against short ranges of the same rows (small tile), bit for bit
+    QH = 2 * H
+    batch, S = (2, T // 2) if T % 2 == 0 else (1, T)
+    q = synth.random_queries(batch, QH, 128, seed=17, dtype="bf16", device="cuda")
+    cos, sin = O.rope_tables(S, 128, base=500000.0)
+    cos_d = torch.from_numpy(cos.astype(np.float32)).cuda()
+    sin_d = torch.from_numpy(sin.astype(np.float32)).cuda()
+    plain = torch.full((batch, QH, S), float("nan"), dtype=torch.float32, device="cuda")
+    roped = torch.full((batch, QH, S), float("nan"), dtype=torch.float32, device="cuda")
+    Ko = lg.alloc_kv(T)
+    B.aquakv_decode_attn_scores(lg, batch, S, QH, kc, ks, Kp, q, 0.125, plain, Ko, ws)
+    B.aquakv_decode_attn_scores_rope(lg, batch, S, QH, kc, ks, Kp, q, cos_d, sin_d, 0.125, roped, None, ws)
+    sync()
+    assert torch.equal(bits(Ko), bits(Kh))
+    assert torch.isfinite(plain).all() and torch.isfinite(roped).all()
+    for b, t0, t1 in [(0, 0, 300), (batch - 1, S - 259, S)]:
+        r0, r1, n_rows = b * S + t0, b * S + t1, t1 - t0
+        cut = lambda x: x[r0:r1].contiguous()
+        sp = torch.empty(1, QH, n_rows, dtype=torch.float32, device="cuda")
+        B.aquakv_decode_attn_scores(lg, 1, n_rows, QH, cut(kc), cut(ks), cut(Kp), q[b:b + 1].contiguous(), 0.125, sp, None,
+                                    lg.alloc_workspace(n_rows))
+        sync()
+        assert torch.equal(sp[0], plain[b, :, t0:t1]), (b, t0)
+        if t0 == 0:                                   # positions of a short range start at 0
+            sr = torch.empty(1, QH, n_rows, dtype=torch.float32, device="cuda")
+            B.aquakv_decode_attn_scores_rope(lg, 1, n_rows, QH, cut(kc), cut(ks), cut(Kp), q[b:b + 1].contiguous(),
+                                             cos_d[:n_rows].contiguous(), sin_d[:n_rows].contiguous(), 0.125, sr, None,
+                                             lg.alloc_workspace(n_rows))
+            sync()
+            assert torch.equal(sr[0], roped[b, :, t0:t1]), (b, t0)
+    # and against the definition on the decoded keys, sampled rows
+    rows = sampled_rows(T, 48, 8)
+    k64 = np.repeat(U.np64(Kh[rows]), 2, axis=1)
+    qb = U.np64(q)[(rows // S).cpu().numpy()]                                   # the query of each row's sequence
+    want = 0.125 * np.einsum("tqd,tqd->tq", qb, k64)
+    mag = 0.125 * np.einsum("tqd,tqd->tq", np.abs(qb), np.abs(k64))
+    got = U.np64(plain.permute(0, 2, 1).reshape(T, QH)[rows])
+    assert np.all(np.abs(got - want) <= U.RTOL["bf16"] * mag + 1e-30)
+
+
 # ------------------------------------------------------------------ fused dequant + q.k
 @pytest.mark.parametrize("dtype,n,with_pred", [("fp32", 16, True), ("bf16", 16, True), ("bf16", 64, False),
                                                ("bf16", 16, False)])
