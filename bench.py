@@ -34,7 +34,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM-side bytes per fused encode launch measured with rocprofv3 --pmc (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB, the
 # factors being what the same counters read for a 256 MiB device copy): profiles/bench_llama31_8b_pmc_counters.md.
 # A constant taken from that profile, keyed by (config, n_codewords); other workloads report null.
-MEASURED_TRAFFIC_BYTES = {("llama3.1-8b", 16): (2.0 * 131530.9 + 1.0 * 74240.0) * 1024.0}
+MEASURED_TRAFFIC_BYTES = {("llama3.1-8b", 16): (2.0 * 110041.1 + 1.0 * 82432.5) * 1024.0}
 
 
 
@@ -322,7 +322,7 @@ def layer0_times(B, layers, Ks, Vs, buf, T, reps):
 def encode_kernel_events(B, layers, Ks, Vs, buf, T, steps):
     """HIP events (on the launch stream) around every `aquakv_encode_layer` call of `steps` passes over
     the predicted layers.  For a bf16 layer with predictors one call is exactly two launches of the
-    dominant kernel, fused_kernel<encode> (keys: K = d_in_k, then values: K = d_in_v).
+    dominant kernel, the fused encoder (keys: K = d_in_k, then values: K = d_in_v).
     Returns (predictor flops, algorithmic HBM bytes, total ms, launches)."""
     import torch
     D = layers[0].d
@@ -638,13 +638,14 @@ def stage_rooflines(B, layers, Ks, Vs, buf, q, T, q_heads, reps):
             prev = (Kh, Vh)
 
     flops = sum(2.0 * T * D * (lay.c.d_in_k + lay.c.d_in_v) for lay in layers[1:])
+    two = B.aquakv_fused_tile_heads(lay1, T) == 2
     ms = timed(lambda: sweep("encode"), reps)
     fused_wide = wide and getattr(B, "WIDE_ENCODE_FUSED", False)
     entry("encode (predicted layers)", "predict_bf16_kernel + quantize_kernel (groups across heads)" if wide and not fused_wide
           else "fused_wide_encode_kernel (64 tokens x 8 heads per workgroup; + retile_w_kernel, a few us)" if fused_wide
+          else "fused_two_heads_kernel<encode> (256 tokens x 2 heads per workgroup)" if two
           else "fused_kernel<encode>", "mfma", flops, ms, 2 * n_pred)
     ms = timed(lambda: sweep("decode"), reps)
-    two = B.aquakv_decode_tile_heads(lay1, T) == 2
     entry("decode (predicted layers)", "fused_two_heads_kernel<decode> (256 tokens x 2 heads per workgroup)" if two
           else "fused_kernel<decode>", "mfma", flops, ms, 2 * n_pred)
     folded = B.aquakv_scores_workspace_bytes(lay1, 1, q_heads) > 0
@@ -740,6 +741,8 @@ def layer_workload(args, config, device, steps, warmup, n_codewords=None, rht_gr
             launches *= 2
         roofline = {"kernel": "predict_bf16_kernel + quantize_kernel per tensor (groups across heads are not fused)" if wide and not fused_wide
                     else "fused_wide_encode_kernel (bf16 MFMA predictor + quantizer epilogue over whole tokens)" if fused_wide
+                    else "fused_two_heads_kernel<encode> (bf16 MFMA predictor + quantizer epilogue, 256 tokens x 2 heads per workgroup)"
+                    if B.aquakv_fused_tile_heads(layers[-1], T) == 2
                     else "fused_kernel<encode> (bf16 MFMA predictor + quantizer epilogue)", "bound": "mfma",
                     "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4),

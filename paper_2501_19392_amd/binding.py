@@ -31,7 +31,7 @@ AQUAKV_KEY, AQUAKV_VALUE = 0, 1
 WIDE_ENCODE_FUSED = True
 
 EXPORTS = [
-    "aquakv_version", "aquakv_status_string", "aquakv_last_error", "aquakv_workspace_bytes", "aquakv_decode_tile_heads",
+    "aquakv_version", "aquakv_status_string", "aquakv_last_error", "aquakv_workspace_bytes", "aquakv_fused_tile_heads",
     "aquakv_search_table_bytes", "aquakv_build_search_table",
     "aquakv_predict", "aquakv_quantize", "aquakv_dequantize",
     "aquakv_encode_layer", "aquakv_decode_layer", "aquakv_decode_attn_scores",
@@ -63,8 +63,8 @@ _lib.aquakv_status_string.argtypes = [ctypes.c_int]
 _lib.aquakv_last_error.restype = ctypes.c_char_p
 _lib.aquakv_workspace_bytes.restype = ctypes.c_size_t
 _lib.aquakv_workspace_bytes.argtypes = [_LP, ctypes.c_int64]
-_lib.aquakv_decode_tile_heads.restype = ctypes.c_int
-_lib.aquakv_decode_tile_heads.argtypes = [_LP, ctypes.c_int64]
+_lib.aquakv_fused_tile_heads.restype = ctypes.c_int
+_lib.aquakv_fused_tile_heads.argtypes = [_LP, ctypes.c_int64]
 _lib.aquakv_scores_workspace_bytes.restype = ctypes.c_size_t
 _lib.aquakv_scores_workspace_bytes.argtypes = [_LP, ctypes.c_int32, ctypes.c_int32]
 _lib.aquakv_search_table_bytes.restype = ctypes.c_size_t
@@ -244,8 +244,8 @@ def aquakv_workspace_bytes(layer, tokens: int) -> int:
     return int(_lib.aquakv_workspace_bytes(_layer_ref(layer), tokens))
 
 
-def aquakv_decode_tile_heads(layer, tokens: int) -> int:
-    return int(_lib.aquakv_decode_tile_heads(_layer_ref(layer), tokens))
+def aquakv_fused_tile_heads(layer, tokens: int) -> int:
+    return int(_lib.aquakv_fused_tile_heads(_layer_ref(layer), tokens))
 
 
 def aquakv_scores_workspace_bytes(layer, batch: int, q_heads: int) -> int:

@@ -331,7 +331,7 @@ size_t aquakv_workspace_bytes(const aquakv_layer* layer, int64_t tokens) {
   return pl.p_bytes + pl.khat_bytes;
 }
 
-int aquakv_decode_tile_heads(const aquakv_layer* layer, int64_t tokens) {
+int aquakv_fused_tile_heads(const aquakv_layer* layer, int64_t tokens) {
   if (check_layer(layer) != AQUAKV_OK || tokens <= 0) return 0;
   const Plan pl = make_plan(layer, tokens);
   if (!pl.fused_dec || layer->d_in_k == 0) return 0;

@@ -452,6 +452,9 @@ hipError_t launch_fused_encode(int n_codewords, const void* x0, int d0, const vo
                                const float* bias, const int8_t* signs, const float* codebook, const void* table,
                                const void* X, uint8_t* codes, uint16_t* scales, void* Xhat, int64_t T, int D,
                                hipStream_t stream) {
+  if (two_heads_pays(T, D))
+    return launch_fused_encode_two_heads(n_codewords, x0, d0, x1, d1, W, bias, signs, codebook, table, X, codes, scales,
+                                         Xhat, T, D, stream);
   return launch<kEncode>(n_codewords, x0, d0, x1, d1, W, bias, signs, codebook, table, X, codes, scales, Xhat, nullptr,
                          0.f, nullptr, 1, 1, T, D, nullptr, nullptr, nullptr, nullptr, false, stream);
 }

@@ -28,13 +28,13 @@ constexpr int kEpilogue2Bytes = (int)sizeof(Lds) + kPark2Bytes;
 constexpr int kFused2LdsBytes = kEpilogue2Bytes > kMainLoop2LdsBytes ? kEpilogue2Bytes : kMainLoop2LdsBytes;
 static_assert(kFused2LdsBytes <= 160 * 1024, "LDS of one CU");
 
-enum Mode2 : int { kDecode2 = 1, kScores2 = 2 };
+enum Mode2 : int { kEncode2 = 0, kDecode2 = 1, kScores2 = 2 };
 
 template <int NCW, int MODE>
 __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
     const bf16_t* __restrict__ x0, int d0, const bf16_t* __restrict__ x1, int d1, const bf16_t* __restrict__ W,
     const float* __restrict__ bias, const int8_t* __restrict__ signs, const float* __restrict__ codebook,
-    const uint8_t* __restrict__ codes, const uint16_t* __restrict__ scales, bf16_t* Xhat,
+    const uint32_t* __restrict__ table, const bf16_t* X, uint8_t* codes, uint16_t* scales, bf16_t* Xhat,
     const bf16_t* __restrict__ qv, float score_scale, float* __restrict__ scores, int seq_len, int q_heads, int64_t T,
     int D, const float* __restrict__ rope_cos, const float* __restrict__ rope_sin) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[kFused2LdsBytes];
@@ -43,6 +43,8 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
   static_assert(kGridPoints <= kWaves2 * 64, "one grid point per thread");
   float cb_a = 0.f, cb_b = 0.f;                      // kept in registers while the main loop owns the LDS
   if ((int)threadIdx.x < kGridPoints) { cb_a = codebook[2 * threadIdx.x]; cb_b = codebook[2 * threadIdx.x + 1]; }
+  const bool use_table = MODE == kEncode2 && !is_rtn(NCW) && table != nullptr;
+  constexpr int kTableChunks = kCells * kCells / 4 / (kWaves2 * 64);
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -56,12 +58,20 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
   const int q = lane & 3;                            // position in the quad that owns a group
 
   constexpr int c = CodeBits<NCW>::c;
-  struct In { u32x4 code; uint32_t scale; };         // scale: fp16 bits (grids) or (step, zero point) (round-to-nearest)
+  constexpr bool kEnc = MODE == kEncode2;
+  // decode: codes and scale; encode: the 32 values of the row to quantize
+  struct In { u32x4 code; uint32_t scale; u32x4 x[kEnc ? 4 : 1]; };   // scale: fp16 bits (grids) or (step, zero point) (round-to-nearest)
   constexpr int kPasses = 4;                         // 2 blocks x 2 passes of 16 groups
-  In in[kPasses];
+  In in[kEnc ? 2 : kPasses];                         // encode: this pass's and the next one's
   const auto fetch = [&](int pi, In& in) {
     int64_t row = mw + pi * 16 + (lane >> 2);
     row = row < T ? row : T - 1;
+    if constexpr (kEnc) {
+      const u32x4* src = reinterpret_cast<const u32x4*>(X + row * D + nw + q * kValsPerLane);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) in.x[k] = src[k];
+      return;
+    }
     const int64_t gid = row * H + head;
     const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + gid * (kGroup / 2 * c / 8) + q * (2 * c));
     in.code = u32x4{0, 0, 0, 0};
@@ -79,11 +89,22 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
 
   f32x16 acc[2][4];
   gemm_mainloop_two_heads(smem, x0, d0, x1, d1, W, T, m0, pair * BN2, acc, [&] {
+    if constexpr (kEnc) {
+      fetch(0, in[0]);
+    } else {
 #pragma unroll
-    for (int pi = 0; pi < kPasses; ++pi) fetch(pi, in[pi]);
+      for (int pi = 0; pi < kPasses; ++pi) fetch(pi, in[pi]);
+    }
   });
 
-  // the LDS is free again: the grid, then block after block of the tile (+ bias) parked row-major in fp32
+  // the LDS is free again: the grid (and the encoder's cell table, requested now and stored once the first block is
+  // parked), then block after block of the tile (+ bias) parked row-major in fp32
+  u32x4 table_regs[kTableChunks];
+  if (use_table) {
+#pragma unroll
+    for (int i = 0; i < kTableChunks; ++i)
+      table_regs[i] = reinterpret_cast<const u32x4*>(table)[threadIdx.x + i * kWaves2 * 64];
+  }
   if ((int)threadIdx.x < kGridPoints)
     cl.cb[threadIdx.x] = make_float4(cb_a, cb_b, -0.5f * (cb_a * cb_a + cb_b * cb_b), 0.f);
   float* const wl = reinterpret_cast<float*>(smem + sizeof(Lds)) + wave * 32 * kLdP2;
@@ -109,6 +130,11 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
     // The parked rows are the wave's own: block 1 only needs the wave's writes to have landed.  Block 0 also waits
     // for the grid, which other waves stage.
     if (blk == 0) {
+      if (use_table) {
+#pragma unroll
+        for (int i = 0; i < kTableChunks; ++i)
+          reinterpret_cast<u32x4*>(cl.table)[threadIdx.x + i * kWaves2 * 64] = table_regs[i];
+      }
       __syncthreads();
     } else {
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -116,12 +142,17 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
     }
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
-      const In& ip = in[2 * blk + pass];
+      const int pi = 2 * blk + pass;
+      const In ip = in[kEnc ? (pi & 1) : pi];
+      if constexpr (kEnc) {
+        if (pi + 1 < kPasses) fetch(pi + 1, in[(pi + 1) & 1]);      // the next pass's rows, while this one is worked on
+      }
       const int lrow = pass * 16 + (lane >> 2);
       const int64_t row = mw + blk * 32 + lrow;
       const bool active = row < T;
       const int64_t rowc = active ? row : T - 1;
       const int64_t off = rowc * D + nw + q * kValsPerLane;
+      const int64_t gid = rowc * H + head;
       float p[32], v[32];
       {
         const float* rowp = wl + lrow * kLdP2;
@@ -131,7 +162,11 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
           p[4 * k] = a.x; p[4 * k + 1] = a.y; p[4 * k + 2] = a.z; p[4 * k + 3] = a.w;
         }
       }
-      if constexpr (is_rtn(NCW)) {
+      if constexpr (kEnc) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) unpack_bf16x8(ip.x[k], &v[8 * k]);
+        quantize_group<NCW>(v, p, sf, q, cl.cb, use_table ? cl.table : nullptr, active, gid, codes, scales, Xhat != nullptr);
+      } else if constexpr (is_rtn(NCW)) {
         rtn_reconstruct<NCW>(ip.code, ip.scale, p, v);
       } else {
         int idx[16];
@@ -169,8 +204,8 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
 
 template <int MODE>
 hipError_t launch2(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W, const float* bias,
-                   const int8_t* signs, const float* codebook, const uint8_t* codes, const uint16_t* scales, void* Xhat,
-                   const void* q, float score_scale, float* scores, int seq_len, int q_heads, int64_t T, int D,
+                   const int8_t* signs, const float* codebook, const void* table, const void* X, uint8_t* codes,
+                   uint16_t* scales, void* Xhat, const void* q, float score_scale, float* scores, int seq_len, int q_heads, int64_t T, int D,
                    const float* rope_cos, const float* rope_sin, hipStream_t stream) {
   if (T == 0) return hipSuccess;
   if (D % BN2 != 0) return hipErrorInvalidValue;
@@ -178,8 +213,9 @@ hipError_t launch2(int n_codewords, const void* x0, int d0, const void* x1, int 
 #define AQUAKV_FUSED2(N)                                                                                              \
   fused_two_heads_kernel<N, MODE><<<blocks, kWaves2 * 64, 0, stream>>>(                                               \
       static_cast<const bf16_t*>(x0), d0, static_cast<const bf16_t*>(x1), d1, static_cast<const bf16_t*>(W), bias,    \
-      signs, codebook, codes, scales, static_cast<bf16_t*>(Xhat), static_cast<const bf16_t*>(q), score_scale, scores, \
-      seq_len, q_heads, T, D, rope_cos, rope_sin)
+      signs, codebook, static_cast<const uint32_t*>(table), static_cast<const bf16_t*>(X), codes, scales,              \
+      static_cast<bf16_t*>(Xhat), static_cast<const bf16_t*>(q), score_scale, scores, seq_len, q_heads, T, D, rope_cos, \
+      rope_sin)
   if (n_codewords == kRtn2) AQUAKV_FUSED2(kRtn2);
   else if (n_codewords == kRtn4) AQUAKV_FUSED2(kRtn4);
   else if (n_codewords == 16) AQUAKV_FUSED2(16);
@@ -206,8 +242,17 @@ hipError_t launch_fused_decode_two_heads(int n_codewords, const void* x0, int d0
                                          const float* bias, const int8_t* signs, const float* codebook,
                                          const uint8_t* codes, const uint16_t* scales, void* Xhat, int64_t T, int D,
                                          hipStream_t stream) {
-  return launch2<kDecode2>(n_codewords, x0, d0, x1, d1, W, bias, signs, codebook, codes, scales, Xhat, nullptr, 0.f,
-                           nullptr, 1, 1, T, D, nullptr, nullptr, stream);
+  return launch2<kDecode2>(n_codewords, x0, d0, x1, d1, W, bias, signs, codebook, nullptr, nullptr,
+                           const_cast<uint8_t*>(codes), const_cast<uint16_t*>(scales), Xhat, nullptr, 0.f, nullptr, 1, 1, T,
+                           D, nullptr, nullptr, stream);
+}
+
+hipError_t launch_fused_encode_two_heads(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W,
+                                         const float* bias, const int8_t* signs, const float* codebook, const void* table,
+                                         const void* X, uint8_t* codes, uint16_t* scales, void* Xhat, int64_t T, int D,
+                                         hipStream_t stream) {
+  return launch2<kEncode2>(n_codewords, x0, d0, x1, d1, W, bias, signs, codebook, table, X, codes, scales, Xhat, nullptr,
+                           0.f, nullptr, 1, 1, T, D, nullptr, nullptr, stream);
 }
 
 hipError_t launch_fused_scores_two_heads(int n_codewords, const void* x0, int d0, const void* W, const float* bias,
@@ -215,8 +260,9 @@ hipError_t launch_fused_scores_two_heads(int n_codewords, const void* x0, int d0
                                          const uint16_t* scales, const void* q, float score_scale, float* scores,
                                          void* Khat_out, int seq_len, int q_heads, int64_t T, int D,
                                          const float* rope_cos, const float* rope_sin, hipStream_t stream) {
-  return launch2<kScores2>(n_codewords, x0, d0, nullptr, 0, W, bias, signs, codebook, codes, scales, Khat_out, q,
-                           score_scale, scores, seq_len, q_heads, T, D, rope_cos, rope_sin, stream);
+  return launch2<kScores2>(n_codewords, x0, d0, nullptr, 0, W, bias, signs, codebook, nullptr, nullptr,
+                           const_cast<uint8_t*>(codes), const_cast<uint16_t*>(scales), Khat_out, q, score_scale, scores,
+                           seq_len, q_heads, T, D, rope_cos, rope_sin, stream);
 }
 
 }  // namespace aquakv

@@ -61,6 +61,10 @@ hipError_t launch_fused_scores(int n_codewords, const void* x0, int d0, const vo
 // loop, half as many workgroups.  launch_fused_decode / launch_fused_scores take this form by themselves when
 // two_heads_pays(T, D): when the larger tile costs no extra round over the CUs.
 bool two_heads_pays(int64_t T, int D);
+hipError_t launch_fused_encode_two_heads(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W,
+                                         const float* bias, const int8_t* signs, const float* codebook, const void* table,
+                                         const void* X, uint8_t* codes, uint16_t* scales, void* Xhat, int64_t T, int D,
+                                         hipStream_t stream);
 hipError_t launch_fused_decode_two_heads(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W,
                                          const float* bias, const int8_t* signs, const float* codebook,
                                          const uint8_t* codes, const uint16_t* scales, void* Xhat, int64_t T, int D,

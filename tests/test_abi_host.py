@@ -76,13 +76,13 @@ def test_decode_tile_rule():
     for T in (1, 256, 8192, 8193, 16384, 16385, 24576, 24577, 32768, 40000, 65536, 1 << 20):
         big = -(-min(T, 65536) // 256) * 4                    # calls are cut into chunks of 65536 rows
         want = 2 if 2 * rounds(big) <= rounds(2 * big) else 1
-        assert B.aquakv_decode_tile_heads(L, T) == want, T
-    assert [B.aquakv_decode_tile_heads(L, T) for T in (8192, 8193, 16384, 16385, 32768)] == [1, 2, 2, 1, 2]
-    assert B.aquakv_decode_tile_heads(layer(kv_heads=3, d_in_k=384, d_in_v=768), 32768) == 1      # D not a multiple of 256
-    assert B.aquakv_decode_tile_heads(layer(rht_group=1024), 32768) == 1                           # groups across the heads
-    assert B.aquakv_decode_tile_heads(layer(dtype=B.AQUAKV_FP32), 32768) == 0                      # separate kernels
-    assert B.aquakv_decode_tile_heads(layer(d_in_k=0, d_in_v=0, w_k=None, w_v=None), 32768) == 0   # no predictor
-    assert B.aquakv_decode_tile_heads(L, 0) == 0 and B.aquakv_decode_tile_heads(layer(head_dim=64), 32768) == 0
+        assert B.aquakv_fused_tile_heads(L, T) == want, T
+    assert [B.aquakv_fused_tile_heads(L, T) for T in (8192, 8193, 16384, 16385, 32768)] == [1, 2, 2, 1, 2]
+    assert B.aquakv_fused_tile_heads(layer(kv_heads=3, d_in_k=384, d_in_v=768), 32768) == 1      # D not a multiple of 256
+    assert B.aquakv_fused_tile_heads(layer(rht_group=1024), 32768) == 1                           # groups across the heads
+    assert B.aquakv_fused_tile_heads(layer(dtype=B.AQUAKV_FP32), 32768) == 0                      # separate kernels
+    assert B.aquakv_fused_tile_heads(layer(d_in_k=0, d_in_v=0, w_k=None, w_v=None), 32768) == 0   # no predictor
+    assert B.aquakv_fused_tile_heads(L, 0) == 0 and B.aquakv_fused_tile_heads(layer(head_dim=64), 32768) == 0
 
 
 def test_bad_call_arguments_are_rejected_without_launching():

@@ -590,12 +590,13 @@ def test_fused_encoder_for_groups_of_1024_equals_the_stage_calls(B, quantizer):
 @pytest.mark.parametrize("H,T,quantizer", [(8, 8200, "n16"), (8, 8449, "rtn2"), (6, 11010, "n64"), (16, 4100, "n256"),
                                            (4, 16390, "rtn4"), (8, 16384, "n64")])
 def test_two_head_tiles_give_the_bits_of_one_head_tiles(B, H, T, quantizer):
-    """Decode and the scoring call switch to tiles of 256 tokens x two heads once that costs no extra round over the
-    CUs (the token counts here; the encoder and short ranges stay on tiles of one head).  The large tile must
-    reproduce the encoder's reconstructions bit for bit (ragged last tile, workgroup counts that are and are not a
-    multiple of the 8 XCDs, with bias, all five quantizers), give the scores of the small tile bit for bit -- taken
-    from a short range of the same rows, plain and with the rotary embedding -- and the encoder itself is checked
-    against the oracle on sampled rows (grids)."""
+    """Encode, decode and the scoring call switch to tiles of 256 tokens x two heads once that costs no extra round
+    over the CUs (the token counts here; short ranges stay on tiles of one head).  The large tile must give the codes,
+    scales and reconstructions of the small tile bit for bit (short ranges of the same rows; ragged last tile,
+    workgroup counts that are and are not a multiple of the 8 XCDs, with bias, all five quantizers, without the
+    reconstruction outputs and in place), decode must reproduce the encoder's reconstructions, the scores must be
+    those of the small tile, plain and with the rotary embedding, and the encoder is checked against the oracle
+    on sampled rows (grids)."""
     print(f"case two-head tiles H={H} T={T} {quantizer}", flush=True)
     D = H * 128
     kw = dict(rtn_bits=int(quantizer[3:])) if quantizer.startswith("rtn") else {}
@@ -622,6 +623,26 @@ def test_two_head_tiles_give_the_bits_of_one_head_tiles(B, H, T, quantizer):
     B.aquakv_decode_layer(lg, T, kc, ks, vc, vs, Kp, Vp, Kd, Vd, ws)
     sync()
     assert torch.equal(bits(Kd), bits(Kh)) and torch.equal(bits(Vd), bits(Vh))
+    # the encoder on short ranges of the same rows (small tile): same codes, scales and reconstructions
+    for r0, r1 in [(0, 300), (T - 259, T)]:
+        m = r1 - r0
+        cut = lambda x: x[r0:r1].contiguous()
+        kc2, ks2 = lg.alloc_codes(m); vc2, vs2 = lg.alloc_codes(m)
+        Kh2, Vh2 = lg.alloc_kv(m), lg.alloc_kv(m)
+        B.aquakv_encode_layer(lg, m, cut(K), cut(V), cut(Kp), cut(Vp), kc2, ks2, vc2, vs2, Kh2, Vh2, lg.alloc_workspace(m))
+        sync()
+        for name, a, b in (("k_codes", kc, kc2), ("k_scales", ks, ks2), ("v_codes", vc, vc2), ("v_scales", vs, vs2)):
+            assert torch.equal(a[r0:r1], b), (r0, name)
+        assert torch.equal(bits(Kh[r0:r1]), bits(Kh2)) and torch.equal(bits(Vh[r0:r1]), bits(Vh2)), r0
+    # without the reconstructions as outputs, and in place
+    kc3, ks3 = lg.alloc_codes(T); vc3, vs3 = lg.alloc_codes(T)
+    B.aquakv_encode_layer(lg, T, K, V, Kp, Vp, kc3, ks3, vc3, vs3, None, None, ws)
+    K2, V2 = K.clone(), V.clone()
+    kc4, ks4 = lg.alloc_codes(T); vc4, vs4 = lg.alloc_codes(T)
+    B.aquakv_encode_layer(lg, T, K2, V2, Kp, Vp, kc4, ks4, vc4, vs4, K2, V2, lg.alloc_workspace(T))
+    sync()
+    assert torch.equal(kc3, kc) and torch.equal(ks3, ks) and torch.equal(vc3, vc) and torch.equal(vs3, vs)
+    assert torch.equal(kc4, kc) and torch.equal(vs4, vs) and torch.equal(bits(K2), bits(Kh)) and torch.equal(bits(V2), bits(Vh))
     # scores: the whole range (large tile) against short ranges of the same rows (small tile), bit for bit
     QH = 2 * H
     batch, S = (2, T // 2) if T % 2 == 0 else (1, T)
