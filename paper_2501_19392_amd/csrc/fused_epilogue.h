@@ -1,0 +1,102 @@
+// Pieces of the epilogue that the fused predictor kernels share (fused_kernels.hip: tiles of 256 tokens x one kv
+// head; fused_two_heads.hip: x two heads): the layout of a parked block of predictions in LDS, and the tails of
+// Alg. "decode" of the AQUA-KV paper on one rotation group per quad of lanes (groups of one head).  One copy of
+// each, so that both tiles produce the same bits by construction.
+#pragma once
+#include "codec_core.h"
+#include "gemm_core.h"
+
+namespace aquakv {
+
+constexpr int kLdP = kGroup + 4;                    // padded fp32 row of a parked block
+// Position of column `col` inside a parked row.  A quad reads 16-byte slot 8q + k of a row in
+// its k-th load; q and q+2 would be 128 B = half the banks apart and collide with the next
+// rows, so the upper half of the row has its slots XOR-ed by 4: the 16 lanes served together
+// (4 rows x 4 lanes) then touch all 64 banks once.
+__device__ __forceinline__ constexpr int park_col(int col) {
+  const int slot = col >> 2;
+  return (((slot & 16) ? (slot ^ 4) : slot) << 2) | (col & 3);
+}
+
+// One 32 x 128 block of a wave's accumulators (+ bias) -> rows 0..31 at `dst` (row stride kLdP floats).  acc[j]: the
+// 32 x 32 block of columns 32 j; the lane holds column lane % 32 and rows 8 b + 4 (lane / 32) + r in register 4 b + r.
+__device__ __forceinline__ void park_block(float* dst, const f32x16 (&acc)[4], const float (&bv)[4], int lane) {
+  const int frow = lane & 31, fk = lane >> 5;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int lrow = (r >> 2) * 8 + fk * 4 + (r & 3);
+      dst[lrow * kLdP + park_col(j * 32 + frow)] = acc[j][r] + bv[j];
+    }
+}
+
+// the 32 predictions of quad position q of a parked row
+__device__ __forceinline__ void read_parked(const float* rowp, int q, float (&p)[32]) {
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const f32x4 a = *reinterpret_cast<const f32x4*>(rowp + park_col(q * kValsPerLane + 4 * k));
+    p[4 * k] = a.x; p[4 * k + 1] = a.y; p[4 * k + 2] = a.z; p[4 * k + 3] = a.w;
+  }
+}
+
+// the lane's share of a group's codes (and of its scales) as the kernels hold them between request and use
+struct CodeWords { u32x4 code; uint32_t scale; };   // scale: fp16 bits (grids) or (step, zero point) (round-to-nearest)
+
+// requests the code bytes of quad position q of group gid (4 c bytes: the lane's 16 sub-vectors)
+template <int NCW>
+__device__ __forceinline__ u32x4 request_codes(const uint8_t* __restrict__ codes, int64_t gid, int q) {
+  constexpr int c = CodeBits<NCW>::c;
+  const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + gid * (kGroup / 2 * c / 8) + q * (2 * c));
+  u32x4 out = {0, 0, 0, 0};
+  if constexpr (c == 4) {
+    const u32x2 v2 = *reinterpret_cast<const u32x2*>(src);
+    out.x = v2.x; out.y = v2.y;
+  } else if constexpr (c == 6) {
+    out.x = src[0]; out.y = src[1]; out.z = src[2];
+  } else {
+    out = *reinterpret_cast<const u32x4*>(src);
+  }
+  return out;
+}
+
+// Q^-1(codes) + p for groups of one head, from the words requested earlier (unrounded, in v)
+template <int NCW>
+__device__ __forceinline__ void decode_from_words(const CodeWords& w, const float (&p)[32], const float (&sf)[32], int q,
+                                                  const float4* cb, float (&v)[32]) {
+  if constexpr (is_rtn(NCW)) {
+    rtn_reconstruct<NCW>(w.code, w.scale, p, v);
+  } else {
+    int idx[16];
+    unpack_codes<NCW>(w.code, idx);
+    gather_zhat(idx, recon_scale(half_bits_to_float((uint16_t)w.scale), q), cb, v);
+    reconstruct(v, q, sf, p);
+  }
+}
+
+// Grouped-query scores of one decoded key row of kv head `head` (the quad's 4 x 32 values in v, unrounded):
+//   scores[b, qh, t] = score_scale * sum_d q[b, qh, d] * round_bf16(v)[d]   for the q_heads / H query heads of the head,
+// the key rotated by its position t first when rope_cos is given (caches that hold keys from before the rotary
+// embedding, Sect. 3.3).  Row index rowc = b * seq_len + t.
+__device__ __forceinline__ void score_row(float (&v)[32], int q, int head, int H, int q_heads, int seq_len, int64_t rowc,
+                                          bool active, const bf16_t* __restrict__ qv, float score_scale,
+                                          float* __restrict__ scores, const float* __restrict__ rope_cos,
+                                          const float* __restrict__ rope_sin) {
+#pragma unroll
+  for (int r = 0; r < 32; ++r) v[r] = Storage<bf16_t>::round(v[r]);      // score the stored keys
+  const int rep = q_heads / H;
+  const int64_t b = rowc / seq_len, t = rowc % seq_len;
+  if (rope_cos != nullptr) rope128(v, q, rope_cos + t * (kGroup / 2), rope_sin + t * (kGroup / 2));
+  for (int r = 0; r < rep; ++r) {
+    const int qh = head * rep + r;
+    float qf[32];
+    Storage<bf16_t>::load32(qv + (b * q_heads + qh) * kGroup + q * kValsPerLane, qf);
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) s = __fmaf_rn(qf[i], v[i], s);
+    s = quad_sum(s);
+    if (active && q == 0) scores[(b * q_heads + qh) * seq_len + t] = s * score_scale;
+  }
+}
+
+}  // namespace aquakv

@@ -11,23 +11,15 @@
 //
 // Arithmetic is the same as in the stand-alone kernels (same main loop, same group bodies,
 // prediction carried in fp32), so fused and unfused paths give identical bits.
-#include "codec_core.h"
+#include "fused_epilogue.h"
 #include "gemm_core.h"
 #include "kernels.h"
 
 namespace aquakv {
 namespace {
 
-constexpr int kLdP = BN + 4;                        // padded fp32 row of the parked prediction tile
-// Position of column `col` inside a parked row.  A quad reads 16-byte slot 8q + k of a row in
-// its k-th load; q and q+2 would be 128 B = half the banks apart and collide with the next
-// rows, so the upper half of the row has its slots XOR-ed by 4: the 16 lanes served together
-// (4 rows x 4 lanes) then touch all 64 banks once.
-__device__ __forceinline__ constexpr int park_col(int col) {
-  const int slot = col >> 2;
-  return (((slot & 16) ? (slot ^ 4) : slot) << 2) | (col & 3);
-}
-constexpr int kPredBytes = BM * kLdP * 4;           // 135168
+static_assert(BN == kGroup, "a tile column block is one rotation group");
+constexpr int kPredBytes = BM * kLdP * 4;           // the parked tile (layout: fused_epilogue.h): 135168
 // LDS use over time: the main loop's ring of k-tiles (3 x 48 KiB), then the grid and the cell table (at the start
 // of the array, so that a grid point's slot is its LDS address) followed by the parked prediction tile, all written
 // once the main loop is done.
@@ -103,8 +95,7 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
   // What the epilogue reads from global memory (rows to quantize, or codes and scales) is
   // requested from inside the main loop, when its own last operand loads are out, so the
   // latency is covered by the remaining MFMA work.
-  constexpr int c = CodeBits<NCW>::c;
-  struct In { u32x4 x[4]; u32x4 code; uint32_t scale; };     // scale: fp16 bits (grids) or (step, zero point) (round-to-nearest)
+  struct In { u32x4 x[4]; CodeWords w; };
   constexpr int kPasses = kRowsPerWave / 16;          // passes of 16 groups per wave, one group per quad
   In in[kPasses];
   const auto fetch = [&](int pass, In& in) {
@@ -116,17 +107,9 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
       for (int k = 0; k < 4; ++k) in.x[k] = src[k];
     } else {
       const int64_t gid = row * H + head;
-      const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + gid * (kGroup / 2 * c / 8) + q * (2 * c));
-      if constexpr (c == 4) {
-        const u32x2 v2 = *reinterpret_cast<const u32x2*>(src);
-        in.code.x = v2.x; in.code.y = v2.y;
-      } else if constexpr (c == 6) {
-        in.code.x = src[0]; in.code.y = src[1]; in.code.z = src[2];
-      } else {
-        in.code = *reinterpret_cast<const u32x4*>(src);
-      }
-      if constexpr (is_rtn(NCW)) in.scale = rtn_load_meta<WIDE>(scales, gid, q);
-      else in.scale = scales[WIDE ? row : gid];
+      in.w.code = request_codes<NCW>(codes, gid, q);
+      if constexpr (is_rtn(NCW)) in.w.scale = rtn_load_meta<WIDE>(scales, gid, q);
+      else in.w.scale = scales[WIDE ? row : gid];
     }
   };
   // WIDE, grids: the code bytes of this lane's 16 sub-vector slots in each of the 8 heads of its token
@@ -136,18 +119,7 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
     int64_t row = m0 + wave * kRowsPerWave + pass * 16 + (lane >> 2);
     row = row < T ? row : T - 1;
 #pragma unroll
-    for (int hh = 0; hh < 8; ++hh) {
-      const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + (row * H + hh) * (kGroup / 2 * c / 8) + q * (2 * c));
-      wc.h[hh] = u32x4{0, 0, 0, 0};
-      if constexpr (c == 4) {
-        const u32x2 v2 = *reinterpret_cast<const u32x2*>(src);
-        wc.h[hh].x = v2.x; wc.h[hh].y = v2.y;
-      } else if constexpr (c == 6) {
-        wc.h[hh].x = src[0]; wc.h[hh].y = src[1]; wc.h[hh].z = src[2];
-      } else {
-        wc.h[hh] = *reinterpret_cast<const u32x4*>(src);
-      }
-    }
+    for (int hh = 0; hh < 8; ++hh) wc.h[hh] = request_codes<NCW>(codes, row * H + hh, q);
   };
   WideCodes wide_codes;                                  // of the pass at hand; the next pass's are fetched while it runs
 
@@ -176,19 +148,11 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
   stage_tables();
   float* wl = reinterpret_cast<float*>(park) + wave * kRowsPerWave * kLdP;
   {
-    const int frow = lane & 31, fk = lane >> 5;
+    float bv[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int col = j * 32 + frow;
-      const float bv = bias != nullptr ? bias[n0 + col] : 0.f;
+    for (int j = 0; j < 4; ++j) bv[j] = bias != nullptr ? bias[n0 + j * 32 + (lane & 31)] : 0.f;
 #pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int lrow = i * 32 + (r >> 2) * 8 + fk * 4 + (r & 3);
-          wl[lrow * kLdP + park_col(col)] = acc[i][j][r] + bv;
-        }
-    }
+    for (int i = 0; i < MI; ++i) park_block(wl + i * 32 * kLdP, acc[i], bv, lane);
   }
   __syncthreads();
 
@@ -204,14 +168,7 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
     const int64_t gid = rowc * H + head;
     const int64_t off = rowc * D + n0 + q * kValsPerLane;
     float p[32], v[32];
-    {
-      const float* rowp = wl + lrow * kLdP;
-#pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        const f32x4 a = *reinterpret_cast<const f32x4*>(rowp + park_col(q * kValsPerLane + 4 * k));
-        p[4 * k] = a.x; p[4 * k + 1] = a.y; p[4 * k + 2] = a.z; p[4 * k + 3] = a.w;
-      }
-    }
+    read_parked(wl + lrow * kLdP, q, p);
     if constexpr (MODE == kEncode) {
 #pragma unroll
       for (int k = 0; k < 4; ++k) unpack_bf16x8(in.x[k], &v[8 * k]);
@@ -219,12 +176,12 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
                           Xhat != nullptr);
       if (Xhat != nullptr && active) Storage<bf16_t>::store32(Xhat + off, v);
     } else {
-      if constexpr (is_rtn(NCW)) {
-        rtn_reconstruct<NCW>(in.code, in.scale, p, v);
-      } else if constexpr (WIDE) {
+      if constexpr (!WIDE || is_rtn(NCW)) {
+        decode_from_words<NCW>(in.w, p, sf, q, cl.cb, v);
+      } else {
         // zhat of the 8 heads, added as the stages across the heads of the 1024-point transform add them for head
         // `head`: ((0 +- 1) +- (2 +- 3)) +- ((4 +- 5) +- (6 +- 7)), minus where the head's bit of that level is set
-        const float s16 = recon_scale<true>(half_bits_to_float((uint16_t)in.scale), q);   // the quad's two lane bits only
+        const float s16 = recon_scale<true>(half_bits_to_float((uint16_t)in.w.scale), q);   // the quad's two lane bits only
         const float g0 = (head & 1) ? -1.0f : 1.0f, g1 = (head & 2) ? -1.0f : 1.0f, g2 = (head & 4) ? -1.0f : 1.0f;
         const WideCodes wc = wide_codes;
         if (pass + 1 < kPasses) fetch_wide(pass + 1, wide_codes);
@@ -262,11 +219,6 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
         wht128<true>(v, q);
 #pragma unroll
         for (int r = 0; r < 32; ++r) v[r] = __fmaf_rn(v[r], sf[r], p[r]);
-      } else {
-        int idx[16];
-        unpack_codes<NCW>(in.code, idx);
-        gather_zhat(idx, recon_scale(half_bits_to_float((uint16_t)in.scale), q), cl.cb, v);
-        reconstruct(v, q, sf, p);
       }
       if (Xhat != nullptr && active) Storage<bf16_t>::store32(Xhat + off, v);
       if constexpr (MODE == kWeighted) {
@@ -282,23 +234,8 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
           *reinterpret_cast<u32x2_alias*>(dst + 8 * k) = w2;
         }
       }
-      if constexpr (MODE == kScores) {
-#pragma unroll
-        for (int r = 0; r < 32; ++r) v[r] = Storage<bf16_t>::round(v[r]);      // score the stored keys
-        const int rep = q_heads / H;
-        const int64_t b = rowc / seq_len, t = rowc % seq_len;
-        if (rope_cos != nullptr) rope128(v, q, rope_cos + t * (kGroup / 2), rope_sin + t * (kGroup / 2));   // cached before RoPE
-        for (int r = 0; r < rep; ++r) {
-          const int qh = head * rep + r;
-          float qf[32];
-          Storage<bf16_t>::load32(qv + (b * q_heads + qh) * kGroup + q * kValsPerLane, qf);
-          float s = 0.f;
-#pragma unroll
-          for (int i = 0; i < 32; ++i) s = __fmaf_rn(qf[i], v[i], s);
-          s = quad_sum(s);
-          if (active && q == 0) scores[(b * q_heads + qh) * seq_len + t] = s * score_scale;
-        }
-      }
+      if constexpr (MODE == kScores)
+        score_row(v, q, head, H, q_heads, seq_len, rowc, active, qv, score_scale, scores, rope_cos, rope_sin);
     }
   };
 #pragma unroll

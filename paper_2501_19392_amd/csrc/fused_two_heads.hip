@@ -10,20 +10,14 @@
 //
 // Half as many, twice as large workgroups: worth it when the token range still gives every CU the same number of
 // rounds (two_heads_pays).
-#include "codec_core.h"
+#include "fused_epilogue.h"
 #include "gemm_two_heads.h"
 #include "kernels.h"
 
 namespace aquakv {
 namespace {
 
-constexpr int kLdP2 = 128 + 4;                       // padded fp32 row of a parked block
-// as in fused_kernels.hip: the upper half of a parked row has its 16-byte slots XOR-ed by 4
-__device__ __forceinline__ constexpr int park_col2(int col) {
-  const int slot = col >> 2;
-  return (((slot & 16) ? (slot ^ 4) : slot) << 2) | (col & 3);
-}
-constexpr int kPark2Bytes = kWaves2 * 32 * kLdP2 * 4;                     // 135168
+constexpr int kPark2Bytes = kWaves2 * 32 * kLdP * 4;                      // one 32-row block per wave: 135168
 constexpr int kEpilogue2Bytes = (int)sizeof(Lds) + kPark2Bytes;
 constexpr int kFused2LdsBytes = kEpilogue2Bytes > kMainLoop2LdsBytes ? kEpilogue2Bytes : kMainLoop2LdsBytes;
 static_assert(kFused2LdsBytes <= 160 * 1024, "LDS of one CU");
@@ -57,10 +51,9 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
   const int64_t mw = m0 + (wave >> 1) * 64;          // its first token row
   const int q = lane & 3;                            // position in the quad that owns a group
 
-  constexpr int c = CodeBits<NCW>::c;
   constexpr bool kEnc = MODE == kEncode2;
   // decode: codes and scale; encode: the 32 values of the row to quantize
-  struct In { u32x4 code; uint32_t scale; u32x4 x[kEnc ? 4 : 1]; };   // scale: fp16 bits (grids) or (step, zero point) (round-to-nearest)
+  struct In { CodeWords w; u32x4 x[kEnc ? 4 : 1]; };
   constexpr int kPasses = 4;                         // 2 blocks x 2 passes of 16 groups
   In in[kEnc ? 2 : kPasses];                         // encode: this pass's and the next one's
   const auto fetch = [&](int pi, In& in) {
@@ -73,18 +66,9 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
       return;
     }
     const int64_t gid = row * H + head;
-    const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + gid * (kGroup / 2 * c / 8) + q * (2 * c));
-    in.code = u32x4{0, 0, 0, 0};
-    if constexpr (c == 4) {
-      const u32x2 v2 = *reinterpret_cast<const u32x2*>(src);
-      in.code.x = v2.x; in.code.y = v2.y;
-    } else if constexpr (c == 6) {
-      in.code.x = src[0]; in.code.y = src[1]; in.code.z = src[2];
-    } else {
-      in.code = *reinterpret_cast<const u32x4*>(src);
-    }
-    if constexpr (is_rtn(NCW)) in.scale = rtn_load_meta<false>(scales, gid, q);
-    else in.scale = scales[gid];
+    in.w.code = request_codes<NCW>(codes, gid, q);
+    if constexpr (is_rtn(NCW)) in.w.scale = rtn_load_meta<false>(scales, gid, q);
+    else in.w.scale = scales[gid];
   };
 
   f32x16 acc[2][4];
@@ -107,7 +91,7 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
   }
   if ((int)threadIdx.x < kGridPoints)
     cl.cb[threadIdx.x] = make_float4(cb_a, cb_b, -0.5f * (cb_a * cb_a + cb_b * cb_b), 0.f);
-  float* const wl = reinterpret_cast<float*>(smem + sizeof(Lds)) + wave * 32 * kLdP2;
+  float* const wl = reinterpret_cast<float*>(smem + sizeof(Lds)) + wave * 32 * kLdP;
   float sf[32] = {};
   if constexpr (!is_rtn(NCW)) load_signs(signs, head, q, sf);
   float bv[4];
@@ -116,17 +100,7 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
 
 #pragma unroll
   for (int blk = 0; blk < 2; ++blk) {
-    {
-      const int frow = lane & 31, fk = lane >> 5;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int lrow = (r >> 2) * 8 + fk * 4 + (r & 3);
-          wl[lrow * kLdP2 + park_col2(j * 32 + frow)] = acc[blk][j][r] + bv[j];
-        }
-      }
-    }
+    park_block(wl, acc[blk], bv, lane);
     // The parked rows are the wave's own: block 1 only needs the wave's writes to have landed.  Block 0 also waits
     // for the grid, which other waves stage.
     if (blk == 0) {
@@ -154,44 +128,17 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
       const int64_t off = rowc * D + nw + q * kValsPerLane;
       const int64_t gid = rowc * H + head;
       float p[32], v[32];
-      {
-        const float* rowp = wl + lrow * kLdP2;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-          const f32x4 a = *reinterpret_cast<const f32x4*>(rowp + park_col2(q * kValsPerLane + 4 * k));
-          p[4 * k] = a.x; p[4 * k + 1] = a.y; p[4 * k + 2] = a.z; p[4 * k + 3] = a.w;
-        }
-      }
+      read_parked(wl + lrow * kLdP, q, p);
       if constexpr (kEnc) {
 #pragma unroll
         for (int k = 0; k < 4; ++k) unpack_bf16x8(ip.x[k], &v[8 * k]);
         quantize_group<NCW>(v, p, sf, q, cl.cb, use_table ? cl.table : nullptr, active, gid, codes, scales, Xhat != nullptr);
-      } else if constexpr (is_rtn(NCW)) {
-        rtn_reconstruct<NCW>(ip.code, ip.scale, p, v);
       } else {
-        int idx[16];
-        unpack_codes<NCW>(ip.code, idx);
-        gather_zhat(idx, recon_scale(half_bits_to_float((uint16_t)ip.scale), q), cl.cb, v);
-        reconstruct(v, q, sf, p);
+        decode_from_words<NCW>(ip.w, p, sf, q, cl.cb, v);
       }
       if (Xhat != nullptr && active) Storage<bf16_t>::store32(Xhat + off, v);
-      if constexpr (MODE == kScores2) {
-#pragma unroll
-        for (int r = 0; r < 32; ++r) v[r] = Storage<bf16_t>::round(v[r]);      // score the stored keys
-        const int rep = q_heads / H;
-        const int64_t b = rowc / seq_len, t = rowc % seq_len;
-        if (rope_cos != nullptr) rope128(v, q, rope_cos + t * (kGroup / 2), rope_sin + t * (kGroup / 2));   // cached before RoPE
-        for (int r = 0; r < rep; ++r) {
-          const int qh = head * rep + r;
-          float qf[32];
-          Storage<bf16_t>::load32(qv + (b * q_heads + qh) * kGroup + q * kValsPerLane, qf);
-          float s = 0.f;
-#pragma unroll
-          for (int i = 0; i < 32; ++i) s = __fmaf_rn(qf[i], v[i], s);
-          s = quad_sum(s);
-          if (active && q == 0) scores[(b * q_heads + qh) * seq_len + t] = s * score_scale;
-        }
-      }
+      if constexpr (MODE == kScores2)
+        score_row(v, q, head, H, q_heads, seq_len, rowc, active, qv, score_scale, scores, rope_cos, rope_sin);
       __builtin_amdgcn_sched_barrier(0);
     }
     // every lane's reads of this block have returned before the next block overwrites the rows
