@@ -183,22 +183,6 @@ __device__ __forceinline__ void unpack_codes(const u32x4 raw, int (&idx)[16]) {
   }
 }
 
-template <int NCW>
-__device__ __forceinline__ void load_codes(const uint8_t* __restrict__ codes, int64_t gid, int q, int (&idx)[16]) {
-  constexpr int c = CodeBits<NCW>::c;
-  const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + gid * (kGroup / 2 * c / 8) + q * (2 * c));
-  u32x4 raw = {0, 0, 0, 0};
-  if constexpr (c == 4) {
-    const u32x2 v = *reinterpret_cast<const u32x2*>(src);
-    raw.x = v.x; raw.y = v.y;
-  } else if constexpr (c == 6) {
-    raw.x = src[0]; raw.y = src[1]; raw.z = src[2];
-  } else {
-    raw = *reinterpret_cast<const u32x4*>(src);
-  }
-  unpack_codes<NCW>(raw, idx);
-}
-
 __device__ __forceinline__ float half_bits_to_float(uint16_t h) {
   return static_cast<float>(__builtin_bit_cast(_Float16, h));
 }
@@ -268,19 +252,6 @@ __device__ __forceinline__ void rtn_reconstruct(const u32x4 raw, uint32_t meta, 
     const int code = (int)((d[r / kPerWord] >> (BITS * (r % kPerWord))) & ((1u << BITS) - 1u));
     v[r] = __fmaf_rn((float)(code - zero), s16, p[r]);     // the product is exact: small integer x fp16
   }
-}
-
-template <int BITS>
-__device__ __forceinline__ u32x4 rtn_load_codes(const uint8_t* __restrict__ codes, int64_t gid, int q) {
-  const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + gid * (kGroup * BITS / 8) + q * (4 * BITS));
-  u32x4 raw = {0, 0, 0, 0};
-  if constexpr (BITS == 2) {
-    const u32x2 v = *reinterpret_cast<const u32x2*>(src);
-    raw.x = v.x; raw.y = v.y;
-  } else {
-    raw = *reinterpret_cast<const u32x4*>(src);
-  }
-  return raw;
 }
 
 // the (step, zero) word of the lane's group: two groups of 64 per head, or (WIDE, 8 heads) one group per token
@@ -395,20 +366,49 @@ __device__ __forceinline__ void quantize_group(float (&v)[32], const float (&p)[
   }
 }
 
-// Q^-1(codes) + p for the 32 coordinates this lane holds of group `gid` (unrounded, in z).
-template <int NCW, bool WIDE = false>
-__device__ __forceinline__ void dequantize_group(float (&z)[32], const float (&p)[32], const float (&sf)[32], int l,
-                                                 const float4* cb, int64_t gid, const uint8_t* __restrict__ codes,
-                                                 const uint16_t* __restrict__ scales) {
-  if constexpr (is_rtn(NCW)) {
-    rtn_reconstruct<NCW>(rtn_load_codes<NCW>(codes, gid, l & 3), rtn_load_meta<WIDE>(scales, gid, l & 3), p, z);
-    return;
+// the lane's share of a group's codes (and of its scales) as the kernels hold them between request and use
+struct CodeWords { u32x4 code; uint32_t scale; };   // scale: fp16 bits (grids) or (step, zero point) (round-to-nearest)
+
+// requests the code bytes of quad position q of group gid (4 c bytes: the lane's 16 sub-vectors)
+template <int NCW>
+__device__ __forceinline__ u32x4 request_codes(const uint8_t* __restrict__ codes, int64_t gid, int q) {
+  constexpr int c = CodeBits<NCW>::c;
+  const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + gid * (kGroup / 2 * c / 8) + q * (2 * c));
+  u32x4 out = {0, 0, 0, 0};
+  if constexpr (c == 4) {
+    const u32x2 v2 = *reinterpret_cast<const u32x2*>(src);
+    out.x = v2.x; out.y = v2.y;
+  } else if constexpr (c == 6) {
+    out.x = src[0]; out.y = src[1]; out.z = src[2];
+  } else {
+    out = *reinterpret_cast<const u32x4*>(src);
   }
-  int idx[16];
-  load_codes<NCW>(codes, gid, l & 3, idx);
-  const float s16 = half_bits_to_float(scales[WIDE ? gid >> 3 : gid]);
-  gather_zhat(idx, recon_scale<WIDE>(s16, l), cb, z);
-  reconstruct<WIDE>(z, l, sf, p);
+  return out;
+}
+
+// the words of quad position l % 4 of head group gid (WIDE: one scale word per token, at gid / 8)
+template <int NCW, bool WIDE = false>
+__device__ __forceinline__ CodeWords request_words(const uint8_t* __restrict__ codes, const uint16_t* __restrict__ scales,
+                                                   int64_t gid, int q) {
+  CodeWords w;
+  w.code = request_codes<NCW>(codes, gid, q);
+  if constexpr (is_rtn(NCW)) w.scale = rtn_load_meta<WIDE>(scales, gid, q);
+  else w.scale = scales[WIDE ? gid >> 3 : gid];
+  return w;
+}
+
+// Q^-1(codes) + p from the words requested earlier (unrounded, in v); l: lane % 4, or with WIDE lane % 32
+template <int NCW, bool WIDE = false>
+__device__ __forceinline__ void dequantize_words(const CodeWords& w, const float (&p)[32], const float (&sf)[32], int l,
+                                                 const float4* cb, float (&v)[32]) {
+  if constexpr (is_rtn(NCW)) {
+    rtn_reconstruct<NCW>(w.code, w.scale, p, v);
+  } else {
+    int idx[16];
+    unpack_codes<NCW>(w.code, idx);
+    gather_zhat(idx, recon_scale<WIDE>(half_bits_to_float((uint16_t)w.scale), l), cb, v);
+    reconstruct<WIDE>(v, l, sf, p);
+  }
 }
 
 }  // namespace aquakv

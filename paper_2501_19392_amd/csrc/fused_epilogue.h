@@ -40,40 +40,6 @@ __device__ __forceinline__ void read_parked(const float* rowp, int q, float (&p)
   }
 }
 
-// the lane's share of a group's codes (and of its scales) as the kernels hold them between request and use
-struct CodeWords { u32x4 code; uint32_t scale; };   // scale: fp16 bits (grids) or (step, zero point) (round-to-nearest)
-
-// requests the code bytes of quad position q of group gid (4 c bytes: the lane's 16 sub-vectors)
-template <int NCW>
-__device__ __forceinline__ u32x4 request_codes(const uint8_t* __restrict__ codes, int64_t gid, int q) {
-  constexpr int c = CodeBits<NCW>::c;
-  const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + gid * (kGroup / 2 * c / 8) + q * (2 * c));
-  u32x4 out = {0, 0, 0, 0};
-  if constexpr (c == 4) {
-    const u32x2 v2 = *reinterpret_cast<const u32x2*>(src);
-    out.x = v2.x; out.y = v2.y;
-  } else if constexpr (c == 6) {
-    out.x = src[0]; out.y = src[1]; out.z = src[2];
-  } else {
-    out = *reinterpret_cast<const u32x4*>(src);
-  }
-  return out;
-}
-
-// Q^-1(codes) + p for groups of one head, from the words requested earlier (unrounded, in v)
-template <int NCW>
-__device__ __forceinline__ void decode_from_words(const CodeWords& w, const float (&p)[32], const float (&sf)[32], int q,
-                                                  const float4* cb, float (&v)[32]) {
-  if constexpr (is_rtn(NCW)) {
-    rtn_reconstruct<NCW>(w.code, w.scale, p, v);
-  } else {
-    int idx[16];
-    unpack_codes<NCW>(w.code, idx);
-    gather_zhat(idx, recon_scale(half_bits_to_float((uint16_t)w.scale), q), cb, v);
-    reconstruct(v, q, sf, p);
-  }
-}
-
 // Grouped-query scores of one decoded key row of kv head `head` (the quad's 4 x 32 values in v, unrounded):
 //   scores[b, qh, t] = score_scale * sum_d q[b, qh, d] * round_bf16(v)[d]   for the q_heads / H query heads of the head,
 // the key rotated by its position t first when rope_cos is given (caches that hold keys from before the rotary

@@ -107,9 +107,7 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
       for (int k = 0; k < 4; ++k) in.x[k] = src[k];
     } else {
       const int64_t gid = row * H + head;
-      in.w.code = request_codes<NCW>(codes, gid, q);
-      if constexpr (is_rtn(NCW)) in.w.scale = rtn_load_meta<WIDE>(scales, gid, q);
-      else in.w.scale = scales[WIDE ? row : gid];
+      in.w = request_words<NCW, WIDE>(codes, scales, gid, q);
     }
   };
   // WIDE, grids: the code bytes of this lane's 16 sub-vector slots in each of the 8 heads of its token
@@ -177,7 +175,7 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
       if (Xhat != nullptr && active) Storage<bf16_t>::store32(Xhat + off, v);
     } else {
       if constexpr (!WIDE || is_rtn(NCW)) {
-        decode_from_words<NCW>(in.w, p, sf, q, cl.cb, v);
+        dequantize_words<NCW>(in.w, p, sf, q, cl.cb, v);
       } else {
         // zhat of the 8 heads, added as the stages across the heads of the 1024-point transform add them for head
         // `head`: ((0 +- 1) +- (2 +- 3)) +- ((4 +- 5) +- (6 +- 7)), minus where the head's bit of that level is set

@@ -66,9 +66,7 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
       return;
     }
     const int64_t gid = row * H + head;
-    in.w.code = request_codes<NCW>(codes, gid, q);
-    if constexpr (is_rtn(NCW)) in.w.scale = rtn_load_meta<false>(scales, gid, q);
-    else in.w.scale = scales[gid];
+    in.w = request_words<NCW>(codes, scales, gid, q);
   };
 
   f32x16 acc[2][4];
@@ -134,7 +132,7 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
         for (int k = 0; k < 4; ++k) unpack_bf16x8(ip.x[k], &v[8 * k]);
         quantize_group<NCW>(v, p, sf, q, cl.cb, use_table ? cl.table : nullptr, active, gid, codes, scales, Xhat != nullptr);
       } else {
-        decode_from_words<NCW>(ip.w, p, sf, q, cl.cb, v);
+        dequantize_words<NCW>(ip.w, p, sf, q, cl.cb, v);
       }
       if (Xhat != nullptr && active) Storage<bf16_t>::store32(Xhat + off, v);
       if constexpr (MODE == kScores2)
