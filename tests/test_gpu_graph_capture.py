@@ -15,7 +15,8 @@ def bits_of(t):
 
 
 @pytest.mark.parametrize("dtype,rtn_bits,T,rht_group", [("bf16", None, 515, None), ("fp32", None, 515, None), ("bf16", 2, 515, None),
-                                                       ("bf16", None, 512, None), ("bf16", None, 512, 1024)])
+                                                       ("bf16", None, 512, None), ("bf16", None, 512, 1024),
+                                                       ("bf16", None, 8459, None)])     # long enough for the tiles of two heads
 def test_layer_sweeps_replay_from_a_graph(dtype, rtn_bits, T, rht_group):
     if not torch.cuda.is_available():
         pytest.fail("no GPU visible: the gpu-marked tests must run on an MI355X")
