@@ -125,7 +125,9 @@ const char* aquakv_last_error(void);
  * Optional accelerator for the nearest-grid-point step of Sect. 2 (the paper calls the
  * encoding cost of vector quantization its practical obstacle).  The table partitions the
  * plane into cells and lists, per cell, every grid point that can be nearest somewhere in
- * it; quantize then scores only those.  The result is identical to the full search.
+ * it; quantize then scores only those (cells with more candidates than fit an entry name
+ * an overflow list kept behind the cell entries, and beyond 8 candidates fall back to the
+ * full search).  The result is identical to the full search.
  * `table` is device memory of aquakv_search_table_bytes(n) bytes, written on `stream`;
  * build it once per grid and put it into aquakv_layer.search_table.
  */

@@ -22,7 +22,30 @@ namespace aquakv {
 constexpr int kCells = 64;                   // table is kCells x kCells
 constexpr float kCellHalfRange = 4.0f;       // cells tile [-4, 4]^2
 constexpr float kCellScale = kCells / (2.0f * kCellHalfRange);   // 8 cells per unit
-constexpr uint32_t kCellFull = 0xffffffffu;  // too many candidates for the list: full search
+// Table layout (32-bit words): kCells * kCells cell entries, then kOvfLists overflow lists of two words each.
+// A cell entry lists up to 4 candidate slots, one per byte from the lowest, ascending, the last one repeated.  A cell
+// with more candidates than the kernels score per cell (3 for the 16-point grid, else 4) is CROWDED: its entry is
+// crowded_entry(n, L) = 0xFF in the top byte, the largest slot (top = (n - 1) << shift) in the two middle bytes and L
+// in the lowest, so that every byte the quantizer may score before it looks at the flag is a slot the grid array can
+// be read at (the 16-point grid never scores the top byte, the others hold 256 entries).  L = list << shift names the
+// overflow list with the cell's (up to 8) candidates, again one per byte, ascending, last repeated; L = top means no
+// list (more than 8 candidates, or no list left): the full search.  An entry is crowded iff it compares >=
+// crowded_threshold(n), which no ordinary entry does except, with 256 points, those that list point 255: such cells
+// get an overflow list as well, and the ones that list nothing else share list 0.
+constexpr int kCellWords = kCells * kCells;
+constexpr int kOvfLists = 128;
+constexpr int kOvfCand = 8;                  // candidates per overflow list
+constexpr int kTableWords = kCellWords + 2 * kOvfLists;
+__host__ __device__ constexpr int slot_shift(int n) { return n == 16 ? 4 : 0; }
+__host__ __device__ constexpr uint32_t slot_top(int n) { return (uint32_t)(n - 1) << slot_shift(n); }
+__host__ __device__ constexpr uint32_t crowded_threshold(int n) {
+  return n == 256 ? 0xFF000000u : ((slot_top(n) + 1u) << 24);
+}
+__host__ __device__ constexpr uint32_t crowded_entry(int n, uint32_t L) {
+  return 0xFF000000u | (slot_top(n) << 16) | (slot_top(n) << 8) | L;
+}
+// lists a grid of n points can name: L = list << shift must stay below top
+__host__ __device__ constexpr int ovf_capacity(int n) { return n == 16 ? 15 : (n - 1 < kOvfLists ? n - 1 : kOvfLists); }
 
 // Quantizer ids, the NCW template argument everywhere: 16 / 64 / 256 = a grid of that many points in R^2;
 // kRtn2 / kRtn4 = the uniform round-to-nearest backbone with 2 / 4 bits per value (see rtn_quantize_group).
@@ -52,7 +75,7 @@ __device__ __forceinline__ float score(float y0, float y1, const float4 c) {
 }
 
 template <int NCW> struct Slot {
-  static constexpr int kShift = NCW == 16 ? 4 : 0;          // slot = j << kShift
+  static constexpr int kShift = slot_shift(NCW);            // slot = j << kShift
 };
 // the LDS entry of a grid point from its slot (SHIFT = 4: the slot is the byte offset itself)
 template <int SHIFT> __device__ __forceinline__ float4 grid_entry(const float4* cb, int slot) {
@@ -60,8 +83,8 @@ template <int SHIFT> __device__ __forceinline__ float4 grid_entry(const float4* 
 }
 
 // Table search: score the (up to 4, ascending, last one repeated) candidates of the cell; returns the winner's slot.
-// Sets `crowded` if the cell lists too many points; the caller then redoes the lane's
-// sub-vectors with the full search in one compact rolled loop (rare; keeps the hot path small).
+// Sets `crowded` if the cell lists too many points; the caller then redoes those of the lane's
+// sub-vectors from the cell's overflow list, or with the full search (rare; keeps the hot path small).
 template <int NCW>
 __device__ __forceinline__ int search_cell(float y0, float y1, const float4* cb, const uint32_t* table,
                                            bool& crowded) {
@@ -69,7 +92,7 @@ __device__ __forceinline__ int search_cell(float y0, float y1, const float4* cb,
   const float fx = __builtin_amdgcn_fmed3f(__fmaf_rn(y0, kCellScale, 0.5f * kCells), 0.0f, kCells - 0.5f);
   const float fy = __builtin_amdgcn_fmed3f(__fmaf_rn(y1, kCellScale, 0.5f * kCells), 0.0f, kCells - 0.5f);
   const uint32_t e = table[(int)fy * kCells + (int)fx];
-  crowded = e == kCellFull;
+  crowded = e >= crowded_threshold(NCW);
   int slot = e & 0xff;
   float best = score(y0, y1, grid_entry<SH>(cb, slot));
   constexpr int kCand = NCW == 16 ? 3 : 4;       // the builder marks cells of a 16-point grid with more than 3
@@ -121,6 +144,47 @@ __device__ __forceinline__ void search_full_masked(const float (&v)[32], float i
       else idx[m] = take ? bi[m] : idx[m];
     }
   }
+}
+
+// The sub-vectors of this lane whose bit is set in `mask` sit in crowded cells: those whose cell has an overflow list
+// are decided among the list's candidates (ascending, strict comparison: the lowest index wins ties, as in the full
+// search); those without get their bit in the returned mask and are left to search_full_masked.
+template <int NCW>
+__device__ __forceinline__ uint32_t search_overflow_masked(const float (&v)[32], float inv, const float4* cb,
+                                                           const uint32_t* table, uint32_t mask, int (&idx)[16]) {
+  constexpr int SH = Slot<NCW>::kShift;
+  uint32_t full = 0;
+#pragma unroll 1
+  for (int half = 0; half < 2; ++half) {
+#pragma unroll
+    for (int m = 0; m < 8; ++m) {
+      const bool mine = (mask >> (8 * half + m)) & 1;
+      if (__builtin_amdgcn_ballot_w64(mine) != 0) {                  // somebody in the wave
+        const float y0 = (half ? v[16 + 2 * m] : v[2 * m]) * inv, y1 = (half ? v[16 + 2 * m + 1] : v[2 * m + 1]) * inv;
+        const float fx = __builtin_amdgcn_fmed3f(__fmaf_rn(y0, kCellScale, 0.5f * kCells), 0.0f, kCells - 0.5f);
+        const float fy = __builtin_amdgcn_fmed3f(__fmaf_rn(y1, kCellScale, 0.5f * kCells), 0.0f, kCells - 0.5f);
+        const uint32_t low = table[(int)fy * kCells + (int)fx] & 0xffu;
+        const bool listed = mine && low != slot_top(NCW);
+        full |= (mine && !listed) ? 1u << (8 * half + m) : 0u;
+        const uint32_t* list = table + kCellWords + 2 * (listed ? (int)(low >> SH) : 0);
+        uint64_t w = list[0] | ((uint64_t)list[1] << 32);
+        int slot = (int)(w & 0xff);
+        float best = score(y0, y1, grid_entry<SH>(cb, slot));
+#pragma unroll 1
+        for (int k = 1; k < kOvfCand; ++k) {               // (rolled: this path is rare, its size is not)
+          w >>= 8;
+          const int j = (int)(w & 0xff);
+          const float sc = score(y0, y1, grid_entry<SH>(cb, j));
+          const bool better = sc > best;
+          best = better ? sc : best;
+          slot = better ? j : slot;
+        }
+        if (half) idx[8 + m] = listed ? slot : idx[8 + m];
+        else idx[m] = listed ? slot : idx[m];
+      }
+    }
+  }
+  return full;
 }
 
 // 16 codes of c bits per lane = 4c contiguous bytes of the group's little-endian bit string.  `slot`: the 16 slots.
@@ -201,7 +265,7 @@ __device__ __forceinline__ void gather_zhat(const int (&slot)[16], float scale, 
 
 struct Lds {
   float4 cb[256];
-  uint32_t table[kCells * kCells];
+  uint32_t table[kTableWords];
 };
 
 template <int NCW>
@@ -211,11 +275,33 @@ __device__ __forceinline__ void stage_lds(Lds& lds, const float* __restrict__ co
   if (table != nullptr) {
     const u32x4* src = reinterpret_cast<const u32x4*>(table);
     u32x4* dst = reinterpret_cast<u32x4*>(lds.table);
-    for (int i = threadIdx.x; i < kCells * kCells / 4; i += blockDim.x) dst[i] = src[i];
+    for (int i = threadIdx.x; i < kTableWords / 4; i += blockDim.x) dst[i] = src[i];
   }
   __syncthreads();
 }
 
+
+// The table on its way from memory to LDS through registers (kernels that request it while their LDS is still in
+// other use): 16-byte chunk t + i * THREADS for thread t.
+template <int THREADS> struct TableRegs {
+  static constexpr int kChunks = kTableWords / 4;
+  static constexpr int kPerThread = (kChunks + THREADS - 1) / THREADS;
+  u32x4 r[kPerThread];
+  __device__ __forceinline__ void request(const uint32_t* __restrict__ table) {
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+      const int ch = (int)threadIdx.x + i * THREADS;
+      if ((i + 1) * THREADS <= kChunks || ch < kChunks) r[i] = reinterpret_cast<const u32x4*>(table)[ch];
+    }
+  }
+  __device__ __forceinline__ void store(uint32_t* lds_table) const {
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+      const int ch = (int)threadIdx.x + i * THREADS;
+      if ((i + 1) * THREADS <= kChunks || ch < kChunks) reinterpret_cast<u32x4*>(lds_table)[ch] = r[i];
+    }
+  }
+};
 
 // ------------------------------------------------------------------ uniform round-to-nearest backbone
 // Sect. 4.1 "Backbone quantization" of the paper: b-bit round-to-nearest with per-group normalisation, groups of
@@ -349,8 +435,10 @@ __device__ __forceinline__ void quantize_group(float (&v)[32], const float (&p)[
       idx[m] = search_cell<NCW>(v[2 * m] * inv, v[2 * m + 1] * inv, cb, table, crowded);
       crowded_mask |= crowded ? 1u << m : 0u;
     }
-    if (__builtin_expect(__builtin_amdgcn_ballot_w64(crowded_mask != 0) != 0, 0))
-      search_full_masked<NCW>(v, inv, cb, crowded_mask, idx);
+    if (__builtin_expect(__builtin_amdgcn_ballot_w64(crowded_mask != 0) != 0, 0)) {
+      const uint32_t full_mask = search_overflow_masked<NCW>(v, inv, cb, table, crowded_mask, idx);
+      if (__builtin_amdgcn_ballot_w64(full_mask != 0) != 0) search_full_masked<NCW>(v, inv, cb, full_mask, idx);
+    }
   } else {
 #pragma unroll
     for (int m = 0; m < 16; ++m) idx[m] = 0;

@@ -212,15 +212,12 @@ __global__ __launch_bounds__(kThreads) void attn_scores_kernel(
 }
 
 // ------------------------------------------------------------------ search table builder
-// One thread per cell.  Grid point j is dropped from a cell only if some single other point i
-// is closer by more than `eps` everywhere in the enlarged cell.  d_j(y) - d_i(y) =
-// -2 y.(C_j - C_i) + |C_j|^2 - |C_i|^2 is linear in y, so its minimum over the rectangle sits at
-// a corner; border cells reach out to +-1e30 (a clamped scale lets |y| grow without bound).
-// The list is a superset of the points that can win anywhere in the cell, also under the
-// kernels' fp32 rounding.
-__global__ void build_table_kernel(const float* __restrict__ codebook, int n, uint32_t* __restrict__ table) {
-  const int cell = blockIdx.x * blockDim.x + threadIdx.x;
-  if (cell >= kCells * kCells) return;
+// Grid point j is dropped from a cell only if some single other point i is closer by more than `eps` everywhere in
+// the enlarged cell.  d_j(y) - d_i(y) = -2 y.(C_j - C_i) + |C_j|^2 - |C_i|^2 is linear in y, so its minimum over the
+// rectangle sits at a corner; border cells reach out to +-1e30 (a clamped scale lets |y| grow without bound).
+// The list is a superset of the points that can win anywhere in the cell, also under the kernels' fp32 rounding.
+// Returns the number of candidates; the first kOvfCand of them (indices, ascending) go to cand[].
+__device__ int cell_candidates(const float* __restrict__ codebook, int n, int cell, int (&cand)[kOvfCand]) {
   const int cx = cell % kCells, cy = cell / kCells;
   const double far = 1e30;
   const double delta = 1e-4, eps = 1e-3;
@@ -229,9 +226,7 @@ __global__ void build_table_kernel(const float* __restrict__ codebook, int n, ui
   double y0 = cy == 0 ? -far : -kCellHalfRange + cy * h, y1 = cy == kCells - 1 ? far : -kCellHalfRange + (cy + 1) * h;
   x0 -= delta; y0 -= delta; x1 += delta; y1 += delta;
   const double cxs[4] = {x0, x1, x0, x1}, cys[4] = {y0, y0, y1, y1};
-  const int shift = n == 16 ? Slot<16>::kShift : 0;      // entries hold slots (codec_core.h)
-  uint32_t entry = 0;
-  int count = 0, last = 0;
+  int count = 0;
   for (int j = 0; j < n; ++j) {
     const double aj = codebook[2 * j], bj = codebook[2 * j + 1];
     bool dominated = false;
@@ -245,17 +240,78 @@ __global__ void build_table_kernel(const float* __restrict__ codebook, int n, ui
       dominated = mn > eps;
     }
     if (!dominated) {
-      if (count < 4) entry |= (uint32_t)(j << shift) << (8 * count);
-      last = j << shift;
+#pragma unroll
+      for (int k = 0; k < kOvfCand; ++k)
+        if (k == count) cand[k] = j;
       ++count;
     }
   }
-  if (count > (n == 16 ? 3 : 4)) {      // more than the kernels score per cell
-    entry = kCellFull;
-  } else {
-    for (int k = count; k < 4; ++k) entry |= (uint32_t)last << (8 * k);   // repeat the last candidate
+  return count;
+}
+
+// candidates -> `bytes` slot bytes, ascending, the last one repeated (little-endian into 32-bit words)
+__device__ void pack_candidates(const int (&cand)[kOvfCand], int count, int shift, int bytes, uint32_t (&w)[2]) {
+  w[0] = w[1] = 0;
+#pragma unroll
+  for (int k = 0; k < kOvfCand; ++k) {
+    int c = 0;
+#pragma unroll
+    for (int t = 0; t < kOvfCand; ++t)
+      if (t == (k < count ? k : count - 1)) c = cand[t];
+    if (k < bytes) w[k >> 2] |= (uint32_t)(c << shift) << (8 * (k & 3));
   }
-  table[cell] = entry;
+}
+
+// First pass, one thread per cell: the ordinary entries; cells that need an overflow list of their own are left marked
+// "full search".  With 256 points the cells that list nothing but point 255 name the shared list 0.
+__global__ void build_table_kernel(const float* __restrict__ codebook, int n, uint32_t* __restrict__ table) {
+  const int cell = blockIdx.x * blockDim.x + threadIdx.x;
+  if (cell >= kCellWords) return;
+  int cand[kOvfCand];
+  const int count = cell_candidates(codebook, n, cell, cand);
+  uint32_t w[2];
+  pack_candidates(cand, count < 4 ? count : 4, slot_shift(n), 4, w);
+  const bool ordinary = count <= (n == 16 ? 3 : 4) && w[0] < crowded_threshold(n);
+  const bool only_last = n == 256 && count == 1 && cand[0] == n - 1;
+  table[cell] = ordinary ? w[0] : crowded_entry(n, only_last ? 0u : slot_top(n));
+}
+
+// Second pass, one workgroup: the marked cells get overflow lists in cell order (a fixed table for a given grid).  A cell
+// with more than kOvfCand candidates, or one that finds no list left, stays "full search".
+__global__ __launch_bounds__(1024) void build_overflow_kernel(const float* __restrict__ codebook, int n,
+                                                              uint32_t* __restrict__ table) {
+  __shared__ int offs[1024];
+  constexpr int kPer = kCellWords / 1024;
+  const uint32_t marked = crowded_entry(n, slot_top(n));
+  int mine = 0;
+  for (int k = 0; k < kPer; ++k) mine += table[threadIdx.x * kPer + k] == marked;
+  offs[threadIdx.x] = mine;
+  __syncthreads();
+  for (int d = 1; d < 1024; d <<= 1) {                    // inclusive scan
+    const int add = (int)threadIdx.x >= d ? offs[threadIdx.x - d] : 0;
+    __syncthreads();
+    offs[threadIdx.x] += add;
+    __syncthreads();
+  }
+  const int first = n == 256 ? 1 : 0;                     // list 0 of the 256-point grid: point 255 alone
+  int list = first + offs[threadIdx.x] - mine;            // lists before this thread's cells
+  // unused lists name point 0; the shared list names the last point in every byte
+  for (int k = threadIdx.x; k < 2 * kOvfLists; k += 1024) table[kCellWords + k] = (first && k < 2) ? 0xFFFFFFFFu : 0u;
+  __syncthreads();
+  for (int k = 0; k < kPer; ++k) {
+    const int cell = threadIdx.x * kPer + k;
+    if (table[cell] != marked) continue;
+    int cand[kOvfCand];
+    const int count = cell_candidates(codebook, n, cell, cand);
+    if (count <= kOvfCand && list < ovf_capacity(n)) {
+      uint32_t w[2];
+      pack_candidates(cand, count, slot_shift(n), kOvfCand, w);
+      table[kCellWords + 2 * list] = w[0];
+      table[kCellWords + 2 * list + 1] = w[1];
+      table[cell] = crowded_entry(n, (uint32_t)list << slot_shift(n));
+    }
+    ++list;
+  }
 }
 
 // Workgroups per CU (256 CUs), the kernels grid-stride.  The quantizer holds two workgroups per CU (registers) and stages
@@ -301,7 +357,8 @@ inline unsigned blocks_for(int64_t n_groups, int per_cu) {
   } while (0)
 
 hipError_t launch_build_search_table(const float* codebook, int n_codewords, void* table, hipStream_t stream) {
-  build_table_kernel<<<kCells * kCells / 64, 64, 0, stream>>>(codebook, n_codewords, static_cast<uint32_t*>(table));
+  build_table_kernel<<<kCellWords / 64, 64, 0, stream>>>(codebook, n_codewords, static_cast<uint32_t*>(table));
+  build_overflow_kernel<<<1, 1024, 0, stream>>>(codebook, n_codewords, static_cast<uint32_t*>(table));
   return hipGetLastError();
 }
 

@@ -60,24 +60,15 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
   unsigned char* const park = smem + sizeof(Lds);          // the parked tile, each wave its own rows
   const bool use_table = MODE == kEncode && table != nullptr;
   // grid and cell table: requested now, kept in registers while the main loop owns the LDS
-  constexpr int kTableChunks = kCells * kCells / 4 / (WAVES * 64);
   static_assert(NCW <= WAVES * 64, "one grid point per thread");
   constexpr int kGridPoints = is_rtn(NCW) ? 0 : NCW;
   float cb_a = 0.f, cb_b = 0.f;
-  u32x4 table_regs[kTableChunks];
+  TableRegs<WAVES * 64> table_regs;
   if (threadIdx.x < kGridPoints) { cb_a = codebook[2 * threadIdx.x]; cb_b = codebook[2 * threadIdx.x + 1]; }
-  if (use_table) {
-#pragma unroll
-    for (int i = 0; i < kTableChunks; ++i)
-      table_regs[i] = reinterpret_cast<const u32x4*>(table)[threadIdx.x + i * WAVES * 64];
-  }
+  if (use_table) table_regs.request(table);
   const auto stage_tables = [&] {
     if (threadIdx.x < kGridPoints) cl.cb[threadIdx.x] = make_float4(cb_a, cb_b, -0.5f * (cb_a * cb_a + cb_b * cb_b), 0.f);
-    if (use_table) {
-#pragma unroll
-      for (int i = 0; i < kTableChunks; ++i)
-        reinterpret_cast<u32x4*>(cl.table)[threadIdx.x + i * WAVES * 64] = table_regs[i];
-    }
+    if (use_table) table_regs.store(cl.table);
   };
 
   const int lane = threadIdx.x & 63;

@@ -38,7 +38,6 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
   float cb_a = 0.f, cb_b = 0.f;                      // kept in registers while the main loop owns the LDS
   if ((int)threadIdx.x < kGridPoints) { cb_a = codebook[2 * threadIdx.x]; cb_b = codebook[2 * threadIdx.x + 1]; }
   const bool use_table = MODE == kEncode2 && !is_rtn(NCW) && table != nullptr;
-  constexpr int kTableChunks = kCells * kCells / 4 / (kWaves2 * 64);
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -81,12 +80,8 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
 
   // the LDS is free again: the grid (and the encoder's cell table, requested now and stored once the first block is
   // parked), then block after block of the tile (+ bias) parked row-major in fp32
-  u32x4 table_regs[kTableChunks];
-  if (use_table) {
-#pragma unroll
-    for (int i = 0; i < kTableChunks; ++i)
-      table_regs[i] = reinterpret_cast<const u32x4*>(table)[threadIdx.x + i * kWaves2 * 64];
-  }
+  TableRegs<kWaves2 * 64> table_regs;
+  if (use_table) table_regs.request(table);
   if ((int)threadIdx.x < kGridPoints)
     cl.cb[threadIdx.x] = make_float4(cb_a, cb_b, -0.5f * (cb_a * cb_a + cb_b * cb_b), 0.f);
   float* const wl = reinterpret_cast<float*>(smem + sizeof(Lds)) + wave * 32 * kLdP;
@@ -102,11 +97,7 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
     // The parked rows are the wave's own: block 1 only needs the wave's writes to have landed.  Block 0 also waits
     // for the grid, which other waves stage.
     if (blk == 0) {
-      if (use_table) {
-#pragma unroll
-        for (int i = 0; i < kTableChunks; ++i)
-          reinterpret_cast<u32x4*>(cl.table)[threadIdx.x + i * kWaves2 * 64] = table_regs[i];
-      }
+      if (use_table) table_regs.store(cl.table);
       __syncthreads();
     } else {
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");

@@ -57,17 +57,12 @@ __global__ __launch_bounds__(kSlabWaves * 64) void fused_wide_encode_kernel(
   constexpr int H = kSlabCols / kGroup;                                // 8
   const bool use_table = !is_rtn(NCW) && table != nullptr;     // (a round-to-nearest layer's grid pointers are never read)
   // grid and cell table: requested now, kept in registers while the main loop owns the LDS
-  constexpr int kTableChunks = kCells * kCells / 4 / kThreadsW;
   constexpr int kGridPoints = is_rtn(NCW) ? 0 : NCW;
   static_assert(kGridPoints <= kThreadsW, "one grid point per thread");
   float cb_a = 0.f, cb_b = 0.f;
-  u32x4 table_regs[kTableChunks];
+  TableRegs<kThreadsW> table_regs;
   if ((int)threadIdx.x < kGridPoints) { cb_a = codebook[2 * threadIdx.x]; cb_b = codebook[2 * threadIdx.x + 1]; }
-  if (use_table) {
-#pragma unroll
-    for (int i = 0; i < kTableChunks; ++i)
-      table_regs[i] = reinterpret_cast<const u32x4*>(table)[threadIdx.x + i * kThreadsW];
-  }
+  if (use_table) table_regs.request(table);
 
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
@@ -112,11 +107,7 @@ __global__ __launch_bounds__(kSlabWaves * 64) void fused_wide_encode_kernel(
     if (half == 0) {                                 // the ring is free: grid and table
       if ((int)threadIdx.x < kGridPoints)
         cl.cb[threadIdx.x] = make_float4(cb_a, cb_b, -0.5f * (cb_a * cb_a + cb_b * cb_b), 0.f);
-      if (use_table) {
-#pragma unroll
-        for (int i = 0; i < kTableChunks; ++i)
-          reinterpret_cast<u32x4*>(cl.table)[threadIdx.x + i * kThreadsW] = table_regs[i];
-      }
+      if (use_table) table_regs.store(cl.table);
     }
     __syncthreads();                                 // a token's 32 lanes read columns parked by all 8 waves
 

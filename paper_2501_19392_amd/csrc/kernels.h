@@ -19,8 +19,8 @@ hipError_t launch_quantize(int dtype, int n_codewords, const void* X, const floa
                            const float* codebook, const void* table, uint8_t* codes, uint16_t* scales, void* Xhat,
                            int64_t T, int H, bool wide, hipStream_t stream);
 
-// 64 x 64 cells x 4 candidate bytes = 16 KiB.
-constexpr size_t kSearchTableBytes = 64 * 64 * 4;
+// 64 x 64 cells x 4 candidate bytes = 16 KiB, and 128 overflow lists of 8 candidate bytes.
+constexpr size_t kSearchTableBytes = (64 * 64 + 2 * 128) * 4;     // cell entries + overflow lists (codec_core.h)
 hipError_t launch_build_search_table(const float* codebook, int n_codewords, void* table, hipStream_t stream);
 
 hipError_t launch_dequantize(int dtype, int n_codewords, const uint8_t* codes, const uint16_t* scales, const float* P,

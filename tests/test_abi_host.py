@@ -121,7 +121,7 @@ def test_bad_call_arguments_are_rejected_without_launching():
     assert status_of(B.aquakv_quantize, L, B.AQUAKV_KEY, 8, FAKE, None, None, FAKE, None) == B.AQUAKV_ENULL
     assert status_of(B.aquakv_dequantize, L, B.AQUAKV_KEY, 8, FAKE, FAKE, None, None) == B.AQUAKV_ENULL
     # search table
-    assert B.aquakv_search_table_bytes(16) == 16384 and B.aquakv_search_table_bytes(17) == 0
+    assert B.aquakv_search_table_bytes(16) == (64 * 64 + 2 * 128) * 4 and B.aquakv_search_table_bytes(17) == 0
     assert status_of(B.aquakv_build_search_table, FAKE, 2, 16, None) == B.AQUAKV_ENULL
     assert status_of(B.aquakv_build_search_table, FAKE, 2, 48, FAKE) == B.AQUAKV_EINVAL
     assert status_of(B.aquakv_build_search_table, FAKE, 3, 16, FAKE) == B.AQUAKV_EUNSUPPORTED

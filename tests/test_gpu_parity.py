@@ -132,13 +132,63 @@ def test_search_table_gives_the_codes_of_the_full_search(B, n):
         sync()
         outs.append((codes, scales))
     assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
-    # a crowded grid (many points inside one cell) must take the full-search fallback and still agree
+    # Cells with more candidates than the kernels score per cell name an overflow list (up to 8 candidates) or, beyond
+    # that, the full search.  Layout of the table words: 64 x 64 cell entries, then 128 lists of two words.
+    from paper_2501_19392_amd import binding
+    shift = 4 if n == 16 else 0
+    top = (n - 1) << shift
+    crowded = 0xFF000000 if n == 256 else (top + 1) << 24               # entries >= this are crowded
+    full_mark = 0xFF000000 | (top << 16) | (top << 8) | top
+    def split(tab):
+        w = tab.cpu().numpy().view(np.uint32)
+        assert w.size == 64 * 64 + 2 * 128
+        cells = w[:4096]
+        return cells, (cells >= crowded) & (cells != full_mark), cells == full_mark, w[4096:]
+    cells, listed, full, lists = split(lg_t.search_table)
+    print(f"   regular grid: {int(listed.sum())} cells with an overflow list, {int(full.sum())} left to the full search", flush=True)
+    assert full.sum() == 0 and listed.sum() >= {16: 1, 64: 3, 256: 12}[n]
+    for e in cells[listed]:                      # a list is ascending with its last candidate repeated
+        k = int(e & 0xff) >> shift
+        c = np.concatenate([lists[2 * k: 2 * k + 2].view(np.uint8)]).astype(int)
+        assert np.all(np.diff(c) >= 0) and np.all(c % (1 << shift) == 0) and c.max() <= top
+        assert len(set(c.tolist())) >= 2 or (n == 256 and k == 0 and c[0] == 255)      # (the list shared by the cells of point 255 alone)
+    # rows built so that their normalised rotated pairs fall into the centres of the cells with overflow lists (random
+    # inputs reach those of the 16- and 64-point grids about once in 1e8 pairs): x = s * H y / sqrt(128) with rms(y) = 1
+    from scipy.linalg import hadamard
+    Hm = hadamard(128).astype(np.float64)
+    cyx = np.argwhere(listed.reshape(64, 64))
+    centres = np.stack([-4.0 + (cyx[:, 1] + 0.5) * 0.125, -4.0 + (cyx[:, 0] + 0.5) * 0.125], 1)       # (y0, y1) per cell
+    rng = np.random.Generator(np.random.PCG64(5))
+    rows = np.zeros((256, H, 128))
+    hit = 0
+    for r in range(256):
+        for h in range(H):
+            y = np.zeros((64, 2))
+            budget, m = 128.0, 0
+            for c in centres[rng.permutation(len(centres))]:
+                if m < 40 and budget - float(c @ c) > 0.02 * (63 - m):
+                    y[m] = c; budget -= float(c @ c); m += 1
+            y[m:] = np.sqrt(budget / (2 * (64 - m))) * rng.choice([-1.0, 1.0], size=(64 - m, 2))
+            hit += m
+            sg = np.where(lg_t.signs_k.cpu().numpy().reshape(H, 128)[h] < 0, -1.0, 1.0)
+            rows[r, h] = sg * (Hm @ y.reshape(128)) / np.sqrt(128.0)
+    assert hit >= 256 * H            # at least one targeted pair per group on average
+    Xc = torch.from_numpy(rows).float().cuda()
+    got = []
+    for lg in (lg_t, lg_f):
+        codes, scales = lg.alloc_codes(256)
+        B.aquakv_quantize(lg, B.AQUAKV_KEY, 256, Xc, None, codes, scales, None)
+        sync()
+        got.append((codes, scales))
+    assert torch.equal(got[0][0], got[1][0]) and torch.equal(got[0][1], got[1][1])
+    print(f"   {hit} pairs aimed at cells with overflow lists: codes equal those of the full search", flush=True)
+    # a crowded grid (many points inside one cell) runs out of lists, takes the full-search fallback and still agrees
     C = torch.from_numpy(synth.lloyd_codebook(n)).clone()
     C[: n // 2] = C[: n // 2] * 0.01
     Cd = C.cuda()
-    from paper_2501_19392_amd import binding
     tab = binding.build_search_table(Cd)
-    assert int((tab.view(torch.int32) == -1).sum()) > 0
+    _, listed_c, full_c, _ = split(tab)
+    assert full_c.sum() > 0 and (n == 16 or listed_c.sum() > 0)
     res = []
     for t in (tab, None):
         lg = binding.Layer(H, 128, Cd, lg_t.signs_k, lg_t.signs_v, torch.float32, search_table=t)
