@@ -34,7 +34,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM-side bytes per fused encode launch measured with rocprofv3 --pmc (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB, the
 # factors being what the same counters read for a 256 MiB device copy): profiles/bench_llama31_8b_pmc_counters.md.
 # A constant taken from that profile, keyed by (config, n_codewords); other workloads report null.
-MEASURED_TRAFFIC_BYTES = {("llama3.1-8b", 16): (2.0 * 110041.1 + 1.0 * 82432.5) * 1024.0}
+MEASURED_TRAFFIC_BYTES = {("llama3.1-8b", 16): (2.0 * 110057.0 + 1.0 * 80384.3) * 1024.0}
 
 
 
