@@ -335,7 +335,7 @@ int aquakv_fused_tile_heads(const aquakv_layer* layer, int64_t tokens) {
   if (check_layer(layer) != AQUAKV_OK || tokens <= 0) return 0;
   const Plan pl = make_plan(layer, tokens);
   if (!pl.fused_dec || layer->d_in_k == 0) return 0;
-  return !is_wide(layer) && aquakv::two_heads_pays(pl.chunk, pl.D) ? 2 : 1;
+  return aquakv::two_heads_pays(pl.chunk, pl.D) ? 2 : 1;
 }
 
 int aquakv_predict(const aquakv_layer* L, int which, int64_t tokens, const void* x0, const void* x1, float* P,

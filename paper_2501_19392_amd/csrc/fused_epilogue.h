@@ -40,6 +40,60 @@ __device__ __forceinline__ void read_parked(const float* rowp, int q, float (&p)
   }
 }
 
+// Rotation groups of 1024 = the whole token of 8 heads (Sect. 4.1), decoded by a quad that holds ONE head of the token:
+// the code words of the lane's 16 sub-vector slots in each of the 8 heads ...
+template <int NCW> struct WideCodes { u32x4 h[8]; };
+template <int NCW>
+__device__ __forceinline__ void request_wide_codes(const uint8_t* __restrict__ codes, int64_t row, int q, WideCodes<NCW>& wc) {
+#pragma unroll
+  for (int hh = 0; hh < 8; ++hh) wc.h[hh] = request_codes<NCW>(codes, row * 8 + hh, q);
+}
+// ... and Q^-1 + p from them (grids): the grid points of the 8 heads, added as the stages across the heads of the
+// 1024-point transform add them for head `head`, ((0 +- 1) +- (2 +- 3)) +- ((4 +- 5) +- (6 +- 7)), minus where the
+// head's bit of that level is set (the tree of Rot<true>::iwht, so the same bits as the stand-alone kernels), then the
+// quad's own 128-point stages, sign and prediction.  scale_word: the token's fp16 scale.
+template <int NCW>
+__device__ __forceinline__ void dequantize_across_heads(const WideCodes<NCW>& wc, uint32_t scale_word, int head, int q,
+                                                        const float (&p)[32], const float (&sf)[32], const float4* cb,
+                                                        float (&v)[32]) {
+  const float s16 = recon_scale<true>(half_bits_to_float((uint16_t)scale_word), q);   // the quad's two lane bits only
+  const float g0 = (head & 1) ? -1.0f : 1.0f, g1 = (head & 2) ? -1.0f : 1.0f, g2 = (head & 4) ? -1.0f : 1.0f;
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    const auto zhat_half = [&](int hh, float (&z)[16]) {
+      int idx[16];
+      unpack_codes<NCW>(wc.h[hh], idx);
+#pragma unroll
+      for (int m = 0; m < 8; ++m) {
+        const float2 cw = *reinterpret_cast<const float2*>(&cb[idx[8 * half + m]]);
+        z[2 * m] = cw.x * s16;
+        z[2 * m + 1] = cw.y * s16;
+      }
+    };
+    const auto pair_of = [&](int hh, float (&t)[16]) {        // z[hh] +- z[hh + 1]
+      float b[16];
+      zhat_half(hh, t);
+      zhat_half(hh + 1, b);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) t[i] = __fmaf_rn(b[i], g0, t[i]);
+    };
+    float u0[16], u1[16], t[16];
+    pair_of(0, u0);
+    pair_of(2, t);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) u0[i] = __fmaf_rn(t[i], g1, u0[i]);
+    pair_of(4, u1);
+    pair_of(6, t);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) u1[i] = __fmaf_rn(t[i], g1, u1[i]);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v[16 * half + i] = __fmaf_rn(u1[i], g2, u0[i]);
+  }
+  wht128<true>(v, q);
+#pragma unroll
+  for (int r = 0; r < 32; ++r) v[r] = __fmaf_rn(v[r], sf[r], p[r]);
+}
+
 // Grouped-query scores of one decoded key row of kv head `head` (the quad's 4 x 32 values in v, unrounded):
 //   scores[b, qh, t] = score_scale * sum_d q[b, qh, d] * round_bf16(v)[d]   for the q_heads / H query heads of the head,
 // the key rotated by its position t first when rope_cos is given (caches that hold keys from before the rotary

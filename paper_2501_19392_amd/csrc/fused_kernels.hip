@@ -103,14 +103,12 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
   };
   // WIDE, grids: the code bytes of this lane's 16 sub-vector slots in each of the 8 heads of its token
   constexpr bool kWideGrid = WIDE && !is_rtn(NCW);
-  struct WideCodes { u32x4 h[kWideGrid ? 8 : 1]; };
-  const auto fetch_wide = [&](int pass, WideCodes& wc) {
+  const auto fetch_wide = [&](int pass, WideCodes<NCW>& wc) {
     int64_t row = m0 + wave * kRowsPerWave + pass * 16 + (lane >> 2);
     row = row < T ? row : T - 1;
-#pragma unroll
-    for (int hh = 0; hh < 8; ++hh) wc.h[hh] = request_codes<NCW>(codes, row * H + hh, q);
+    request_wide_codes<NCW>(codes, row, q, wc);
   };
-  WideCodes wide_codes;                                  // of the pass at hand; the next pass's are fetched while it runs
+  WideCodes<NCW> wide_codes;                             // of the pass at hand; the next pass's are fetched while it runs
 
   // kWeighted: the attention weights of query head slot lane % 16 (of this kv head) for 8 of the wave's 32 token rows,
   // in the layout of the A operand of the 16x16x32 matrix instruction; slots beyond the group's heads stay zero.
@@ -168,46 +166,9 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
       if constexpr (!WIDE || is_rtn(NCW)) {
         dequantize_words<NCW>(in.w, p, sf, q, cl.cb, v);
       } else {
-        // zhat of the 8 heads, added as the stages across the heads of the 1024-point transform add them for head
-        // `head`: ((0 +- 1) +- (2 +- 3)) +- ((4 +- 5) +- (6 +- 7)), minus where the head's bit of that level is set
-        const float s16 = recon_scale<true>(half_bits_to_float((uint16_t)in.w.scale), q);   // the quad's two lane bits only
-        const float g0 = (head & 1) ? -1.0f : 1.0f, g1 = (head & 2) ? -1.0f : 1.0f, g2 = (head & 4) ? -1.0f : 1.0f;
-        const WideCodes wc = wide_codes;
+        const WideCodes<NCW> wc = wide_codes;
         if (pass + 1 < kPasses) fetch_wide(pass + 1, wide_codes);
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-          const auto zhat_half = [&](int hh, float (&z)[16]) {
-            int idx[16];
-            unpack_codes<NCW>(wc.h[hh], idx);
-#pragma unroll
-            for (int m = 0; m < 8; ++m) {
-              const float2 cw = *reinterpret_cast<const float2*>(&cl.cb[idx[8 * half + m]]);
-              z[2 * m] = cw.x * s16;
-              z[2 * m + 1] = cw.y * s16;
-            }
-          };
-          const auto pair_of = [&](int hh, float (&t)[16]) {        // z[hh] +- z[hh + 1]
-            float b[16];
-            zhat_half(hh, t);
-            zhat_half(hh + 1, b);
-#pragma unroll
-            for (int i = 0; i < 16; ++i) t[i] = __fmaf_rn(b[i], g0, t[i]);
-          };
-          float u0[16], u1[16], t[16];
-          pair_of(0, u0);
-          pair_of(2, t);
-#pragma unroll
-          for (int i = 0; i < 16; ++i) u0[i] = __fmaf_rn(t[i], g1, u0[i]);
-          pair_of(4, u1);
-          pair_of(6, t);
-#pragma unroll
-          for (int i = 0; i < 16; ++i) u1[i] = __fmaf_rn(t[i], g1, u1[i]);
-#pragma unroll
-          for (int i = 0; i < 16; ++i) v[16 * half + i] = __fmaf_rn(u1[i], g2, u0[i]);
-        }
-        wht128<true>(v, q);
-#pragma unroll
-        for (int r = 0; r < 32; ++r) v[r] = __fmaf_rn(v[r], sf[r], p[r]);
+        dequantize_across_heads<NCW>(wc, in.w.scale, head, q, p, sf, cl.cb, v);
       }
       if (Xhat != nullptr && active) Storage<bf16_t>::store32(Xhat + off, v);
       if constexpr (MODE == kWeighted) {
@@ -388,9 +349,9 @@ hipError_t launch_fused_encode(int n_codewords, const void* x0, int d0, const vo
 hipError_t launch_fused_decode(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W,
                                const float* bias, const int8_t* signs, const float* codebook, const uint8_t* codes,
                                const uint16_t* scales, void* Xhat, int64_t T, int D, bool wide, hipStream_t stream) {
-  if (!wide && two_heads_pays(T, D))
+  if (two_heads_pays(T, D))
     return launch_fused_decode_two_heads(n_codewords, x0, d0, x1, d1, W, bias, signs, codebook, codes, scales, Xhat, T, D,
-                                         stream);
+                                         wide, stream);
   return launch<kDecode>(n_codewords, x0, d0, x1, d1, W, bias, signs, codebook, nullptr, nullptr,
                          const_cast<uint8_t*>(codes), const_cast<uint16_t*>(scales), Xhat, nullptr, 0.f, nullptr, 1, 1,
                          T, D, nullptr, nullptr, nullptr, nullptr, wide, stream);
@@ -401,9 +362,9 @@ hipError_t launch_fused_scores(int n_codewords, const void* x0, int d0, const vo
                                const uint16_t* scales, const void* q, float score_scale, float* scores, void* Khat_out,
                                int seq_len, int q_heads, int64_t T, int D, const float* rope_cos, const float* rope_sin,
                                bool wide, hipStream_t stream) {
-  if (!wide && two_heads_pays(T, D))
+  if (two_heads_pays(T, D))
     return launch_fused_scores_two_heads(n_codewords, x0, d0, W, bias, signs, codebook, codes, scales, q, score_scale,
-                                         scores, Khat_out, seq_len, q_heads, T, D, rope_cos, rope_sin, stream);
+                                         scores, Khat_out, seq_len, q_heads, T, D, rope_cos, rope_sin, wide, stream);
   return launch<kScores>(n_codewords, x0, d0, nullptr, 0, W, bias, signs, codebook, nullptr, nullptr,
                          const_cast<uint8_t*>(codes), const_cast<uint16_t*>(scales), Khat_out, q, score_scale, scores,
                          seq_len, q_heads, T, D, rope_cos, rope_sin, nullptr, nullptr, wide, stream);

@@ -24,7 +24,11 @@ static_assert(kFused2LdsBytes <= 160 * 1024, "LDS of one CU");
 
 enum Mode2 : int { kEncode2 = 0, kDecode2 = 1, kScores2 = 2 };
 
-template <int NCW, int MODE>
+// WIDE (decode and scores; 8 heads): rotation groups of 1024 = the whole token.  A wave still owns one head of its 64
+// tokens, so the inverse rotation's stages across the heads are taken on the grid points of all 8 heads, which the lane
+// fetches itself (fused_epilogue.h); the round-to-nearest backbone has no rotation and only reads its step and zero
+// point per token.
+template <int NCW, int MODE, bool WIDE = false>
 __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
     const bf16_t* __restrict__ x0, int d0, const bf16_t* __restrict__ x1, int d1, const bf16_t* __restrict__ W,
     const float* __restrict__ bias, const int8_t* __restrict__ signs, const float* __restrict__ codebook,
@@ -51,6 +55,8 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
   const int q = lane & 3;                            // position in the quad that owns a group
 
   constexpr bool kEnc = MODE == kEncode2;
+  static_assert(!WIDE || !kEnc, "the quantizer needs the whole group: groups across the heads are encoded elsewhere");
+  constexpr bool kWideGrid = WIDE && !is_rtn(NCW);
   // decode: codes and scale; encode: the 32 values of the row to quantize
   struct In { CodeWords w; u32x4 x[kEnc ? 4 : 1]; };
   constexpr int kPasses = 4;                         // 2 blocks x 2 passes of 16 groups
@@ -65,8 +71,14 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
       return;
     }
     const int64_t gid = row * H + head;
-    in.w = request_words<NCW>(codes, scales, gid, q);
+    in.w = request_words<NCW, WIDE>(codes, scales, gid, q);
   };
+  const auto fetch_wide = [&](int pi, WideCodes<NCW>& wc) {
+    int64_t row = mw + pi * 16 + (lane >> 2);
+    row = row < T ? row : T - 1;
+    request_wide_codes<NCW>(codes, row, q, wc);
+  };
+  WideCodes<NCW> wide_codes;                         // of the pass at hand; the next pass's are fetched while it runs
 
   f32x16 acc[2][4];
   gemm_mainloop_two_heads(smem, x0, d0, x1, d1, W, T, m0, pair * BN2, acc, [&] {
@@ -75,6 +87,7 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
     } else {
 #pragma unroll
       for (int pi = 0; pi < kPasses; ++pi) fetch(pi, in[pi]);
+      if constexpr (kWideGrid) fetch_wide(0, wide_codes);
     }
   });
 
@@ -122,6 +135,10 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
 #pragma unroll
         for (int k = 0; k < 4; ++k) unpack_bf16x8(ip.x[k], &v[8 * k]);
         quantize_group<NCW>(v, p, sf, q, cl.cb, use_table ? cl.table : nullptr, active, gid, codes, scales, Xhat != nullptr);
+      } else if constexpr (kWideGrid) {
+        const WideCodes<NCW> wc = wide_codes;
+        if (pi + 1 < kPasses) fetch_wide(pi + 1, wide_codes);
+        dequantize_across_heads<NCW>(wc, ip.w.scale, head, q, p, sf, cl.cb, v);
       } else {
         dequantize_words<NCW>(ip.w, p, sf, q, cl.cb, v);
       }
@@ -142,22 +159,30 @@ template <int MODE>
 hipError_t launch2(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W, const float* bias,
                    const int8_t* signs, const float* codebook, const void* table, const void* X, uint8_t* codes,
                    uint16_t* scales, void* Xhat, const void* q, float score_scale, float* scores, int seq_len, int q_heads, int64_t T, int D,
-                   const float* rope_cos, const float* rope_sin, hipStream_t stream) {
+                   const float* rope_cos, const float* rope_sin, bool wide, hipStream_t stream) {
   if (T == 0) return hipSuccess;
-  if (D % BN2 != 0) return hipErrorInvalidValue;
+  if (D % BN2 != 0 || (wide && (MODE == kEncode2 || D != 8 * kGroup))) return hipErrorInvalidValue;
   const unsigned blocks = (unsigned)(((T + BM2 - 1) / BM2) * (D / BN2));
-#define AQUAKV_FUSED2(N)                                                                                              \
-  fused_two_heads_kernel<N, MODE><<<blocks, kWaves2 * 64, 0, stream>>>(                                               \
+#define AQUAKV_FUSED2_W(N, WIDE)                                                                                      \
+  fused_two_heads_kernel<N, MODE, WIDE><<<blocks, kWaves2 * 64, 0, stream>>>(                                         \
       static_cast<const bf16_t*>(x0), d0, static_cast<const bf16_t*>(x1), d1, static_cast<const bf16_t*>(W), bias,    \
       signs, codebook, static_cast<const uint32_t*>(table), static_cast<const bf16_t*>(X), codes, scales,              \
       static_cast<bf16_t*>(Xhat), static_cast<const bf16_t*>(q), score_scale, scores, seq_len, q_heads, T, D, rope_cos, \
       rope_sin)
+#define AQUAKV_FUSED2(N)                                           \
+  do {                                                             \
+    if constexpr (MODE != kEncode2) {                              \
+      if (wide) { AQUAKV_FUSED2_W(N, true); break; }               \
+    }                                                              \
+    AQUAKV_FUSED2_W(N, false);                                     \
+  } while (0)
   if (n_codewords == kRtn2) AQUAKV_FUSED2(kRtn2);
   else if (n_codewords == kRtn4) AQUAKV_FUSED2(kRtn4);
   else if (n_codewords == 16) AQUAKV_FUSED2(16);
   else if (n_codewords == 64) AQUAKV_FUSED2(64);
   else AQUAKV_FUSED2(256);
 #undef AQUAKV_FUSED2
+#undef AQUAKV_FUSED2_W
   return hipGetLastError();
 }
 
@@ -177,10 +202,10 @@ bool two_heads_pays(int64_t T, int D) {
 hipError_t launch_fused_decode_two_heads(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W,
                                          const float* bias, const int8_t* signs, const float* codebook,
                                          const uint8_t* codes, const uint16_t* scales, void* Xhat, int64_t T, int D,
-                                         hipStream_t stream) {
+                                         bool wide, hipStream_t stream) {
   return launch2<kDecode2>(n_codewords, x0, d0, x1, d1, W, bias, signs, codebook, nullptr, nullptr,
                            const_cast<uint8_t*>(codes), const_cast<uint16_t*>(scales), Xhat, nullptr, 0.f, nullptr, 1, 1, T,
-                           D, nullptr, nullptr, stream);
+                           D, nullptr, nullptr, wide, stream);
 }
 
 hipError_t launch_fused_encode_two_heads(int n_codewords, const void* x0, int d0, const void* x1, int d1, const void* W,
@@ -188,17 +213,17 @@ hipError_t launch_fused_encode_two_heads(int n_codewords, const void* x0, int d0
                                          const void* X, uint8_t* codes, uint16_t* scales, void* Xhat, int64_t T, int D,
                                          hipStream_t stream) {
   return launch2<kEncode2>(n_codewords, x0, d0, x1, d1, W, bias, signs, codebook, table, X, codes, scales, Xhat, nullptr,
-                           0.f, nullptr, 1, 1, T, D, nullptr, nullptr, stream);
+                           0.f, nullptr, 1, 1, T, D, nullptr, nullptr, false, stream);
 }
 
 hipError_t launch_fused_scores_two_heads(int n_codewords, const void* x0, int d0, const void* W, const float* bias,
                                          const int8_t* signs, const float* codebook, const uint8_t* codes,
                                          const uint16_t* scales, const void* q, float score_scale, float* scores,
                                          void* Khat_out, int seq_len, int q_heads, int64_t T, int D,
-                                         const float* rope_cos, const float* rope_sin, hipStream_t stream) {
+                                         const float* rope_cos, const float* rope_sin, bool wide, hipStream_t stream) {
   return launch2<kScores2>(n_codewords, x0, d0, nullptr, 0, W, bias, signs, codebook, nullptr, nullptr,
                            const_cast<uint8_t*>(codes), const_cast<uint16_t*>(scales), Khat_out, q, score_scale, scores,
-                           seq_len, q_heads, T, D, rope_cos, rope_sin, stream);
+                           seq_len, q_heads, T, D, rope_cos, rope_sin, wide, stream);
 }
 
 }  // namespace aquakv

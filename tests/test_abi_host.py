@@ -79,7 +79,7 @@ def test_decode_tile_rule():
         assert B.aquakv_fused_tile_heads(L, T) == want, T
     assert [B.aquakv_fused_tile_heads(L, T) for T in (8192, 8193, 16384, 16385, 32768)] == [1, 2, 2, 1, 2]
     assert B.aquakv_fused_tile_heads(layer(kv_heads=3, d_in_k=384, d_in_v=768), 32768) == 1      # D not a multiple of 256
-    assert B.aquakv_fused_tile_heads(layer(rht_group=1024), 32768) == 1                           # groups across the heads
+    assert B.aquakv_fused_tile_heads(layer(rht_group=1024), 32768) == 2                           # groups across the heads: the decode kernels' tile
     assert B.aquakv_fused_tile_heads(layer(dtype=B.AQUAKV_FP32), 32768) == 0                      # separate kernels
     assert B.aquakv_fused_tile_heads(layer(d_in_k=0, d_in_v=0, w_k=None, w_v=None), 32768) == 0   # no predictor
     assert B.aquakv_fused_tile_heads(L, 0) == 0 and B.aquakv_fused_tile_heads(layer(head_dim=64), 32768) == 0

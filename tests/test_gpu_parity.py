@@ -638,7 +638,10 @@ def test_fused_encoder_for_groups_of_1024_equals_the_stage_calls(B, quantizer):
 
 
 @pytest.mark.parametrize("H,T,quantizer", [(8, 8200, "n16"), (8, 8449, "rtn2"), (6, 11010, "n64"), (16, 4100, "n256"),
-                                           (4, 16390, "rtn4"), (8, 16384, "n64")])
+                                           (4, 16390, "rtn4"), (8, 16384, "n64"),
+                                           # rotation groups of 1024: decode and scores on the large tile (the encoder has its own kernel)
+                                           (8, 8200, "n16-g1024"), (8, 8449, "n256-g1024"), (8, 8300, "n64-g1024"),
+                                           (8, 8200, "rtn2-g1024")])
 def test_two_head_tiles_give_the_bits_of_one_head_tiles(B, H, T, quantizer):
     """Encode, decode and the scoring call switch to tiles of 256 tokens x two heads once that costs no extra round
     over the CUs (the token counts here; short ranges stay on tiles of one head).  The large tile must give the codes,
@@ -649,7 +652,11 @@ def test_two_head_tiles_give_the_bits_of_one_head_tiles(B, H, T, quantizer):
     on sampled rows (grids)."""
     print(f"case two-head tiles H={H} T={T} {quantizer}", flush=True)
     D = H * 128
+    wide = quantizer.endswith("-g1024")
+    quantizer = quantizer.split("-")[0]
     kw = dict(rtn_bits=int(quantizer[3:])) if quantizer.startswith("rtn") else {}
+    if wide:
+        kw["rht_group"] = 1024
     n = 16 if quantizer.startswith("rtn") else int(quantizer[1:])
     gb = torch.Generator().manual_seed(6)
     bk, bv = torch.randn(D, generator=gb) * 0.3, torch.randn(D, generator=gb) * 0.3
@@ -664,7 +671,8 @@ def test_two_head_tiles_give_the_bits_of_one_head_tiles(B, H, T, quantizer):
     B.aquakv_encode_layer(lg, T, K, V, Kp, Vp, kc, ks, vc, vs, Kh, Vh, ws)
     sync()
     out = dict(k_codes=kc, k_scales=ks, v_codes=vc, v_scales=vs, Khat=Kh, Vhat=Vh, Kp=Kp, Vp=Vp)
-    if not kw:               # (the round-to-nearest encoder has its oracle comparison in test_gpu_rtn_backbone.py)
+    if not kw:               # (the round-to-nearest encoder has its oracle comparison in test_gpu_rtn_backbone.py, the
+                             # one for groups of 1024 in test_rotation_group_1024_across_heads)
         for rep in check_layer_against_oracle(B, lo, lg, K, V, out, rows=sampled_rows(T, 48, 4)):
             print(f"   {rep}", flush=True)
     Kd, Vd = lg.alloc_kv(T), lg.alloc_kv(T)
