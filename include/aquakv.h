@@ -145,7 +145,8 @@ size_t aquakv_workspace_bytes(const aquakv_layer* layer, int64_t tokens);
 /* Which tile the fused bf16 kernels (predictor of Sect. 3.2 with the quantizer or its inverse inside: aquakv_encode_layer,
  * aquakv_encode_keys / _values, aquakv_decode_layer, aquakv_decode_values, aquakv_decode_attn_scores and its rotary
  * form) take for a call over `tokens` rows: 2 = 256 tokens x two kv heads per workgroup, 1 = 256 tokens x one head (for
- * layers with rotation groups across the heads: the decode kernels' tile; their encoder works on 64 tokens x all heads),
+ * layers with rotation groups across the heads: the tile of aquakv_decode_layer / _values; their encoder works on 64
+ * tokens x all heads, their scoring call on one head),
  * 0 = the layer does not go through them (fp32, no predictor) or the arguments are invalid.  The large tile has the
  * faster main loop and is taken when it costs no extra round of workgroups over the compute units; the value sums of
  * aquakv_decode_values_weighted / _attend stay on the small tile.  For information (benchmarks label their kernels by

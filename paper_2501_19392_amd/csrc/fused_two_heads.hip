@@ -24,7 +24,7 @@ static_assert(kFused2LdsBytes <= 160 * 1024, "LDS of one CU");
 
 enum Mode2 : int { kEncode2 = 0, kDecode2 = 1, kScores2 = 2 };
 
-// WIDE (decode and scores; 8 heads): rotation groups of 1024 = the whole token.  A wave still owns one head of its 64
+// WIDE (decode; 8 heads): rotation groups of 1024 = the whole token.  A wave still owns one head of its 64
 // tokens, so the inverse rotation's stages across the heads are taken on the grid points of all 8 heads, which the lane
 // fetches itself (fused_epilogue.h); the round-to-nearest backbone has no rotation and only reads its step and zero
 // point per token.
@@ -55,7 +55,7 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
   const int q = lane & 3;                            // position in the quad that owns a group
 
   constexpr bool kEnc = MODE == kEncode2;
-  static_assert(!WIDE || !kEnc, "the quantizer needs the whole group: groups across the heads are encoded elsewhere");
+  static_assert(!WIDE || MODE == kDecode2, "groups across the heads: only the decode variant pays on this tile");
   constexpr bool kWideGrid = WIDE && !is_rtn(NCW);
   // decode: codes and scale; encode: the 32 values of the row to quantize
   struct In { CodeWords w; u32x4 x[kEnc ? 4 : 1]; };
@@ -161,7 +161,7 @@ hipError_t launch2(int n_codewords, const void* x0, int d0, const void* x1, int 
                    uint16_t* scales, void* Xhat, const void* q, float score_scale, float* scores, int seq_len, int q_heads, int64_t T, int D,
                    const float* rope_cos, const float* rope_sin, bool wide, hipStream_t stream) {
   if (T == 0) return hipSuccess;
-  if (D % BN2 != 0 || (wide && (MODE == kEncode2 || D != 8 * kGroup))) return hipErrorInvalidValue;
+  if (D % BN2 != 0 || (wide && (MODE != kDecode2 || D != 8 * kGroup))) return hipErrorInvalidValue;
   const unsigned blocks = (unsigned)(((T + BM2 - 1) / BM2) * (D / BN2));
 #define AQUAKV_FUSED2_W(N, WIDE)                                                                                      \
   fused_two_heads_kernel<N, MODE, WIDE><<<blocks, kWaves2 * 64, 0, stream>>>(                                         \
@@ -171,7 +171,7 @@ hipError_t launch2(int n_codewords, const void* x0, int d0, const void* x1, int 
       rope_sin)
 #define AQUAKV_FUSED2(N)                                           \
   do {                                                             \
-    if constexpr (MODE != kEncode2) {                              \
+    if constexpr (MODE == kDecode2) {                              \
       if (wide) { AQUAKV_FUSED2_W(N, true); break; }               \
     }                                                              \
     AQUAKV_FUSED2_W(N, false);                                     \
@@ -220,10 +220,10 @@ hipError_t launch_fused_scores_two_heads(int n_codewords, const void* x0, int d0
                                          const int8_t* signs, const float* codebook, const uint8_t* codes,
                                          const uint16_t* scales, const void* q, float score_scale, float* scores,
                                          void* Khat_out, int seq_len, int q_heads, int64_t T, int D,
-                                         const float* rope_cos, const float* rope_sin, bool wide, hipStream_t stream) {
+                                         const float* rope_cos, const float* rope_sin, hipStream_t stream) {
   return launch2<kScores2>(n_codewords, x0, d0, nullptr, 0, W, bias, signs, codebook, nullptr, nullptr,
                            const_cast<uint8_t*>(codes), const_cast<uint16_t*>(scales), Khat_out, q, score_scale, scores,
-                           seq_len, q_heads, T, D, rope_cos, rope_sin, wide, stream);
+                           seq_len, q_heads, T, D, rope_cos, rope_sin, false, stream);
 }
 
 }  // namespace aquakv

@@ -57,7 +57,7 @@ hipError_t launch_fused_scores(int n_codewords, const void* x0, int d0, const vo
                                int seq_len, int q_heads, int64_t T, int D, const float* rope_cos, const float* rope_sin,
                                bool wide, hipStream_t stream);
 
-// The same on tiles of 256 tokens x two heads (D a multiple of 256; wide: decode and scores only): same bits, a faster main
+// The same on tiles of 256 tokens x two heads (D a multiple of 256; wide: decode only): same bits, a faster main
 // loop, half as many workgroups.  launch_fused_decode / launch_fused_scores take this form by themselves when
 // two_heads_pays(T, D): when the larger tile costs no extra round over the CUs.
 bool two_heads_pays(int64_t T, int D);
@@ -73,7 +73,7 @@ hipError_t launch_fused_scores_two_heads(int n_codewords, const void* x0, int d0
                                          const int8_t* signs, const float* codebook, const uint8_t* codes,
                                          const uint16_t* scales, const void* q, float score_scale, float* scores,
                                          void* Khat_out, int seq_len, int q_heads, int64_t T, int D,
-                                         const float* rope_cos, const float* rope_sin, bool wide, hipStream_t stream);
+                                         const float* rope_cos, const float* rope_sin, hipStream_t stream);
 
 // Value side of attention.  The sums over tokens are taken per chunk of kWeightedChunk tokens of one sequence
 // (part[batch * chunks_per_seq, q_heads, 128] fp32, chunks_per_seq = ceil(seq_len / kWeightedChunk)) and then added in
