@@ -98,10 +98,42 @@ __device__ __forceinline__ void dequantize_across_heads(const WideCodes<NCW>& wc
 //   scores[b, qh, t] = score_scale * sum_d q[b, qh, d] * round_bf16(v)[d]   for the q_heads / H query heads of the head,
 // the key rotated by its position t first when rope_cos is given (caches that hold keys from before the rotary
 // embedding, Sect. 3.3).  Row index rowc = b * seq_len + t.
+// q_lds (nullable): the queries of this row's sequence for the query heads of `head`, staged by the caller as fp32,
+// kQueryLdsStride floats per query head, quad position q at float q * kQueryLdsQuad (stage_queries below); the same
+// values as in memory, so the same bits either way.
+constexpr int kQueryLdsQuad = kValsPerLane + 4;          // 144-byte steps: the four quad positions fall on disjoint banks
+constexpr int kQueryLdsStride = 4 * kQueryLdsQuad;
+// The queries a tile scores against, on their way to LDS: when the tile's rows [m0, m0 + rows) lie inside one sequence, the
+// n_qh query heads from first_qh on (adjacent in memory: the query heads of the tile's kv heads) are requested early, 4
+// values per thread, and stored as fp32 once the LDS is free; the epilogue then reads them from LDS instead of waiting
+// for memory once per query head and pass.  n_qh <= 16.
+struct QueryStage {
+  u32x2 regs;
+  bool staged;
+  __device__ __forceinline__ void request(const bf16_t* __restrict__ qv, int64_t m0, int rows, int64_t T, int seq_len,
+                                          int q_heads, int first_qh, int n_qh) {
+    const int64_t last = m0 + rows - 1 < T ? m0 + rows - 1 : T - 1;
+    const int64_t b = m0 / seq_len;
+    regs = u32x2{0, 0};
+    staged = last / seq_len == b && n_qh * kGroup <= 4 * (int)blockDim.x;
+    if (staged && (int)threadIdx.x * 4 < n_qh * kGroup)
+      regs = *reinterpret_cast<const u32x2*>(qv + (b * q_heads + first_qh) * kGroup + threadIdx.x * 4);
+  }
+  __device__ __forceinline__ void store(float* q_lds, int n_qh) const {
+    if (staged && (int)threadIdx.x * 4 < n_qh * kGroup) {
+      const int e = threadIdx.x * 4, qh = e / kGroup, d = e % kGroup;       // 4 consecutive values of one quad position
+      f32x4 f;
+      f.x = __uint_as_float(regs.x << 16); f.y = __uint_as_float(regs.x & 0xffff0000u);
+      f.z = __uint_as_float(regs.y << 16); f.w = __uint_as_float(regs.y & 0xffff0000u);
+      *reinterpret_cast<f32x4*>(q_lds + qh * kQueryLdsStride + (d / kValsPerLane) * kQueryLdsQuad + d % kValsPerLane) = f;
+    }
+  }
+};
+
 __device__ __forceinline__ void score_row(float (&v)[32], int q, int head, int H, int q_heads, int seq_len, int64_t rowc,
                                           bool active, const bf16_t* __restrict__ qv, float score_scale,
                                           float* __restrict__ scores, const float* __restrict__ rope_cos,
-                                          const float* __restrict__ rope_sin) {
+                                          const float* __restrict__ rope_sin, const float* q_lds = nullptr) {
 #pragma unroll
   for (int r = 0; r < 32; ++r) v[r] = Storage<bf16_t>::round(v[r]);      // score the stored keys
   const int rep = q_heads / H;
@@ -110,7 +142,16 @@ __device__ __forceinline__ void score_row(float (&v)[32], int q, int head, int H
   for (int r = 0; r < rep; ++r) {
     const int qh = head * rep + r;
     float qf[32];
-    Storage<bf16_t>::load32(qv + (b * q_heads + qh) * kGroup + q * kValsPerLane, qf);
+    if (q_lds != nullptr) {
+      const float* src = q_lds + r * kQueryLdsStride + q * kQueryLdsQuad;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const f32x4 a = *reinterpret_cast<const f32x4*>(src + 4 * k);
+        qf[4 * k] = a.x; qf[4 * k + 1] = a.y; qf[4 * k + 2] = a.z; qf[4 * k + 3] = a.w;
+      }
+    } else {
+      Storage<bf16_t>::load32(qv + (b * q_heads + qh) * kGroup + q * kValsPerLane, qf);
+    }
     float s = 0.f;
 #pragma unroll
     for (int i = 0; i < 32; ++i) s = __fmaf_rn(qf[i], v[i], s);

@@ -82,6 +82,8 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
   constexpr int MI = BM / WAVES / 32;              // 32-row blocks per wave
   constexpr int kRowsPerWave = MI * 32;
   const int q = lane & 3;                          // position in the quad that owns a group
+  QueryStage queries = {};                         // scores: the queries of the tile's kv head, via LDS (no cell table in that mode)
+  if constexpr (MODE == kScores) queries.request(qv, m0, BM, T, seq_len, q_heads, head * (q_heads / H), q_heads / H);
 
   // What the epilogue reads from global memory (rows to quantize, or codes and scales) is
   // requested from inside the main loop, when its own last operand loads are out, so the
@@ -133,6 +135,8 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
 
   // the LDS is free again: grid and table, then the tile (+ bias) parked row-major in fp32, each wave its own rows
   stage_tables();
+  float* const q_lds = reinterpret_cast<float*>(cl.table);
+  if constexpr (MODE == kScores) queries.store(q_lds, q_heads / H);
   float* wl = reinterpret_cast<float*>(park) + wave * kRowsPerWave * kLdP;
   {
     float bv[4];
@@ -185,7 +189,8 @@ __global__ __launch_bounds__(WAVES * 64) void fused_kernel(
         }
       }
       if constexpr (MODE == kScores)
-        score_row(v, q, head, H, q_heads, seq_len, rowc, active, qv, score_scale, scores, rope_cos, rope_sin);
+        score_row(v, q, head, H, q_heads, seq_len, rowc, active, qv, score_scale, scores, rope_cos, rope_sin,
+                  queries.staged ? q_lds : nullptr);
     }
   };
 #pragma unroll

@@ -42,6 +42,7 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
   float cb_a = 0.f, cb_b = 0.f;                      // kept in registers while the main loop owns the LDS
   if ((int)threadIdx.x < kGridPoints) { cb_a = codebook[2 * threadIdx.x]; cb_b = codebook[2 * threadIdx.x + 1]; }
   const bool use_table = MODE == kEncode2 && !is_rtn(NCW) && table != nullptr;
+  QueryStage queries = {};                           // scores: the queries of the tile's two kv heads, via LDS
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -54,6 +55,7 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
   const int64_t mw = m0 + (wave >> 1) * 64;          // its first token row
   const int q = lane & 3;                            // position in the quad that owns a group
 
+  if constexpr (MODE == kScores2) queries.request(qv, m0, BM2, T, seq_len, q_heads, 2 * pair * (q_heads / H), 2 * (q_heads / H));
   constexpr bool kEnc = MODE == kEncode2;
   static_assert(!WIDE || MODE == kDecode2, "groups across the heads: only the decode variant pays on this tile");
   constexpr bool kWideGrid = WIDE && !is_rtn(NCW);
@@ -97,6 +99,11 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
   if (use_table) table_regs.request(table);
   if ((int)threadIdx.x < kGridPoints)
     cl.cb[threadIdx.x] = make_float4(cb_a, cb_b, -0.5f * (cb_a * cb_a + cb_b * cb_b), 0.f);
+  float* const q_lds = reinterpret_cast<float*>(cl.table);      // (no cell table in this mode)
+  if constexpr (MODE == kScores2) {
+    static_assert(MODE != kScores2 || 16 * kQueryLdsStride * 4 <= (int)sizeof(cl.table), "queries of two kv heads fit");
+    queries.store(q_lds, 2 * (q_heads / H));
+  }
   float* const wl = reinterpret_cast<float*>(smem + sizeof(Lds)) + wave * 32 * kLdP;
   float sf[32] = {};
   if constexpr (!is_rtn(NCW)) load_signs(signs, head, q, sf);
@@ -144,7 +151,8 @@ __global__ __launch_bounds__(kWaves2 * 64) void fused_two_heads_kernel(
       }
       if (Xhat != nullptr && active) Storage<bf16_t>::store32(Xhat + off, v);
       if constexpr (MODE == kScores2)
-        score_row(v, q, head, H, q_heads, seq_len, rowc, active, qv, score_scale, scores, rope_cos, rope_sin);
+        score_row(v, q, head, H, q_heads, seq_len, rowc, active, qv, score_scale, scores, rope_cos, rope_sin,
+                  queries.staged ? q_lds + (wave & 1) * (q_heads / H) * kQueryLdsStride : nullptr);
       __builtin_amdgcn_sched_barrier(0);
     }
     // every lane's reads of this block have returned before the next block overwrites the rows
