@@ -315,7 +315,7 @@ __global__ __launch_bounds__(1024) void build_overflow_kernel(const float* __res
 }
 
 // Workgroups per CU (256 CUs), the kernels grid-stride.  The quantizer holds two workgroups per CU (registers) and stages
-// 20 KiB of grid and cell table per workgroup, more than the 16 KiB of rows of one round: with exactly the resident
+// 21 KiB of grid and cell table per workgroup, more than the 16 KiB of rows of one round: with exactly the resident
 // number of workgroups the staging is paid once and the request of the next round's rows has a next round to run ahead
 // of (measured at 32768 tokens: 52 us against 67 us with 16 per CU).  The inverse stages 256 B and runs four waves per
 // SIMD; four workgroups per CU were the best of 2 / 4 / 8 / 16 at 32768 tokens (25.7 against 29 us with 16).
