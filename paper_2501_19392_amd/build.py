@@ -15,6 +15,9 @@ SOURCES = ["api.hip", "predict_gemm.hip", "codec_kernels.hip", "fused_kernels.hi
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed fp32 VALU ops
+    # loops marked `#pragma unroll` index register arrays (accumulator blocks, passes): they must be unrolled whatever
+    # the size of the quantizer body inlined into them (the default limit leaves the encoder for groups of 1024 rolled)
+    "-mllvm", "-pragma-unroll-threshold=65536",
     "-Wall", "-Wno-unused-function",
 ]
 

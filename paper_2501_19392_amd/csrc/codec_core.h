@@ -20,8 +20,12 @@
 namespace aquakv {
 
 constexpr int kCells = 64;                   // table is kCells x kCells
-constexpr float kCellHalfRange = 4.0f;       // cells tile [-4, 4]^2
-constexpr float kCellScale = kCells / (2.0f * kCellHalfRange);   // 8 cells per unit
+// The cells tile [-R, R]^2 (border cells reach out to infinity).  R = 4 for the grids of 16 and 64 points.  For the
+// 256-point grid R = 3.25: where the cell edges fall relative to the grid decides how many cells see more candidates than an
+// entry holds, and with R = 4 twelve such cells sit where a Gaussian puts 0.9 % of its mass (so nearly every wave of 1024
+// sub-vectors meets one), with R = 3.25 they hold less than 1e-5 of it.
+__host__ __device__ constexpr float cell_half_range(int n) { return n == 256 ? 3.25f : 4.0f; }
+__host__ __device__ constexpr float cell_scale(int n) { return kCells / (2.0f * cell_half_range(n)); }   // cells per unit
 // Table layout (32-bit words): kCells * kCells cell entries, then kOvfLists overflow lists of two words each.
 // A cell entry lists up to 4 candidate slots, one per byte from the lowest, ascending, the last one repeated.  A cell
 // with more candidates than the kernels score per cell (3 for the 16-point grid, else 4) is CROWDED: its entry is
@@ -89,8 +93,8 @@ template <int NCW>
 __device__ __forceinline__ int search_cell(float y0, float y1, const float4* cb, const uint32_t* table,
                                            bool& crowded) {
   constexpr int SH = Slot<NCW>::kShift;
-  const float fx = __builtin_amdgcn_fmed3f(__fmaf_rn(y0, kCellScale, 0.5f * kCells), 0.0f, kCells - 0.5f);
-  const float fy = __builtin_amdgcn_fmed3f(__fmaf_rn(y1, kCellScale, 0.5f * kCells), 0.0f, kCells - 0.5f);
+  const float fx = __builtin_amdgcn_fmed3f(__fmaf_rn(y0, cell_scale(NCW), 0.5f * kCells), 0.0f, kCells - 0.5f);
+  const float fy = __builtin_amdgcn_fmed3f(__fmaf_rn(y1, cell_scale(NCW), 0.5f * kCells), 0.0f, kCells - 0.5f);
   const uint32_t e = table[(int)fy * kCells + (int)fx];
   crowded = e >= crowded_threshold(NCW);
   int slot = e & 0xff;
@@ -161,23 +165,31 @@ __device__ __forceinline__ uint32_t search_overflow_masked(const float (&v)[32],
       const bool mine = (mask >> (8 * half + m)) & 1;
       if (__builtin_amdgcn_ballot_w64(mine) != 0) {                  // somebody in the wave
         const float y0 = (half ? v[16 + 2 * m] : v[2 * m]) * inv, y1 = (half ? v[16 + 2 * m + 1] : v[2 * m + 1]) * inv;
-        const float fx = __builtin_amdgcn_fmed3f(__fmaf_rn(y0, kCellScale, 0.5f * kCells), 0.0f, kCells - 0.5f);
-        const float fy = __builtin_amdgcn_fmed3f(__fmaf_rn(y1, kCellScale, 0.5f * kCells), 0.0f, kCells - 0.5f);
+        const float fx = __builtin_amdgcn_fmed3f(__fmaf_rn(y0, cell_scale(NCW), 0.5f * kCells), 0.0f, kCells - 0.5f);
+        const float fy = __builtin_amdgcn_fmed3f(__fmaf_rn(y1, cell_scale(NCW), 0.5f * kCells), 0.0f, kCells - 0.5f);
         const uint32_t low = table[(int)fy * kCells + (int)fx] & 0xffu;
         const bool listed = mine && low != slot_top(NCW);
         full |= (mine && !listed) ? 1u << (8 * half + m) : 0u;
         const uint32_t* list = table + kCellWords + 2 * (listed ? (int)(low >> SH) : 0);
-        uint64_t w = list[0] | ((uint64_t)list[1] << 32);
-        int slot = (int)(w & 0xff);
+        // two rounds of four candidates: the four grid points of a round are fetched together (a loop over single
+        // candidates would wait for LDS eight times in a row); rolled, because this path is rare and its size is not
+        int slot = (int)(list[0] & 0xff);
         float best = score(y0, y1, grid_entry<SH>(cb, slot));
 #pragma unroll 1
-        for (int k = 1; k < kOvfCand; ++k) {               // (rolled: this path is rare, its size is not)
-          w >>= 8;
-          const int j = (int)(w & 0xff);
-          const float sc = score(y0, y1, grid_entry<SH>(cb, j));
-          const bool better = sc > best;
-          best = better ? sc : best;
-          slot = better ? j : slot;
+        for (int rnd = 0; rnd < 2; ++rnd) {
+          const uint32_t w = list[rnd];
+          float4 c[4];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) c[k] = grid_entry<SH>(cb, (int)((w >> (8 * k)) & 0xff));
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {                     // (the first candidate again in round 0: a tie, no change)
+            const float sc = score(y0, y1, c[k]);
+            const bool better = sc > best;
+            best = better ? sc : best;
+            slot = better ? (int)((w >> (8 * k)) & 0xff) : slot;
+          }
+          // a list ends in repeats of its last candidate: no second round if no lane of the wave has more than four
+          if (__builtin_amdgcn_ballot_w64(listed && list[1] != (w >> 24) * 0x01010101u) == 0) break;
         }
         if (half) idx[8 + m] = listed ? slot : idx[8 + m];
         else idx[m] = listed ? slot : idx[m];

@@ -221,9 +221,10 @@ __device__ int cell_candidates(const float* __restrict__ codebook, int n, int ce
   const int cx = cell % kCells, cy = cell / kCells;
   const double far = 1e30;
   const double delta = 1e-4, eps = 1e-3;
-  const double h = 2.0 * kCellHalfRange / kCells;
-  double x0 = cx == 0 ? -far : -kCellHalfRange + cx * h, x1 = cx == kCells - 1 ? far : -kCellHalfRange + (cx + 1) * h;
-  double y0 = cy == 0 ? -far : -kCellHalfRange + cy * h, y1 = cy == kCells - 1 ? far : -kCellHalfRange + (cy + 1) * h;
+  const double R = cell_half_range(n);
+  const double h = 2.0 * R / kCells;
+  double x0 = cx == 0 ? -far : -R + cx * h, x1 = cx == kCells - 1 ? far : -R + (cx + 1) * h;
+  double y0 = cy == 0 ? -far : -R + cy * h, y1 = cy == kCells - 1 ? far : -R + (cy + 1) * h;
   x0 -= delta; y0 -= delta; x1 += delta; y1 += delta;
   const double cxs[4] = {x0, x1, x0, x1}, cys[4] = {y0, y0, y1, y1};
   int count = 0;
