@@ -832,6 +832,7 @@ def main():
         others = {}
         for name, kw, st, wu in (
                 ("llama3.1-8b, 3 bits (n=64)", dict(config="llama3.1-8b", n_codewords=64), min(args.steps, 5), 1),
+                ("llama3.1-8b, 4 bits (n=256)", dict(config="llama3.1-8b", n_codewords=256), min(args.steps, 5), 1),
                 ("llama3.1-70b, mixed 2/3 bits", dict(config="llama3.1-70b"), min(args.steps, 2), 1),
                 ("llama3.2-3b, 2 bits", dict(config="llama3.2-3b"), min(args.steps, 10), 2),
                 ("llama3.1-8b, 2 bits, rotation groups of 1024 (the paper's grouping)",
