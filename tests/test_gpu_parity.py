@@ -200,6 +200,60 @@ def test_search_table_gives_the_codes_of_the_full_search(B, n):
     assert torch.equal(res[0], res[1])
 
 
+@pytest.mark.parametrize("n", [16, 64, 256])
+def test_search_table_lists_the_candidates_of_every_cell(B, n):
+    """The table against its definition, cell by cell, in numpy: grid point j belongs to a cell unless one other point
+    i is closer by more than eps at all four corners of the slightly enlarged cell (the difference of two squared
+    distances is linear, so the corners decide).  A cell entry, or the overflow list it names, must hold exactly
+    that set, ascending; all cells for the two small grids, the crowded ones and a seeded sample for the 256-point grid."""
+    print(f"case table contents n={n}", flush=True)
+    from paper_2501_19392_amd import binding
+    C32 = np.ascontiguousarray(synth.lloyd_codebook(n), dtype=np.float32).reshape(n, 2)
+    C = C32.astype(np.float64)                                       # the values the builder reads
+    tab = binding.build_search_table(torch.from_numpy(C32).cuda())
+    sync()
+    w = tab.cpu().numpy().view(np.uint32)
+    cells, lists = w[:4096], w[4096:]
+    shift = 4 if n == 16 else 0
+    top = (n - 1) << shift
+    crowded = 0xFF000000 if n == 256 else (top + 1) << 24
+    full_mark = 0xFF000000 | (top << 16) | (top << 8) | top
+    R = 3.25 if n == 256 else 4.0
+    h, far, delta, eps = 2 * R / 64, 1e30, 1e-4, 1e-3
+    A, Bv = C[:, 0][:, None], C[:, 1][:, None]
+    gx, gy = -2 * (A - A.T), -2 * (Bv - Bv.T)
+    c0 = (A * A + Bv * Bv) - (A * A + Bv * Bv).T                      # [j, i]: d_j - d_i = gx x + gy y + c0
+    if n == 256:
+        rng = np.random.Generator(np.random.PCG64(11))
+        todo = sorted(set(np.nonzero(cells >= crowded)[0].tolist()[:150] + rng.choice(4096, 250, replace=False).tolist()
+                          + [0, 63, 4032, 4095, 2080]))
+    else:
+        todo = range(4096)
+    for cell in todo:
+        cx, cy = cell % 64, cell // 64
+        x0 = -far if cx == 0 else -R + cx * h
+        x1 = far if cx == 63 else -R + (cx + 1) * h
+        y0 = -far if cy == 0 else -R + cy * h
+        y1 = far if cy == 63 else -R + (cy + 1) * h
+        xs = np.array([x0 - delta, x1 + delta, x0 - delta, x1 + delta])
+        ys = np.array([y0 - delta, y0 - delta, y1 + delta, y1 + delta])
+        mn = np.min(gx[:, :, None] * xs + gy[:, :, None] * ys + c0[:, :, None], axis=2)
+        np.fill_diagonal(mn, -1.0)
+        want = np.nonzero(~(mn > eps).any(axis=1))[0].tolist()
+        e = int(cells[cell])
+        if e >= crowded:
+            assert e != full_mark, cell
+            k = (e & 0xff) >> shift
+            got = lists[2 * k: 2 * k + 2].view(np.uint8).astype(int)
+            assert len(want) > (3 if n == 16 else 4) or (n == 256 and want[-1] == 255), (cell, want)
+        else:
+            got = np.array([e & 0xff, (e >> 8) & 0xff, (e >> 16) & 0xff, e >> 24])
+        got = (got >> shift).tolist()
+        assert np.all(np.diff(got) >= 0) and sorted(set(got)) == want, (cell, got, want)
+        assert got[len(want) - 1:] == [want[-1]] * (len(got) - len(want) + 1), (cell, got)     # the last one repeated
+    print(f"   {len(todo)} cells: candidate sets as defined", flush=True)
+
+
 def test_quantize_edge_cases(B):
     """Zero residual, huge values (scale clamps at the fp16 maximum), tiny values (subnormal
     fp16 scales), in-place reconstruction, and a row count that leaves most of a block idle."""
